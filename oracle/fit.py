@@ -1,0 +1,159 @@
+"""Oracle wave-aware piecewise bilinear modelling (Sec. 4.3) and extrapolation (Sec. 4.5).
+
+Input: profiling records <key, micro, G, L, w, mean latency> (Sec. 4.2, profiling output).
+Output: a DualTable -- coefficient table <key, w> -> (alpha, beta, gamma, delta) plus one
+extrapolation tuple per key, and the anchor micro table <key, w, L> -> micro (plus ext).
+
+"key" is the structural (macro) configuration: every parameter that fixes G, L and the number
+of co-resident blocks; "micro" is what is left (Sec. 4.1).
+
+TEST INFRASTRUCTURE: see the package docstring.
+"""
+from __future__ import annotations
+
+from collections import defaultdict
+from dataclasses import dataclass, field
+from typing import NamedTuple, Optional
+
+import numpy as np
+
+
+class Sample(NamedTuple):
+    key: int
+    micro: int
+    G: int
+    L: int
+    w: int
+    us: float
+
+
+class KeyDesc(NamedTuple):
+    bm: int
+    bn: int
+    bk: int
+    nwave: int
+    stages: int
+    occ: int
+    cap: int
+
+
+@dataclass
+class Bucket:
+    theta: tuple = (0.0, 0.0, 0.0, 0.0)   # alpha, beta, gamma, delta
+    status: int = 0                        # 0: no model; else bit0..3 = alpha..delta identified
+    anchors: list = field(default_factory=list)   # [(L, micro)] ascending in L
+
+
+@dataclass
+class DualTable:
+    W: int
+    keys: list            # [KeyDesc]
+    local: list           # local[key][w-1] -> Bucket
+    ext: list             # ext[key] -> Bucket
+
+
+def shared_micro(records) -> Optional[tuple[int, list]]:
+    """Sec. 4.3: for one <key, w, L> group (or one <key, L> group of the merged ext waves) pick
+    the micro with the smallest latency averaged over the group's sampled grid sizes; return
+    (micro, [(G, L, us)] of that micro).  A micro lacking a record for any grid size of the
+    group is ineligible; ties go to the lowest micro id.  None when no micro is eligible.
+    """
+    grid = {r.G for r in records}
+    by_micro = defaultdict(list)
+    for r in records:
+        by_micro[r.micro].append(r)
+    best = None
+    for micro in sorted(by_micro):
+        rs = by_micro[micro]
+        if {r.G for r in rs} != grid:
+            continue
+        mean = sum(r.us for r in rs) / len(rs)
+        if best is None or mean < best[0]:
+            best = (mean, micro, rs)
+    if best is None:
+        return None
+    return best[1], [(r.G, r.L, r.us) for r in best[2]]
+
+
+def fit_bilinear(rows) -> tuple[tuple, int]:
+    """Ordinary least squares of T ~ alpha*G*L + beta*G + gamma*L + delta (Sec. 4.3, bucket
+    model; Sec. 5.1 "least-squares regression").  rows = [(G, L, T)].
+
+    Solved in centred, scaled variables u=(G-g0)/sg, v=(L-l0)/sl (on a product grid the columns
+    uv, u, v, 1 are mutually orthogonal), then mapped back.  With a single distinct G (or L) the
+    terms that cannot be identified are dropped and their coefficients set to 0.
+    Returns ((alpha, beta, gamma, delta), status bitmask).
+    """
+    if not rows:
+        return (0.0, 0.0, 0.0, 0.0), 0
+    G = np.array([r[0] for r in rows], dtype=np.float64)
+    L = np.array([r[1] for r in rows], dtype=np.float64)
+    T = np.array([r[2] for r in rows], dtype=np.float64)
+    nG, nL = len(set(G.tolist())), len(set(L.tolist()))
+    g0, l0 = float(G.mean()), float(L.mean())
+    sg = float(np.max(np.abs(G - g0))) or 1.0
+    sl = float(np.max(np.abs(L - l0))) or 1.0
+    u, v, one = (G - g0) / sg, (L - l0) / sl, np.ones_like(G)
+    a = b = c = 0.0
+    if nG >= 2 and nL >= 2:
+        sol = np.linalg.lstsq(np.stack([u * v, u, v, one], axis=1), T, rcond=None)[0]
+        a, b, c, d = (float(x) for x in sol)
+        status = 0b1111
+    elif nG >= 2:
+        sol = np.linalg.lstsq(np.stack([u, one], axis=1), T, rcond=None)[0]
+        b, d = float(sol[0]), float(sol[1])
+        status = 0b1010
+    elif nL >= 2:
+        sol = np.linalg.lstsq(np.stack([v, one], axis=1), T, rcond=None)[0]
+        c, d = float(sol[0]), float(sol[1])
+        status = 0b1100
+    else:
+        d = float(T.mean())
+        status = 0b1000
+    alpha = a / (sg * sl)
+    beta = b / sg - a * l0 / (sg * sl)
+    gamma = c / sl - a * g0 / (sg * sl)
+    delta = d - b * g0 / sg - c * l0 / sl + a * g0 * l0 / (sg * sl)
+    return (alpha, beta, gamma, delta), status
+
+
+def _fit_group(records) -> Bucket:
+    """Shared micro per L, then one bilinear fit over the chosen micros' rows."""
+    by_L = defaultdict(list)
+    for r in records:
+        by_L[r.L].append(r)
+    rows, anchors = [], []
+    for L in sorted(by_L):
+        pick = shared_micro(by_L[L])
+        if pick is None:
+            continue
+        anchors.append((L, pick[0]))
+        rows.extend(pick[1])
+    theta, status = fit_bilinear(rows)
+    return Bucket(theta=theta, status=status, anchors=anchors)
+
+
+def fit_tables(samples, keys, W: int, p: int) -> DualTable:
+    """Build the dual table (Sec. 4.3) with per-key extrapolation entries fitted on the merged
+    samples of the last p profiled waves, max(1, W-p+1)..W (Sec. 4.5).  Samples with w > W are
+    ignored."""
+    per_key_w = defaultdict(list)
+    for s in samples:
+        s = Sample(*s)
+        if 1 <= s.w <= W:
+            per_key_w[(s.key, s.w)].append(s)
+    local, ext = [], []
+    lo = max(1, W - p + 1)
+    for k in range(len(keys)):
+        local.append([_fit_group(per_key_w.get((k, w), [])) for w in range(1, W + 1)])
+        merged = [s for w in range(lo, W + 1) for s in per_key_w.get((k, w), [])]
+        ext.append(_fit_group(merged))
+    return DualTable(W=W, keys=list(keys), local=local, ext=ext)
+
+
+def r_squared(rows, theta) -> float:
+    """Coefficient of determination of a fitted bucket on its own rows (Fig. 5 reports ~0.999)."""
+    T = np.array([r[2] for r in rows], dtype=np.float64)
+    pred = np.array([theta[0] * r[0] * r[1] + theta[1] * r[0] + theta[2] * r[1] + theta[3] for r in rows])
+    ss_tot = float(np.sum((T - T.mean()) ** 2))
+    return 1.0 - float(np.sum((T - pred) ** 2)) / ss_tot if ss_tot > 0 else 1.0

@@ -1,0 +1,92 @@
+"""Oracle sparse structural sampling (Sec. 4.2).
+
+Wave-aligned regions are cut into I sub-intervals; each contributes the largest grid size that
+factors into a nearly square 2D block grid; every grid size is paired with every loop anchor
+and turned into a concrete (M, N, K).
+
+TEST INFRASTRUCTURE: see the package docstring.
+"""
+from __future__ import annotations
+
+import math
+from typing import NamedTuple, Optional
+
+from .geometry import wave_region
+
+
+class GridSample(NamedTuple):
+    w: int   # wave index, 1-based
+    i: int   # sub-interval index, 1-based
+    g: int   # representative grid size (0 when the sub-interval has none)
+    m: int   # block-grid rows (m <= n)
+    n: int   # block-grid columns
+
+
+def sub_interval(w: int, i: int, cap: int, I: int) -> tuple[int, int]:
+    """[a, b] of the i-th of I parts of R_w (Sec. 4.2).  The paper does not say how to split
+    when I does not divide cap; this reading uses floors: offsets floor((i-1)*cap/I)+1 ..
+    floor(i*cap/I), which tile R_w exactly and are equal-sized when I | cap."""
+    if not (1 <= i <= I):
+        raise ValueError("1 <= i <= I")
+    lo, _ = wave_region(w, cap)
+    a = lo + ((i - 1) * cap) // I
+    b = lo - 1 + (i * cap) // I
+    return a, b
+
+
+def most_square(g: int) -> tuple[int, int]:
+    """(m, n) with m*n = g, m <= n and m the largest divisor of g not exceeding sqrt(g)."""
+    if g < 1:
+        raise ValueError("g >= 1")
+    m = math.isqrt(g)
+    while g % m:
+        m -= 1
+    return m, g // m
+
+
+def qualifies(m: int, n: int, tau_num: int, tau_den: int) -> bool:
+    """Aspect-ratio constraint n/m <= tau with tau = tau_num/tau_den, compared in integers."""
+    return m <= n and n * tau_den <= m * tau_num
+
+
+def representative(a: int, b: int, tau_num: int, tau_den: int) -> Optional[tuple[int, int, int]]:
+    """Largest g in [a, b] with a factorisation g = m*n, m <= n, n/m <= tau (Sec. 4.2).
+
+    A value qualifies iff its most-square factorisation does (that one minimises n/m), so the
+    scan tests only that factorisation.  Returns (g, m, n) or None when nothing qualifies.
+    """
+    for g in range(b, a - 1, -1):
+        if g < 1:
+            break
+        m, n = most_square(g)
+        if qualifies(m, n, tau_num, tau_den):
+            return g, m, n
+    return None
+
+
+def sample_set(cap: int, W: int, I: int, tau_num: int = 11, tau_den: int = 10) -> list[GridSample]:
+    """The sampling set {g_{w,i}} (Sec. 4.2), w-major then i; empty sub-intervals have g = 0."""
+    out = []
+    for w in range(1, W + 1):
+        for i in range(1, I + 1):
+            a, b = sub_interval(w, i, cap, I)
+            r = representative(a, b, tau_num, tau_den) if b >= a else None
+            out.append(GridSample(w, i, *(r if r else (0, 0, 0))))
+    return out
+
+
+def instantiate(m: int, n: int, L: int, BM: int, BN: int, BK: int) -> tuple[int, int, int]:
+    """Sec. 4.2, workload instantiation: M = m_G*T_M, N = n_G*T_N, K = L*T_K."""
+    return m * BM, n * BN, L * BK
+
+
+def loop_anchors(k_anchors, BK: int) -> list[int]:
+    """Loop counts for a list of K anchors under tile depth BK: L_j = ceil(K_j / BK), ascending,
+    duplicates removed.  (The paper lists anchors in K -- five spanning [1024, 5120] -- so the
+    loop anchors differ per tile depth.)"""
+    return sorted({-(-int(k) // BK) for k in k_anchors})
+
+
+def profile_budget(n_grid: int, n_loop: int, n_macro: int, n_micro: int) -> int:
+    """Sec. 4.2, profiling complexity: N_profile = |G| * |L| * |C_macro| * |C_micro|."""
+    return n_grid * n_loop * n_macro * n_micro

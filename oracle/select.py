@@ -1,0 +1,107 @@
+"""Oracle two-stage runtime selection (Sec. 4.4) with the extrapolation rule (Sec. 4.5), and a
+reader for the binary dual-table file written by the product library, so that lookups can be
+compared bit-for-bit on the very same table.
+
+TEST INFRASTRUCTURE: see the package docstring.
+"""
+from __future__ import annotations
+
+import math
+import struct
+
+import numpy as np
+
+from .fit import Bucket, DualTable, KeyDesc
+from .geometry import phi_gemm, wave_count
+
+
+def predict(theta, G: int, L: int) -> float:
+    """T-hat = alpha*G*L + beta*G + gamma*L + delta (Sec. 4.3 bucket model), evaluated in IEEE
+    binary64 as ((alpha*(G*L) + beta*G) + gamma*L) + delta with G*L formed exactly in integers.
+    Python floats never fuse multiply-add, so each product and sum rounds once."""
+    a, b, c, d = theta
+    return ((a * float(G * L) + b * float(G)) + c * float(L)) + d
+
+
+def bucket_for(table: DualTable, key: int, w: int):
+    """Sec. 4.5 rule: wave-local coefficients when w <= W (and that bucket was fitted), the
+    extrapolation tuple otherwise.  Returns the Bucket or None when the key has no model."""
+    if 1 <= w <= table.W:
+        b = table.local[key][w - 1]
+        if b.status:
+            return b
+    b = table.ext[key]
+    return b if b.status else None
+
+
+def nearest_anchor(anchors, L: int):
+    """Sec. 4.4 Stage II: anchor minimising |L* - L_i|; equal distances go to the smaller anchor."""
+    best = None
+    for (La, micro) in anchors:
+        d = abs(L - La)
+        if best is None or d < best[0]:
+            best = (d, La, micro)
+    return best[1], best[2]
+
+
+def select(table: DualTable, M: int, N: int, K: int):
+    """Stage I: argmin over keys of T-hat (strict '<', so ties keep the lowest key id);
+    Stage II: nearest loop anchor in the chosen bucket.  Returns (key, micro, T-hat) or None."""
+    best = None
+    for k, kd in enumerate(table.keys):
+        G, L = phi_gemm(M, N, K, kd.bm, kd.bn, kd.bk)
+        w = wave_count(G, kd.cap)
+        b = bucket_for(table, k, w)
+        if b is None:
+            continue
+        t = predict(b.theta, G, L)
+        if math.isnan(t):
+            continue
+        if best is None or t < best[0]:
+            best = (t, k, b, L)
+    if best is None:
+        return None
+    t, k, b, L = best
+    _, micro = nearest_anchor(b.anchors, L) if b.anchors else (0, 0)
+    return k, micro, t
+
+
+# ---- reader for the product's table file ------------------------------------------------------
+MAGIC = b"WTDT"
+
+
+def read_table(path: str) -> tuple[DualTable, dict]:
+    """Parse the flat little-endian dual-table file.
+
+    Header, 16 uint32: magic 'WTDT', version (1), n_keys, W, I, p, tau_num, tau_den, n_cu,
+    A (anchor slots per bucket), in_type, out_type, key_mode, 3 reserved.
+    Then per key: 8 int32 (bm, bn, bk, nwave, stages, occ, n_micro, reserved), int64 cap,
+    (W+1)*4 float64 theta (rows w=1..W, then ext), (W+1) int32 status, (W+1) int32 n_anchor,
+    (W+1)*A int32 anchor L, (W+1)*A int32 anchor micro.
+    """
+    raw = open(path, "rb").read()
+    hdr = struct.unpack_from("<4s15I", raw, 0)
+    if hdr[0] != MAGIC or hdr[1] != 1:
+        raise ValueError("not a version-1 dual table")
+    n_keys, W, I, p, tnum, tden, n_cu, A, in_t, out_t, mode = hdr[2:13]
+    off = 64
+    keys, local, ext = [], [], []
+    for _ in range(n_keys):
+        bm, bn, bk, nwave, stages, occ, n_micro, _r = struct.unpack_from("<8i", raw, off); off += 32
+        (cap,) = struct.unpack_from("<q", raw, off); off += 8
+        theta = np.frombuffer(raw, dtype="<f8", count=(W + 1) * 4, offset=off).reshape(W + 1, 4); off += (W + 1) * 32
+        status = np.frombuffer(raw, dtype="<i4", count=W + 1, offset=off); off += (W + 1) * 4
+        n_anchor = np.frombuffer(raw, dtype="<i4", count=W + 1, offset=off); off += (W + 1) * 4
+        aL = np.frombuffer(raw, dtype="<i4", count=(W + 1) * A, offset=off).reshape(W + 1, A); off += (W + 1) * A * 4
+        aM = np.frombuffer(raw, dtype="<i4", count=(W + 1) * A, offset=off).reshape(W + 1, A); off += (W + 1) * A * 4
+        keys.append(KeyDesc(bm, bn, bk, nwave, stages, occ, cap))
+        buckets = []
+        for r in range(W + 1):
+            anchors = [(int(aL[r, j]), int(aM[r, j])) for j in range(int(n_anchor[r]))]
+            buckets.append(Bucket(theta=tuple(float(x) for x in theta[r]), status=int(status[r]), anchors=anchors))
+        local.append(buckets[:W])
+        ext.append(buckets[W])
+    if off != len(raw):
+        raise ValueError("trailing bytes in dual table")
+    meta = dict(I=I, p=p, tau_num=tnum, tau_den=tden, n_cu=n_cu, A=A, in_type=in_t, out_type=out_t, key_mode=mode)
+    return DualTable(W=W, keys=keys, local=local, ext=ext), meta

@@ -1,0 +1,259 @@
+"""Pins for oracle/fit.py, oracle/select.py and oracle/exhaustive.py: closed forms, exact
+rational least squares, known generating surfaces, and brute force over the generating
+function."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import wt_synth
+from _pins import load_pins
+from oracle import exhaustive as oex
+from oracle import fit as ofit
+from oracle import geometry as geo
+from oracle import sampler as smp
+from oracle import select as osel
+
+P = load_pins()
+
+
+def _exact_ls(rows, cols):
+    """Exact rational least squares through the normal equations (Gauss-Jordan on Fractions)."""
+    X = [[Fraction(f(r)) for f in cols] for r in rows]
+    y = [Fraction(r[2]) for r in rows]
+    n = len(cols)
+    A = [[sum(X[k][i] * X[k][j] for k in range(len(X))) for j in range(n)]
+         + [sum(X[k][i] * y[k] for k in range(len(X)))] for i in range(n)]
+    for c in range(n):
+        piv = next(r for r in range(c, n) if A[r][c] != 0)
+        A[c], A[piv] = A[piv], A[c]
+        A[c] = [v / A[c][c] for v in A[c]]
+        for r in range(n):
+            if r != c:
+                A[r] = [vr - A[r][c] * vc for vr, vc in zip(A[r], A[c])]
+    return [float(A[i][n]) for i in range(n)]
+
+
+FULL = (lambda r: r[0] * r[1], lambda r: r[0], lambda r: r[1], lambda r: 1)
+
+
+def test_two_by_two_closed_form():
+    # four points on a 2x2 grid are interpolated exactly:
+    # alpha = (T11 - T12 - T21 + T22) / ((G1-G2)(L1-L2))
+    G1, G2, L1, L2 = 300, 500, 16, 80
+    T = {(G1, L1): 10.0, (G1, L2): 31.0, (G2, L1): 14.5, (G2, L2): 52.0}
+    rows = [(g, l, t) for (g, l), t in T.items()]
+    (a, b, c, d), status = ofit.fit_bilinear(rows)
+    assert status == 0b1111
+    alpha = (T[G1, L1] - T[G1, L2] - T[G2, L1] + T[G2, L2]) / ((G1 - G2) * (L1 - L2))
+    assert abs(a - alpha) < 1e-15
+    for g, l, t in rows:
+        assert abs(a * g * l + b * g + c * l + d - t) < 1e-11
+
+
+def test_fit_matches_exact_rational_least_squares():
+    rng = np.random.default_rng(4)
+    Gs, Ls = [9985, 10050, 10111, 10240], [16, 32, 48, 64, 80]
+    rows = [(g, l, int(rng.integers(100, 100000))) for g in Gs for l in Ls]   # integer "latencies"
+    theta, _ = ofit.fit_bilinear(rows)
+    want = _exact_ls(rows, FULL)
+    # compare through predictions and through coefficients (well-conditioned after centring)
+    assert np.allclose(theta, want, rtol=1e-8, atol=0)
+
+
+def test_recovers_known_surface_far_from_origin():
+    th = (3.1e-4, 2.0e-2, 0.7, 5.0)
+    rows = [(g, l, th[0] * g * l + th[1] * g + th[2] * l + th[3])
+            for g in (20225, 20300, 20449, 20480) for l in (8, 16, 24, 32, 40)]
+    got, _ = ofit.fit_bilinear(rows)
+    assert np.allclose(got, th, rtol=1e-9)
+
+
+def test_one_dimensional_reductions():
+    rows = [(g, 32, 2.5 * g + 7.0 + e) for g, e in zip((10, 20, 30, 40), (0.1, -0.2, 0.05, 0.05))]
+    (a, b, c, d), status = ofit.fit_bilinear(rows)
+    slope, icpt = np.polyfit([r[0] for r in rows], [r[2] for r in rows], 1)
+    assert status == 0b1010 and a == 0 and c == 0
+    assert abs(b - slope) < 1e-12 and abs(d - icpt) < 1e-10
+    rows = [(77, l, 0.5 * l + 1.0) for l in (16, 32, 64)]
+    (a, b, c, d), status = ofit.fit_bilinear(rows)
+    assert status == 0b1100 and a == 0 and b == 0 and abs(c - 0.5) < 1e-13 and abs(d - 1.0) < 1e-12
+    (a, b, c, d), status = ofit.fit_bilinear([(5, 6, 2.0), (5, 6, 4.0)])
+    assert status == 0b1000 and (a, b, c) == (0, 0, 0) and d == 3.0
+    assert ofit.fit_bilinear([]) == ((0.0, 0.0, 0.0, 0.0), 0)
+
+
+def test_shared_micro_minimises_the_average_not_each_point():
+    # micro 0 wins at three grid sizes by a hair, micro 1 wins the average by a lot
+    S = ofit.Sample
+    recs = [S(0, 0, 10, 4, 1, 1.0), S(0, 0, 20, 4, 1, 1.0), S(0, 0, 30, 4, 1, 1.0), S(0, 0, 40, 4, 1, 9.0),
+            S(0, 1, 10, 4, 1, 1.1), S(0, 1, 20, 4, 1, 1.1), S(0, 1, 30, 4, 1, 1.1), S(0, 1, 40, 4, 1, 2.0)]
+    micro, rows = ofit.shared_micro(recs)
+    assert micro == 1 and sorted(rows) == [(10, 4, 1.1), (20, 4, 1.1), (30, 4, 1.1), (40, 4, 2.0)]
+    # ties go to the lowest id; a micro missing a grid size is ineligible
+    tie = [S(0, 2, 10, 4, 1, 1.0), S(0, 1, 10, 4, 1, 1.0)]
+    assert ofit.shared_micro(tie)[0] == 1
+    part = [S(0, 0, 10, 4, 1, 0.1), S(0, 1, 10, 4, 1, 1.0), S(0, 1, 20, 4, 1, 1.0)]
+    assert ofit.shared_micro(part)[0] == 1
+    assert ofit.shared_micro([S(0, 0, 10, 4, 1, 1.0), S(0, 1, 20, 4, 1, 1.0)]) is None
+
+
+# ---- a synthetic tuning problem with a known answer -------------------------------------------
+KEYS = [ofit.KeyDesc(256, 256, 64, 4, 2, 1, 256), ofit.KeyDesc(128, 128, 64, 4, 2, 2, 512),
+        ofit.KeyDesc(64, 64, 64, 4, 2, 5, 1280), ofit.KeyDesc(128, 64, 32, 4, 3, 3, 768),
+        ofit.KeyDesc(16, 64, 128, 1, 2, 8, 2048)]
+K_ANCHORS = (1024, 2048, 3072, 4096, 5120)
+N_MICRO = 3
+
+
+def _surface_theta(key, w, W, seed=21):
+    """Per-<key, w> generating coefficients; waves beyond W continue the last bucket's."""
+    th = wt_synth.random_theta(seed + 97 * key, W + 1)
+    return th[min(w, W) - 1]
+
+
+def _latency(key, micro, G, L, W, micro_penalty):
+    kd = KEYS[key]
+    w = geo.wave_count(G, kd.cap)
+    a, b, c, d = _surface_theta(key, w, W)
+    base = a * G * L + b * G + c * L + d
+    return base * (1.0 + micro_penalty(key, micro, L))
+
+
+def _make_samples(W, I, micro_penalty):
+    out = []
+    for k, kd in enumerate(KEYS):
+        for s in smp.sample_set(kd.cap, W, I):
+            for L in smp.loop_anchors(K_ANCHORS, kd.bk):
+                for mi in range(N_MICRO):
+                    out.append(ofit.Sample(k, mi, s.g, L, s.w, _latency(k, mi, s.g, L, W, micro_penalty)))
+    return out
+
+
+def _penalty(key, micro, L):
+    # best micro depends on the loop count: micro 0 below L=40, micro 2 from 40 up; micro 1 never
+    best = 0 if L < 40 else 2
+    return 0.0 if micro == best else 0.05 * (1 + micro)
+
+
+def test_fit_recovers_every_bucket_and_the_step_surface():
+    W, I = 6, 4
+    table = ofit.fit_tables(_make_samples(W, I, _penalty), KEYS, W, p=3)
+    for k in range(len(KEYS)):
+        for w in range(1, W + 1):
+            b = table.local[k][w - 1]
+            assert b.status == 0b1111
+            assert np.allclose(b.theta, _surface_theta(k, w, W), rtol=1e-7)
+            La = smp.loop_anchors(K_ANCHORS, KEYS[k].bk)
+            assert [a[0] for a in b.anchors] == La
+            assert [a[1] for a in b.anchors] == [0 if L < 40 else 2 for L in La]
+    # pure step surface T = mu * ceil(G/cap) * L (zero-variance simulation scaled by L): inside
+    # bucket w the fit must find gamma = mu*w and nothing else -> buckets are isolated and w is
+    # computed with the right capacity
+    mu = float(P["fig4_mu"])
+    samples = [ofit.Sample(k, 0, s.g, L, s.w, mu * geo.wave_count(s.g, kd.cap) * L)
+               for k, kd in enumerate(KEYS) for s in smp.sample_set(kd.cap, W, I)
+               for L in smp.loop_anchors(K_ANCHORS, kd.bk)]
+    step = ofit.fit_tables(samples, KEYS, W, p=1)
+    for k in range(len(KEYS)):
+        for w in range(1, W + 1):
+            a, b, c, d = step.local[k][w - 1].theta
+            assert abs(c - mu * w) < 1e-6 * mu and abs(a) < 1e-9 and abs(b) < 1e-7 and abs(d) < 1e-3
+        assert abs(step.ext[k].theta[2] - mu * W) < 1e-6 * mu      # p=1: ext is the last wave
+
+
+def test_ext_merges_exactly_the_last_p_waves():
+    W, I, p = 8, 4, 3
+    samples = _make_samples(W, I, _penalty)
+    table = ofit.fit_tables(samples, KEYS, W, p)
+    for k in range(len(KEYS)):
+        merged = [s for s in samples if s.key == k and W - p + 1 <= s.w <= W]
+        rows = []
+        for L in sorted({s.L for s in merged}):
+            micro, r = ofit.shared_micro([s for s in merged if s.L == L])
+            rows += r
+        assert len(rows) == p * I * len(smp.loop_anchors(K_ANCHORS, KEYS[k].bk))
+        want, _ = ofit.fit_bilinear(rows)
+        assert np.allclose(table.ext[k].theta, want, rtol=1e-12)
+    # W < p: the merge starts at wave 1
+    t2 = ofit.fit_tables(_make_samples(2, 2, _penalty), KEYS, 2, p=10)
+    assert all(b.status == 0b1111 for b in t2.ext)
+
+
+def test_select_equals_brute_force_over_the_generating_function():
+    W, I = 6, 4
+    table = ofit.fit_tables(_make_samples(W, I, _penalty), KEYS, W, p=3)
+    shapes = [(m, n, k) for m in (1, 17, 100, 256, 333, 1024, 2000) for (n, k) in ((4096, 4096), (1536, 2048), (2304, 5120))]
+    n_in_range = 0
+    for (M, N, K) in shapes:
+        cand = []
+        for kid, kd in enumerate(KEYS):
+            G, L = geo.phi_gemm(M, N, K, kd.bm, kd.bn, kd.bk)
+            if geo.wave_count(G, kd.cap) > W:
+                cand = None
+                break
+            for mi in range(N_MICRO):
+                cand.append(((kid, mi), _latency(kid, mi, G, L, W, _penalty)))
+        if cand is None:
+            continue
+        n_in_range += 1
+        (bk, bm), bt = oex.argmin_config(cand)
+        key, micro, t = osel.select(table, M, N, K)
+        assert key == bk and abs(t - bt) <= 1e-7 * bt
+        # the micro comes from the nearest anchor; at the anchors' own L it is the generating best
+        L = geo.phi_gemm(M, N, K, *KEYS[key][:3])[1]
+        if L in smp.loop_anchors(K_ANCHORS, KEYS[key].bk):
+            assert micro == bm
+    assert n_in_range >= 10
+
+
+def test_extrapolation_rule_switches_on_w_greater_than_W():
+    W = 3
+    table = ofit.fit_tables(_make_samples(W, 4, _penalty), KEYS, W, p=2)
+    for b in table.ext:                       # make the ext entries unmistakable
+        b.theta = (0.0, 0.0, 0.0, 1.0e9)
+    table.ext[2].theta = (0.0, 0.0, 0.0, 123.0)
+    table.ext[2].anchors = [(16, 1), (80, 2)]
+    # 16384 x 16384: every key needs far more than 3 waves -> all use ext, key 2 wins
+    key, micro, t = osel.select(table, 16384, 16384, 4096)
+    assert (key, t) == (2, 123.0) and micro == 2          # L = 64 is nearer to 80 than to 16
+    # a small shape stays inside the profiled range and must not see the ext entries
+    key, _, t = osel.select(table, 256, 256, 1024)
+    assert t < 1.0e6
+    # an unfitted local bucket falls back to ext
+    table.local[0][0].status = 0
+    assert osel.bucket_for(table, 0, 1) is table.ext[0]
+    assert osel.bucket_for(table, 0, 2) is table.local[0][1]
+    assert osel.bucket_for(table, 0, W + 1) is table.ext[0]
+
+
+def test_nearest_anchor_cases():
+    anchors = [(16, 5), (32, 6), (48, 7)]
+    assert osel.nearest_anchor(anchors, 1) == (16, 5)        # below the first
+    assert osel.nearest_anchor(anchors, 500) == (48, 7)      # above the last
+    assert osel.nearest_anchor(anchors, 24) == (16, 5)       # exactly mid-way -> smaller anchor
+    assert osel.nearest_anchor(anchors, 25) == (32, 6)
+    assert osel.nearest_anchor(anchors, 32) == (32, 6)
+
+
+def test_stage_one_ties_keep_the_lowest_key():
+    keys = [ofit.KeyDesc(64, 64, 64, 4, 2, 1, 256)] * 3
+    mk = lambda th: ofit.Bucket(theta=th, status=15, anchors=[(8, 1)])
+    table = ofit.DualTable(W=1, keys=keys, local=[[mk((0, 0, 0, 2.0))], [mk((0, 0, 0, 1.0))], [mk((0, 0, 0, 1.0))]],
+                           ext=[mk((0, 0, 0, 9.0))] * 3)
+    assert osel.select(table, 64, 64, 64)[:2] == (1, 1)
+
+
+def test_predict_is_the_bilinear_form():
+    assert osel.predict((2.0, 3.0, 5.0, 7.0), 11, 13) == 2 * 143 + 33 + 65 + 7
+    assert osel.predict((0.5, 0.0, 0.0, 0.0), 3, 5) == 7.5
+
+
+def test_exhaustive_helpers():
+    assert oex.argmin_config([(0, 3.0), (1, float("nan")), (2, 1.0), (3, 1.0)]) == (2, 1.0)
+    with pytest.raises(ValueError):
+        oex.argmin_config([(0, float("inf"))])
+    res = oex.search([1, 2], [10, 20, 30], lambda s, c: abs(c - 15 * s))
+    assert res == [(10, 5), (30, 0)]
+    assert oex.fraction_of_best(2.0, 1.0) == 0.5
+    assert abs(oex.geomean([0.5, 2.0]) - 1.0) < 1e-15

@@ -1,0 +1,110 @@
+"""Seeded synthetic inputs shared by the HIP path's tests, the CPU oracle's tests and bench.py.
+
+This module only *draws data*: random matrices in their storage encodings, shape lists and
+latency surfaces used as stand-ins for measurements.  It holds none of the method's arithmetic
+(no GEMM, no tile/wave geometry, no sampling rule, no fit, no lookup) and imports neither the
+oracle nor the HIP binding.  Storage encodings are produced with PyTorch's CPU dtype casts, so
+neither side under test is used to make its own inputs.
+
+Workload recipe (stand-in for the paper's Dense-GEMM shape sets, which are not public):
+values are N(0,1) drawn with numpy's PCG64 from a seed, rounded once to the storage type.
+"""
+from __future__ import annotations
+
+import math
+import zlib
+
+import numpy as np
+import torch
+
+E4M3_MAX = 448.0  # largest finite magnitude of OCP FP8 E4M3 (the "fn" flavour)
+
+# (N, K) pairs of the LLM-projection sweep and of the runtime stream.
+SWEEP_M = (1, 16, 17, 64, 100, 256, 333, 1024, 4096)
+SWEEP_NK = ((4096, 4096), (11008, 4096), (4096, 11008))
+STREAM_NK = ((8192, 8192), (28672, 8192), (8192, 28672), (10240, 8192))
+
+
+def shape_seed(base: int, M: int, N: int, K: int) -> int:
+    """Deterministic per-shape sub-seed (CRC32 of the shape mixed with a base seed)."""
+    return (base * 1000003 + zlib.crc32(f"{M}x{N}x{K}".encode())) & 0x7FFFFFFF
+
+
+def normal_f32(rows: int, cols: int, seed: int) -> np.ndarray:
+    """rows x cols standard-normal fp32 matrix from a seed."""
+    rng = np.random.default_rng(seed)
+    return rng.standard_normal((rows, cols), dtype=np.float32)
+
+
+def small_int_f32(rows: int, cols: int, seed: int, lo: int = -8, hi: int = 8) -> np.ndarray:
+    """Integer-valued fp32 matrix with entries in [lo, hi] (exact in bf16 and in e4m3)."""
+    rng = np.random.default_rng(seed)
+    return rng.integers(lo, hi + 1, size=(rows, cols)).astype(np.float32)
+
+
+def to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """fp32 -> bf16 storage bits (uint16), round-to-nearest-even, via torch's CPU cast."""
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.bfloat16)
+    return t.view(torch.int16).numpy().view(np.uint16).copy()
+
+
+def to_e4m3_bits(x: np.ndarray) -> tuple[np.ndarray, np.float32]:
+    """fp32 -> (e4m3 storage bytes, per-tensor fp32 scale s) with s = amax/448, q = rne(x/s).
+
+    x/s is clamped to +-448 before the cast, so the encoding saturates instead of producing NaN.
+    An all-zero tensor gets s = 1.
+    """
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    amax = np.float32(np.max(np.abs(x))) if x.size else np.float32(0.0)
+    s = np.float32(amax / np.float32(E4M3_MAX)) if amax > 0 else np.float32(1.0)
+    y = np.clip(x / s, -E4M3_MAX, E4M3_MAX).astype(np.float32)
+    q = torch.from_numpy(y).to(torch.float8_e4m3fn)
+    return q.view(torch.uint8).numpy().copy(), s
+
+
+def gemm_operands(M: int, N: int, K: int, seed: int, kind: str = "normal"):
+    """fp32 A[M,K] and B[N,K] (both K-contiguous) for one GEMM; kind is 'normal' or 'int'."""
+    gen = normal_f32 if kind == "normal" else small_int_f32
+    return gen(M, K, seed), gen(N, K, seed + 1)
+
+
+def sweep_shapes():
+    """The 27 LLM-projection shapes (M x (N,K))."""
+    return [(m, n, k) for (n, k) in SWEEP_NK for m in SWEEP_M]
+
+
+def wave_stress_shapes():
+    """M=K=4096, N = 128..16384 step 128 (128 shapes)."""
+    return [(4096, n, 4096) for n in range(128, 16384 + 1, 128)]
+
+
+def stream_shapes(count: int = 10000, seed: int = 1005):
+    """Runtime stream: M log-uniform in [1,8192], (N,K) uniform over STREAM_NK; duplicates kept."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        u = rng.random()
+        m = int(min(8192, max(1, round(math.exp(u * math.log(8192.0))))))
+        n, k = STREAM_NK[int(rng.integers(0, len(STREAM_NK)))]
+        out.append((m, n, k))
+    return out
+
+
+def noise_factors(n: int, seed: int, rel: float) -> np.ndarray:
+    """n multiplicative noise factors 1 + rel*N(0,1), clipped to stay positive."""
+    rng = np.random.default_rng(seed)
+    return np.clip(1.0 + rel * rng.standard_normal(n), 0.05, None)
+
+
+def random_theta(seed: int, count: int) -> np.ndarray:
+    """count random positive coefficient tuples (alpha, beta, gamma, delta) in microseconds.
+
+    Magnitudes follow a GEMM-like surface: alpha ~ 1e-4..1e-3 us per (tile x loop), beta and
+    gamma ~ 1e-3..1e-1, delta ~ 1..10.  Used to synthesise latency tables with a known optimum.
+    """
+    rng = np.random.default_rng(seed)
+    a = 10.0 ** rng.uniform(-4.0, -3.0, count)
+    b = 10.0 ** rng.uniform(-3.0, -1.0, count)
+    g = 10.0 ** rng.uniform(-3.0, -1.0, count)
+    d = 10.0 ** rng.uniform(0.0, 1.0, count)
+    return np.stack([a, b, g, d], axis=1)
