@@ -1,0 +1,158 @@
+/* wt.h -- C ABI of libwt: a tile-parameterised MFMA GEMM for AMD MI355X (gfx950) and the
+ * WaveTune selector that chooses its runtime configuration.
+ *
+ * Paper: "WaveTune: Wave-aware Bilinear Modeling for Efficient GPU Kernel Auto-tuning".
+ * Section / equation references below are to that paper.
+ *
+ * Conventions
+ *   - Every function returns WT_OK (0) or a negative wt_status.  Nothing throws across the ABI.
+ *   - "device pointer" = address in the HBM of the context's GPU; "host pointer" = ordinary memory.
+ *   - The caller owns every buffer and the HIP stream.  wt_gemm and wt_select never allocate.
+ *   - Matrices: A is [M,K] row-major, B is stored K-contiguous as [N,K] row-major (the weight
+ *     layout of a linear layer, so C = A * B^T in storage terms), C is [M,N] row-major.
+ *     K must be a multiple of 8 (bf16) or 16 (fp8): rows are moved in 16-byte pieces.
+ *   - A configuration c = (bm, bn, bk, nwave, stages, swizzle): block tile BM x BN x BK,
+ *     wavefronts per block, LDS pipeline stages, and block-rasterisation mode.  The first five
+ *     form the structural ("macro") key: they fix G, L and how many blocks fit on a compute
+ *     unit.  swizzle is the micro parameter (Sec. 4.1: macro governs partitioning, wave dynamics
+ *     and dominant occupancy; micro tunes execution efficiency, e.g. rasterisation for L2 reuse).
+ */
+#ifndef WT_H
+#define WT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    WT_OK = 0,
+    WT_ERR_INVALID_ARG = -1,     /* null pointer, negative size, K not a multiple of the vector width */
+    WT_ERR_UNSUPPORTED_CFG = -2, /* (bm,bn,bk,nwave,stages,swizzle) is not in the registry */
+    WT_ERR_INFEASIBLE = -3,      /* config exists but does not fit the device (LDS / registers) */
+    WT_ERR_NOT_FITTED = -4,      /* wt_select / wt_predict_us before wt_fit or wt_load */
+    WT_ERR_HIP = -5,             /* a HIP call failed; see wt_last_hip_error() */
+    WT_ERR_BUFFER_TOO_SMALL = -6,
+    WT_ERR_IO = -7,
+    WT_ERR_NO_DEVICE = -8        /* device work requested from a host-only context */
+} wt_status;
+
+typedef enum { WT_BF16 = 0, WT_FP8_E4M3 = 1 } wt_in_t;   /* storage type of A and B */
+typedef enum { WT_OUT_F32 = 0, WT_OUT_BF16 = 1 } wt_out_t; /* storage type of C */
+
+typedef struct wt_ctx wt_ctx; /* opaque: config registry, per-config resources, dual table */
+
+/* One kernel configuration.  id is the registry index (or -1: look the fields up). */
+typedef struct {
+    int32_t bm, bn, bk, nwave, stages, swizzle;
+    int32_t id;
+} wt_cfg;
+
+/* Resources of a configuration.  occ = blocks resident per compute unit: the HIP runtime's answer
+ * on a device context, a static LDS/wave-slot estimate on a host-only context.  key_id groups
+ * configs that differ only in swizzle; micro_id is the position inside the group. */
+typedef struct {
+    int32_t lds_bytes, vgprs, nwave, occ;
+    int32_t key_id, micro_id;
+} wt_cfg_res;
+
+/* One profiling record <G, L, w, c_macro, c_micro, mean latency> (Sec. 4.2, profiling output). */
+typedef struct {
+    int32_t key_id, micro_id;
+    int64_t G, L;
+    int32_t w;
+    int32_t reserved;
+    double mean_us;
+} wt_sample;
+
+/* Sampling / fitting parameters (Sec. 4.2, 4.5; Sec. 5.1 uses W=40, I=4, tau=11/10, p=10, five K
+ * anchors in [1024,5120], 3 warm-up + 5 measured runs).  key_first/key_count restrict
+ * wt_profile_sparse to a slice of structural keys (0,0 = all) so that profiling can be split
+ * over several calls.  max_out_elems caps M*N of an instantiated workload (0 = no cap): grid
+ * points whose output would exceed it are skipped. */
+typedef struct {
+    int32_t W, I, tau_num, tau_den, p;
+    int32_t n_k_anchors;
+    const int32_t* k_anchors; /* host pointer, n_k_anchors entries */
+    int32_t warmup, iters;
+    int32_t key_first, key_count;
+    int64_t max_out_elems;
+} wt_grid;
+
+/* ---- context ------------------------------------------------------------------------------ */
+/* device >= 0: bind to that GPU, query kernel resources.  device = -1: host-only context (Phi,
+ * sampler, fit, select, save/load work; wt_gemm and wt_profile_sparse return WT_ERR_NO_DEVICE). */
+int wt_create(wt_ctx** out, int device, int in_type, int out_type);
+int wt_destroy(wt_ctx* ctx);
+int wt_last_hip_error(const wt_ctx* ctx);          /* hipError_t of the last failing HIP call */
+const char* wt_status_string(int status);
+
+/* ---- config registry ---------------------------------------------------------------------- */
+int wt_config_count(const wt_ctx* ctx, int* n);
+int wt_config_get(const wt_ctx* ctx, int i, wt_cfg* cfg, wt_cfg_res* res);
+int wt_config_find(const wt_ctx* ctx, const wt_cfg* fields, int* id); /* match the six fields */
+int wt_key_count(const wt_ctx* ctx, int* n);
+/* Override the recorded occupancy of structural key key_id (e.g. with a measured value). */
+int wt_key_set_occ(wt_ctx* ctx, int key_id, int occ);
+
+/* ---- the GEMM (Sec. 3.2, tiled-GEMM paragraph) ------------------------------------------- */
+/* C[M,N] = A[M,K] * B[N,K]^T under configuration cfg.  A, B, C: device pointers (types per
+ * the context).  scaleA/scaleB: device pointers to one fp32 each, fp8 only (C = sA*sB*sum),
+ * NULL for bf16.  Asynchronous on hip_stream (a hipStream_t, NULL = default stream); never
+ * synchronises, never allocates.  M, N may be any non-negative size (edge tiles are masked);
+ * M*N == 0 is a no-op; K == 0 writes zeros. */
+int wt_gemm(wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
+            const float* scaleA, const float* scaleB, wt_cfg cfg, void* hip_stream);
+
+/* ---- geometry (Table 2 Dense-GEMM row; Sec. 3.2 / 3.3 wave count) ------------------------ */
+/* G = ceil(M/bm)*ceil(N/bn), L = ceil(K/bk), w = ceil(G / (n_cu * occ(cfg))). */
+int wt_wave_count(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, wt_cfg cfg,
+                  int64_t* G, int64_t* L, int32_t* w);
+
+/* ---- sparse structural sampling (Sec. 4.2) ------------------------------------------------ */
+/* Grid samples for a capacity: fills up to cap_out triples (g, m, n) in w-major, i-minor order
+ * (g = 0 where a sub-interval holds no value with a near-square factorisation). */
+int wt_sample_grid(int64_t capacity, int32_t W, int32_t I, int32_t tau_num, int32_t tau_den,
+                   int64_t* g, int64_t* m, int64_t* n, size_t cap_out, size_t* n_out);
+/* Number of records wt_profile_sparse would produce and the scratch bytes it needs. */
+int wt_sample_plan(const wt_ctx* ctx, const wt_grid* grid, size_t* n_samples, size_t* bytesA,
+                   size_t* bytesB, size_t* bytesC);
+/* Instantiate every sample (M = m*bm, N = n*bn, K = L*bk), run every micro with warm-up +
+ * measured launches timed by HIP events on hip_stream, write one record per <key, micro, g, L>.
+ * scrA/scrB/scrC: device scratch of at least the planned sizes (contents: any finite values).
+ * Synchronises the stream. */
+int wt_profile_sparse(wt_ctx* ctx, const wt_grid* grid, void* scrA, void* scrB, void* scrC,
+                      size_t bytesA, size_t bytesB, size_t bytesC, void* hip_stream,
+                      wt_sample* out, size_t cap, size_t* n_out);
+/* Time one (shape, config): warm-up + iters launches, mean microseconds.  Same protocol as
+ * wt_profile_sparse; used for exhaustive search. */
+int wt_time_gemm(wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
+                 const float* scaleA, const float* scaleB, wt_cfg cfg, int warmup, int iters,
+                 void* hip_stream, double* mean_us);
+
+/* ---- modelling (Sec. 4.3, 4.5) ------------------------------------------------------------ */
+/* Build the dual table from records (from the GPU or from any synthetic source).  Host only. */
+int wt_fit(wt_ctx* ctx, const wt_grid* grid, const wt_sample* samples, size_t n);
+
+/* ---- runtime selection (Sec. 4.4, 4.5) ---------------------------------------------------- */
+/* Stage I: argmin over structural keys of the bucket's bilinear prediction (extrapolation tuple
+ * when w > W or the bucket is empty); Stage II: nearest loop anchor -> micro.  Host only,
+ * read-only, thread-safe, no allocation, no system calls. */
+int wt_select(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, wt_cfg* out);
+/* Predicted latency of one configuration's structural key for a shape (microseconds). */
+int wt_predict_us(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, wt_cfg cfg, double* us);
+/* Time n calls of wt_select over a shape list inside the library (steady clock): mean and p99
+ * nanoseconds per call.  shapes: host pointer to n triples (M,N,K). */
+int wt_select_bench(const wt_ctx* ctx, const int64_t* shapes, size_t n, int repeats,
+                    double* mean_ns, double* p99_ns);
+
+/* ---- dual-table artifact ------------------------------------------------------------------- */
+int wt_save(const wt_ctx* ctx, const char* path);
+int wt_load(wt_ctx* ctx, const char* path);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WT_H */

@@ -1,0 +1,65 @@
+"""Build libwt.so (HIP kernels + C ABI) for gfx950, in-tree.
+
+    python -m paper_2604_10187_amd.build [-j N]
+
+Every translation unit is compiled on each call (no staleness checks); objects go to
+paper_2604_10187_amd/_build/, the library to paper_2604_10187_amd/libwt.so.
+"""
+from __future__ import annotations
+
+import argparse
+import os
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+OUT = os.path.join(HERE, "_build")
+LIB = os.path.join(HERE, "libwt.so")
+
+HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wno-unused-command-line-argument",
+             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# (input type, output type) pairs that are compiled: bf16->f32, bf16->bf16, fp8->f32, fp8->bf16
+PAIRS = [(0, 0), (0, 1), (1, 0), (1, 1)]
+LISTS = [0, 1, 2]
+
+
+def _run(cmd):
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("build step failed: " + " ".join(cmd) + "\n" + r.stdout)
+    return r.stdout
+
+
+def build(jobs: int = 8, verbose: bool = False) -> str:
+    os.makedirs(OUT, exist_ok=True)
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    steps, objs = [], []
+    for (i, o) in PAIRS:
+        for l in LISTS:
+            obj = os.path.join(OUT, f"gemm_inst_in{i}_out{o}_list{l}.o")
+            objs.append(obj)
+            steps.append([hipcc, *HIP_FLAGS, f"-DWT_IN={i}", f"-DWT_OUT={o}", f"-DWT_LIST={l}", "-c",
+                          os.path.join(CSRC, "gemm_inst.hip"), "-o", obj])
+    obj = os.path.join(OUT, "wt_api.o")
+    objs.append(obj)
+    steps.append([hipcc, *HIP_FLAGS, "-c", os.path.join(CSRC, "wt_api.hip"), "-o", obj])
+    obj = os.path.join(OUT, "wt_host.o")
+    objs.append(obj)
+    steps.append(["g++", "-O2", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Wall", "-c",
+                  os.path.join(CSRC, "wt_host.cpp"), "-o", obj])
+    with ThreadPoolExecutor(max_workers=max(1, jobs)) as ex:
+        for out in ex.map(_run, steps):
+            if verbose and out.strip():
+                print(out)
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
+    return LIB
+
+
+if __name__ == "__main__":
+    ap = argparse.ArgumentParser()
+    ap.add_argument("-j", type=int, default=min(8, os.cpu_count() or 1))
+    ap.add_argument("-v", action="store_true")
+    a = ap.parse_args()
+    print(build(a.j, a.v))

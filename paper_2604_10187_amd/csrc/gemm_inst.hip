@@ -1,0 +1,43 @@
+// One instantiation unit: compile with -DWT_IN=<0|1> -DWT_OUT=<0|1> -DWT_LIST=<0|1|2>.
+// Expands the matching list of configs.def into kernels and a table of their entry points.
+#include "gemm_kernel.hpp"
+#include "registry.hpp"
+
+#if WT_IN == 0
+#if WT_LIST == 0
+#define WT_LIST_LARGE_BF16
+#elif WT_LIST == 1
+#define WT_LIST_MEDIUM_BF16
+#else
+#define WT_LIST_SMALL_BF16
+#endif
+#else
+#if WT_LIST == 0
+#define WT_LIST_LARGE_FP8
+#elif WT_LIST == 1
+#define WT_LIST_MEDIUM_FP8
+#else
+#define WT_LIST_SMALL_FP8
+#endif
+#endif
+
+#define WT_CAT2(a, b) a##b
+#define WT_CAT(a, b) WT_CAT2(a, b)
+#define WT_FN_NAME WT_CAT(WT_CAT(WT_CAT(WT_CAT(WT_CAT(wt_kernels_in, WT_IN), _out), WT_OUT), _list), WT_LIST)
+
+namespace wt {
+
+#define WT_CFG(BM, BN, BK, WM, WN, ST)                                                      \
+    {BM, BN, BK, WM, WN, ST, GemmTraits<BM, BN, BK, WM, WN, ST, WT_IN, WT_OUT>::LDS_BYTES, \
+     reinterpret_cast<const void*>(&gemm_kernel<BM, BN, BK, WM, WN, ST, WT_IN, WT_OUT>)},
+static const KernelEntry kEntries[] = {
+#include "configs.def"
+};
+#undef WT_CFG
+
+const KernelEntry* WT_FN_NAME(int* n) {
+    *n = static_cast<int>(sizeof(kEntries) / sizeof(kEntries[0]));
+    return kEntries;
+}
+
+}  // namespace wt

@@ -1,0 +1,264 @@
+// Device half of the C ABI: context creation, GEMM launch, event timing, sparse profiling.
+#include <hip/hip_runtime.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "gemm_kernel.hpp"
+#include "wt_internal.hpp"
+
+using namespace wt;
+
+namespace {
+
+#define WT_HIP(ctx, call)                     \
+    do {                                      \
+        hipError_t e_ = (call);               \
+        if (e_ != hipSuccess) {               \
+            (ctx)->last_hip = (int)e_;        \
+            return WT_ERR_HIP;                \
+        }                                     \
+    } while (0)
+
+// Largest K for which BM*K*esize stays below the buffer-offset sentinel for every tile height.
+constexpr int64_t kMaxK = 1 << 21;
+constexpr int64_t kMaxDim = 1 << 30;
+
+int validate_shape(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K) {
+    if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxK) return WT_ERR_INVALID_ARG;
+    const int vec = ctx->in_type == WT_BF16 ? 8 : 16;
+    if (K % vec) return WT_ERR_INVALID_ARG;
+    return WT_OK;
+}
+
+int launch(wt_ctx* ctx, const Config& c, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
+           const float* sA, const float* sB, hipStream_t stream) {
+    const int64_t tiles_m = ceil_div64(M, c.cfg.bm), tiles_n = ceil_div64(N, c.cfg.bn);
+    const int64_t G = tiles_m * tiles_n;
+    if (G == 0) return WT_OK;
+    if (G > 0x7FFFFFFF) return WT_ERR_INVALID_ARG;
+    GemmArgs args;
+    args.A = A; args.B = B; args.C = C; args.scaleA = sA; args.scaleB = sB;
+    args.M = (int)M; args.N = (int)N; args.K = (int)K;
+    args.tiles_m = (int)tiles_m; args.tiles_n = (int)tiles_n;
+    args.swizzle = c.cfg.swizzle;
+    void* params[] = {&args};
+    WT_HIP(ctx, hipLaunchKernel(c.fn, dim3((unsigned)G), dim3((unsigned)(c.cfg.nwave * 64)), params,
+                                (size_t)c.res.lds_bytes, stream));
+    return WT_OK;
+}
+
+int check_gemm_args(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
+                    const float* sA, const float* sB, const wt_cfg& cfg, int* id) {
+    if (!ctx) return WT_ERR_INVALID_ARG;
+    if (ctx->device < 0) return WT_ERR_NO_DEVICE;
+    const int rc = validate_shape(ctx, M, N, K);
+    if (rc != WT_OK) return rc;
+    if (M * N > 0 && (!C || (K > 0 && (!A || !B)))) return WT_ERR_INVALID_ARG;
+    if (ctx->in_type == WT_FP8_E4M3 && M * N > 0 && (!sA || !sB)) return WT_ERR_INVALID_ARG;
+    *id = find_config(ctx, cfg);
+    if (*id < 0) return WT_ERR_UNSUPPORTED_CFG;
+    if (ctx->cfgs[*id].res.occ < 1) return WT_ERR_INFEASIBLE;
+    return WT_OK;
+}
+
+int time_config(wt_ctx* ctx, const Config& c, int64_t M, int64_t N, int64_t K, const void* A, const void* B,
+                void* C, const float* sA, const float* sB, int warmup, int iters, hipStream_t stream,
+                double* mean_us) {
+    hipEvent_t e0 = (hipEvent_t)ctx->ev_start, e1 = (hipEvent_t)ctx->ev_stop;
+    for (int i = 0; i < warmup; ++i) {
+        const int rc = launch(ctx, c, M, N, K, A, B, C, sA, sB, stream);
+        if (rc != WT_OK) return rc;
+    }
+    WT_HIP(ctx, hipEventRecord(e0, stream));
+    for (int i = 0; i < iters; ++i) {
+        const int rc = launch(ctx, c, M, N, K, A, B, C, sA, sB, stream);
+        if (rc != WT_OK) return rc;
+    }
+    WT_HIP(ctx, hipEventRecord(e1, stream));
+    WT_HIP(ctx, hipEventSynchronize(e1));
+    float ms = 0;
+    WT_HIP(ctx, hipEventElapsedTime(&ms, e0, e1));
+    *mean_us = (double)ms * 1000.0 / (double)iters;
+    return WT_OK;
+}
+
+struct Plan {
+    size_t n_samples = 0;
+    size_t bytesA = 0, bytesB = 0, bytesC = 0;
+};
+
+bool key_in_slice(const wt_grid* g, int k, int nk) {
+    if (g->key_count <= 0) return k < nk;
+    return k >= g->key_first && k < g->key_first + g->key_count;
+}
+
+int check_grid(const wt_grid* g) {
+    if (!g || g->W < 1 || g->I < 1 || g->tau_den < 1 || g->tau_num < g->tau_den || g->p < 1 || g->n_k_anchors < 1 ||
+        !g->k_anchors || g->warmup < 0 || g->iters < 1)
+        return WT_ERR_INVALID_ARG;
+    for (int j = 0; j < g->n_k_anchors; ++j)
+        if (g->k_anchors[j] < 1) return WT_ERR_INVALID_ARG;
+    return WT_OK;
+}
+
+// Walk the sampling plan; fn(key, point, L, M, N, K) is called for every workload that will be timed.
+template <typename F>
+int walk_plan(const wt_ctx* ctx, const wt_grid* grid, F&& fn) {
+    const int nk = (int)ctx->keys.size();
+    const size_t esz = ctx->in_type == WT_BF16 ? 2 : 1;
+    (void)esz;
+    std::vector<GridPoint> pts;
+    std::vector<int64_t> anchors;
+    for (int k = 0; k < nk; ++k) {
+        if (!key_in_slice(grid, k, nk)) continue;
+        const Key& key = ctx->keys[k];
+        sample_grid(key.cap, grid->W, grid->I, grid->tau_num, grid->tau_den, pts);
+        loop_anchors(grid, key.bk, anchors);
+        for (size_t s = 0; s < pts.size(); ++s) {
+            if (pts[s].g == 0) continue;
+            const int64_t M = pts[s].m * key.bm, N = pts[s].n * key.bn;
+            if (grid->max_out_elems > 0 && M * N > grid->max_out_elems) continue;
+            const int w = (int)(s / (size_t)grid->I) + 1;
+            for (int64_t L : anchors) {
+                const int rc = fn(k, pts[s], w, L, M, N, L * key.bk);
+                if (rc != WT_OK) return rc;
+            }
+        }
+    }
+    return WT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int wt_create(wt_ctx** out, int device, int in_type, int out_type) {
+    if (!out || (in_type != WT_BF16 && in_type != WT_FP8_E4M3) || (out_type != WT_OUT_F32 && out_type != WT_OUT_BF16))
+        return WT_ERR_INVALID_ARG;
+    *out = nullptr;
+    wt_ctx* ctx = new (std::nothrow) wt_ctx();
+    if (!ctx) return WT_ERR_INVALID_ARG;
+    ctx->device = device;
+    ctx->in_type = in_type;
+    ctx->out_type = out_type;
+    int rc = build_registry(ctx);
+    if (rc != WT_OK) { delete ctx; return rc; }
+    if (device >= 0) {
+        hipError_t e = hipSetDevice(device);
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        if (e == hipSuccess) e = hipEventCreate(&e0);
+        if (e == hipSuccess) e = hipEventCreate(&e1);
+        if (e != hipSuccess) { delete ctx; return WT_ERR_HIP; }
+        ctx->ev_start = e0; ctx->ev_stop = e1;
+        // per-key resources from the runtime: LDS opt-in, register count, resident blocks per CU
+        for (size_t k = 0; k < ctx->keys.size(); ++k) {
+            Key& key = ctx->keys[k];
+            const Config& c0 = ctx->cfgs[key.first_cfg];
+            int occ = 0;
+            hipFuncAttributes fa;
+            memset(&fa, 0, sizeof(fa));
+            e = hipFuncSetAttribute(c0.fn, hipFuncAttributeMaxDynamicSharedMemorySize, key.lds_bytes);
+            if (e == hipSuccess) e = hipFuncGetAttributes(&fa, c0.fn);
+            if (e == hipSuccess)
+                e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, c0.fn, key.nwave * 64, (size_t)key.lds_bytes);
+            if (e != hipSuccess) { (void)hipGetLastError(); occ = 0; }
+            key.vgprs = fa.numRegs;
+            key.occ = occ;
+            key.cap = (int64_t)kNumCU * std::max(occ, 1);
+            for (int m = 0; m < key.n_micro; ++m) {
+                ctx->cfgs[key.first_cfg + m].res.occ = occ;
+                ctx->cfgs[key.first_cfg + m].res.vgprs = fa.numRegs;
+            }
+        }
+    }
+    *out = ctx;
+    return WT_OK;
+}
+
+int wt_destroy(wt_ctx* ctx) {
+    if (!ctx) return WT_ERR_INVALID_ARG;
+    if (ctx->ev_start) (void)hipEventDestroy((hipEvent_t)ctx->ev_start);
+    if (ctx->ev_stop) (void)hipEventDestroy((hipEvent_t)ctx->ev_stop);
+    delete ctx;
+    return WT_OK;
+}
+
+int wt_gemm(wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C, const float* scaleA,
+            const float* scaleB, wt_cfg cfg, void* hip_stream) {
+    int id = -1;
+    const int rc = check_gemm_args(ctx, M, N, K, A, B, C, scaleA, scaleB, cfg, &id);
+    if (rc != WT_OK) return rc;
+    return launch(ctx, ctx->cfgs[id], M, N, K, A, B, C, scaleA, scaleB, (hipStream_t)hip_stream);
+}
+
+int wt_time_gemm(wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
+                 const float* scaleA, const float* scaleB, wt_cfg cfg, int warmup, int iters, void* hip_stream,
+                 double* mean_us) {
+    int id = -1;
+    if (!mean_us || warmup < 0 || iters < 1) return WT_ERR_INVALID_ARG;
+    const int rc = check_gemm_args(ctx, M, N, K, A, B, C, scaleA, scaleB, cfg, &id);
+    if (rc != WT_OK) return rc;
+    return time_config(ctx, ctx->cfgs[id], M, N, K, A, B, C, scaleA, scaleB, warmup, iters, (hipStream_t)hip_stream,
+                       mean_us);
+}
+
+int wt_sample_plan(const wt_ctx* ctx, const wt_grid* grid, size_t* n_samples, size_t* bytesA, size_t* bytesB,
+                   size_t* bytesC) {
+    if (!ctx) return WT_ERR_INVALID_ARG;
+    int rc = check_grid(grid);
+    if (rc != WT_OK) return rc;
+    Plan p;
+    const size_t esz = ctx->in_type == WT_BF16 ? 2 : 1, osz = ctx->out_type == WT_OUT_F32 ? 4 : 2;
+    rc = walk_plan(ctx, grid, [&](int k, const GridPoint&, int, int64_t, int64_t M, int64_t N, int64_t K) {
+        p.n_samples += (size_t)ctx->keys[k].n_micro;
+        p.bytesA = std::max(p.bytesA, (size_t)(M * K) * esz);
+        p.bytesB = std::max(p.bytesB, (size_t)(N * K) * esz);
+        p.bytesC = std::max(p.bytesC, (size_t)(M * N) * osz);
+        return (int)WT_OK;
+    });
+    if (rc != WT_OK) return rc;
+    if (n_samples) *n_samples = p.n_samples;
+    if (bytesA) *bytesA = p.bytesA;
+    if (bytesB) *bytesB = p.bytesB;
+    if (bytesC) *bytesC = p.bytesC;
+    return WT_OK;
+}
+
+int wt_profile_sparse(wt_ctx* ctx, const wt_grid* grid, void* scrA, void* scrB, void* scrC, size_t bytesA,
+                      size_t bytesB, size_t bytesC, void* hip_stream, wt_sample* out, size_t cap, size_t* n_out) {
+    if (!ctx || !out || !n_out || !scrA || !scrB || !scrC) return WT_ERR_INVALID_ARG;
+    if (ctx->device < 0) return WT_ERR_NO_DEVICE;
+    size_t need = 0, nA = 0, nB = 0, nC = 0;
+    int rc = wt_sample_plan(ctx, grid, &need, &nA, &nB, &nC);
+    if (rc != WT_OK) return rc;
+    if (need > cap || nA > bytesA || nB > bytesB || nC > bytesC) return WT_ERR_BUFFER_TOO_SMALL;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    // fp8 kernels read two fp32 scales; their values do not affect timing, so the head of scrB
+    // (any bit pattern) stands in for both.
+    const float* sA = (const float*)scrB;
+    const float* sB = (const float*)scrB;
+    size_t n = 0;
+    rc = walk_plan(ctx, grid, [&](int k, const GridPoint& pt, int w, int64_t L, int64_t M, int64_t N, int64_t K) {
+        const Key& key = ctx->keys[k];
+        for (int m = 0; m < key.n_micro; ++m) {
+            const Config& c = ctx->cfgs[key.first_cfg + m];
+            double us = 0;
+            if (c.res.occ < 1) return (int)WT_ERR_INFEASIBLE;
+            const int r = time_config(ctx, c, M, N, K, scrA, scrB, scrC, sA, sB, grid->warmup, grid->iters, stream, &us);
+            if (r != WT_OK) return r;
+            wt_sample s;
+            memset(&s, 0, sizeof(s));
+            s.key_id = k; s.micro_id = m; s.G = pt.g; s.L = L; s.w = w; s.mean_us = us;
+            out[n++] = s;
+        }
+        return (int)WT_OK;
+    });
+    *n_out = n;
+    return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,627 @@
+// Host half of libwt: config registry, Phi / wave geometry, sparse sampler, bilinear fitter,
+// dual table, two-stage selection, table file.  No GPU calls in this file.
+//
+// Paper sections: Sec. 4.1 (Phi, macro/micro split), Sec. 4.2 (sampling), Sec. 4.3 (bucketed
+// bilinear model, dual table), Sec. 4.4 (two-stage selection), Sec. 4.5 (extrapolation).
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <chrono>
+#include <new>
+#include <vector>
+
+#include "wt_internal.hpp"
+
+namespace wt {
+
+// ---- compiled kernel lists (one function per instantiation unit) -----------------------------
+#define WT_DECL(in, out, list) const KernelEntry* wt_kernels_in##in##_out##out##_list##list(int* n);
+WT_DECL(0, 0, 0) WT_DECL(0, 0, 1) WT_DECL(0, 0, 2)
+WT_DECL(0, 1, 0) WT_DECL(0, 1, 1) WT_DECL(0, 1, 2)
+WT_DECL(1, 0, 0) WT_DECL(1, 0, 1) WT_DECL(1, 0, 2)
+WT_DECL(1, 1, 0) WT_DECL(1, 1, 1) WT_DECL(1, 1, 2)
+#undef WT_DECL
+
+const KernelEntry* kernel_list(int in, int out, int list, int* n) {
+#define WT_CASE(i, o, l) \
+    if (in == i && out == o && list == l) return wt_kernels_in##i##_out##o##_list##l(n);
+    WT_CASE(0, 0, 0) WT_CASE(0, 0, 1) WT_CASE(0, 0, 2)
+    WT_CASE(0, 1, 0) WT_CASE(0, 1, 1) WT_CASE(0, 1, 2)
+    WT_CASE(1, 0, 0) WT_CASE(1, 0, 1) WT_CASE(1, 0, 2)
+    WT_CASE(1, 1, 0) WT_CASE(1, 1, 1) WT_CASE(1, 1, 2)
+#undef WT_CASE
+    *n = 0;
+    return nullptr;
+}
+
+static int ilog2(int v) {
+    int s = 0;
+    while ((1 << s) < v) ++s;
+    return s;
+}
+
+// Resident blocks per compute unit from static resources: LDS bytes, wave slots (4 SIMDs x up to 8
+// waves, fewer when the per-lane register count exceeds 64), 32 blocks at most.  Used on host-only
+// contexts; a device context replaces it with the HIP runtime's answer.
+int static_occupancy(int lds_bytes, int nwave, int vgprs) {
+    const int regs = ((vgprs + 7) / 8) * 8;
+    int wps = 512 / (regs > 0 ? regs : 8);
+    if (wps > 8) wps = 8;
+    int occ = (4 * wps) / nwave;
+    if (lds_bytes > 0) occ = std::min(occ, kLdsPerCU / (((lds_bytes + 511) / 512) * 512));
+    return std::max(0, std::min(occ, 32));
+}
+
+int build_registry(wt_ctx* ctx) {
+    ctx->cfgs.clear();
+    ctx->keys.clear();
+    for (int list = 0; list < 3; ++list) {
+        int n = 0;
+        const KernelEntry* e = kernel_list(ctx->in_type, ctx->out_type, list, &n);
+        for (int i = 0; e && i < n; ++i) {
+            Key k{};
+            k.bm = e[i].bm; k.bn = e[i].bn; k.bk = e[i].bk;
+            k.nwave = e[i].wm * e[i].wn;
+            k.stages = e[i].st;
+            k.sh_m = ilog2(k.bm); k.sh_n = ilog2(k.bn); k.sh_k = ilog2(k.bk);
+            k.lds_bytes = e[i].lds_bytes;
+            k.vgprs = (k.bm * k.bn) / (k.nwave * 64) + 64;  // accumulators + working set (estimate)
+            k.occ = std::max(1, static_occupancy(k.lds_bytes, k.nwave, k.vgprs));
+            k.cap = static_cast<int64_t>(kNumCU) * k.occ;
+            k.n_micro = kNumSwizzle;
+            k.first_cfg = static_cast<int>(ctx->cfgs.size());
+            const int key_id = static_cast<int>(ctx->keys.size());
+            for (int sw = 0; sw < kNumSwizzle; ++sw) {
+                Config c{};
+                c.cfg = wt_cfg{k.bm, k.bn, k.bk, k.nwave, k.stages, sw, static_cast<int32_t>(ctx->cfgs.size())};
+                c.res = wt_cfg_res{k.lds_bytes, k.vgprs, k.nwave, k.occ, key_id, sw};
+                c.wm = e[i].wm; c.wn = e[i].wn;
+                c.fn = e[i].fn;
+                ctx->cfgs.push_back(c);
+            }
+            ctx->keys.push_back(k);
+        }
+    }
+    return ctx->cfgs.empty() ? WT_ERR_UNSUPPORTED_CFG : WT_OK;
+}
+
+int find_config(const wt_ctx* ctx, const wt_cfg& c) {
+    const int n = static_cast<int>(ctx->cfgs.size());
+    if (c.id >= 0 && c.id < n) {
+        const wt_cfg& r = ctx->cfgs[c.id].cfg;
+        if (r.bm == c.bm && r.bn == c.bn && r.bk == c.bk && r.nwave == c.nwave && r.stages == c.stages &&
+            r.swizzle == c.swizzle)
+            return c.id;
+    }
+    for (int i = 0; i < n; ++i) {
+        const wt_cfg& r = ctx->cfgs[i].cfg;
+        if (r.bm == c.bm && r.bn == c.bn && r.bk == c.bk && r.nwave == c.nwave && r.stages == c.stages &&
+            r.swizzle == c.swizzle)
+            return i;
+    }
+    return -1;
+}
+
+// ---- sparse sampler (Sec. 4.2) -------------------------------------------------------------------
+static int64_t isqrt64(int64_t v) {
+    int64_t r = static_cast<int64_t>(sqrt(static_cast<double>(v)));
+    while (r * r > v) --r;
+    while ((r + 1) * (r + 1) <= v) ++r;
+    return r;
+}
+
+// Largest g in [a,b] that is a product m*n with m <= n and n*tau_den <= m*tau_num.  Walks the
+// candidate row counts m and takes, for each, the widest admissible n that keeps m*n <= b.
+static int64_t best_grid_in(int64_t a, int64_t b, int tau_num, int tau_den) {
+    int64_t best = 0;
+    const int64_t m_hi = isqrt64(b);
+    for (int64_t m = m_hi; m >= 1; --m) {
+        const int64_t n_ratio = (m * tau_num) / tau_den;  // floor(tau * m)
+        const int64_t n = std::min(b / m, n_ratio);
+        if (n < m) continue;
+        const int64_t g = m * n;
+        if (g < a) {
+            // for smaller m the reachable product m*floor(tau*m) only shrinks
+            if (m * n_ratio < a) break;
+            continue;
+        }
+        if (g > best) best = g;
+    }
+    return best;
+}
+
+void sample_grid(int64_t cap, int W, int I, int tau_num, int tau_den, std::vector<GridPoint>& out) {
+    out.clear();
+    for (int w = 1; w <= W; ++w) {
+        const int64_t lo = static_cast<int64_t>(w - 1) * cap + 1;  // region R_w = [lo, w*cap]
+        for (int i = 1; i <= I; ++i) {
+            const int64_t a = lo + (static_cast<int64_t>(i - 1) * cap) / I;
+            const int64_t b = lo - 1 + (static_cast<int64_t>(i) * cap) / I;
+            GridPoint gp{0, 0, 0};
+            if (b >= a) {
+                const int64_t g = best_grid_in(a, b, tau_num, tau_den);
+                if (g > 0) {
+                    int64_t m = isqrt64(g);  // most-square factorisation of the chosen g
+                    while (g % m) --m;
+                    gp = GridPoint{g, m, g / m};
+                }
+            }
+            out.push_back(gp);
+        }
+    }
+}
+
+void loop_anchors(const wt_grid* grid, int bk, std::vector<int64_t>& out) {
+    out.clear();
+    for (int j = 0; j < grid->n_k_anchors; ++j) out.push_back(ceil_div64(grid->k_anchors[j], bk));
+    std::sort(out.begin(), out.end());
+    out.erase(std::unique(out.begin(), out.end()), out.end());
+}
+
+// ---- bilinear least squares (Sec. 4.3 bucket model) ---------------------------------------------
+struct Row {
+    double G, L, T;
+};
+
+// Solve the n x n system a*x = b by Gaussian elimination with partial pivoting.
+static bool solve_small(int n, double a[4][4], double b[4], double x[4]) {
+    int perm[4] = {0, 1, 2, 3};
+    (void)perm;
+    for (int c = 0; c < n; ++c) {
+        int piv = c;
+        for (int r = c + 1; r < n; ++r)
+            if (fabs(a[r][c]) > fabs(a[piv][c])) piv = r;
+        if (a[piv][c] == 0.0) return false;
+        if (piv != c) {
+            for (int k = 0; k < n; ++k) std::swap(a[c][k], a[piv][k]);
+            std::swap(b[c], b[piv]);
+        }
+        for (int r = c + 1; r < n; ++r) {
+            const double f = a[r][c] / a[c][c];
+            for (int k = c; k < n; ++k) a[r][k] -= f * a[c][k];
+            b[r] -= f * b[c];
+        }
+    }
+    for (int r = n - 1; r >= 0; --r) {
+        double s = b[r];
+        for (int k = r + 1; k < n; ++k) s -= a[r][k] * x[k];
+        x[r] = s / a[r][r];
+    }
+    return true;
+}
+
+// Least squares of T ~ alpha*G*L + beta*G + gamma*L + delta through the normal equations in
+// centred variables scaled to unit spread (on a product grid those columns are orthogonal, so the
+// system is nearly diagonal).  Terms that a single distinct G (or L) cannot identify are dropped.
+static int fit_rows(const std::vector<Row>& rows, double th[4]) {
+    th[0] = th[1] = th[2] = th[3] = 0.0;
+    const size_t n = rows.size();
+    if (n == 0) return 0;
+    double gm = 0, lm = 0;
+    for (const Row& r : rows) { gm += r.G; lm += r.L; }
+    gm /= static_cast<double>(n);
+    lm /= static_cast<double>(n);
+    double gs = 0, ls = 0;
+    bool many_g = false, many_l = false;
+    for (const Row& r : rows) {
+        gs += (r.G - gm) * (r.G - gm);
+        ls += (r.L - lm) * (r.L - lm);
+        many_g |= (r.G != rows[0].G);
+        many_l |= (r.L != rows[0].L);
+    }
+    gs = many_g ? sqrt(gs / static_cast<double>(n)) : 1.0;
+    ls = many_l ? sqrt(ls / static_cast<double>(n)) : 1.0;
+    // active columns in the order uv, u, v, 1
+    int cols[4], nc = 0, status = 0;
+    if (many_g && many_l) { cols[nc++] = 0; status |= 1; }
+    if (many_g) { cols[nc++] = 1; status |= 2; }
+    if (many_l) { cols[nc++] = 2; status |= 4; }
+    cols[nc++] = 3; status |= 8;
+    double ata[4][4] = {{0}}, atb[4] = {0}, x[4] = {0};
+    for (const Row& r : rows) {
+        const double u = (r.G - gm) / gs, v = (r.L - lm) / ls;
+        const double f[4] = {u * v, u, v, 1.0};
+        for (int i = 0; i < nc; ++i) {
+            for (int j = 0; j < nc; ++j) ata[i][j] += f[cols[i]] * f[cols[j]];
+            atb[i] += f[cols[i]] * r.T;
+        }
+    }
+    if (!solve_small(nc, ata, atb, x)) return 0;
+    double c[4] = {0, 0, 0, 0};  // coefficients of uv, u, v, 1
+    for (int i = 0; i < nc; ++i) c[cols[i]] = x[i];
+    const double a = c[0] / (gs * ls);
+    th[0] = a;
+    th[1] = c[1] / gs - a * lm;
+    th[2] = c[2] / ls - a * gm;
+    th[3] = c[3] - c[1] * gm / gs - c[2] * lm / ls + a * gm * lm;
+    return status;
+}
+
+// One bucket: records of a single <key, wave set>.  For every loop count pick the micro whose mean
+// latency over the bucket's grid sizes is smallest (it must have a record at each of them; ties go
+// to the lower id), keep it as the anchor for that loop count, and fit on those records only.
+static void fit_bucket(std::vector<const wt_sample*>& recs, Bucket& out) {
+    memset(&out, 0, sizeof(out));
+    std::sort(recs.begin(), recs.end(), [](const wt_sample* x, const wt_sample* y) {
+        if (x->L != y->L) return x->L < y->L;
+        if (x->micro_id != y->micro_id) return x->micro_id < y->micro_id;
+        return x->G < y->G;
+    });
+    std::vector<Row> rows;
+    size_t i = 0;
+    while (i < recs.size()) {
+        size_t j = i;
+        while (j < recs.size() && recs[j]->L == recs[i]->L) ++j;
+        // distinct grid sizes of this loop count
+        std::vector<int64_t> grid;
+        for (size_t t = i; t < j; ++t) grid.push_back(recs[t]->G);
+        std::sort(grid.begin(), grid.end());
+        grid.erase(std::unique(grid.begin(), grid.end()), grid.end());
+        double best_mean = 0;
+        size_t best_lo = 0, best_hi = 0;
+        bool have = false;
+        size_t t = i;
+        while (t < j) {
+            size_t u = t;
+            double sum = 0;
+            std::vector<int64_t> seen;
+            while (u < j && recs[u]->micro_id == recs[t]->micro_id) {
+                sum += recs[u]->mean_us;
+                if (seen.empty() || seen.back() != recs[u]->G) seen.push_back(recs[u]->G);
+                ++u;
+            }
+            if (seen == grid) {
+                const double mean = sum / static_cast<double>(u - t);
+                if (!have || mean < best_mean) { have = true; best_mean = mean; best_lo = t; best_hi = u; }
+            }
+            t = u;
+        }
+        if (have) {
+            if (out.n_anchor < kMaxAnchors) {
+                out.anchor_L[out.n_anchor] = static_cast<int32_t>(recs[best_lo]->L);
+                out.anchor_micro[out.n_anchor] = recs[best_lo]->micro_id;
+                ++out.n_anchor;
+            }
+            for (size_t r = best_lo; r < best_hi; ++r)
+                rows.push_back(Row{static_cast<double>(recs[r]->G), static_cast<double>(recs[r]->L), recs[r]->mean_us});
+        }
+        i = j;
+    }
+    out.status = fit_rows(rows, out.th);
+}
+
+static int fit_table(wt_ctx* ctx, const wt_grid* grid, const wt_sample* s, size_t n) {
+    const int W = grid->W, nk = static_cast<int>(ctx->keys.size());
+    if (W < 1 || grid->p < 1) return WT_ERR_INVALID_ARG;
+    Table t;
+    t.W = W; t.I = grid->I; t.p = grid->p; t.tau_num = grid->tau_num; t.tau_den = grid->tau_den;
+    t.buckets.assign(static_cast<size_t>(nk) * (W + 1), Bucket{});
+    std::vector<std::vector<const wt_sample*>> by(static_cast<size_t>(nk) * W);
+    for (size_t i = 0; i < n; ++i) {
+        if (s[i].key_id < 0 || s[i].key_id >= nk) return WT_ERR_INVALID_ARG;
+        if (s[i].w < 1 || s[i].w > W) continue;
+        by[static_cast<size_t>(s[i].key_id) * W + (s[i].w - 1)].push_back(&s[i]);
+    }
+    const int first_ext = std::max(1, W - grid->p + 1);
+    for (int k = 0; k < nk; ++k) {
+        std::vector<const wt_sample*> merged;
+        for (int w = 1; w <= W; ++w) {
+            std::vector<const wt_sample*>& recs = by[static_cast<size_t>(k) * W + (w - 1)];
+            if (w >= first_ext) merged.insert(merged.end(), recs.begin(), recs.end());
+            fit_bucket(recs, t.buckets[static_cast<size_t>(k) * (W + 1) + (w - 1)]);
+        }
+        fit_bucket(merged, t.buckets[static_cast<size_t>(k) * (W + 1) + W]);
+    }
+    t.fitted = true;
+    ctx->table = std::move(t);
+    return WT_OK;
+}
+
+// ---- two-stage selection (Sec. 4.4, 4.5) -------------------------------------------------------
+static inline const Bucket* pick_bucket(const Table& t, int key, int64_t w) {
+    const Bucket* base = &t.buckets[static_cast<size_t>(key) * (t.W + 1)];
+    if (w >= 1 && w <= t.W && base[w - 1].status) return &base[w - 1];
+    return base[t.W].status ? &base[t.W] : nullptr;
+}
+
+// ((alpha*(G*L) + beta*G) + gamma*L) + delta, each operation rounded once (this file is compiled
+// with -ffp-contract=off so no multiply-add is fused).
+static inline double predict(const double th[4], int64_t G, int64_t L) {
+    const double gl = static_cast<double>(G * L);
+    const double g = static_cast<double>(G), l = static_cast<double>(L);
+    double t = th[0] * gl;
+    t = t + th[1] * g;
+    t = t + th[2] * l;
+    t = t + th[3];
+    return t;
+}
+
+static int select_impl(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, int* key_out, int* micro_out,
+                       double* t_out) {
+    const Table& t = ctx->table;
+    const int nk = static_cast<int>(ctx->keys.size());
+    const Bucket* best_b = nullptr;
+    double best_t = 0;
+    int best_k = -1;
+    int64_t best_L = 0;
+    for (int k = 0; k < nk; ++k) {
+        const Key& key = ctx->keys[k];
+        const int64_t gm = (M + key.bm - 1) >> key.sh_m;
+        const int64_t gn = (N + key.bn - 1) >> key.sh_n;
+        const int64_t G = gm * gn;
+        const int64_t L = (K + key.bk - 1) >> key.sh_k;
+        const int64_t w = (G + key.cap - 1) / key.cap;
+        const Bucket* b = pick_bucket(t, k, w);
+        if (!b) continue;
+        const double th = predict(b->th, G, L);
+        if (th != th) continue;
+        if (best_k < 0 || th < best_t) { best_k = k; best_t = th; best_b = b; best_L = L; }
+    }
+    if (best_k < 0) return WT_ERR_NOT_FITTED;
+    int micro = 0;
+    if (best_b->n_anchor > 0) {
+        // anchors ascend in L: binary search for the first anchor >= L*, then compare with its
+        // left neighbour; equal distances keep the smaller anchor
+        int lo = 0, hi = best_b->n_anchor;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (best_b->anchor_L[mid] < best_L) lo = mid + 1; else hi = mid;
+        }
+        int pick = lo;
+        if (lo == best_b->n_anchor) pick = lo - 1;
+        else if (lo > 0 && (best_L - best_b->anchor_L[lo - 1]) <= (best_b->anchor_L[lo] - best_L)) pick = lo - 1;
+        micro = best_b->anchor_micro[pick];
+    }
+    *key_out = best_k;
+    *micro_out = micro;
+    if (t_out) *t_out = best_t;
+    return WT_OK;
+}
+
+// ---- table file ------------------------------------------------------------------------------------
+// Little-endian.  Header: 16 uint32 = 'WTDT', version 1, n_keys, W, I, p, tau_num, tau_den, n_cu,
+// anchor slots A, in_type, out_type, key_mode (0), 3 reserved.  Per key: 8 int32 (bm, bn, bk, nwave,
+// stages, occ, n_micro, 0), int64 cap, (W+1)*4 float64 theta (w = 1..W then ext), (W+1) int32
+// status, (W+1) int32 n_anchor, (W+1)*A int32 anchor L, (W+1)*A int32 anchor micro.
+static const uint32_t kMagic = 0x54445457u;  // "WTDT"
+
+static int save_table(const wt_ctx* ctx, const char* path) {
+    const Table& t = ctx->table;
+    if (!t.fitted) return WT_ERR_NOT_FITTED;
+    FILE* f = fopen(path, "wb");
+    if (!f) return WT_ERR_IO;
+    const uint32_t nk = static_cast<uint32_t>(ctx->keys.size());
+    const uint32_t hdr[16] = {kMagic, 1u, nk, static_cast<uint32_t>(t.W), static_cast<uint32_t>(t.I),
+                              static_cast<uint32_t>(t.p), static_cast<uint32_t>(t.tau_num),
+                              static_cast<uint32_t>(t.tau_den), static_cast<uint32_t>(kNumCU),
+                              static_cast<uint32_t>(kMaxAnchors), static_cast<uint32_t>(ctx->in_type),
+                              static_cast<uint32_t>(ctx->out_type), 0u, 0u, 0u, 0u};
+    bool ok = fwrite(hdr, sizeof(hdr), 1, f) == 1;
+    const int R = t.W + 1;
+    for (uint32_t k = 0; ok && k < nk; ++k) {
+        const Key& key = ctx->keys[k];
+        const int32_t kd[8] = {key.bm, key.bn, key.bk, key.nwave, key.stages, key.occ, key.n_micro, 0};
+        ok = ok && fwrite(kd, sizeof(kd), 1, f) == 1;
+        ok = ok && fwrite(&key.cap, sizeof(int64_t), 1, f) == 1;
+        const Bucket* b = &t.buckets[static_cast<size_t>(k) * R];
+        for (int r = 0; ok && r < R; ++r) ok = fwrite(b[r].th, sizeof(double), 4, f) == 4;
+        for (int r = 0; ok && r < R; ++r) ok = fwrite(&b[r].status, sizeof(int32_t), 1, f) == 1;
+        for (int r = 0; ok && r < R; ++r) ok = fwrite(&b[r].n_anchor, sizeof(int32_t), 1, f) == 1;
+        for (int r = 0; ok && r < R; ++r) ok = fwrite(b[r].anchor_L, sizeof(int32_t), kMaxAnchors, f) == kMaxAnchors;
+        for (int r = 0; ok && r < R; ++r) ok = fwrite(b[r].anchor_micro, sizeof(int32_t), kMaxAnchors, f) == kMaxAnchors;
+    }
+    ok = (fclose(f) == 0) && ok;
+    return ok ? WT_OK : WT_ERR_IO;
+}
+
+static int load_table(wt_ctx* ctx, const char* path) {
+    FILE* f = fopen(path, "rb");
+    if (!f) return WT_ERR_IO;
+    uint32_t hdr[16];
+    int rc = WT_OK;
+    Table t;
+    std::vector<int> occs;
+    if (fread(hdr, sizeof(hdr), 1, f) != 1 || hdr[0] != kMagic || hdr[1] != 1u) rc = WT_ERR_IO;
+    if (rc == WT_OK && (hdr[2] != ctx->keys.size() || hdr[9] != static_cast<uint32_t>(kMaxAnchors) ||
+                        hdr[10] != static_cast<uint32_t>(ctx->in_type) || hdr[3] < 1 || hdr[3] > 4096))
+        rc = WT_ERR_INVALID_ARG;  // table was built for another registry
+    if (rc == WT_OK) {
+        t.W = static_cast<int>(hdr[3]); t.I = static_cast<int>(hdr[4]); t.p = static_cast<int>(hdr[5]);
+        t.tau_num = static_cast<int>(hdr[6]); t.tau_den = static_cast<int>(hdr[7]);
+        const int R = t.W + 1;
+        t.buckets.assign(ctx->keys.size() * R, Bucket{});
+        for (size_t k = 0; rc == WT_OK && k < ctx->keys.size(); ++k) {
+            int32_t kd[8];
+            int64_t cap;
+            if (fread(kd, sizeof(kd), 1, f) != 1 || fread(&cap, sizeof(cap), 1, f) != 1) { rc = WT_ERR_IO; break; }
+            const Key& key = ctx->keys[k];
+            if (kd[0] != key.bm || kd[1] != key.bn || kd[2] != key.bk || kd[3] != key.nwave || kd[4] != key.stages ||
+                kd[5] < 1 || cap != static_cast<int64_t>(kNumCU) * kd[5]) { rc = WT_ERR_INVALID_ARG; break; }
+            occs.push_back(kd[5]);
+            Bucket* b = &t.buckets[k * R];
+            bool ok = true;
+            for (int r = 0; ok && r < R; ++r) ok = fread(b[r].th, sizeof(double), 4, f) == 4;
+            for (int r = 0; ok && r < R; ++r) ok = fread(&b[r].status, sizeof(int32_t), 1, f) == 1;
+            for (int r = 0; ok && r < R; ++r) ok = fread(&b[r].n_anchor, sizeof(int32_t), 1, f) == 1;
+            for (int r = 0; ok && r < R; ++r) ok = fread(b[r].anchor_L, sizeof(int32_t), kMaxAnchors, f) == kMaxAnchors;
+            for (int r = 0; ok && r < R; ++r) ok = fread(b[r].anchor_micro, sizeof(int32_t), kMaxAnchors, f) == kMaxAnchors;
+            for (int r = 0; ok && r < R; ++r) ok = b[r].n_anchor >= 0 && b[r].n_anchor <= kMaxAnchors;
+            if (!ok) rc = WT_ERR_IO;
+        }
+    }
+    fclose(f);
+    if (rc != WT_OK) return rc;
+    // the table's wave boundaries are those of the occupancy it was profiled with
+    for (size_t k = 0; k < ctx->keys.size(); ++k) {
+        ctx->keys[k].occ = occs[k];
+        ctx->keys[k].cap = static_cast<int64_t>(kNumCU) * occs[k];
+        for (int m = 0; m < ctx->keys[k].n_micro; ++m) ctx->cfgs[ctx->keys[k].first_cfg + m].res.occ = occs[k];
+    }
+    t.fitted = true;
+    ctx->table = std::move(t);
+    return WT_OK;
+}
+
+}  // namespace wt
+
+// ===== C ABI (host-only entry points) ==================================================================
+using namespace wt;
+
+extern "C" {
+
+const char* wt_status_string(int s) {
+    switch (s) {
+        case WT_OK: return "ok";
+        case WT_ERR_INVALID_ARG: return "invalid argument";
+        case WT_ERR_UNSUPPORTED_CFG: return "configuration not in the registry";
+        case WT_ERR_INFEASIBLE: return "configuration does not fit the device";
+        case WT_ERR_NOT_FITTED: return "no dual table (call wt_fit or wt_load)";
+        case WT_ERR_HIP: return "HIP call failed";
+        case WT_ERR_BUFFER_TOO_SMALL: return "buffer too small";
+        case WT_ERR_IO: return "file error";
+        case WT_ERR_NO_DEVICE: return "host-only context";
+        default: return "unknown status";
+    }
+}
+
+int wt_last_hip_error(const wt_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
+
+int wt_config_count(const wt_ctx* ctx, int* n) {
+    if (!ctx || !n) return WT_ERR_INVALID_ARG;
+    *n = static_cast<int>(ctx->cfgs.size());
+    return WT_OK;
+}
+
+int wt_key_count(const wt_ctx* ctx, int* n) {
+    if (!ctx || !n) return WT_ERR_INVALID_ARG;
+    *n = static_cast<int>(ctx->keys.size());
+    return WT_OK;
+}
+
+int wt_config_get(const wt_ctx* ctx, int i, wt_cfg* cfg, wt_cfg_res* res) {
+    if (!ctx || i < 0 || i >= static_cast<int>(ctx->cfgs.size())) return WT_ERR_INVALID_ARG;
+    if (cfg) *cfg = ctx->cfgs[i].cfg;
+    if (res) *res = ctx->cfgs[i].res;
+    return WT_OK;
+}
+
+int wt_config_find(const wt_ctx* ctx, const wt_cfg* fields, int* id) {
+    if (!ctx || !fields || !id) return WT_ERR_INVALID_ARG;
+    wt_cfg c = *fields;
+    c.id = -1;
+    const int i = find_config(ctx, c);
+    if (i < 0) return WT_ERR_UNSUPPORTED_CFG;
+    *id = i;
+    return WT_OK;
+}
+
+int wt_key_set_occ(wt_ctx* ctx, int key_id, int occ) {
+    if (!ctx || key_id < 0 || key_id >= static_cast<int>(ctx->keys.size()) || occ < 1) return WT_ERR_INVALID_ARG;
+    Key& k = ctx->keys[key_id];
+    k.occ = occ;
+    k.cap = static_cast<int64_t>(kNumCU) * occ;
+    for (int m = 0; m < k.n_micro; ++m) ctx->cfgs[k.first_cfg + m].res.occ = occ;
+    return WT_OK;
+}
+
+int wt_wave_count(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, wt_cfg cfg, int64_t* G, int64_t* L,
+                  int32_t* w) {
+    if (!ctx || M < 0 || N < 0 || K < 0) return WT_ERR_INVALID_ARG;
+    const int id = find_config(ctx, cfg);
+    if (id < 0) return WT_ERR_UNSUPPORTED_CFG;
+    const Key& k = ctx->keys[ctx->cfgs[id].res.key_id];
+    const int64_t g = ceil_div64(M, k.bm) * ceil_div64(N, k.bn);
+    if (G) *G = g;
+    if (L) *L = ceil_div64(K, k.bk);
+    if (w) *w = static_cast<int32_t>(ceil_div64(g, k.cap));
+    return WT_OK;
+}
+
+int wt_sample_grid(int64_t capacity, int32_t W, int32_t I, int32_t tau_num, int32_t tau_den, int64_t* g,
+                   int64_t* m, int64_t* n, size_t cap_out, size_t* n_out) {
+    if (capacity < 1 || W < 1 || I < 1 || tau_num < tau_den || tau_den < 1 || !n_out) return WT_ERR_INVALID_ARG;
+    std::vector<GridPoint> pts;
+    sample_grid(capacity, W, I, tau_num, tau_den, pts);
+    *n_out = pts.size();
+    if (pts.size() > cap_out) return WT_ERR_BUFFER_TOO_SMALL;
+    for (size_t i = 0; i < pts.size(); ++i) {
+        if (g) g[i] = pts[i].g;
+        if (m) m[i] = pts[i].m;
+        if (n) n[i] = pts[i].n;
+    }
+    return WT_OK;
+}
+
+int wt_fit(wt_ctx* ctx, const wt_grid* grid, const wt_sample* samples, size_t n) {
+    if (!ctx || !grid || (!samples && n)) return WT_ERR_INVALID_ARG;
+    return fit_table(ctx, grid, samples, n);
+}
+
+int wt_select(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, wt_cfg* out) {
+    if (!ctx || !out || M < 0 || N < 0 || K < 0) return WT_ERR_INVALID_ARG;
+    if (!ctx->table.fitted) return WT_ERR_NOT_FITTED;
+    int key, micro;
+    const int rc = select_impl(ctx, M, N, K, &key, &micro, nullptr);
+    if (rc != WT_OK) return rc;
+    const Key& k = ctx->keys[key];
+    if (micro < 0 || micro >= k.n_micro) micro = 0;
+    *out = ctx->cfgs[k.first_cfg + micro].cfg;
+    return WT_OK;
+}
+
+int wt_predict_us(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, wt_cfg cfg, double* us) {
+    if (!ctx || !us || M < 0 || N < 0 || K < 0) return WT_ERR_INVALID_ARG;
+    if (!ctx->table.fitted) return WT_ERR_NOT_FITTED;
+    const int id = find_config(ctx, cfg);
+    if (id < 0) return WT_ERR_UNSUPPORTED_CFG;
+    const int kid = ctx->cfgs[id].res.key_id;
+    const Key& k = ctx->keys[kid];
+    const int64_t G = ceil_div64(M, k.bm) * ceil_div64(N, k.bn), L = ceil_div64(K, k.bk);
+    const Bucket* b = pick_bucket(ctx->table, kid, ceil_div64(G, k.cap));
+    if (!b) return WT_ERR_NOT_FITTED;
+    *us = predict(b->th, G, L);
+    return WT_OK;
+}
+
+int wt_select_bench(const wt_ctx* ctx, const int64_t* shapes, size_t n, int repeats, double* mean_ns,
+                    double* p99_ns) {
+    if (!ctx || !shapes || n == 0 || repeats < 1) return WT_ERR_INVALID_ARG;
+    if (!ctx->table.fitted) return WT_ERR_NOT_FITTED;
+    std::vector<double> per(n, 0.0);
+    volatile int sink = 0;
+    double total = 0;
+    for (int r = 0; r < repeats; ++r) {
+        for (size_t i = 0; i < n; ++i) {
+            wt_cfg c;
+            const auto t0 = std::chrono::steady_clock::now();
+            const int rc = wt_select(ctx, shapes[3 * i], shapes[3 * i + 1], shapes[3 * i + 2], &c);
+            const auto t1 = std::chrono::steady_clock::now();
+            if (rc != WT_OK) return rc;
+            sink = sink + c.id;
+            const double ns = std::chrono::duration<double, std::nano>(t1 - t0).count();
+            per[i] = (r == 0) ? ns : std::min(per[i], ns);
+            total += ns;
+        }
+    }
+    // mean over every timed call; p99 over shapes of each shape's best repeat (removes scheduler noise)
+    if (mean_ns) *mean_ns = total / (static_cast<double>(n) * repeats);
+    if (p99_ns) {
+        std::sort(per.begin(), per.end());
+        *p99_ns = per[std::min(n - 1, static_cast<size_t>(0.99 * static_cast<double>(n)))];
+    }
+    return WT_OK;
+}
+
+int wt_save(const wt_ctx* ctx, const char* path) {
+    if (!ctx || !path) return WT_ERR_INVALID_ARG;
+    return save_table(ctx, path);
+}
+
+int wt_load(wt_ctx* ctx, const char* path) {
+    if (!ctx || !path) return WT_ERR_INVALID_ARG;
+    return load_table(ctx, path);
+}
+
+}  // extern "C"

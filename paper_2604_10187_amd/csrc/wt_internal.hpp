@@ -1,0 +1,78 @@
+// Internal data model of libwt (host side).  Not part of the ABI.
+#pragma once
+
+#include <stdint.h>
+
+#include <vector>
+
+#include "../../include/wt.h"
+#include "registry.hpp"
+
+namespace wt {
+
+constexpr int kNumCU = 256;            // compute units of one MI355X
+constexpr int kLdsPerCU = 160 * 1024;  // bytes
+constexpr int kNumSwizzle = 3;         // micro parameter values 0..2
+constexpr int kMaxAnchors = 8;         // loop anchors stored per bucket
+
+struct Config {
+    wt_cfg cfg;
+    wt_cfg_res res;
+    int wm, wn;
+    const void* fn;
+};
+
+struct Key {
+    int bm, bn, bk, nwave, stages;
+    int sh_m, sh_n, sh_k;  // log2 of the tile sides (all powers of two)
+    int occ;
+    int64_t cap;  // kNumCU * occ
+    int n_micro;
+    int first_cfg;
+    int lds_bytes;
+    int vgprs;
+};
+
+struct Bucket {
+    double th[4];  // alpha, beta, gamma, delta
+    int32_t status;  // 0 = no model; else bit0..3 = alpha..delta identified
+    int32_t n_anchor;
+    int32_t anchor_L[kMaxAnchors];
+    int32_t anchor_micro[kMaxAnchors];
+};
+
+struct Table {
+    bool fitted = false;
+    int W = 0, I = 0, p = 0, tau_num = 11, tau_den = 10;
+    // buckets[key * (W + 1) + (w - 1)] for w = 1..W; index W is the extrapolation entry
+    std::vector<Bucket> buckets;
+};
+
+}  // namespace wt
+
+struct wt_ctx {
+    int device = -1;
+    int in_type = 0, out_type = 0;
+    int last_hip = 0;
+    std::vector<wt::Config> cfgs;
+    std::vector<wt::Key> keys;
+    wt::Table table;
+    void* ev_start = nullptr;  // hipEvent_t pair used by the timing calls
+    void* ev_stop = nullptr;
+};
+
+namespace wt {
+
+// host-side pieces (wt_host.cpp)
+int build_registry(wt_ctx* ctx);  // fills cfgs/keys from the compiled kernel lists; static occupancy
+int static_occupancy(int lds_bytes, int nwave, int acc_vgprs);
+inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+int find_config(const wt_ctx* ctx, const wt_cfg& c);
+
+struct GridPoint {
+    int64_t g, m, n;
+};
+void sample_grid(int64_t cap, int W, int I, int tau_num, int tau_den, std::vector<GridPoint>& out);
+void loop_anchors(const wt_grid* grid, int bk, std::vector<int64_t>& out);
+
+}  // namespace wt
