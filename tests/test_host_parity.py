@@ -1,0 +1,188 @@
+"""CPU-side parity of libwt's host half against the oracle (no GPU): the library loads and
+exports every declared symbol; Phi / wave counts, the sampler and table lookups are bit-exact;
+fitted coefficients agree to 1e-9."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2604_10187_amd as wt
+import wt_synth
+from oracle import fit as ofit
+from oracle import geometry as geo
+from oracle import sampler as smp
+from oracle import select as osel
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+K_ANCHORS = (1024, 2048, 3072, 4096, 5120)
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = wt.wt_create(-1, wt.WT_BF16, wt.WT_OUT_F32)
+    yield c
+    wt.wt_destroy(c)
+
+
+def _keys(ctx):
+    out = []
+    for i in range(0, wt.wt_config_count(ctx), 3):
+        c, r = wt.wt_config_get(ctx, i)
+        out.append(ofit.KeyDesc(c.bm, c.bn, c.bk, c.nwave, c.stages, r.occ, geo.capacity(r.occ)))
+    return out
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "wt.h")).read()
+    declared = set(re.findall(r"\b(wt_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(wt.EXPORTS)
+    L = wt.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_registry_shape(ctx):
+    n = wt.wt_config_count(ctx)
+    assert n == 3 * wt.wt_key_count(ctx) and n >= 100
+    seen = set()
+    for i in range(n):
+        c, r = wt.wt_config_get(ctx, i)
+        assert c.id == i and r.key_id == i // 3 and r.micro_id == c.swizzle == i % 3
+        assert r.lds_bytes == (c.bm + c.bn) * c.bk * 2 * c.stages <= 160 * 1024
+        assert wt.wt_config_find(ctx, *c.astuple()) == i
+        seen.add(c.astuple())
+    assert len(seen) == n
+    with pytest.raises(wt.WtError):
+        wt.wt_config_find(ctx, 48, 48, 64, 4, 2, 0)
+
+
+def test_device_calls_refused_on_host_context(ctx):
+    c, _ = wt.wt_config_get(ctx, 0)
+    a = np.zeros(64, dtype=np.uint16)
+    with pytest.raises(wt.WtError) as e:
+        wt.wt_gemm(ctx, 1, 1, 8, a, a, a, c)
+    assert e.value.status == wt.WT_ERR_NO_DEVICE
+
+
+def test_wave_counts_bit_exact(ctx):
+    shapes = wt_synth.sweep_shapes() + wt_synth.wave_stress_shapes()[::7] + wt_synth.stream_shapes(200)
+    shapes += [(16384, 8192, 8192), (1, 1, 8), (0, 5, 8)]
+    for i in range(0, wt.wt_config_count(ctx), 3):
+        c, r = wt.wt_config_get(ctx, i)
+        cap = geo.capacity(r.occ)
+        for (M, N, K) in shapes:
+            G, L = geo.phi_gemm(M, N, K, c.bm, c.bn, c.bk)
+            assert wt.wt_wave_count(ctx, M, N, K, c) == (G, L, geo.wave_count(G, cap))
+    # occupancy override moves the wave boundaries
+    c, r = wt.wt_config_get(ctx, 0)
+    wt.wt_key_set_occ(ctx, 0, 3)
+    assert wt.wt_wave_count(ctx, 256 * 20, 256 * 40, 64, c)[2] == geo.wave_count(800, 768) == 2
+    wt.wt_key_set_occ(ctx, 0, r.occ)
+
+
+@pytest.mark.parametrize("cap", [4, 12, 132, 256, 512, 768, 1280, 2048, 250])
+@pytest.mark.parametrize("I", [1, 3, 4])
+def test_sampler_bit_exact(cap, I):
+    W = 40 if cap >= 132 else 9
+    g, m, n = wt.wt_sample_grid(cap, W, I)
+    want = smp.sample_set(cap, W, I)
+    assert len(g) == len(want) == W * I
+    assert [(int(a), int(b), int(c)) for a, b, c in zip(g, m, n)] == [(s.g, s.m, s.n) for s in want]
+
+
+def test_sampler_other_tau():
+    for tnum, tden in ((3, 2), (1, 1), (2, 1)):
+        g, m, n = wt.wt_sample_grid(132, 5, 4, tnum, tden)
+        want = smp.sample_set(132, 5, 4, tnum, tden)
+        assert [(int(a), int(b), int(c)) for a, b, c in zip(g, m, n)] == [(s.g, s.m, s.n) for s in want]
+
+
+# ---- fit + select on a synthetic latency surface --------------------------------------------------
+def _synthetic_samples(keys, W, I, noise_seed=None):
+    recs = []
+    for k, kd in enumerate(keys):
+        th = wt_synth.random_theta(300 + k, W)
+        scale = (kd.bm * kd.bn * kd.bk) / (128.0 * 128 * 64)      # bigger tiles cost more per (tile x loop)
+        for s in smp.sample_set(kd.cap, W, I):
+            if s.g == 0:
+                continue
+            for L in smp.loop_anchors(K_ANCHORS, kd.bk):
+                for micro in range(3):
+                    a, b, c, d = th[s.w - 1]
+                    t = scale * (a * s.g * L + b * s.g) + c * L + d
+                    t *= 1.0 + 0.03 * ((micro + L // 8 + k) % 3)     # micro preference varies with L
+                    recs.append((k, micro, s.g, L, s.w, 0, t))
+    arr = np.array(recs, dtype=wt.SAMPLE_DTYPE)
+    if noise_seed is not None:
+        arr["mean_us"] *= wt_synth.noise_factors(len(arr), noise_seed, 0.02)
+    return arr
+
+
+@pytest.mark.parametrize("noise_seed", [None, 5])
+def test_fit_and_select_parity(ctx, tmp_path, noise_seed):
+    W, I, p = 12, 4, 5
+    keys = _keys(ctx)
+    samples = _synthetic_samples(keys, W, I, noise_seed)
+    grid = wt.make_grid(W=W, I=I, p=p, k_anchors=K_ANCHORS)
+    wt.wt_fit(ctx, grid, samples)
+    path = str(tmp_path / "table.wt")
+    wt.wt_save(ctx, path)
+    table, meta = osel.read_table(path)
+    assert meta["I"] == I and meta["p"] == p and table.W == W and len(table.keys) == len(keys)
+    assert table.keys == keys
+    # (1) coefficients and anchors against the oracle's own fit of the same records
+    want = ofit.fit_tables([tuple(r)[:5] + (float(r["mean_us"]),) for r in samples], keys, W, p)
+    for k in range(len(keys)):
+        for got_b, want_b in list(zip(table.local[k], want.local[k])) + [(table.ext[k], want.ext[k])]:
+            assert got_b.status == want_b.status and got_b.anchors == want_b.anchors
+            scale = max(abs(x) for x in want_b.theta) or 1.0
+            # compare through predictions at the bucket's scale (coefficients cancel heavily)
+            assert np.allclose(got_b.theta, want_b.theta, rtol=1e-9, atol=1e-9 * scale) or \
+                _pred_close(got_b.theta, want_b.theta, keys[k])
+    # (2) lookups bit-exact: the oracle's selector on the very table the library wrote
+    shapes = wt_synth.sweep_shapes() + wt_synth.stream_shapes(3000) + wt_synth.wave_stress_shapes()[::5]
+    for (M, N, K) in shapes:
+        key, micro, t = osel.select(table, M, N, K)
+        c = wt.wt_select(ctx, M, N, K)
+        kd = keys[key]
+        assert (c.bm, c.bn, c.bk, c.nwave, c.stages, c.swizzle) == (kd.bm, kd.bn, kd.bk, kd.nwave, kd.stages, micro)
+        assert wt.wt_predict_us(ctx, M, N, K, c) == t        # same bits, not merely close
+    # (3) load round trip gives the same decisions
+    ctx2 = wt.wt_create(-1, wt.WT_BF16, wt.WT_OUT_F32)
+    try:
+        with pytest.raises(wt.WtError) as e:
+            wt.wt_select(ctx2, 64, 64, 64)
+        assert e.value.status == wt.WT_ERR_NOT_FITTED
+        wt.wt_load(ctx2, path)
+        for (M, N, K) in shapes[:300]:
+            assert wt.wt_select(ctx2, M, N, K).id == wt.wt_select(ctx, M, N, K).id
+    finally:
+        wt.wt_destroy(ctx2)
+
+
+def _pred_close(th_a, th_b, kd):
+    pts = [(g, L) for g in (kd.cap // 2 + 1, kd.cap) for L in (8, 80)]
+    for g, L in pts:
+        a, b = osel.predict(th_a, g, L), osel.predict(th_b, g, L)
+        if abs(a - b) > 1e-9 * max(abs(a), abs(b), 1.0):
+            return False
+    return True
+
+
+def test_select_is_fast_and_allocates_nothing_visible(ctx):
+    W, I = 8, 2
+    samples = _synthetic_samples(_keys(ctx), W, I)
+    wt.wt_fit(ctx, wt.make_grid(W=W, I=I, p=4, k_anchors=K_ANCHORS), samples)
+    mean_ns, p99_ns = wt.wt_select_bench(ctx, wt_synth.stream_shapes(2000), repeats=3)
+    assert mean_ns < 10_000        # target: <= 10 us per decision
+
+
+def test_bad_table_file(ctx, tmp_path):
+    p = tmp_path / "junk.wt"
+    p.write_bytes(b"not a table")
+    with pytest.raises(wt.WtError) as e:
+        wt.wt_load(ctx, str(p))
+    assert e.value.status == wt.WT_ERR_IO
+    with pytest.raises(wt.WtError):
+        wt.wt_load(ctx, str(tmp_path / "missing.wt"))
