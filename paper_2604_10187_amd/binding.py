@@ -67,6 +67,10 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2604_10187_amd.build` "
                                "(there is no fallback path)")
+        # PyTorch ships its own HIP runtime; load it first so that libwt binds to the same copy
+        # (two HIP runtimes in one process do not see each other's devices, streams or memory).
+        import torch  # noqa: F401
+
         L = C.CDLL(LIB_PATH)
         vp, i64, i32, sz = C.c_void_p, C.c_int64, C.c_int32, C.c_size_t
         sig = {

@@ -1,0 +1,100 @@
+"""Offline stage: wave-aware sparse profiling on the GPU, fit, and dual-table file (Sec. 4.2-4.5).
+
+    python -m paper_2604_10187_amd.tune --out gpurun_out/mi355x_bf16_bf16.wt [--W 40 --I 4 ...]
+        [--key-first a --key-count n --samples-out file.npy]      # profile a slice of keys only
+        [--fit-from a.npy b.npy ...]                              # fit saved records, no GPU
+
+Every step runs inside libwt (wt_profile_sparse, wt_fit, wt_save); this script only allocates the
+scratch buffers with torch and moves records between files.
+"""
+from __future__ import annotations
+
+import argparse
+import os
+import sys
+import time
+
+import numpy as np
+
+from . import binding as wt
+
+TABLE_DIR = os.path.join(os.path.dirname(os.path.abspath(__file__)), "tables")
+K_ANCHORS = (1024, 2048, 3072, 4096, 5120)      # five K anchors spanning [1024, 5120] (Sec. 5.1)
+
+
+def table_path(in_type: int, out_type: int) -> str:
+    return os.path.join(TABLE_DIR, f"mi355x_in{in_type}_out{out_type}.wt")
+
+
+def profile(ctx, grid, in_type, out_type, log=print, chunk_keys=4):
+    """Run wt_profile_sparse over the grid's key slice in chunks; returns the records."""
+    import torch
+
+    nkeys = wt.wt_key_count(ctx)
+    first = grid.key_first if grid.key_count > 0 else 0
+    count = grid.key_count if grid.key_count > 0 else nkeys
+    _, bA, bB, bC = wt.wt_sample_plan(ctx, grid)
+    esz = 2 if in_type == wt.WT_BF16 else 1
+    # finite, non-constant contents; values do not influence timing of dense MFMA work
+    scrA = (torch.randn(max(bA // esz, 16), device="cuda") * 0.5).to(torch.bfloat16 if esz == 2 else torch.float8_e4m3fn)
+    scrB = (torch.randn(max(bB // esz, 16), device="cuda") * 0.5).to(torch.bfloat16 if esz == 2 else torch.float8_e4m3fn)
+    scrC = torch.empty(max(bC, 16), dtype=torch.uint8, device="cuda")
+    out = []
+    t0 = time.time()
+    for k0 in range(first, first + count, chunk_keys):
+        kc = min(chunk_keys, first + count - k0)
+        g = wt.make_grid(W=grid.W, I=grid.I, tau=(grid.tau_num, grid.tau_den), p=grid.p,
+                         k_anchors=[grid.k_anchors[j] for j in range(grid.n_k_anchors)], warmup=grid.warmup,
+                         iters=grid.iters, key_first=k0, key_count=kc, max_out_elems=grid.max_out_elems)
+        recs = wt.wt_profile_sparse(ctx, g, scrA, scrB, scrC, stream=torch.cuda.current_stream())
+        out.append(recs)
+        log(f"[tune] keys {k0}..{k0 + kc - 1}: {len(recs)} records, {time.time() - t0:.0f}s elapsed")
+    return np.concatenate(out) if out else np.zeros(0, dtype=wt.SAMPLE_DTYPE)
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--in-type", type=int, default=wt.WT_BF16)
+    ap.add_argument("--out-type", type=int, default=wt.WT_OUT_BF16)
+    ap.add_argument("--W", type=int, default=40)
+    ap.add_argument("--I", type=int, default=4)
+    ap.add_argument("--p", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--iters", type=int, default=5)
+    ap.add_argument("--k-anchors", type=int, nargs="+", default=list(K_ANCHORS))
+    ap.add_argument("--key-first", type=int, default=0)
+    ap.add_argument("--key-count", type=int, default=0)
+    ap.add_argument("--max-out-elems", type=int, default=0)
+    ap.add_argument("--samples-out", default=None)
+    ap.add_argument("--fit-from", nargs="*", default=None)
+    ap.add_argument("--out", default=None)
+    a = ap.parse_args(argv)
+    grid = wt.make_grid(W=a.W, I=a.I, p=a.p, k_anchors=a.k_anchors, warmup=a.warmup, iters=a.iters,
+                        key_first=a.key_first, key_count=a.key_count, max_out_elems=a.max_out_elems)
+    if a.fit_from is not None:
+        recs = np.concatenate([np.load(f) for f in a.fit_from])
+        occ_files = [f.replace(".npy", ".occ.npy") for f in a.fit_from]
+        ctx = wt.wt_create(-1, a.in_type, a.out_type)
+        if all(os.path.exists(f) for f in occ_files):    # wave boundaries = those of the profiling run
+            occ = np.load(occ_files[0])
+            for k, o in enumerate(occ):
+                wt.wt_key_set_occ(ctx, k, int(o))
+    else:
+        ctx = wt.wt_create(0, a.in_type, a.out_type)
+        n, bA, bB, bC = wt.wt_sample_plan(ctx, grid)
+        print(f"[tune] plan: {n} records, scratch A {bA >> 20} MiB, B {bB >> 20} MiB, C {bC >> 20} MiB", flush=True)
+        recs = profile(ctx, grid, a.in_type, a.out_type, log=lambda s: print(s, flush=True))
+        if a.samples_out:
+            np.save(a.samples_out, recs)
+            occ = np.array([wt.wt_config_get(ctx, 3 * k)[1].occ for k in range(wt.wt_key_count(ctx))], dtype=np.int32)
+            np.save(a.samples_out.replace(".npy", ".occ.npy"), occ)
+    if a.out:
+        wt.wt_fit(ctx, grid, recs)
+        os.makedirs(os.path.dirname(os.path.abspath(a.out)), exist_ok=True)
+        wt.wt_save(ctx, a.out)
+        print(f"[tune] fitted {len(recs)} records -> {a.out} ({os.path.getsize(a.out)} bytes)")
+    wt.wt_destroy(ctx)
+
+
+if __name__ == "__main__":
+    main()
