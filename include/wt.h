@@ -132,6 +132,13 @@ int wt_time_gemm(wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, co
                  const float* scaleA, const float* scaleB, wt_cfg cfg, int warmup, int iters,
                  void* hip_stream, double* mean_us);
 
+/* Diagnostic: sustained MFMA-only throughput of the device (register operands of magnitude ~1,
+ * no memory traffic; 2 blocks of 4 wavefronts per compute unit, iters x 16 MFMAs each).  This is
+ * the power- and clock-limited ceiling of a dense contraction, reported beside the nominal peak.
+ * sink_dev: device pointer to one float (never written in practice).  Synchronises the stream. */
+int wt_mfma_ceiling(wt_ctx* ctx, int in_type, int iters, void* hip_stream, float* sink_dev,
+                    double* tflops);
+
 /* ---- modelling (Sec. 4.3, 4.5) ------------------------------------------------------------ */
 /* Build the dual table from records (from the GPU or from any synthetic source).  Host only. */
 int wt_fit(wt_ctx* ctx, const wt_grid* grid, const wt_sample* samples, size_t n);

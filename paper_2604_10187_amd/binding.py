@@ -88,6 +88,7 @@ def lib():
             "wt_sample_plan": [vp, C.POINTER(wt_grid), C.POINTER(sz), C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)],
             "wt_profile_sparse": [vp, C.POINTER(wt_grid), vp, vp, vp, sz, sz, sz, vp, vp, sz, C.POINTER(sz)],
             "wt_time_gemm": [vp, i64, i64, i64, vp, vp, vp, vp, vp, wt_cfg, C.c_int, C.c_int, vp, C.POINTER(C.c_double)],
+            "wt_mfma_ceiling": [vp, C.c_int, C.c_int, vp, vp, C.POINTER(C.c_double)],
             "wt_fit": [vp, C.POINTER(wt_grid), vp, sz],
             "wt_select": [vp, i64, i64, i64, C.POINTER(wt_cfg)],
             "wt_predict_us": [vp, i64, i64, i64, wt_cfg, C.POINTER(C.c_double)],
@@ -107,7 +108,7 @@ def lib():
 
 EXPORTS = ("wt_create", "wt_destroy", "wt_last_hip_error", "wt_status_string", "wt_config_count", "wt_config_get",
            "wt_config_find", "wt_key_count", "wt_key_set_occ", "wt_gemm", "wt_wave_count", "wt_sample_grid",
-           "wt_sample_plan", "wt_profile_sparse", "wt_time_gemm", "wt_fit", "wt_select", "wt_predict_us",
+           "wt_sample_plan", "wt_profile_sparse", "wt_time_gemm", "wt_mfma_ceiling", "wt_fit", "wt_select", "wt_predict_us",
            "wt_select_bench", "wt_save", "wt_load")
 
 
@@ -198,6 +199,15 @@ def wt_time_gemm(ctx, M, N, K, A, B, Cout, cfg, warmup=3, iters=5, scaleA=None, 
     _check(lib().wt_time_gemm(ctx, M, N, K, _ptr(A), _ptr(B), _ptr(Cout), _ptr(scaleA), _ptr(scaleB), cfg,
                               warmup, iters, _stream(stream), C.byref(us)), "wt_time_gemm")
     return us.value
+
+
+def wt_mfma_ceiling(ctx, in_type=WT_BF16, iters=20000, stream=None) -> float:
+    import torch
+
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    tf = C.c_double()
+    _check(lib().wt_mfma_ceiling(ctx, in_type, iters, _stream(stream), _ptr(sink), C.byref(tf)), "wt_mfma_ceiling")
+    return tf.value
 
 
 def wt_wave_count(ctx, M, N, K, cfg):

@@ -45,6 +45,9 @@ def build(jobs: int = 8, verbose: bool = False) -> str:
     obj = os.path.join(OUT, "wt_api.o")
     objs.append(obj)
     steps.append([hipcc, *HIP_FLAGS, "-c", os.path.join(CSRC, "wt_api.hip"), "-o", obj])
+    obj = os.path.join(OUT, "mfma_ceiling.o")
+    objs.append(obj)
+    steps.append([hipcc, *HIP_FLAGS, "-c", os.path.join(CSRC, "mfma_ceiling.hip"), "-o", obj])
     obj = os.path.join(OUT, "wt_host.o")
     objs.append(obj)
     steps.append(["g++", "-O2", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Wall", "-c",

@@ -27,6 +27,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace wt {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -84,15 +86,21 @@ __device__ __forceinline__ i32x4 make_rsrc(const void* base, uint32_t num_record
 }
 
 // 16 bytes per lane, global -> LDS.  lds_base is the wave-uniform LDS byte address of the
-// 1 KiB destination; lane l lands at lds_base + 16*l.
-__device__ __forceinline__ void load_lds_16B(i32x4 rsrc, uint32_t voffset, uint32_t lds_base) {
+// 1 KiB destination; lane l lands at lds_base + 16*l.  Source = rsrc base + voffset + soffset.
+__device__ __forceinline__ void load_lds_16B(i32x4 rsrc, uint32_t voffset, uint32_t soffset, uint32_t lds_base) {
     asm volatile(
         "s_mov_b32 m0, %0\n\t"
-        "buffer_load_dwordx4 %1, %2, 0 offen lds"
+        "s_nop 0\n\t"
+        "buffer_load_dwordx4 %1, %2, %3 offen lds"
         :
-        : "s"(lds_base), "v"(voffset), "s"(rsrc)
+        : "s"(lds_base), "v"(voffset), "s"(rsrc), "s"(soffset)
         : "memory");
 }
+
+__device__ __forceinline__ void wait_lgkmcnt0() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+// keep the instruction scheduler from moving anything across this point
+__device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0); }
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
@@ -127,9 +135,9 @@ struct GemmTraits {
     static constexpr int CPR = RB / 16;          // 16-byte chunks per row
     static constexpr int TM = BM / WM;           // wavefront sub-tile
     static constexpr int TN = BN / WN;
-    static constexpr int MI = (IN == 0 && TM % 32 == 0 && TN % 32 == 0) ? 32 : 16;
-    // k extent of one MFMA: bf16 32x32x16 / 16x16x32; fp8 16x16x128
-    static constexpr int KS = (IN == 0) ? (MI == 32 ? 16 : 32) : 128;
+    static constexpr int MI = (TM % 32 == 0 && TN % 32 == 0) ? 32 : 16;
+    // k extent of one MFMA: bf16 32x32x16 / 16x16x32; fp8 32x32x64 / 16x16x128
+    static constexpr int KS = (IN == 0) ? (MI == 32 ? 16 : 32) : (MI == 32 ? 64 : 128);
     static constexpr int CPK = KS * esize / 16;  // chunks one MFMA consumes along k per row
     static constexpr int CPL = CPK / (kWave / MI);  // chunks per lane per MFMA operand
     static constexpr int STAGE_BYTES = (BM + BN) * RB;
@@ -142,13 +150,31 @@ struct GemmTraits {
     static constexpr int SWZ_SH = (RB >= 256) ? 0 : (RB == 128 ? 1 : 2);
     static constexpr int FM = TM / MI, FN = TN / MI;
     static constexpr int ACC = MI * MI / kWave;  // accumulator floats per lane per MFMA tile
+    static constexpr int KSTEPS = BK / KS;
+    static constexpr int NMK = FM * FN;           // MFMAs per k-step per wavefront
+    // With three or more stages the refill of a freed stage is spread over a whole k-tile (the
+    // loads of k-tile t+ST-1 ride along the MFMAs of k-tile t); with two stages it has to follow the
+    // barrier inside the last k-step (k-tile t+ST then rides along the last MFMAs of k-tile t).
+    static constexpr bool SPREAD = ST >= 3;
     static_assert(BK % KS == 0, "BK must hold whole MFMA k-steps");
     static_assert((BM * CPR) % kWave == 0 && (BN * CPR) % kWave == 0, "whole 1 KiB loads");
     static_assert((A_INSTR + B_INSTR) % NW == 0, "equal loads per wavefront");
     static_assert(TM % MI == 0 && TN % MI == 0, "sub-tile is a whole number of MFMA tiles");
     static_assert(CPR >= 4 && (CPR & (CPR - 1)) == 0, "row of 64..512 bytes");
-    static_assert(LPW * (ST > 2 ? ST - 2 : 0) <= 63, "vmcnt range");
+    static_assert(LPW * (ST - 1) <= 63, "vmcnt range");
+    static_assert(ST == 1 || KSTEPS >= 1, "k-steps");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS per workgroup");
+};
+
+template <int IN>
+struct FragType;
+template <>
+struct FragType<0> {
+    using type = bf16x8;
+};
+template <>
+struct FragType<1> {
+    using type = i32x8;
 };
 
 template <int MI>
@@ -189,42 +215,56 @@ __global__ __launch_bounds__(WM* WN* kWave) void gemm_kernel(const GemmArgs args
                                   records(args.M - row0));
     const i32x4 rsrcB = make_rsrc(static_cast<const char*>(args.B) + static_cast<int64_t>(col0) * row_bytes,
                                   records(args.N - col0));
-    uint32_t ld_voff[T::LPW];  // byte offset of this lane's piece at k-tile 0 (relative to the tile's first row)
-    uint32_t ld_k[T::LPW];     // element offset of the piece inside a k-tile
+    // Load slot t of this wavefront fills the 1 KiB LDS piece j = wv + t*NW of a stage.  The lane's
+    // source offset at k-tile 0 stays in a register for the whole kernel; the k advance is a scalar.
+    // ld_tail[t] is the same offset for the one partial k-tile (K % BK != 0), already replaced by
+    // the out-of-range sentinel where the piece lies at or past K, so that it reads as zeros.
+    const int L = (K + BK - 1) / BK;
+    const int L_full = K / BK;
+    uint32_t ld_voff[T::LPW], ld_tail[T::LPW];
 #pragma unroll
     for (int t = 0; t < T::LPW; ++t) {
-        const int j = wv + t * T::NW;                 // 1 KiB slot index inside the stage
+        const int j = wv + t * T::NW;
         const int p = j * kWave + lane;               // 16-byte slot index inside the stage
         const int r = p / T::CPR;                     // staged row: [0,BM) = A, [BM,BM+BN) = B
         const int slot = p % T::CPR;
         const int chunk = slot ^ ((r >> T::SWZ_SH) & (T::CPR - 1));
         const int rl = (j < T::A_INSTR) ? r : r - BM; // row inside its own matrix tile
         ld_voff[t] = static_cast<uint32_t>(rl) * static_cast<uint32_t>(row_bytes) + chunk * 16;
-        ld_k[t] = chunk * T::epc;
+        ld_tail[t] = (L_full * BK + chunk * T::epc < K) ? ld_voff[t] : kOobOffset;
     }
-    auto issue_tile = [&](int kt, int stage) {
-        const int k0 = kt * BK;
-#pragma unroll
-        for (int t = 0; t < T::LPW; ++t) {
-            const int j = wv + t * T::NW;
-            const bool in_k = (k0 + static_cast<int>(ld_k[t])) < K;
-            const uint32_t off = in_k ? ld_voff[t] + static_cast<uint32_t>(k0) * T::esize : kOobOffset;
-            const uint32_t dst = lds0 + stage * T::STAGE_BYTES + j * 1024;
-            if constexpr (T::SPLIT) {
-                if (t < T::A_INSTR / T::NW)
-                    load_lds_16B(rsrcA, off, dst);
-                else
-                    load_lds_16B(rsrcB, off, dst);
-            } else {
-                const bool is_a = j < T::A_INSTR;  // wave-uniform
-                i32x4 rs;
-                rs.x = is_a ? rsrcA.x : rsrcB.x;
-                rs.y = is_a ? rsrcA.y : rsrcB.y;
-                rs.z = is_a ? rsrcA.z : rsrcB.z;
-                rs.w = rsrcA.w;
-                load_lds_16B(rs, off, dst);
-            }
+    // One load: slot t of k-tile kt into LDS stage `stage`.  TAIL = the k-tile may be the partial one
+    // or lie past the end (then every piece is out of range and zero-fills the stage), so every
+    // k-tile index issues the same number of loads and the vmcnt bookkeeping stays uniform.
+    auto issue_load = [&](int t, int kt, int stage, bool tail) {
+        const int j = wv + t * T::NW;
+        const uint32_t dst = lds0 + stage * T::STAGE_BYTES + j * 1024;
+        // The hardware range-checks the per-lane offset only (the scalar offset is added after the
+        // check), so anything that must read as zeros is expressed through voff.
+        uint32_t koff = static_cast<uint32_t>(kt) * (BK * T::esize);
+        uint32_t voff = ld_voff[t];
+        if (tail) {
+            if (kt >= L_full) voff = (kt < L) ? ld_tail[t] : kOobOffset;  // uniform conditions
+            if (kt >= L) koff = 0;
         }
+        if constexpr (T::SPLIT) {
+            if (t < T::A_INSTR / T::NW)
+                load_lds_16B(rsrcA, voff, koff, dst);
+            else
+                load_lds_16B(rsrcB, voff, koff, dst);
+        } else {
+            const bool is_a = j < T::A_INSTR;  // wave-uniform
+            i32x4 rs;
+            rs.x = is_a ? rsrcA.x : rsrcB.x;
+            rs.y = is_a ? rsrcA.y : rsrcB.y;
+            rs.z = is_a ? rsrcA.z : rsrcB.z;
+            rs.w = rsrcA.w;
+            load_lds_16B(rs, voff, koff, dst);
+        }
+    };
+    auto issue_tile = [&](int kt, int stage) {
+#pragma unroll
+        for (int t = 0; t < T::LPW; ++t) issue_load(t, kt, stage, true);
     };
 
     // ---- fragment read plan -------------------------------------------------------------------
@@ -239,84 +279,146 @@ __global__ __launch_bounds__(WM* WN* kWave) void gemm_kernel(const GemmArgs args
 #pragma unroll
             for (int e = 0; e < T::ACC; ++e) acc[i][j][e] = 0.0f;
 
-    auto frag_ptr = [&](int stage, int r, int chunk) -> const char* {
-        const int slot = chunk ^ ((r >> T::SWZ_SH) & (T::CPR - 1));
-        return smem + stage * T::STAGE_BYTES + r * T::RB + slot * 16;
-    };
-
-    auto compute_tile = [&](int stage) {
-#pragma unroll
-        for (int ks = 0; ks < BK / T::KS; ++ks) {
-            if constexpr (IN == 0) {
-                bf16x8 af[T::FM], bfr[T::FN];
-#pragma unroll
-                for (int i = 0; i < T::FM; ++i)
-                    af[i] = *reinterpret_cast<const bf16x8*>(
-                        frag_ptr(stage, wm * T::TM + i * T::MI + frow, ks * T::CPK + fchunk));
-#pragma unroll
-                for (int j = 0; j < T::FN; ++j)
-                    bfr[j] = *reinterpret_cast<const bf16x8*>(
-                        frag_ptr(stage, BM + wn * T::TN + j * T::MI + frow, ks * T::CPK + fchunk));
-#pragma unroll
-                for (int i = 0; i < T::FM; ++i)
-#pragma unroll
-                    for (int j = 0; j < T::FN; ++j) {
-                        if constexpr (T::MI == 32)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-                        else
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-                    }
-            } else {
-                // fp8: each lane feeds 32 consecutive k (two 16-byte chunks) of its row
-                i32x8 af[T::FM], bfr[T::FN];
-#pragma unroll
-                for (int i = 0; i < T::FM; ++i) {
-                    const int r = wm * T::TM + i * T::MI + frow;
-                    const i32x4 lo = *reinterpret_cast<const i32x4*>(frag_ptr(stage, r, ks * T::CPK + fchunk));
-                    const i32x4 hi = *reinterpret_cast<const i32x4*>(frag_ptr(stage, r, ks * T::CPK + fchunk + 1));
-                    af[i] = i32x8{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-                }
-#pragma unroll
-                for (int j = 0; j < T::FN; ++j) {
-                    const int r = BM + wn * T::TN + j * T::MI + frow;
-                    const i32x4 lo = *reinterpret_cast<const i32x4*>(frag_ptr(stage, r, ks * T::CPK + fchunk));
-                    const i32x4 hi = *reinterpret_cast<const i32x4*>(frag_ptr(stage, r, ks * T::CPK + fchunk + 1));
-                    bfr[j] = i32x8{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-                }
-#pragma unroll
-                for (int i = 0; i < T::FM; ++i)
-#pragma unroll
-                    for (int j = 0; j < T::FN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
-                            af[i], bfr[j], acc[i][j], 0 /*A: e4m3*/, 0 /*B: e4m3*/, 0, 0, 0, 0);
-            }
+    using frag_t = typename FragType<IN>::type;
+    auto read_frag = [&](int stage, int r, int ks) -> frag_t {
+        const int sw = (r >> T::SWZ_SH) & (T::CPR - 1);
+        const char* row = smem + stage * T::STAGE_BYTES + r * T::RB;
+        const int c0 = ks * T::CPK + fchunk;
+        if constexpr (IN == 0) {
+            return *reinterpret_cast<const bf16x8*>(row + ((c0 ^ sw) * 16));
+        } else {
+            // fp8: each lane feeds 32 consecutive k (two 16-byte chunks) of its row
+            const i32x4 lo = *reinterpret_cast<const i32x4*>(row + ((c0 ^ sw) * 16));
+            const i32x4 hi = *reinterpret_cast<const i32x4*>(row + (((c0 + 1) ^ sw) * 16));
+            return i32x8{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
         }
+    };
+    struct Frags {
+        frag_t a[T::FM];
+        frag_t b[T::FN];
+    };
+    auto load_frags = [&](Frags& f, int stage, int ks) {
+#pragma unroll
+        for (int i = 0; i < T::FM; ++i) f.a[i] = read_frag(stage, wm * T::TM + i * T::MI + frow, ks);
+#pragma unroll
+        for (int j = 0; j < T::FN; ++j) f.b[j] = read_frag(stage, BM + wn * T::TN + j * T::MI + frow, ks);
+    };
+    auto mfma = [&](const Frags& f, int i, int j) {
+        if constexpr (IN == 0) {
+            if constexpr (T::MI == 32)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+            else
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+        } else {
+            // cbsz = blgp = 0 select e4m3 for both operands; unit block scales
+            if constexpr (T::MI == 32)
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f.a[i], f.b[j], acc[i][j], 0, 0, 0, 0, 0, 0);
+            else
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(f.a[i], f.b[j], acc[i][j], 0, 0, 0, 0, 0, 0);
+        }
+    };
+    auto mma = [&](const Frags& f) {
+#pragma unroll
+        for (int i = 0; i < T::FM; ++i)
+#pragma unroll
+            for (int j = 0; j < T::FN; ++j) mfma(f, i, j);
     };
 
     // ---- main loop --------------------------------------------------------------------------------
-    const int L = (K + BK - 1) / BK;
+    constexpr int KSTEPS = T::KSTEPS;
+    constexpr int NMK = T::NMK;
+    constexpr int NFR = T::FM + T::FN;  // fragments read per k-step
     if constexpr (ST == 1) {
+        Frags f;
         for (int kt = 0; kt < L; ++kt) {
             issue_tile(kt, 0);
             wait_vmcnt<0>();
             block_barrier();
-            compute_tile(0);
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) {
+                load_frags(f, 0, ks);
+                mma(f);
+            }
             block_barrier();
         }
     } else {
-        // prologue: tiles 0..ST-2 (tiles past L are all out of range and load zeros)
+        // Software pipeline, one barrier per k-tile.  Every MFMA is followed by at most one fragment
+        // read and a share of the global->LDS loads, and the scheduler is fenced after each such
+        // group, so address arithmetic and memory issue sit in the shadow of the running MFMA.
+        //   * fragments of k-step ks+1 are read during the MFMAs of ks (two register sets);
+        //   * at the start of the last k-step the wavefront waits for its reads of k-tile t and for
+        //     its share of k-tile t+1, meets the others at the barrier (after which stage t%ST is
+        //     free and k-tile t+1 is complete), and reads k-tile t+1's first fragments during the
+        //     last MFMAs of k-tile t;
+        //   * refill: SPREAD (ST >= 3) issues k-tile t+ST-1 into the stage freed one barrier earlier,
+        //     evenly over all MFMAs of k-tile t; otherwise k-tile t+ST goes into the stage just freed,
+        //     over the MFMAs of the last k-step.
+        constexpr int AHEAD = T::SPREAD ? ST - 1 : ST;     // k-tiles issued by the prologue
+        constexpr int NM = KSTEPS * NMK;
+        // loads placed before the barrier point of a k-tile (SPREAD only)
+        constexpr int N_BEFORE = T::SPREAD ? ((KSTEPS - 1) * NMK * T::LPW + NM - 1) / NM : 0;
+        constexpr int WAIT_LOOP = T::SPREAD ? T::LPW * (ST - 3) + N_BEFORE : T::LPW * (ST - 2);
+        static_assert(WAIT_LOOP <= 63, "vmcnt range");
+        Frags f[2];
 #pragma unroll
-        for (int s = 0; s < ST - 1; ++s) issue_tile(s, s);
+        for (int s = 0; s < AHEAD; ++s) issue_tile(s, s);
+        wait_vmcnt<T::LPW*(AHEAD - 1)>();
+        block_barrier();
+        load_frags(f[0], 0, 0);
         int stage = 0;
-        for (int kt = 0; kt < L; ++kt) {
-            wait_vmcnt<T::LPW*(ST - 2)>();  // tile kt has landed (this wavefront's share)
-            block_barrier();                // ... everyone's share; and stage (kt-1)%ST is free
-            int nxt = stage + (ST - 1);
-            if (nxt >= ST) nxt -= ST;
-            issue_tile(kt + ST - 1, nxt);
-            compute_tile(stage);
-            stage = (stage + 1 == ST) ? 0 : stage + 1;
-        }
+        auto read_one = [&](Frags& dst, int q, int stg, int ks) {
+            if (q < T::FM)
+                dst.a[q] = read_frag(stg, wm * T::TM + q * T::MI + frow, ks);
+            else
+                dst.b[q - T::FM] = read_frag(stg, BM + wn * T::TN + (q - T::FM) * T::MI + frow, ks);
+        };
+        auto tile_body = [&](int kt, auto tail_tag) {
+            constexpr bool TAIL = decltype(tail_tag)::value;
+            const int nxt = (stage + 1 == ST) ? 0 : stage + 1;
+            int fill = stage + (ST - 1);      // SPREAD: stage of k-tile kt+ST-1
+            if (fill >= ST) fill -= ST;
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) {
+                const bool last = ks == KSTEPS - 1;
+                Frags& cur = f[ks & 1];
+                Frags& nx = f[(ks + 1) & 1];
+                if (last) {
+                    wait_lgkmcnt0();          // this wavefront's reads of k-tile kt are done
+                    wait_vmcnt<WAIT_LOOP>();  // its share of k-tile kt+1 has landed
+                    block_barrier();
+                    sched_fence();
+                }
+#pragma unroll
+                for (int idx = 0; idx < NMK; ++idx) {
+                    mfma(cur, idx / T::FN, idx % T::FN);
+                    // fragment reads for the next k-step, spaced over this k-step's MFMAs and finished a few
+                    // MFMAs before its end so that their latency is covered
+#pragma unroll
+                    for (int q = 0; q < NFR; ++q)
+                        if ((q * (NMK > 4 ? NMK - 3 : 1)) / NFR == idx) read_one(nx, q, last ? nxt : stage, last ? 0 : ks + 1);
+                    // refill loads
+                    if constexpr (T::SPREAD) {
+                        const int g = ks * NMK + idx;
+#pragma unroll
+                        for (int l = 0; l < T::LPW; ++l)
+                            if ((l * NM) / T::LPW == g) issue_load(l, kt + ST - 1, fill, TAIL);
+                    } else {
+                        if (last) {
+#pragma unroll
+                            for (int l = 0; l < T::LPW; ++l)
+                                if ((l * NMK) / T::LPW == idx) issue_load(l, kt + ST, stage, TAIL);
+                        }
+                    }
+                    sched_fence();
+                }
+            }
+            if constexpr ((KSTEPS & 1) != 0) f[0] = f[1];
+            stage = nxt;
+        };
+        int kt = 0;
+        // k-tiles whose refill target lies wholly inside K need no range handling
+        for (; kt + AHEAD < L_full; ++kt) tile_body(kt, std::false_type{});
+        for (; kt < L; ++kt) tile_body(kt, std::true_type{});
         wait_vmcnt<0>();
     }
 

@@ -1,0 +1,121 @@
+// Sustained MFMA-only throughput of the device: every wavefront issues back-to-back MFMAs on
+// register operands, no memory traffic.  The result is the practical (power- and clock-limited)
+// ceiling for a dense contraction, reported beside the nominal peak.
+#include <hip/hip_runtime.h>
+
+#include "gemm_kernel.hpp"
+#include "wt_internal.hpp"
+
+namespace wt {
+
+// Operand bits: a cheap per-lane hash mapped to bf16 / e4m3 values of magnitude ~1, so that the
+// multipliers see data like the GEMM's N(0,1) inputs (all-zero operands draw less power and would
+// overstate the ceiling).
+__device__ __forceinline__ uint32_t mix(uint32_t x) {
+    x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+    return x;
+}
+
+template <int IN>
+__global__ __launch_bounds__(256) void mfma_ceiling_kernel(int iters, float* sink) {
+    const uint32_t seed = mix(threadIdx.x + 977u * blockIdx.x);
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+    if constexpr (IN == 0) {
+        bf16x8 a[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            union { uint32_t u[4]; bf16x8 v; } ua, ub;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                // two bf16 per word: sign random, exponent 126..127, random mantissa -> |x| in [0.5, 2)
+                ua.u[q] = (mix(seed + 11u * i + q) & 0x80FF80FFu) | 0x3F003F00u;
+                ub.u[q] = (mix(seed + 101u * i + q + 7u) & 0x80FF80FFu) | 0x3F003F00u;
+            }
+            a[i] = ua.v; b[i] = ub.v;
+        }
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+    } else {
+        i32x8 a[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                // four e4m3 per word: sign random, exponent 6..7 (|x| in [0.5, 2)), random mantissa
+                a[i][q] = (int)((mix(seed + 13u * i + q) & 0x8F8F8F8Fu) | 0x30303030u);
+                b[i][q] = (int)((mix(seed + 131u * i + q + 5u) & 0x8F8F8F8Fu) | 0x30303030u);
+            }
+        f32x4 acc4[4][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc4[i][j][e] = 0.0f;
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc4[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[i], b[j], acc4[i][j], 0, 0, 0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[i][j][e] = acc4[i][j][e];
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) s += acc[i][j][e];
+    if (s == 12345.678f) sink[0] = s;  // keeps the accumulators alive; practically never true
+}
+
+}  // namespace wt
+
+using namespace wt;
+
+extern "C" int wt_mfma_ceiling(wt_ctx* ctx, int in_type, int iters, void* hip_stream, float* sink_dev,
+                               double* tflops) {
+    if (!ctx || !tflops || !sink_dev || iters < 1 || (in_type != WT_BF16 && in_type != WT_FP8_E4M3))
+        return WT_ERR_INVALID_ARG;
+    if (ctx->device < 0) return WT_ERR_NO_DEVICE;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    hipEvent_t e0 = (hipEvent_t)ctx->ev_start, e1 = (hipEvent_t)ctx->ev_stop;
+    const int blocks = kNumCU * 2;  // two 4-wavefront blocks per compute unit
+    hipError_t e = hipSuccess;
+    for (int rep = 0; rep < 2 && e == hipSuccess; ++rep) {  // first pass warms up
+        e = hipEventRecord(e0, stream);
+        if (e != hipSuccess) break;
+        if (in_type == WT_BF16)
+            hipLaunchKernelGGL(mfma_ceiling_kernel<0>, dim3(blocks), dim3(256), 0, stream, iters, sink_dev);
+        else
+            hipLaunchKernelGGL(mfma_ceiling_kernel<1>, dim3(blocks), dim3(256), 0, stream, iters, sink_dev);
+        e = hipGetLastError();
+        if (e == hipSuccess) e = hipEventRecord(e1, stream);
+        if (e == hipSuccess) e = hipEventSynchronize(e1);
+    }
+    float ms = 0;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e != hipSuccess) { ctx->last_hip = (int)e; return WT_ERR_HIP; }
+    // flops per MFMA: bf16 32x32x16 = 2*32*32*16; fp8 16x16x128 = 2*16*16*128 (both 32768)
+    const double flops = (double)blocks * 4.0 * (double)iters * 16.0 * 32768.0;
+    *tflops = flops / ((double)ms * 1e-3) / 1e12;
+    return WT_OK;
+}
