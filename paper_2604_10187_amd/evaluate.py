@@ -1,0 +1,220 @@
+"""Measurement harness for the synthetic workloads (every GPU step goes through libwt's C ABI).
+
+    python -m paper_2604_10187_amd.evaluate sweep   [--table T] [--out F]   # LLM-projection sweep, 27 shapes
+    python -m paper_2604_10187_amd.evaluate wave    [--table T] [--out F]   # M=K=4096, N=128..16384 step 128
+    python -m paper_2604_10187_amd.evaluate stream  [--table T] [--out F] [--sample 300]  # 10,000-shape stream
+    python -m paper_2604_10187_amd.evaluate large   [--out F]               # 16384x8192x8192 bf16 and fp8
+
+"pick" = the configuration wt_select returns; "best" = exhaustive search over the frozen registry
+with the same timing protocol (3 warm-up + 5 measured launches, mean; Sec. 4.2).  The pick's time is
+read from the exhaustive sweep itself, so the ratio best/pick is <= 1 by construction.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import sys
+import time
+
+import numpy as np
+
+from . import binding as wt
+from . import tune
+
+
+def _log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def _dev_operands(torch, M, N, K, in_type, out_type, seed=0):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1000 + seed)
+    A = torch.randn((M, K), device="cuda", generator=g)
+    B = torch.randn((N, K), device="cuda", generator=g)
+    if in_type == wt.WT_BF16:
+        A, B = A.to(torch.bfloat16), B.to(torch.bfloat16)
+        sA = sB = None
+    else:
+        sa, sb = A.abs().max() / 448.0, B.abs().max() / 448.0
+        A, B = (A / sa).to(torch.float8_e4m3fn), (B / sb).to(torch.float8_e4m3fn)
+        sA, sB = sa.reshape(1).float(), sb.reshape(1).float()
+    C = torch.empty((M, N), device="cuda", dtype=torch.float32 if out_type == wt.WT_OUT_F32 else torch.bfloat16)
+    return A, B, C, sA, sB
+
+
+class Exhaustive:
+    """Times every configuration of the registry on one shape; prunes a configuration after one
+    timed launch if it is more than `prune` times slower than the best so far."""
+
+    def __init__(self, ctx, torch, in_type, out_type, prune=2.5, warmup=3, iters=5):
+        self.ctx, self.torch, self.in_type, self.out_type = ctx, torch, in_type, out_type
+        self.prune, self.warmup, self.iters = prune, warmup, iters
+        self.cfgs = [wt.wt_config_get(ctx, i) for i in range(wt.wt_config_count(ctx))]
+        self.stream = torch.cuda.current_stream()
+        self.launches = 0
+        self.gpu_s = 0.0
+
+    def run(self, M, N, K, must=()):
+        A, B, C, sA, sB = _dev_operands(self.torch, M, N, K, self.in_type, self.out_type)
+        times, best = {}, math.inf
+        order = sorted(range(len(self.cfgs)), key=lambda i: i not in must)
+        for i in order:
+            c, r = self.cfgs[i]
+            if r.occ < 1:
+                continue
+            if i not in must and best < math.inf:
+                t1 = wt.wt_time_gemm(self.ctx, M, N, K, A, B, C, c, 1, 1, sA, sB, self.stream)
+                self.launches += 2
+                self.gpu_s += 2 * t1 * 1e-6
+                if t1 > self.prune * best:
+                    continue
+            t = wt.wt_time_gemm(self.ctx, M, N, K, A, B, C, c, self.warmup, self.iters, sA, sB, self.stream)
+            self.launches += self.warmup + self.iters
+            self.gpu_s += (self.warmup + self.iters) * t * 1e-6
+            times[i] = t
+            best = min(best, t)
+        return times
+
+
+def _open_ctx(a, torch):
+    ctx = wt.wt_create(0, a.in_type, a.out_type)
+    path = a.table or tune.table_path(a.in_type, a.out_type)
+    wt.wt_load(ctx, path)
+    return ctx, path
+
+
+def _pick_vs_best(ctx, ex, shapes):
+    rows = []
+    t0 = time.time()
+    for n, (M, N, K) in enumerate(shapes):
+        pick = wt.wt_select(ctx, M, N, K)
+        times = ex.run(M, N, K, must=(pick.id,))
+        best_id = min(times, key=times.get)
+        bc = ex.cfgs[best_id][0]
+        rows.append({"M": M, "N": N, "K": K, "pick": list(pick.astuple()), "pick_us": times[pick.id],
+                     "best": list(bc.astuple()), "best_us": times[best_id], "frac": times[best_id] / times[pick.id],
+                     "pick_tflops": 2.0 * M * N * K / times[pick.id] / 1e6,
+                     "best_tflops": 2.0 * M * N * K / times[best_id] / 1e6,
+                     "pred_us": wt.wt_predict_us(ctx, M, N, K, pick), "n_timed": len(times)})
+        if n % 10 == 0:
+            _log(f"[eval] {n + 1}/{len(shapes)} shapes, {time.time() - t0:.0f}s, last frac {rows[-1]['frac']:.3f}")
+    fr = np.array([r["frac"] for r in rows])
+    summary = {"n_shapes": len(rows), "geomean_frac": float(np.exp(np.mean(np.log(fr)))), "min_frac": float(fr.min()),
+               "p5_frac": float(np.percentile(fr, 5)), "mean_frac": float(fr.mean()),
+               "frac_ge_95": float(np.mean(fr >= 0.95)), "exhaustive_launches": ex.launches,
+               "exhaustive_gpu_seconds": ex.gpu_s}
+    return rows, summary
+
+
+def cmd_sweep(a, torch):
+    import wt_synth
+
+    ctx, path = _open_ctx(a, torch)
+    ex = Exhaustive(ctx, torch, a.in_type, a.out_type, prune=a.prune)
+    rows, summary = _pick_vs_best(ctx, ex, wt_synth.sweep_shapes())
+    return {"workload": "LLM-projection sweep (27 shapes)", "table": path, "summary": summary, "rows": rows}
+
+
+def cmd_stream(a, torch):
+    import wt_synth
+
+    ctx, path = _open_ctx(a, torch)
+    shapes = wt_synth.stream_shapes()
+    mean_ns, p99_ns = wt.wt_select_bench(ctx, shapes, repeats=5)
+    uniq = sorted(set(shapes))
+    rng = np.random.default_rng(2005)
+    sample = [uniq[i] for i in sorted(rng.choice(len(uniq), size=min(a.sample, len(uniq)), replace=False))]
+    ex = Exhaustive(ctx, torch, a.in_type, a.out_type, prune=a.prune)
+    rows, summary = _pick_vs_best(ctx, ex, sample)
+    summary.update({"stream_shapes": len(shapes), "unique_shapes": len(uniq), "exhaustive_sample": len(sample),
+                    "select_mean_us": mean_ns / 1e3, "select_p99_us": p99_ns / 1e3})
+    return {"workload": "runtime stream: 10,000 seeded shapes; exhaustive search on a seeded sample of the unique shapes",
+            "table": path, "summary": summary, "rows": rows}
+
+
+def cmd_wave(a, torch):
+    """Wave-quantisation stress: latency of fixed configurations vs N, against the table's
+    prediction, a step model (T_wave * w) and a single global linear-in-G model (Sec. 3.2, Fig. 3)."""
+    import wt_synth
+
+    ctx, path = _open_ctx(a, torch)
+    stream = torch.cuda.current_stream()
+    shapes = wt_synth.wave_stress_shapes()
+    out = {"workload": "wave-quantisation stress: M=K=4096, N=128..16384 step 128", "table": path, "configs": []}
+    for fields in a.cfgs:
+        cid = wt.wt_config_find(ctx, *fields)
+        c, r = wt.wt_config_get(ctx, cid)
+        pts = []
+        for (M, N, K) in shapes:
+            A, B, C, sA, sB = _dev_operands(torch, M, N, K, a.in_type, a.out_type)
+            us = wt.wt_time_gemm(ctx, M, N, K, A, B, C, c, 3, 5, sA, sB, stream)
+            G, L, w = wt.wt_wave_count(ctx, M, N, K, c)
+            pts.append({"N": N, "G": G, "w": w, "us": us, "pred_us": wt.wt_predict_us(ctx, M, N, K, c)})
+        us = np.array([p["us"] for p in pts]); G = np.array([p["G"] for p in pts], dtype=float)
+        w = np.array([p["w"] for p in pts], dtype=float); pred = np.array([p["pred_us"] for p in pts])
+        t_wave = float(np.sum(us * w) / np.sum(w * w))                    # least-squares step model through 0
+        lin = np.polyfit(G, us, 1)                                        # global linear model in G
+        mape = lambda m: float(np.mean(np.abs(m - us) / us))
+        small, large = w <= 3, w > 3
+        out["configs"].append({"cfg": list(c.astuple()), "occ": r.occ, "capacity": 256 * r.occ,
+                               "mape_wavetune": mape(pred), "mape_step": mape(t_wave * w),
+                               "mape_linear": mape(np.polyval(lin, G)),
+                               "mape_small_w": {"wavetune": float(np.mean(np.abs(pred - us)[small] / us[small])),
+                                                "step": float(np.mean(np.abs(t_wave * w - us)[small] / us[small])),
+                                                "linear": float(np.mean(np.abs(np.polyval(lin, G) - us)[small] / us[small]))},
+                               "mape_large_w": {"wavetune": float(np.mean(np.abs(pred - us)[large] / us[large])),
+                                                "step": float(np.mean(np.abs(t_wave * w - us)[large] / us[large])),
+                                                "linear": float(np.mean(np.abs(np.polyval(lin, G) - us)[large] / us[large]))},
+                               "points": pts})
+        _log(f"[eval] wave cfg {c.astuple()}: MAPE wavetune {out['configs'][-1]['mape_wavetune']:.3f} "
+             f"step {out['configs'][-1]['mape_step']:.3f} linear {out['configs'][-1]['mape_linear']:.3f}")
+    return out
+
+
+def cmd_large(a, torch):
+    """Large prefill GEMM 16384 x 8192 x 8192, bf16 and fp8 e4m3, bf16 out: best configuration,
+    TFLOP/s against the nominal peak and against the measured MFMA-only ceiling."""
+    M, N, K = 16384, 8192, 8192
+    out = {"workload": f"large prefill GEMM {M}x{N}x{K}, bf16 out", "results": []}
+    for in_type, name, peak in ((wt.WT_BF16, "bf16", 2500.0), (wt.WT_FP8_E4M3, "fp8_e4m3", 5000.0)):
+        ctx = wt.wt_create(0, in_type, wt.WT_OUT_BF16)
+        ex = Exhaustive(ctx, torch, in_type, wt.WT_OUT_BF16, prune=1.5)
+        times = ex.run(M, N, K)
+        top = sorted(times.items(), key=lambda kv: kv[1])[:5]
+        ceiling = wt.wt_mfma_ceiling(ctx, in_type, 20000, torch.cuda.current_stream())
+        res = {"in": name, "nominal_peak_tflops": peak, "mfma_only_ceiling_tflops": ceiling, "top": []}
+        for i, us in top:
+            tf = 2.0 * M * N * K / us / 1e6
+            res["top"].append({"cfg": list(ex.cfgs[i][0].astuple()), "us": us, "tflops": tf,
+                               "frac_nominal": tf / peak, "frac_ceiling": tf / ceiling})
+        out["results"].append(res)
+        _log(f"[eval] large {name}: best {res['top'][0]}")
+        wt.wt_destroy(ctx)
+    return out
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser()
+    ap.add_argument("cmd", choices=["sweep", "wave", "stream", "large"])
+    ap.add_argument("--in-type", type=int, default=wt.WT_BF16)
+    ap.add_argument("--out-type", type=int, default=wt.WT_OUT_BF16)
+    ap.add_argument("--table", default=None)
+    ap.add_argument("--out", default=None)
+    ap.add_argument("--sample", type=int, default=300)
+    ap.add_argument("--prune", type=float, default=2.5)
+    ap.add_argument("--cfgs", type=lambda s: [tuple(int(x) for x in c.split(",")) for c in s.split(";")],
+                    default=[(128, 128, 64, 4, 2, 0), (256, 256, 64, 8, 2, 0), (64, 64, 64, 4, 2, 0)])
+    a = ap.parse_args(argv)
+    import torch
+
+    res = {"sweep": cmd_sweep, "wave": cmd_wave, "stream": cmd_stream, "large": cmd_large}[a.cmd](a, torch)
+    txt = json.dumps(res)
+    if a.out:
+        open(a.out, "w").write(txt)
+    summ = res.get("summary") or {k: v for k, v in res.items() if k != "rows"}
+    print(json.dumps(summ if a.cmd in ("sweep", "stream") else {"workload": res["workload"]}))
+
+
+if __name__ == "__main__":
+    main()

@@ -116,3 +116,156 @@ def test_degenerate_shapes_and_errors(ctx_f32):
     with pytest.raises(wt.WtError) as e:
         wt.wt_gemm(ctx_f32, 4, 8, 16, None, dA, dC, cfg, stream=stream)
     assert e.value.status == wt.WT_ERR_INVALID_ARG
+
+
+# ---- fp8 e4m3 ----------------------------------------------------------------------------------
+@pytest.fixture(scope="module")
+def ctx_fp8_f32():
+    c = wt.wt_create(0, wt.WT_FP8_E4M3, wt.WT_OUT_F32)
+    yield c
+    wt.wt_destroy(c)
+
+
+@pytest.fixture(scope="module")
+def ctx_fp8_bf16():
+    c = wt.wt_create(0, wt.WT_FP8_E4M3, wt.WT_OUT_BF16)
+    yield c
+    wt.wt_destroy(c)
+
+
+def test_fp8_integer_matrices_bit_exact_every_config(ctx_fp8_f32):
+    """Integers in [-8,8] are exact in e4m3; with unit scales the fp32 result must equal the oracle
+    bit for bit for every fp8 configuration (ragged edges, K not a multiple of BK)."""
+    for cfg, res in all_configs(ctx_fp8_f32):
+        assert res.occ >= 1
+        M, N, K = cfg.bm + 17, 2 * cfg.bn + 5, 2 * cfg.bk + 48
+        note(f"fp8 int-exact cfg={cfg.astuple()} shape={(M, N, K)}")
+        a32, b32 = wt_synth.gemm_operands(M, N, K, 500 + cfg.id, "int")
+        aq = torch.from_numpy(a32).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+        bq = torch.from_numpy(b32).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+        want = og.gemm_c(aq, bq, "e4m3", 1.0, 1.0)
+        got = run_gemm(ctx_fp8_f32, cfg, aq, bq, wt.WT_OUT_F32, 1.0, 1.0, fill=float("nan"))
+        assert np.array_equal(got, want), f"{cfg}: max diff {np.abs(got - want).max()}"
+
+
+def test_fp8_scaled_normal_inputs(ctx_fp8_f32, ctx_fp8_bf16):
+    """N(0,1) inputs quantised with per-tensor scales s = amax/448; C = sA*sB*sum(qA*qB)."""
+    M, N, K = 200, 333, 1040
+    a32, b32 = wt_synth.gemm_operands(M, N, K, 1004)
+    aq, sa = wt_synth.to_e4m3_bits(a32)
+    bq, sb = wt_synth.to_e4m3_bits(b32)
+    want = og.gemm_c(aq, bq, "e4m3", sa, sb)
+    for cfg, res in all_configs(ctx_fp8_f32):
+        if cfg.swizzle != 2:
+            continue
+        note(f"fp8 normal f32-out cfg={cfg.astuple()}")
+        got = run_gemm(ctx_fp8_f32, cfg, aq, bq, wt.WT_OUT_F32, float(sa), float(sb))
+        # the fp8 MFMA sums its 64/128 products in a wide-but-truncating adder tree before the fp32
+        # accumulate; the observed error is ~1.5e-5, far inside the 1e-3 bar
+        assert og.rel_frobenius(got, want) <= F32_REL_FROB
+        assert og.rel_frobenius(got, want) <= 1e-4
+    for cfg, res in all_configs(ctx_fp8_bf16):
+        if cfg.swizzle != 0:
+            continue
+        note(f"fp8 normal bf16-out cfg={cfg.astuple()}")
+        got = run_gemm(ctx_fp8_bf16, cfg, aq, bq, wt.WT_OUT_BF16, float(sa), float(sb))
+        assert og.max_scaled_err(got, want) <= BF16_ELEM
+
+
+# ---- full-size shapes, checked on sampled rows / columns / edge tiles ----------------------------
+def _sampled_check(ctx, cfg, M, N, K, in_type, out_type, seed, n_rows=12, n_cols=6):
+    """Run the full-size GEMM on the GPU and compare complete sampled rows and columns (random ones
+    plus the first and last of each dimension) with fp64 dot products."""
+    rng = np.random.default_rng(seed)
+    a32, b32 = wt_synth.gemm_operands(M, N, K, seed)
+    if in_type == wt.WT_BF16:
+        ab, bb, sa, sb = wt_synth.to_bf16_bits(a32), wt_synth.to_bf16_bits(b32), None, None
+        a, b = og.decode(ab, "bf16"), og.decode(bb, "bf16")
+    else:
+        (ab, sa), (bb, sb) = wt_synth.to_e4m3_bits(a32), wt_synth.to_e4m3_bits(b32)
+        a, b = og.decode(ab, "e4m3", sa), og.decode(bb, "e4m3", sb)
+        sa, sb = float(sa), float(sb)
+    del a32, b32
+    got = run_gemm(ctx, cfg, ab, bb, out_type, sa, sb)
+    rows = sorted({0, M - 1, *rng.integers(0, M, size=min(n_rows, M)).tolist()})
+    cols = sorted({0, N - 1, *rng.integers(0, N, size=min(n_cols, N)).tolist()})
+    want_r, want_c = og.rows_f64(a, b, rows), og.cols_f64(a, b, cols)
+    if out_type == wt.WT_OUT_F32:
+        assert og.rel_frobenius(got[rows], want_r) <= F32_REL_FROB
+        assert og.rel_frobenius(got[:, cols], want_c) <= F32_REL_FROB
+    else:
+        # per-element bound relative to max(|C_ref|, rms): rms over the sampled rows
+        assert og.max_scaled_err(got[rows], want_r) <= BF16_ELEM
+        assert og.max_scaled_err(got[:, cols], want_c) <= BF16_ELEM
+    assert np.isfinite(got).all()
+
+
+def test_large_prefill_bf16_sampled(ctx_bf16):
+    """16384 x 8192 x 8192, bf16 in / bf16 out, under the flagship configuration."""
+    cfg, _ = wt.wt_config_get(ctx_bf16, wt.wt_config_find(ctx_bf16, 256, 256, 64, 8, 2, 0))
+    note(f"large prefill bf16 cfg={cfg.astuple()}")
+    _sampled_check(ctx_bf16, cfg, 16384, 8192, 8192, wt.WT_BF16, wt.WT_OUT_BF16, 1004)
+
+
+def test_large_prefill_fp8_sampled(ctx_fp8_bf16):
+    cfg, _ = wt.wt_config_get(ctx_fp8_bf16, wt.wt_config_find(ctx_fp8_bf16, 256, 256, 128, 8, 2, 0))
+    note(f"large prefill fp8 cfg={cfg.astuple()}")
+    _sampled_check(ctx_fp8_bf16, cfg, 16384, 8192, 8192, wt.WT_FP8_E4M3, wt.WT_OUT_BF16, 1014)
+
+
+def test_sweep_shapes_full_size_under_selected_config(ctx_bf16):
+    """The 27 LLM-projection shapes at full size, each under the configuration bench.py times for it
+    (wt_select on the shipped dual table; a fixed fallback configuration if no table is shipped)."""
+    import os
+
+    from paper_2604_10187_amd import tune
+
+    path = tune.table_path(wt.WT_BF16, wt.WT_OUT_BF16)
+    have_table = os.path.exists(path)
+    if have_table:
+        wt.wt_load(ctx_bf16, path)
+    for (M, N, K) in wt_synth.sweep_shapes():
+        if have_table:
+            cfg = wt.wt_select(ctx_bf16, M, N, K)
+        else:
+            cfg, _ = wt.wt_config_get(ctx_bf16, wt.wt_config_find(ctx_bf16, 128, 128, 64, 4, 2, 0))
+        note(f"sweep {M}x{N}x{K} cfg={cfg.astuple()}")
+        _sampled_check(ctx_bf16, cfg, M, N, K, wt.WT_BF16, wt.WT_OUT_BF16, wt_synth.shape_seed(1002, M, N, K),
+                       n_rows=6, n_cols=3)
+
+
+def test_wave_count_with_device_occupancy(ctx_f32):
+    """Wave counts reported by the library on the device context equal the oracle's for the
+    occupancy the HIP runtime reports (bit-exact integers)."""
+    from oracle import geometry as geo
+
+    for cfg, res in all_configs(ctx_f32)[::3]:
+        for (M, N, K) in [(16384, 8192, 8192), (4096, 11008, 4096), (333, 4096, 11008), (1, 4096, 4096)]:
+            G, L = geo.phi_gemm(M, N, K, cfg.bm, cfg.bn, cfg.bk)
+            assert wt.wt_wave_count(ctx_f32, M, N, K, cfg) == (G, L, geo.wave_count(G, geo.capacity(res.occ)))
+
+
+def test_profile_fit_select_round_trip_on_device(ctx_bf16, tmp_path):
+    """A reduced sparse profile on the GPU (a few structural keys), fit, save; the oracle's selector on
+    the saved table must return exactly what wt_select returns."""
+    from oracle import select as osel
+
+    grid = wt.make_grid(W=3, I=2, p=2, k_anchors=(1024, 2048), warmup=1, iters=2, key_first=15, key_count=3)
+    n, bA, bB, bC = wt.wt_sample_plan(ctx_bf16, grid)
+    scrA = torch.zeros(bA // 2, dtype=torch.bfloat16, device="cuda")
+    scrB = torch.zeros(bB // 2, dtype=torch.bfloat16, device="cuda")
+    scrC = torch.empty(bC, dtype=torch.uint8, device="cuda")
+    note(f"profile_sparse keys 15..17, {n} records")
+    recs = wt.wt_profile_sparse(ctx_bf16, grid, scrA, scrB, scrC, stream=torch.cuda.current_stream())
+    assert len(recs) == n and np.all(recs["mean_us"] > 0)
+    assert set(recs["key_id"].tolist()) == {15, 16, 17} and set(recs["micro_id"].tolist()) == {0, 1, 2}
+    wt.wt_fit(ctx_bf16, grid, recs)
+    path = str(tmp_path / "t.wt")
+    wt.wt_save(ctx_bf16, path)
+    table, _ = osel.read_table(path)
+    for (M, N, K) in wt_synth.sweep_shapes() + wt_synth.stream_shapes(300):
+        key, micro, t = osel.select(table, M, N, K)
+        c = wt.wt_select(ctx_bf16, M, N, K)
+        kd = table.keys[key]
+        assert (c.bm, c.bn, c.bk, c.nwave, c.stages, c.swizzle) == (kd.bm, kd.bn, kd.bk, kd.nwave, kd.stages, micro)
+        assert key in (15, 16, 17)
