@@ -79,7 +79,16 @@ typedef struct {
     int32_t warmup, iters;
     int32_t key_first, key_count;
     int64_t max_out_elems;
+    int32_t model;    /* wt_model: which latency model wt_fit builds (0 = the paper's) */
+    int32_t reserved;
 } wt_grid;
+
+/* Latency models wt_fit can build into the dual table.  WAVE_BILINEAR is the method (Sec. 4.3);
+ * the other two are its ablations (Sec. 5.4) expressed in the same table form:
+ *   LINEAR  no wave buckets: one bilinear tuple per key fitted over all profiled waves;
+ *   STEP    T = w*(a*L + b), w = ceil(G/capacity): latency as a function of the wave count only
+ *           (the classical T_wave*ceil(G/N) model of Sec. 3.2), continued linearly beyond W. */
+typedef enum { WT_MODEL_WAVE_BILINEAR = 0, WT_MODEL_LINEAR = 1, WT_MODEL_STEP = 2 } wt_model;
 
 /* ---- context ------------------------------------------------------------------------------ */
 /* device >= 0: bind to that GPU, query kernel resources.  device = -1: host-only context (Phi,

@@ -133,10 +133,67 @@ def _fit_group(records) -> Bucket:
     return Bucket(theta=theta, status=status, anchors=anchors)
 
 
-def fit_tables(samples, keys, W: int, p: int) -> DualTable:
+def fit_step(records, cap: int):
+    """Ablation "Step" (Sec. 5.4): latency depends on the wave count only, T = w * (a*L + b) with
+    w = ceil(G/cap) -- the classical T_wave * ceil(G/N) model (Sec. 3.2) with a per-iteration and a
+    fixed cost per wave.  Shared micro per L over all records, then least squares on (w*L, w).
+    Returns (a, b, anchors)."""
+    by_L = defaultdict(list)
+    for r in records:
+        by_L[r.L].append(r)
+    X, y, anchors = [], [], []
+    for L in sorted(by_L):
+        pick = shared_micro(by_L[L])
+        if pick is None:
+            continue
+        anchors.append((L, pick[0]))
+        for (G, Lr, us) in pick[1]:
+            w = -(-G // cap)
+            X.append([w * Lr, w])
+            y.append(us)
+    if not X:
+        return 0.0, 0.0, anchors
+    X, y = np.array(X, dtype=np.float64), np.array(y, dtype=np.float64)
+    if len({row[0] / row[1] for row in X.tolist()}) >= 2:
+        scale = np.max(np.abs(X), axis=0)
+        sol = np.linalg.lstsq(X / scale, y, rcond=None)[0] / scale
+        return float(sol[0]), float(sol[1]), anchors
+    return 0.0, float(np.sum(X[:, 1] * y) / np.sum(X[:, 1] ** 2)), anchors
+
+
+MODEL_WAVE_BILINEAR, MODEL_LINEAR, MODEL_STEP = 0, 1, 2
+
+
+def fit_tables(samples, keys, W: int, p: int, model: int = MODEL_WAVE_BILINEAR) -> DualTable:
     """Build the dual table (Sec. 4.3) with per-key extrapolation entries fitted on the merged
     samples of the last p profiled waves, max(1, W-p+1)..W (Sec. 4.5).  Samples with w > W are
-    ignored."""
+    ignored.
+
+    model selects the ablations of Sec. 5.4 expressed in the same table form:
+      LINEAR  no wave buckets; one bilinear tuple per key fitted on all waves (stored as the
+              extrapolation entry, which every query then uses);
+      STEP    T = w*(a*L + b): bucket w holds (0, 0, a*w, b*w); beyond W the step function is
+              continued by its linear envelope (a/cap, b/cap, 0, 0).
+    """
+    if model == MODEL_LINEAR:
+        t = fit_tables(samples, keys, W, W, MODEL_WAVE_BILINEAR)
+        for k in range(len(keys)):
+            t.local[k] = [Bucket() for _ in range(W)]
+        return t
+    if model == MODEL_STEP:
+        per_key = defaultdict(list)
+        for s in samples:
+            s = Sample(*s)
+            if 1 <= s.w <= W:
+                per_key[s.key].append(s)
+        local, ext = [], []
+        for k, kd in enumerate(keys):
+            a, b, anchors = fit_step(per_key.get(k, []), kd.cap)
+            ok = bool(per_key.get(k))
+            local.append([Bucket(theta=(0.0, 0.0, a * w, b * w), status=0b1100 if ok else 0, anchors=list(anchors))
+                          for w in range(1, W + 1)])
+            ext.append(Bucket(theta=(a / kd.cap, b / kd.cap, 0.0, 0.0), status=0b0011 if ok else 0, anchors=list(anchors)))
+        return DualTable(W=W, keys=list(keys), local=local, ext=ext)
     per_key_w = defaultdict(list)
     for s in samples:
         s = Sample(*s)

@@ -19,6 +19,7 @@ WT_ERR_INVALID_ARG, WT_ERR_UNSUPPORTED_CFG, WT_ERR_INFEASIBLE, WT_ERR_NOT_FITTED
 WT_ERR_HIP, WT_ERR_BUFFER_TOO_SMALL, WT_ERR_IO, WT_ERR_NO_DEVICE = -5, -6, -7, -8
 WT_BF16, WT_FP8_E4M3 = 0, 1
 WT_OUT_F32, WT_OUT_BF16 = 0, 1
+WT_MODEL_WAVE_BILINEAR, WT_MODEL_LINEAR, WT_MODEL_STEP = 0, 1, 2
 
 
 class wt_cfg(C.Structure):
@@ -49,7 +50,8 @@ class wt_grid(C.Structure):
     _fields_ = [("W", C.c_int32), ("I", C.c_int32), ("tau_num", C.c_int32), ("tau_den", C.c_int32),
                 ("p", C.c_int32), ("n_k_anchors", C.c_int32), ("k_anchors", C.POINTER(C.c_int32)),
                 ("warmup", C.c_int32), ("iters", C.c_int32), ("key_first", C.c_int32),
-                ("key_count", C.c_int32), ("max_out_elems", C.c_int64)]
+                ("key_count", C.c_int32), ("max_out_elems", C.c_int64), ("model", C.c_int32),
+                ("reserved", C.c_int32)]
 
 
 class WtError(RuntimeError):
@@ -137,10 +139,10 @@ def _stream(stream):
 
 
 def make_grid(W=40, I=4, tau=(11, 10), p=10, k_anchors=(1024, 2048, 3072, 4096, 5120), warmup=3, iters=5,
-              key_first=0, key_count=0, max_out_elems=0):
+              key_first=0, key_count=0, max_out_elems=0, model=0):
     arr = (C.c_int32 * len(k_anchors))(*k_anchors)
     g = wt_grid(W, I, tau[0], tau[1], p, len(k_anchors), C.cast(arr, C.POINTER(C.c_int32)), warmup, iters,
-                key_first, key_count, max_out_elems)
+                key_first, key_count, max_out_elems, model, 0)
     g._keep = arr  # keep the anchor array alive with the struct
     return g
 

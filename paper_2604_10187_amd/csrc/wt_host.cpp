@@ -292,9 +292,57 @@ static void fit_bucket(std::vector<const wt_sample*>& recs, Bucket& out) {
     out.status = fit_rows(rows, out.th);
 }
 
+// Ablation "Step": T = w*(a*L + b) with w = ceil(G/cap).  Shared micro per loop count over all of the
+// key's records, then the 2x2 normal equations on the columns (w*L, w), each scaled by its largest
+// magnitude.  With a single distinct L only b is identified.
+static void fit_step(std::vector<const wt_sample*>& recs, int64_t cap, double* a_out, double* b_out, Bucket& anchors) {
+    Bucket tmp;
+    fit_bucket(recs, tmp);  // sorts recs by (L, micro, G) and yields the anchors (shared micro per L)
+    anchors = tmp;
+    double sxx = 0, sxz = 0, szz = 0, sxy = 0, szy = 0, xmax = 0, zmax = 0;
+    bool many = false;
+    double first_ratio = -1;
+    std::vector<Row> rows;
+    size_t i = 0;
+    int ai = 0;
+    while (i < recs.size()) {
+        size_t j = i;
+        while (j < recs.size() && recs[j]->L == recs[i]->L) ++j;
+        if (ai < tmp.n_anchor && tmp.anchor_L[ai] == recs[i]->L) {
+            for (size_t t = i; t < j; ++t)
+                if (recs[t]->micro_id == tmp.anchor_micro[ai]) {
+                    const double w = static_cast<double>(ceil_div64(recs[t]->G, cap));
+                    rows.push_back(Row{w * static_cast<double>(recs[t]->L), w, recs[t]->mean_us});
+                }
+            ++ai;
+        }
+        i = j;
+    }
+    for (const Row& r : rows) {
+        xmax = std::max(xmax, fabs(r.G));
+        zmax = std::max(zmax, fabs(r.L));
+        const double ratio = r.G / r.L;
+        if (first_ratio < 0) first_ratio = ratio; else many |= (ratio != first_ratio);
+    }
+    *a_out = *b_out = 0.0;
+    if (rows.empty()) return;
+    for (const Row& r : rows) {
+        const double x = r.G / xmax, z = r.L / zmax;
+        sxx += x * x; sxz += x * z; szz += z * z; sxy += x * r.T; szy += z * r.T;
+    }
+    if (many) {
+        const double det = sxx * szz - sxz * sxz;
+        *a_out = ((sxy * szz - szy * sxz) / det) / xmax;
+        *b_out = ((szy * sxx - sxy * sxz) / det) / zmax;
+    } else {
+        *b_out = (szy / szz) / zmax;
+    }
+}
+
 static int fit_table(wt_ctx* ctx, const wt_grid* grid, const wt_sample* s, size_t n) {
     const int W = grid->W, nk = static_cast<int>(ctx->keys.size());
     if (W < 1 || grid->p < 1) return WT_ERR_INVALID_ARG;
+    if (grid->model < WT_MODEL_WAVE_BILINEAR || grid->model > WT_MODEL_STEP) return WT_ERR_INVALID_ARG;
     Table t;
     t.W = W; t.I = grid->I; t.p = grid->p; t.tau_num = grid->tau_num; t.tau_den = grid->tau_den;
     t.buckets.assign(static_cast<size_t>(nk) * (W + 1), Bucket{});
@@ -304,13 +352,36 @@ static int fit_table(wt_ctx* ctx, const wt_grid* grid, const wt_sample* s, size_
         if (s[i].w < 1 || s[i].w > W) continue;
         by[static_cast<size_t>(s[i].key_id) * W + (s[i].w - 1)].push_back(&s[i]);
     }
-    const int first_ext = std::max(1, W - grid->p + 1);
+    const int first_ext = grid->model == WT_MODEL_LINEAR ? 1 : std::max(1, W - grid->p + 1);
     for (int k = 0; k < nk; ++k) {
         std::vector<const wt_sample*> merged;
+        if (grid->model == WT_MODEL_STEP) {
+            for (int w = 1; w <= W; ++w) {
+                std::vector<const wt_sample*>& recs = by[static_cast<size_t>(k) * W + (w - 1)];
+                merged.insert(merged.end(), recs.begin(), recs.end());
+            }
+            double a = 0, b = 0;
+            Bucket anchors;
+            const bool ok = !merged.empty();
+            fit_step(merged, ctx->keys[k].cap, &a, &b, anchors);
+            for (int w = 1; w <= W; ++w) {
+                Bucket& bk = t.buckets[static_cast<size_t>(k) * (W + 1) + (w - 1)];
+                bk = anchors;
+                bk.th[0] = 0; bk.th[1] = 0; bk.th[2] = a * w; bk.th[3] = b * w;
+                bk.status = ok ? 0xC : 0;
+            }
+            Bucket& ex = t.buckets[static_cast<size_t>(k) * (W + 1) + W];
+            ex = anchors;
+            const double cap = static_cast<double>(ctx->keys[k].cap);
+            ex.th[0] = a / cap; ex.th[1] = b / cap; ex.th[2] = 0; ex.th[3] = 0;
+            ex.status = ok ? 0x3 : 0;
+            continue;
+        }
         for (int w = 1; w <= W; ++w) {
             std::vector<const wt_sample*>& recs = by[static_cast<size_t>(k) * W + (w - 1)];
             if (w >= first_ext) merged.insert(merged.end(), recs.begin(), recs.end());
-            fit_bucket(recs, t.buckets[static_cast<size_t>(k) * (W + 1) + (w - 1)]);
+            if (grid->model == WT_MODEL_WAVE_BILINEAR)
+                fit_bucket(recs, t.buckets[static_cast<size_t>(k) * (W + 1) + (w - 1)]);
         }
         fit_bucket(merged, t.buckets[static_cast<size_t>(k) * (W + 1) + W]);
     }

@@ -186,3 +186,32 @@ def test_bad_table_file(ctx, tmp_path):
     assert e.value.status == wt.WT_ERR_IO
     with pytest.raises(wt.WtError):
         wt.wt_load(ctx, str(tmp_path / "missing.wt"))
+
+
+@pytest.mark.parametrize("model", [wt.WT_MODEL_LINEAR, wt.WT_MODEL_STEP])
+def test_ablation_models_parity(ctx, tmp_path, model):
+    """Step and Linear tables built by the library equal the oracle's (coefficients to 1e-9, anchors
+    and lookups exactly)."""
+    W, I, p = 10, 4, 4
+    keys = _keys(ctx)
+    samples = _synthetic_samples(keys, W, I, noise_seed=9)
+    wt.wt_fit(ctx, wt.make_grid(W=W, I=I, p=p, k_anchors=K_ANCHORS, model=model), samples)
+    path = str(tmp_path / "abl.wt")
+    wt.wt_save(ctx, path)
+    table, _ = osel.read_table(path)
+    want = ofit.fit_tables([tuple(r)[:5] + (float(r["mean_us"]),) for r in samples], keys, W, p, model=model)
+    for k in range(len(keys)):
+        for got_b, want_b in list(zip(table.local[k], want.local[k])) + [(table.ext[k], want.ext[k])]:
+            assert got_b.status == want_b.status
+            if want_b.status:
+                assert got_b.anchors == want_b.anchors
+                scale = max(abs(x) for x in want_b.theta) or 1.0
+                assert np.allclose(got_b.theta, want_b.theta, rtol=1e-9, atol=1e-12 * scale) or \
+                    _pred_close(got_b.theta, want_b.theta, keys[k])
+    for (M, N, K) in wt_synth.sweep_shapes() + wt_synth.stream_shapes(500):
+        key, micro, t = osel.select(table, M, N, K)
+        c = wt.wt_select(ctx, M, N, K)
+        kd = keys[key]
+        assert (c.bm, c.bn, c.bk, c.nwave, c.stages, c.swizzle) == (kd.bm, kd.bn, kd.bk, kd.nwave, kd.stages, micro)
+    with pytest.raises(wt.WtError):
+        wt.wt_fit(ctx, wt.make_grid(W=W, I=I, p=p, k_anchors=K_ANCHORS, model=7), samples)

@@ -257,3 +257,42 @@ def test_exhaustive_helpers():
     assert res == [(10, 5), (30, 0)]
     assert oex.fraction_of_best(2.0, 1.0) == 0.5
     assert abs(oex.geomean([0.5, 2.0]) - 1.0) < 1e-15
+
+
+# ---- ablation models (Sec. 5.4): Step and Linear ---------------------------------------------------
+def test_step_model_recovers_a_pure_step_surface():
+    # T = w * (a*L + b) exactly -> the Step fit returns a and b, bucket w holds (0,0,a*w,b*w), and a
+    # query beyond W is priced by the linear envelope a/cap, b/cap
+    a, b, W = 0.37, 4.5, 5
+    samples = [ofit.Sample(k, mi, s.g, L, s.w, geo.wave_count(s.g, kd.cap) * (a * L + b) * (1.0 + 0.1 * mi))
+               for k, kd in enumerate(KEYS) for s in smp.sample_set(kd.cap, W, 4)
+               for L in smp.loop_anchors(K_ANCHORS, kd.bk) for mi in range(2)]
+    t = ofit.fit_tables(samples, KEYS, W, p=2, model=ofit.MODEL_STEP)
+    for k, kd in enumerate(KEYS):
+        for w in range(1, W + 1):
+            th = t.local[k][w - 1].theta
+            assert th[0] == 0 and th[1] == 0 and abs(th[2] - a * w) < 1e-9 and abs(th[3] - b * w) < 1e-8
+            assert all(m == 0 for _, m in t.local[k][w - 1].anchors)       # micro 0 is 10 % faster
+        assert np.allclose(t.ext[k].theta, (a / kd.cap, b / kd.cap, 0, 0), rtol=1e-9)
+        # inside a wave the Step model is flat in G
+        G1, G2 = kd.cap + 1, 2 * kd.cap
+        assert osel.predict(t.local[k][1].theta, G1, 32) == osel.predict(t.local[k][1].theta, G2, 32)
+
+
+def test_linear_model_is_one_global_bilinear_per_key():
+    W = 6
+    samples = _make_samples(W, 4, _penalty)
+    t = ofit.fit_tables(samples, KEYS, W, p=2, model=ofit.MODEL_LINEAR)
+    full = ofit.fit_tables(samples, KEYS, W, p=W)           # ext over all waves = the global fit
+    for k in range(len(KEYS)):
+        assert all(b.status == 0 for b in t.local[k])
+        assert t.ext[k].theta == full.ext[k].theta and t.ext[k].anchors == full.ext[k].anchors
+        assert osel.bucket_for(t, k, 1) is t.ext[k] and osel.bucket_for(t, k, W + 3) is t.ext[k]
+    # on data that really has per-wave structure the global fit is worse than the bucketed one
+    err_lin = err_full = 0.0
+    for s in samples:
+        if s.micro == 0 and s.key == 1:
+            truth = _latency(s.key, s.micro, s.G, s.L, W, lambda *a: 0.0)
+            err_lin += abs(osel.predict(t.ext[1].theta, s.G, s.L) - truth) / truth
+            err_full += abs(osel.predict(full.local[1][s.w - 1].theta, s.G, s.L) - truth) / truth
+    assert err_full < 1e-6 < err_lin
