@@ -105,6 +105,12 @@ int wt_config_find(const wt_ctx* ctx, const wt_cfg* fields, int* id); /* match t
 int wt_key_count(const wt_ctx* ctx, int* n);
 /* Override the recorded occupancy of structural key key_id (e.g. with a measured value). */
 int wt_key_set_occ(wt_ctx* ctx, int key_id, int occ);
+/* Wave capacity used by the wave count, the sampler and the table buckets:
+ *   WT_CAP_CU_TIMES_OCC (default)  capacity = 256 CUs x resident blocks per CU of the key;
+ *   WT_CAP_CU_ONLY                 capacity = 256, the paper's literal w = ceil(G / N_SM) (Sec. 3.2, 3.3).
+ * Changing the mode discards a fitted table; wt_load sets the mode the table was built with. */
+typedef enum { WT_CAP_CU_TIMES_OCC = 0, WT_CAP_CU_ONLY = 1 } wt_cap_mode;
+int wt_set_capacity_mode(wt_ctx* ctx, int mode);
 
 /* ---- the GEMM (Sec. 3.2, tiled-GEMM paragraph) ------------------------------------------- */
 /* C[M,N] = A[M,K] * B[N,K]^T under configuration cfg.  A, B, C: device pointers (types per

@@ -20,6 +20,7 @@ WT_ERR_HIP, WT_ERR_BUFFER_TOO_SMALL, WT_ERR_IO, WT_ERR_NO_DEVICE = -5, -6, -7, -
 WT_BF16, WT_FP8_E4M3 = 0, 1
 WT_OUT_F32, WT_OUT_BF16 = 0, 1
 WT_MODEL_WAVE_BILINEAR, WT_MODEL_LINEAR, WT_MODEL_STEP = 0, 1, 2
+WT_CAP_CU_TIMES_OCC, WT_CAP_CU_ONLY = 0, 1
 
 
 class wt_cfg(C.Structure):
@@ -84,6 +85,7 @@ def lib():
             "wt_config_find": [vp, C.POINTER(wt_cfg), C.POINTER(C.c_int)],
             "wt_key_count": [vp, C.POINTER(C.c_int)],
             "wt_key_set_occ": [vp, C.c_int, C.c_int],
+            "wt_set_capacity_mode": [vp, C.c_int],
             "wt_gemm": [vp, i64, i64, i64, vp, vp, vp, vp, vp, wt_cfg, vp],
             "wt_wave_count": [vp, i64, i64, i64, wt_cfg, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32)],
             "wt_sample_grid": [i64, i32, i32, i32, i32, vp, vp, vp, sz, C.POINTER(sz)],
@@ -109,7 +111,7 @@ def lib():
 
 
 EXPORTS = ("wt_create", "wt_destroy", "wt_last_hip_error", "wt_status_string", "wt_config_count", "wt_config_get",
-           "wt_config_find", "wt_key_count", "wt_key_set_occ", "wt_gemm", "wt_wave_count", "wt_sample_grid",
+           "wt_config_find", "wt_key_count", "wt_key_set_occ", "wt_set_capacity_mode", "wt_gemm", "wt_wave_count", "wt_sample_grid",
            "wt_sample_plan", "wt_profile_sparse", "wt_time_gemm", "wt_mfma_ceiling", "wt_fit", "wt_select", "wt_predict_us",
            "wt_select_bench", "wt_save", "wt_load")
 
@@ -189,6 +191,10 @@ def wt_config_find(ctx, bm, bn, bk, nwave, stages, swizzle) -> int:
 
 def wt_key_set_occ(ctx, key_id: int, occ: int):
     _check(lib().wt_key_set_occ(ctx, key_id, occ), "wt_key_set_occ")
+
+
+def wt_set_capacity_mode(ctx, mode: int):
+    _check(lib().wt_set_capacity_mode(ctx, mode), "wt_set_capacity_mode")
 
 
 def wt_gemm(ctx, M, N, K, A, B, Cout, cfg, scaleA=None, scaleB=None, stream=None):

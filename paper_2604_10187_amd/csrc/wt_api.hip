@@ -168,7 +168,7 @@ int wt_create(wt_ctx** out, int device, int in_type, int out_type) {
             if (e != hipSuccess) { (void)hipGetLastError(); occ = 0; }
             key.vgprs = fa.numRegs;
             key.occ = occ;
-            key.cap = (int64_t)kNumCU * std::max(occ, 1);
+            key.cap = key_capacity(ctx->cap_mode, occ);
             for (int m = 0; m < key.n_micro; ++m) {
                 ctx->cfgs[key.first_cfg + m].res.occ = occ;
                 ctx->cfgs[key.first_cfg + m].res.vgprs = fa.numRegs;

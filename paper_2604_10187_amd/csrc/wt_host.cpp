@@ -69,7 +69,7 @@ int build_registry(wt_ctx* ctx) {
             k.lds_bytes = e[i].lds_bytes;
             k.vgprs = (k.bm * k.bn) / (k.nwave * 64) + 64;  // accumulators + working set (estimate)
             k.occ = std::max(1, static_occupancy(k.lds_bytes, k.nwave, k.vgprs));
-            k.cap = static_cast<int64_t>(kNumCU) * k.occ;
+            k.cap = key_capacity(ctx->cap_mode, k.occ);
             k.n_micro = kNumSwizzle;
             k.first_cfg = static_cast<int>(ctx->cfgs.size());
             const int key_id = static_cast<int>(ctx->keys.size());
@@ -453,8 +453,8 @@ static int select_impl(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, int* 
 
 // ---- table file ------------------------------------------------------------------------------------
 // Little-endian.  Header: 16 uint32 = 'WTDT', version 1, n_keys, W, I, p, tau_num, tau_den, n_cu,
-// anchor slots A, in_type, out_type, key_mode (0), 3 reserved.  Per key: 8 int32 (bm, bn, bk, nwave,
-// stages, occ, n_micro, 0), int64 cap, (W+1)*4 float64 theta (w = 1..W then ext), (W+1) int32
+// anchor slots A, in_type, out_type, key_mode (capacity mode), 3 reserved.  Per key: 8 int32 (bm, bn, bk, nwave,
+// stages, occ, n_micro, 0), int64 cap (256*occ, or 256 when key_mode = 1), (W+1)*4 float64 theta (w = 1..W then ext), (W+1) int32
 // status, (W+1) int32 n_anchor, (W+1)*A int32 anchor L, (W+1)*A int32 anchor micro.
 static const uint32_t kMagic = 0x54445457u;  // "WTDT"
 
@@ -468,7 +468,7 @@ static int save_table(const wt_ctx* ctx, const char* path) {
                               static_cast<uint32_t>(t.p), static_cast<uint32_t>(t.tau_num),
                               static_cast<uint32_t>(t.tau_den), static_cast<uint32_t>(kNumCU),
                               static_cast<uint32_t>(kMaxAnchors), static_cast<uint32_t>(ctx->in_type),
-                              static_cast<uint32_t>(ctx->out_type), 0u, 0u, 0u, 0u};
+                              static_cast<uint32_t>(ctx->out_type), static_cast<uint32_t>(ctx->cap_mode), 0u, 0u, 0u};
     bool ok = fwrite(hdr, sizeof(hdr), 1, f) == 1;
     const int R = t.W + 1;
     for (uint32_t k = 0; ok && k < nk; ++k) {
@@ -496,7 +496,7 @@ static int load_table(wt_ctx* ctx, const char* path) {
     std::vector<int> occs;
     if (fread(hdr, sizeof(hdr), 1, f) != 1 || hdr[0] != kMagic || hdr[1] != 1u) rc = WT_ERR_IO;
     if (rc == WT_OK && (hdr[2] != ctx->keys.size() || hdr[9] != static_cast<uint32_t>(kMaxAnchors) ||
-                        hdr[10] != static_cast<uint32_t>(ctx->in_type) || hdr[3] < 1 || hdr[3] > 4096))
+                        hdr[10] != static_cast<uint32_t>(ctx->in_type) || hdr[3] < 1 || hdr[3] > 4096 || hdr[12] > 1u))
         rc = WT_ERR_INVALID_ARG;  // table was built for another registry
     if (rc == WT_OK) {
         t.W = static_cast<int>(hdr[3]); t.I = static_cast<int>(hdr[4]); t.p = static_cast<int>(hdr[5]);
@@ -509,7 +509,7 @@ static int load_table(wt_ctx* ctx, const char* path) {
             if (fread(kd, sizeof(kd), 1, f) != 1 || fread(&cap, sizeof(cap), 1, f) != 1) { rc = WT_ERR_IO; break; }
             const Key& key = ctx->keys[k];
             if (kd[0] != key.bm || kd[1] != key.bn || kd[2] != key.bk || kd[3] != key.nwave || kd[4] != key.stages ||
-                kd[5] < 1 || cap != static_cast<int64_t>(kNumCU) * kd[5]) { rc = WT_ERR_INVALID_ARG; break; }
+                kd[5] < 1 || cap != key_capacity(static_cast<int>(hdr[12]), kd[5])) { rc = WT_ERR_INVALID_ARG; break; }
             occs.push_back(kd[5]);
             Bucket* b = &t.buckets[k * R];
             bool ok = true;
@@ -525,9 +525,10 @@ static int load_table(wt_ctx* ctx, const char* path) {
     fclose(f);
     if (rc != WT_OK) return rc;
     // the table's wave boundaries are those of the occupancy it was profiled with
+    ctx->cap_mode = static_cast<int>(hdr[12]);
     for (size_t k = 0; k < ctx->keys.size(); ++k) {
         ctx->keys[k].occ = occs[k];
-        ctx->keys[k].cap = static_cast<int64_t>(kNumCU) * occs[k];
+        ctx->keys[k].cap = key_capacity(ctx->cap_mode, occs[k]);
         for (int m = 0; m < ctx->keys[k].n_micro; ++m) ctx->cfgs[ctx->keys[k].first_cfg + m].res.occ = occs[k];
     }
     t.fitted = true;
@@ -592,8 +593,16 @@ int wt_key_set_occ(wt_ctx* ctx, int key_id, int occ) {
     if (!ctx || key_id < 0 || key_id >= static_cast<int>(ctx->keys.size()) || occ < 1) return WT_ERR_INVALID_ARG;
     Key& k = ctx->keys[key_id];
     k.occ = occ;
-    k.cap = static_cast<int64_t>(kNumCU) * occ;
+    k.cap = key_capacity(ctx->cap_mode, occ);
     for (int m = 0; m < k.n_micro; ++m) ctx->cfgs[k.first_cfg + m].res.occ = occ;
+    return WT_OK;
+}
+
+int wt_set_capacity_mode(wt_ctx* ctx, int mode) {
+    if (!ctx || (mode != WT_CAP_CU_TIMES_OCC && mode != WT_CAP_CU_ONLY)) return WT_ERR_INVALID_ARG;
+    ctx->cap_mode = mode;
+    for (Key& k : ctx->keys) k.cap = key_capacity(mode, k.occ);
+    ctx->table = Table();
     return WT_OK;
 }
 

@@ -54,6 +54,7 @@ struct wt_ctx {
     int device = -1;
     int in_type = 0, out_type = 0;
     int last_hip = 0;
+    int cap_mode = 0;  // wt_cap_mode
     std::vector<wt::Config> cfgs;
     std::vector<wt::Key> keys;
     wt::Table table;
@@ -67,6 +68,9 @@ namespace wt {
 int build_registry(wt_ctx* ctx);  // fills cfgs/keys from the compiled kernel lists; static occupancy
 int static_occupancy(int lds_bytes, int nwave, int acc_vgprs);
 inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline int64_t key_capacity(int cap_mode, int occ) {
+    return cap_mode == WT_CAP_CU_ONLY ? kNumCU : static_cast<int64_t>(kNumCU) * (occ > 0 ? occ : 1);
+}
 int find_config(const wt_ctx* ctx, const wt_cfg& c);
 
 struct GridPoint {

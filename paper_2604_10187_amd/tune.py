@@ -45,7 +45,7 @@ def profile(ctx, grid, in_type, out_type, log=print, chunk_keys=4):
         kc = min(chunk_keys, first + count - k0)
         g = wt.make_grid(W=grid.W, I=grid.I, tau=(grid.tau_num, grid.tau_den), p=grid.p,
                          k_anchors=[grid.k_anchors[j] for j in range(grid.n_k_anchors)], warmup=grid.warmup,
-                         iters=grid.iters, key_first=k0, key_count=kc, max_out_elems=grid.max_out_elems)
+                         iters=grid.iters, key_first=k0, key_count=kc, max_out_elems=grid.max_out_elems, model=grid.model)
         recs = wt.wt_profile_sparse(ctx, g, scrA, scrB, scrC, stream=torch.cuda.current_stream())
         out.append(recs)
         log(f"[tune] keys {k0}..{k0 + kc - 1}: {len(recs)} records, {time.time() - t0:.0f}s elapsed")
@@ -65,22 +65,26 @@ def main(argv=None):
     ap.add_argument("--key-first", type=int, default=0)
     ap.add_argument("--key-count", type=int, default=0)
     ap.add_argument("--max-out-elems", type=int, default=0)
+    ap.add_argument("--cap-mode", type=int, default=0, help="0: 256 x resident blocks per CU, 1: 256 (paper-literal)")
+    ap.add_argument("--model", type=int, default=0, help="0 wave-bilinear, 1 linear, 2 step")
     ap.add_argument("--samples-out", default=None)
     ap.add_argument("--fit-from", nargs="*", default=None)
     ap.add_argument("--out", default=None)
     a = ap.parse_args(argv)
     grid = wt.make_grid(W=a.W, I=a.I, p=a.p, k_anchors=a.k_anchors, warmup=a.warmup, iters=a.iters,
-                        key_first=a.key_first, key_count=a.key_count, max_out_elems=a.max_out_elems)
+                        key_first=a.key_first, key_count=a.key_count, max_out_elems=a.max_out_elems, model=a.model)
     if a.fit_from is not None:
         recs = np.concatenate([np.load(f) for f in a.fit_from])
         occ_files = [f.replace(".npy", ".occ.npy") for f in a.fit_from]
         ctx = wt.wt_create(-1, a.in_type, a.out_type)
+        wt.wt_set_capacity_mode(ctx, a.cap_mode)
         if all(os.path.exists(f) for f in occ_files):    # wave boundaries = those of the profiling run
             occ = np.load(occ_files[0])
             for k, o in enumerate(occ):
                 wt.wt_key_set_occ(ctx, k, int(o))
     else:
         ctx = wt.wt_create(0, a.in_type, a.out_type)
+        wt.wt_set_capacity_mode(ctx, a.cap_mode)
         n, bA, bB, bC = wt.wt_sample_plan(ctx, grid)
         print(f"[tune] plan: {n} records, scratch A {bA >> 20} MiB, B {bB >> 20} MiB, C {bC >> 20} MiB", flush=True)
         recs = profile(ctx, grid, a.in_type, a.out_type, log=lambda s: print(s, flush=True))

@@ -215,3 +215,37 @@ def test_ablation_models_parity(ctx, tmp_path, model):
         assert (c.bm, c.bn, c.bk, c.nwave, c.stages, c.swizzle) == (kd.bm, kd.bn, kd.bk, kd.nwave, kd.stages, micro)
     with pytest.raises(wt.WtError):
         wt.wt_fit(ctx, wt.make_grid(W=W, I=I, p=p, k_anchors=K_ANCHORS, model=7), samples)
+
+
+def test_paper_literal_capacity_mode(tmp_path):
+    """Capacity = number of CUs (the paper's w = ceil(G / N_SM)): wave counts, table and lookups
+    follow the 256-tile waves; the file records the mode and wt_load restores it."""
+    c = wt.wt_create(-1, wt.WT_BF16, wt.WT_OUT_F32)
+    try:
+        wt.wt_set_capacity_mode(c, wt.WT_CAP_CU_ONLY)
+        keys = [k._replace(cap=geo.N_CU) for k in _keys(c)]
+        cfg, res = wt.wt_config_get(c, 3 * 31)          # a key with several resident blocks per CU
+        assert res.occ > 1
+        G, L, w = wt.wt_wave_count(c, 4096, 4096, 4096, cfg)
+        assert w == geo.wave_count(G, 256)
+        W, I = 8, 4
+        samples = _synthetic_samples(keys, W, I, noise_seed=3)
+        wt.wt_fit(c, wt.make_grid(W=W, I=I, p=3, k_anchors=K_ANCHORS), samples)
+        path = str(tmp_path / "lit.wt")
+        wt.wt_save(c, path)
+        table, meta = osel.read_table(path)
+        assert meta["key_mode"] == 1 and table.keys == keys
+        c2 = wt.wt_create(-1, wt.WT_BF16, wt.WT_OUT_F32)
+        wt.wt_load(c2, path)
+        assert wt.wt_wave_count(c2, 4096, 4096, 4096, cfg)[2] == w
+        for (M, N, K) in wt_synth.sweep_shapes() + wt_synth.stream_shapes(500):
+            key, micro, t = osel.select(table, M, N, K)
+            for cc in (c, c2):
+                s = wt.wt_select(cc, M, N, K)
+                assert s.id == 3 * key + micro and wt.wt_predict_us(cc, M, N, K, s) == t
+        wt.wt_destroy(c2)
+        wt.wt_set_capacity_mode(c, wt.WT_CAP_CU_TIMES_OCC)       # switching discards the table
+        with pytest.raises(wt.WtError):
+            wt.wt_select(c, 64, 64, 64)
+    finally:
+        wt.wt_destroy(c)
