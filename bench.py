@@ -24,6 +24,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
 PEAK_HBM_GBS = 8000.0
+# HBM-side bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled
+# by the copy-kernel calibration (x2.0 / x1.0): profiles/gemm_traffic_pmc.md.  Keyed by (kernel, shape);
+# reported as null when the run picks another kernel than the profiled one.
+TRAFFIC_BYTES = {((256, 256, 64, 8, 2, 2), (4096, 11008, 4096)): 718.6e6}
 
 
 def log(*a):
@@ -120,8 +124,12 @@ def main():
     dA, dB, dC = bufs[big]
     us_big = wt.wt_time_gemm(ctx, *big, dA, dB, dC, cfg_big, warmup=3, iters=20, stream=stream)
     ach = 2.0 * big[0] * big[1] * big[2] / us_big / 1e6
+    ceiling = wt.wt_mfma_ceiling(ctx, in_type, 20000, stream)   # MFMA-only loop, N(0,1)-like operands
     roofline = {"bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "frac": round(ach / PEAK_BF16_TFLOPS, 4),
+                "traffic": TRAFFIC_BYTES.get((cfg_big.astuple(), tuple(big))),
+                "algorithmic_flop": 2.0 * big[0] * big[1] * big[2],
+                "mfma_only_ceiling": round(ceiling, 1), "frac_of_mfma_only_ceiling": round(ach / ceiling, 4),
                 "kernel": f"gemm_kernel<{cfg_big.bm},{cfg_big.bn},{cfg_big.bk},nw{cfg_big.nwave},st{cfg_big.stages}>"
                           f" sw{cfg_big.swizzle} on {big[0]}x{big[1]}x{big[2]}", "avg_us": round(us_big, 2)}
 

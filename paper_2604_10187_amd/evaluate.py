@@ -96,7 +96,8 @@ def _pick_vs_best(ctx, ex, shapes):
                      "best": list(bc.astuple()), "best_us": times[best_id], "frac": times[best_id] / times[pick.id],
                      "pick_tflops": 2.0 * M * N * K / times[pick.id] / 1e6,
                      "best_tflops": 2.0 * M * N * K / times[best_id] / 1e6,
-                     "pred_us": wt.wt_predict_us(ctx, M, N, K, pick), "n_timed": len(times)})
+                     "pred_us": wt.wt_predict_us(ctx, M, N, K, pick), "n_timed": len(times),
+                     "times": {str(i): round(t, 3) for i, t in times.items()}})
         if n % 10 == 0:
             _log(f"[eval] {n + 1}/{len(shapes)} shapes, {time.time() - t0:.0f}s, last frac {rows[-1]['frac']:.3f}")
     fr = np.array([r["frac"] for r in rows])
@@ -194,9 +195,65 @@ def cmd_large(a, torch):
     return out
 
 
+def cmd_ablate(a, torch=None):
+    """CPU only.  Re-fit the saved profiling records under model / (W, I) variants with wt_fit on a
+    host-only context and score each variant's picks against saved exhaustive timings (the `times` of
+    a sweep/stream result file).  A pick that the exhaustive run pruned (more than `prune` times slower
+    than the best after one launch) is scored at 1/prune."""
+    z = np.load(a.samples)
+    recs, occ = z["samples"], z["occ"]
+    evals = [json.load(open(f)) for f in a.scores]
+    rows = [r for e in evals for r in e["rows"]]
+    out = {"workload": "ablation of the latency model and of the profiling range, scored on " +
+                       ", ".join(e["workload"] for e in evals), "variants": []}
+    W0, I0 = int(recs["w"].max()), a.I
+
+    def score(model, W, I, cap_mode):
+        ctx = wt.wt_create(-1, a.in_type, a.out_type)
+        wt.wt_set_capacity_mode(ctx, cap_mode)
+        for k, o in enumerate(occ):
+            wt.wt_key_set_occ(ctx, k, int(o))
+        sub = recs[recs["w"] <= W]
+        if I < I0:       # sub-intervals of a coarser split are unions of the finer ones: keep each union's top sample
+            keep = np.zeros(len(sub), dtype=bool)
+            step = I0 // I
+            for k in range(len(occ)):
+                cap = 256 if cap_mode == 1 else 256 * int(occ[k])
+                m = sub["key_id"] == k
+                pos = (sub["G"][m] - 1) % cap                       # offset inside the wave region
+                idx = np.minimum(pos * I0 // cap, I0 - 1)            # which of the I0 sub-intervals
+                keep[np.where(m)[0]] = (idx % step) == (step - 1)
+            sub = sub[keep]
+        wt.wt_fit(ctx, wt.make_grid(W=W, I=I, p=min(a.p, W), k_anchors=tune.K_ANCHORS, model=model), sub)
+        fr = []
+        for r in rows:
+            c = wt.wt_select(ctx, r["M"], r["N"], r["K"])
+            t = r["times"].get(str(c.id))
+            fr.append(r["best_us"] / t if t else 1.0 / a.prune)
+        wt.wt_destroy(ctx)
+        fr = np.array(fr)
+        return {"geomean_frac": float(np.exp(np.mean(np.log(fr)))), "min_frac": float(fr.min()),
+                "frac_ge_95": float(np.mean(fr >= 0.95)), "records": int(len(sub))}
+
+    for name, model in (("wave-bilinear (full)", 0), ("linear", 1), ("step", 2)):
+        out["variants"].append({"model": name, "W": W0, "I": I0, **score(model, W0, I0, a.cap_mode)})
+    for W in (5, 10, 20, W0):
+        for I in (1, 2, I0):
+            if (W, I) != (W0, I0):
+                out["variants"].append({"model": "wave-bilinear (full)", "W": W, "I": I, **score(0, W, I, a.cap_mode)})
+    for v in out["variants"]:
+        _log(f"[ablate] {v}")
+    return out
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser()
-    ap.add_argument("cmd", choices=["sweep", "wave", "stream", "large"])
+    ap.add_argument("cmd", choices=["sweep", "wave", "stream", "large", "ablate"])
+    ap.add_argument("--samples", default=None, help="ablate: .npz with `samples` and `occ`")
+    ap.add_argument("--scores", nargs="*", default=[], help="ablate: sweep/stream result files with exhaustive timings")
+    ap.add_argument("--cap-mode", type=int, default=0)
+    ap.add_argument("--I", type=int, default=4)
+    ap.add_argument("--p", type=int, default=10)
     ap.add_argument("--in-type", type=int, default=wt.WT_BF16)
     ap.add_argument("--out-type", type=int, default=wt.WT_OUT_BF16)
     ap.add_argument("--table", default=None)
@@ -206,9 +263,12 @@ def main(argv=None):
     ap.add_argument("--cfgs", type=lambda s: [tuple(int(x) for x in c.split(",")) for c in s.split(";")],
                     default=[(128, 128, 64, 4, 2, 0), (256, 256, 64, 8, 2, 0), (64, 64, 64, 4, 2, 0)])
     a = ap.parse_args(argv)
-    import torch
+    if a.cmd == "ablate":
+        res = cmd_ablate(a)
+    else:
+        import torch
 
-    res = {"sweep": cmd_sweep, "wave": cmd_wave, "stream": cmd_stream, "large": cmd_large}[a.cmd](a, torch)
+        res = {"sweep": cmd_sweep, "wave": cmd_wave, "stream": cmd_stream, "large": cmd_large}[a.cmd](a, torch)
     txt = json.dumps(res)
     if a.out:
         open(a.out, "w").write(txt)
