@@ -106,8 +106,9 @@ int wt_key_count(const wt_ctx* ctx, int* n);
 /* Override the recorded occupancy of structural key key_id (e.g. with a measured value). */
 int wt_key_set_occ(wt_ctx* ctx, int key_id, int occ);
 /* Wave capacity used by the wave count, the sampler and the table buckets:
- *   WT_CAP_CU_TIMES_OCC (default)  capacity = 256 CUs x resident blocks per CU of the key;
- *   WT_CAP_CU_ONLY                 capacity = 256, the paper's literal w = ceil(G / N_SM) (Sec. 3.2, 3.3).
+ *   WT_CAP_CU_ONLY (default)  capacity = 256 compute units: the paper's w = ceil(G / N_SM) (Sec. 3.2, 3.3);
+ *   WT_CAP_CU_TIMES_OCC       capacity = 256 x resident blocks per CU of the key (a "wave" = everything
+ *                             that can be resident at once).
  * Changing the mode discards a fitted table; wt_load sets the mode the table was built with. */
 typedef enum { WT_CAP_CU_TIMES_OCC = 0, WT_CAP_CU_ONLY = 1 } wt_cap_mode;
 int wt_set_capacity_mode(wt_ctx* ctx, int mode);
@@ -122,7 +123,7 @@ int wt_gemm(wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, const v
             const float* scaleA, const float* scaleB, wt_cfg cfg, void* hip_stream);
 
 /* ---- geometry (Table 2 Dense-GEMM row; Sec. 3.2 / 3.3 wave count) ------------------------ */
-/* G = ceil(M/bm)*ceil(N/bn), L = ceil(K/bk), w = ceil(G / (n_cu * occ(cfg))). */
+/* G = ceil(M/bm)*ceil(N/bn), L = ceil(K/bk), w = ceil(G / capacity) (see wt_set_capacity_mode). */
 int wt_wave_count(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, wt_cfg cfg,
                   int64_t* G, int64_t* L, int32_t* w);
 

@@ -54,7 +54,7 @@ struct wt_ctx {
     int device = -1;
     int in_type = 0, out_type = 0;
     int last_hip = 0;
-    int cap_mode = 0;  // wt_cap_mode
+    int cap_mode = WT_CAP_CU_ONLY;  // wt_cap_mode
     std::vector<wt::Config> cfgs;
     std::vector<wt::Key> keys;
     wt::Table table;

@@ -251,7 +251,7 @@ def main(argv=None):
     ap.add_argument("cmd", choices=["sweep", "wave", "stream", "large", "ablate"])
     ap.add_argument("--samples", default=None, help="ablate: .npz with `samples` and `occ`")
     ap.add_argument("--scores", nargs="*", default=[], help="ablate: sweep/stream result files with exhaustive timings")
-    ap.add_argument("--cap-mode", type=int, default=0)
+    ap.add_argument("--cap-mode", type=int, default=1)
     ap.add_argument("--I", type=int, default=4)
     ap.add_argument("--p", type=int, default=10)
     ap.add_argument("--in-type", type=int, default=wt.WT_BF16)

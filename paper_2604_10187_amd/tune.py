@@ -65,7 +65,7 @@ def main(argv=None):
     ap.add_argument("--key-first", type=int, default=0)
     ap.add_argument("--key-count", type=int, default=0)
     ap.add_argument("--max-out-elems", type=int, default=0)
-    ap.add_argument("--cap-mode", type=int, default=0, help="0: 256 x resident blocks per CU, 1: 256 (paper-literal)")
+    ap.add_argument("--cap-mode", type=int, default=1, help="1: 256 CUs (the paper's wave count), 0: 256 x resident blocks per CU")
     ap.add_argument("--model", type=int, default=0, help="0 wave-bilinear, 1 linear, 2 step")
     ap.add_argument("--samples-out", default=None)
     ap.add_argument("--fit-from", nargs="*", default=None)

@@ -234,15 +234,20 @@ def test_sweep_shapes_full_size_under_selected_config(ctx_bf16):
                        n_rows=6, n_cols=3)
 
 
-def test_wave_count_with_device_occupancy(ctx_f32):
-    """Wave counts reported by the library on the device context equal the oracle's for the
-    occupancy the HIP runtime reports (bit-exact integers)."""
+def test_wave_count_on_device_context(ctx_f32):
+    """Wave counts reported by the library on the device context equal the oracle's (bit-exact
+    integers) in both capacity modes: 256 CUs, and 256 x the occupancy the HIP runtime reports."""
     from oracle import geometry as geo
 
     for cfg, res in all_configs(ctx_f32)[::3]:
         for (M, N, K) in [(16384, 8192, 8192), (4096, 11008, 4096), (333, 4096, 11008), (1, 4096, 4096)]:
             G, L = geo.phi_gemm(M, N, K, cfg.bm, cfg.bn, cfg.bk)
-            assert wt.wt_wave_count(ctx_f32, M, N, K, cfg) == (G, L, geo.wave_count(G, geo.capacity(res.occ)))
+            assert wt.wt_wave_count(ctx_f32, M, N, K, cfg) == (G, L, geo.wave_count(G, geo.capacity(1)))
+    wt.wt_set_capacity_mode(ctx_f32, wt.WT_CAP_CU_TIMES_OCC)
+    for cfg, res in all_configs(ctx_f32)[::3]:
+        G, L = geo.phi_gemm(4096, 11008, 4096, cfg.bm, cfg.bn, cfg.bk)
+        assert wt.wt_wave_count(ctx_f32, 4096, 11008, 4096, cfg) == (G, L, geo.wave_count(G, geo.capacity(res.occ)))
+    wt.wt_set_capacity_mode(ctx_f32, wt.WT_CAP_CU_ONLY)
 
 
 def test_profile_fit_select_round_trip_on_device(ctx_bf16, tmp_path):

@@ -25,11 +25,12 @@ def ctx():
     wt.wt_destroy(c)
 
 
-def _keys(ctx):
+def _keys(ctx, occ_aware=False):
+    """Structural keys as the oracle sees them; capacity = 256 CUs (default mode) or 256 x occupancy."""
     out = []
     for i in range(0, wt.wt_config_count(ctx), 3):
         c, r = wt.wt_config_get(ctx, i)
-        out.append(ofit.KeyDesc(c.bm, c.bn, c.bk, c.nwave, c.stages, r.occ, geo.capacity(r.occ)))
+        out.append(ofit.KeyDesc(c.bm, c.bn, c.bk, c.nwave, c.stages, r.occ, geo.capacity(r.occ if occ_aware else 1)))
     return out
 
 
@@ -70,15 +71,18 @@ def test_wave_counts_bit_exact(ctx):
     shapes += [(16384, 8192, 8192), (1, 1, 8), (0, 5, 8)]
     for i in range(0, wt.wt_config_count(ctx), 3):
         c, r = wt.wt_config_get(ctx, i)
-        cap = geo.capacity(r.occ)
+        cap = geo.capacity(1)
         for (M, N, K) in shapes:
             G, L = geo.phi_gemm(M, N, K, c.bm, c.bn, c.bk)
             assert wt.wt_wave_count(ctx, M, N, K, c) == (G, L, geo.wave_count(G, cap))
-    # occupancy override moves the wave boundaries
+    # in the occupancy-aware mode an occupancy override moves the wave boundaries
     c, r = wt.wt_config_get(ctx, 0)
+    assert wt.wt_wave_count(ctx, 256 * 20, 256 * 40, 64, c)[2] == geo.wave_count(800, 256) == 4
+    wt.wt_set_capacity_mode(ctx, wt.WT_CAP_CU_TIMES_OCC)
     wt.wt_key_set_occ(ctx, 0, 3)
     assert wt.wt_wave_count(ctx, 256 * 20, 256 * 40, 64, c)[2] == geo.wave_count(800, 768) == 2
     wt.wt_key_set_occ(ctx, 0, r.occ)
+    wt.wt_set_capacity_mode(ctx, wt.WT_CAP_CU_ONLY)
 
 
 @pytest.mark.parametrize("cap", [4, 12, 132, 256, 512, 768, 1280, 2048, 250])
@@ -217,25 +221,26 @@ def test_ablation_models_parity(ctx, tmp_path, model):
         wt.wt_fit(ctx, wt.make_grid(W=W, I=I, p=p, k_anchors=K_ANCHORS, model=7), samples)
 
 
-def test_paper_literal_capacity_mode(tmp_path):
-    """Capacity = number of CUs (the paper's w = ceil(G / N_SM)): wave counts, table and lookups
-    follow the 256-tile waves; the file records the mode and wt_load restores it."""
+def test_occupancy_aware_capacity_mode(tmp_path):
+    """Capacity = 256 x resident blocks per CU: wave counts, table and lookups follow those wider waves;
+    the file records the mode and wt_load restores it."""
     c = wt.wt_create(-1, wt.WT_BF16, wt.WT_OUT_F32)
     try:
-        wt.wt_set_capacity_mode(c, wt.WT_CAP_CU_ONLY)
-        keys = [k._replace(cap=geo.N_CU) for k in _keys(c)]
+        wt.wt_set_capacity_mode(c, wt.WT_CAP_CU_TIMES_OCC)
+        keys = _keys(c, occ_aware=True)
         cfg, res = wt.wt_config_get(c, 3 * 31)          # a key with several resident blocks per CU
         assert res.occ > 1
         G, L, w = wt.wt_wave_count(c, 4096, 4096, 4096, cfg)
-        assert w == geo.wave_count(G, 256)
+        assert w == geo.wave_count(G, 256 * res.occ) < geo.wave_count(G, 256)
         W, I = 8, 4
         samples = _synthetic_samples(keys, W, I, noise_seed=3)
         wt.wt_fit(c, wt.make_grid(W=W, I=I, p=3, k_anchors=K_ANCHORS), samples)
-        path = str(tmp_path / "lit.wt")
+        path = str(tmp_path / "occ.wt")
         wt.wt_save(c, path)
         table, meta = osel.read_table(path)
-        assert meta["key_mode"] == 1 and table.keys == keys
+        assert meta["key_mode"] == 0 and table.keys == keys
         c2 = wt.wt_create(-1, wt.WT_BF16, wt.WT_OUT_F32)
+        assert wt.wt_wave_count(c2, 4096, 4096, 4096, cfg)[2] == geo.wave_count(G, 256)
         wt.wt_load(c2, path)
         assert wt.wt_wave_count(c2, 4096, 4096, 4096, cfg)[2] == w
         for (M, N, K) in wt_synth.sweep_shapes() + wt_synth.stream_shapes(500):
@@ -244,7 +249,7 @@ def test_paper_literal_capacity_mode(tmp_path):
                 s = wt.wt_select(cc, M, N, K)
                 assert s.id == 3 * key + micro and wt.wt_predict_us(cc, M, N, K, s) == t
         wt.wt_destroy(c2)
-        wt.wt_set_capacity_mode(c, wt.WT_CAP_CU_TIMES_OCC)       # switching discards the table
+        wt.wt_set_capacity_mode(c, wt.WT_CAP_CU_ONLY)       # switching discards the table
         with pytest.raises(wt.WtError):
             wt.wt_select(c, 64, 64, 64)
     finally:
