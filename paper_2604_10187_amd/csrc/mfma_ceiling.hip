@@ -56,26 +56,13 @@ __global__ __launch_bounds__(256) void mfma_ceiling_kernel(int iters, float* sin
                 a[i][q] = (int)((mix(seed + 13u * i + q) & 0x8F8F8F8Fu) | 0x30303030u);
                 b[i][q] = (int)((mix(seed + 131u * i + q + 5u) & 0x8F8F8F8Fu) | 0x30303030u);
             }
-        f32x4 acc4[4][4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) acc4[i][j][e] = 0.0f;
         for (int it = 0; it < iters; ++it) {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    acc4[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[i], b[j], acc4[i][j], 0, 0, 0, 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i][j], 0, 0, 0, 0, 0, 0);
         }
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) acc[i][j][e] = acc4[i][j][e];
     }
     float s = 0.0f;
 #pragma unroll
@@ -114,8 +101,9 @@ extern "C" int wt_mfma_ceiling(wt_ctx* ctx, int in_type, int iters, void* hip_st
     float ms = 0;
     if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
     if (e != hipSuccess) { ctx->last_hip = (int)e; return WT_ERR_HIP; }
-    // flops per MFMA: bf16 32x32x16 = 2*32*32*16; fp8 16x16x128 = 2*16*16*128 (both 32768)
-    const double flops = (double)blocks * 4.0 * (double)iters * 16.0 * 32768.0;
+    // flops per MFMA: bf16 32x32x16 = 2*32*32*16 = 32768; fp8 32x32x64 = 2*32*32*64 = 131072
+    const double per_mfma = in_type == WT_BF16 ? 32768.0 : 131072.0;
+    const double flops = (double)blocks * 4.0 * (double)iters * 16.0 * per_mfma;
     *tflops = flops / ((double)ms * 1e-3) / 1e12;
     return WT_OK;
 }

@@ -123,14 +123,26 @@ def cmd_stream(a, torch):
     ctx, path = _open_ctx(a, torch)
     shapes = wt_synth.stream_shapes()
     mean_ns, p99_ns = wt.wt_select_bench(ctx, shapes, repeats=5)
-    uniq = sorted(set(shapes))
+    # exhaustive search on a seeded sample of the stream's draws (duplicates collapse into weights, so
+    # the score is weighted the way the stream itself weights shapes)
     rng = np.random.default_rng(2005)
-    sample = [uniq[i] for i in sorted(rng.choice(len(uniq), size=min(a.sample, len(uniq)), replace=False))]
+    draws = [shapes[i] for i in rng.choice(len(shapes), size=min(a.sample, len(shapes)), replace=False)]
+    weight = {}
+    for sh in draws:
+        weight[sh] = weight.get(sh, 0) + 1
+    sample = sorted(weight)
     ex = Exhaustive(ctx, torch, a.in_type, a.out_type, prune=a.prune)
     rows, summary = _pick_vs_best(ctx, ex, sample)
-    summary.update({"stream_shapes": len(shapes), "unique_shapes": len(uniq), "exhaustive_sample": len(sample),
+    wts = np.array([weight[(r["M"], r["N"], r["K"])] for r in rows], dtype=float)
+    fr = np.array([r["frac"] for r in rows])
+    for r, w in zip(rows, wts):
+        r["weight"] = int(w)
+    summary.update({"stream_shapes": len(shapes), "unique_shapes": len(set(shapes)), "sampled_draws": len(draws),
+                    "exhaustive_shapes": len(sample),
+                    "weighted_geomean_frac": float(np.exp(np.sum(wts * np.log(fr)) / wts.sum())),
+                    "weighted_frac_ge_95": float(np.sum(wts * (fr >= 0.95)) / wts.sum()),
                     "select_mean_us": mean_ns / 1e3, "select_p99_us": p99_ns / 1e3})
-    return {"workload": "runtime stream: 10,000 seeded shapes; exhaustive search on a seeded sample of the unique shapes",
+    return {"workload": "runtime stream: 10,000 seeded shapes; exhaustive search on a seeded sample of its draws",
             "table": path, "summary": summary, "rows": rows}
 
 
@@ -258,7 +270,7 @@ def main(argv=None):
     ap.add_argument("--out-type", type=int, default=wt.WT_OUT_BF16)
     ap.add_argument("--table", default=None)
     ap.add_argument("--out", default=None)
-    ap.add_argument("--sample", type=int, default=300)
+    ap.add_argument("--sample", type=int, default=400)
     ap.add_argument("--prune", type=float, default=2.5)
     ap.add_argument("--cfgs", type=lambda s: [tuple(int(x) for x in c.split(",")) for c in s.split(";")],
                     default=[(128, 128, 64, 4, 2, 0), (256, 256, 64, 8, 2, 0), (64, 64, 64, 4, 2, 0)])
