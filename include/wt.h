@@ -63,7 +63,7 @@ typedef struct {
     int32_t key_id, micro_id;
     int64_t G, L;
     int32_t w;
-    int32_t reserved;
+    int32_t family; /* 0: near-square grid (the paper's sampler); 1: single tile row (see wt_grid.W_row) */
     double mean_us;
 } wt_sample;
 
@@ -80,7 +80,11 @@ typedef struct {
     int32_t key_first, key_count;
     int64_t max_out_elems;
     int32_t model;    /* wt_model: which latency model wt_fit builds (0 = the paper's) */
-    int32_t reserved;
+    int32_t W_row;    /* extension, 0 = off (the paper's method): also profile and fit W_row waves of
+                       * single-tile-row grids (m_G = 1, n_G = top of each sub-interval; M = bm), kept in
+                       * a second set of buckets that wt_select consults for shapes with M <= bm.  The
+                       * paper's sampler stays near-square (tau) and its test shapes have M >= 64; these
+                       * grids cover the decode-like shapes whose B operand is streamed once from HBM. */
 } wt_grid;
 
 /* Latency models wt_fit can build into the dual table.  WAVE_BILINEAR is the method (Sec. 4.3);

@@ -75,6 +75,19 @@ def sample_set(cap: int, W: int, I: int, tau_num: int = 11, tau_den: int = 10) -
     return out
 
 
+def row_sample_set(cap: int, W_row: int, I: int) -> list[GridSample]:
+    """Extension beyond the paper (its sampler keeps to near-square grids and its test shapes have
+    M >= 64): grids of a single tile row, m_G = 1, n_G = g, for shapes with M <= T_M whose B operand
+    is streamed once and never reused.  The same wave regions and sub-intervals are used (Sec. 4.2);
+    every g factors as 1 x g, so the representative of a sub-interval is its upper end."""
+    out = []
+    for w in range(1, W_row + 1):
+        for i in range(1, I + 1):
+            a, b = sub_interval(w, i, cap, I)
+            out.append(GridSample(w, i, b, 1, b) if b >= a else GridSample(w, i, 0, 0, 0))
+    return out
+
+
 def instantiate(m: int, n: int, L: int, BM: int, BN: int, BK: int) -> tuple[int, int, int]:
     """Sec. 4.2, workload instantiation: M = m_G*T_M, N = n_G*T_N, K = L*T_K."""
     return m * BM, n * BN, L * BK

@@ -23,9 +23,16 @@ def predict(theta, G: int, L: int) -> float:
     return ((a * float(G * L) + b * float(G)) + c * float(L)) + d
 
 
-def bucket_for(table: DualTable, key: int, w: int):
+def bucket_for(table: DualTable, key: int, w: int, fam: int = 0):
     """Sec. 4.5 rule: wave-local coefficients when w <= W (and that bucket was fitted), the
-    extrapolation tuple otherwise.  Returns the Bucket or None when the key has no model."""
+    extrapolation tuple otherwise.  Returns the Bucket or None when the key has no model.
+    fam = 1 looks in the single-tile-row family first (extension) and falls back to the paper's
+    near-square buckets when that family has nothing for the key."""
+    if fam == 1 and table.W_row > 0:
+        if 1 <= w <= table.W_row and table.row_local[key][w - 1].status:
+            return table.row_local[key][w - 1]
+        if table.row_ext[key].status:
+            return table.row_ext[key]
     if 1 <= w <= table.W:
         b = table.local[key][w - 1]
         if b.status:
@@ -51,7 +58,7 @@ def select(table: DualTable, M: int, N: int, K: int):
     for k, kd in enumerate(table.keys):
         G, L = phi_gemm(M, N, K, kd.bm, kd.bn, kd.bk)
         w = wave_count(G, kd.cap)
-        b = bucket_for(table, k, w)
+        b = bucket_for(table, k, w, 1 if M <= kd.bm else 0)     # one tile row <=> M <= T_M
         if b is None:
             continue
         t = predict(b.theta, G, L)
@@ -73,35 +80,48 @@ MAGIC = b"WTDT"
 def read_table(path: str) -> tuple[DualTable, dict]:
     """Parse the flat little-endian dual-table file.
 
-    Header, 16 uint32: magic 'WTDT', version (1), n_keys, W, I, p, tau_num, tau_den, n_cu,
-    A (anchor slots per bucket), in_type, out_type, key_mode, 3 reserved.
-    Then per key: 8 int32 (bm, bn, bk, nwave, stages, occ, n_micro, reserved), int64 cap,
-    (W+1)*4 float64 theta (rows w=1..W, then ext), (W+1) int32 status, (W+1) int32 n_anchor,
-    (W+1)*A int32 anchor L, (W+1)*A int32 anchor micro.
+    Header, 16 uint32: magic 'WTDT', version (1 or 2), n_keys, W, I, p, tau_num, tau_den, n_cu,
+    A (anchor slots per bucket), in_type, out_type, key_mode, W_row (version 2, else 0), 2 reserved.
+    Then per key: 8 int32 (bm, bn, bk, nwave, stages, occ, n_micro, reserved), int64 cap, and a
+    bucket block of R = W+1 rows (w = 1..W, then ext): R*4 float64 theta, R int32 status, R int32
+    n_anchor, R*A int32 anchor L, R*A int32 anchor micro.  Version 2 appends a second block of
+    W_row+1 rows per key for the single-tile-row family.
     """
     raw = open(path, "rb").read()
     hdr = struct.unpack_from("<4s15I", raw, 0)
-    if hdr[0] != MAGIC or hdr[1] != 1:
-        raise ValueError("not a version-1 dual table")
+    if hdr[0] != MAGIC or hdr[1] not in (1, 2):
+        raise ValueError("not a version-1/2 dual table")
     n_keys, W, I, p, tnum, tden, n_cu, A, in_t, out_t, mode = hdr[2:13]
+    W_row = hdr[13] if hdr[1] == 2 else 0
     off = 64
-    keys, local, ext = [], [], []
+
+    def block(R):
+        nonlocal off
+        theta = np.frombuffer(raw, dtype="<f8", count=R * 4, offset=off).reshape(R, 4); off += R * 32
+        status = np.frombuffer(raw, dtype="<i4", count=R, offset=off); off += R * 4
+        n_anchor = np.frombuffer(raw, dtype="<i4", count=R, offset=off); off += R * 4
+        aL = np.frombuffer(raw, dtype="<i4", count=R * A, offset=off).reshape(R, A); off += R * A * 4
+        aM = np.frombuffer(raw, dtype="<i4", count=R * A, offset=off).reshape(R, A); off += R * A * 4
+        out = []
+        for r in range(R):
+            anchors = [(int(aL[r, j]), int(aM[r, j])) for j in range(int(n_anchor[r]))]
+            out.append(Bucket(theta=tuple(float(x) for x in theta[r]), status=int(status[r]), anchors=anchors))
+        return out
+
+    keys, local, ext, row_local, row_ext = [], [], [], [], []
     for _ in range(n_keys):
         bm, bn, bk, nwave, stages, occ, n_micro, _r = struct.unpack_from("<8i", raw, off); off += 32
         (cap,) = struct.unpack_from("<q", raw, off); off += 8
-        theta = np.frombuffer(raw, dtype="<f8", count=(W + 1) * 4, offset=off).reshape(W + 1, 4); off += (W + 1) * 32
-        status = np.frombuffer(raw, dtype="<i4", count=W + 1, offset=off); off += (W + 1) * 4
-        n_anchor = np.frombuffer(raw, dtype="<i4", count=W + 1, offset=off); off += (W + 1) * 4
-        aL = np.frombuffer(raw, dtype="<i4", count=(W + 1) * A, offset=off).reshape(W + 1, A); off += (W + 1) * A * 4
-        aM = np.frombuffer(raw, dtype="<i4", count=(W + 1) * A, offset=off).reshape(W + 1, A); off += (W + 1) * A * 4
         keys.append(KeyDesc(bm, bn, bk, nwave, stages, occ, cap))
-        buckets = []
-        for r in range(W + 1):
-            anchors = [(int(aL[r, j]), int(aM[r, j])) for j in range(int(n_anchor[r]))]
-            buckets.append(Bucket(theta=tuple(float(x) for x in theta[r]), status=int(status[r]), anchors=anchors))
+        buckets = block(W + 1)
         local.append(buckets[:W])
         ext.append(buckets[W])
+        if W_row > 0:
+            buckets = block(W_row + 1)
+            row_local.append(buckets[:W_row])
+            row_ext.append(buckets[W_row])
     if off != len(raw):
         raise ValueError("trailing bytes in dual table")
-    meta = dict(I=I, p=p, tau_num=tnum, tau_den=tden, n_cu=n_cu, A=A, in_type=in_t, out_type=out_t, key_mode=mode)
-    return DualTable(W=W, keys=keys, local=local, ext=ext), meta
+    meta = dict(I=I, p=p, tau_num=tnum, tau_den=tden, n_cu=n_cu, A=A, in_type=in_t, out_type=out_t, key_mode=mode,
+                W_row=W_row)
+    return DualTable(W=W, keys=keys, local=local, ext=ext, W_row=W_row, row_local=row_local, row_ext=row_ext), meta

@@ -39,11 +39,11 @@ class wt_cfg_res(C.Structure):
 
 class wt_sample(C.Structure):
     _fields_ = [("key_id", C.c_int32), ("micro_id", C.c_int32), ("G", C.c_int64), ("L", C.c_int64),
-                ("w", C.c_int32), ("reserved", C.c_int32), ("mean_us", C.c_double)]
+                ("w", C.c_int32), ("family", C.c_int32), ("mean_us", C.c_double)]
 
 
 SAMPLE_DTYPE = np.dtype([("key_id", "<i4"), ("micro_id", "<i4"), ("G", "<i8"), ("L", "<i8"),
-                         ("w", "<i4"), ("reserved", "<i4"), ("mean_us", "<f8")])
+                         ("w", "<i4"), ("family", "<i4"), ("mean_us", "<f8")])
 assert SAMPLE_DTYPE.itemsize == C.sizeof(wt_sample)
 
 
@@ -52,7 +52,7 @@ class wt_grid(C.Structure):
                 ("p", C.c_int32), ("n_k_anchors", C.c_int32), ("k_anchors", C.POINTER(C.c_int32)),
                 ("warmup", C.c_int32), ("iters", C.c_int32), ("key_first", C.c_int32),
                 ("key_count", C.c_int32), ("max_out_elems", C.c_int64), ("model", C.c_int32),
-                ("reserved", C.c_int32)]
+                ("W_row", C.c_int32)]
 
 
 class WtError(RuntimeError):
@@ -141,10 +141,10 @@ def _stream(stream):
 
 
 def make_grid(W=40, I=4, tau=(11, 10), p=10, k_anchors=(1024, 2048, 3072, 4096, 5120), warmup=3, iters=5,
-              key_first=0, key_count=0, max_out_elems=0, model=0):
+              key_first=0, key_count=0, max_out_elems=0, model=0, W_row=0):
     arr = (C.c_int32 * len(k_anchors))(*k_anchors)
     g = wt_grid(W, I, tau[0], tau[1], p, len(k_anchors), C.cast(arr, C.POINTER(C.c_int32)), warmup, iters,
-                key_first, key_count, max_out_elems, model, 0)
+                key_first, key_count, max_out_elems, model, W_row)
     g._keep = arr  # keep the anchor array alive with the struct
     return g
 

@@ -98,14 +98,16 @@ bool key_in_slice(const wt_grid* g, int k, int nk) {
 
 int check_grid(const wt_grid* g) {
     if (!g || g->W < 1 || g->I < 1 || g->tau_den < 1 || g->tau_num < g->tau_den || g->p < 1 || g->n_k_anchors < 1 ||
-        !g->k_anchors || g->warmup < 0 || g->iters < 1)
+        !g->k_anchors || g->warmup < 0 || g->iters < 1 || g->W_row < 0)
         return WT_ERR_INVALID_ARG;
     for (int j = 0; j < g->n_k_anchors; ++j)
         if (g->k_anchors[j] < 1) return WT_ERR_INVALID_ARG;
     return WT_OK;
 }
 
-// Walk the sampling plan; fn(key, point, L, M, N, K) is called for every workload that will be timed.
+// Walk the sampling plan; fn(key, point, w, family, L, M, N, K) is called for every workload that will be
+// timed: the paper's near-square grids (family 0), then, when grid->W_row > 0, single-tile-row grids
+// 1 x g with g the top of each sub-interval (family 1).
 template <typename F>
 int walk_plan(const wt_ctx* ctx, const wt_grid* grid, F&& fn) {
     const int nk = (int)ctx->keys.size();
@@ -124,8 +126,23 @@ int walk_plan(const wt_ctx* ctx, const wt_grid* grid, F&& fn) {
             if (grid->max_out_elems > 0 && M * N > grid->max_out_elems) continue;
             const int w = (int)(s / (size_t)grid->I) + 1;
             for (int64_t L : anchors) {
-                const int rc = fn(k, pts[s], w, L, M, N, L * key.bk);
+                const int rc = fn(k, pts[s], w, 0, L, M, N, L * key.bk);
                 if (rc != WT_OK) return rc;
+            }
+        }
+        for (int w = 1; w <= grid->W_row; ++w) {
+            for (int i = 1; i <= grid->I; ++i) {
+                const int64_t lo = (int64_t)(w - 1) * key.cap + 1;
+                const int64_t a = lo + ((int64_t)(i - 1) * key.cap) / grid->I;
+                const int64_t b = lo - 1 + ((int64_t)i * key.cap) / grid->I;
+                if (b < a) continue;
+                const GridPoint pt{b, 1, b};
+                const int64_t M = key.bm, N = b * key.bn;
+                if (grid->max_out_elems > 0 && M * N > grid->max_out_elems) continue;
+                for (int64_t L : anchors) {
+                    const int rc = fn(k, pt, w, 1, L, M, N, L * key.bk);
+                    if (rc != WT_OK) return rc;
+                }
             }
         }
     }
@@ -213,7 +230,7 @@ int wt_sample_plan(const wt_ctx* ctx, const wt_grid* grid, size_t* n_samples, si
     if (rc != WT_OK) return rc;
     Plan p;
     const size_t esz = ctx->in_type == WT_BF16 ? 2 : 1, osz = ctx->out_type == WT_OUT_F32 ? 4 : 2;
-    rc = walk_plan(ctx, grid, [&](int k, const GridPoint&, int, int64_t, int64_t M, int64_t N, int64_t K) {
+    rc = walk_plan(ctx, grid, [&](int k, const GridPoint&, int, int, int64_t, int64_t M, int64_t N, int64_t K) {
         p.n_samples += (size_t)ctx->keys[k].n_micro;
         p.bytesA = std::max(p.bytesA, (size_t)(M * K) * esz);
         p.bytesB = std::max(p.bytesB, (size_t)(N * K) * esz);
@@ -242,7 +259,7 @@ int wt_profile_sparse(wt_ctx* ctx, const wt_grid* grid, void* scrA, void* scrB, 
     const float* sA = (const float*)scrB;
     const float* sB = (const float*)scrB;
     size_t n = 0;
-    rc = walk_plan(ctx, grid, [&](int k, const GridPoint& pt, int w, int64_t L, int64_t M, int64_t N, int64_t K) {
+    rc = walk_plan(ctx, grid, [&](int k, const GridPoint& pt, int w, int family, int64_t L, int64_t M, int64_t N, int64_t K) {
         const Key& key = ctx->keys[k];
         for (int m = 0; m < key.n_micro; ++m) {
             const Config& c = ctx->cfgs[key.first_cfg + m];
@@ -252,7 +269,7 @@ int wt_profile_sparse(wt_ctx* ctx, const wt_grid* grid, void* scrA, void* scrB, 
             if (r != WT_OK) return r;
             wt_sample s;
             memset(&s, 0, sizeof(s));
-            s.key_id = k; s.micro_id = m; s.G = pt.g; s.L = L; s.w = w; s.mean_us = us;
+            s.key_id = k; s.micro_id = m; s.G = pt.g; s.L = L; s.w = w; s.family = family; s.mean_us = us;
             out[n++] = s;
         }
         return (int)WT_OK;

@@ -339,23 +339,23 @@ static void fit_step(std::vector<const wt_sample*>& recs, int64_t cap, double* a
     }
 }
 
-static int fit_table(wt_ctx* ctx, const wt_grid* grid, const wt_sample* s, size_t n) {
-    const int W = grid->W, nk = static_cast<int>(ctx->keys.size());
-    if (W < 1 || grid->p < 1) return WT_ERR_INVALID_ARG;
-    if (grid->model < WT_MODEL_WAVE_BILINEAR || grid->model > WT_MODEL_STEP) return WT_ERR_INVALID_ARG;
-    Table t;
-    t.W = W; t.I = grid->I; t.p = grid->p; t.tau_num = grid->tau_num; t.tau_den = grid->tau_den;
-    t.buckets.assign(static_cast<size_t>(nk) * (W + 1), Bucket{});
+// Buckets of one sample family: wave buckets 1..W plus the extrapolation entry from the last p waves,
+// laid out as out[key * (W + 1) + (w - 1)] with the extrapolation entry last.
+static int fit_family(const wt_ctx* ctx, int family, int model, int W, int p, const wt_sample* s, size_t n,
+                      std::vector<Bucket>& out) {
+    const int nk = static_cast<int>(ctx->keys.size());
+    out.assign(static_cast<size_t>(nk) * (W + 1), Bucket{});
     std::vector<std::vector<const wt_sample*>> by(static_cast<size_t>(nk) * W);
     for (size_t i = 0; i < n; ++i) {
         if (s[i].key_id < 0 || s[i].key_id >= nk) return WT_ERR_INVALID_ARG;
-        if (s[i].w < 1 || s[i].w > W) continue;
+        if (s[i].family != family || s[i].w < 1 || s[i].w > W) continue;
         by[static_cast<size_t>(s[i].key_id) * W + (s[i].w - 1)].push_back(&s[i]);
     }
-    const int first_ext = grid->model == WT_MODEL_LINEAR ? 1 : std::max(1, W - grid->p + 1);
+    const int first_ext = model == WT_MODEL_LINEAR ? 1 : std::max(1, W - p + 1);
     for (int k = 0; k < nk; ++k) {
+        Bucket* kb = &out[static_cast<size_t>(k) * (W + 1)];
         std::vector<const wt_sample*> merged;
-        if (grid->model == WT_MODEL_STEP) {
+        if (model == WT_MODEL_STEP) {
             for (int w = 1; w <= W; ++w) {
                 std::vector<const wt_sample*>& recs = by[static_cast<size_t>(k) * W + (w - 1)];
                 merged.insert(merged.end(), recs.begin(), recs.end());
@@ -365,12 +365,12 @@ static int fit_table(wt_ctx* ctx, const wt_grid* grid, const wt_sample* s, size_
             const bool ok = !merged.empty();
             fit_step(merged, ctx->keys[k].cap, &a, &b, anchors);
             for (int w = 1; w <= W; ++w) {
-                Bucket& bk = t.buckets[static_cast<size_t>(k) * (W + 1) + (w - 1)];
+                Bucket& bk = kb[w - 1];
                 bk = anchors;
                 bk.th[0] = 0; bk.th[1] = 0; bk.th[2] = a * w; bk.th[3] = b * w;
                 bk.status = ok ? 0xC : 0;
             }
-            Bucket& ex = t.buckets[static_cast<size_t>(k) * (W + 1) + W];
+            Bucket& ex = kb[W];
             ex = anchors;
             const double cap = static_cast<double>(ctx->keys[k].cap);
             ex.th[0] = a / cap; ex.th[1] = b / cap; ex.th[2] = 0; ex.th[3] = 0;
@@ -380,10 +380,25 @@ static int fit_table(wt_ctx* ctx, const wt_grid* grid, const wt_sample* s, size_
         for (int w = 1; w <= W; ++w) {
             std::vector<const wt_sample*>& recs = by[static_cast<size_t>(k) * W + (w - 1)];
             if (w >= first_ext) merged.insert(merged.end(), recs.begin(), recs.end());
-            if (grid->model == WT_MODEL_WAVE_BILINEAR)
-                fit_bucket(recs, t.buckets[static_cast<size_t>(k) * (W + 1) + (w - 1)]);
+            if (model == WT_MODEL_WAVE_BILINEAR) fit_bucket(recs, kb[w - 1]);
         }
-        fit_bucket(merged, t.buckets[static_cast<size_t>(k) * (W + 1) + W]);
+        fit_bucket(merged, kb[W]);
+    }
+    return WT_OK;
+}
+
+static int fit_table(wt_ctx* ctx, const wt_grid* grid, const wt_sample* s, size_t n) {
+    const int W = grid->W;
+    if (W < 1 || grid->p < 1 || grid->W_row < 0 || grid->W_row > 4096) return WT_ERR_INVALID_ARG;
+    if (grid->model < WT_MODEL_WAVE_BILINEAR || grid->model > WT_MODEL_STEP) return WT_ERR_INVALID_ARG;
+    Table t;
+    t.W = W; t.I = grid->I; t.p = grid->p; t.tau_num = grid->tau_num; t.tau_den = grid->tau_den;
+    int rc = fit_family(ctx, 0, grid->model, W, grid->p, s, n, t.buckets);
+    if (rc != WT_OK) return rc;
+    if (grid->W_row > 0) {  // the single-tile-row family always uses the wave-bucketed bilinear model
+        t.W_row = grid->W_row;
+        rc = fit_family(ctx, 1, WT_MODEL_WAVE_BILINEAR, t.W_row, std::min(grid->p, t.W_row), s, n, t.row_buckets);
+        if (rc != WT_OK) return rc;
     }
     t.fitted = true;
     ctx->table = std::move(t);
@@ -391,7 +406,12 @@ static int fit_table(wt_ctx* ctx, const wt_grid* grid, const wt_sample* s, size_
 }
 
 // ---- two-stage selection (Sec. 4.4, 4.5) -------------------------------------------------------
-static inline const Bucket* pick_bucket(const Table& t, int key, int64_t w) {
+static inline const Bucket* pick_bucket(const Table& t, int key, int64_t w, bool one_row) {
+    if (one_row && t.W_row > 0) {  // M <= bm: single-tile-row buckets first, the paper's as fallback
+        const Bucket* rb = &t.row_buckets[static_cast<size_t>(key) * (t.W_row + 1)];
+        if (w >= 1 && w <= t.W_row && rb[w - 1].status) return &rb[w - 1];
+        if (rb[t.W_row].status) return &rb[t.W_row];
+    }
     const Bucket* base = &t.buckets[static_cast<size_t>(key) * (t.W + 1)];
     if (w >= 1 && w <= t.W && base[w - 1].status) return &base[w - 1];
     return base[t.W].status ? &base[t.W] : nullptr;
@@ -424,7 +444,7 @@ static int select_impl(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, int* 
         const int64_t G = gm * gn;
         const int64_t L = (K + key.bk - 1) >> key.sh_k;
         const int64_t w = (G + key.cap - 1) / key.cap;
-        const Bucket* b = pick_bucket(t, k, w);
+        const Bucket* b = pick_bucket(t, k, w, M <= key.bm);
         if (!b) continue;
         const double th = predict(b->th, G, L);
         if (th != th) continue;
@@ -452,11 +472,34 @@ static int select_impl(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, int* 
 }
 
 // ---- table file ------------------------------------------------------------------------------------
-// Little-endian.  Header: 16 uint32 = 'WTDT', version 1, n_keys, W, I, p, tau_num, tau_den, n_cu,
-// anchor slots A, in_type, out_type, key_mode (capacity mode), 3 reserved.  Per key: 8 int32 (bm, bn, bk, nwave,
-// stages, occ, n_micro, 0), int64 cap (256*occ, or 256 when key_mode = 1), (W+1)*4 float64 theta (w = 1..W then ext), (W+1) int32
-// status, (W+1) int32 n_anchor, (W+1)*A int32 anchor L, (W+1)*A int32 anchor micro.
+// Little-endian.  Header: 16 uint32 = 'WTDT', version (1, or 2 when the single-tile-row family is
+// present), n_keys, W, I, p, tau_num, tau_den, n_cu, anchor slots A, in_type, out_type, key_mode
+// (capacity mode), W_row (version 2), 2 reserved.  Per key: 8 int32 (bm, bn, bk, nwave, stages, occ,
+// n_micro, 0), int64 cap (256, or 256*occ when key_mode = 0), then a bucket block of R = W+1 rows
+// (w = 1..W then ext): R*4 float64 theta, R int32 status, R int32 n_anchor, R*A int32 anchor L,
+// R*A int32 anchor micro; version 2 appends a block of W_row+1 rows for the single-tile-row family.
 static const uint32_t kMagic = 0x54445457u;  // "WTDT"
+
+static bool write_block(FILE* f, const Bucket* b, int R) {
+    bool ok = true;
+    for (int r = 0; ok && r < R; ++r) ok = fwrite(b[r].th, sizeof(double), 4, f) == 4;
+    for (int r = 0; ok && r < R; ++r) ok = fwrite(&b[r].status, sizeof(int32_t), 1, f) == 1;
+    for (int r = 0; ok && r < R; ++r) ok = fwrite(&b[r].n_anchor, sizeof(int32_t), 1, f) == 1;
+    for (int r = 0; ok && r < R; ++r) ok = fwrite(b[r].anchor_L, sizeof(int32_t), kMaxAnchors, f) == kMaxAnchors;
+    for (int r = 0; ok && r < R; ++r) ok = fwrite(b[r].anchor_micro, sizeof(int32_t), kMaxAnchors, f) == kMaxAnchors;
+    return ok;
+}
+
+static bool read_block(FILE* f, Bucket* b, int R) {
+    bool ok = true;
+    for (int r = 0; ok && r < R; ++r) ok = fread(b[r].th, sizeof(double), 4, f) == 4;
+    for (int r = 0; ok && r < R; ++r) ok = fread(&b[r].status, sizeof(int32_t), 1, f) == 1;
+    for (int r = 0; ok && r < R; ++r) ok = fread(&b[r].n_anchor, sizeof(int32_t), 1, f) == 1;
+    for (int r = 0; ok && r < R; ++r) ok = fread(b[r].anchor_L, sizeof(int32_t), kMaxAnchors, f) == kMaxAnchors;
+    for (int r = 0; ok && r < R; ++r) ok = fread(b[r].anchor_micro, sizeof(int32_t), kMaxAnchors, f) == kMaxAnchors;
+    for (int r = 0; ok && r < R; ++r) ok = b[r].n_anchor >= 0 && b[r].n_anchor <= kMaxAnchors;
+    return ok;
+}
 
 static int save_table(const wt_ctx* ctx, const char* path) {
     const Table& t = ctx->table;
@@ -464,11 +507,12 @@ static int save_table(const wt_ctx* ctx, const char* path) {
     FILE* f = fopen(path, "wb");
     if (!f) return WT_ERR_IO;
     const uint32_t nk = static_cast<uint32_t>(ctx->keys.size());
-    const uint32_t hdr[16] = {kMagic, 1u, nk, static_cast<uint32_t>(t.W), static_cast<uint32_t>(t.I),
+    const uint32_t hdr[16] = {kMagic, t.W_row > 0 ? 2u : 1u, nk, static_cast<uint32_t>(t.W), static_cast<uint32_t>(t.I),
                               static_cast<uint32_t>(t.p), static_cast<uint32_t>(t.tau_num),
                               static_cast<uint32_t>(t.tau_den), static_cast<uint32_t>(kNumCU),
                               static_cast<uint32_t>(kMaxAnchors), static_cast<uint32_t>(ctx->in_type),
-                              static_cast<uint32_t>(ctx->out_type), static_cast<uint32_t>(ctx->cap_mode), 0u, 0u, 0u};
+                              static_cast<uint32_t>(ctx->out_type), static_cast<uint32_t>(ctx->cap_mode),
+                              static_cast<uint32_t>(t.W_row), 0u, 0u};
     bool ok = fwrite(hdr, sizeof(hdr), 1, f) == 1;
     const int R = t.W + 1;
     for (uint32_t k = 0; ok && k < nk; ++k) {
@@ -476,12 +520,8 @@ static int save_table(const wt_ctx* ctx, const char* path) {
         const int32_t kd[8] = {key.bm, key.bn, key.bk, key.nwave, key.stages, key.occ, key.n_micro, 0};
         ok = ok && fwrite(kd, sizeof(kd), 1, f) == 1;
         ok = ok && fwrite(&key.cap, sizeof(int64_t), 1, f) == 1;
-        const Bucket* b = &t.buckets[static_cast<size_t>(k) * R];
-        for (int r = 0; ok && r < R; ++r) ok = fwrite(b[r].th, sizeof(double), 4, f) == 4;
-        for (int r = 0; ok && r < R; ++r) ok = fwrite(&b[r].status, sizeof(int32_t), 1, f) == 1;
-        for (int r = 0; ok && r < R; ++r) ok = fwrite(&b[r].n_anchor, sizeof(int32_t), 1, f) == 1;
-        for (int r = 0; ok && r < R; ++r) ok = fwrite(b[r].anchor_L, sizeof(int32_t), kMaxAnchors, f) == kMaxAnchors;
-        for (int r = 0; ok && r < R; ++r) ok = fwrite(b[r].anchor_micro, sizeof(int32_t), kMaxAnchors, f) == kMaxAnchors;
+        ok = ok && write_block(f, &t.buckets[static_cast<size_t>(k) * R], R);
+        if (t.W_row > 0) ok = ok && write_block(f, &t.row_buckets[static_cast<size_t>(k) * (t.W_row + 1)], t.W_row + 1);
     }
     ok = (fclose(f) == 0) && ok;
     return ok ? WT_OK : WT_ERR_IO;
@@ -494,7 +534,9 @@ static int load_table(wt_ctx* ctx, const char* path) {
     int rc = WT_OK;
     Table t;
     std::vector<int> occs;
-    if (fread(hdr, sizeof(hdr), 1, f) != 1 || hdr[0] != kMagic || hdr[1] != 1u) rc = WT_ERR_IO;
+    if (fread(hdr, sizeof(hdr), 1, f) != 1 || hdr[0] != kMagic || (hdr[1] != 1u && hdr[1] != 2u)) rc = WT_ERR_IO;
+    if (rc == WT_OK && hdr[1] == 1u) hdr[13] = 0;
+    if (rc == WT_OK && hdr[13] > 4096u) rc = WT_ERR_INVALID_ARG;
     if (rc == WT_OK && (hdr[2] != ctx->keys.size() || hdr[9] != static_cast<uint32_t>(kMaxAnchors) ||
                         hdr[10] != static_cast<uint32_t>(ctx->in_type) || hdr[3] < 1 || hdr[3] > 4096 || hdr[12] > 1u))
         rc = WT_ERR_INVALID_ARG;  // table was built for another registry
@@ -502,7 +544,9 @@ static int load_table(wt_ctx* ctx, const char* path) {
         t.W = static_cast<int>(hdr[3]); t.I = static_cast<int>(hdr[4]); t.p = static_cast<int>(hdr[5]);
         t.tau_num = static_cast<int>(hdr[6]); t.tau_den = static_cast<int>(hdr[7]);
         const int R = t.W + 1;
+        t.W_row = static_cast<int>(hdr[13]);
         t.buckets.assign(ctx->keys.size() * R, Bucket{});
+        if (t.W_row > 0) t.row_buckets.assign(ctx->keys.size() * (t.W_row + 1), Bucket{});
         for (size_t k = 0; rc == WT_OK && k < ctx->keys.size(); ++k) {
             int32_t kd[8];
             int64_t cap;
@@ -511,14 +555,8 @@ static int load_table(wt_ctx* ctx, const char* path) {
             if (kd[0] != key.bm || kd[1] != key.bn || kd[2] != key.bk || kd[3] != key.nwave || kd[4] != key.stages ||
                 kd[5] < 1 || cap != key_capacity(static_cast<int>(hdr[12]), kd[5])) { rc = WT_ERR_INVALID_ARG; break; }
             occs.push_back(kd[5]);
-            Bucket* b = &t.buckets[k * R];
-            bool ok = true;
-            for (int r = 0; ok && r < R; ++r) ok = fread(b[r].th, sizeof(double), 4, f) == 4;
-            for (int r = 0; ok && r < R; ++r) ok = fread(&b[r].status, sizeof(int32_t), 1, f) == 1;
-            for (int r = 0; ok && r < R; ++r) ok = fread(&b[r].n_anchor, sizeof(int32_t), 1, f) == 1;
-            for (int r = 0; ok && r < R; ++r) ok = fread(b[r].anchor_L, sizeof(int32_t), kMaxAnchors, f) == kMaxAnchors;
-            for (int r = 0; ok && r < R; ++r) ok = fread(b[r].anchor_micro, sizeof(int32_t), kMaxAnchors, f) == kMaxAnchors;
-            for (int r = 0; ok && r < R; ++r) ok = b[r].n_anchor >= 0 && b[r].n_anchor <= kMaxAnchors;
+            bool ok = read_block(f, &t.buckets[k * R], R);
+            if (ok && t.W_row > 0) ok = read_block(f, &t.row_buckets[k * (t.W_row + 1)], t.W_row + 1);
             if (!ok) rc = WT_ERR_IO;
         }
     }
@@ -659,7 +697,7 @@ int wt_predict_us(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, wt_cfg cfg
     const int kid = ctx->cfgs[id].res.key_id;
     const Key& k = ctx->keys[kid];
     const int64_t G = ceil_div64(M, k.bm) * ceil_div64(N, k.bn), L = ceil_div64(K, k.bk);
-    const Bucket* b = pick_bucket(ctx->table, kid, ceil_div64(G, k.cap));
+    const Bucket* b = pick_bucket(ctx->table, kid, ceil_div64(G, k.cap), M <= k.bm);
     if (!b) return WT_ERR_NOT_FITTED;
     *us = predict(b->th, G, L);
     return WT_OK;

@@ -46,6 +46,9 @@ struct Table {
     int W = 0, I = 0, p = 0, tau_num = 11, tau_den = 10;
     // buckets[key * (W + 1) + (w - 1)] for w = 1..W; index W is the extrapolation entry
     std::vector<Bucket> buckets;
+    // single-tile-row family (extension): row_buckets[key * (W_row + 1) + (w - 1)], last = extrapolation
+    int W_row = 0;
+    std::vector<Bucket> row_buckets;
 };
 
 }  // namespace wt

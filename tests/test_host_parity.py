@@ -254,3 +254,51 @@ def test_occupancy_aware_capacity_mode(tmp_path):
             wt.wt_select(c, 64, 64, 64)
     finally:
         wt.wt_destroy(c)
+
+
+def test_single_row_family_parity(ctx, tmp_path):
+    """Extension: records of 1 x g grids (family 1) build a second bucket set; table, file (version 2)
+    and lookups match the oracle exactly."""
+    W, W_row, I, p = 8, 3, 4, 4
+    keys = _keys(ctx)
+    near = _synthetic_samples(keys, W, I, noise_seed=11)
+    rows = []
+    for k, kd in enumerate(keys):
+        th = wt_synth.random_theta(900 + k, W_row)
+        for s in smp.row_sample_set(kd.cap, W_row, I):
+            for L in smp.loop_anchors(K_ANCHORS, kd.bk):
+                for micro in range(3):
+                    a, b, c, d = th[s.w - 1]
+                    t = 2.0 * (kd.bn * kd.bk / 8192.0) * (a * s.g * L + b * s.g) + c * L + d
+                    rows.append((k, micro, s.g, L, s.w, 1, t * (1.0 + 0.02 * ((micro + k) % 3))))
+    samples = np.concatenate([near, np.array(rows, dtype=wt.SAMPLE_DTYPE)])
+    grid = wt.make_grid(W=W, I=I, p=p, k_anchors=K_ANCHORS, W_row=W_row)
+    wt.wt_fit(ctx, grid, samples)
+    path = str(tmp_path / "row.wt")
+    wt.wt_save(ctx, path)
+    table, meta = osel.read_table(path)
+    assert meta["W_row"] == W_row and table.W_row == W_row
+    want = ofit.fit_tables([(int(r["key_id"]), int(r["micro_id"]), int(r["G"]), int(r["L"]), int(r["w"]),
+                             float(r["mean_us"]), int(r["family"])) for r in samples], keys, W, p, W_row=W_row)
+    for k in range(len(keys)):
+        pairs = list(zip(table.local[k], want.local[k])) + [(table.ext[k], want.ext[k])]
+        pairs += list(zip(table.row_local[k], want.row_local[k])) + [(table.row_ext[k], want.row_ext[k])]
+        for got_b, want_b in pairs:
+            assert got_b.status == want_b.status and got_b.anchors == want_b.anchors
+            scale = max(abs(x) for x in want_b.theta) or 1.0
+            assert np.allclose(got_b.theta, want_b.theta, rtol=1e-9, atol=1e-9 * scale) or \
+                _pred_close(got_b.theta, want_b.theta, keys[k])
+    ctx2 = wt.wt_create(-1, wt.WT_BF16, wt.WT_OUT_F32)
+    wt.wt_load(ctx2, path)
+    used_row = 0
+    for (M, N, K) in wt_synth.sweep_shapes() + wt_synth.stream_shapes(2000):
+        key, micro, t = osel.select(table, M, N, K)
+        used_row += M <= keys[key].bm
+        for cc in (ctx, ctx2):
+            c = wt.wt_select(cc, M, N, K)
+            assert c.id == 3 * key + micro and wt.wt_predict_us(cc, M, N, K, c) == t
+    assert used_row > 100
+    wt.wt_destroy(ctx2)
+    n_near, *_ = wt.wt_sample_plan(ctx, wt.make_grid(W=W, I=I, p=p, k_anchors=K_ANCHORS))
+    n_both, *_ = wt.wt_sample_plan(ctx, grid)
+    assert n_both - n_near == len(rows)          # the plan adds exactly the 1 x g workloads

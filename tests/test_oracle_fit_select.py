@@ -296,3 +296,52 @@ def test_linear_model_is_one_global_bilinear_per_key():
             err_lin += abs(osel.predict(t.ext[1].theta, s.G, s.L) - truth) / truth
             err_full += abs(osel.predict(full.local[1][s.w - 1].theta, s.G, s.L) - truth) / truth
     assert err_full < 1e-6 < err_lin
+
+
+# ---- single-tile-row family (extension beyond the paper's near-square sampler) ----------------------
+def _row_samples(W_row, I, slow=3.0):
+    """1 x g grids whose latency surface is `slow` times the near-square one (B streamed from HBM)."""
+    out = []
+    for k, kd in enumerate(KEYS):
+        for s in smp.row_sample_set(kd.cap, W_row, I):
+            for L in smp.loop_anchors(K_ANCHORS, kd.bk):
+                for mi in range(N_MICRO):
+                    out.append(ofit.Sample(k, mi, s.g, L, s.w, slow * _latency(k, mi, s.g, L, 6, _penalty), 1))
+    return out
+
+
+def test_single_row_family_is_fitted_and_used_only_for_one_tile_row():
+    W, W_row, I = 6, 2, 4
+    near = _make_samples(W, I, _penalty)
+    table = ofit.fit_tables(near + _row_samples(W_row, I), KEYS, W, p=3, W_row=W_row)
+    plain = ofit.fit_tables(near, KEYS, W, p=3)
+    assert table.W_row == W_row and plain.W_row == 0
+    for k in range(len(KEYS)):
+        # the paper's buckets are untouched by the extra family
+        assert [b.theta for b in table.local[k]] == [b.theta for b in plain.local[k]]
+        assert table.ext[k].theta == plain.ext[k].theta
+        for w in range(1, W_row + 1):
+            assert np.allclose(table.row_local[k][w - 1].theta, 3.0 * _surface_theta(k, w, 6), rtol=1e-7)
+    kd = KEYS[1]                                   # 128 x 128 x 64
+    # M <= BM: one tile row -> row family; M = BM + 1: two tile rows -> the paper's buckets
+    assert osel.bucket_for(table, 1, 1, 1) is table.row_local[1][0]
+    assert osel.bucket_for(table, 1, W_row + 1, 1) is table.row_ext[1]
+    assert osel.bucket_for(table, 1, 1, 0) is table.local[1][0]
+    assert osel.bucket_for(plain, 1, 1, 1) is plain.local[1][0]
+    t1 = osel.predict(osel.bucket_for(table, 1, 1, 1).theta, 32, 64)
+    t0 = osel.predict(osel.bucket_for(table, 1, 1, 0).theta, 32, 64)
+    assert abs(t1 - 3.0 * t0) < 1e-6 * t1
+    # a skinny shape: every key with BM >= M is priced 3x higher than in the plain table, so the pick
+    # moves to what the generating function says is best under the slow surface
+    M, N, K = 16, 4096, 4096
+    cand = []
+    for kid, kd in enumerate(KEYS):
+        G, L = geo.phi_gemm(M, N, K, kd.bm, kd.bn, kd.bk)
+        for mi in range(N_MICRO):
+            cand.append(((kid, mi), (3.0 if M <= kd.bm else 1.0) * _latency(kid, mi, G, L, W, _penalty)))
+    (bk, _), bt = oex.argmin_config(cand)
+    key, _, t = osel.select(table, M, N, K)
+    assert key == bk and abs(t - bt) < 1e-6 * bt
+    # a key without row records falls back to its near-square buckets
+    t2 = ofit.fit_tables(near + [s for s in _row_samples(W_row, I) if s.key != 0], KEYS, W, p=3, W_row=W_row)
+    assert osel.bucket_for(t2, 0, 1, 1) is t2.local[0][0]

@@ -182,3 +182,15 @@ def test_loop_anchors_per_tile_depth():
     assert smp.loop_anchors(ks, 64) == [16, 32, 48, 64, 80]
     assert smp.loop_anchors(ks, 128) == [8, 16, 24, 32, 40]
     assert smp.loop_anchors((100, 64, 65), 64) == [1, 2]
+
+
+def test_single_row_sample_set():
+    # extension: 1 x g grids, g = top of each sub-interval, same regions as the paper's sampler
+    S = smp.row_sample_set(256, 2, 4)
+    assert [(s.w, s.i, s.g, s.m, s.n) for s in S] == [
+        (1, 1, 64, 1, 64), (1, 2, 128, 1, 128), (1, 3, 192, 1, 192), (1, 4, 256, 1, 256),
+        (2, 1, 320, 1, 320), (2, 2, 384, 1, 384), (2, 3, 448, 1, 448), (2, 4, 512, 1, 512)]
+    for s in smp.row_sample_set(132, 5, 3):
+        a, b = smp.sub_interval(s.w, s.i, 132, 3)
+        assert s.g == b and geo.wave_count(s.g, 132) == s.w
+        assert geo.phi_gemm(*smp.instantiate(s.m, s.n, 7, 16, 64, 128), 16, 64, 128) == (s.g, 7)
