@@ -146,8 +146,10 @@ int wt_sample_plan(const wt_ctx* ctx, const wt_grid* grid, size_t* n_samples, si
 int wt_profile_sparse(wt_ctx* ctx, const wt_grid* grid, void* scrA, void* scrB, void* scrC,
                       size_t bytesA, size_t bytesB, size_t bytesC, void* hip_stream,
                       wt_sample* out, size_t cap, size_t* n_out);
-/* Time one (shape, config): warm-up + iters launches, mean microseconds.  Same protocol as
- * wt_profile_sparse; used for exhaustive search. */
+/* Time one (shape, config): warm-up + iters launches between one HIP event pair, mean microseconds.
+ * If the timed batch lasts under 300 us it is repeated with proportionally more launches (at most
+ * 64x) so that kernels of a few microseconds are not timed at the resolution of the events.  Same
+ * protocol as wt_profile_sparse; used for exhaustive search. */
 int wt_time_gemm(wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
                  const float* scaleA, const float* scaleB, wt_cfg cfg, int warmup, int iters,
                  void* hip_stream, double* mean_us);

@@ -26,6 +26,7 @@ namespace {
 // Largest K for which BM*K*esize stays below the buffer-offset sentinel for every tile height.
 constexpr int64_t kMaxK = 1 << 21;
 constexpr int64_t kMaxDim = 1 << 30;
+constexpr double kMinTimedUs = 300.0;  // shortest event-timed batch that is trusted
 
 int validate_shape(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K) {
     if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxK) return WT_ERR_INVALID_ARG;
@@ -73,15 +74,25 @@ int time_config(wt_ctx* ctx, const Config& c, int64_t M, int64_t N, int64_t K, c
         const int rc = launch(ctx, c, M, N, K, A, B, C, sA, sB, stream);
         if (rc != WT_OK) return rc;
     }
-    WT_HIP(ctx, hipEventRecord(e0, stream));
-    for (int i = 0; i < iters; ++i) {
-        const int rc = launch(ctx, c, M, N, K, A, B, C, sA, sB, stream);
-        if (rc != WT_OK) return rc;
-    }
-    WT_HIP(ctx, hipEventRecord(e1, stream));
-    WT_HIP(ctx, hipEventSynchronize(e1));
+    // Timed batch: `iters` back-to-back launches between one event pair.  A batch shorter than
+    // kMinTimedUs is too close to the event resolution and to launch jitter, so it is repeated with
+    // proportionally more launches (at most 64x); the mean is over the launches of the last batch.
     float ms = 0;
-    WT_HIP(ctx, hipEventElapsedTime(&ms, e0, e1));
+    for (int pass = 0; pass < 2; ++pass) {
+        WT_HIP(ctx, hipEventRecord(e0, stream));
+        for (int i = 0; i < iters; ++i) {
+            const int rc = launch(ctx, c, M, N, K, A, B, C, sA, sB, stream);
+            if (rc != WT_OK) return rc;
+        }
+        WT_HIP(ctx, hipEventRecord(e1, stream));
+        WT_HIP(ctx, hipEventSynchronize(e1));
+        WT_HIP(ctx, hipEventElapsedTime(&ms, e0, e1));
+        const double total_us = (double)ms * 1000.0;
+        if (pass == 1 || total_us >= kMinTimedUs) break;
+        const double per = total_us > 0.5 ? total_us / iters : 0.5;
+        const int more = (int)(kMinTimedUs / per) + 1;
+        iters = std::min(std::max(more, iters), iters * 64);
+    }
     *mean_us = (double)ms * 1000.0 / (double)iters;
     return WT_OK;
 }

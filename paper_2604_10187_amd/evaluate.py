@@ -218,14 +218,16 @@ def cmd_ablate(a, torch=None):
     rows = [r for e in evals for r in e["rows"]]
     out = {"workload": "ablation of the latency model and of the profiling range, scored on " +
                        ", ".join(e["workload"] for e in evals), "variants": []}
+    if "family" not in recs.dtype.names:      # records saved before the family field had its name
+        recs = recs.view(wt.SAMPLE_DTYPE)
     W0, I0 = int(recs["w"].max()), a.I
 
-    def score(model, W, I, cap_mode):
+    def score(model, W, I, cap_mode, W_row=0):
         ctx = wt.wt_create(-1, a.in_type, a.out_type)
         wt.wt_set_capacity_mode(ctx, cap_mode)
         for k, o in enumerate(occ):
             wt.wt_key_set_occ(ctx, k, int(o))
-        sub = recs[recs["w"] <= W]
+        sub = recs[((recs["family"] == 0) & (recs["w"] <= W)) | ((recs["family"] == 1) & (recs["w"] <= W_row))]
         if I < I0:       # sub-intervals of a coarser split are unions of the finer ones: keep each union's top sample
             keep = np.zeros(len(sub), dtype=bool)
             step = I0 // I
@@ -236,7 +238,7 @@ def cmd_ablate(a, torch=None):
                 idx = np.minimum(pos * I0 // cap, I0 - 1)            # which of the I0 sub-intervals
                 keep[np.where(m)[0]] = (idx % step) == (step - 1)
             sub = sub[keep]
-        wt.wt_fit(ctx, wt.make_grid(W=W, I=I, p=min(a.p, W), k_anchors=tune.K_ANCHORS, model=model), sub)
+        wt.wt_fit(ctx, wt.make_grid(W=W, I=I, p=min(a.p, W), k_anchors=tune.K_ANCHORS, model=model, W_row=W_row), sub)
         fr = []
         for r in rows:
             c = wt.wt_select(ctx, r["M"], r["N"], r["K"])
@@ -247,6 +249,11 @@ def cmd_ablate(a, torch=None):
         return {"geomean_frac": float(np.exp(np.mean(np.log(fr)))), "min_frac": float(fr.min()),
                 "frac_ge_95": float(np.mean(fr >= 0.95)), "records": int(len(sub))}
 
+    W0 = int(recs["w"][recs["family"] == 0].max())
+    Wr = int(recs["w"][recs["family"] == 1].max()) if (recs["family"] == 1).any() else 0
+    if Wr:
+        out["variants"].append({"model": "wave-bilinear + single-row family", "W": W0, "I": I0, "W_row": Wr,
+                                **score(0, W0, I0, a.cap_mode, Wr)})
     for name, model in (("wave-bilinear (full)", 0), ("linear", 1), ("step", 2)):
         out["variants"].append({"model": name, "W": W0, "I": I0, **score(model, W0, I0, a.cap_mode)})
     for W in (5, 10, 20, W0):
