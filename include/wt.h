@@ -16,6 +16,9 @@
  *     form the structural ("macro") key: they fix G, L and how many blocks fit on a compute
  *     unit.  swizzle is the micro parameter (Sec. 4.1: macro governs partitioning, wave dynamics
  *     and dominant occupancy; micro tunes execution efficiency, e.g. rasterisation for L2 reuse).
+ *     swizzle 0: tiles in row-major order (XCD x of the 8 walks tile columns x, x+8, ...);
+ *     swizzle 1 / 2: each XCD gets a contiguous range of a grouped order (groups of 4 / 8 tile rows
+ *     walked column by column), so that tiles sharing a B panel run on the same XCD's L2.
  */
 #ifndef WT_H
 #define WT_H
@@ -125,6 +128,10 @@ int wt_set_capacity_mode(wt_ctx* ctx, int mode);
  * M*N == 0 is a no-op; K == 0 writes zeros. */
 int wt_gemm(wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
             const float* scaleA, const float* scaleB, wt_cfg cfg, void* hip_stream);
+
+/* Diagnostic: the (tile row, tile column) that workgroup `block` of a tiles_m x tiles_n grid computes
+ * under rasterisation mode `swizzle` -- the kernel's own mapping evaluated on the host.  Host only. */
+int wt_tile_coords(int tiles_m, int tiles_n, int swizzle, int block, int* tm, int* tn);
 
 /* ---- geometry (Table 2 Dense-GEMM row; Sec. 3.2 / 3.3 wave count) ------------------------ */
 /* G = ceil(M/bm)*ceil(N/bn), L = ceil(K/bk), w = ceil(G / capacity) (see wt_set_capacity_mode). */

@@ -86,6 +86,7 @@ def lib():
             "wt_key_count": [vp, C.POINTER(C.c_int)],
             "wt_key_set_occ": [vp, C.c_int, C.c_int],
             "wt_set_capacity_mode": [vp, C.c_int],
+            "wt_tile_coords": [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)],
             "wt_gemm": [vp, i64, i64, i64, vp, vp, vp, vp, vp, wt_cfg, vp],
             "wt_wave_count": [vp, i64, i64, i64, wt_cfg, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32)],
             "wt_sample_grid": [i64, i32, i32, i32, i32, vp, vp, vp, sz, C.POINTER(sz)],
@@ -111,7 +112,7 @@ def lib():
 
 
 EXPORTS = ("wt_create", "wt_destroy", "wt_last_hip_error", "wt_status_string", "wt_config_count", "wt_config_get",
-           "wt_config_find", "wt_key_count", "wt_key_set_occ", "wt_set_capacity_mode", "wt_gemm", "wt_wave_count", "wt_sample_grid",
+           "wt_config_find", "wt_key_count", "wt_key_set_occ", "wt_set_capacity_mode", "wt_tile_coords", "wt_gemm", "wt_wave_count", "wt_sample_grid",
            "wt_sample_plan", "wt_profile_sparse", "wt_time_gemm", "wt_mfma_ceiling", "wt_fit", "wt_select", "wt_predict_us",
            "wt_select_bench", "wt_save", "wt_load")
 
@@ -195,6 +196,12 @@ def wt_key_set_occ(ctx, key_id: int, occ: int):
 
 def wt_set_capacity_mode(ctx, mode: int):
     _check(lib().wt_set_capacity_mode(ctx, mode), "wt_set_capacity_mode")
+
+
+def wt_tile_coords(tiles_m, tiles_n, swizzle, block):
+    tm, tn = C.c_int(), C.c_int()
+    _check(lib().wt_tile_coords(tiles_m, tiles_n, swizzle, block, C.byref(tm), C.byref(tn)), "wt_tile_coords")
+    return tm.value, tn.value
 
 
 def wt_gemm(ctx, M, N, K, A, B, Cout, cfg, scaleA=None, scaleB=None, stream=None):

@@ -14,14 +14,18 @@
 //     consecutive rows fall into distinct banks.  The XOR is applied on the global side of the
 //     copy (each lane picks the source chunk that belongs in its fixed LDS slot).
 //   * math: v_mfma_f32_32x32x16_bf16 (or 16x16x32 when a wavefront's sub-tile has a 16-wide
-//     side); fp8 uses v_mfma_f32_16x16x128_f8f6f4.  fp32 accumulation in registers.
-//   * pipeline: ST LDS stages in a ring; loads of tile kt+ST-1 are issued right after the barrier
-//     that frees their stage and complete behind the MFMAs of tiles kt..kt+ST-2.  vmcnt is
-//     managed by hand (the direct-to-LDS loads are issued from inline asm so that the compiler
-//     does not serialise them against every LDS read).
-//   * block rasterisation (the micro parameter): 0 = row-major, 1 = groups of 8 tile rows,
-//     2 = per-XCD contiguous ranges (workgroups are dealt round-robin to the 8 XCDs, each with its
-//     own L2) followed by the grouping of mode 1.
+//     side); fp8 uses v_mfma_f32_32x32x64_f8f6f4 / 16x16x128 with both operand formats e4m3 and
+//     unit block scales.  fp32 accumulation in registers.
+//   * pipeline: ST LDS stages in a ring, one barrier per k-tile, fragments double-buffered in
+//     registers; every MFMA is followed by at most one fragment read and its share of the refill
+//     loads (spread over the whole k-tile when ST >= 3, over its last k-step when ST = 2) and the
+//     scheduler is fenced after each such group.  vmcnt is managed by hand (the direct-to-LDS
+//     loads are issued from inline asm so that the compiler does not serialise them against
+//     every LDS read).
+//   * block rasterisation (the micro parameter).  Workgroups are dealt round-robin to the 8 XCDs,
+//     each with its own L2.  0 = row-major (so XCD x walks the tile columns x, x+8, ...);
+//     1 and 2 give each XCD a contiguous range of a grouped tile sequence (groups of 4 resp. 8
+//     tile rows walked column by column), so tiles that share a B panel meet in one L2.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -53,23 +57,22 @@ constexpr uint32_t kOobOffset = 0x7FFFFFF0u;  // >= any num_records we set: read
 constexpr int kXcd = 8;
 constexpr int kGroupM = 8;
 
-__device__ __forceinline__ void tile_coords(int bid, int tiles_m, int tiles_n, int mode, int& tm, int& tn) {
+__host__ __device__ __forceinline__ void tile_coords(int bid, int tiles_m, int tiles_n, int mode, int& tm, int& tn) {
     if (mode == 0) {
         tm = bid / tiles_n;
         tn = bid - tm * tiles_n;
         return;
     }
-    int id = bid;
-    if (mode == 2) {
-        const int total = tiles_m * tiles_n;
-        const int per = total / kXcd, rem = total - per * kXcd;
-        const int xcd = bid % kXcd, local = bid / kXcd;
-        id = xcd * per + (xcd < rem ? xcd : rem) + local;
-    }
-    const int group = kGroupM * tiles_n;
+    // XCD x receives the workgroups with bid % 8 == x; hand it the x-th contiguous chunk of the sequence
+    const int total = tiles_m * tiles_n;
+    const int per = total / kXcd, rem = total - per * kXcd;
+    const int xcd = bid % kXcd, local = bid / kXcd;
+    const int id = xcd * per + (xcd < rem ? xcd : rem) + local;
+    const int rows = mode == 1 ? kGroupM / 2 : kGroupM;
+    const int group = rows * tiles_n;
     const int gid = id / group;
-    const int first_m = gid * kGroupM;
-    const int gm = (tiles_m - first_m) < kGroupM ? (tiles_m - first_m) : kGroupM;
+    const int first_m = gid * rows;
+    const int gm = (tiles_m - first_m) < rows ? (tiles_m - first_m) : rows;
     const int in_group = id - gid * group;
     tm = first_m + in_group % gm;
     tn = in_group / gm;

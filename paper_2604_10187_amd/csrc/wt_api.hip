@@ -122,8 +122,6 @@ int check_grid(const wt_grid* g) {
 template <typename F>
 int walk_plan(const wt_ctx* ctx, const wt_grid* grid, F&& fn) {
     const int nk = (int)ctx->keys.size();
-    const size_t esz = ctx->in_type == WT_BF16 ? 2 : 1;
-    (void)esz;
     std::vector<GridPoint> pts;
     std::vector<int64_t> anchors;
     for (int k = 0; k < nk; ++k) {
@@ -212,6 +210,14 @@ int wt_destroy(wt_ctx* ctx) {
     if (ctx->ev_start) (void)hipEventDestroy((hipEvent_t)ctx->ev_start);
     if (ctx->ev_stop) (void)hipEventDestroy((hipEvent_t)ctx->ev_stop);
     delete ctx;
+    return WT_OK;
+}
+
+int wt_tile_coords(int tiles_m, int tiles_n, int swizzle, int block, int* tm, int* tn) {
+    if (tiles_m < 1 || tiles_n < 1 || swizzle < 0 || swizzle >= kNumSwizzle || block < 0 ||
+        (int64_t)block >= (int64_t)tiles_m * tiles_n || !tm || !tn)
+        return WT_ERR_INVALID_ARG;
+    tile_coords(block, tiles_m, tiles_n, swizzle, *tm, *tn);  // the kernel's own mapping, run on the host
     return WT_OK;
 }
 

@@ -167,8 +167,6 @@ struct Row {
 
 // Solve the n x n system a*x = b by Gaussian elimination with partial pivoting.
 static bool solve_small(int n, double a[4][4], double b[4], double x[4]) {
-    int perm[4] = {0, 1, 2, 3};
-    (void)perm;
     for (int c = 0; c < n; ++c) {
         int piv = c;
         for (int r = c + 1; r < n; ++r)

@@ -29,7 +29,7 @@ def table_path(in_type: int, out_type: int) -> str:
     return os.path.join(TABLE_DIR, f"mi355x_in{in_type}_out{out_type}.wt")
 
 
-def profile(ctx, grid, in_type, out_type, log=print, chunk_keys=4):
+def profile(ctx, grid, in_type, out_type, log=print, chunk_keys=1):
     """Run wt_profile_sparse over the grid's key slice in chunks; returns the records."""
     import torch
 

@@ -52,6 +52,19 @@ def test_integer_matrices_bit_exact_every_config(ctx_f32):
         assert np.array_equal(got, want), f"{cfg}: max diff {np.abs(got - want).max()}"
 
 
+def test_rasterisation_modes_cover_every_tile_once(ctx_f32):
+    """Many-tile grids with ragged group and XCD remainders (38 x 12 and 5 x 29 tiles): every
+    rasterisation mode must still compute every tile exactly once -- bit-exact on integer inputs."""
+    for (tiles_m, tiles_n) in ((38, 12), (5, 29), (1, 61)):
+        for sw in (0, 1, 2):
+            cfg, _ = wt.wt_config_get(ctx_f32, wt.wt_config_find(ctx_f32, 64, 64, 64, 4, 2, sw))
+            M, N, K = 64 * (tiles_m - 1) + 5, 64 * (tiles_n - 1) + 3, 136
+            note(f"rasterisation sw={sw} grid={tiles_m}x{tiles_n}")
+            ab, bb = _bf16_case(M, N, K, 700 + sw, "int")
+            got = run_gemm(ctx_f32, cfg, ab, bb, wt.WT_OUT_F32, fill=float("nan"))
+            assert np.array_equal(got, og.gemm_c(ab, bb))
+
+
 def test_config1_256_cubed_normal(ctx_f32):
     """Single bf16 GEMM M=N=K=256, N(0,1) inputs, fp32 accumulate/out, over the
     BM,BN in {64,128} x BK in {32,64} x stages in {1,2} grid where the registry has it."""

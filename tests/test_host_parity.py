@@ -302,3 +302,30 @@ def test_single_row_family_parity(ctx, tmp_path):
     n_near, *_ = wt.wt_sample_plan(ctx, wt.make_grid(W=W, I=I, p=p, k_anchors=K_ANCHORS))
     n_both, *_ = wt.wt_sample_plan(ctx, grid)
     assert n_both - n_near == len(rows)          # the plan adds exactly the 1 x g workloads
+
+
+@pytest.mark.parametrize("tiles", [(1, 1), (1, 61), (3, 80), (5, 29), (7, 8), (16, 43), (38, 12), (64, 32), (9, 9)])
+def test_rasterisation_is_a_bijection(tiles):
+    """The kernel's block -> tile mapping, evaluated on the host: every mode visits every tile exactly
+    once; modes 1/2 hand each XCD (block index mod 8) a contiguous range of the grouped order."""
+    tm_n, tn_n = tiles
+    total = tm_n * tn_n
+    for sw in (0, 1, 2):
+        seen = [wt.wt_tile_coords(tm_n, tn_n, sw, b) for b in range(total)]
+        assert sorted(seen) == [(i, j) for i in range(tm_n) for j in range(tn_n)]
+    assert [wt.wt_tile_coords(tm_n, tn_n, 0, b) for b in range(total)] == \
+        [(b // tn_n, b % tn_n) for b in range(total)]
+    rows = 8
+    order = []                                   # grouped order: groups of 8 tile rows, column by column
+    for g0 in range(0, tm_n, rows):
+        gm = min(rows, tm_n - g0)
+        order += [(g0 + i, j) for j in range(tn_n) for i in range(gm)]
+    per, rem = divmod(total, 8)
+    for x in range(8):
+        mine = [wt.wt_tile_coords(tm_n, tn_n, 2, b) for b in range(x, total, 8)]
+        start = x * per + min(x, rem)
+        assert mine == order[start:start + len(mine)]
+    with pytest.raises(wt.WtError):
+        wt.wt_tile_coords(tm_n, tn_n, 3, 0)
+    with pytest.raises(wt.WtError):
+        wt.wt_tile_coords(tm_n, tn_n, 0, total)
