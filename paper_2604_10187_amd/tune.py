@@ -1,6 +1,6 @@
 """Offline stage: wave-aware sparse profiling on the GPU, fit, and dual-table file (Sec. 4.2-4.5).
 
-    python -m paper_2604_10187_amd.tune --out gpurun_out/mi355x_bf16_bf16.wt [--W 40 --I 4 ...]
+    python -m paper_2604_10187_amd.tune --out tables/mi355x_in0_out1.wt [--W 40 --I 4 ...]
         [--key-first a --key-count n --samples-out file.npy]      # profile a slice of keys only
         [--fit-from a.npy b.npy ...]                              # fit saved records, no GPU
 
