@@ -27,7 +27,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM-side bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled
 # by the copy-kernel calibration (x2.0 / x1.0): profiles/gemm_traffic_pmc.md.  Keyed by (kernel, shape);
 # reported as null when the run picks another kernel than the profiled one.
-TRAFFIC_BYTES = {((256, 256, 64, 8, 2, 2), (4096, 11008, 4096)): 720.1e6}
+TRAFFIC_BYTES = {((256, 256, 64, 8, 2, 2, 1), (4096, 11008, 4096)): 720.1e6}
 
 
 def log(*a):
@@ -132,7 +132,7 @@ def main():
                 "algorithmic_flop": 2.0 * big[0] * big[1] * big[2],
                 "mfma_only_ceiling": round(ceiling, 1), "frac_of_mfma_only_ceiling": round(ach / ceiling, 4),
                 "kernel": f"gemm_kernel<{cfg_big.bm},{cfg_big.bn},{cfg_big.bk},nw{cfg_big.nwave},st{cfg_big.stages}>"
-                          f" sw{cfg_big.swizzle} on {big[0]}x{big[1]}x{big[2]}", "avg_us": round(us_big, 2)}
+                          f" sw{cfg_big.swizzle} split{cfg_big.split} on {big[0]}x{big[1]}x{big[2]}", "avg_us": round(us_big, 2)}
 
     # ---- pick vs exhaustive search over the frozen grid (same timing protocol for both) --------
     extra = {}
@@ -145,8 +145,9 @@ def main():
             times = {}
             for i in range(ncfg):
                 c, r = wt.wt_config_get(ctx, i)
-                if r.occ < 1:
-                    continue
+                tiles = -(-M // c.bm) * -(-N // c.bn)
+                if r.occ < 1 or (c.split > 1 and tiles * c.split * c.bm * c.bn > (1 << 26)):
+                    continue    # does not fit the device / its split-K partial tiles exceed the workspace
                 times[i] = wt.wt_time_gemm(ctx, M, N, K, dA, dB, dC, c, warmup=3, iters=5, stream=stream)
             if pick.id not in times:
                 times[pick.id] = wt.wt_time_gemm(ctx, M, N, K, dA, dB, dC, pick, warmup=3, iters=5, stream=stream)

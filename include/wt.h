@@ -11,10 +11,14 @@
  *   - Matrices: A is [M,K] row-major, B is stored K-contiguous as [N,K] row-major (the weight
  *     layout of a linear layer, so C = A * B^T in storage terms), C is [M,N] row-major.
  *     K must be a multiple of 8 (bf16) or 16 (fp8): rows are moved in 16-byte pieces.
- *   - A configuration c = (bm, bn, bk, nwave, stages, swizzle): block tile BM x BN x BK,
- *     wavefronts per block, LDS pipeline stages, and block-rasterisation mode.  The first five
- *     form the structural ("macro") key: they fix G, L and how many blocks fit on a compute
- *     unit.  swizzle is the micro parameter (Sec. 4.1: macro governs partitioning, wave dynamics
+ *   - A configuration c = (bm, bn, bk, nwave, stages, swizzle, split): block tile BM x BN x BK,
+ *     wavefronts per block, LDS pipeline stages, block-rasterisation mode, and the number S of
+ *     blocks that share one output tile along K (split-K; 1 = none).  All but swizzle form the
+ *     structural ("macro") key: they fix G, L and how many blocks fit on a compute unit.  With
+ *     split S the kernel launches G = S * tiles tasks of L = ceil(K / (S*bk)) loop iterations
+ *     (Table 2's mapping applied to the kernel's own task list); partial tiles meet in a workspace
+ *     owned by the context and the last block to arrive adds them in split order.
+ *     swizzle is the micro parameter (Sec. 4.1: macro governs partitioning, wave dynamics
  *     and dominant occupancy; micro tunes execution efficiency, e.g. rasterisation for L2 reuse).
  *     swizzle 0: tiles in row-major order (XCD x of the 8 walks tile columns x, x+8, ...);
  *     swizzle 1 / 2: each XCD gets a contiguous range of a grouped order (groups of 4 / 8 tile rows
@@ -33,8 +37,9 @@ extern "C" {
 typedef enum {
     WT_OK = 0,
     WT_ERR_INVALID_ARG = -1,     /* null pointer, negative size, K not a multiple of the vector width */
-    WT_ERR_UNSUPPORTED_CFG = -2, /* (bm,bn,bk,nwave,stages,swizzle) is not in the registry */
-    WT_ERR_INFEASIBLE = -3,      /* config exists but does not fit the device (LDS / registers) */
+    WT_ERR_UNSUPPORTED_CFG = -2, /* (bm,bn,bk,nwave,stages,swizzle,split) is not in the registry */
+    WT_ERR_INFEASIBLE = -3,      /* config exists but does not fit the device (LDS / registers), or a split-K
+                                  * config's partial tiles for this shape exceed the context's workspace */
     WT_ERR_NOT_FITTED = -4,      /* wt_select / wt_predict_us before wt_fit or wt_load */
     WT_ERR_HIP = -5,             /* a HIP call failed; see wt_last_hip_error() */
     WT_ERR_BUFFER_TOO_SMALL = -6,
@@ -50,6 +55,7 @@ typedef struct wt_ctx wt_ctx; /* opaque: config registry, per-config resources, 
 /* One kernel configuration.  id is the registry index (or -1: look the fields up). */
 typedef struct {
     int32_t bm, bn, bk, nwave, stages, swizzle;
+    int32_t split; /* S >= 1 */
     int32_t id;
 } wt_cfg;
 
@@ -83,6 +89,8 @@ typedef struct {
     int32_t key_first, key_count;
     int64_t max_out_elems;
     int32_t model;    /* wt_model: which latency model wt_fit builds (0 = the paper's) */
+    int32_t W_split;  /* split-K keys are profiled for waves 1..min(W, W_split) only (0 = all W); beyond their
+                       * profiled waves they have no model and wt_select does not consider them */
     int32_t W_row;    /* extension, 0 = off (the paper's method): also profile and fit W_row waves of
                        * single-tile-row grids (m_G = 1, n_G = top of each sub-interval; M = bm), kept in
                        * a second set of buckets that wt_select consults for shapes with M <= bm.  The
@@ -108,7 +116,7 @@ const char* wt_status_string(int status);
 /* ---- config registry ---------------------------------------------------------------------- */
 int wt_config_count(const wt_ctx* ctx, int* n);
 int wt_config_get(const wt_ctx* ctx, int i, wt_cfg* cfg, wt_cfg_res* res);
-int wt_config_find(const wt_ctx* ctx, const wt_cfg* fields, int* id); /* match the six fields */
+int wt_config_find(const wt_ctx* ctx, const wt_cfg* fields, int* id); /* match the seven fields */
 int wt_key_count(const wt_ctx* ctx, int* n);
 /* Override the recorded occupancy of structural key key_id (e.g. with a measured value). */
 int wt_key_set_occ(wt_ctx* ctx, int key_id, int occ);
@@ -125,7 +133,11 @@ int wt_set_capacity_mode(wt_ctx* ctx, int mode);
  * the context).  scaleA/scaleB: device pointers to one fp32 each, fp8 only (C = sA*sB*sum),
  * NULL for bf16.  Asynchronous on hip_stream (a hipStream_t, NULL = default stream); never
  * synchronises, never allocates.  M, N may be any non-negative size (edge tiles are masked);
- * M*N == 0 is a no-op; K == 0 writes zeros. */
+ * M*N == 0 is a no-op; K == 0 writes zeros.
+ * Split-K configurations (cfg.split > 1) stage partial tiles in the context's workspace (256 MiB,
+ * allocated by wt_create): WT_ERR_INFEASIBLE when ceil(M/bm)*ceil(N/bn)*split*bm*bn exceeds 2^26
+ * floats or there are more than 65536 tiles.  Launches that use the workspace must be ordered on
+ * one stream per context: two of them running concurrently race on it. */
 int wt_gemm(wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
             const float* scaleA, const float* scaleB, wt_cfg cfg, void* hip_stream);
 
@@ -134,19 +146,20 @@ int wt_gemm(wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, const v
 int wt_tile_coords(int tiles_m, int tiles_n, int swizzle, int block, int* tm, int* tn);
 
 /* ---- geometry (Table 2 Dense-GEMM row; Sec. 3.2 / 3.3 wave count) ------------------------ */
-/* G = ceil(M/bm)*ceil(N/bn), L = ceil(K/bk), w = ceil(G / capacity) (see wt_set_capacity_mode). */
+/* G = split*ceil(M/bm)*ceil(N/bn), L = ceil(K/(split*bk)), w = ceil(G / capacity) (see wt_set_capacity_mode). */
 int wt_wave_count(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, wt_cfg cfg,
                   int64_t* G, int64_t* L, int32_t* w);
 
 /* ---- sparse structural sampling (Sec. 4.2) ------------------------------------------------ */
 /* Grid samples for a capacity: fills up to cap_out triples (g, m, n) in w-major, i-minor order
- * (g = 0 where a sub-interval holds no value with a near-square factorisation). */
-int wt_sample_grid(int64_t capacity, int32_t W, int32_t I, int32_t tau_num, int32_t tau_den,
+ * (g = 0 where a sub-interval holds no value with a near-square factorisation).  split = S >= 1:
+ * task counts are multiples of S, g = S*m*n with m x n the near-square tile grid (S = 1: Eq. 3-4). */
+int wt_sample_grid(int64_t capacity, int32_t W, int32_t I, int32_t tau_num, int32_t tau_den, int32_t split,
                    int64_t* g, int64_t* m, int64_t* n, size_t cap_out, size_t* n_out);
 /* Number of records wt_profile_sparse would produce and the scratch bytes it needs. */
 int wt_sample_plan(const wt_ctx* ctx, const wt_grid* grid, size_t* n_samples, size_t* bytesA,
                    size_t* bytesB, size_t* bytesC);
-/* Instantiate every sample (M = m*bm, N = n*bn, K = L*bk), run every micro with warm-up +
+/* Instantiate every sample (M = m*bm, N = n*bn, K = L*split*bk), run every micro with warm-up +
  * measured launches timed by HIP events on hip_stream, write one record per <key, micro, g, L>.
  * scrA/scrB/scrC: device scratch of at least the planned sizes (contents: any finite values).
  * Synchronises the stream. */

@@ -36,6 +36,7 @@ class KeyDesc(NamedTuple):
     stages: int
     occ: int
     cap: int
+    split: int = 1   # S blocks per output tile along K
 
 
 @dataclass

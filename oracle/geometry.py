@@ -21,9 +21,32 @@ def ceil_div(a: int, b: int) -> int:
     return -((-a) // b)
 
 
-def phi_gemm(M: int, N: int, K: int, BM: int, BN: int, BK: int) -> tuple[int, int]:
-    """Table 2, Dense-GEMM row: G = ceil(M/T_M) * ceil(N/T_N) blocks, L = ceil(K/T_K) iterations."""
-    return ceil_div(M, BM) * ceil_div(N, BN), ceil_div(K, BK)
+def phi_gemm(M: int, N: int, K: int, BM: int, BN: int, BK: int, S: int = 1) -> tuple[int, int]:
+    """Table 2, Dense-GEMM row: G = ceil(M/T_M) * ceil(N/T_N) blocks, L = ceil(K/T_K) iterations.
+
+    S > 1 (split-K, a kernel parameter the paper's kernels do not have; reading: Phi counts the
+    kernel's own tasks): every output tile is shared by S blocks that divide its ceil(K/T_K)
+    k-tiles evenly, the last ones possibly short or empty, so G = S * tiles and each block loops
+    L = ceil(ceil(K/T_K) / S) times."""
+    if S < 1:
+        raise ValueError("S >= 1")
+    return S * ceil_div(M, BM) * ceil_div(N, BN), ceil_div(ceil_div(K, BK), S)
+
+
+# Limits of the product's split-K workspace as stated in its header: partial tiles of one launch may
+# hold at most 2^26 floats and there is one arrival counter for each of at most 2^16 output tiles.
+WS_ELEMS = 1 << 26
+MAX_SPLIT_TILES = 1 << 16
+
+
+def split_fits(M: int, N: int, BM: int, BN: int, S: int, ws_elems: int = WS_ELEMS,
+               max_tiles: int = MAX_SPLIT_TILES) -> bool:
+    """Whether a split-K configuration can run a shape: S fp32 partial tiles of BM x BN per output
+    tile must fit the workspace.  Unsplit configurations always fit."""
+    if S == 1:
+        return True
+    tiles = ceil_div(M, BM) * ceil_div(N, BN)
+    return tiles <= max_tiles and tiles * S * BM * BN <= ws_elems
 
 
 def capacity(occ: int, n_cu: int = N_CU) -> int:

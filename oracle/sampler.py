@@ -64,13 +64,34 @@ def representative(a: int, b: int, tau_num: int, tau_den: int) -> Optional[tuple
     return None
 
 
-def sample_set(cap: int, W: int, I: int, tau_num: int = 11, tau_den: int = 10) -> list[GridSample]:
-    """The sampling set {g_{w,i}} (Sec. 4.2), w-major then i; empty sub-intervals have g = 0."""
+def representative_split(a: int, b: int, S: int, tau_num: int, tau_den: int) -> Optional[tuple[int, int, int]]:
+    """Split-K reading of the representative: the task count g of a kernel with S blocks per output
+    tile is S times its tile count, so only multiples of S can occur; the largest g in [a, b] whose
+    tile grid g/S = m*n is nearly square.  Returns (g, m, n) with m*n = g/S, or None."""
+    for g in range(b, a - 1, -1):
+        if g < 1:
+            break
+        if g % S:
+            continue
+        m, n = most_square(g // S)
+        if qualifies(m, n, tau_num, tau_den):
+            return g, m, n
+    return None
+
+
+def sample_set(cap: int, W: int, I: int, tau_num: int = 11, tau_den: int = 10, S: int = 1) -> list[GridSample]:
+    """The sampling set {g_{w,i}} (Sec. 4.2), w-major then i; empty sub-intervals have g = 0.
+    S > 1: see representative_split (m x n is then the tile grid and g = S*m*n)."""
     out = []
     for w in range(1, W + 1):
         for i in range(1, I + 1):
             a, b = sub_interval(w, i, cap, I)
-            r = representative(a, b, tau_num, tau_den) if b >= a else None
+            if b < a:
+                r = None
+            elif S == 1:
+                r = representative(a, b, tau_num, tau_den)
+            else:
+                r = representative_split(a, b, S, tau_num, tau_den)
             out.append(GridSample(w, i, *(r if r else (0, 0, 0))))
     return out
 
@@ -88,16 +109,17 @@ def row_sample_set(cap: int, W_row: int, I: int) -> list[GridSample]:
     return out
 
 
-def instantiate(m: int, n: int, L: int, BM: int, BN: int, BK: int) -> tuple[int, int, int]:
-    """Sec. 4.2, workload instantiation: M = m_G*T_M, N = n_G*T_N, K = L*T_K."""
-    return m * BM, n * BN, L * BK
+def instantiate(m: int, n: int, L: int, BM: int, BN: int, BK: int, S: int = 1) -> tuple[int, int, int]:
+    """Sec. 4.2, workload instantiation: M = m_G*T_M, N = n_G*T_N, K = L*T_K.  With S blocks per tile
+    each of them gets exactly L k-tiles: K = L*S*T_K."""
+    return m * BM, n * BN, L * S * BK
 
 
-def loop_anchors(k_anchors, BK: int) -> list[int]:
+def loop_anchors(k_anchors, BK: int, S: int = 1) -> list[int]:
     """Loop counts for a list of K anchors under tile depth BK: L_j = ceil(K_j / BK), ascending,
     duplicates removed.  (The paper lists anchors in K -- five spanning [1024, 5120] -- so the
-    loop anchors differ per tile depth.)"""
-    return sorted({-(-int(k) // BK) for k in k_anchors})
+    loop anchors differ per tile depth.)  With S blocks per tile, L_j = ceil(ceil(K_j/BK) / S)."""
+    return sorted({-(-(-(-int(k) // BK)) // S) for k in k_anchors})
 
 
 def profile_budget(n_grid: int, n_loop: int, n_macro: int, n_micro: int) -> int:

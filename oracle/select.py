@@ -12,7 +12,7 @@ import struct
 import numpy as np
 
 from .fit import Bucket, DualTable, KeyDesc
-from .geometry import phi_gemm, wave_count
+from .geometry import phi_gemm, split_fits, wave_count
 
 
 def predict(theta, G: int, L: int) -> float:
@@ -56,7 +56,9 @@ def select(table: DualTable, M: int, N: int, K: int):
     Stage II: nearest loop anchor in the chosen bucket.  Returns (key, micro, T-hat) or None."""
     best = None
     for k, kd in enumerate(table.keys):
-        G, L = phi_gemm(M, N, K, kd.bm, kd.bn, kd.bk)
+        if not split_fits(M, N, kd.bm, kd.bn, kd.split):
+            continue     # its partial tiles would not fit the workspace: not a candidate
+        G, L = phi_gemm(M, N, K, kd.bm, kd.bn, kd.bk, kd.split)
         w = wave_count(G, kd.cap)
         b = bucket_for(table, k, w, 1 if M <= kd.bm else 0)     # one tile row <=> M <= T_M
         if b is None:
@@ -82,7 +84,7 @@ def read_table(path: str) -> tuple[DualTable, dict]:
 
     Header, 16 uint32: magic 'WTDT', version (1 or 2), n_keys, W, I, p, tau_num, tau_den, n_cu,
     A (anchor slots per bucket), in_type, out_type, key_mode, W_row (version 2, else 0), 2 reserved.
-    Then per key: 8 int32 (bm, bn, bk, nwave, stages, occ, n_micro, reserved), int64 cap, and a
+    Then per key: 8 int32 (bm, bn, bk, nwave, stages, occ, n_micro, split [0 = 1]), int64 cap, and a
     bucket block of R = W+1 rows (w = 1..W, then ext): R*4 float64 theta, R int32 status, R int32
     n_anchor, R*A int32 anchor L, R*A int32 anchor micro.  Version 2 appends a second block of
     W_row+1 rows per key for the single-tile-row family.
@@ -112,7 +114,7 @@ def read_table(path: str) -> tuple[DualTable, dict]:
     for _ in range(n_keys):
         bm, bn, bk, nwave, stages, occ, n_micro, _r = struct.unpack_from("<8i", raw, off); off += 32
         (cap,) = struct.unpack_from("<q", raw, off); off += 8
-        keys.append(KeyDesc(bm, bn, bk, nwave, stages, occ, cap))
+        keys.append(KeyDesc(bm, bn, bk, nwave, stages, occ, cap, max(1, _r)))
         buckets = block(W + 1)
         local.append(buckets[:W])
         ext.append(buckets[W])

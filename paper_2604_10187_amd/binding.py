@@ -24,13 +24,14 @@ WT_CAP_CU_TIMES_OCC, WT_CAP_CU_ONLY = 0, 1
 
 
 class wt_cfg(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("bm", "bn", "bk", "nwave", "stages", "swizzle", "id")]
+    _fields_ = [(n, C.c_int32) for n in ("bm", "bn", "bk", "nwave", "stages", "swizzle", "split", "id")]
 
     def astuple(self):
-        return (self.bm, self.bn, self.bk, self.nwave, self.stages, self.swizzle)
+        return (self.bm, self.bn, self.bk, self.nwave, self.stages, self.swizzle, self.split)
 
     def __repr__(self):
-        return f"wt_cfg(bm={self.bm}, bn={self.bn}, bk={self.bk}, nwave={self.nwave}, stages={self.stages}, swizzle={self.swizzle}, id={self.id})"
+        return (f"wt_cfg(bm={self.bm}, bn={self.bn}, bk={self.bk}, nwave={self.nwave}, stages={self.stages}, "
+                f"swizzle={self.swizzle}, split={self.split}, id={self.id})")
 
 
 class wt_cfg_res(C.Structure):
@@ -52,7 +53,7 @@ class wt_grid(C.Structure):
                 ("p", C.c_int32), ("n_k_anchors", C.c_int32), ("k_anchors", C.POINTER(C.c_int32)),
                 ("warmup", C.c_int32), ("iters", C.c_int32), ("key_first", C.c_int32),
                 ("key_count", C.c_int32), ("max_out_elems", C.c_int64), ("model", C.c_int32),
-                ("W_row", C.c_int32)]
+                ("W_split", C.c_int32), ("W_row", C.c_int32)]
 
 
 class WtError(RuntimeError):
@@ -89,7 +90,7 @@ def lib():
             "wt_tile_coords": [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)],
             "wt_gemm": [vp, i64, i64, i64, vp, vp, vp, vp, vp, wt_cfg, vp],
             "wt_wave_count": [vp, i64, i64, i64, wt_cfg, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32)],
-            "wt_sample_grid": [i64, i32, i32, i32, i32, vp, vp, vp, sz, C.POINTER(sz)],
+            "wt_sample_grid": [i64, i32, i32, i32, i32, i32, vp, vp, vp, sz, C.POINTER(sz)],
             "wt_sample_plan": [vp, C.POINTER(wt_grid), C.POINTER(sz), C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)],
             "wt_profile_sparse": [vp, C.POINTER(wt_grid), vp, vp, vp, sz, sz, sz, vp, vp, sz, C.POINTER(sz)],
             "wt_time_gemm": [vp, i64, i64, i64, vp, vp, vp, vp, vp, wt_cfg, C.c_int, C.c_int, vp, C.POINTER(C.c_double)],
@@ -142,10 +143,10 @@ def _stream(stream):
 
 
 def make_grid(W=40, I=4, tau=(11, 10), p=10, k_anchors=(1024, 2048, 3072, 4096, 5120), warmup=3, iters=5,
-              key_first=0, key_count=0, max_out_elems=0, model=0, W_row=0):
+              key_first=0, key_count=0, max_out_elems=0, model=0, W_row=0, W_split=0):
     arr = (C.c_int32 * len(k_anchors))(*k_anchors)
     g = wt_grid(W, I, tau[0], tau[1], p, len(k_anchors), C.cast(arr, C.POINTER(C.c_int32)), warmup, iters,
-                key_first, key_count, max_out_elems, model, W_row)
+                key_first, key_count, max_out_elems, model, W_split, W_row)
     g._keep = arr  # keep the anchor array alive with the struct
     return g
 
@@ -183,8 +184,8 @@ def wt_config_get(ctx, i: int):
     return c, r
 
 
-def wt_config_find(ctx, bm, bn, bk, nwave, stages, swizzle) -> int:
-    c = wt_cfg(bm, bn, bk, nwave, stages, swizzle, -1)
+def wt_config_find(ctx, bm, bn, bk, nwave, stages, swizzle, split=1) -> int:
+    c = wt_cfg(bm, bn, bk, nwave, stages, swizzle, split, -1)
     i = C.c_int()
     _check(lib().wt_config_find(ctx, C.byref(c), C.byref(i)), "wt_config_find")
     return i.value
@@ -231,11 +232,11 @@ def wt_wave_count(ctx, M, N, K, cfg):
     return G.value, L.value, w.value
 
 
-def wt_sample_grid(capacity, W, I, tau_num=11, tau_den=10):
+def wt_sample_grid(capacity, W, I, tau_num=11, tau_den=10, split=1):
     n = W * I
     g, m, nn = (np.zeros(n, dtype=np.int64) for _ in range(3))
     got = C.c_size_t()
-    _check(lib().wt_sample_grid(capacity, W, I, tau_num, tau_den, g.ctypes.data, m.ctypes.data, nn.ctypes.data,
+    _check(lib().wt_sample_grid(capacity, W, I, tau_num, tau_den, split, g.ctypes.data, m.ctypes.data, nn.ctypes.data,
                                 n, C.byref(got)), "wt_sample_grid")
     return g[:got.value], m[:got.value], nn[:got.value]
 

@@ -26,6 +26,12 @@
 //     each with its own L2.  0 = row-major (so XCD x walks the tile columns x, x+8, ...);
 //     1 and 2 give each XCD a contiguous range of a grouped tile sequence (groups of 4 resp. 8
 //     tile rows walked column by column), so tiles that share a B panel meet in one L2.
+//   * split-K (structural parameter S > 1): the grid holds S blocks per output tile, block
+//     (tile, s) walks k-tiles [s*Ls, (s+1)*Ls) with Ls = ceil(K / (S*BK)), stores its fp32
+//     accumulators to a workspace slab, four registers per lane per 16-byte piece (fully coalesced), and bumps the tile's
+//     arrival counter; the block that arrives last adds the S slabs in split order (so the result
+//     does not depend on arrival order), writes C and clears the counter.  Nobody waits for anybody.
+//     Slabs travel as agent-scope coherent (sc1) 16-byte buffer accesses, the counter as an agent-scope atomic.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -39,6 +45,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 typedef __attribute__((ext_vector_type(8))) int i32x8;
 
 struct GemmArgs {
@@ -50,6 +57,10 @@ struct GemmArgs {
     int M, N, K;
     int tiles_m, tiles_n;
     int swizzle;
+    int splits;         // S >= 1
+    int k_per_split;    // Ls * BK elements (multiple of BK); unused when S == 1
+    float* ws;          // S > 1: tiles * S slabs of BM*BN floats
+    int* counters;      // S > 1: one arrival counter per tile, zero before and after every launch
 };
 
 constexpr int kWave = 64;
@@ -201,22 +212,37 @@ __global__ __launch_bounds__(WM* WN* kWave) void gemm_kernel(const GemmArgs args
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wv / WN, wn = wv - wm * WN;
 
+    // blocks [s*tiles, (s+1)*tiles) form split s; within a split the rasterisation is the usual one
+    int tile = blockIdx.x, split = 0;
+    if (args.splits > 1) {
+        const int tiles = args.tiles_m * args.tiles_n;
+        split = tile / tiles;
+        tile -= split * tiles;
+    }
     int tm, tn;
-    tile_coords(blockIdx.x, args.tiles_m, args.tiles_n, args.swizzle, tm, tn);
+    tile_coords(tile, args.tiles_m, args.tiles_n, args.swizzle, tm, tn);
     const int row0 = tm * BM, col0 = tn * BN;
-    const int K = args.K;
+    // this block's k range [k0, k0 + K): the whole of args.K unless split
+    int k0 = 0, K = args.K;
+    if (args.splits > 1) {
+        k0 = split * args.k_per_split;
+        K = args.K - k0;
+        K = K < 0 ? 0 : (K > args.k_per_split ? args.k_per_split : K);
+        if (K == 0) k0 = 0;  // empty range: every load is sent out of range below
+    }
 
     // ---- global -> LDS plan: this wavefront's LPW loads per stage --------------------------
     const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
         (__attribute__((address_space(3))) char*)smem));
-    const int64_t row_bytes = static_cast<int64_t>(K) * T::esize;
-    auto records = [&](int rows_left) -> uint32_t {
-        const int64_t b = static_cast<int64_t>(rows_left) * row_bytes;
+    const int64_t row_bytes = static_cast<int64_t>(args.K) * T::esize;
+    const int64_t k0_bytes = static_cast<int64_t>(k0) * T::esize;
+    auto records = [&](int rows_left) -> uint32_t {  // bytes from the descriptor base to the end of the matrix
+        const int64_t b = static_cast<int64_t>(rows_left) * row_bytes - k0_bytes;
         return b > static_cast<int64_t>(kOobOffset) ? kOobOffset : static_cast<uint32_t>(b);
     };
-    const i32x4 rsrcA = make_rsrc(static_cast<const char*>(args.A) + static_cast<int64_t>(row0) * row_bytes,
+    const i32x4 rsrcA = make_rsrc(static_cast<const char*>(args.A) + static_cast<int64_t>(row0) * row_bytes + k0_bytes,
                                   records(args.M - row0));
-    const i32x4 rsrcB = make_rsrc(static_cast<const char*>(args.B) + static_cast<int64_t>(col0) * row_bytes,
+    const i32x4 rsrcB = make_rsrc(static_cast<const char*>(args.B) + static_cast<int64_t>(col0) * row_bytes + k0_bytes,
                                   records(args.N - col0));
     // Load slot t of this wavefront fills the 1 KiB LDS piece j = wv + t*NW of a stage.  The lane's
     // source offset at k-tile 0 stays in a register for the whole kernel; the k advance is a scalar.
@@ -423,6 +449,65 @@ __global__ __launch_bounds__(WM* WN* kWave) void gemm_kernel(const GemmArgs args
         for (; kt + AHEAD < L_full; ++kt) tile_body(kt, std::false_type{});
         for (; kt < L; ++kt) tile_body(kt, std::true_type{});
         wait_vmcnt<0>();
+    }
+
+    // ---- split-K reduction ---------------------------------------------------------------------
+    // Partial tiles travel as 16-byte buffer stores / loads marked agent-scope coherent (sc1): the
+    // stores write through the XCD's L2 and the loads are served coherently across the XCDs, so no
+    // cache-wide write-back or invalidate (what a device-scope fence costs here) is needed.  Order:
+    // this block's slab stores are waited for, then the block is counted in with an agent-scope
+    // atomic; the block that finds S-1 earlier arrivals knows every slab is in memory.
+    if (args.splits > 1) {
+        constexpr int NREG = T::FM * T::FN * T::ACC;
+        constexpr int NQ = NREG / 4;                      // 16-byte pieces per lane
+        constexpr int QPT = T::ACC / 4;                   // pieces per MFMA tile
+        constexpr uint32_t SLAB_BYTES = static_cast<uint32_t>(NREG) * T::NT * 4;   // = BM*BN*4
+        constexpr int SC1 = 16;                           // cache-policy bit: agent-scope coherence
+        static_assert(T::ACC % 4 == 0, "accumulators move in groups of four");
+        const int S = args.splits;
+        const __amdgpu_buffer_rsrc_t ws_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            args.ws + static_cast<size_t>(tile) * S * (SLAB_BYTES / 4), 0, static_cast<int>(S * SLAB_BYTES), 0x00020000);
+        const uint32_t lane_off = threadIdx.x * 16u;
+        const uint32_t mine = static_cast<uint32_t>(split) * SLAB_BYTES + lane_off;
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            const int ij = q / QPT, e0 = 4 * (q % QPT);
+            const acc_t& a = acc[ij / T::FN][ij % T::FN];
+            const u32x4 v = {__float_as_uint(a[e0]), __float_as_uint(a[e0 + 1]), __float_as_uint(a[e0 + 2]),
+                             __float_as_uint(a[e0 + 3])};
+            __builtin_amdgcn_raw_buffer_store_b128(v, ws_rsrc, mine + q * (T::NT * 16), 0, SC1);
+        }
+        wait_vmcnt<0>();   // this lane's slab stores have been acknowledged
+        __syncthreads();   // ... and everybody's; every wavefront is also past its last LDS access
+        int* flag = reinterpret_cast<int*>(smem);
+        if (threadIdx.x == 0)
+            *flag = __hip_atomic_fetch_add(args.counters + tile, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (*flag != S - 1) return;
+        // Sum in split order, whatever the arrival order.  S is dispatched to a compile-time constant
+        // so that the loads of all slabs are independent and in flight together.
+        auto reduce = [&](auto s_tag) {
+            constexpr int SS = decltype(s_tag)::value;
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+                const int ij = q / QPT, e0 = 4 * (q % QPT);
+                float v0 = 0.0f, v1 = 0.0f, v2 = 0.0f, v3 = 0.0f;
+#pragma unroll
+                for (int sp = 0; sp < SS; ++sp) {
+                    const u32x4 p = __builtin_amdgcn_raw_buffer_load_b128(
+                        ws_rsrc, sp * SLAB_BYTES + lane_off + q * (T::NT * 16), 0, SC1);
+                    v0 += __uint_as_float(p.x); v1 += __uint_as_float(p.y);
+                    v2 += __uint_as_float(p.z); v3 += __uint_as_float(p.w);
+                }
+                acc_t& a = acc[ij / T::FN][ij % T::FN];
+                a[e0] = v0; a[e0 + 1] = v1; a[e0 + 2] = v2; a[e0 + 3] = v3;
+            }
+        };
+        if (S == 2) reduce(std::integral_constant<int, 2>{});
+        else if (S == 4) reduce(std::integral_constant<int, 4>{});
+        else reduce(std::integral_constant<int, 8>{});
+        if (threadIdx.x == 0)   // ready for the next launch on this stream
+            __hip_atomic_store(args.counters + tile, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 
     // ---- epilogue ---------------------------------------------------------------------------------

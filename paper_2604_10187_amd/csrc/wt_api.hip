@@ -37,15 +37,23 @@ int validate_shape(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K) {
 
 int launch(wt_ctx* ctx, const Config& c, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
            const float* sA, const float* sB, hipStream_t stream) {
+    const Key& key = ctx->keys[c.res.key_id];
     const int64_t tiles_m = ceil_div64(M, c.cfg.bm), tiles_n = ceil_div64(N, c.cfg.bn);
-    const int64_t G = tiles_m * tiles_n;
+    int64_t tiles, G, L;
+    key_phi(key, M, N, K, &tiles, &G, &L);
     if (G == 0) return WT_OK;
     if (G > 0x7FFFFFFF) return WT_ERR_INVALID_ARG;
+    if (!key_fits(key, tiles)) return WT_ERR_INFEASIBLE;
     GemmArgs args;
     args.A = A; args.B = B; args.C = C; args.scaleA = sA; args.scaleB = sB;
     args.M = (int)M; args.N = (int)N; args.K = (int)K;
     args.tiles_m = (int)tiles_m; args.tiles_n = (int)tiles_n;
     args.swizzle = c.cfg.swizzle;
+    args.splits = key.split;
+    args.k_per_split = (int)(L * key.bk);  // L = ceil(K / (S*bk)) k-tiles per block
+    args.ws = ctx->ws;
+    args.counters = ctx->counters;
+    if (key.split > 1 && (!ctx->ws || !ctx->counters)) return WT_ERR_NO_DEVICE;
     void* params[] = {&args};
     WT_HIP(ctx, hipLaunchKernel(c.fn, dim3((unsigned)G), dim3((unsigned)(c.cfg.nwave * 64)), params,
                                 (size_t)c.res.lds_bytes, stream));
@@ -109,7 +117,7 @@ bool key_in_slice(const wt_grid* g, int k, int nk) {
 
 int check_grid(const wt_grid* g) {
     if (!g || g->W < 1 || g->I < 1 || g->tau_den < 1 || g->tau_num < g->tau_den || g->p < 1 || g->n_k_anchors < 1 ||
-        !g->k_anchors || g->warmup < 0 || g->iters < 1 || g->W_row < 0)
+        !g->k_anchors || g->warmup < 0 || g->iters < 1 || g->W_row < 0 || g->W_split < 0)
         return WT_ERR_INVALID_ARG;
     for (int j = 0; j < g->n_k_anchors; ++j)
         if (g->k_anchors[j] < 1) return WT_ERR_INVALID_ARG;
@@ -127,18 +135,22 @@ int walk_plan(const wt_ctx* ctx, const wt_grid* grid, F&& fn) {
     for (int k = 0; k < nk; ++k) {
         if (!key_in_slice(grid, k, nk)) continue;
         const Key& key = ctx->keys[k];
-        sample_grid(key.cap, grid->W, grid->I, grid->tau_num, grid->tau_den, pts);
-        loop_anchors(grid, key.bk, anchors);
+        // split-K keys: only the first W_split waves are worth profiling (0 = all W)
+        const int W = (key.split > 1 && grid->W_split > 0) ? std::min(grid->W, grid->W_split) : grid->W;
+        sample_grid(key.cap, W, grid->I, grid->tau_num, grid->tau_den, key.split, pts);
+        loop_anchors(grid, key.bk * key.split, anchors);
         for (size_t s = 0; s < pts.size(); ++s) {
             if (pts[s].g == 0) continue;
             const int64_t M = pts[s].m * key.bm, N = pts[s].n * key.bn;
             if (grid->max_out_elems > 0 && M * N > grid->max_out_elems) continue;
+            if (!key_fits(key, pts[s].m * pts[s].n)) continue;
             const int w = (int)(s / (size_t)grid->I) + 1;
             for (int64_t L : anchors) {
-                const int rc = fn(k, pts[s], w, 0, L, M, N, L * key.bk);
+                const int rc = fn(k, pts[s], w, 0, L, M, N, L * key.bk * key.split);
                 if (rc != WT_OK) return rc;
             }
         }
+        if (key.split > 1) continue;  // the single-tile-row family is profiled for unsplit keys only
         for (int w = 1; w <= grid->W_row; ++w) {
             for (int i = 1; i <= grid->I; ++i) {
                 const int64_t lo = (int64_t)(w - 1) * key.cap + 1;
@@ -180,6 +192,20 @@ int wt_create(wt_ctx** out, int device, int in_type, int out_type) {
         if (e == hipSuccess) e = hipEventCreate(&e1);
         if (e != hipSuccess) { delete ctx; return WT_ERR_HIP; }
         ctx->ev_start = e0; ctx->ev_stop = e1;
+        // split-K workspace: partial tiles, then the arrival counters (zero now; every launch leaves them zero)
+        void* ws = nullptr;
+        const size_t ws_bytes = (size_t)kWsElems * sizeof(float), cnt_bytes = (size_t)kMaxSplitTiles * sizeof(int);
+        e = hipMalloc(&ws, ws_bytes + cnt_bytes);
+        if (e == hipSuccess) e = hipMemset((char*)ws + ws_bytes, 0, cnt_bytes);
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        if (e != hipSuccess) {
+            if (ws) (void)hipFree(ws);
+            (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+            delete ctx;
+            return WT_ERR_HIP;
+        }
+        ctx->ws = (float*)ws;
+        ctx->counters = (int*)((char*)ws + ws_bytes);
         // per-key resources from the runtime: LDS opt-in, register count, resident blocks per CU
         for (size_t k = 0; k < ctx->keys.size(); ++k) {
             Key& key = ctx->keys[k];
@@ -209,6 +235,7 @@ int wt_destroy(wt_ctx* ctx) {
     if (!ctx) return WT_ERR_INVALID_ARG;
     if (ctx->ev_start) (void)hipEventDestroy((hipEvent_t)ctx->ev_start);
     if (ctx->ev_stop) (void)hipEventDestroy((hipEvent_t)ctx->ev_stop);
+    if (ctx->ws) (void)hipFree(ctx->ws);
     delete ctx;
     return WT_OK;
 }

@@ -54,53 +54,89 @@ int static_occupancy(int lds_bytes, int nwave, int vgprs) {
     return std::max(0, std::min(occ, 32));
 }
 
+struct SplitEntry {
+    int bm, bn, bk, wm, wn, st, split;
+};
+#define WT_SPLIT(BM, BN, BK, WM, WN, ST, S) {BM, BN, BK, WM, WN, ST, S},
+static const SplitEntry kSplitBf16[] = {
+#define WT_LIST_SPLIT_BF16
+#include "configs.def"
+#undef WT_LIST_SPLIT_BF16
+};
+static const SplitEntry kSplitFp8[] = {
+#define WT_LIST_SPLIT_FP8
+#include "configs.def"
+#undef WT_LIST_SPLIT_FP8
+};
+#undef WT_SPLIT
+
+static void add_key(wt_ctx* ctx, const KernelEntry& e, int split) {
+    Key k{};
+    k.bm = e.bm; k.bn = e.bn; k.bk = e.bk;
+    k.nwave = e.wm * e.wn;
+    k.stages = e.st;
+    k.split = split;
+    k.sh_m = ilog2(k.bm); k.sh_n = ilog2(k.bn); k.sh_k = ilog2(k.bk * split);
+    k.sh_s = ilog2(split);
+    k.lds_bytes = e.lds_bytes;
+    k.vgprs = (k.bm * k.bn) / (k.nwave * 64) + 64;  // accumulators + working set (estimate)
+    k.occ = std::max(1, static_occupancy(k.lds_bytes, k.nwave, k.vgprs));
+    k.cap = key_capacity(ctx->cap_mode, k.occ);
+    k.n_micro = kNumSwizzle;
+    k.first_cfg = static_cast<int>(ctx->cfgs.size());
+    const int key_id = static_cast<int>(ctx->keys.size());
+    for (int sw = 0; sw < kNumSwizzle; ++sw) {
+        Config c{};
+        c.cfg = wt_cfg{k.bm, k.bn, k.bk, k.nwave, k.stages, sw, split, static_cast<int32_t>(ctx->cfgs.size())};
+        c.res = wt_cfg_res{k.lds_bytes, k.vgprs, k.nwave, k.occ, key_id, sw};
+        c.wm = e.wm; c.wn = e.wn;
+        c.fn = e.fn;
+        ctx->cfgs.push_back(c);
+    }
+    ctx->keys.push_back(k);
+}
+
 int build_registry(wt_ctx* ctx) {
     ctx->cfgs.clear();
     ctx->keys.clear();
+    std::vector<KernelEntry> base;
     for (int list = 0; list < 3; ++list) {
         int n = 0;
         const KernelEntry* e = kernel_list(ctx->in_type, ctx->out_type, list, &n);
         for (int i = 0; e && i < n; ++i) {
-            Key k{};
-            k.bm = e[i].bm; k.bn = e[i].bn; k.bk = e[i].bk;
-            k.nwave = e[i].wm * e[i].wn;
-            k.stages = e[i].st;
-            k.sh_m = ilog2(k.bm); k.sh_n = ilog2(k.bn); k.sh_k = ilog2(k.bk);
-            k.lds_bytes = e[i].lds_bytes;
-            k.vgprs = (k.bm * k.bn) / (k.nwave * 64) + 64;  // accumulators + working set (estimate)
-            k.occ = std::max(1, static_occupancy(k.lds_bytes, k.nwave, k.vgprs));
-            k.cap = key_capacity(ctx->cap_mode, k.occ);
-            k.n_micro = kNumSwizzle;
-            k.first_cfg = static_cast<int>(ctx->cfgs.size());
-            const int key_id = static_cast<int>(ctx->keys.size());
-            for (int sw = 0; sw < kNumSwizzle; ++sw) {
-                Config c{};
-                c.cfg = wt_cfg{k.bm, k.bn, k.bk, k.nwave, k.stages, sw, static_cast<int32_t>(ctx->cfgs.size())};
-                c.res = wt_cfg_res{k.lds_bytes, k.vgprs, k.nwave, k.occ, key_id, sw};
-                c.wm = e[i].wm; c.wn = e[i].wn;
-                c.fn = e[i].fn;
-                ctx->cfgs.push_back(c);
-            }
-            ctx->keys.push_back(k);
+            add_key(ctx, e[i], 1);
+            base.push_back(e[i]);
         }
+    }
+    // split-K keys reuse the kernel of their base entry
+    const SplitEntry* sp = ctx->in_type == WT_BF16 ? kSplitBf16 : kSplitFp8;
+    const size_t nsp = ctx->in_type == WT_BF16 ? sizeof(kSplitBf16) / sizeof(kSplitBf16[0])
+                                               : sizeof(kSplitFp8) / sizeof(kSplitFp8[0]);
+    for (size_t i = 0; i < nsp; ++i) {
+        if (sp[i].split != 2 && sp[i].split != 4 && sp[i].split != 8) return WT_ERR_UNSUPPORTED_CFG;  // the kernel reduces 2, 4 or 8 slabs
+        bool found = false;
+        for (const KernelEntry& e : base)
+            if (e.bm == sp[i].bm && e.bn == sp[i].bn && e.bk == sp[i].bk && e.wm == sp[i].wm && e.wn == sp[i].wn &&
+                e.st == sp[i].st) {
+                add_key(ctx, e, sp[i].split);
+                found = true;
+                break;
+            }
+        if (!found) return WT_ERR_UNSUPPORTED_CFG;
     }
     return ctx->cfgs.empty() ? WT_ERR_UNSUPPORTED_CFG : WT_OK;
 }
 
+static inline bool same_fields(const wt_cfg& r, const wt_cfg& c) {
+    return r.bm == c.bm && r.bn == c.bn && r.bk == c.bk && r.nwave == c.nwave && r.stages == c.stages &&
+           r.swizzle == c.swizzle && r.split == c.split;
+}
+
 int find_config(const wt_ctx* ctx, const wt_cfg& c) {
     const int n = static_cast<int>(ctx->cfgs.size());
-    if (c.id >= 0 && c.id < n) {
-        const wt_cfg& r = ctx->cfgs[c.id].cfg;
-        if (r.bm == c.bm && r.bn == c.bn && r.bk == c.bk && r.nwave == c.nwave && r.stages == c.stages &&
-            r.swizzle == c.swizzle)
-            return c.id;
-    }
-    for (int i = 0; i < n; ++i) {
-        const wt_cfg& r = ctx->cfgs[i].cfg;
-        if (r.bm == c.bm && r.bn == c.bn && r.bk == c.bk && r.nwave == c.nwave && r.stages == c.stages &&
-            r.swizzle == c.swizzle)
-            return i;
-    }
+    if (c.id >= 0 && c.id < n && same_fields(ctx->cfgs[c.id].cfg, c)) return c.id;
+    for (int i = 0; i < n; ++i)
+        if (same_fields(ctx->cfgs[i].cfg, c)) return i;
     return -1;
 }
 
@@ -132,20 +168,23 @@ static int64_t best_grid_in(int64_t a, int64_t b, int tau_num, int tau_den) {
     return best;
 }
 
-void sample_grid(int64_t cap, int W, int I, int tau_num, int tau_den, std::vector<GridPoint>& out) {
+// Grid samples of a key with S blocks per output tile: G = S * tiles, so the sub-interval [a,b] of
+// task counts holds the tile counts ceil(a/S)..floor(b/S); the representative is the largest of those
+// with a near-square factorisation m x n.  S = 1 is the paper's rule verbatim.
+void sample_grid(int64_t cap, int W, int I, int tau_num, int tau_den, int split, std::vector<GridPoint>& out) {
     out.clear();
     for (int w = 1; w <= W; ++w) {
         const int64_t lo = static_cast<int64_t>(w - 1) * cap + 1;  // region R_w = [lo, w*cap]
         for (int i = 1; i <= I; ++i) {
-            const int64_t a = lo + (static_cast<int64_t>(i - 1) * cap) / I;
-            const int64_t b = lo - 1 + (static_cast<int64_t>(i) * cap) / I;
+            const int64_t a = ceil_div64(lo + (static_cast<int64_t>(i - 1) * cap) / I, split);
+            const int64_t b = (lo - 1 + (static_cast<int64_t>(i) * cap) / I) / split;
             GridPoint gp{0, 0, 0};
             if (b >= a) {
-                const int64_t g = best_grid_in(a, b, tau_num, tau_den);
-                if (g > 0) {
-                    int64_t m = isqrt64(g);  // most-square factorisation of the chosen g
-                    while (g % m) --m;
-                    gp = GridPoint{g, m, g / m};
+                const int64_t t = best_grid_in(a, b, tau_num, tau_den);
+                if (t > 0) {
+                    int64_t m = isqrt64(t);  // most-square factorisation of the chosen tile count
+                    while (t % m) --m;
+                    gp = GridPoint{t * split, m, t / m};
                 }
             }
             out.push_back(gp);
@@ -153,9 +192,9 @@ void sample_grid(int64_t cap, int W, int I, int tau_num, int tau_den, std::vecto
     }
 }
 
-void loop_anchors(const wt_grid* grid, int bk, std::vector<int64_t>& out) {
+void loop_anchors(const wt_grid* grid, int bk_eff, std::vector<int64_t>& out) {
     out.clear();
-    for (int j = 0; j < grid->n_k_anchors; ++j) out.push_back(ceil_div64(grid->k_anchors[j], bk));
+    for (int j = 0; j < grid->n_k_anchors; ++j) out.push_back(ceil_div64(grid->k_anchors[j], bk_eff));
     std::sort(out.begin(), out.end());
     out.erase(std::unique(out.begin(), out.end()), out.end());
 }
@@ -437,10 +476,9 @@ static int select_impl(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, int* 
     int64_t best_L = 0;
     for (int k = 0; k < nk; ++k) {
         const Key& key = ctx->keys[k];
-        const int64_t gm = (M + key.bm - 1) >> key.sh_m;
-        const int64_t gn = (N + key.bn - 1) >> key.sh_n;
-        const int64_t G = gm * gn;
-        const int64_t L = (K + key.bk - 1) >> key.sh_k;
+        int64_t tiles, G, L;
+        key_phi(key, M, N, K, &tiles, &G, &L);
+        if (!key_fits(key, tiles)) continue;
         const int64_t w = (G + key.cap - 1) / key.cap;
         const Bucket* b = pick_bucket(t, k, w, M <= key.bm);
         if (!b) continue;
@@ -473,7 +511,7 @@ static int select_impl(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, int* 
 // Little-endian.  Header: 16 uint32 = 'WTDT', version (1, or 2 when the single-tile-row family is
 // present), n_keys, W, I, p, tau_num, tau_den, n_cu, anchor slots A, in_type, out_type, key_mode
 // (capacity mode), W_row (version 2), 2 reserved.  Per key: 8 int32 (bm, bn, bk, nwave, stages, occ,
-// n_micro, 0), int64 cap (256, or 256*occ when key_mode = 0), then a bucket block of R = W+1 rows
+// n_micro, split [0 in older files = 1]), int64 cap (256, or 256*occ when key_mode = 0), then a bucket block of R = W+1 rows
 // (w = 1..W then ext): R*4 float64 theta, R int32 status, R int32 n_anchor, R*A int32 anchor L,
 // R*A int32 anchor micro; version 2 appends a block of W_row+1 rows for the single-tile-row family.
 static const uint32_t kMagic = 0x54445457u;  // "WTDT"
@@ -515,7 +553,7 @@ static int save_table(const wt_ctx* ctx, const char* path) {
     const int R = t.W + 1;
     for (uint32_t k = 0; ok && k < nk; ++k) {
         const Key& key = ctx->keys[k];
-        const int32_t kd[8] = {key.bm, key.bn, key.bk, key.nwave, key.stages, key.occ, key.n_micro, 0};
+        const int32_t kd[8] = {key.bm, key.bn, key.bk, key.nwave, key.stages, key.occ, key.n_micro, key.split};
         ok = ok && fwrite(kd, sizeof(kd), 1, f) == 1;
         ok = ok && fwrite(&key.cap, sizeof(int64_t), 1, f) == 1;
         ok = ok && write_block(f, &t.buckets[static_cast<size_t>(k) * R], R);
@@ -551,7 +589,7 @@ static int load_table(wt_ctx* ctx, const char* path) {
             if (fread(kd, sizeof(kd), 1, f) != 1 || fread(&cap, sizeof(cap), 1, f) != 1) { rc = WT_ERR_IO; break; }
             const Key& key = ctx->keys[k];
             if (kd[0] != key.bm || kd[1] != key.bn || kd[2] != key.bk || kd[3] != key.nwave || kd[4] != key.stages ||
-                kd[5] < 1 || cap != key_capacity(static_cast<int>(hdr[12]), kd[5])) { rc = WT_ERR_INVALID_ARG; break; }
+                (kd[7] < 1 ? 1 : kd[7]) != key.split || kd[5] < 1 || cap != key_capacity(static_cast<int>(hdr[12]), kd[5])) { rc = WT_ERR_INVALID_ARG; break; }
             occs.push_back(kd[5]);
             bool ok = read_block(f, &t.buckets[k * R], R);
             if (ok && t.W_row > 0) ok = read_block(f, &t.row_buckets[k * (t.W_row + 1)], t.W_row + 1);
@@ -584,7 +622,7 @@ const char* wt_status_string(int s) {
         case WT_OK: return "ok";
         case WT_ERR_INVALID_ARG: return "invalid argument";
         case WT_ERR_UNSUPPORTED_CFG: return "configuration not in the registry";
-        case WT_ERR_INFEASIBLE: return "configuration does not fit the device";
+        case WT_ERR_INFEASIBLE: return "configuration does not fit the device or the split-K workspace";
         case WT_ERR_NOT_FITTED: return "no dual table (call wt_fit or wt_load)";
         case WT_ERR_HIP: return "HIP call failed";
         case WT_ERR_BUFFER_TOO_SMALL: return "buffer too small";
@@ -648,18 +686,20 @@ int wt_wave_count(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, wt_cfg cfg
     const int id = find_config(ctx, cfg);
     if (id < 0) return WT_ERR_UNSUPPORTED_CFG;
     const Key& k = ctx->keys[ctx->cfgs[id].res.key_id];
-    const int64_t g = ceil_div64(M, k.bm) * ceil_div64(N, k.bn);
+    int64_t tiles, g, l;
+    key_phi(k, M, N, K, &tiles, &g, &l);
     if (G) *G = g;
-    if (L) *L = ceil_div64(K, k.bk);
+    if (L) *L = l;
     if (w) *w = static_cast<int32_t>(ceil_div64(g, k.cap));
     return WT_OK;
 }
 
-int wt_sample_grid(int64_t capacity, int32_t W, int32_t I, int32_t tau_num, int32_t tau_den, int64_t* g,
-                   int64_t* m, int64_t* n, size_t cap_out, size_t* n_out) {
-    if (capacity < 1 || W < 1 || I < 1 || tau_num < tau_den || tau_den < 1 || !n_out) return WT_ERR_INVALID_ARG;
+int wt_sample_grid(int64_t capacity, int32_t W, int32_t I, int32_t tau_num, int32_t tau_den, int32_t split,
+                   int64_t* g, int64_t* m, int64_t* n, size_t cap_out, size_t* n_out) {
+    if (capacity < 1 || W < 1 || I < 1 || tau_num < tau_den || tau_den < 1 || split < 1 || !n_out)
+        return WT_ERR_INVALID_ARG;
     std::vector<GridPoint> pts;
-    sample_grid(capacity, W, I, tau_num, tau_den, pts);
+    sample_grid(capacity, W, I, tau_num, tau_den, split, pts);
     *n_out = pts.size();
     if (pts.size() > cap_out) return WT_ERR_BUFFER_TOO_SMALL;
     for (size_t i = 0; i < pts.size(); ++i) {
@@ -694,7 +734,9 @@ int wt_predict_us(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, wt_cfg cfg
     if (id < 0) return WT_ERR_UNSUPPORTED_CFG;
     const int kid = ctx->cfgs[id].res.key_id;
     const Key& k = ctx->keys[kid];
-    const int64_t G = ceil_div64(M, k.bm) * ceil_div64(N, k.bn), L = ceil_div64(K, k.bk);
+    int64_t tiles, G, L;
+    key_phi(k, M, N, K, &tiles, &G, &L);
+    if (!key_fits(k, tiles)) return WT_ERR_INFEASIBLE;
     const Bucket* b = pick_bucket(ctx->table, kid, ceil_div64(G, k.cap), M <= k.bm);
     if (!b) return WT_ERR_NOT_FITTED;
     *us = predict(b->th, G, L);

@@ -14,6 +14,9 @@ constexpr int kNumCU = 256;            // compute units of one MI355X
 constexpr int kLdsPerCU = 160 * 1024;  // bytes
 constexpr int kNumSwizzle = 3;         // micro parameter values 0..2
 constexpr int kMaxAnchors = 8;         // loop anchors stored per bucket
+// Split-K workspace owned by a context: fp32 partial tiles and one arrival counter per output tile.
+constexpr int64_t kWsElems = int64_t{1} << 26;   // 256 MiB of floats
+constexpr int64_t kMaxSplitTiles = 1 << 16;      // arrival counters
 
 struct Config {
     wt_cfg cfg;
@@ -24,7 +27,9 @@ struct Config {
 
 struct Key {
     int bm, bn, bk, nwave, stages;
-    int sh_m, sh_n, sh_k;  // log2 of the tile sides (all powers of two)
+    int split;             // S: blocks per output tile along K (1 = no split); a power of two
+    int sh_m, sh_n, sh_k;  // log2 of bm, bn and of split*bk (all powers of two)
+    int sh_s;              // log2 of split
     int occ;
     int64_t cap;  // kNumCU * occ
     int n_micro;
@@ -63,6 +68,8 @@ struct wt_ctx {
     wt::Table table;
     void* ev_start = nullptr;  // hipEvent_t pair used by the timing calls
     void* ev_stop = nullptr;
+    float* ws = nullptr;       // device: split-K partial tiles (kWsElems floats), then the counters
+    int* counters = nullptr;   // device: kMaxSplitTiles ints, zero between launches
 };
 
 namespace wt {
@@ -75,11 +82,23 @@ inline int64_t key_capacity(int cap_mode, int occ) {
     return cap_mode == WT_CAP_CU_ONLY ? kNumCU : static_cast<int64_t>(kNumCU) * (occ > 0 ? occ : 1);
 }
 int find_config(const wt_ctx* ctx, const wt_cfg& c);
+// Phi of a structural key (Table 2, dense GEMM row; split-K makes S tasks per output tile, each
+// walking ceil(K / (S*bk)) k-tiles).
+inline void key_phi(const Key& k, int64_t M, int64_t N, int64_t K, int64_t* tiles, int64_t* G, int64_t* L) {
+    const int64_t t = ((M + k.bm - 1) >> k.sh_m) * ((N + k.bn - 1) >> k.sh_n);
+    *tiles = t;
+    *G = t << k.sh_s;
+    *L = (K + (int64_t{1} << k.sh_k) - 1) >> k.sh_k;
+}
+// A split-K key can run a shape only if its partial tiles fit the context's workspace.
+inline bool key_fits(const Key& k, int64_t tiles) {
+    return k.split == 1 || (tiles <= kMaxSplitTiles && ((tiles << k.sh_s) << (k.sh_m + k.sh_n)) <= kWsElems);
+}
 
 struct GridPoint {
     int64_t g, m, n;
 };
-void sample_grid(int64_t cap, int W, int I, int tau_num, int tau_den, std::vector<GridPoint>& out);
-void loop_anchors(const wt_grid* grid, int bk, std::vector<int64_t>& out);
+void sample_grid(int64_t cap, int W, int I, int tau_num, int tau_den, int split, std::vector<GridPoint>& out);
+void loop_anchors(const wt_grid* grid, int bk_eff, std::vector<int64_t>& out);
 
 }  // namespace wt

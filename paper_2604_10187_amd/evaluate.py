@@ -55,13 +55,20 @@ class Exhaustive:
         self.launches = 0
         self.gpu_s = 0.0
 
+    @staticmethod
+    def runnable(c, M, N):
+        """Split-K configurations need their partial tiles to fit the context's workspace (wt_gemm refuses
+        the launch otherwise): 2^26 floats and at most 2^16 tiles."""
+        tiles = -(-M // c.bm) * -(-N // c.bn)
+        return c.split == 1 or (tiles <= (1 << 16) and tiles * c.split * c.bm * c.bn <= (1 << 26))
+
     def run(self, M, N, K, must=()):
         A, B, C, sA, sB = _dev_operands(self.torch, M, N, K, self.in_type, self.out_type)
         times, best = {}, math.inf
         order = sorted(range(len(self.cfgs)), key=lambda i: i not in must)
         for i in order:
             c, r = self.cfgs[i]
-            if r.occ < 1:
+            if r.occ < 1 or not self.runnable(c, M, N):
                 continue
             if i not in must and best < math.inf:
                 t1 = wt.wt_time_gemm(self.ctx, M, N, K, A, B, C, c, 1, 1, sA, sB, self.stream)

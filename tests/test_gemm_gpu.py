@@ -107,6 +107,62 @@ def test_bf16_output(ctx_bf16):
         assert og.max_scaled_err(got, want) <= 2.0 ** -8    # one bf16 rounding of an fp32 sum
 
 
+def _split_configs(ctx):
+    return [(c, r) for c, r in all_configs(ctx) if c.split > 1]
+
+
+def test_split_k_normal_inputs_repeated_launches(ctx_f32, ctx_bf16):
+    """Split-K configurations on N(0,1) data with many k-tiles per split, a ragged K tail in the last
+    split, ragged M/N, and three launches in a row into fresh outputs: every launch must leave the
+    arrival counters clean for the next, and -- the partial tiles being added in split order whatever
+    the arrival order -- produce the same bits each time."""
+    M, N, K = 333, 1000, 4104
+    ab, bb = _bf16_case(M, N, K, wt_synth.shape_seed(1002, M, N, K), "normal")
+    want = og.gemm_c(ab, bb)
+    assert len(_split_configs(ctx_f32)) >= 20
+    for cfg, res in _split_configs(ctx_f32):
+        if cfg.swizzle != cfg.id % 3:
+            continue
+        note(f"split-K f32 cfg={cfg.astuple()}")
+        first = None
+        for rep in range(3):
+            got = run_gemm(ctx_f32, cfg, ab, bb, wt.WT_OUT_F32, fill=float("nan"))
+            assert og.rel_frobenius(got, want) <= 1e-5
+            first = got if first is None else first
+            assert np.array_equal(got, first)
+    for cfg, res in _split_configs(ctx_bf16):
+        if cfg.swizzle != 1 or cfg.split != 4:
+            continue
+        note(f"split-K bf16-out cfg={cfg.astuple()}")
+        got = run_gemm(ctx_bf16, cfg, ab, bb, wt.WT_OUT_BF16)
+        assert og.max_scaled_err(got, want) <= BF16_ELEM
+        assert og.max_scaled_err(got, want) <= 2.0 ** -8
+
+
+def test_split_k_many_tiles_and_unsplit_between(ctx_f32):
+    """A grid of several hundred tiles x 4 splits (more tasks than can be resident at once, so splits
+    of one tile run far apart in time), interleaved with an unsplit launch on the same stream."""
+    cfg, _ = wt.wt_config_get(ctx_f32, wt.wt_config_find(ctx_f32, 64, 64, 128, 4, 3, 1, 4))
+    plain, _ = wt.wt_config_get(ctx_f32, wt.wt_config_find(ctx_f32, 64, 64, 128, 4, 3, 1, 1))
+    M, N, K = 64 * 19 + 7, 64 * 23 + 9, 2048 + 64
+    note(f"split-K many tiles cfg={cfg.astuple()} shape={(M, N, K)}")
+    ab, bb = _bf16_case(M, N, K, 4242, "int")
+    want = og.gemm_c(ab, bb)
+    for c in (cfg, plain, cfg):
+        got = run_gemm(ctx_f32, c, ab, bb, wt.WT_OUT_F32, fill=float("nan"))
+        assert np.array_equal(got, want)
+
+
+def test_split_k_workspace_limit(ctx_f32):
+    """Shapes whose partial tiles exceed the context's workspace are refused, not truncated."""
+    cfg, _ = wt.wt_config_get(ctx_f32, wt.wt_config_find(ctx_f32, 128, 128, 64, 4, 3, 0, 4))
+    dA = torch.zeros(8, dtype=torch.int16, device="cuda")
+    M = N = 128 * 32 + 1                      # 33 x 33 tiles x 4 x 128 x 128 floats > 2^26
+    with pytest.raises(wt.WtError) as e:
+        wt.wt_gemm(ctx_f32, M, N, 8, dA, dA, dA, cfg, stream=torch.cuda.current_stream())
+    assert e.value.status == wt.WT_ERR_INFEASIBLE
+
+
 def test_degenerate_shapes_and_errors(ctx_f32):
     cfg, _ = wt.wt_config_get(ctx_f32, 0)
     stream = torch.cuda.current_stream()
@@ -122,7 +178,7 @@ def test_degenerate_shapes_and_errors(ctx_f32):
     with pytest.raises(wt.WtError) as e:
         wt.wt_gemm(ctx_f32, 4, 8, 12, dA, dA, dC, cfg, stream=stream)   # K not a multiple of 8
     assert e.value.status == wt.WT_ERR_INVALID_ARG
-    bad = wt.wt_cfg(100, 100, 64, 4, 2, 0, -1)
+    bad = wt.wt_cfg(100, 100, 64, 4, 2, 0, 1, -1)
     with pytest.raises(wt.WtError) as e:
         wt.wt_gemm(ctx_f32, 4, 8, 16, dA, dA, dC, bad, stream=stream)
     assert e.value.status == wt.WT_ERR_UNSUPPORTED_CFG
@@ -254,11 +310,11 @@ def test_wave_count_on_device_context(ctx_f32):
 
     for cfg, res in all_configs(ctx_f32)[::3]:
         for (M, N, K) in [(16384, 8192, 8192), (4096, 11008, 4096), (333, 4096, 11008), (1, 4096, 4096)]:
-            G, L = geo.phi_gemm(M, N, K, cfg.bm, cfg.bn, cfg.bk)
+            G, L = geo.phi_gemm(M, N, K, cfg.bm, cfg.bn, cfg.bk, cfg.split)
             assert wt.wt_wave_count(ctx_f32, M, N, K, cfg) == (G, L, geo.wave_count(G, geo.capacity(1)))
     wt.wt_set_capacity_mode(ctx_f32, wt.WT_CAP_CU_TIMES_OCC)
     for cfg, res in all_configs(ctx_f32)[::3]:
-        G, L = geo.phi_gemm(4096, 11008, 4096, cfg.bm, cfg.bn, cfg.bk)
+        G, L = geo.phi_gemm(4096, 11008, 4096, cfg.bm, cfg.bn, cfg.bk, cfg.split)
         assert wt.wt_wave_count(ctx_f32, 4096, 11008, 4096, cfg) == (G, L, geo.wave_count(G, geo.capacity(res.occ)))
     wt.wt_set_capacity_mode(ctx_f32, wt.WT_CAP_CU_ONLY)
 
@@ -285,5 +341,5 @@ def test_profile_fit_select_round_trip_on_device(ctx_bf16, tmp_path):
         key, micro, t = osel.select(table, M, N, K)
         c = wt.wt_select(ctx_bf16, M, N, K)
         kd = table.keys[key]
-        assert (c.bm, c.bn, c.bk, c.nwave, c.stages, c.swizzle) == (kd.bm, kd.bn, kd.bk, kd.nwave, kd.stages, micro)
+        assert (c.bm, c.bn, c.bk, c.nwave, c.stages, c.swizzle, c.split) == (kd.bm, kd.bn, kd.bk, kd.nwave, kd.stages, micro, 1)
         assert key in (15, 16, 17)

@@ -16,6 +16,7 @@ from oracle import select as osel
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 K_ANCHORS = (1024, 2048, 3072, 4096, 5120)
+W_SPLIT = 6        # waves for which the synthetic split-K keys have records
 
 
 @pytest.fixture(scope="module")
@@ -30,7 +31,7 @@ def _keys(ctx, occ_aware=False):
     out = []
     for i in range(0, wt.wt_config_count(ctx), 3):
         c, r = wt.wt_config_get(ctx, i)
-        out.append(ofit.KeyDesc(c.bm, c.bn, c.bk, c.nwave, c.stages, r.occ, geo.capacity(r.occ if occ_aware else 1)))
+        out.append(ofit.KeyDesc(c.bm, c.bn, c.bk, c.nwave, c.stages, r.occ, geo.capacity(r.occ if occ_aware else 1), c.split))
     return out
 
 
@@ -52,10 +53,20 @@ def test_registry_shape(ctx):
         assert c.id == i and r.key_id == i // 3 and r.micro_id == c.swizzle == i % 3
         assert r.lds_bytes == (c.bm + c.bn) * c.bk * 2 * c.stages <= 160 * 1024
         assert wt.wt_config_find(ctx, *c.astuple()) == i
+        assert c.split in (1, 2, 4, 8)
         seen.add(c.astuple())
     assert len(seen) == n
+    # split-K keys come after every unsplit key and reuse an unsplit key's kernel
+    splits = [wt.wt_config_get(ctx, i)[0].split for i in range(0, n, 3)]
+    first = next(i for i, sp in enumerate(splits) if sp > 1)
+    assert all(sp == 1 for sp in splits[:first]) and all(sp > 1 for sp in splits[first:]) and first >= 50
+    for i in range(3 * first, n, 3):
+        c, _ = wt.wt_config_get(ctx, i)
+        assert wt.wt_config_find(ctx, c.bm, c.bn, c.bk, c.nwave, c.stages, 0, 1) < 3 * first
     with pytest.raises(wt.WtError):
         wt.wt_config_find(ctx, 48, 48, 64, 4, 2, 0)
+    with pytest.raises(wt.WtError):
+        wt.wt_config_find(ctx, 128, 128, 64, 4, 3, 0, 3)
 
 
 def test_device_calls_refused_on_host_context(ctx):
@@ -73,7 +84,7 @@ def test_wave_counts_bit_exact(ctx):
         c, r = wt.wt_config_get(ctx, i)
         cap = geo.capacity(1)
         for (M, N, K) in shapes:
-            G, L = geo.phi_gemm(M, N, K, c.bm, c.bn, c.bk)
+            G, L = geo.phi_gemm(M, N, K, c.bm, c.bn, c.bk, c.split)
             assert wt.wt_wave_count(ctx, M, N, K, c) == (G, L, geo.wave_count(G, cap))
     # in the occupancy-aware mode an occupancy override moves the wave boundaries
     c, r = wt.wt_config_get(ctx, 0)
@@ -95,6 +106,19 @@ def test_sampler_bit_exact(cap, I):
     assert [(int(a), int(b), int(c)) for a, b, c in zip(g, m, n)] == [(s.g, s.m, s.n) for s in want]
 
 
+@pytest.mark.parametrize("cap", [256, 512, 768, 250, 12])
+@pytest.mark.parametrize("S", [2, 4, 8])
+@pytest.mark.parametrize("I", [1, 3, 4])
+def test_sampler_split_bit_exact(cap, S, I):
+    """Split-K keys: task counts are multiples of S; the library derives the tile-count interval and
+    searches it, the oracle scans task counts downwards -- same samples."""
+    W = 12
+    g, m, n = wt.wt_sample_grid(cap, W, I, split=S)
+    want = smp.sample_set(cap, W, I, S=S)
+    assert [(int(a), int(b), int(c)) for a, b, c in zip(g, m, n)] == [(s.g, s.m, s.n) for s in want]
+    assert all(int(a) == S * int(b) * int(c) for a, b, c in zip(g, m, n))
+
+
 def test_sampler_other_tau():
     for tnum, tden in ((3, 2), (1, 1), (2, 1)):
         g, m, n = wt.wt_sample_grid(132, 5, 4, tnum, tden)
@@ -108,13 +132,15 @@ def _synthetic_samples(keys, W, I, noise_seed=None):
     for k, kd in enumerate(keys):
         th = wt_synth.random_theta(300 + k, W)
         scale = (kd.bm * kd.bn * kd.bk) / (128.0 * 128 * 64)      # bigger tiles cost more per (tile x loop)
-        for s in smp.sample_set(kd.cap, W, I):
-            if s.g == 0:
-                continue
-            for L in smp.loop_anchors(K_ANCHORS, kd.bk):
+        # split-K keys are profiled for the first waves only and cost a little extra per task
+        Wk = W if kd.split == 1 else min(W, W_SPLIT)
+        for s in smp.sample_set(kd.cap, Wk, I, S=kd.split):
+            if s.g == 0 or not geo.split_fits(s.m * kd.bm, s.n * kd.bn, kd.bm, kd.bn, kd.split):
+                continue                              # no such grid, or it cannot run: never profiled
+            for L in smp.loop_anchors(K_ANCHORS, kd.bk, kd.split):
                 for micro in range(3):
                     a, b, c, d = th[s.w - 1]
-                    t = scale * (a * s.g * L + b * s.g) + c * L + d
+                    t = scale * (a * s.g * L + b * s.g * (1.0 + 0.05 * (kd.split > 1))) + c * L + d
                     t *= 1.0 + 0.03 * ((micro + L // 8 + k) % 3)     # micro preference varies with L
                     recs.append((k, micro, s.g, L, s.w, 0, t))
     arr = np.array(recs, dtype=wt.SAMPLE_DTYPE)
@@ -150,7 +176,7 @@ def test_fit_and_select_parity(ctx, tmp_path, noise_seed):
         key, micro, t = osel.select(table, M, N, K)
         c = wt.wt_select(ctx, M, N, K)
         kd = keys[key]
-        assert (c.bm, c.bn, c.bk, c.nwave, c.stages, c.swizzle) == (kd.bm, kd.bn, kd.bk, kd.nwave, kd.stages, micro)
+        assert (c.bm, c.bn, c.bk, c.nwave, c.stages, c.swizzle, c.split) == (kd.bm, kd.bn, kd.bk, kd.nwave, kd.stages, micro, kd.split)
         assert wt.wt_predict_us(ctx, M, N, K, c) == t        # same bits, not merely close
     # (3) load round trip gives the same decisions
     ctx2 = wt.wt_create(-1, wt.WT_BF16, wt.WT_OUT_F32)
@@ -163,6 +189,44 @@ def test_fit_and_select_parity(ctx, tmp_path, noise_seed):
             assert wt.wt_select(ctx2, M, N, K).id == wt.wt_select(ctx, M, N, K).id
     finally:
         wt.wt_destroy(ctx2)
+
+
+def test_split_keys_in_selection(ctx, tmp_path):
+    """Split-K keys take part in Stage I with G = S*tiles and L = ceil(K/(S*bk)); outside their profiled
+    waves (no bucket, no extrapolation tuple) and where their partial tiles exceed the workspace they are
+    not candidates.  Decisions and predictions equal the oracle's bit for bit."""
+    W, I, p = 12, 4, 5
+    keys = _keys(ctx)
+    samples = _synthetic_samples(keys, W, I, noise_seed=21)
+    grid = wt.make_grid(W=W, I=I, p=p, k_anchors=K_ANCHORS, W_split=W_SPLIT)
+    wt.wt_fit(ctx, grid, samples)
+    path = str(tmp_path / "split.wt")
+    wt.wt_save(ctx, path)
+    table, _ = osel.read_table(path)
+    assert table.keys == keys
+    # the plan holds exactly the records the oracle's sampler enumerates (3 micros each)
+    n_plan, *_ = wt.wt_sample_plan(ctx, grid)
+    assert n_plan == len(samples)
+    picked_split = 0
+    shapes = wt_synth.sweep_shapes() + wt_synth.stream_shapes(1500) + [(256, 256, 8192), (64, 512, 16384), (8, 1024, 4096)]
+    for (M, N, K) in shapes:
+        key, micro, t = osel.select(table, M, N, K)
+        c = wt.wt_select(ctx, M, N, K)
+        assert c.id == 3 * key + micro and wt.wt_predict_us(ctx, M, N, K, c) == t
+        picked_split += keys[key].split > 1
+    assert picked_split > 20
+    for k, kd in enumerate(keys):
+        if kd.split == 1:
+            continue
+        cfg, _ = wt.wt_config_get(ctx, 3 * k)
+        assert not table.ext[k].status                       # nothing profiled in the last p waves
+        M = N = 16 * 1024                                     # far beyond the profiled waves
+        G, L = geo.phi_gemm(M, N, 4096, kd.bm, kd.bn, kd.bk, kd.split)
+        assert geo.wave_count(G, kd.cap) > W_SPLIT
+        with pytest.raises(wt.WtError) as e:
+            wt.wt_predict_us(ctx, M, N, 4096, cfg)
+        fits = geo.split_fits(M, N, kd.bm, kd.bn, kd.split)
+        assert e.value.status == (wt.WT_ERR_NOT_FITTED if fits else wt.WT_ERR_INFEASIBLE)
 
 
 def _pred_close(th_a, th_b, kd):
@@ -216,7 +280,7 @@ def test_ablation_models_parity(ctx, tmp_path, model):
         key, micro, t = osel.select(table, M, N, K)
         c = wt.wt_select(ctx, M, N, K)
         kd = keys[key]
-        assert (c.bm, c.bn, c.bk, c.nwave, c.stages, c.swizzle) == (kd.bm, kd.bn, kd.bk, kd.nwave, kd.stages, micro)
+        assert (c.bm, c.bn, c.bk, c.nwave, c.stages, c.swizzle, c.split) == (kd.bm, kd.bn, kd.bk, kd.nwave, kd.stages, micro, kd.split)
     with pytest.raises(wt.WtError):
         wt.wt_fit(ctx, wt.make_grid(W=W, I=I, p=p, k_anchors=K_ANCHORS, model=7), samples)
 
@@ -265,6 +329,8 @@ def test_single_row_family_parity(ctx, tmp_path):
     rows = []
     for k, kd in enumerate(keys):
         th = wt_synth.random_theta(900 + k, W_row)
+        if kd.split > 1:
+            continue                                  # the row family exists for unsplit keys only
         for s in smp.row_sample_set(kd.cap, W_row, I):
             for L in smp.loop_anchors(K_ANCHORS, kd.bk):
                 for micro in range(3):

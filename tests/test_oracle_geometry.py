@@ -194,3 +194,47 @@ def test_single_row_sample_set():
         a, b = smp.sub_interval(s.w, s.i, 132, 3)
         assert s.g == b and geo.wave_count(s.g, 132) == s.w
         assert geo.phi_gemm(*smp.instantiate(s.m, s.n, 7, 16, 64, 128), 16, 64, 128) == (s.g, 7)
+
+
+# ---- split-K reading of Phi and of the sampler ------------------------------------------------------
+def test_split_phi_partitions_the_k_tiles():
+    """S blocks per tile, each with L = ceil(ceil(K/BK)/S) k-tiles: the ranges [s*L, (s+1)*L) clipped to
+    the tile's ceil(K/BK) k-tiles cover each of them exactly once, L is the longest range, and the
+    nested ceiling equals ceil(K/(S*BK)).  S = 1 is Table 2's row unchanged."""
+    for K in (8, 64, 100, 1000, 1024, 4096, 4104, 11008, 28672):
+        for BK in (32, 64, 128, 256):
+            Lt = math.ceil(Fraction(K, BK))
+            assert geo.phi_gemm(300, 500, K, 128, 64, BK) == (3 * 8, Lt) == geo.phi_gemm(300, 500, K, 128, 64, BK, 1)
+            for S in (2, 4, 8):
+                G, L = geo.phi_gemm(300, 500, K, 128, 64, BK, S)
+                assert G == S * 3 * 8
+                assert L == math.ceil(Fraction(K, S * BK))
+                ranges = [range(s * L, min(Lt, (s + 1) * L)) for s in range(S)]
+                assert sorted(t for r in ranges for t in r) == list(range(Lt))
+                assert max(len(r) for r in ranges) == L
+
+
+def test_split_workspace_rule():
+    assert geo.split_fits(10**6, 10**6, 256, 256, 1)
+    # 2^26 floats hold 1024 tiles of 128x128 split in 4, and not one more
+    assert geo.split_fits(128 * 32, 128 * 32, 128, 128, 4)
+    assert not geo.split_fits(128 * 32 + 1, 128 * 32, 128, 128, 4)
+    assert geo.split_fits(16 * 256, 16 * 256, 16, 16, 2) and not geo.split_fits(16 * 256 + 1, 16 * 256, 16, 16, 2)  # 2^16 tiles
+
+
+@pytest.mark.parametrize("cap,S", [(8, 2), (12, 4), (64, 2), (64, 8), (132, 4), (256, 8)])
+def test_split_sampler_brute_force(cap, S):
+    """Every split-K representative is the largest multiple of S in its sub-interval whose tile count
+    has any factorisation with 1 <= n/m <= tau, found here by trying all (m, n)."""
+    I, W = 4, 6
+    for smp_ in smp.sample_set(cap, W, I, S=S):
+        a, b = smp.sub_interval(smp_.w, smp_.i, cap, I)
+        ok = [S * m * n for m in range(1, b + 1) for n in range(m, b // m + 1)
+              if a <= S * m * n <= b and 10 * n <= 11 * m]
+        assert smp_.g == (max(ok) if ok else 0)
+        if smp_.g:
+            assert smp_.g == S * smp_.m * smp_.n and smp_.m <= smp_.n and 10 * smp_.n <= 11 * smp_.m
+            assert geo.wave_count(smp_.g, cap) == smp_.w
+    assert smp.sample_set(cap, W, I, S=1) == smp.sample_set(cap, W, I)
+    assert smp.loop_anchors((1024, 2048, 3072), 64, S) == sorted({math.ceil(Fraction(k, 64 * S)) for k in (1024, 2048, 3072)})
+    assert smp.instantiate(3, 4, 5, 128, 64, 32, S) == (384, 256, 5 * 32 * S)
