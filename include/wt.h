@@ -141,6 +141,31 @@ int wt_set_capacity_mode(wt_ctx* ctx, int mode);
 int wt_gemm(wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
             const float* scaleA, const float* scaleB, wt_cfg cfg, void* hip_stream);
 
+/* ---- grouped GEMM (Table 2, grouped-GEMM row: G = sum_e ceil(M_e/bm) * ceil(N/bn), L = ceil(K/bk)) ---- */
+/* For every group e in [0, groups): C[r0:r1, :] = A[r0:r1, :] * B[e]^T with r0 = offsets[e], r1 = offsets[e+1].
+ * A: [M_total, K] rows of all groups back to back; B: [groups, N, K]; C: [M_total, N]; all device pointers.
+ * group_offsets: DEVICE pointer to groups+1 ascending int32 row offsets (offsets[0] = 0, offsets[groups] =
+ * M_total), read by the kernel -- the host never needs the routing result, so no synchronisation is needed
+ * between the router and this call.  Entries are clipped to [0, M_total] on the device, so wrong contents give
+ * wrong results but never an access outside A, B or C.  The grid is sized for the worst case
+ * (ceil(M_total/bm) + groups row tiles); surplus blocks exit at once.  groups <= 1024; cfg.split must be 1
+ * (WT_ERR_UNSUPPORTED_CFG otherwise).  Asynchronous, never allocates. */
+int wt_gemm_grouped(wt_ctx* ctx, int32_t groups, const int32_t* group_offsets, int64_t M_total, int64_t N,
+                    int64_t K, const void* A, const void* B, void* C, const float* scaleA, const float* scaleB,
+                    wt_cfg cfg, void* hip_stream);
+/* wt_time_gemm's protocol for a grouped launch. */
+int wt_time_gemm_grouped(wt_ctx* ctx, int32_t groups, const int32_t* group_offsets, int64_t M_total, int64_t N,
+                         int64_t K, const void* A, const void* B, void* C, const float* scaleA,
+                         const float* scaleB, wt_cfg cfg, int warmup, int iters, void* hip_stream,
+                         double* mean_us);
+/* Exact Phi of a grouped launch whose per-group row counts are known (host pointer, groups entries). */
+int wt_wave_count_grouped(const wt_ctx* ctx, int32_t groups, const int64_t* group_rows, int64_t N, int64_t K,
+                          wt_cfg cfg, int64_t* G, int64_t* L, int32_t* w);
+/* Runtime selection for a grouped launch from the dense dual table (Sec. 4.2: grouped GEMM is sampled as the
+ * single-group case) under the uniform approximation of Sec. 5.2: per-group counts are unknown on the host, so
+ * each group is taken to hold ceil(M_total/groups) rows.  Split-K keys are not candidates.  Host only. */
+int wt_select_grouped(const wt_ctx* ctx, int32_t groups, int64_t M_total, int64_t N, int64_t K, wt_cfg* out);
+
 /* Diagnostic: the (tile row, tile column) that workgroup `block` of a tiles_m x tiles_n grid computes
  * under rasterisation mode `swizzle` -- the kernel's own mapping evaluated on the host.  Host only. */
 int wt_tile_coords(int tiles_m, int tiles_n, int swizzle, int block, int* tm, int* tn);

@@ -130,6 +130,22 @@ def gemm_c(a_bits: np.ndarray, b_bits: np.ndarray, in_type: str = "bf16",
     return c
 
 
+def grouped_gemm_c(a_bits: np.ndarray, b_bits: np.ndarray, offsets, in_type: str = "bf16",
+                   scale_a: float = 1.0, scale_b: float = 1.0) -> np.ndarray:
+    """Grouped GEMM by its definition (Table 2, grouped-GEMM row; MoE: the rows routed to expert e are
+    multiplied by expert e's weights): for every group e, C[r0:r1] = A[r0:r1] * B[e]^T with
+    r0, r1 = offsets[e], offsets[e+1].  a_bits [M_total, K], b_bits [E, N, K]; one plain dense product
+    per group, rows outside every group stay NaN so that a test notices if they are touched."""
+    E, N, K = b_bits.shape
+    assert len(offsets) == E + 1 and a_bits.shape[1] == K
+    c = np.full((a_bits.shape[0], N), np.nan, dtype=np.float64)
+    for e in range(E):
+        r0, r1 = int(offsets[e]), int(offsets[e + 1])
+        if r1 > r0:
+            c[r0:r1] = gemm_c(a_bits[r0:r1], b_bits[e], in_type, scale_a, scale_b)
+    return c
+
+
 # ---- comparison metrics used by the parity tests ---------------------------------------------
 def rel_frobenius(c: np.ndarray, c_ref: np.ndarray) -> float:
     """||C - C_ref||_F / ||C_ref||_F (0 when both are all-zero)."""

@@ -49,6 +49,19 @@ def split_fits(M: int, N: int, BM: int, BN: int, S: int, ws_elems: int = WS_ELEM
     return tiles <= max_tiles and tiles * S * BM * BN <= ws_elems
 
 
+def phi_grouped(rows, N: int, K: int, BM: int, BN: int, BK: int) -> tuple[int, int]:
+    """Table 2, Grouped-GEMM row: G = sum_i ceil(M_i/T_M) * ceil(N/T_N), L = ceil(K/T_K)."""
+    return sum(ceil_div(int(m), BM) * ceil_div(N, BN) for m in rows), ceil_div(K, BK)
+
+
+def uniform_rows(M_total: int, E: int) -> list[int]:
+    """Uniform approximation of the routing (Sec. 5.2, grouped-GEMM paragraph): the host does not know the
+    per-expert counts, so every one of the E groups is taken to hold ceil(M_total / E) rows."""
+    if E < 1:
+        raise ValueError("E >= 1")
+    return [ceil_div(M_total, E)] * E
+
+
 def capacity(occ: int, n_cu: int = N_CU) -> int:
     """Blocks that can be resident at once: compute units times resident blocks per unit.
 

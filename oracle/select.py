@@ -12,7 +12,7 @@ import struct
 import numpy as np
 
 from .fit import Bucket, DualTable, KeyDesc
-from .geometry import phi_gemm, split_fits, wave_count
+from .geometry import phi_gemm, phi_grouped, split_fits, uniform_rows, wave_count
 
 
 def predict(theta, G: int, L: int) -> float:
@@ -61,6 +61,32 @@ def select(table: DualTable, M: int, N: int, K: int):
         G, L = phi_gemm(M, N, K, kd.bm, kd.bn, kd.bk, kd.split)
         w = wave_count(G, kd.cap)
         b = bucket_for(table, k, w, 1 if M <= kd.bm else 0)     # one tile row <=> M <= T_M
+        if b is None:
+            continue
+        t = predict(b.theta, G, L)
+        if math.isnan(t):
+            continue
+        if best is None or t < best[0]:
+            best = (t, k, b, L)
+    if best is None:
+        return None
+    t, k, b, L = best
+    _, micro = nearest_anchor(b.anchors, L) if b.anchors else (0, 0)
+    return k, micro, t
+
+
+def select_grouped(table: DualTable, E: int, M_total: int, N: int, K: int):
+    """Grouped GEMM at run time: the dense table serves (Sec. 4.2 samples grouped GEMM as the single-group
+    case); G comes from Table 2's grouped row evaluated on the uniform approximation of the routing
+    (Sec. 5.2).  Configurations that split K do not run grouped launches and are left out.  Otherwise the
+    two stages are those of select().  Returns (key, micro, T-hat) or None."""
+    rows = uniform_rows(M_total, E)
+    best = None
+    for k, kd in enumerate(table.keys):
+        if kd.split != 1:
+            continue
+        G, L = phi_grouped(rows, N, K, kd.bm, kd.bn, kd.bk)
+        b = bucket_for(table, k, wave_count(G, kd.cap), 1 if rows[0] <= kd.bm else 0)
         if b is None:
             continue
         t = predict(b.theta, G, L)

@@ -89,6 +89,11 @@ def lib():
             "wt_set_capacity_mode": [vp, C.c_int],
             "wt_tile_coords": [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)],
             "wt_gemm": [vp, i64, i64, i64, vp, vp, vp, vp, vp, wt_cfg, vp],
+            "wt_gemm_grouped": [vp, i32, vp, i64, i64, i64, vp, vp, vp, vp, vp, wt_cfg, vp],
+            "wt_time_gemm_grouped": [vp, i32, vp, i64, i64, i64, vp, vp, vp, vp, vp, wt_cfg, C.c_int, C.c_int, vp,
+                                     C.POINTER(C.c_double)],
+            "wt_wave_count_grouped": [vp, i32, vp, i64, i64, wt_cfg, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32)],
+            "wt_select_grouped": [vp, i32, i64, i64, i64, C.POINTER(wt_cfg)],
             "wt_wave_count": [vp, i64, i64, i64, wt_cfg, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32)],
             "wt_sample_grid": [i64, i32, i32, i32, i32, i32, vp, vp, vp, sz, C.POINTER(sz)],
             "wt_sample_plan": [vp, C.POINTER(wt_grid), C.POINTER(sz), C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)],
@@ -113,7 +118,8 @@ def lib():
 
 
 EXPORTS = ("wt_create", "wt_destroy", "wt_last_hip_error", "wt_status_string", "wt_config_count", "wt_config_get",
-           "wt_config_find", "wt_key_count", "wt_key_set_occ", "wt_set_capacity_mode", "wt_tile_coords", "wt_gemm", "wt_wave_count", "wt_sample_grid",
+           "wt_config_find", "wt_key_count", "wt_key_set_occ", "wt_set_capacity_mode", "wt_tile_coords", "wt_gemm", "wt_gemm_grouped",
+           "wt_time_gemm_grouped", "wt_wave_count_grouped", "wt_select_grouped", "wt_wave_count", "wt_sample_grid",
            "wt_sample_plan", "wt_profile_sparse", "wt_time_gemm", "wt_mfma_ceiling", "wt_fit", "wt_select", "wt_predict_us",
            "wt_select_bench", "wt_save", "wt_load")
 
@@ -208,6 +214,35 @@ def wt_tile_coords(tiles_m, tiles_n, swizzle, block):
 def wt_gemm(ctx, M, N, K, A, B, Cout, cfg, scaleA=None, scaleB=None, stream=None):
     _check(lib().wt_gemm(ctx, M, N, K, _ptr(A), _ptr(B), _ptr(Cout), _ptr(scaleA), _ptr(scaleB), cfg,
                          _stream(stream)), "wt_gemm")
+
+
+def wt_gemm_grouped(ctx, groups, offsets, M_total, N, K, A, B, Cout, cfg, scaleA=None, scaleB=None, stream=None):
+    """offsets: device int32 tensor of groups+1 row offsets."""
+    _check(lib().wt_gemm_grouped(ctx, groups, _ptr(offsets), M_total, N, K, _ptr(A), _ptr(B), _ptr(Cout),
+                                 _ptr(scaleA), _ptr(scaleB), cfg, _stream(stream)), "wt_gemm_grouped")
+
+
+def wt_time_gemm_grouped(ctx, groups, offsets, M_total, N, K, A, B, Cout, cfg, warmup=3, iters=5, scaleA=None,
+                         scaleB=None, stream=None) -> float:
+    us = C.c_double()
+    _check(lib().wt_time_gemm_grouped(ctx, groups, _ptr(offsets), M_total, N, K, _ptr(A), _ptr(B), _ptr(Cout),
+                                      _ptr(scaleA), _ptr(scaleB), cfg, warmup, iters, _stream(stream),
+                                      C.byref(us)), "wt_time_gemm_grouped")
+    return us.value
+
+
+def wt_wave_count_grouped(ctx, group_rows, N, K, cfg):
+    rows = np.ascontiguousarray(np.asarray(group_rows, dtype=np.int64))
+    G, L, w = C.c_int64(), C.c_int64(), C.c_int32()
+    _check(lib().wt_wave_count_grouped(ctx, len(rows), rows.ctypes.data, N, K, cfg, C.byref(G), C.byref(L),
+                                       C.byref(w)), "wt_wave_count_grouped")
+    return G.value, L.value, w.value
+
+
+def wt_select_grouped(ctx, groups, M_total, N, K) -> wt_cfg:
+    c = wt_cfg()
+    _check(lib().wt_select_grouped(ctx, groups, M_total, N, K, C.byref(c)), "wt_select_grouped")
+    return c
 
 
 def wt_time_gemm(ctx, M, N, K, A, B, Cout, cfg, warmup=3, iters=5, scaleA=None, scaleB=None, stream=None) -> float:

@@ -61,6 +61,12 @@ struct GemmArgs {
     int k_per_split;    // Ls * BK elements (multiple of BK); unused when S == 1
     float* ws;          // S > 1: tiles * S slabs of BM*BN floats
     int* counters;      // S > 1: one arrival counter per tile, zero before and after every launch
+    // Grouped GEMM (Table 2, grouped row): rows [off[e], off[e+1]) of A and C belong to group e and
+    // are multiplied by B[e] (N x K each).  group_offsets: device pointer to groups+1 ascending row
+    // offsets, NULL for a dense GEMM.  M is then the total row count and tiles_m an upper bound
+    // (ceil(M/BM) + groups) on the number of row tiles; surplus blocks exit at once.
+    const int* group_offsets;
+    int groups;
 };
 
 constexpr int kWave = 64;
@@ -221,7 +227,26 @@ __global__ __launch_bounds__(WM* WN* kWave) void gemm_kernel(const GemmArgs args
     }
     int tm, tn;
     tile_coords(tile, args.tiles_m, args.tiles_n, args.swizzle, tm, tn);
-    const int row0 = tm * BM, col0 = tn * BN;
+    int row0 = tm * BM, m_end = args.M;
+    const int col0 = tn * BN;
+    const char* Bbase = static_cast<const char*>(args.B);
+    if (args.group_offsets) {
+        // tm counts row tiles over the groups' concatenated tile lists: find the group it falls in.
+        // Offsets are read on the device (the host never learns the routing) and clipped to [0, M],
+        // so whatever they hold, every access stays inside A, B[0..groups) and C.
+        int e = 0, first = 0, lo = 0, hi = 0;
+        for (; e < args.groups; ++e) {
+            lo = min(max(args.group_offsets[e], 0), args.M);
+            hi = min(max(args.group_offsets[e + 1], lo), args.M);
+            const int t = (hi - lo + BM - 1) / BM;
+            if (tm < first + t) break;
+            first += t;
+        }
+        if (e == args.groups) return;  // past the last row tile
+        row0 = lo + (tm - first) * BM;
+        m_end = hi;
+        Bbase += static_cast<int64_t>(e) * args.N * (static_cast<int64_t>(args.K) * T::esize);
+    }
     // this block's k range [k0, k0 + K): the whole of args.K unless split
     int k0 = 0, K = args.K;
     if (args.splits > 1) {
@@ -241,8 +266,8 @@ __global__ __launch_bounds__(WM* WN* kWave) void gemm_kernel(const GemmArgs args
         return b > static_cast<int64_t>(kOobOffset) ? kOobOffset : static_cast<uint32_t>(b);
     };
     const i32x4 rsrcA = make_rsrc(static_cast<const char*>(args.A) + static_cast<int64_t>(row0) * row_bytes + k0_bytes,
-                                  records(args.M - row0));
-    const i32x4 rsrcB = make_rsrc(static_cast<const char*>(args.B) + static_cast<int64_t>(col0) * row_bytes + k0_bytes,
+                                  records(m_end - row0));
+    const i32x4 rsrcB = make_rsrc(Bbase + static_cast<int64_t>(col0) * row_bytes + k0_bytes,
                                   records(args.N - col0));
     // Load slot t of this wavefront fills the 1 KiB LDS piece j = wv + t*NW of a stage.  The lane's
     // source offset at k-tile 0 stays in a register for the whole kernel; the k advance is a scalar.
@@ -513,7 +538,7 @@ __global__ __launch_bounds__(WM* WN* kWave) void gemm_kernel(const GemmArgs args
     // ---- epilogue ---------------------------------------------------------------------------------
     float scale = 1.0f;
     if constexpr (IN == 1) scale = args.scaleA[0] * args.scaleB[0];
-    const int M = args.M, N = args.N;
+    const int M = m_end, N = args.N;
 #pragma unroll
     for (int i = 0; i < T::FM; ++i) {
 #pragma unroll

@@ -35,24 +35,44 @@ int validate_shape(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K) {
     return WT_OK;
 }
 
-int launch(wt_ctx* ctx, const Config& c, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
-           const float* sA, const float* sB, hipStream_t stream) {
+// One GEMM problem as the launch code sees it; groups == 0 is the dense case.
+struct Problem {
+    int64_t M, N, K;
+    const void* A;
+    const void* B;
+    void* C;
+    const float* sA;
+    const float* sB;
+    int groups = 0;
+    const int32_t* offsets = nullptr;  // device, groups + 1 entries
+};
+
+constexpr int kMaxGroups = 1024;
+
+int launch(wt_ctx* ctx, const Config& c, const Problem& p, hipStream_t stream) {
     const Key& key = ctx->keys[c.res.key_id];
-    const int64_t tiles_m = ceil_div64(M, c.cfg.bm), tiles_n = ceil_div64(N, c.cfg.bn);
-    int64_t tiles, G, L;
-    key_phi(key, M, N, K, &tiles, &G, &L);
-    if (G == 0) return WT_OK;
+    int64_t tiles_m = ceil_div64(p.M, c.cfg.bm);
+    const int64_t tiles_n = ceil_div64(p.N, c.cfg.bn);
+    if (p.M == 0 || p.N == 0) return WT_OK;
+    if (p.groups > 0) {
+        if (key.split != 1) return WT_ERR_UNSUPPORTED_CFG;  // grouped launches do not split K
+        tiles_m += p.groups;  // every group may end in a partial row tile; surplus blocks exit at once
+    }
+    const int64_t tiles = tiles_m * tiles_n, G = tiles << key.sh_s;
     if (G > 0x7FFFFFFF) return WT_ERR_INVALID_ARG;
     if (!key_fits(key, tiles)) return WT_ERR_INFEASIBLE;
     GemmArgs args;
-    args.A = A; args.B = B; args.C = C; args.scaleA = sA; args.scaleB = sB;
-    args.M = (int)M; args.N = (int)N; args.K = (int)K;
+    args.A = p.A; args.B = p.B; args.C = p.C; args.scaleA = p.sA; args.scaleB = p.sB;
+    args.M = (int)p.M; args.N = (int)p.N; args.K = (int)p.K;
     args.tiles_m = (int)tiles_m; args.tiles_n = (int)tiles_n;
     args.swizzle = c.cfg.swizzle;
     args.splits = key.split;
-    args.k_per_split = (int)(L * key.bk);  // L = ceil(K / (S*bk)) k-tiles per block
+    // each block of a split tile walks L = ceil(K / (S*bk)) k-tiles
+    args.k_per_split = (int)(ceil_div64(p.K, (int64_t)key.bk * key.split) * key.bk);
     args.ws = ctx->ws;
     args.counters = ctx->counters;
+    args.group_offsets = p.groups > 0 ? p.offsets : nullptr;
+    args.groups = p.groups;
     if (key.split > 1 && (!ctx->ws || !ctx->counters)) return WT_ERR_NO_DEVICE;
     void* params[] = {&args};
     WT_HIP(ctx, hipLaunchKernel(c.fn, dim3((unsigned)G), dim3((unsigned)(c.cfg.nwave * 64)), params,
@@ -60,26 +80,26 @@ int launch(wt_ctx* ctx, const Config& c, int64_t M, int64_t N, int64_t K, const 
     return WT_OK;
 }
 
-int check_gemm_args(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
-                    const float* sA, const float* sB, const wt_cfg& cfg, int* id) {
+int check_gemm_args(const wt_ctx* ctx, const Problem& p, const wt_cfg& cfg, int* id) {
     if (!ctx) return WT_ERR_INVALID_ARG;
     if (ctx->device < 0) return WT_ERR_NO_DEVICE;
-    const int rc = validate_shape(ctx, M, N, K);
+    const int rc = validate_shape(ctx, p.M, p.N, p.K);
     if (rc != WT_OK) return rc;
-    if (M * N > 0 && (!C || (K > 0 && (!A || !B)))) return WT_ERR_INVALID_ARG;
-    if (ctx->in_type == WT_FP8_E4M3 && M * N > 0 && (!sA || !sB)) return WT_ERR_INVALID_ARG;
+    if (p.groups < 0 || p.groups > kMaxGroups) return WT_ERR_INVALID_ARG;
+    if (p.groups > 0 && p.M > 0 && !p.offsets) return WT_ERR_INVALID_ARG;
+    if (p.M * p.N > 0 && (!p.C || (p.K > 0 && (!p.A || !p.B)))) return WT_ERR_INVALID_ARG;
+    if (ctx->in_type == WT_FP8_E4M3 && p.M * p.N > 0 && (!p.sA || !p.sB)) return WT_ERR_INVALID_ARG;
     *id = find_config(ctx, cfg);
     if (*id < 0) return WT_ERR_UNSUPPORTED_CFG;
     if (ctx->cfgs[*id].res.occ < 1) return WT_ERR_INFEASIBLE;
     return WT_OK;
 }
 
-int time_config(wt_ctx* ctx, const Config& c, int64_t M, int64_t N, int64_t K, const void* A, const void* B,
-                void* C, const float* sA, const float* sB, int warmup, int iters, hipStream_t stream,
+int time_config(wt_ctx* ctx, const Config& c, const Problem& p, int warmup, int iters, hipStream_t stream,
                 double* mean_us) {
     hipEvent_t e0 = (hipEvent_t)ctx->ev_start, e1 = (hipEvent_t)ctx->ev_stop;
     for (int i = 0; i < warmup; ++i) {
-        const int rc = launch(ctx, c, M, N, K, A, B, C, sA, sB, stream);
+        const int rc = launch(ctx, c, p, stream);
         if (rc != WT_OK) return rc;
     }
     // Timed batch: `iters` back-to-back launches between one event pair.  A batch shorter than
@@ -89,7 +109,7 @@ int time_config(wt_ctx* ctx, const Config& c, int64_t M, int64_t N, int64_t K, c
     for (int pass = 0; pass < 2; ++pass) {
         WT_HIP(ctx, hipEventRecord(e0, stream));
         for (int i = 0; i < iters; ++i) {
-            const int rc = launch(ctx, c, M, N, K, A, B, C, sA, sB, stream);
+            const int rc = launch(ctx, c, p, stream);
             if (rc != WT_OK) return rc;
         }
         WT_HIP(ctx, hipEventRecord(e1, stream));
@@ -251,9 +271,10 @@ int wt_tile_coords(int tiles_m, int tiles_n, int swizzle, int block, int* tm, in
 int wt_gemm(wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C, const float* scaleA,
             const float* scaleB, wt_cfg cfg, void* hip_stream) {
     int id = -1;
-    const int rc = check_gemm_args(ctx, M, N, K, A, B, C, scaleA, scaleB, cfg, &id);
+    const Problem p{M, N, K, A, B, C, scaleA, scaleB};
+    const int rc = check_gemm_args(ctx, p, cfg, &id);
     if (rc != WT_OK) return rc;
-    return launch(ctx, ctx->cfgs[id], M, N, K, A, B, C, scaleA, scaleB, (hipStream_t)hip_stream);
+    return launch(ctx, ctx->cfgs[id], p, (hipStream_t)hip_stream);
 }
 
 int wt_time_gemm(wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
@@ -261,10 +282,32 @@ int wt_time_gemm(wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, co
                  double* mean_us) {
     int id = -1;
     if (!mean_us || warmup < 0 || iters < 1) return WT_ERR_INVALID_ARG;
-    const int rc = check_gemm_args(ctx, M, N, K, A, B, C, scaleA, scaleB, cfg, &id);
+    const Problem p{M, N, K, A, B, C, scaleA, scaleB};
+    const int rc = check_gemm_args(ctx, p, cfg, &id);
     if (rc != WT_OK) return rc;
-    return time_config(ctx, ctx->cfgs[id], M, N, K, A, B, C, scaleA, scaleB, warmup, iters, (hipStream_t)hip_stream,
-                       mean_us);
+    return time_config(ctx, ctx->cfgs[id], p, warmup, iters, (hipStream_t)hip_stream, mean_us);
+}
+
+int wt_gemm_grouped(wt_ctx* ctx, int32_t groups, const int32_t* group_offsets, int64_t M_total, int64_t N, int64_t K,
+                    const void* A, const void* B, void* C, const float* scaleA, const float* scaleB, wt_cfg cfg,
+                    void* hip_stream) {
+    int id = -1;
+    if (groups < 1) return WT_ERR_INVALID_ARG;
+    const Problem p{M_total, N, K, A, B, C, scaleA, scaleB, groups, group_offsets};
+    const int rc = check_gemm_args(ctx, p, cfg, &id);
+    if (rc != WT_OK) return rc;
+    return launch(ctx, ctx->cfgs[id], p, (hipStream_t)hip_stream);
+}
+
+int wt_time_gemm_grouped(wt_ctx* ctx, int32_t groups, const int32_t* group_offsets, int64_t M_total, int64_t N,
+                         int64_t K, const void* A, const void* B, void* C, const float* scaleA, const float* scaleB,
+                         wt_cfg cfg, int warmup, int iters, void* hip_stream, double* mean_us) {
+    int id = -1;
+    if (!mean_us || warmup < 0 || iters < 1 || groups < 1) return WT_ERR_INVALID_ARG;
+    const Problem p{M_total, N, K, A, B, C, scaleA, scaleB, groups, group_offsets};
+    const int rc = check_gemm_args(ctx, p, cfg, &id);
+    if (rc != WT_OK) return rc;
+    return time_config(ctx, ctx->cfgs[id], p, warmup, iters, (hipStream_t)hip_stream, mean_us);
 }
 
 int wt_sample_plan(const wt_ctx* ctx, const wt_grid* grid, size_t* n_samples, size_t* bytesA, size_t* bytesB,
@@ -309,7 +352,8 @@ int wt_profile_sparse(wt_ctx* ctx, const wt_grid* grid, void* scrA, void* scrB, 
             const Config& c = ctx->cfgs[key.first_cfg + m];
             double us = 0;
             if (c.res.occ < 1) return (int)WT_ERR_INFEASIBLE;
-            const int r = time_config(ctx, c, M, N, K, scrA, scrB, scrC, sA, sB, grid->warmup, grid->iters, stream, &us);
+            const Problem p{M, N, K, scrA, scrB, scrC, sA, sB};
+            const int r = time_config(ctx, c, p, grid->warmup, grid->iters, stream, &us);
             if (r != WT_OK) return r;
             wt_sample s;
             memset(&s, 0, sizeof(s));

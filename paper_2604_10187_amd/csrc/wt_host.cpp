@@ -466,8 +466,14 @@ static inline double predict(const double th[4], int64_t G, int64_t L) {
     return t;
 }
 
-static int select_impl(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, int* key_out, int* micro_out,
+// groups = 0: dense GEMM of M rows.  groups > 0: grouped GEMM of M rows in total under the uniform
+// approximation (Sec. 5.2, grouped-GEMM discussion: per-expert counts are not known on the host without
+// a synchronisation): every group is taken to hold ceil(M/groups) rows, so G = groups * tiles of one
+// group (Table 2, grouped row), looked up in the dense table (Sec. 4.2 reduces grouped sampling to the
+// dense case).  Split-K keys do not run grouped launches and are skipped.
+static int select_impl(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, int groups, int* key_out, int* micro_out,
                        double* t_out) {
+    const int64_t Mg = groups > 0 ? ceil_div64(M, groups) : M;
     const Table& t = ctx->table;
     const int nk = static_cast<int>(ctx->keys.size());
     const Bucket* best_b = nullptr;
@@ -477,10 +483,15 @@ static int select_impl(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, int* 
     for (int k = 0; k < nk; ++k) {
         const Key& key = ctx->keys[k];
         int64_t tiles, G, L;
-        key_phi(key, M, N, K, &tiles, &G, &L);
-        if (!key_fits(key, tiles)) continue;
+        key_phi(key, Mg, N, K, &tiles, &G, &L);
+        if (groups > 0) {
+            if (key.split != 1) continue;
+            G *= groups;
+        } else if (!key_fits(key, tiles)) {
+            continue;
+        }
         const int64_t w = (G + key.cap - 1) / key.cap;
-        const Bucket* b = pick_bucket(t, k, w, M <= key.bm);
+        const Bucket* b = pick_bucket(t, k, w, Mg <= key.bm);
         if (!b) continue;
         const double th = predict(b->th, G, L);
         if (th != th) continue;
@@ -719,11 +730,43 @@ int wt_select(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, wt_cfg* out) {
     if (!ctx || !out || M < 0 || N < 0 || K < 0) return WT_ERR_INVALID_ARG;
     if (!ctx->table.fitted) return WT_ERR_NOT_FITTED;
     int key, micro;
-    const int rc = select_impl(ctx, M, N, K, &key, &micro, nullptr);
+    const int rc = select_impl(ctx, M, N, K, 0, &key, &micro, nullptr);
     if (rc != WT_OK) return rc;
     const Key& k = ctx->keys[key];
     if (micro < 0 || micro >= k.n_micro) micro = 0;
     *out = ctx->cfgs[k.first_cfg + micro].cfg;
+    return WT_OK;
+}
+
+int wt_select_grouped(const wt_ctx* ctx, int32_t groups, int64_t M_total, int64_t N, int64_t K, wt_cfg* out) {
+    if (!ctx || !out || groups < 1 || M_total < 0 || N < 0 || K < 0) return WT_ERR_INVALID_ARG;
+    if (!ctx->table.fitted) return WT_ERR_NOT_FITTED;
+    int key, micro;
+    const int rc = select_impl(ctx, M_total, N, K, groups, &key, &micro, nullptr);
+    if (rc != WT_OK) return rc;
+    const Key& k = ctx->keys[key];
+    if (micro < 0 || micro >= k.n_micro) micro = 0;
+    *out = ctx->cfgs[k.first_cfg + micro].cfg;
+    return WT_OK;
+}
+
+int wt_wave_count_grouped(const wt_ctx* ctx, int32_t groups, const int64_t* group_rows, int64_t N, int64_t K,
+                          wt_cfg cfg, int64_t* G, int64_t* L, int32_t* w) {
+    if (!ctx || groups < 1 || !group_rows || N < 0 || K < 0) return WT_ERR_INVALID_ARG;
+    const int id = find_config(ctx, cfg);
+    if (id < 0) return WT_ERR_UNSUPPORTED_CFG;
+    const Key& k = ctx->keys[ctx->cfgs[id].res.key_id];
+    if (k.split != 1) return WT_ERR_UNSUPPORTED_CFG;
+    int64_t g = 0, l = 0;
+    for (int e = 0; e < groups; ++e) {
+        if (group_rows[e] < 0) return WT_ERR_INVALID_ARG;
+        int64_t tiles, ge;
+        key_phi(k, group_rows[e], N, K, &tiles, &ge, &l);
+        g += ge;
+    }
+    if (G) *G = g;
+    if (L) *L = l;
+    if (w) *w = static_cast<int32_t>(ceil_div64(g, k.cap));
     return WT_OK;
 }
 

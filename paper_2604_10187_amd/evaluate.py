@@ -214,6 +214,58 @@ def cmd_large(a, torch):
     return out
 
 
+def cmd_grouped(a, torch):
+    """Grouped GEMM (MoE expert projections): synthetic skewed routing, every unsplit configuration timed
+    with the routing's real group sizes; the pick comes from wt_select_grouped, which sees only the number
+    of groups and the total row count (uniform approximation).
+    """
+    import wt_synth
+
+    ctx, path = _open_ctx(a, torch)
+    stream = torch.cuda.current_stream()
+    cfgs = [wt.wt_config_get(ctx, i) for i in range(wt.wt_config_count(ctx))]
+    rows = []
+    for (E, top_k, N, K) in wt_synth.MOE_LAYERS:
+        g = torch.Generator(device="cuda")
+        g.manual_seed(4000 + E + N)
+        B = torch.randn((E * N, K), device="cuda", generator=g).to(torch.bfloat16)
+        for tokens in wt_synth.MOE_TOKENS:
+            counts = wt_synth.moe_routing(tokens, E, top_k, seed=tokens + E, skew=1.0)
+            M_total = int(counts.sum())
+            off = torch.from_numpy(wt_synth.group_offsets(counts)).cuda()
+            A = torch.randn((M_total, K), device="cuda", generator=g).to(torch.bfloat16)
+            C = torch.empty((M_total, N), device="cuda", dtype=torch.bfloat16)
+            pick = wt.wt_select_grouped(ctx, E, M_total, N, K)
+            times, best = {}, math.inf
+            for i, (c, r) in enumerate(cfgs):
+                if c.split != 1 or r.occ < 1:
+                    continue
+                if i != pick.id and best < math.inf:
+                    t1 = wt.wt_time_gemm_grouped(ctx, E, off, M_total, N, K, A, B, C, c, 1, 1, stream=stream)
+                    if t1 > a.prune * best:
+                        continue
+                t = wt.wt_time_gemm_grouped(ctx, E, off, M_total, N, K, A, B, C, c, 3, 5, stream=stream)
+                times[i] = t
+                best = min(best, t)
+            best_id = min(times, key=times.get)
+            rows.append({"experts": E, "top_k": top_k, "tokens": tokens, "rows": M_total, "N": N, "K": K,
+                         "rows_per_expert_min_max": [int(counts.min()), int(counts.max())],
+                         "pick": list(pick.astuple()), "pick_us": times[pick.id],
+                         "best": list(cfgs[best_id][0].astuple()), "best_us": times[best_id],
+                         "frac": times[best_id] / times[pick.id],
+                         "pick_tflops": 2.0 * M_total * N * K / times[pick.id] / 1e6,
+                         "best_tflops": 2.0 * M_total * N * K / times[best_id] / 1e6, "n_timed": len(times)})
+            _log(f"[eval] grouped E={E} tokens={tokens} N={N} K={K}: frac {rows[-1]['frac']:.3f} "
+                 f"pick {rows[-1]['pick_us']:.1f}us {rows[-1]['pick_tflops']:.0f} TF")
+            del A, C
+        del B
+    fr = np.array([r["frac"] for r in rows])
+    summary = {"n_cases": len(rows), "geomean_frac": float(np.exp(np.mean(np.log(fr)))), "min_frac": float(fr.min()),
+               "frac_ge_95": float(np.mean(fr >= 0.95))}
+    return {"workload": "grouped GEMM, MoE expert projections, routing 1/rank skew, bf16", "table": path,
+            "summary": summary, "rows": rows}
+
+
 def cmd_ablate(a, torch=None):
     """CPU only.  Re-fit the saved profiling records under model / (W, I) variants with wt_fit on a
     host-only context and score each variant's picks against saved exhaustive timings (the `times` of
@@ -274,7 +326,7 @@ def cmd_ablate(a, torch=None):
 
 def main(argv=None):
     ap = argparse.ArgumentParser()
-    ap.add_argument("cmd", choices=["sweep", "wave", "stream", "large", "ablate"])
+    ap.add_argument("cmd", choices=["sweep", "wave", "stream", "large", "grouped", "ablate"])
     ap.add_argument("--samples", default=None, help="ablate: .npz with `samples` and `occ`")
     ap.add_argument("--scores", nargs="*", default=[], help="ablate: sweep/stream result files with exhaustive timings")
     ap.add_argument("--cap-mode", type=int, default=1)
@@ -294,7 +346,7 @@ def main(argv=None):
     else:
         import torch
 
-        res = {"sweep": cmd_sweep, "wave": cmd_wave, "stream": cmd_stream, "large": cmd_large}[a.cmd](a, torch)
+        res = {"sweep": cmd_sweep, "wave": cmd_wave, "stream": cmd_stream, "large": cmd_large, "grouped": cmd_grouped}[a.cmd](a, torch)
     txt = json.dumps(res)
     if a.out:
         open(a.out, "w").write(txt)

@@ -37,5 +37,21 @@ def run_gemm(ctx, cfg, a_bits, b_bits, out_type, scale_a=None, scale_b=None, fil
     return dC.float().cpu().numpy()
 
 
+def run_gemm_grouped(ctx, cfg, a_bits, b_bits, offsets, out_type, fill=None):
+    """Launch wt_gemm_grouped; a_bits [M_total, K], b_bits [E, N, K], offsets int32 [E+1] (copied to the GPU)."""
+    M, K = a_bits.shape
+    E, N, _ = b_bits.shape
+    dA, dB = dev_bits(a_bits), dev_bits(b_bits.reshape(E * N, K))
+    dOff = torch.from_numpy(np.asarray(offsets, dtype=np.int32).copy()).cuda()
+    dt = torch.float32 if out_type == wt.WT_OUT_F32 else torch.bfloat16
+    dC = torch.empty((M, N), dtype=dt, device="cuda")
+    if fill is not None:
+        dC.fill_(fill)
+    torch.cuda.synchronize()
+    wt.wt_gemm_grouped(ctx, E, dOff, M, N, K, dA, dB, dC, cfg, stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    return dC.float().cpu().numpy()
+
+
 def all_configs(ctx):
     return [wt.wt_config_get(ctx, i) for i in range(wt.wt_config_count(ctx))]

@@ -5,7 +5,7 @@ import torch
 
 import paper_2604_10187_amd as wt
 import wt_synth
-from gpu_util import all_configs, note, run_gemm
+from gpu_util import all_configs, note, run_gemm, run_gemm_grouped
 from oracle import gemm as og
 
 pytestmark = pytest.mark.gpu
@@ -161,6 +161,55 @@ def test_split_k_workspace_limit(ctx_f32):
     with pytest.raises(wt.WtError) as e:
         wt.wt_gemm(ctx_f32, M, N, 8, dA, dA, dA, cfg, stream=torch.cuda.current_stream())
     assert e.value.status == wt.WT_ERR_INFEASIBLE
+
+
+# ---- grouped GEMM ---------------------------------------------------------------------------------
+def test_grouped_integer_bit_exact(ctx_f32):
+    """Ragged groups (one empty, one of a single row, sizes that are no multiple of any tile) on integer
+    data: every unsplit structural key, one rasterisation mode each, must equal the oracle's per-group
+    products bit for bit, and must leave rows of no group untouched."""
+    counts = [130, 0, 17, 1, 300, 64]
+    off = wt_synth.group_offsets(counts)
+    E, N, K = len(counts), 200, 136
+    M_total = int(off[-1]) + 5                        # five trailing rows belong to no group
+    a32, _ = wt_synth.gemm_operands(M_total, 8, K, 8801, "int")
+    b32, _ = wt_synth.gemm_operands(E * N, 8, K, 8802, "int")
+    ab, bb = wt_synth.to_bf16_bits(a32), wt_synth.to_bf16_bits(b32).reshape(E, N, K)
+    want = og.grouped_gemm_c(ab, bb, off)
+    n = 0
+    for cfg, res in all_configs(ctx_f32):
+        if cfg.split != 1 or cfg.swizzle != (cfg.id // 3) % 3:
+            continue
+        note(f"grouped int-exact cfg={cfg.astuple()}")
+        got = run_gemm_grouped(ctx_f32, cfg, ab, bb, off, wt.WT_OUT_F32, fill=float("nan"))
+        assert np.array_equal(got[:off[-1]], want[:off[-1]]), f"{cfg}"
+        assert np.isnan(got[off[-1]:]).all()
+        n += 1
+    assert n >= 50
+    split_cfg = next(c for c, _ in all_configs(ctx_f32) if c.split > 1)
+    with pytest.raises(wt.WtError) as e:
+        run_gemm_grouped(ctx_f32, split_cfg, ab, bb, off, wt.WT_OUT_F32)
+    assert e.value.status == wt.WT_ERR_UNSUPPORTED_CFG
+
+
+def test_grouped_moe_layer_normal(ctx_bf16):
+    """A 128-expert / top-8 layer's fused gate+up projection (N = 1536, K = 2048) for 256 tokens with a
+    skewed synthetic routing, N(0,1) data, bf16 out, under three configurations."""
+    E, top_k, N, K = wt_synth.MOE_LAYERS[0]
+    counts = wt_synth.moe_routing(256, E, top_k, seed=77, skew=1.2)
+    off = wt_synth.group_offsets(counts)
+    M_total = int(off[-1])
+    assert M_total == 256 * top_k and counts.min() == 0
+    a32, _ = wt_synth.gemm_operands(M_total, 8, K, 8811)
+    b32, _ = wt_synth.gemm_operands(E * N, 8, K, 8812)
+    ab, bb = wt_synth.to_bf16_bits(a32), wt_synth.to_bf16_bits(b32).reshape(E, N, K)
+    want = og.grouped_gemm_c(ab, bb, off)
+    for fields in ((16, 64, 128, 4, 5, 0), (64, 64, 128, 4, 3, 1), (128, 128, 64, 4, 3, 2)):
+        cfg, _ = wt.wt_config_get(ctx_bf16, wt.wt_config_find(ctx_bf16, *fields))
+        note(f"grouped MoE layer cfg={cfg.astuple()} rows={M_total}")
+        got = run_gemm_grouped(ctx_bf16, cfg, ab, bb, off, wt.WT_OUT_BF16)
+        assert og.max_scaled_err(got, want) <= BF16_ELEM
+        assert og.max_scaled_err(got, want) <= 2.0 ** -8
 
 
 def test_degenerate_shapes_and_errors(ctx_f32):

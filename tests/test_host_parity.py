@@ -229,6 +229,36 @@ def test_split_keys_in_selection(ctx, tmp_path):
         assert e.value.status == (wt.WT_ERR_NOT_FITTED if fits else wt.WT_ERR_INFEASIBLE)
 
 
+def test_grouped_geometry_and_selection(ctx):
+    """Grouped GEMM: exact Phi for known per-group rows (Table 2, grouped row) and the uniform-approximation
+    selection on the dense table, both bit-exact against the oracle."""
+    W, I, p = 12, 4, 5
+    keys = _keys(ctx)
+    wt.wt_fit(ctx, wt.make_grid(W=W, I=I, p=p, k_anchors=K_ANCHORS, W_split=W_SPLIT), _synthetic_samples(keys, W, I, 31))
+    import tempfile
+    with tempfile.TemporaryDirectory() as d:
+        wt.wt_save(ctx, d + "/g.wt")
+        table, _ = osel.read_table(d + "/g.wt")
+    for (E, top_k, N, K) in wt_synth.MOE_LAYERS:
+        for tokens in wt_synth.MOE_TOKENS:
+            rows = wt_synth.moe_routing(tokens, E, top_k, seed=tokens + E)
+            for i in range(0, wt.wt_config_count(ctx), 3 * 7):
+                c, _ = wt.wt_config_get(ctx, i)
+                if c.split != 1:
+                    with pytest.raises(wt.WtError):
+                        wt.wt_wave_count_grouped(ctx, rows, N, K, c)
+                    continue
+                G, L = geo.phi_grouped(rows.tolist(), N, K, c.bm, c.bn, c.bk)
+                assert wt.wt_wave_count_grouped(ctx, rows, N, K, c) == (G, L, geo.wave_count(G, geo.capacity(1)))
+            key, micro, t = osel.select_grouped(table, E, tokens * top_k, N, K)
+            c = wt.wt_select_grouped(ctx, E, tokens * top_k, N, K)
+            assert c.id == 3 * key + micro and c.split == 1
+    # one group is the dense problem
+    for (M, N, K) in wt_synth.sweep_shapes():
+        key, micro, _ = osel.select_grouped(table, 1, M, N, K)
+        assert wt.wt_select_grouped(ctx, 1, M, N, K).id == 3 * key + micro
+
+
 def _pred_close(th_a, th_b, kd):
     pts = [(g, L) for g in (kd.cap // 2 + 1, kd.cap) for L in (8, 80)]
     for g, L in pts:

@@ -108,3 +108,29 @@ def random_theta(seed: int, count: int) -> np.ndarray:
     g = 10.0 ** rng.uniform(-3.0, -1.0, count)
     d = 10.0 ** rng.uniform(0.0, 1.0, count)
     return np.stack([a, b, g, d], axis=1)
+
+
+def moe_routing(tokens: int, experts: int, top_k: int, seed: int, skew: float = 1.0) -> np.ndarray:
+    """Rows per expert for a synthetic MoE layer: every token picks top_k distinct experts with
+    probabilities proportional to 1/rank^skew (skew 0 = uniform), the experts' ranks shuffled by the
+    seed.  Returns int64 counts summing to tokens*top_k; some may be 0.  Stands in for a trained
+    router's output (no trained weights here)."""
+    rng = np.random.default_rng(seed)
+    w = 1.0 / np.arange(1, experts + 1, dtype=np.float64) ** skew
+    w = rng.permutation(w / w.sum())
+    counts = np.zeros(experts, dtype=np.int64)
+    for _ in range(tokens):
+        counts[rng.choice(experts, size=min(top_k, experts), replace=False, p=w)] += 1
+    return counts
+
+
+def group_offsets(counts) -> np.ndarray:
+    """int32 row offsets [0, c0, c0+c1, ...] of back-to-back groups."""
+    return np.concatenate([[0], np.cumsum(np.asarray(counts, dtype=np.int64))]).astype(np.int32)
+
+
+# MoE grouped-GEMM workloads (experts, top_k, N, K): the expert projections of a 128-expert / top-8 /
+# hidden 2048 / expert width 768 layer (gate+up fused: N = 1536, K = 2048; down: N = 2048, K = 768) and of
+# an 8-expert / top-2 / hidden 4096 / expert width 14336 layer.
+MOE_LAYERS = [(128, 8, 1536, 2048), (128, 8, 2048, 768), (8, 2, 28672, 4096), (8, 2, 4096, 14336)]
+MOE_TOKENS = [16, 128, 1024, 8192]
