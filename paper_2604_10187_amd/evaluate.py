@@ -132,7 +132,7 @@ def cmd_stream(a, torch):
     mean_ns, p99_ns = wt.wt_select_bench(ctx, shapes, repeats=5)
     # exhaustive search on a seeded sample of the stream's draws (duplicates collapse into weights, so
     # the score is weighted the way the stream itself weights shapes)
-    rng = np.random.default_rng(2005)
+    rng = np.random.default_rng(a.sample_seed)
     draws = [shapes[i] for i in rng.choice(len(shapes), size=min(a.sample, len(shapes)), replace=False)]
     weight = {}
     for sh in draws:
@@ -337,6 +337,7 @@ def main(argv=None):
     ap.add_argument("--table", default=None)
     ap.add_argument("--out", default=None)
     ap.add_argument("--sample", type=int, default=400)
+    ap.add_argument("--sample-seed", type=int, default=2005, help="stream: seed of the sampled draws")
     ap.add_argument("--prune", type=float, default=2.5)
     ap.add_argument("--cfgs", type=lambda s: [tuple(int(x) for x in c.split(",")) for c in s.split(";")],
                     default=[(128, 128, 64, 4, 2, 0), (256, 256, 64, 8, 2, 0), (64, 64, 64, 4, 2, 0)])
