@@ -72,7 +72,7 @@ typedef struct {
     int32_t key_id, micro_id;
     int64_t G, L;
     int32_t w;
-    int32_t family; /* 0: near-square grid (the paper's sampler); 1: single tile row (see wt_grid.W_row) */
+    int32_t family; /* 0: near-square grid (the paper's sampler); 1, 2, 3: grids of 1, 2, 4 tile rows (wt_grid.W_row) */
     double mean_us;
 } wt_sample;
 
@@ -91,11 +91,17 @@ typedef struct {
     int32_t model;    /* wt_model: which latency model wt_fit builds (0 = the paper's) */
     int32_t W_split;  /* split-K keys are profiled for waves 1..min(W, W_split) only (0 = all W); beyond their
                        * profiled waves they have no model and wt_select does not consider them */
-    int32_t W_row;    /* extension, 0 = off (the paper's method): also profile and fit W_row waves of
-                       * single-tile-row grids (m_G = 1, n_G = top of each sub-interval; M = bm), kept in
-                       * a second set of buckets that wt_select consults for shapes with M <= bm.  The
-                       * paper's sampler stays near-square (tau) and its test shapes have M >= 64; these
-                       * grids cover the decode-like shapes whose B operand is streamed once from HBM. */
+    int32_t W_row;    /* extension, 0 = off (the paper's method): also profile and fit W_row waves of few-row
+                       * grids -- families 1..row_fams with m_G = 1, 2, 4 tile rows (M = m_G*bm) and, per
+                       * sub-interval, the widest n_G that keeps the task count inside it -- kept in their own
+                       * bucket sets.  wt_select consults family 1 for shapes with ceil(M/bm) = 1, family 2 for
+                       * 2..3 and family 3 for 4..7 tile rows, falling back to the paper's buckets.  The paper's
+                       * sampler stays near-square (tau) and its test shapes have M >= 64; these grids cover
+                       * the serving shapes (few tile rows, very wide) whose B operand streams from HBM with
+                       * little reuse, which near-square samples of the same G do not show. */
+    int32_t row_fams; /* number of few-row families, 1..3 (0 is read as 1); used only when W_row > 0 */
+    int32_t skip_near; /* 1: wt_sample_plan / wt_profile_sparse leave out the near-square family (to add few-row
+                        * records to an existing set); wt_fit ignores it */
 } wt_grid;
 
 /* Latency models wt_fit can build into the dual table.  WAVE_BILINEAR is the method (Sec. 4.3);

@@ -25,7 +25,7 @@ class Sample(NamedTuple):
     L: int
     w: int
     us: float
-    fam: int = 0     # 0: near-square grid (the paper's sampler); 1: single tile row (extension)
+    fam: int = 0     # 0: near-square grid (the paper's sampler); 1, 2, 3: grids of 1, 2, 4 tile rows (extension)
 
 
 class KeyDesc(NamedTuple):
@@ -52,9 +52,13 @@ class DualTable:
     keys: list            # [KeyDesc]
     local: list           # local[key][w-1] -> Bucket
     ext: list             # ext[key] -> Bucket
-    W_row: int = 0        # single-tile-row family (extension): profiled waves, 0 = absent
-    row_local: list = field(default_factory=list)   # row_local[key][w-1] -> Bucket
-    row_ext: list = field(default_factory=list)     # row_ext[key] -> Bucket
+    W_row: int = 0        # few-row families (extension): profiled waves, 0 = absent
+    row_local: list = field(default_factory=list)   # row_local[fam-1][key][w-1] -> Bucket, fam = 1..row_fams
+    row_ext: list = field(default_factory=list)     # row_ext[fam-1][key] -> Bucket
+
+    @property
+    def row_fams(self) -> int:
+        return len(self.row_local)
 
 
 def shared_micro(records) -> Optional[tuple[int, list]]:
@@ -169,7 +173,8 @@ def fit_step(records, cap: int):
 MODEL_WAVE_BILINEAR, MODEL_LINEAR, MODEL_STEP = 0, 1, 2
 
 
-def fit_tables(samples, keys, W: int, p: int, model: int = MODEL_WAVE_BILINEAR, W_row: int = 0) -> DualTable:
+def fit_tables(samples, keys, W: int, p: int, model: int = MODEL_WAVE_BILINEAR, W_row: int = 0,
+               row_fams: int = 1) -> DualTable:
     """Build the dual table (Sec. 4.3) with per-key extrapolation entries fitted on the merged
     samples of the last p profiled waves, max(1, W-p+1)..W (Sec. 4.5).  Samples with w > W are
     ignored.
@@ -182,11 +187,14 @@ def fit_tables(samples, keys, W: int, p: int, model: int = MODEL_WAVE_BILINEAR, 
     """
     samples = [Sample(*s) for s in samples]
     if W_row > 0:
-        # the single-tile-row family is a second, independent set of buckets built the same way
+        # every few-row family is a further, independent set of buckets built the same way
         # (wave buckets 1..W_row, extrapolation from the last min(p, W_row) of them)
-        rows_t = fit_tables([s._replace(fam=0) for s in samples if s.fam == 1], keys, W_row, min(p, W_row))
         t = fit_tables([s for s in samples if s.fam == 0], keys, W, p, model)
-        t.W_row, t.row_local, t.row_ext = W_row, rows_t.local, rows_t.ext
+        t.W_row = W_row
+        for f in range(1, row_fams + 1):
+            rows_t = fit_tables([s._replace(fam=0) for s in samples if s.fam == f], keys, W_row, min(p, W_row))
+            t.row_local.append(rows_t.local)
+            t.row_ext.append(rows_t.ext)
         return t
     samples = [s for s in samples if s.fam == 0]
     if model == MODEL_LINEAR:

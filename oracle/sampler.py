@@ -96,17 +96,27 @@ def sample_set(cap: int, W: int, I: int, tau_num: int = 11, tau_den: int = 10, S
     return out
 
 
-def row_sample_set(cap: int, W_row: int, I: int) -> list[GridSample]:
+def row_sample_set(cap: int, W_row: int, I: int, m: int = 1, S: int = 1) -> list[GridSample]:
     """Extension beyond the paper (its sampler keeps to near-square grids and its test shapes have
-    M >= 64): grids of a single tile row, m_G = 1, n_G = g, for shapes with M <= T_M whose B operand
-    is streamed once and never reused.  The same wave regions and sub-intervals are used (Sec. 4.2);
-    every g factors as 1 x g, so the representative of a sub-interval is its upper end."""
+    M >= 64): grids of m = 1, 2 or 4 tile rows for the serving shapes -- few tile rows, very wide --
+    whose B operand streams from HBM with little reuse.  The same wave regions and sub-intervals are
+    used (Sec. 4.2); with m rows (and S blocks per tile) a task count must be a multiple of S*m, and
+    the representative of a sub-interval is the largest such count in it: g = S*m*n, n = floor(b/(S*m)),
+    kept if it is not below a."""
     out = []
     for w in range(1, W_row + 1):
         for i in range(1, I + 1):
             a, b = sub_interval(w, i, cap, I)
-            out.append(GridSample(w, i, b, 1, b) if b >= a else GridSample(w, i, 0, 0, 0))
+            n = b // (S * m)
+            g = S * m * n
+            out.append(GridSample(w, i, g, m, n) if (b >= a and n >= 1 and g >= a) else GridSample(w, i, 0, 0, 0))
     return out
+
+
+def row_family(tile_rows: int) -> int:
+    """Which sample family serves a shape with ceil(M/T_M) = tile_rows tile rows: the 1-row family for 1,
+    the 2-row family for 2..3, the 4-row family for 4..7, the paper's near-square samples (0) otherwise."""
+    return 1 if tile_rows <= 1 else 2 if tile_rows <= 3 else 3 if tile_rows <= 7 else 0
 
 
 def instantiate(m: int, n: int, L: int, BM: int, BN: int, BK: int, S: int = 1) -> tuple[int, int, int]:

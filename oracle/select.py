@@ -12,7 +12,8 @@ import struct
 import numpy as np
 
 from .fit import Bucket, DualTable, KeyDesc
-from .geometry import phi_gemm, phi_grouped, split_fits, uniform_rows, wave_count
+from .geometry import ceil_div, phi_gemm, phi_grouped, split_fits, uniform_rows, wave_count
+from .sampler import row_family
 
 
 def predict(theta, G: int, L: int) -> float:
@@ -26,13 +27,13 @@ def predict(theta, G: int, L: int) -> float:
 def bucket_for(table: DualTable, key: int, w: int, fam: int = 0):
     """Sec. 4.5 rule: wave-local coefficients when w <= W (and that bucket was fitted), the
     extrapolation tuple otherwise.  Returns the Bucket or None when the key has no model.
-    fam = 1 looks in the single-tile-row family first (extension) and falls back to the paper's
-    near-square buckets when that family has nothing for the key."""
-    if fam == 1 and table.W_row > 0:
-        if 1 <= w <= table.W_row and table.row_local[key][w - 1].status:
-            return table.row_local[key][w - 1]
-        if table.row_ext[key].status:
-            return table.row_ext[key]
+    fam = 1, 2, 3 looks in that few-row family first (extension) and falls back to the paper's
+    near-square buckets when the table lacks the family or it has nothing for the key."""
+    if 1 <= fam <= table.row_fams and table.W_row > 0:
+        if 1 <= w <= table.W_row and table.row_local[fam - 1][key][w - 1].status:
+            return table.row_local[fam - 1][key][w - 1]
+        if table.row_ext[fam - 1][key].status:
+            return table.row_ext[fam - 1][key]
     if 1 <= w <= table.W:
         b = table.local[key][w - 1]
         if b.status:
@@ -60,7 +61,7 @@ def select(table: DualTable, M: int, N: int, K: int):
             continue     # its partial tiles would not fit the workspace: not a candidate
         G, L = phi_gemm(M, N, K, kd.bm, kd.bn, kd.bk, kd.split)
         w = wave_count(G, kd.cap)
-        b = bucket_for(table, k, w, 1 if M <= kd.bm else 0)     # one tile row <=> M <= T_M
+        b = bucket_for(table, k, w, row_family(ceil_div(M, kd.bm)))
         if b is None:
             continue
         t = predict(b.theta, G, L)
@@ -86,7 +87,7 @@ def select_grouped(table: DualTable, E: int, M_total: int, N: int, K: int):
         if kd.split != 1:
             continue
         G, L = phi_grouped(rows, N, K, kd.bm, kd.bn, kd.bk)
-        b = bucket_for(table, k, wave_count(G, kd.cap), 1 if rows[0] <= kd.bm else 0)
+        b = bucket_for(table, k, wave_count(G, kd.cap), row_family(ceil_div(rows[0], kd.bm)))
         if b is None:
             continue
         t = predict(b.theta, G, L)
@@ -108,19 +109,21 @@ MAGIC = b"WTDT"
 def read_table(path: str) -> tuple[DualTable, dict]:
     """Parse the flat little-endian dual-table file.
 
-    Header, 16 uint32: magic 'WTDT', version (1 or 2), n_keys, W, I, p, tau_num, tau_den, n_cu,
-    A (anchor slots per bucket), in_type, out_type, key_mode, W_row (version 2, else 0), 2 reserved.
+    Header, 16 uint32: magic 'WTDT', version (1, 2 or 3), n_keys, W, I, p, tau_num, tau_den, n_cu,
+    A (anchor slots per bucket), in_type, out_type, key_mode, W_row (version >= 2, else 0), number of
+    few-row families (version 3; version 2 has one), 1 reserved.
     Then per key: 8 int32 (bm, bn, bk, nwave, stages, occ, n_micro, split [0 = 1]), int64 cap, and a
     bucket block of R = W+1 rows (w = 1..W, then ext): R*4 float64 theta, R int32 status, R int32
-    n_anchor, R*A int32 anchor L, R*A int32 anchor micro.  Version 2 appends a second block of
-    W_row+1 rows per key for the single-tile-row family.
+    n_anchor, R*A int32 anchor L, R*A int32 anchor micro.  Versions 2 / 3 append, per key, one further
+    block of W_row+1 rows for every few-row family.
     """
     raw = open(path, "rb").read()
     hdr = struct.unpack_from("<4s15I", raw, 0)
-    if hdr[0] != MAGIC or hdr[1] not in (1, 2):
-        raise ValueError("not a version-1/2 dual table")
+    if hdr[0] != MAGIC or hdr[1] not in (1, 2, 3):
+        raise ValueError("not a version-1/2/3 dual table")
     n_keys, W, I, p, tnum, tden, n_cu, A, in_t, out_t, mode = hdr[2:13]
-    W_row = hdr[13] if hdr[1] == 2 else 0
+    W_row = hdr[13] if hdr[1] >= 2 else 0
+    n_fams = 0 if W_row == 0 else (hdr[14] if hdr[1] == 3 else 1)
     off = 64
 
     def block(R):
@@ -136,7 +139,8 @@ def read_table(path: str) -> tuple[DualTable, dict]:
             out.append(Bucket(theta=tuple(float(x) for x in theta[r]), status=int(status[r]), anchors=anchors))
         return out
 
-    keys, local, ext, row_local, row_ext = [], [], [], [], []
+    keys, local, ext = [], [], []
+    row_local, row_ext = [[] for _ in range(n_fams)], [[] for _ in range(n_fams)]
     for _ in range(n_keys):
         bm, bn, bk, nwave, stages, occ, n_micro, _r = struct.unpack_from("<8i", raw, off); off += 32
         (cap,) = struct.unpack_from("<q", raw, off); off += 8
@@ -144,10 +148,10 @@ def read_table(path: str) -> tuple[DualTable, dict]:
         buckets = block(W + 1)
         local.append(buckets[:W])
         ext.append(buckets[W])
-        if W_row > 0:
+        for f in range(n_fams):
             buckets = block(W_row + 1)
-            row_local.append(buckets[:W_row])
-            row_ext.append(buckets[W_row])
+            row_local[f].append(buckets[:W_row])
+            row_ext[f].append(buckets[W_row])
     if off != len(raw):
         raise ValueError("trailing bytes in dual table")
     meta = dict(I=I, p=p, tau_num=tnum, tau_den=tden, n_cu=n_cu, A=A, in_type=in_t, out_type=out_t, key_mode=mode,

@@ -137,7 +137,7 @@ bool key_in_slice(const wt_grid* g, int k, int nk) {
 
 int check_grid(const wt_grid* g) {
     if (!g || g->W < 1 || g->I < 1 || g->tau_den < 1 || g->tau_num < g->tau_den || g->p < 1 || g->n_k_anchors < 1 ||
-        !g->k_anchors || g->warmup < 0 || g->iters < 1 || g->W_row < 0 || g->W_split < 0)
+        !g->k_anchors || g->warmup < 0 || g->iters < 1 || g->W_row < 0 || g->W_split < 0 || g->row_fams < 0 || g->row_fams > kMaxRowFams)
         return WT_ERR_INVALID_ARG;
     for (int j = 0; j < g->n_k_anchors; ++j)
         if (g->k_anchors[j] < 1) return WT_ERR_INVALID_ARG;
@@ -145,8 +145,8 @@ int check_grid(const wt_grid* g) {
 }
 
 // Walk the sampling plan; fn(key, point, w, family, L, M, N, K) is called for every workload that will be
-// timed: the paper's near-square grids (family 0), then, when grid->W_row > 0, single-tile-row grids
-// 1 x g with g the top of each sub-interval (family 1).
+// timed: the paper's near-square grids (family 0), then, when grid->W_row > 0, the few-row grids m x n
+// (m = 1, 2, 4 tile rows: families 1, 2, 3) with n the widest that keeps the task count in the sub-interval.
 template <typename F>
 int walk_plan(const wt_ctx* ctx, const wt_grid* grid, F&& fn) {
     const int nk = (int)ctx->keys.size();
@@ -159,7 +159,7 @@ int walk_plan(const wt_ctx* ctx, const wt_grid* grid, F&& fn) {
         const int W = (key.split > 1 && grid->W_split > 0) ? std::min(grid->W, grid->W_split) : grid->W;
         sample_grid(key.cap, W, grid->I, grid->tau_num, grid->tau_den, key.split, pts);
         loop_anchors(grid, key.bk * key.split, anchors);
-        for (size_t s = 0; s < pts.size(); ++s) {
+        for (size_t s = 0; s < pts.size() && !grid->skip_near; ++s) {
             if (pts[s].g == 0) continue;
             const int64_t M = pts[s].m * key.bm, N = pts[s].n * key.bn;
             if (grid->max_out_elems > 0 && M * N > grid->max_out_elems) continue;
@@ -170,19 +170,26 @@ int walk_plan(const wt_ctx* ctx, const wt_grid* grid, F&& fn) {
                 if (rc != WT_OK) return rc;
             }
         }
-        if (key.split > 1) continue;  // the single-tile-row family is profiled for unsplit keys only
-        for (int w = 1; w <= grid->W_row; ++w) {
-            for (int i = 1; i <= grid->I; ++i) {
-                const int64_t lo = (int64_t)(w - 1) * key.cap + 1;
-                const int64_t a = lo + ((int64_t)(i - 1) * key.cap) / grid->I;
-                const int64_t b = lo - 1 + ((int64_t)i * key.cap) / grid->I;
-                if (b < a) continue;
-                const GridPoint pt{b, 1, b};
-                const int64_t M = key.bm, N = b * key.bn;
-                if (grid->max_out_elems > 0 && M * N > grid->max_out_elems) continue;
-                for (int64_t L : anchors) {
-                    const int rc = fn(k, pt, w, 1, L, M, N, L * key.bk);
-                    if (rc != WT_OK) return rc;
+        // few-row families: m rows of tiles, the widest n that keeps the task count S*m*n inside the sub-interval
+        const int n_fams = grid->W_row > 0 ? (grid->row_fams > 0 ? grid->row_fams : 1) : 0;
+        const int W_row = (key.split > 1 && grid->W_split > 0) ? std::min(grid->W_row, grid->W_split) : grid->W_row;
+        for (int fam = 1; fam <= n_fams; ++fam) {
+            const int64_t m = int64_t{1} << (fam - 1);
+            for (int w = 1; w <= W_row; ++w) {
+                for (int i = 1; i <= grid->I; ++i) {
+                    const int64_t lo = (int64_t)(w - 1) * key.cap + 1;
+                    const int64_t a = lo + ((int64_t)(i - 1) * key.cap) / grid->I;
+                    const int64_t b = lo - 1 + ((int64_t)i * key.cap) / grid->I;
+                    const int64_t n = b / (m * key.split);
+                    const GridPoint pt{n * m * key.split, m, n};
+                    if (n < 1 || pt.g < a) continue;
+                    const int64_t M = m * key.bm, N = n * key.bn;
+                    if (grid->max_out_elems > 0 && M * N > grid->max_out_elems) continue;
+                    if (!key_fits(key, m * n)) continue;
+                    for (int64_t L : anchors) {
+                        const int rc = fn(k, pt, w, fam, L, M, N, L * key.bk * key.split);
+                        if (rc != WT_OK) return rc;
+                    }
                 }
             }
         }

@@ -432,10 +432,14 @@ static int fit_table(wt_ctx* ctx, const wt_grid* grid, const wt_sample* s, size_
     t.W = W; t.I = grid->I; t.p = grid->p; t.tau_num = grid->tau_num; t.tau_den = grid->tau_den;
     int rc = fit_family(ctx, 0, grid->model, W, grid->p, s, n, t.buckets);
     if (rc != WT_OK) return rc;
-    if (grid->W_row > 0) {  // the single-tile-row family always uses the wave-bucketed bilinear model
+    if (grid->W_row > 0) {  // the few-row families always use the wave-bucketed bilinear model
+        if (grid->row_fams < 0 || grid->row_fams > kMaxRowFams) return WT_ERR_INVALID_ARG;
         t.W_row = grid->W_row;
-        rc = fit_family(ctx, 1, WT_MODEL_WAVE_BILINEAR, t.W_row, std::min(grid->p, t.W_row), s, n, t.row_buckets);
-        if (rc != WT_OK) return rc;
+        t.row_fams = grid->row_fams > 0 ? grid->row_fams : 1;
+        for (int f = 1; f <= t.row_fams; ++f) {
+            rc = fit_family(ctx, f, WT_MODEL_WAVE_BILINEAR, t.W_row, std::min(grid->p, t.W_row), s, n, t.row_buckets[f - 1]);
+            if (rc != WT_OK) return rc;
+        }
     }
     t.fitted = true;
     ctx->table = std::move(t);
@@ -443,9 +447,10 @@ static int fit_table(wt_ctx* ctx, const wt_grid* grid, const wt_sample* s, size_
 }
 
 // ---- two-stage selection (Sec. 4.4, 4.5) -------------------------------------------------------
-static inline const Bucket* pick_bucket(const Table& t, int key, int64_t w, bool one_row) {
-    if (one_row && t.W_row > 0) {  // M <= bm: single-tile-row buckets first, the paper's as fallback
-        const Bucket* rb = &t.row_buckets[static_cast<size_t>(key) * (t.W_row + 1)];
+static inline const Bucket* pick_bucket(const Table& t, int key, int64_t w, int64_t tile_rows) {
+    const int fam = t.W_row > 0 ? row_family(tile_rows) : 0;
+    if (fam >= 1 && fam <= t.row_fams) {  // few tile rows: that family's buckets first, the paper's as fallback
+        const Bucket* rb = &t.row_buckets[fam - 1][static_cast<size_t>(key) * (t.W_row + 1)];
         if (w >= 1 && w <= t.W_row && rb[w - 1].status) return &rb[w - 1];
         if (rb[t.W_row].status) return &rb[t.W_row];
     }
@@ -491,7 +496,7 @@ static int select_impl(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, int g
             continue;
         }
         const int64_t w = (G + key.cap - 1) / key.cap;
-        const Bucket* b = pick_bucket(t, k, w, Mg <= key.bm);
+        const Bucket* b = pick_bucket(t, k, w, (Mg + key.bm - 1) >> key.sh_m);
         if (!b) continue;
         const double th = predict(b->th, G, L);
         if (th != th) continue;
@@ -519,12 +524,12 @@ static int select_impl(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, int g
 }
 
 // ---- table file ------------------------------------------------------------------------------------
-// Little-endian.  Header: 16 uint32 = 'WTDT', version (1, or 2 when the single-tile-row family is
-// present), n_keys, W, I, p, tau_num, tau_den, n_cu, anchor slots A, in_type, out_type, key_mode
-// (capacity mode), W_row (version 2), 2 reserved.  Per key: 8 int32 (bm, bn, bk, nwave, stages, occ,
+// Little-endian.  Header: 16 uint32 = 'WTDT', version (1; 2 with the single-tile-row family; 3 with several
+// few-row families), n_keys, W, I, p, tau_num, tau_den, n_cu, anchor slots A, in_type, out_type, key_mode
+// (capacity mode), W_row (version >= 2), row_fams (version 3), 1 reserved.  Per key: 8 int32 (bm, bn, bk, nwave, stages, occ,
 // n_micro, split [0 in older files = 1]), int64 cap (256, or 256*occ when key_mode = 0), then a bucket block of R = W+1 rows
 // (w = 1..W then ext): R*4 float64 theta, R int32 status, R int32 n_anchor, R*A int32 anchor L,
-// R*A int32 anchor micro; version 2 appends a block of W_row+1 rows for the single-tile-row family.
+// R*A int32 anchor micro; versions 2 / 3 append one block of W_row+1 rows per few-row family.
 static const uint32_t kMagic = 0x54445457u;  // "WTDT"
 
 static bool write_block(FILE* f, const Bucket* b, int R) {
@@ -554,12 +559,12 @@ static int save_table(const wt_ctx* ctx, const char* path) {
     FILE* f = fopen(path, "wb");
     if (!f) return WT_ERR_IO;
     const uint32_t nk = static_cast<uint32_t>(ctx->keys.size());
-    const uint32_t hdr[16] = {kMagic, t.W_row > 0 ? 2u : 1u, nk, static_cast<uint32_t>(t.W), static_cast<uint32_t>(t.I),
+    const uint32_t hdr[16] = {kMagic, t.W_row > 0 ? (t.row_fams > 1 ? 3u : 2u) : 1u, nk, static_cast<uint32_t>(t.W), static_cast<uint32_t>(t.I),
                               static_cast<uint32_t>(t.p), static_cast<uint32_t>(t.tau_num),
                               static_cast<uint32_t>(t.tau_den), static_cast<uint32_t>(kNumCU),
                               static_cast<uint32_t>(kMaxAnchors), static_cast<uint32_t>(ctx->in_type),
                               static_cast<uint32_t>(ctx->out_type), static_cast<uint32_t>(ctx->cap_mode),
-                              static_cast<uint32_t>(t.W_row), 0u, 0u};
+                              static_cast<uint32_t>(t.W_row), static_cast<uint32_t>(t.row_fams), 0u};
     bool ok = fwrite(hdr, sizeof(hdr), 1, f) == 1;
     const int R = t.W + 1;
     for (uint32_t k = 0; ok && k < nk; ++k) {
@@ -568,7 +573,8 @@ static int save_table(const wt_ctx* ctx, const char* path) {
         ok = ok && fwrite(kd, sizeof(kd), 1, f) == 1;
         ok = ok && fwrite(&key.cap, sizeof(int64_t), 1, f) == 1;
         ok = ok && write_block(f, &t.buckets[static_cast<size_t>(k) * R], R);
-        if (t.W_row > 0) ok = ok && write_block(f, &t.row_buckets[static_cast<size_t>(k) * (t.W_row + 1)], t.W_row + 1);
+        for (int fam = 0; fam < t.row_fams; ++fam)
+            ok = ok && write_block(f, &t.row_buckets[fam][static_cast<size_t>(k) * (t.W_row + 1)], t.W_row + 1);
     }
     ok = (fclose(f) == 0) && ok;
     return ok ? WT_OK : WT_ERR_IO;
@@ -581,8 +587,10 @@ static int load_table(wt_ctx* ctx, const char* path) {
     int rc = WT_OK;
     Table t;
     std::vector<int> occs;
-    if (fread(hdr, sizeof(hdr), 1, f) != 1 || hdr[0] != kMagic || (hdr[1] != 1u && hdr[1] != 2u)) rc = WT_ERR_IO;
+    if (fread(hdr, sizeof(hdr), 1, f) != 1 || hdr[0] != kMagic || hdr[1] < 1u || hdr[1] > 3u) rc = WT_ERR_IO;
     if (rc == WT_OK && hdr[1] == 1u) hdr[13] = 0;
+    if (rc == WT_OK) hdr[14] = hdr[13] == 0 ? 0u : (hdr[1] == 3u ? hdr[14] : 1u);
+    if (rc == WT_OK && hdr[14] > static_cast<uint32_t>(kMaxRowFams)) rc = WT_ERR_INVALID_ARG;
     if (rc == WT_OK && hdr[13] > 4096u) rc = WT_ERR_INVALID_ARG;
     if (rc == WT_OK && (hdr[2] != ctx->keys.size() || hdr[9] != static_cast<uint32_t>(kMaxAnchors) ||
                         hdr[10] != static_cast<uint32_t>(ctx->in_type) || hdr[3] < 1 || hdr[3] > 4096 || hdr[12] > 1u))
@@ -592,8 +600,9 @@ static int load_table(wt_ctx* ctx, const char* path) {
         t.tau_num = static_cast<int>(hdr[6]); t.tau_den = static_cast<int>(hdr[7]);
         const int R = t.W + 1;
         t.W_row = static_cast<int>(hdr[13]);
+        t.row_fams = static_cast<int>(hdr[14]);
         t.buckets.assign(ctx->keys.size() * R, Bucket{});
-        if (t.W_row > 0) t.row_buckets.assign(ctx->keys.size() * (t.W_row + 1), Bucket{});
+        for (int fam = 0; fam < t.row_fams; ++fam) t.row_buckets[fam].assign(ctx->keys.size() * (t.W_row + 1), Bucket{});
         for (size_t k = 0; rc == WT_OK && k < ctx->keys.size(); ++k) {
             int32_t kd[8];
             int64_t cap;
@@ -603,7 +612,7 @@ static int load_table(wt_ctx* ctx, const char* path) {
                 (kd[7] < 1 ? 1 : kd[7]) != key.split || kd[5] < 1 || cap != key_capacity(static_cast<int>(hdr[12]), kd[5])) { rc = WT_ERR_INVALID_ARG; break; }
             occs.push_back(kd[5]);
             bool ok = read_block(f, &t.buckets[k * R], R);
-            if (ok && t.W_row > 0) ok = read_block(f, &t.row_buckets[k * (t.W_row + 1)], t.W_row + 1);
+            for (int fam = 0; ok && fam < t.row_fams; ++fam) ok = read_block(f, &t.row_buckets[fam][k * (t.W_row + 1)], t.W_row + 1);
             if (!ok) rc = WT_ERR_IO;
         }
     }
@@ -780,7 +789,7 @@ int wt_predict_us(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, wt_cfg cfg
     int64_t tiles, G, L;
     key_phi(k, M, N, K, &tiles, &G, &L);
     if (!key_fits(k, tiles)) return WT_ERR_INFEASIBLE;
-    const Bucket* b = pick_bucket(ctx->table, kid, ceil_div64(G, k.cap), M <= k.bm);
+    const Bucket* b = pick_bucket(ctx->table, kid, ceil_div64(G, k.cap), ceil_div64(M, k.bm));
     if (!b) return WT_ERR_NOT_FITTED;
     *us = predict(b->th, G, L);
     return WT_OK;

@@ -14,6 +14,9 @@ constexpr int kNumCU = 256;            // compute units of one MI355X
 constexpr int kLdsPerCU = 160 * 1024;  // bytes
 constexpr int kNumSwizzle = 3;         // micro parameter values 0..2
 constexpr int kMaxAnchors = 8;         // loop anchors stored per bucket
+constexpr int kMaxRowFams = 3;         // few-row sample families: 1, 2 and 4 tile rows
+// Family consulted for a shape with `rows` = ceil(M/bm) tile rows: 1 -> 1, 2..3 -> 2, 4..7 -> 3, else 0.
+inline int row_family(int64_t rows) { return rows <= 1 ? 1 : rows <= 3 ? 2 : rows <= 7 ? 3 : 0; }
 // Split-K workspace owned by a context: fp32 partial tiles and one arrival counter per output tile.
 constexpr int64_t kWsElems = int64_t{1} << 26;   // 256 MiB of floats
 constexpr int64_t kMaxSplitTiles = 1 << 16;      // arrival counters
@@ -51,9 +54,11 @@ struct Table {
     int W = 0, I = 0, p = 0, tau_num = 11, tau_den = 10;
     // buckets[key * (W + 1) + (w - 1)] for w = 1..W; index W is the extrapolation entry
     std::vector<Bucket> buckets;
-    // single-tile-row family (extension): row_buckets[key * (W_row + 1) + (w - 1)], last = extrapolation
+    // few-row families (extension) f = 1..row_fams, grids of 1, 2, 4 tile rows:
+    // row_buckets[f - 1][key * (W_row + 1) + (w - 1)], last = extrapolation
     int W_row = 0;
-    std::vector<Bucket> row_buckets;
+    int row_fams = 0;
+    std::vector<Bucket> row_buckets[3];
 };
 
 }  // namespace wt

@@ -281,12 +281,13 @@ def cmd_ablate(a, torch=None):
         recs = recs.view(wt.SAMPLE_DTYPE)
     W0, I0 = int(recs["w"].max()), a.I
 
-    def score(model, W, I, cap_mode, W_row=0):
+    def score(model, W, I, cap_mode, W_row=0, row_fams=0):
         ctx = wt.wt_create(-1, a.in_type, a.out_type)
         wt.wt_set_capacity_mode(ctx, cap_mode)
         for k, o in enumerate(occ):
             wt.wt_key_set_occ(ctx, k, int(o))
-        sub = recs[((recs["family"] == 0) & (recs["w"] <= W)) | ((recs["family"] == 1) & (recs["w"] <= W_row))]
+        sub = recs[((recs["family"] == 0) & (recs["w"] <= W)) |
+                   ((recs["family"] >= 1) & (recs["family"] <= row_fams) & (recs["w"] <= W_row))]
         if I < I0:       # sub-intervals of a coarser split are unions of the finer ones: keep each union's top sample
             keep = np.zeros(len(sub), dtype=bool)
             step = I0 // I
@@ -297,7 +298,8 @@ def cmd_ablate(a, torch=None):
                 idx = np.minimum(pos * I0 // cap, I0 - 1)            # which of the I0 sub-intervals
                 keep[np.where(m)[0]] = (idx % step) == (step - 1)
             sub = sub[keep]
-        wt.wt_fit(ctx, wt.make_grid(W=W, I=I, p=min(a.p, W), k_anchors=tune.K_ANCHORS, model=model, W_row=W_row), sub)
+        wt.wt_fit(ctx, wt.make_grid(W=W, I=I, p=min(a.p, W), k_anchors=tune.K_ANCHORS, model=model, W_row=W_row,
+                                      row_fams=row_fams), sub)
         fr = []
         for r in rows:
             c = wt.wt_select(ctx, r["M"], r["N"], r["K"])
@@ -309,10 +311,10 @@ def cmd_ablate(a, torch=None):
                 "frac_ge_95": float(np.mean(fr >= 0.95)), "records": int(len(sub))}
 
     W0 = int(recs["w"][recs["family"] == 0].max())
-    Wr = int(recs["w"][recs["family"] == 1].max()) if (recs["family"] == 1).any() else 0
-    if Wr:
-        out["variants"].append({"model": "wave-bilinear + single-row family", "W": W0, "I": I0, "W_row": Wr,
-                                **score(0, W0, I0, a.cap_mode, Wr)})
+    Wr = int(recs["w"][recs["family"] >= 1].max()) if (recs["family"] >= 1).any() else 0
+    for nf in range(1, int(recs["family"].max()) + 1):
+        out["variants"].append({"model": f"wave-bilinear + {nf} few-row families", "W": W0, "I": I0, "W_row": Wr,
+                                **score(0, W0, I0, a.cap_mode, Wr, nf)})
     for name, model in (("wave-bilinear (full)", 0), ("linear", 1), ("step", 2)):
         out["variants"].append({"model": name, "W": W0, "I": I0, **score(model, W0, I0, a.cap_mode)})
     for W in (5, 10, 20, W0):

@@ -49,7 +49,7 @@ def profile(ctx, grid, in_type, out_type, log=print, chunk_keys=1):
         g = wt.make_grid(W=grid.W, I=grid.I, tau=(grid.tau_num, grid.tau_den), p=grid.p,
                          k_anchors=[grid.k_anchors[j] for j in range(grid.n_k_anchors)], warmup=grid.warmup,
                          iters=grid.iters, key_first=k0, key_count=kc, max_out_elems=grid.max_out_elems, model=grid.model, W_row=grid.W_row,
-                         W_split=grid.W_split)
+                         W_split=grid.W_split, row_fams=grid.row_fams, skip_near=grid.skip_near)
         recs = wt.wt_profile_sparse(ctx, g, scrA, scrB, scrC, stream=torch.cuda.current_stream())
         out.append(recs)
         log(f"[tune] keys {k0}..{k0 + kc - 1}: {len(recs)} records, {time.time() - t0:.0f}s elapsed")
@@ -72,6 +72,8 @@ def main(argv=None):
     ap.add_argument("--cap-mode", type=int, default=1, help="1: 256 CUs (the paper's wave count), 0: 256 x resident blocks per CU")
     ap.add_argument("--model", type=int, default=0, help="0 wave-bilinear, 1 linear, 2 step")
     ap.add_argument("--W-row", type=int, default=0, help="extension: waves of single-tile-row grids to profile/fit (0 = off)")
+    ap.add_argument("--row-fams", type=int, default=1, help="extension: few-row families to profile/fit when --W-row > 0 (1..3: 1, 2, 4 tile rows)")
+    ap.add_argument("--skip-near", action="store_true", help="profile only the few-row families (records are merged by --fit-from)")
     ap.add_argument("--W-split", type=int, default=8, help="split-K keys are profiled for the first W-split waves only (0 = all)")
     ap.add_argument("--samples-out", default=None)
     ap.add_argument("--fit-from", nargs="*", default=None)
@@ -79,7 +81,7 @@ def main(argv=None):
     a = ap.parse_args(argv)
     grid = wt.make_grid(W=a.W, I=a.I, p=a.p, k_anchors=a.k_anchors, warmup=a.warmup, iters=a.iters,
                         key_first=a.key_first, key_count=a.key_count, max_out_elems=a.max_out_elems, model=a.model, W_row=a.W_row,
-                        W_split=a.W_split)
+                        W_split=a.W_split, row_fams=a.row_fams, skip_near=int(a.skip_near))
     if a.fit_from is not None:
         recs = np.concatenate([np.load(f) for f in a.fit_from])
         occ_files = [f.replace(".npy", ".occ.npy") for f in a.fit_from]

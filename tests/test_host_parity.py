@@ -350,35 +350,41 @@ def test_occupancy_aware_capacity_mode(tmp_path):
         wt.wt_destroy(c)
 
 
-def test_single_row_family_parity(ctx, tmp_path):
-    """Extension: records of 1 x g grids (family 1) build a second bucket set; table, file (version 2)
-    and lookups match the oracle exactly."""
+@pytest.mark.parametrize("row_fams", [1, 3])
+def test_few_row_families_parity(ctx, tmp_path, row_fams):
+    """Extension: records of 1-, 2- and 4-row grids (families 1..3) build further bucket sets; table, file
+    (version 2 with one family, 3 with several) and lookups match the oracle exactly."""
     W, W_row, I, p = 8, 3, 4, 4
     keys = _keys(ctx)
     near = _synthetic_samples(keys, W, I, noise_seed=11)
     rows = []
-    for k, kd in enumerate(keys):
-        th = wt_synth.random_theta(900 + k, W_row)
-        if kd.split > 1:
-            continue                                  # the row family exists for unsplit keys only
-        for s in smp.row_sample_set(kd.cap, W_row, I):
-            for L in smp.loop_anchors(K_ANCHORS, kd.bk):
-                for micro in range(3):
-                    a, b, c, d = th[s.w - 1]
-                    t = 2.0 * (kd.bn * kd.bk / 8192.0) * (a * s.g * L + b * s.g) + c * L + d
-                    rows.append((k, micro, s.g, L, s.w, 1, t * (1.0 + 0.02 * ((micro + k) % 3))))
+    for f in range(1, row_fams + 1):
+        m = 1 << (f - 1)
+        for k, kd in enumerate(keys):
+            th = wt_synth.random_theta(900 + 7 * f + k, W_row)
+            Wk = W_row if kd.split == 1 else min(W_row, W_SPLIT)
+            for s in smp.row_sample_set(kd.cap, Wk, I, m, kd.split):
+                if s.g == 0 or not geo.split_fits(s.m * kd.bm, s.n * kd.bn, kd.bm, kd.bn, kd.split):
+                    continue
+                for L in smp.loop_anchors(K_ANCHORS, kd.bk, kd.split):
+                    for micro in range(3):
+                        a, b, c, d = th[s.w - 1]
+                        t = (4.0 / (f + 1)) * (kd.bn * kd.bk / 8192.0) * (a * s.g * L + b * s.g) + c * L + d
+                        rows.append((k, micro, s.g, L, s.w, f, t * (1.0 + 0.02 * ((micro + k) % 3))))
     samples = np.concatenate([near, np.array(rows, dtype=wt.SAMPLE_DTYPE)])
-    grid = wt.make_grid(W=W, I=I, p=p, k_anchors=K_ANCHORS, W_row=W_row)
+    grid = wt.make_grid(W=W, I=I, p=p, k_anchors=K_ANCHORS, W_row=W_row, row_fams=row_fams, W_split=W_SPLIT)
     wt.wt_fit(ctx, grid, samples)
     path = str(tmp_path / "row.wt")
     wt.wt_save(ctx, path)
     table, meta = osel.read_table(path)
-    assert meta["W_row"] == W_row and table.W_row == W_row
+    assert meta["W_row"] == W_row and table.W_row == W_row and table.row_fams == row_fams
     want = ofit.fit_tables([(int(r["key_id"]), int(r["micro_id"]), int(r["G"]), int(r["L"]), int(r["w"]),
-                             float(r["mean_us"]), int(r["family"])) for r in samples], keys, W, p, W_row=W_row)
+                             float(r["mean_us"]), int(r["family"])) for r in samples], keys, W, p, W_row=W_row,
+                           row_fams=row_fams)
     for k in range(len(keys)):
         pairs = list(zip(table.local[k], want.local[k])) + [(table.ext[k], want.ext[k])]
-        pairs += list(zip(table.row_local[k], want.row_local[k])) + [(table.row_ext[k], want.row_ext[k])]
+        for f in range(row_fams):
+            pairs += list(zip(table.row_local[f][k], want.row_local[f][k])) + [(table.row_ext[f][k], want.row_ext[f][k])]
         for got_b, want_b in pairs:
             assert got_b.status == want_b.status and got_b.anchors == want_b.anchors
             scale = max(abs(x) for x in want_b.theta) or 1.0
@@ -386,18 +392,18 @@ def test_single_row_family_parity(ctx, tmp_path):
                 _pred_close(got_b.theta, want_b.theta, keys[k])
     ctx2 = wt.wt_create(-1, wt.WT_BF16, wt.WT_OUT_F32)
     wt.wt_load(ctx2, path)
-    used_row = 0
+    used = [0, 0, 0, 0]
     for (M, N, K) in wt_synth.sweep_shapes() + wt_synth.stream_shapes(2000):
         key, micro, t = osel.select(table, M, N, K)
-        used_row += M <= keys[key].bm
+        used[smp.row_family(geo.ceil_div(M, keys[key].bm))] += 1
         for cc in (ctx, ctx2):
             c = wt.wt_select(cc, M, N, K)
             assert c.id == 3 * key + micro and wt.wt_predict_us(cc, M, N, K, c) == t
-    assert used_row > 100
+    assert all(u > 30 for u in used[:row_fams + 1])
     wt.wt_destroy(ctx2)
-    n_near, *_ = wt.wt_sample_plan(ctx, wt.make_grid(W=W, I=I, p=p, k_anchors=K_ANCHORS))
+    n_near, *_ = wt.wt_sample_plan(ctx, wt.make_grid(W=W, I=I, p=p, k_anchors=K_ANCHORS, W_split=W_SPLIT))
     n_both, *_ = wt.wt_sample_plan(ctx, grid)
-    assert n_both - n_near == len(rows)          # the plan adds exactly the 1 x g workloads
+    assert n_both - n_near == len(rows)          # the plan adds exactly the few-row workloads
 
 
 @pytest.mark.parametrize("tiles", [(1, 1), (1, 61), (3, 80), (5, 29), (7, 8), (16, 43), (38, 12), (64, 32), (9, 9)])

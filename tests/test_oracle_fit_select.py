@@ -321,11 +321,12 @@ def test_single_row_family_is_fitted_and_used_only_for_one_tile_row():
         assert [b.theta for b in table.local[k]] == [b.theta for b in plain.local[k]]
         assert table.ext[k].theta == plain.ext[k].theta
         for w in range(1, W_row + 1):
-            assert np.allclose(table.row_local[k][w - 1].theta, 3.0 * _surface_theta(k, w, 6), rtol=1e-7)
+            assert np.allclose(table.row_local[0][k][w - 1].theta, 3.0 * _surface_theta(k, w, 6), rtol=1e-7)
     kd = KEYS[1]                                   # 128 x 128 x 64
     # M <= BM: one tile row -> row family; M = BM + 1: two tile rows -> the paper's buckets
-    assert osel.bucket_for(table, 1, 1, 1) is table.row_local[1][0]
-    assert osel.bucket_for(table, 1, W_row + 1, 1) is table.row_ext[1]
+    assert osel.bucket_for(table, 1, 1, 1) is table.row_local[0][1][0]
+    assert osel.bucket_for(table, 1, W_row + 1, 1) is table.row_ext[0][1]
+    assert osel.bucket_for(table, 1, 1, 2) is table.local[1][0]          # no 2-row family in this table
     assert osel.bucket_for(table, 1, 1, 0) is table.local[1][0]
     assert osel.bucket_for(plain, 1, 1, 1) is plain.local[1][0]
     t1 = osel.predict(osel.bucket_for(table, 1, 1, 1).theta, 32, 64)
@@ -345,3 +346,43 @@ def test_single_row_family_is_fitted_and_used_only_for_one_tile_row():
     # a key without row records falls back to its near-square buckets
     t2 = ofit.fit_tables(near + [s for s in _row_samples(W_row, I) if s.key != 0], KEYS, W, p=3, W_row=W_row)
     assert osel.bucket_for(t2, 0, 1, 1) is t2.local[0][0]
+
+
+def test_few_row_families_are_chosen_by_tile_rows():
+    """Three families (1, 2, 4 tile rows), each with its own latency surface (x3, x2, x1.5 of the
+    near-square one): a shape is priced by the family of its tile-row count under every key, and by the
+    paper's buckets from 8 tile rows on."""
+    W, W_row, I = 6, 2, 4
+    near = _make_samples(W, I, _penalty)
+    slow = {1: 3.0, 2: 2.0, 3: 1.5}
+    extra = []
+    for f, m in ((1, 1), (2, 2), (3, 4)):
+        for k, kd in enumerate(KEYS):
+            for s in smp.row_sample_set(kd.cap, W_row, I, m):
+                if s.g == 0:
+                    continue
+                assert s.g == s.m * s.n and s.m == m
+                for L in smp.loop_anchors(K_ANCHORS, kd.bk):
+                    for mi in range(N_MICRO):
+                        extra.append(ofit.Sample(k, mi, s.g, L, s.w, slow[f] * _latency(k, mi, s.g, L, 6, _penalty), f))
+    table = ofit.fit_tables(near + extra, KEYS, W, p=3, W_row=W_row, row_fams=3)
+    assert table.row_fams == 3
+    assert [smp.row_family(r) for r in (0, 1, 2, 3, 4, 7, 8, 100)] == [1, 1, 2, 2, 3, 3, 0, 0]
+    kd = KEYS[1]                                   # 128 x 128 x 64
+    for M, f in ((100, 1), (128, 1), (129, 2), (384, 2), (385, 3), (896, 3), (897, 0)):
+        fam = smp.row_family(geo.ceil_div(M, kd.bm))
+        assert fam == f
+        b = osel.bucket_for(table, 1, 1, fam)
+        t0 = osel.predict(table.local[1][0].theta, 40, 64)
+        assert abs(osel.predict(b.theta, 40, 64) - slow.get(f, 1.0) * t0) < 1e-6 * t0
+    # Stage I uses, for every key, the family of that key's own tile-row count
+    M, N, K = 200, 4096, 4096
+    cand = []
+    for kid, kd in enumerate(KEYS):
+        G, L = geo.phi_gemm(M, N, K, kd.bm, kd.bn, kd.bk)
+        f = smp.row_family(geo.ceil_div(M, kd.bm))
+        for mi in range(N_MICRO):
+            cand.append(((kid, mi), slow.get(f, 1.0) * _latency(kid, mi, G, L, W, _penalty)))
+    (bk, _), bt = oex.argmin_config(cand)
+    key, _, t = osel.select(table, M, N, K)
+    assert key == bk and abs(t - bt) < 1e-6 * bt

@@ -196,6 +196,19 @@ def test_single_row_sample_set():
         assert geo.phi_gemm(*smp.instantiate(s.m, s.n, 7, 16, 64, 128), 16, 64, 128) == (s.g, 7)
 
 
+def test_few_row_sample_sets_brute_force():
+    """m-row grids: the representative is the largest multiple of S*m in the sub-interval (none if the
+    interval holds no multiple), found here by scanning every count."""
+    for cap, m, S in ((256, 2, 1), (256, 4, 1), (256, 4, 2), (132, 4, 1), (12, 4, 1), (64, 2, 8)):
+        for s in smp.row_sample_set(cap, 5, 3, m, S):
+            a, b = smp.sub_interval(s.w, s.i, cap, 3)
+            ok = [g for g in range(a, b + 1) if g % (S * m) == 0]
+            assert s.g == (max(ok) if ok else 0)
+            if s.g:
+                assert (s.m, s.n) == (m, s.g // (S * m)) and geo.wave_count(s.g, cap) == s.w
+    assert smp.row_sample_set(256, 3, 4, 1, 1) == smp.row_sample_set(256, 3, 4)
+
+
 # ---- split-K reading of Phi and of the sampler ------------------------------------------------------
 def test_split_phi_partitions_the_k_tiles():
     """S blocks per tile, each with L = ceil(ceil(K/BK)/S) k-tiles: the ranges [s*L, (s+1)*L) clipped to
