@@ -230,7 +230,7 @@ def cmd_grouped(a, torch):
         g.manual_seed(4000 + E + N)
         B = torch.randn((E * N, K), device="cuda", generator=g).to(torch.bfloat16)
         for tokens in wt_synth.MOE_TOKENS:
-            counts = wt_synth.moe_routing(tokens, E, top_k, seed=tokens + E, skew=1.0)
+            counts = wt_synth.moe_routing(tokens, E, top_k, seed=tokens + E, skew=a.skew)
             M_total = int(counts.sum())
             off = torch.from_numpy(wt_synth.group_offsets(counts)).cuda()
             A = torch.randn((M_total, K), device="cuda", generator=g).to(torch.bfloat16)
@@ -262,7 +262,7 @@ def cmd_grouped(a, torch):
     fr = np.array([r["frac"] for r in rows])
     summary = {"n_cases": len(rows), "geomean_frac": float(np.exp(np.mean(np.log(fr)))), "min_frac": float(fr.min()),
                "frac_ge_95": float(np.mean(fr >= 0.95))}
-    return {"workload": "grouped GEMM, MoE expert projections, routing 1/rank skew, bf16", "table": path,
+    return {"workload": f"grouped GEMM, MoE expert projections, routing probabilities 1/rank^{a.skew}, bf16", "table": path,
             "summary": summary, "rows": rows}
 
 
@@ -339,6 +339,7 @@ def main(argv=None):
     ap.add_argument("--table", default=None)
     ap.add_argument("--out", default=None)
     ap.add_argument("--sample", type=int, default=400)
+    ap.add_argument("--skew", type=float, default=1.0, help="grouped: routing probabilities ~ 1/rank^skew (0 = uniform)")
     ap.add_argument("--sample-seed", type=int, default=2005, help="stream: seed of the sampled draws")
     ap.add_argument("--prune", type=float, default=2.5)
     ap.add_argument("--cfgs", type=lambda s: [tuple(int(x) for x in c.split(",")) for c in s.split(";")],

@@ -1,8 +1,8 @@
 """Time one configuration on one shape through the C ABI (also the program profiled under rocprofv3).
 
-    python -m paper_2604_10187_amd.run_one M N K bm bn bk nwave stages swizzle [iters] [in_type] [out_type]
+    python -m paper_2604_10187_amd.run_one M N K bm bn bk nwave stages swizzle [iters] [in_type] [out_type] [split]
 
-in_type 0 = bf16, 1 = fp8 e4m3; out_type 0 = f32, 1 = bf16.  N(0,1) operands (fp8: per-tensor scales).
+in_type 0 = bf16, 1 = fp8 e4m3; out_type 0 = f32, 1 = bf16; split = blocks per output tile along K (default 1).  N(0,1) operands (fp8: per-tensor scales).
 """
 import sys
 
@@ -20,8 +20,9 @@ def main(argv=None):
     iters = a[9] if len(a) > 9 else 5
     it = a[10] if len(a) > 10 else wt.WT_BF16
     ot = a[11] if len(a) > 11 else wt.WT_OUT_BF16
+    split = a[12] if len(a) > 12 else 1
     ctx = wt.wt_create(0, it, ot)
-    cfg, res = wt.wt_config_get(ctx, wt.wt_config_find(ctx, bm, bn, bk, nw, st, sw))
+    cfg, res = wt.wt_config_get(ctx, wt.wt_config_find(ctx, bm, bn, bk, nw, st, sw, split))
     A = torch.randn(M, K, device="cuda")
     B = torch.randn(N, K, device="cuda")
     sA = sB = None
