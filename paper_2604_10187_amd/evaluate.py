@@ -254,7 +254,8 @@ def cmd_grouped(a, torch):
                          "best": list(cfgs[best_id][0].astuple()), "best_us": times[best_id],
                          "frac": times[best_id] / times[pick.id],
                          "pick_tflops": 2.0 * M_total * N * K / times[pick.id] / 1e6,
-                         "best_tflops": 2.0 * M_total * N * K / times[best_id] / 1e6, "n_timed": len(times)})
+                         "best_tflops": 2.0 * M_total * N * K / times[best_id] / 1e6, "n_timed": len(times),
+                         "times": {str(i): round(t, 3) for i, t in times.items()}})
             _log(f"[eval] grouped E={E} tokens={tokens} N={N} K={K}: frac {rows[-1]['frac']:.3f} "
                  f"pick {rows[-1]['pick_us']:.1f}us {rows[-1]['pick_tflops']:.0f} TF")
             del A, C
