@@ -22,7 +22,8 @@
  *     and dominant occupancy; micro tunes execution efficiency, e.g. rasterisation for L2 reuse).
  *     swizzle 0: tiles in row-major order (XCD x of the 8 walks tile columns x, x+8, ...);
  *     swizzle 1 / 2: each XCD gets a contiguous range of a grouped order (groups of 4 / 8 tile rows
- *     walked column by column), so that tiles sharing a B panel run on the same XCD's L2.
+ *     walked column by column), so that tiles sharing a B panel run on the same XCD's L2.  A grid of
+ *     at most 8 tile rows is walked as one such group under every mode (row-major never pays there).
  */
 #ifndef WT_H
 #define WT_H

@@ -25,7 +25,8 @@
 //   * block rasterisation (the micro parameter).  Workgroups are dealt round-robin to the 8 XCDs,
 //     each with its own L2.  0 = row-major (so XCD x walks the tile columns x, x+8, ...);
 //     1 and 2 give each XCD a contiguous range of a grouped tile sequence (groups of 4 resp. 8
-//     tile rows walked column by column), so tiles that share a B panel meet in one L2.
+//     tile rows walked column by column), so tiles that share a B panel meet in one L2.  Grids of
+//     at most 8 tile rows are one such group under every mode.
 //   * split-K (structural parameter S > 1): the grid holds S blocks per output tile, block
 //     (tile, s) walks k-tiles [s*Ls, (s+1)*Ls) with Ls = ceil(K / (S*BK)), stores its fp32
 //     accumulators to a workspace slab, four registers per lane per 16-byte piece (fully coalesced), and bumps the tile's
@@ -74,8 +75,11 @@ constexpr uint32_t kOobOffset = 0x7FFFFFF0u;  // >= any num_records we set: read
 constexpr int kXcd = 8;
 constexpr int kGroupM = 8;
 
+// Grids of at most kGroupM tile rows are walked the same way under every mode: as one group, column by
+// column, each XCD taking a contiguous range.  On such grids row-major order is never the better one (the
+// XCDs would each stream every B panel), so the mode only distinguishes taller grids.
 __host__ __device__ __forceinline__ void tile_coords(int bid, int tiles_m, int tiles_n, int mode, int& tm, int& tn) {
-    if (mode == 0) {
+    if (mode == 0 && tiles_m > kGroupM) {
         tm = bid / tiles_n;
         tn = bid - tm * tiles_n;
         return;
@@ -85,7 +89,7 @@ __host__ __device__ __forceinline__ void tile_coords(int bid, int tiles_m, int t
     const int per = total / kXcd, rem = total - per * kXcd;
     const int xcd = bid % kXcd, local = bid / kXcd;
     const int id = xcd * per + (xcd < rem ? xcd : rem) + local;
-    const int rows = mode == 1 ? kGroupM / 2 : kGroupM;
+    const int rows = (mode == 1 && tiles_m > kGroupM) ? kGroupM / 2 : kGroupM;
     const int group = rows * tiles_n;
     const int gid = id / group;
     const int first_m = gid * rows;

@@ -352,6 +352,33 @@ def test_sweep_shapes_full_size_under_selected_config(ctx_bf16):
                        n_rows=6, n_cols=3)
 
 
+def test_stream_and_wave_stress_shapes_full_size_under_selected_config(ctx_bf16):
+    """Seeded picks from the 10 000-shape runtime stream (K = 8192 and 28672, where wt_select often
+    chooses split-K) and from the wave-quantisation stress set, at full size under wt_select's
+    configuration, checked on sampled rows and columns."""
+    import os
+
+    from paper_2604_10187_amd import tune
+
+    path = tune.table_path(wt.WT_BF16, wt.WT_OUT_BF16)
+    if not os.path.exists(path):
+        pytest.skip("no shipped dual table")
+    wt.wt_load(ctx_bf16, path)
+    stream = wt_synth.stream_shapes()
+    rng = np.random.default_rng(77)
+    shapes = [stream[i] for i in rng.choice(len(stream), size=10, replace=False)]
+    shapes += [s for s in stream if s[2] == 28672 and 100 <= s[0] <= 300][:2]        # split-K territory
+    shapes += wt_synth.wave_stress_shapes()[15::37]
+    n_split = 0
+    for (M, N, K) in shapes:
+        cfg = wt.wt_select(ctx_bf16, M, N, K)
+        n_split += cfg.split > 1
+        note(f"stream/wave {M}x{N}x{K} cfg={cfg.astuple()}")
+        _sampled_check(ctx_bf16, cfg, M, N, K, wt.WT_BF16, wt.WT_OUT_BF16, wt_synth.shape_seed(1005, M, N, K),
+                       n_rows=4, n_cols=2)
+    assert n_split >= 2
+
+
 def test_wave_count_on_device_context(ctx_f32):
     """Wave counts reported by the library on the device context equal the oracle's (bit-exact
     integers) in both capacity modes: 256 CUs, and 256 x the occupancy the HIP runtime reports."""

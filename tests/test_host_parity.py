@@ -409,14 +409,19 @@ def test_few_row_families_parity(ctx, tmp_path, row_fams):
 @pytest.mark.parametrize("tiles", [(1, 1), (1, 61), (3, 80), (5, 29), (7, 8), (16, 43), (38, 12), (64, 32), (9, 9)])
 def test_rasterisation_is_a_bijection(tiles):
     """The kernel's block -> tile mapping, evaluated on the host: every mode visits every tile exactly
-    once; modes 1/2 hand each XCD (block index mod 8) a contiguous range of the grouped order."""
+    once; modes 1/2 hand each XCD (block index mod 8) a contiguous range of the grouped order; grids of at
+    most 8 tile rows are walked as a single group whatever the mode."""
     tm_n, tn_n = tiles
     total = tm_n * tn_n
     for sw in (0, 1, 2):
         seen = [wt.wt_tile_coords(tm_n, tn_n, sw, b) for b in range(total)]
         assert sorted(seen) == [(i, j) for i in range(tm_n) for j in range(tn_n)]
-    assert [wt.wt_tile_coords(tm_n, tn_n, 0, b) for b in range(total)] == \
-        [(b // tn_n, b % tn_n) for b in range(total)]
+    modes = [[wt.wt_tile_coords(tm_n, tn_n, sw, b) for b in range(total)] for sw in (0, 1, 2)]
+    if tm_n > 8:     # tall grids: mode 0 is plain row-major and the three modes differ
+        assert modes[0] == [(b // tn_n, b % tn_n) for b in range(total)]
+        assert modes[0] != modes[1] != modes[2]
+    else:            # at most 8 tile rows: one group under every mode
+        assert modes[0] == modes[1] == modes[2]
     rows = 8
     order = []                                   # grouped order: groups of 8 tile rows, column by column
     for g0 in range(0, tm_n, rows):
