@@ -148,6 +148,13 @@ int wt_set_capacity_mode(wt_ctx* ctx, int mode);
 int wt_gemm(wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
             const float* scaleA, const float* scaleB, wt_cfg cfg, void* hip_stream);
 
+/* Launch policy (Sec. 3.2, note on persistent kernels: the launched grid is clamped to what the device holds
+ * at once while G remains the logical task count).  on = 1: every later launch of this context starts
+ * min(G, 256 x resident blocks per CU) blocks and block b runs tasks b, b + grid, b + 2*grid, ... of the same
+ * task list (same rasterisation, same split-K protocol, same results); on = 0 (default): one block per task.
+ * Phi, wave counts, tables and selection are unaffected. */
+int wt_set_persistent(wt_ctx* ctx, int on);
+
 /* ---- grouped GEMM (Table 2, grouped-GEMM row: G = sum_e ceil(M_e/bm) * ceil(N/bn), L = ceil(K/bk)) ---- */
 /* For every group e in [0, groups): C[r0:r1, :] = A[r0:r1, :] * B[e]^T with r0 = offsets[e], r1 = offsets[e+1].
  * A: [M_total, K] rows of all groups back to back; B: [groups, N, K]; C: [M_total, N]; all device pointers.

@@ -87,6 +87,7 @@ def lib():
             "wt_key_count": [vp, C.POINTER(C.c_int)],
             "wt_key_set_occ": [vp, C.c_int, C.c_int],
             "wt_set_capacity_mode": [vp, C.c_int],
+            "wt_set_persistent": [vp, C.c_int],
             "wt_tile_coords": [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)],
             "wt_gemm": [vp, i64, i64, i64, vp, vp, vp, vp, vp, wt_cfg, vp],
             "wt_gemm_grouped": [vp, i32, vp, i64, i64, i64, vp, vp, vp, vp, vp, wt_cfg, vp],
@@ -118,7 +119,7 @@ def lib():
 
 
 EXPORTS = ("wt_create", "wt_destroy", "wt_last_hip_error", "wt_status_string", "wt_config_count", "wt_config_get",
-           "wt_config_find", "wt_key_count", "wt_key_set_occ", "wt_set_capacity_mode", "wt_tile_coords", "wt_gemm", "wt_gemm_grouped",
+           "wt_config_find", "wt_key_count", "wt_key_set_occ", "wt_set_capacity_mode", "wt_set_persistent", "wt_tile_coords", "wt_gemm", "wt_gemm_grouped",
            "wt_time_gemm_grouped", "wt_wave_count_grouped", "wt_select_grouped", "wt_wave_count", "wt_sample_grid",
            "wt_sample_plan", "wt_profile_sparse", "wt_time_gemm", "wt_mfma_ceiling", "wt_fit", "wt_select", "wt_predict_us",
            "wt_select_bench", "wt_save", "wt_load")
@@ -203,6 +204,10 @@ def wt_key_set_occ(ctx, key_id: int, occ: int):
 
 def wt_set_capacity_mode(ctx, mode: int):
     _check(lib().wt_set_capacity_mode(ctx, mode), "wt_set_capacity_mode")
+
+
+def wt_set_persistent(ctx, on: bool):
+    _check(lib().wt_set_persistent(ctx, int(bool(on))), "wt_set_persistent")
 
 
 def wt_tile_coords(tiles_m, tiles_n, swizzle, block):

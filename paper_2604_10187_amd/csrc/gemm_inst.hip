@@ -29,7 +29,8 @@ namespace wt {
 
 #define WT_CFG(BM, BN, BK, WM, WN, ST)                                                      \
     {BM, BN, BK, WM, WN, ST, GemmTraits<BM, BN, BK, WM, WN, ST, WT_IN, WT_OUT>::LDS_BYTES, \
-     reinterpret_cast<const void*>(&gemm_kernel<BM, BN, BK, WM, WN, ST, WT_IN, WT_OUT>)},
+     reinterpret_cast<const void*>(&gemm_kernel<BM, BN, BK, WM, WN, ST, WT_IN, WT_OUT>),            \
+     reinterpret_cast<const void*>(&gemm_kernel_persistent<BM, BN, BK, WM, WN, ST, WT_IN, WT_OUT>)},
 static const KernelEntry kEntries[] = {
 #include "configs.def"
 };

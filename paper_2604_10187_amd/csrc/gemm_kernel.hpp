@@ -68,6 +68,7 @@ struct GemmArgs {
     // (ceil(M/BM) + groups) on the number of row tiles; surplus blocks exit at once.
     const int* group_offsets;
     int groups;
+    int vgrid;          // number of tasks; read by the persistent kernel only
 };
 
 constexpr int kWave = 64;
@@ -212,8 +213,9 @@ struct AccType<16> {
     using type = f32x4;
 };
 
+// One task of the launch: task `block_id` of the task list (a tile, or one split of a tile).
 template <int BM, int BN, int BK, int WM, int WN, int ST, int IN, int OUT>
-__global__ __launch_bounds__(WM* WN* kWave) void gemm_kernel(const GemmArgs args) {
+__device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_id) {
     using T = GemmTraits<BM, BN, BK, WM, WN, ST, IN, OUT>;
     using acc_t = typename AccType<T::MI>::type;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -221,349 +223,368 @@ __global__ __launch_bounds__(WM* WN* kWave) void gemm_kernel(const GemmArgs args
     const int lane = threadIdx.x & (kWave - 1);
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wv / WN, wn = wv - wm * WN;
+    {
+        // blocks [s*tiles, (s+1)*tiles) form split s; within a split the rasterisation is the usual one
+        int tile = block_id, split = 0;
+        if (args.splits > 1) {
+            const int tiles = args.tiles_m * args.tiles_n;
+            split = tile / tiles;
+            tile -= split * tiles;
+        }
+        int tm, tn;
+        tile_coords(tile, args.tiles_m, args.tiles_n, args.swizzle, tm, tn);
+        int row0 = tm * BM, m_end = args.M;
+        const int col0 = tn * BN;
+        const char* Bbase = static_cast<const char*>(args.B);
+        if (args.group_offsets) {
+            // tm counts row tiles over the groups' concatenated tile lists: find the group it falls in.
+            // Offsets are read on the device (the host never learns the routing) and clipped to [0, M],
+            // so whatever they hold, every access stays inside A, B[0..groups) and C.
+            int e = 0, first = 0, lo = 0, hi = 0;
+            for (; e < args.groups; ++e) {
+                lo = min(max(args.group_offsets[e], 0), args.M);
+                hi = min(max(args.group_offsets[e + 1], lo), args.M);
+                const int t = (hi - lo + BM - 1) / BM;
+                if (tm < first + t) break;
+                first += t;
+            }
+            if (e == args.groups) return;  // past the last row tile
+            row0 = lo + (tm - first) * BM;
+            m_end = hi;
+            Bbase += static_cast<int64_t>(e) * args.N * (static_cast<int64_t>(args.K) * T::esize);
+        }
+        // this block's k range [k0, k0 + K): the whole of args.K unless split
+        int k0 = 0, K = args.K;
+        if (args.splits > 1) {
+            k0 = split * args.k_per_split;
+            K = args.K - k0;
+            K = K < 0 ? 0 : (K > args.k_per_split ? args.k_per_split : K);
+            if (K == 0) k0 = 0;  // empty range: every load is sent out of range below
+        }
 
-    // blocks [s*tiles, (s+1)*tiles) form split s; within a split the rasterisation is the usual one
-    int tile = blockIdx.x, split = 0;
-    if (args.splits > 1) {
-        const int tiles = args.tiles_m * args.tiles_n;
-        split = tile / tiles;
-        tile -= split * tiles;
-    }
-    int tm, tn;
-    tile_coords(tile, args.tiles_m, args.tiles_n, args.swizzle, tm, tn);
-    int row0 = tm * BM, m_end = args.M;
-    const int col0 = tn * BN;
-    const char* Bbase = static_cast<const char*>(args.B);
-    if (args.group_offsets) {
-        // tm counts row tiles over the groups' concatenated tile lists: find the group it falls in.
-        // Offsets are read on the device (the host never learns the routing) and clipped to [0, M],
-        // so whatever they hold, every access stays inside A, B[0..groups) and C.
-        int e = 0, first = 0, lo = 0, hi = 0;
-        for (; e < args.groups; ++e) {
-            lo = min(max(args.group_offsets[e], 0), args.M);
-            hi = min(max(args.group_offsets[e + 1], lo), args.M);
-            const int t = (hi - lo + BM - 1) / BM;
-            if (tm < first + t) break;
-            first += t;
+        // ---- global -> LDS plan: this wavefront's LPW loads per stage --------------------------
+        const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+            (__attribute__((address_space(3))) char*)smem));
+        const int64_t row_bytes = static_cast<int64_t>(args.K) * T::esize;
+        const int64_t k0_bytes = static_cast<int64_t>(k0) * T::esize;
+        auto records = [&](int rows_left) -> uint32_t {  // bytes from the descriptor base to the end of the matrix
+            const int64_t b = static_cast<int64_t>(rows_left) * row_bytes - k0_bytes;
+            return b > static_cast<int64_t>(kOobOffset) ? kOobOffset : static_cast<uint32_t>(b);
+        };
+        const i32x4 rsrcA = make_rsrc(static_cast<const char*>(args.A) + static_cast<int64_t>(row0) * row_bytes + k0_bytes,
+                                      records(m_end - row0));
+        const i32x4 rsrcB = make_rsrc(Bbase + static_cast<int64_t>(col0) * row_bytes + k0_bytes,
+                                      records(args.N - col0));
+        // Load slot t of this wavefront fills the 1 KiB LDS piece j = wv + t*NW of a stage.  The lane's
+        // source offset at k-tile 0 stays in a register for the whole kernel; the k advance is a scalar.
+        // ld_tail[t] is the same offset for the one partial k-tile (K % BK != 0), already replaced by
+        // the out-of-range sentinel where the piece lies at or past K, so that it reads as zeros.
+        const int L = (K + BK - 1) / BK;
+        const int L_full = K / BK;
+        uint32_t ld_voff[T::LPW], ld_tail[T::LPW];
+    #pragma unroll
+        for (int t = 0; t < T::LPW; ++t) {
+            const int j = wv + t * T::NW;
+            const int p = j * kWave + lane;               // 16-byte slot index inside the stage
+            const int r = p / T::CPR;                     // staged row: [0,BM) = A, [BM,BM+BN) = B
+            const int slot = p % T::CPR;
+            const int chunk = slot ^ ((r >> T::SWZ_SH) & (T::CPR - 1));
+            const int rl = (j < T::A_INSTR) ? r : r - BM; // row inside its own matrix tile
+            ld_voff[t] = static_cast<uint32_t>(rl) * static_cast<uint32_t>(row_bytes) + chunk * 16;
+            ld_tail[t] = (L_full * BK + chunk * T::epc < K) ? ld_voff[t] : kOobOffset;
         }
-        if (e == args.groups) return;  // past the last row tile
-        row0 = lo + (tm - first) * BM;
-        m_end = hi;
-        Bbase += static_cast<int64_t>(e) * args.N * (static_cast<int64_t>(args.K) * T::esize);
-    }
-    // this block's k range [k0, k0 + K): the whole of args.K unless split
-    int k0 = 0, K = args.K;
-    if (args.splits > 1) {
-        k0 = split * args.k_per_split;
-        K = args.K - k0;
-        K = K < 0 ? 0 : (K > args.k_per_split ? args.k_per_split : K);
-        if (K == 0) k0 = 0;  // empty range: every load is sent out of range below
-    }
+        // One load: slot t of k-tile kt into LDS stage `stage`.  TAIL = the k-tile may be the partial one
+        // or lie past the end (then every piece is out of range and zero-fills the stage), so every
+        // k-tile index issues the same number of loads and the vmcnt bookkeeping stays uniform.
+        auto issue_load = [&](int t, int kt, int stage, bool tail) {
+            const int j = wv + t * T::NW;
+            const uint32_t dst = lds0 + stage * T::STAGE_BYTES + j * 1024;
+            // The hardware range-checks the per-lane offset only (the scalar offset is added after the
+            // check), so anything that must read as zeros is expressed through voff.
+            uint32_t koff = static_cast<uint32_t>(kt) * (BK * T::esize);
+            uint32_t voff = ld_voff[t];
+            if (tail) {
+                if (kt >= L_full) voff = (kt < L) ? ld_tail[t] : kOobOffset;  // uniform conditions
+                if (kt >= L) koff = 0;
+            }
+            if constexpr (T::SPLIT) {
+                if (t < T::A_INSTR / T::NW)
+                    load_lds_16B(rsrcA, voff, koff, dst);
+                else
+                    load_lds_16B(rsrcB, voff, koff, dst);
+            } else {
+                const bool is_a = j < T::A_INSTR;  // wave-uniform
+                i32x4 rs;
+                rs.x = is_a ? rsrcA.x : rsrcB.x;
+                rs.y = is_a ? rsrcA.y : rsrcB.y;
+                rs.z = is_a ? rsrcA.z : rsrcB.z;
+                rs.w = rsrcA.w;
+                load_lds_16B(rs, voff, koff, dst);
+            }
+        };
+        auto issue_tile = [&](int kt, int stage) {
+    #pragma unroll
+            for (int t = 0; t < T::LPW; ++t) issue_load(t, kt, stage, true);
+        };
 
-    // ---- global -> LDS plan: this wavefront's LPW loads per stage --------------------------
-    const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
-        (__attribute__((address_space(3))) char*)smem));
-    const int64_t row_bytes = static_cast<int64_t>(args.K) * T::esize;
-    const int64_t k0_bytes = static_cast<int64_t>(k0) * T::esize;
-    auto records = [&](int rows_left) -> uint32_t {  // bytes from the descriptor base to the end of the matrix
-        const int64_t b = static_cast<int64_t>(rows_left) * row_bytes - k0_bytes;
-        return b > static_cast<int64_t>(kOobOffset) ? kOobOffset : static_cast<uint32_t>(b);
-    };
-    const i32x4 rsrcA = make_rsrc(static_cast<const char*>(args.A) + static_cast<int64_t>(row0) * row_bytes + k0_bytes,
-                                  records(m_end - row0));
-    const i32x4 rsrcB = make_rsrc(Bbase + static_cast<int64_t>(col0) * row_bytes + k0_bytes,
-                                  records(args.N - col0));
-    // Load slot t of this wavefront fills the 1 KiB LDS piece j = wv + t*NW of a stage.  The lane's
-    // source offset at k-tile 0 stays in a register for the whole kernel; the k advance is a scalar.
-    // ld_tail[t] is the same offset for the one partial k-tile (K % BK != 0), already replaced by
-    // the out-of-range sentinel where the piece lies at or past K, so that it reads as zeros.
-    const int L = (K + BK - 1) / BK;
-    const int L_full = K / BK;
-    uint32_t ld_voff[T::LPW], ld_tail[T::LPW];
-#pragma unroll
-    for (int t = 0; t < T::LPW; ++t) {
-        const int j = wv + t * T::NW;
-        const int p = j * kWave + lane;               // 16-byte slot index inside the stage
-        const int r = p / T::CPR;                     // staged row: [0,BM) = A, [BM,BM+BN) = B
-        const int slot = p % T::CPR;
-        const int chunk = slot ^ ((r >> T::SWZ_SH) & (T::CPR - 1));
-        const int rl = (j < T::A_INSTR) ? r : r - BM; // row inside its own matrix tile
-        ld_voff[t] = static_cast<uint32_t>(rl) * static_cast<uint32_t>(row_bytes) + chunk * 16;
-        ld_tail[t] = (L_full * BK + chunk * T::epc < K) ? ld_voff[t] : kOobOffset;
-    }
-    // One load: slot t of k-tile kt into LDS stage `stage`.  TAIL = the k-tile may be the partial one
-    // or lie past the end (then every piece is out of range and zero-fills the stage), so every
-    // k-tile index issues the same number of loads and the vmcnt bookkeeping stays uniform.
-    auto issue_load = [&](int t, int kt, int stage, bool tail) {
-        const int j = wv + t * T::NW;
-        const uint32_t dst = lds0 + stage * T::STAGE_BYTES + j * 1024;
-        // The hardware range-checks the per-lane offset only (the scalar offset is added after the
-        // check), so anything that must read as zeros is expressed through voff.
-        uint32_t koff = static_cast<uint32_t>(kt) * (BK * T::esize);
-        uint32_t voff = ld_voff[t];
-        if (tail) {
-            if (kt >= L_full) voff = (kt < L) ? ld_tail[t] : kOobOffset;  // uniform conditions
-            if (kt >= L) koff = 0;
-        }
-        if constexpr (T::SPLIT) {
-            if (t < T::A_INSTR / T::NW)
-                load_lds_16B(rsrcA, voff, koff, dst);
-            else
-                load_lds_16B(rsrcB, voff, koff, dst);
-        } else {
-            const bool is_a = j < T::A_INSTR;  // wave-uniform
-            i32x4 rs;
-            rs.x = is_a ? rsrcA.x : rsrcB.x;
-            rs.y = is_a ? rsrcA.y : rsrcB.y;
-            rs.z = is_a ? rsrcA.z : rsrcB.z;
-            rs.w = rsrcA.w;
-            load_lds_16B(rs, voff, koff, dst);
-        }
-    };
-    auto issue_tile = [&](int kt, int stage) {
-#pragma unroll
-        for (int t = 0; t < T::LPW; ++t) issue_load(t, kt, stage, true);
-    };
-
-    // ---- fragment read plan -------------------------------------------------------------------
-    // lane -> (row inside an MFMA tile, first chunk along k)
-    const int frow = lane % T::MI;
-    const int fchunk = (lane / T::MI) * T::CPL;
-    acc_t acc[T::FM][T::FN];
-#pragma unroll
-    for (int i = 0; i < T::FM; ++i)
-#pragma unroll
-        for (int j = 0; j < T::FN; ++j)
-#pragma unroll
-            for (int e = 0; e < T::ACC; ++e) acc[i][j][e] = 0.0f;
-
-    using frag_t = typename FragType<IN>::type;
-    auto read_frag = [&](int stage, int r, int ks) -> frag_t {
-        const int sw = (r >> T::SWZ_SH) & (T::CPR - 1);
-        const char* row = smem + stage * T::STAGE_BYTES + r * T::RB;
-        const int c0 = ks * T::CPK + fchunk;
-        if constexpr (IN == 0) {
-            return *reinterpret_cast<const bf16x8*>(row + ((c0 ^ sw) * 16));
-        } else {
-            // fp8: each lane feeds 32 consecutive k (two 16-byte chunks) of its row
-            const i32x4 lo = *reinterpret_cast<const i32x4*>(row + ((c0 ^ sw) * 16));
-            const i32x4 hi = *reinterpret_cast<const i32x4*>(row + (((c0 + 1) ^ sw) * 16));
-            return i32x8{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-        }
-    };
-    struct Frags {
-        frag_t a[T::FM];
-        frag_t b[T::FN];
-    };
-    auto load_frags = [&](Frags& f, int stage, int ks) {
-#pragma unroll
-        for (int i = 0; i < T::FM; ++i) f.a[i] = read_frag(stage, wm * T::TM + i * T::MI + frow, ks);
-#pragma unroll
-        for (int j = 0; j < T::FN; ++j) f.b[j] = read_frag(stage, BM + wn * T::TN + j * T::MI + frow, ks);
-    };
-    auto mfma = [&](const Frags& f, int i, int j) {
-        if constexpr (IN == 0) {
-            if constexpr (T::MI == 32)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
-            else
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
-        } else {
-            // cbsz = blgp = 0 select e4m3 for both operands; unit block scales
-            if constexpr (T::MI == 32)
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f.a[i], f.b[j], acc[i][j], 0, 0, 0, 0, 0, 0);
-            else
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(f.a[i], f.b[j], acc[i][j], 0, 0, 0, 0, 0, 0);
-        }
-    };
-    auto mma = [&](const Frags& f) {
-#pragma unroll
+        // ---- fragment read plan -------------------------------------------------------------------
+        // lane -> (row inside an MFMA tile, first chunk along k)
+        const int frow = lane % T::MI;
+        const int fchunk = (lane / T::MI) * T::CPL;
+        acc_t acc[T::FM][T::FN];
+    #pragma unroll
         for (int i = 0; i < T::FM; ++i)
-#pragma unroll
-            for (int j = 0; j < T::FN; ++j) mfma(f, i, j);
-    };
+    #pragma unroll
+            for (int j = 0; j < T::FN; ++j)
+    #pragma unroll
+                for (int e = 0; e < T::ACC; ++e) acc[i][j][e] = 0.0f;
 
-    // ---- main loop --------------------------------------------------------------------------------
-    constexpr int KSTEPS = T::KSTEPS;
-    constexpr int NMK = T::NMK;
-    constexpr int NFR = T::FM + T::FN;  // fragments read per k-step
-    if constexpr (ST == 1) {
-        Frags f;
-        for (int kt = 0; kt < L; ++kt) {
-            issue_tile(kt, 0);
-            wait_vmcnt<0>();
-            block_barrier();
-#pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks) {
-                load_frags(f, 0, ks);
-                mma(f);
+        using frag_t = typename FragType<IN>::type;
+        auto read_frag = [&](int stage, int r, int ks) -> frag_t {
+            const int sw = (r >> T::SWZ_SH) & (T::CPR - 1);
+            const char* row = smem + stage * T::STAGE_BYTES + r * T::RB;
+            const int c0 = ks * T::CPK + fchunk;
+            if constexpr (IN == 0) {
+                return *reinterpret_cast<const bf16x8*>(row + ((c0 ^ sw) * 16));
+            } else {
+                // fp8: each lane feeds 32 consecutive k (two 16-byte chunks) of its row
+                const i32x4 lo = *reinterpret_cast<const i32x4*>(row + ((c0 ^ sw) * 16));
+                const i32x4 hi = *reinterpret_cast<const i32x4*>(row + (((c0 + 1) ^ sw) * 16));
+                return i32x8{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
             }
-            block_barrier();
-        }
-    } else {
-        // Software pipeline, one barrier per k-tile.  Every MFMA is followed by at most one fragment
-        // read and a share of the global->LDS loads, and the scheduler is fenced after each such
-        // group, so address arithmetic and memory issue sit in the shadow of the running MFMA.
-        //   * fragments of k-step ks+1 are read during the MFMAs of ks (two register sets);
-        //   * at the start of the last k-step the wavefront waits for its reads of k-tile t and for
-        //     its share of k-tile t+1, meets the others at the barrier (after which stage t%ST is
-        //     free and k-tile t+1 is complete), and reads k-tile t+1's first fragments during the
-        //     last MFMAs of k-tile t;
-        //   * refill: SPREAD (ST >= 3) issues k-tile t+ST-1 into the stage freed one barrier earlier,
-        //     evenly over all MFMAs of k-tile t; otherwise k-tile t+ST goes into the stage just freed,
-        //     over the MFMAs of the last k-step.
-        constexpr int AHEAD = T::SPREAD ? ST - 1 : ST;     // k-tiles issued by the prologue
-        constexpr int NM = KSTEPS * NMK;
-        // loads placed before the barrier point of a k-tile (SPREAD only)
-        constexpr int N_BEFORE = T::SPREAD ? ((KSTEPS - 1) * NMK * T::LPW + NM - 1) / NM : 0;
-        constexpr int WAIT_LOOP = T::SPREAD ? T::LPW * (ST - 3) + N_BEFORE : T::LPW * (ST - 2);
-        static_assert(WAIT_LOOP <= 63, "vmcnt range");
-        Frags f[2];
-#pragma unroll
-        for (int s = 0; s < AHEAD; ++s) issue_tile(s, s);
-        wait_vmcnt<T::LPW*(AHEAD - 1)>();
-        block_barrier();
-        load_frags(f[0], 0, 0);
-        int stage = 0;
-        auto read_one = [&](Frags& dst, int q, int stg, int ks) {
-            if (q < T::FM)
-                dst.a[q] = read_frag(stg, wm * T::TM + q * T::MI + frow, ks);
-            else
-                dst.b[q - T::FM] = read_frag(stg, BM + wn * T::TN + (q - T::FM) * T::MI + frow, ks);
         };
-        auto tile_body = [&](int kt, auto tail_tag) {
-            constexpr bool TAIL = decltype(tail_tag)::value;
-            const int nxt = (stage + 1 == ST) ? 0 : stage + 1;
-            int fill = stage + (ST - 1);      // SPREAD: stage of k-tile kt+ST-1
-            if (fill >= ST) fill -= ST;
-#pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks) {
-                const bool last = ks == KSTEPS - 1;
-                Frags& cur = f[ks & 1];
-                Frags& nx = f[(ks + 1) & 1];
-                if (last) {
-                    wait_lgkmcnt0();          // this wavefront's reads of k-tile kt are done
-                    wait_vmcnt<WAIT_LOOP>();  // its share of k-tile kt+1 has landed
-                    block_barrier();
-                    sched_fence();
+        struct Frags {
+            frag_t a[T::FM];
+            frag_t b[T::FN];
+        };
+        auto load_frags = [&](Frags& f, int stage, int ks) {
+    #pragma unroll
+            for (int i = 0; i < T::FM; ++i) f.a[i] = read_frag(stage, wm * T::TM + i * T::MI + frow, ks);
+    #pragma unroll
+            for (int j = 0; j < T::FN; ++j) f.b[j] = read_frag(stage, BM + wn * T::TN + j * T::MI + frow, ks);
+        };
+        auto mfma = [&](const Frags& f, int i, int j) {
+            if constexpr (IN == 0) {
+                if constexpr (T::MI == 32)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+                else
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+            } else {
+                // cbsz = blgp = 0 select e4m3 for both operands; unit block scales
+                if constexpr (T::MI == 32)
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f.a[i], f.b[j], acc[i][j], 0, 0, 0, 0, 0, 0);
+                else
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(f.a[i], f.b[j], acc[i][j], 0, 0, 0, 0, 0, 0);
+            }
+        };
+        auto mma = [&](const Frags& f) {
+    #pragma unroll
+            for (int i = 0; i < T::FM; ++i)
+    #pragma unroll
+                for (int j = 0; j < T::FN; ++j) mfma(f, i, j);
+        };
+
+        // ---- main loop --------------------------------------------------------------------------------
+        constexpr int KSTEPS = T::KSTEPS;
+        constexpr int NMK = T::NMK;
+        constexpr int NFR = T::FM + T::FN;  // fragments read per k-step
+        if constexpr (ST == 1) {
+            Frags f;
+            for (int kt = 0; kt < L; ++kt) {
+                issue_tile(kt, 0);
+                wait_vmcnt<0>();
+                block_barrier();
+    #pragma unroll
+                for (int ks = 0; ks < KSTEPS; ++ks) {
+                    load_frags(f, 0, ks);
+                    mma(f);
                 }
-#pragma unroll
-                for (int idx = 0; idx < NMK; ++idx) {
-                    mfma(cur, idx / T::FN, idx % T::FN);
-                    // fragment reads for the next k-step, spaced over this k-step's MFMAs and finished a few
-                    // MFMAs before its end so that their latency is covered
-#pragma unroll
-                    for (int q = 0; q < NFR; ++q)
-                        if ((q * (NMK > 4 ? NMK - 3 : 1)) / NFR == idx) read_one(nx, q, last ? nxt : stage, last ? 0 : ks + 1);
-                    // refill loads
-                    if constexpr (T::SPREAD) {
-                        const int g = ks * NMK + idx;
-#pragma unroll
-                        for (int l = 0; l < T::LPW; ++l)
-                            if ((l * NM) / T::LPW == g) issue_load(l, kt + ST - 1, fill, TAIL);
-                    } else {
-                        if (last) {
-#pragma unroll
-                            for (int l = 0; l < T::LPW; ++l)
-                                if ((l * NMK) / T::LPW == idx) issue_load(l, kt + ST, stage, TAIL);
-                        }
+                block_barrier();
+            }
+        } else {
+            // Software pipeline, one barrier per k-tile.  Every MFMA is followed by at most one fragment
+            // read and a share of the global->LDS loads, and the scheduler is fenced after each such
+            // group, so address arithmetic and memory issue sit in the shadow of the running MFMA.
+            //   * fragments of k-step ks+1 are read during the MFMAs of ks (two register sets);
+            //   * at the start of the last k-step the wavefront waits for its reads of k-tile t and for
+            //     its share of k-tile t+1, meets the others at the barrier (after which stage t%ST is
+            //     free and k-tile t+1 is complete), and reads k-tile t+1's first fragments during the
+            //     last MFMAs of k-tile t;
+            //   * refill: SPREAD (ST >= 3) issues k-tile t+ST-1 into the stage freed one barrier earlier,
+            //     evenly over all MFMAs of k-tile t; otherwise k-tile t+ST goes into the stage just freed,
+            //     over the MFMAs of the last k-step.
+            constexpr int AHEAD = T::SPREAD ? ST - 1 : ST;     // k-tiles issued by the prologue
+            constexpr int NM = KSTEPS * NMK;
+            // loads placed before the barrier point of a k-tile (SPREAD only)
+            constexpr int N_BEFORE = T::SPREAD ? ((KSTEPS - 1) * NMK * T::LPW + NM - 1) / NM : 0;
+            constexpr int WAIT_LOOP = T::SPREAD ? T::LPW * (ST - 3) + N_BEFORE : T::LPW * (ST - 2);
+            static_assert(WAIT_LOOP <= 63, "vmcnt range");
+            Frags f[2];
+    #pragma unroll
+            for (int s = 0; s < AHEAD; ++s) issue_tile(s, s);
+            wait_vmcnt<T::LPW*(AHEAD - 1)>();
+            block_barrier();
+            load_frags(f[0], 0, 0);
+            int stage = 0;
+            auto read_one = [&](Frags& dst, int q, int stg, int ks) {
+                if (q < T::FM)
+                    dst.a[q] = read_frag(stg, wm * T::TM + q * T::MI + frow, ks);
+                else
+                    dst.b[q - T::FM] = read_frag(stg, BM + wn * T::TN + (q - T::FM) * T::MI + frow, ks);
+            };
+            auto tile_body = [&](int kt, auto tail_tag) {
+                constexpr bool TAIL = decltype(tail_tag)::value;
+                const int nxt = (stage + 1 == ST) ? 0 : stage + 1;
+                int fill = stage + (ST - 1);      // SPREAD: stage of k-tile kt+ST-1
+                if (fill >= ST) fill -= ST;
+    #pragma unroll
+                for (int ks = 0; ks < KSTEPS; ++ks) {
+                    const bool last = ks == KSTEPS - 1;
+                    Frags& cur = f[ks & 1];
+                    Frags& nx = f[(ks + 1) & 1];
+                    if (last) {
+                        wait_lgkmcnt0();          // this wavefront's reads of k-tile kt are done
+                        wait_vmcnt<WAIT_LOOP>();  // its share of k-tile kt+1 has landed
+                        block_barrier();
+                        sched_fence();
                     }
-                    sched_fence();
+    #pragma unroll
+                    for (int idx = 0; idx < NMK; ++idx) {
+                        mfma(cur, idx / T::FN, idx % T::FN);
+                        // fragment reads for the next k-step, spaced over this k-step's MFMAs and finished a few
+                        // MFMAs before its end so that their latency is covered
+    #pragma unroll
+                        for (int q = 0; q < NFR; ++q)
+                            if ((q * (NMK > 4 ? NMK - 3 : 1)) / NFR == idx) read_one(nx, q, last ? nxt : stage, last ? 0 : ks + 1);
+                        // refill loads
+                        if constexpr (T::SPREAD) {
+                            const int g = ks * NMK + idx;
+    #pragma unroll
+                            for (int l = 0; l < T::LPW; ++l)
+                                if ((l * NM) / T::LPW == g) issue_load(l, kt + ST - 1, fill, TAIL);
+                        } else {
+                            if (last) {
+    #pragma unroll
+                                for (int l = 0; l < T::LPW; ++l)
+                                    if ((l * NMK) / T::LPW == idx) issue_load(l, kt + ST, stage, TAIL);
+                            }
+                        }
+                        sched_fence();
+                    }
                 }
-            }
-            if constexpr ((KSTEPS & 1) != 0) f[0] = f[1];
-            stage = nxt;
-        };
-        int kt = 0;
-        // k-tiles whose refill target lies wholly inside K need no range handling
-        for (; kt + AHEAD < L_full; ++kt) tile_body(kt, std::false_type{});
-        for (; kt < L; ++kt) tile_body(kt, std::true_type{});
-        wait_vmcnt<0>();
-    }
-
-    // ---- split-K reduction ---------------------------------------------------------------------
-    // Partial tiles travel as 16-byte buffer stores / loads marked agent-scope coherent (sc1): the
-    // stores write through the XCD's L2 and the loads are served coherently across the XCDs, so no
-    // cache-wide write-back or invalidate (what a device-scope fence costs here) is needed.  Order:
-    // this block's slab stores are waited for, then the block is counted in with an agent-scope
-    // atomic; the block that finds S-1 earlier arrivals knows every slab is in memory.
-    if (args.splits > 1) {
-        constexpr int NREG = T::FM * T::FN * T::ACC;
-        constexpr int NQ = NREG / 4;                      // 16-byte pieces per lane
-        constexpr int QPT = T::ACC / 4;                   // pieces per MFMA tile
-        constexpr uint32_t SLAB_BYTES = static_cast<uint32_t>(NREG) * T::NT * 4;   // = BM*BN*4
-        constexpr int SC1 = 16;                           // cache-policy bit: agent-scope coherence
-        static_assert(T::ACC % 4 == 0, "accumulators move in groups of four");
-        const int S = args.splits;
-        const __amdgpu_buffer_rsrc_t ws_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            args.ws + static_cast<size_t>(tile) * S * (SLAB_BYTES / 4), 0, static_cast<int>(S * SLAB_BYTES), 0x00020000);
-        const uint32_t lane_off = threadIdx.x * 16u;
-        const uint32_t mine = static_cast<uint32_t>(split) * SLAB_BYTES + lane_off;
-#pragma unroll
-        for (int q = 0; q < NQ; ++q) {
-            const int ij = q / QPT, e0 = 4 * (q % QPT);
-            const acc_t& a = acc[ij / T::FN][ij % T::FN];
-            const u32x4 v = {__float_as_uint(a[e0]), __float_as_uint(a[e0 + 1]), __float_as_uint(a[e0 + 2]),
-                             __float_as_uint(a[e0 + 3])};
-            __builtin_amdgcn_raw_buffer_store_b128(v, ws_rsrc, mine + q * (T::NT * 16), 0, SC1);
+                if constexpr ((KSTEPS & 1) != 0) f[0] = f[1];
+                stage = nxt;
+            };
+            int kt = 0;
+            // k-tiles whose refill target lies wholly inside K need no range handling
+            for (; kt + AHEAD < L_full; ++kt) tile_body(kt, std::false_type{});
+            for (; kt < L; ++kt) tile_body(kt, std::true_type{});
+            wait_vmcnt<0>();
         }
-        wait_vmcnt<0>();   // this lane's slab stores have been acknowledged
-        __syncthreads();   // ... and everybody's; every wavefront is also past its last LDS access
-        int* flag = reinterpret_cast<int*>(smem);
-        if (threadIdx.x == 0)
-            *flag = __hip_atomic_fetch_add(args.counters + tile, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __syncthreads();
-        if (*flag != S - 1) return;
-        // Sum in split order, whatever the arrival order.  S is dispatched to a compile-time constant
-        // so that the loads of all slabs are independent and in flight together.
-        auto reduce = [&](auto s_tag) {
-            constexpr int SS = decltype(s_tag)::value;
-#pragma unroll
+
+        // ---- split-K reduction ---------------------------------------------------------------------
+        // Partial tiles travel as 16-byte buffer stores / loads marked agent-scope coherent (sc1): the
+        // stores write through the XCD's L2 and the loads are served coherently across the XCDs, so no
+        // cache-wide write-back or invalidate (what a device-scope fence costs here) is needed.  Order:
+        // this block's slab stores are waited for, then the block is counted in with an agent-scope
+        // atomic; the block that finds S-1 earlier arrivals knows every slab is in memory.
+        if (args.splits > 1) {
+            constexpr int NREG = T::FM * T::FN * T::ACC;
+            constexpr int NQ = NREG / 4;                      // 16-byte pieces per lane
+            constexpr int QPT = T::ACC / 4;                   // pieces per MFMA tile
+            constexpr uint32_t SLAB_BYTES = static_cast<uint32_t>(NREG) * T::NT * 4;   // = BM*BN*4
+            constexpr int SC1 = 16;                           // cache-policy bit: agent-scope coherence
+            static_assert(T::ACC % 4 == 0, "accumulators move in groups of four");
+            const int S = args.splits;
+            const __amdgpu_buffer_rsrc_t ws_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                args.ws + static_cast<size_t>(tile) * S * (SLAB_BYTES / 4), 0, static_cast<int>(S * SLAB_BYTES), 0x00020000);
+            const uint32_t lane_off = threadIdx.x * 16u;
+            const uint32_t mine = static_cast<uint32_t>(split) * SLAB_BYTES + lane_off;
+    #pragma unroll
             for (int q = 0; q < NQ; ++q) {
                 const int ij = q / QPT, e0 = 4 * (q % QPT);
-                float v0 = 0.0f, v1 = 0.0f, v2 = 0.0f, v3 = 0.0f;
-#pragma unroll
-                for (int sp = 0; sp < SS; ++sp) {
-                    const u32x4 p = __builtin_amdgcn_raw_buffer_load_b128(
-                        ws_rsrc, sp * SLAB_BYTES + lane_off + q * (T::NT * 16), 0, SC1);
-                    v0 += __uint_as_float(p.x); v1 += __uint_as_float(p.y);
-                    v2 += __uint_as_float(p.z); v3 += __uint_as_float(p.w);
-                }
-                acc_t& a = acc[ij / T::FN][ij % T::FN];
-                a[e0] = v0; a[e0 + 1] = v1; a[e0 + 2] = v2; a[e0 + 3] = v3;
+                const acc_t& a = acc[ij / T::FN][ij % T::FN];
+                const u32x4 v = {__float_as_uint(a[e0]), __float_as_uint(a[e0 + 1]), __float_as_uint(a[e0 + 2]),
+                                 __float_as_uint(a[e0 + 3])};
+                __builtin_amdgcn_raw_buffer_store_b128(v, ws_rsrc, mine + q * (T::NT * 16), 0, SC1);
             }
-        };
-        if (S == 2) reduce(std::integral_constant<int, 2>{});
-        else if (S == 4) reduce(std::integral_constant<int, 4>{});
-        else reduce(std::integral_constant<int, 8>{});
-        if (threadIdx.x == 0)   // ready for the next launch on this stream
-            __hip_atomic_store(args.counters + tile, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
+            wait_vmcnt<0>();   // this lane's slab stores have been acknowledged
+            __syncthreads();   // ... and everybody's; every wavefront is also past its last LDS access
+            int* flag = reinterpret_cast<int*>(smem);
+            if (threadIdx.x == 0)
+                *flag = __hip_atomic_fetch_add(args.counters + tile, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            if (*flag != S - 1) return;
+            // Sum in split order, whatever the arrival order.  S is dispatched to a compile-time constant
+            // so that the loads of all slabs are independent and in flight together.
+            auto reduce = [&](auto s_tag) {
+                constexpr int SS = decltype(s_tag)::value;
+    #pragma unroll
+                for (int q = 0; q < NQ; ++q) {
+                    const int ij = q / QPT, e0 = 4 * (q % QPT);
+                    float v0 = 0.0f, v1 = 0.0f, v2 = 0.0f, v3 = 0.0f;
+    #pragma unroll
+                    for (int sp = 0; sp < SS; ++sp) {
+                        const u32x4 p = __builtin_amdgcn_raw_buffer_load_b128(
+                            ws_rsrc, sp * SLAB_BYTES + lane_off + q * (T::NT * 16), 0, SC1);
+                        v0 += __uint_as_float(p.x); v1 += __uint_as_float(p.y);
+                        v2 += __uint_as_float(p.z); v3 += __uint_as_float(p.w);
+                    }
+                    acc_t& a = acc[ij / T::FN][ij % T::FN];
+                    a[e0] = v0; a[e0 + 1] = v1; a[e0 + 2] = v2; a[e0 + 3] = v3;
+                }
+            };
+            if (S == 2) reduce(std::integral_constant<int, 2>{});
+            else if (S == 4) reduce(std::integral_constant<int, 4>{});
+            else reduce(std::integral_constant<int, 8>{});
+            if (threadIdx.x == 0)   // ready for the next launch on this stream
+                __hip_atomic_store(args.counters + tile, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
 
-    // ---- epilogue ---------------------------------------------------------------------------------
-    float scale = 1.0f;
-    if constexpr (IN == 1) scale = args.scaleA[0] * args.scaleB[0];
-    const int M = m_end, N = args.N;
-#pragma unroll
-    for (int i = 0; i < T::FM; ++i) {
-#pragma unroll
-        for (int j = 0; j < T::FN; ++j) {
-            const int col = col0 + wn * T::TN + j * T::MI + (lane % T::MI);
-#pragma unroll
-            for (int e = 0; e < T::ACC; ++e) {
-                // 32x32: row = 8*(e/4) + 4*(lane/32) + e%4 ; 16x16: row = 4*(lane/16) + e
-                const int rin = (T::MI == 32) ? (8 * (e / 4) + 4 * (lane / 32) + (e % 4)) : (4 * (lane / 16) + e);
-                const int row = row0 + wm * T::TM + i * T::MI + rin;
-                if (row < M && col < N) {
-                    float v = acc[i][j][e];
-                    if constexpr (IN == 1) v *= scale;
-                    const int64_t idx = static_cast<int64_t>(row) * N + col;
-                    if constexpr (OUT == 0)
-                        static_cast<float*>(args.C)[idx] = v;
-                    else
-                        static_cast<__bf16*>(args.C)[idx] = static_cast<__bf16>(v);
+        // ---- epilogue ---------------------------------------------------------------------------------
+        float scale = 1.0f;
+        if constexpr (IN == 1) scale = args.scaleA[0] * args.scaleB[0];
+        const int M = m_end, N = args.N;
+    #pragma unroll
+        for (int i = 0; i < T::FM; ++i) {
+    #pragma unroll
+            for (int j = 0; j < T::FN; ++j) {
+                const int col = col0 + wn * T::TN + j * T::MI + (lane % T::MI);
+    #pragma unroll
+                for (int e = 0; e < T::ACC; ++e) {
+                    // 32x32: row = 8*(e/4) + 4*(lane/32) + e%4 ; 16x16: row = 4*(lane/16) + e
+                    const int rin = (T::MI == 32) ? (8 * (e / 4) + 4 * (lane / 32) + (e % 4)) : (4 * (lane / 16) + e);
+                    const int row = row0 + wm * T::TM + i * T::MI + rin;
+                    if (row < M && col < N) {
+                        float v = acc[i][j][e];
+                        if constexpr (IN == 1) v *= scale;
+                        const int64_t idx = static_cast<int64_t>(row) * N + col;
+                        if constexpr (OUT == 0)
+                            static_cast<float*>(args.C)[idx] = v;
+                        else
+                            static_cast<__bf16*>(args.C)[idx] = static_cast<__bf16>(v);
+                    }
                 }
             }
         }
+    }
+}
+
+// One block per task.
+template <int BM, int BN, int BK, int WM, int WN, int ST, int IN, int OUT>
+__global__ __launch_bounds__(WM* WN* kWave) void gemm_kernel(const GemmArgs args) {
+    gemm_task<BM, BN, BK, WM, WN, ST, IN, OUT>(args, blockIdx.x);
+}
+
+// Persistent launch (Sec. 3.2, note on persistent kernels): the host starts only as many blocks as can be
+// resident at once and block b runs the tasks b, b + gridDim.x, ... of the same task list, so G stays the
+// logical task count while the physical grid is clamped.  Kept as a kernel of its own: wrapping the task in
+// a loop costs the one-block-per-task path 1-5 % (registers that stay live across tasks).
+template <int BM, int BN, int BK, int WM, int WN, int ST, int IN, int OUT>
+__global__ __launch_bounds__(WM* WN* kWave) void gemm_kernel_persistent(const GemmArgs args) {
+    for (int b = blockIdx.x; b < args.vgrid; b += gridDim.x) {
+        gemm_task<BM, BN, BK, WM, WN, ST, IN, OUT>(args, b);
+        if (b + static_cast<int>(gridDim.x) < args.vgrid) __syncthreads();  // LDS is reused by the next task
     }
 }
 

@@ -8,6 +8,7 @@ struct KernelEntry {
     int bm, bn, bk, wm, wn, st;
     int lds_bytes;
     const void* fn;  // __global__ function taking GemmArgs by value (NULL in a host-only build)
+    const void* fn_persistent;  // the same configuration as a persistent kernel
 };
 
 // list: 0 = large, 1 = medium, 2 = small.  in: 0 bf16, 1 fp8.  out: 0 f32, 1 bf16.

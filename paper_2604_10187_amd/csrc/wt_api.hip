@@ -73,9 +73,13 @@ int launch(wt_ctx* ctx, const Config& c, const Problem& p, hipStream_t stream) {
     args.counters = ctx->counters;
     args.group_offsets = p.groups > 0 ? p.offsets : nullptr;
     args.groups = p.groups;
+    args.vgrid = (int)G;
+    // persistent launch: as many blocks as the device holds at once, each walking the task list with that stride
+    const int64_t resident = (int64_t)kNumCU * std::max(1, c.occ_persistent);
+    const int64_t grid = ctx->persistent ? std::min(G, resident) : G;
     if (key.split > 1 && (!ctx->ws || !ctx->counters)) return WT_ERR_NO_DEVICE;
     void* params[] = {&args};
-    WT_HIP(ctx, hipLaunchKernel(c.fn, dim3((unsigned)G), dim3((unsigned)(c.cfg.nwave * 64)), params,
+    WT_HIP(ctx, hipLaunchKernel(ctx->persistent ? c.fn_persistent : c.fn, dim3((unsigned)grid), dim3((unsigned)(c.cfg.nwave * 64)), params,
                                 (size_t)c.res.lds_bytes, stream));
     return WT_OK;
 }
@@ -241,6 +245,8 @@ int wt_create(wt_ctx** out, int device, int in_type, int out_type) {
             hipFuncAttributes fa;
             memset(&fa, 0, sizeof(fa));
             e = hipFuncSetAttribute(c0.fn, hipFuncAttributeMaxDynamicSharedMemorySize, key.lds_bytes);
+            if (e == hipSuccess)
+                e = hipFuncSetAttribute(c0.fn_persistent, hipFuncAttributeMaxDynamicSharedMemorySize, key.lds_bytes);
             if (e == hipSuccess) e = hipFuncGetAttributes(&fa, c0.fn);
             if (e == hipSuccess)
                 e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, c0.fn, key.nwave * 64, (size_t)key.lds_bytes);
@@ -248,9 +254,16 @@ int wt_create(wt_ctx** out, int device, int in_type, int out_type) {
             key.vgprs = fa.numRegs;
             key.occ = occ;
             key.cap = key_capacity(ctx->cap_mode, occ);
+            int occ_p = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_p, c0.fn_persistent, key.nwave * 64,
+                                                             (size_t)key.lds_bytes) != hipSuccess) {
+                (void)hipGetLastError();
+                occ_p = 1;
+            }
             for (int m = 0; m < key.n_micro; ++m) {
                 ctx->cfgs[key.first_cfg + m].res.occ = occ;
                 ctx->cfgs[key.first_cfg + m].res.vgprs = fa.numRegs;
+                ctx->cfgs[key.first_cfg + m].occ_persistent = std::max(1, occ_p);
             }
         }
     }
@@ -264,6 +277,12 @@ int wt_destroy(wt_ctx* ctx) {
     if (ctx->ev_stop) (void)hipEventDestroy((hipEvent_t)ctx->ev_stop);
     if (ctx->ws) (void)hipFree(ctx->ws);
     delete ctx;
+    return WT_OK;
+}
+
+int wt_set_persistent(wt_ctx* ctx, int on) {
+    if (!ctx || (on != 0 && on != 1)) return WT_ERR_INVALID_ARG;
+    ctx->persistent = on;
     return WT_OK;
 }
 

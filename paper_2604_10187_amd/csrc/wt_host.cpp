@@ -91,6 +91,7 @@ static void add_key(wt_ctx* ctx, const KernelEntry& e, int split) {
         c.res = wt_cfg_res{k.lds_bytes, k.vgprs, k.nwave, k.occ, key_id, sw};
         c.wm = e.wm; c.wn = e.wn;
         c.fn = e.fn;
+        c.fn_persistent = e.fn_persistent;
         ctx->cfgs.push_back(c);
     }
     ctx->keys.push_back(k);

@@ -26,6 +26,8 @@ struct Config {
     wt_cfg_res res;
     int wm, wn;
     const void* fn;
+    const void* fn_persistent;
+    int occ_persistent = 1;  // resident blocks per CU of the persistent kernel (its grid is 256 x this)
 };
 
 struct Key {
@@ -68,6 +70,7 @@ struct wt_ctx {
     int in_type = 0, out_type = 0;
     int last_hip = 0;
     int cap_mode = WT_CAP_CU_ONLY;  // wt_cap_mode
+    int persistent = 0;             // 1: launches clamp the grid to the resident block count
     std::vector<wt::Config> cfgs;
     std::vector<wt::Key> keys;
     wt::Table table;

@@ -267,6 +267,41 @@ def cmd_grouped(a, torch):
             "summary": summary, "rows": rows}
 
 
+def cmd_persistent(a, torch):
+    """Persistent launch (grid clamped to the resident block count, blocks walk the task list) against the
+    ordinary one block per task, same configuration (wt_select's pick), same protocol, on the sweep, the
+    large prefill and a sample of the stream."""
+    import wt_synth
+
+    ctx, path = _open_ctx(a, torch)
+    stream = torch.cuda.current_stream()
+    rng = np.random.default_rng(2007)
+    st = wt_synth.stream_shapes()
+    shapes = wt_synth.sweep_shapes() + [(16384, 8192, 8192)] + [st[i] for i in rng.choice(len(st), size=40, replace=False)]
+    rows = []
+    for (M, N, K) in shapes:
+        A, B, C, sA, sB = _dev_operands(torch, M, N, K, a.in_type, a.out_type)
+        cfg = wt.wt_select(ctx, M, N, K)
+        G, L, w = wt.wt_wave_count(ctx, M, N, K, cfg)
+        t = []
+        for rep in range(2):                     # alternate to cancel clock drift
+            for on in (False, True):
+                wt.wt_set_persistent(ctx, on)
+                t.append(wt.wt_time_gemm(ctx, M, N, K, A, B, C, cfg, 3, 10, sA, sB, stream))
+        wt.wt_set_persistent(ctx, False)
+        plain, pers = min(t[0], t[2]), min(t[1], t[3])
+        rows.append({"M": M, "N": N, "K": K, "cfg": list(cfg.astuple()), "tasks": G, "waves": w,
+                     "plain_us": plain, "persistent_us": pers, "speedup": plain / pers})
+        _log(f"[eval] persistent {M}x{N}x{K} {cfg.astuple()} tasks {G}: {plain:.1f} -> {pers:.1f} us ({plain / pers:.3f}x)")
+    multi = [r["speedup"] for r in rows if r["waves"] > 1]
+    sp = np.array([r["speedup"] for r in rows])
+    summary = {"n_shapes": len(rows), "geomean_speedup": float(np.exp(np.mean(np.log(sp)))),
+               "geomean_speedup_multi_wave": float(np.exp(np.mean(np.log(multi)))) if multi else None,
+               "min": float(sp.min()), "max": float(sp.max())}
+    return {"workload": "persistent vs one-block-per-task launch under wt_select's configuration", "table": path,
+            "summary": summary, "rows": rows}
+
+
 def cmd_ablate(a, torch=None):
     """CPU only.  Re-fit the saved profiling records under model / (W, I) variants with wt_fit on a
     host-only context and score each variant's picks against saved exhaustive timings (the `times` of
@@ -329,7 +364,7 @@ def cmd_ablate(a, torch=None):
 
 def main(argv=None):
     ap = argparse.ArgumentParser()
-    ap.add_argument("cmd", choices=["sweep", "wave", "stream", "large", "grouped", "ablate"])
+    ap.add_argument("cmd", choices=["sweep", "wave", "stream", "large", "grouped", "persistent", "ablate"])
     ap.add_argument("--samples", default=None, help="ablate: .npz with `samples` and `occ`")
     ap.add_argument("--scores", nargs="*", default=[], help="ablate: sweep/stream result files with exhaustive timings")
     ap.add_argument("--cap-mode", type=int, default=1)
@@ -351,7 +386,7 @@ def main(argv=None):
     else:
         import torch
 
-        res = {"sweep": cmd_sweep, "wave": cmd_wave, "stream": cmd_stream, "large": cmd_large, "grouped": cmd_grouped}[a.cmd](a, torch)
+        res = {"sweep": cmd_sweep, "wave": cmd_wave, "stream": cmd_stream, "large": cmd_large, "grouped": cmd_grouped, "persistent": cmd_persistent}[a.cmd](a, torch)
     txt = json.dumps(res)
     if a.out:
         open(a.out, "w").write(txt)

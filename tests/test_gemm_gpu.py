@@ -163,6 +163,60 @@ def test_split_k_workspace_limit(ctx_f32):
     assert e.value.status == wt.WT_ERR_INFEASIBLE
 
 
+# ---- persistent launches ---------------------------------------------------------------------------
+def test_persistent_launch_bit_exact(ctx_f32):
+    """Grid clamped to the resident block count: on problems with more tasks than that, every structural
+    key (split-K ones included) must give the bits of the one-block-per-task launch and of the oracle."""
+    import math
+
+    wt.wt_set_persistent(ctx_f32, True)
+    try:
+        for cfg, res in all_configs(ctx_f32):
+            if cfg.swizzle != cfg.id // 3 % 3:
+                continue
+            need = (256 * res.occ) // cfg.split + 37            # tiles, so that tasks exceed what is resident
+            tm = max(2, math.isqrt(need))
+            tn = -(-need // tm) + 1
+            M, N, K = tm * cfg.bm - 3, tn * cfg.bn - 5, cfg.split * cfg.bk + 24
+            G, L, w = wt.wt_wave_count(ctx_f32, M, N, K, cfg)
+            assert G > 256 * res.occ
+            note(f"persistent cfg={cfg.astuple()} shape={(M, N, K)} tasks={G} resident={256 * res.occ}")
+            ab, bb = _bf16_case(M, N, K, 300 + cfg.id, "int")
+            got = run_gemm(ctx_f32, cfg, ab, bb, wt.WT_OUT_F32, fill=float("nan"))
+            assert np.array_equal(got, og.gemm_c(ab, bb)), f"{cfg}"
+    finally:
+        wt.wt_set_persistent(ctx_f32, False)
+
+
+def test_persistent_grouped_and_normal(ctx_bf16):
+    """Persistent launch of a grouped problem (surplus blocks past the last row tile) and of an N(0,1)
+    problem spanning several waves, bf16 out."""
+    wt.wt_set_persistent(ctx_bf16, True)
+    try:
+        counts = [700, 0, 33, 1, 900, 64, 2000]
+        off = wt_synth.group_offsets(counts)
+        E, N, K = len(counts), 1000, 264
+        a32, _ = wt_synth.gemm_operands(int(off[-1]), 8, K, 8901)
+        b32, _ = wt_synth.gemm_operands(E * N, 8, K, 8902)
+        ab, bb = wt_synth.to_bf16_bits(a32), wt_synth.to_bf16_bits(b32).reshape(E, N, K)
+        want = og.grouped_gemm_c(ab, bb, off)
+        for fields in ((64, 64, 64, 4, 2, 1), (32, 64, 128, 4, 3, 2), (128, 128, 64, 4, 3, 0)):
+            cfg, _ = wt.wt_config_get(ctx_bf16, wt.wt_config_find(ctx_bf16, *fields))
+            note(f"persistent grouped cfg={cfg.astuple()}")
+            got = run_gemm_grouped(ctx_bf16, cfg, ab, bb, off, wt.WT_OUT_BF16)
+            assert og.max_scaled_err(got, want) <= 2.0 ** -8
+        M, N, K = 2500, 3000, 1032
+        ab, bb = _bf16_case(M, N, K, 8903, "normal")
+        want = og.gemm_c(ab, bb)
+        for fields in ((64, 64, 128, 4, 3, 1), (128, 128, 64, 4, 4, 2), (64, 64, 128, 4, 3, 0, 2)):
+            cfg, _ = wt.wt_config_get(ctx_bf16, wt.wt_config_find(ctx_bf16, *fields))
+            note(f"persistent normal cfg={cfg.astuple()}")
+            got = run_gemm(ctx_bf16, cfg, ab, bb, wt.WT_OUT_BF16)
+            assert og.max_scaled_err(got, want) <= 2.0 ** -8
+    finally:
+        wt.wt_set_persistent(ctx_bf16, False)
+
+
 # ---- grouped GEMM ---------------------------------------------------------------------------------
 def test_grouped_integer_bit_exact(ctx_f32):
     """Ragged groups (one empty, one of a single row, sizes that are no multiple of any tile) on integer
