@@ -240,15 +240,42 @@ __device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_
             // tm counts row tiles over the groups' concatenated tile lists: find the group it falls in.
             // Offsets are read on the device (the host never learns the routing) and clipped to [0, M],
             // so whatever they hold, every access stays inside A, B[0..groups) and C.
-            int e = 0, first = 0, lo = 0, hi = 0;
-            for (; e < args.groups; ++e) {
+            // Every wavefront does the lookup for itself: lane l sums the tiles of groups [l*c, (l+1)*c),
+            // a scan over the lanes locates the lane whose range holds tm, and only that lane's <= c groups
+            // are walked one by one (a serial walk over all groups costs ~0.2 us per group and block, more
+            // than a small tile's arithmetic when there are a hundred experts).
+            const int E = args.groups;
+            auto bounds = [&](int e, int& lo, int& hi) {
                 lo = min(max(args.group_offsets[e], 0), args.M);
                 hi = min(max(args.group_offsets[e + 1], lo), args.M);
-                const int t = (hi - lo + BM - 1) / BM;
-                if (tm < first + t) break;
+                return (hi - lo + BM - 1) / BM;
+            };
+            const int c = (E + kWave - 1) / kWave;
+            int mine = 0;
+            for (int i = 0; i < c; ++i) {
+                const int e = lane * c + i;
+                int lo, hi;
+                if (e < E) mine += bounds(e, lo, hi);
+            }
+            int incl = mine;
+#pragma unroll
+            for (int d = 1; d < kWave; d <<= 1) {
+                const int v = __shfl_up(incl, d);
+                if (lane >= d) incl += v;
+            }
+            const int excl = incl - mine;
+            const unsigned long long hit = __ballot(tm >= excl && tm < incl);
+            if (hit == 0) return;  // past the last row tile
+            const int src = __builtin_amdgcn_readfirstlane(__ffsll(static_cast<long long>(hit)) - 1);
+            int first = __builtin_amdgcn_readfirstlane(__shfl(excl, src));
+            int e = src * c, lo = 0, hi = 0;
+            bool found = false;
+            for (int i = 0; i < c && e < E; ++i, ++e) {
+                const int t = bounds(e, lo, hi);
+                if (tm < first + t) { found = true; break; }
                 first += t;
             }
-            if (e == args.groups) return;  // past the last row tile
+            if (!found) return;
             row0 = lo + (tm - first) * BM;
             m_end = hi;
             Bbase += static_cast<int64_t>(e) * args.N * (static_cast<int64_t>(args.K) * T::esize);
