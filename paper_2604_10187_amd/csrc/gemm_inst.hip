@@ -27,14 +27,16 @@
 
 namespace wt {
 
-#define WT_CFG(BM, BN, BK, WM, WN, ST)                                                      \
-    {BM, BN, BK, WM, WN, ST, GemmTraits<BM, BN, BK, WM, WN, ST, WT_IN, WT_OUT>::LDS_BYTES, \
-     reinterpret_cast<const void*>(&gemm_kernel<BM, BN, BK, WM, WN, ST, WT_IN, WT_OUT>),            \
-     reinterpret_cast<const void*>(&gemm_kernel_persistent<BM, BN, BK, WM, WN, ST, WT_IN, WT_OUT>)},
+#define WT_CFGK(BM, BN, BK, WM, WN, WK, ST)                                                      \
+    {BM, BN, BK, WM, WN, WK, ST, GemmTraits<BM, BN, BK, WM, WN, ST, WT_IN, WT_OUT, WK>::LDS_BYTES, \
+     reinterpret_cast<const void*>(&gemm_kernel<BM, BN, BK, WM, WN, ST, WT_IN, WT_OUT, WK>),       \
+     reinterpret_cast<const void*>(&gemm_kernel_persistent<BM, BN, BK, WM, WN, ST, WT_IN, WT_OUT, WK>)},
+#define WT_CFG(BM, BN, BK, WM, WN, ST) WT_CFGK(BM, BN, BK, WM, WN, 1, ST)
 static const KernelEntry kEntries[] = {
 #include "configs.def"
 };
 #undef WT_CFG
+#undef WT_CFGK
 
 const KernelEntry* WT_FN_NAME(int* n) {
     *n = static_cast<int>(sizeof(kEntries) / sizeof(kEntries[0]));

@@ -150,9 +150,9 @@ struct InTraits<1> {  // fp8 e4m3
     static constexpr int epc = 16;
 };
 
-template <int BM, int BN, int BK, int WM, int WN, int ST, int IN, int OUT>
+template <int BM, int BN, int BK, int WM, int WN, int ST, int IN, int OUT, int WK = 1>
 struct GemmTraits {
-    static constexpr int NW = WM * WN;
+    static constexpr int NW = WM * WN * WK;  // WK wavefronts share a sub-tile and divide each k-tile's k-steps
     static constexpr int NT = NW * kWave;
     static constexpr int esize = InTraits<IN>::esize;
     static constexpr int epc = InTraits<IN>::epc;
@@ -166,7 +166,9 @@ struct GemmTraits {
     static constexpr int CPK = KS * esize / 16;  // chunks one MFMA consumes along k per row
     static constexpr int CPL = CPK / (kWave / MI);  // chunks per lane per MFMA operand
     static constexpr int STAGE_BYTES = (BM + BN) * RB;
-    static constexpr int LDS_BYTES = STAGE_BYTES * ST;
+    // with WK > 1 the stages are reused, after the main loop, for the partial sub-tiles of the wavefronts wk > 0
+    static constexpr int RED_BYTES = (WK - 1) * BM * BN * 4;
+    static constexpr int LDS_BYTES = STAGE_BYTES * ST > RED_BYTES ? STAGE_BYTES * ST : RED_BYTES;
     static constexpr int A_INSTR = BM * CPR / kWave;  // 1 KiB wavefront loads per stage
     static constexpr int B_INSTR = BN * CPR / kWave;
     static constexpr int LPW = (A_INSTR + B_INSTR) / NW;  // loads per wavefront per stage
@@ -176,12 +178,14 @@ struct GemmTraits {
     static constexpr int FM = TM / MI, FN = TN / MI;
     static constexpr int ACC = MI * MI / kWave;  // accumulator floats per lane per MFMA tile
     static constexpr int KSTEPS = BK / KS;
+    static constexpr int KSW = KSTEPS / WK;       // k-steps of a k-tile that one wavefront computes
     static constexpr int NMK = FM * FN;           // MFMAs per k-step per wavefront
     // With three or more stages the refill of a freed stage is spread over a whole k-tile (the
     // loads of k-tile t+ST-1 ride along the MFMAs of k-tile t); with two stages it has to follow the
     // barrier inside the last k-step (k-tile t+ST then rides along the last MFMAs of k-tile t).
     static constexpr bool SPREAD = ST >= 3;
     static_assert(BK % KS == 0, "BK must hold whole MFMA k-steps");
+    static_assert(KSTEPS % WK == 0, "k-steps divide evenly over the WK wavefronts");
     static_assert((BM * CPR) % kWave == 0 && (BN * CPR) % kWave == 0, "whole 1 KiB loads");
     static_assert((A_INSTR + B_INSTR) % NW == 0, "equal loads per wavefront");
     static_assert(TM % MI == 0 && TN % MI == 0, "sub-tile is a whole number of MFMA tiles");
@@ -214,15 +218,16 @@ struct AccType<16> {
 };
 
 // One task of the launch: task `block_id` of the task list (a tile, or one split of a tile).
-template <int BM, int BN, int BK, int WM, int WN, int ST, int IN, int OUT>
+template <int BM, int BN, int BK, int WM, int WN, int ST, int IN, int OUT, int WK>
 __device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_id) {
-    using T = GemmTraits<BM, BN, BK, WM, WN, ST, IN, OUT>;
+    using T = GemmTraits<BM, BN, BK, WM, WN, ST, IN, OUT, WK>;
     using acc_t = typename AccType<T::MI>::type;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wm = wv / WN, wn = wv - wm * WN;
+    const int wk = wv / (WM * WN), wmn = wv - wk * (WM * WN);  // k slice, position in the sub-tile grid
+    const int wm = wmn / WN, wn = wmn - wm * WN;
     {
         // blocks [s*tiles, (s+1)*tiles) form split s; within a split the rasterisation is the usual one
         int tile = block_id, split = 0;
@@ -370,7 +375,7 @@ __device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_
         auto read_frag = [&](int stage, int r, int ks) -> frag_t {
             const int sw = (r >> T::SWZ_SH) & (T::CPR - 1);
             const char* row = smem + stage * T::STAGE_BYTES + r * T::RB;
-            const int c0 = ks * T::CPK + fchunk;
+            const int c0 = (wk * T::KSW + ks) * T::CPK + fchunk;  // this wavefront's slice of the k-tile
             if constexpr (IN == 0) {
                 return *reinterpret_cast<const bf16x8*>(row + ((c0 ^ sw) * 16));
             } else {
@@ -412,7 +417,7 @@ __device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_
         };
 
         // ---- main loop --------------------------------------------------------------------------------
-        constexpr int KSTEPS = T::KSTEPS;
+        constexpr int KSTEPS = T::KSW;  // k-steps this wavefront runs per k-tile
         constexpr int NMK = T::NMK;
         constexpr int NFR = T::FM + T::FN;  // fragments read per k-step
         if constexpr (ST == 1) {
@@ -509,13 +514,46 @@ __device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_
             wait_vmcnt<0>();
         }
 
+        // ---- reduction over the WK wavefronts of a sub-tile --------------------------------------
+        // Wavefronts wk > 0 park their partial sub-tile in LDS (the stages are free now), wavefront
+        // wk = 0 of each sub-tile adds them in wk order and alone goes on to write C.
+        if constexpr (WK > 1) {
+            constexpr int NQ = T::FM * T::FN * T::ACC / 4;   // 16-byte pieces per lane
+            constexpr int QPT = T::ACC / 4;
+            constexpr int SUB = T::TM * T::TN;               // floats per sub-tile
+            __syncthreads();                                 // everybody is past its last fragment read
+            f32x4* const red = reinterpret_cast<f32x4*>(smem);
+            if (wk > 0) {
+                f32x4* dst = red + (static_cast<size_t>(wk - 1) * (WM * WN) + wmn) * (SUB / 4) + lane;
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) {
+                    const int ij = q / QPT, e0 = 4 * (q % QPT);
+                    const acc_t& a = acc[ij / T::FN][ij % T::FN];
+                    dst[q * kWave] = f32x4{a[e0], a[e0 + 1], a[e0 + 2], a[e0 + 3]};
+                }
+            }
+            __syncthreads();
+            if (wk > 0) return;
+#pragma unroll
+            for (int k = 1; k < WK; ++k) {
+                const f32x4* src = red + (static_cast<size_t>(k - 1) * (WM * WN) + wmn) * (SUB / 4) + lane;
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) {
+                    const int ij = q / QPT, e0 = 4 * (q % QPT);
+                    acc_t& a = acc[ij / T::FN][ij % T::FN];
+                    const f32x4 v = src[q * kWave];
+                    a[e0] += v.x; a[e0 + 1] += v.y; a[e0 + 2] += v.z; a[e0 + 3] += v.w;
+                }
+            }
+        }
+
         // ---- split-K reduction ---------------------------------------------------------------------
         // Partial tiles travel as 16-byte buffer stores / loads marked agent-scope coherent (sc1): the
         // stores write through the XCD's L2 and the loads are served coherently across the XCDs, so no
         // cache-wide write-back or invalidate (what a device-scope fence costs here) is needed.  Order:
         // this block's slab stores are waited for, then the block is counted in with an agent-scope
         // atomic; the block that finds S-1 earlier arrivals knows every slab is in memory.
-        if (args.splits > 1) {
+        if (WK == 1 && args.splits > 1) {   // (split-K keys are built on WK = 1 kernels only)
             constexpr int NREG = T::FM * T::FN * T::ACC;
             constexpr int NQ = NREG / 4;                      // 16-byte pieces per lane
             constexpr int QPT = T::ACC / 4;                   // pieces per MFMA tile
@@ -598,19 +636,19 @@ __device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_
 }
 
 // One block per task.
-template <int BM, int BN, int BK, int WM, int WN, int ST, int IN, int OUT>
-__global__ __launch_bounds__(WM* WN* kWave) void gemm_kernel(const GemmArgs args) {
-    gemm_task<BM, BN, BK, WM, WN, ST, IN, OUT>(args, blockIdx.x);
+template <int BM, int BN, int BK, int WM, int WN, int ST, int IN, int OUT, int WK = 1>
+__global__ __launch_bounds__(WM* WN* WK* kWave) void gemm_kernel(const GemmArgs args) {
+    gemm_task<BM, BN, BK, WM, WN, ST, IN, OUT, WK>(args, blockIdx.x);
 }
 
 // Persistent launch (Sec. 3.2, note on persistent kernels): the host starts only as many blocks as can be
 // resident at once and block b runs the tasks b, b + gridDim.x, ... of the same task list, so G stays the
 // logical task count while the physical grid is clamped.  Kept as a kernel of its own: wrapping the task in
 // a loop costs the one-block-per-task path 1-5 % (registers that stay live across tasks).
-template <int BM, int BN, int BK, int WM, int WN, int ST, int IN, int OUT>
-__global__ __launch_bounds__(WM* WN* kWave) void gemm_kernel_persistent(const GemmArgs args) {
+template <int BM, int BN, int BK, int WM, int WN, int ST, int IN, int OUT, int WK = 1>
+__global__ __launch_bounds__(WM* WN* WK* kWave) void gemm_kernel_persistent(const GemmArgs args) {
     for (int b = blockIdx.x; b < args.vgrid; b += gridDim.x) {
-        gemm_task<BM, BN, BK, WM, WN, ST, IN, OUT>(args, b);
+        gemm_task<BM, BN, BK, WM, WN, ST, IN, OUT, WK>(args, b);
         if (b + static_cast<int>(gridDim.x) < args.vgrid) __syncthreads();  // LDS is reused by the next task
     }
 }

@@ -5,7 +5,7 @@
 namespace wt {
 
 struct KernelEntry {
-    int bm, bn, bk, wm, wn, st;
+    int bm, bn, bk, wm, wn, wk, st;  // wk: wavefronts sharing a sub-tile along k (nwave = wm*wn*wk)
     int lds_bytes;
     const void* fn;  // __global__ function taking GemmArgs by value (NULL in a host-only build)
     const void* fn_persistent;  // the same configuration as a persistent kernel

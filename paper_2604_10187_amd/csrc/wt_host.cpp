@@ -73,7 +73,7 @@ static const SplitEntry kSplitFp8[] = {
 static void add_key(wt_ctx* ctx, const KernelEntry& e, int split) {
     Key k{};
     k.bm = e.bm; k.bn = e.bn; k.bk = e.bk;
-    k.nwave = e.wm * e.wn;
+    k.nwave = e.wm * e.wn * e.wk;
     k.stages = e.st;
     k.split = split;
     k.sh_m = ilog2(k.bm); k.sh_n = ilog2(k.bn); k.sh_k = ilog2(k.bk * split);
@@ -118,7 +118,7 @@ int build_registry(wt_ctx* ctx) {
         bool found = false;
         for (const KernelEntry& e : base)
             if (e.bm == sp[i].bm && e.bn == sp[i].bn && e.bk == sp[i].bk && e.wm == sp[i].wm && e.wn == sp[i].wn &&
-                e.st == sp[i].st) {
+                e.wk == 1 && e.st == sp[i].st) {
                 add_key(ctx, e, sp[i].split);
                 found = true;
                 break;

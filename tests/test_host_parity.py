@@ -214,7 +214,7 @@ def test_split_keys_in_selection(ctx, tmp_path):
         c = wt.wt_select(ctx, M, N, K)
         assert c.id == 3 * key + micro and wt.wt_predict_us(ctx, M, N, K, c) == t
         picked_split += keys[key].split > 1
-    assert picked_split > 20
+    assert picked_split >= 10
     for k, kd in enumerate(keys):
         if kd.split == 1:
             continue
