@@ -344,6 +344,35 @@ def test_fp8_scaled_normal_inputs(ctx_fp8_f32, ctx_fp8_bf16):
         assert og.max_scaled_err(got, want) <= BF16_ELEM
 
 
+def test_fp8_grouped_and_persistent_bit_exact(ctx_fp8_f32):
+    """fp8 inputs through the grouped and the persistent launch paths (integer data, unit scales)."""
+    counts = [70, 0, 5, 129]
+    off = wt_synth.group_offsets(counts)
+    E, N, K = len(counts), 150, 304
+    a32, _ = wt_synth.gemm_operands(int(off[-1]), 16, K, 8921, "int")
+    b32, _ = wt_synth.gemm_operands(E * N, 16, K, 8922, "int")
+    aq = torch.from_numpy(a32).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    bq = torch.from_numpy(b32).to(torch.float8_e4m3fn).view(torch.uint8).numpy().reshape(E, N, K)
+    want = og.grouped_gemm_c(aq, bq, off, "e4m3", 1.0, 1.0)
+    one = torch.ones(1, dtype=torch.float32, device="cuda")
+    dOff = torch.from_numpy(off.copy()).cuda()
+    dA, dB = torch.from_numpy(aq.copy()).cuda(), torch.from_numpy(bq.reshape(E * N, K).copy()).cuda()
+    for persistent in (False, True):
+        wt.wt_set_persistent(ctx_fp8_f32, persistent)
+        try:
+            for cfg, res in all_configs(ctx_fp8_f32):
+                if cfg.split != 1 or cfg.swizzle != (cfg.id // 3) % 3:
+                    continue
+                note(f"fp8 grouped persistent={persistent} cfg={cfg.astuple()}")
+                dC = torch.full((int(off[-1]), N), float("nan"), dtype=torch.float32, device="cuda")
+                wt.wt_gemm_grouped(ctx_fp8_f32, E, dOff, int(off[-1]), N, K, dA, dB, dC, cfg, one, one,
+                                   stream=torch.cuda.current_stream())
+                torch.cuda.synchronize()
+                assert np.array_equal(dC.cpu().numpy(), want), f"{cfg}"
+        finally:
+            wt.wt_set_persistent(ctx_fp8_f32, False)
+
+
 # ---- full-size shapes, checked on sampled rows / columns / edge tiles ----------------------------
 def _sampled_check(ctx, cfg, M, N, K, in_type, out_type, seed, n_rows=12, n_cols=6):
     """Run the full-size GEMM on the GPU and compare complete sampled rows and columns (random ones
