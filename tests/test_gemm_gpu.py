@@ -163,6 +163,64 @@ def test_split_k_workspace_limit(ctx_f32):
     assert e.value.status == wt.WT_ERR_INFEASIBLE
 
 
+# ---- HIP graph capture -------------------------------------------------------------------------------
+def test_launches_replay_from_a_hip_graph(ctx_f32):
+    """wt_gemm neither allocates nor synchronises, so a sequence of launches (an unsplit one, two split-K
+    ones that share the context's workspace and counters, a grouped one) can be captured into a HIP graph.
+    Every replay -- with eager launches and synchronisations between replays -- must reproduce the eager
+    result bit for bit."""
+    cases = [((300, 520, 1032), (128, 128, 64, 4, 3, 1, 1)), ((130, 1000, 4104), (64, 64, 128, 4, 3, 2, 4)),
+             ((64, 777, 2056), (16, 64, 256, 4, 3, 0, 2))]
+    bufs, eager = [], []
+    cur = torch.cuda.current_stream()
+    for (M, N, K), f in cases:
+        ab, bb = _bf16_case(M, N, K, 9100 + M, "normal")
+        cfg, _ = wt.wt_config_get(ctx_f32, wt.wt_config_find(ctx_f32, *f))
+        dA, dB = torch.from_numpy(ab.view(np.int16).copy()).cuda(), torch.from_numpy(bb.view(np.int16).copy()).cuda()
+        bufs.append((M, N, K, cfg, dA, dB, torch.empty((M, N), dtype=torch.float32, device="cuda")))
+    counts = [40, 0, 200, 7]
+    off = wt_synth.group_offsets(counts)
+    gab, _ = wt_synth.gemm_operands(int(off[-1]), 8, 520, 9200)
+    gbb, _ = wt_synth.gemm_operands(4 * 300, 8, 520, 9201)
+    gA = torch.from_numpy(wt_synth.to_bf16_bits(gab).view(np.int16).copy()).cuda()
+    gB = torch.from_numpy(wt_synth.to_bf16_bits(gbb).view(np.int16).copy()).cuda()
+    gC = torch.empty((int(off[-1]), 300), dtype=torch.float32, device="cuda")
+    gOff = torch.from_numpy(off.copy()).cuda()
+    gcfg, _ = wt.wt_config_get(ctx_f32, wt.wt_config_find(ctx_f32, 32, 64, 128, 4, 3, 1))
+
+    def launch_all(stream):
+        for (M, N, K, cfg, dA, dB, dC) in bufs:
+            wt.wt_gemm(ctx_f32, M, N, K, dA, dB, dC, cfg, stream=stream)
+        wt.wt_gemm_grouped(ctx_f32, 4, gOff, int(off[-1]), 300, 520, gA, gB, gC, gcfg, stream=stream)
+
+    note("graph: eager reference")
+    launch_all(cur)
+    torch.cuda.synchronize()
+    eager = [b[6].clone() for b in bufs] + [gC.clone()]
+    side = torch.cuda.Stream()
+    side.wait_stream(cur)
+    with torch.cuda.stream(side):       # warm-up on a side stream, as torch asks before a capture
+        launch_all(side)
+    cur.wait_stream(side)
+    torch.cuda.synchronize()
+    note("graph: capture")
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        launch_all(torch.cuda.current_stream())
+    for rep in range(3):
+        for b in bufs:
+            b[6].fill_(float("nan"))
+        gC.fill_(float("nan"))
+        note(f"graph: replay {rep}")
+        g.replay()
+        torch.cuda.synchronize()
+        got = [b[6] for b in bufs] + [gC]
+        assert all(torch.equal(x, y) for x, y in zip(got, eager)), f"replay {rep}"
+        launch_all(cur)                 # eager work between replays
+        torch.cuda.synchronize()
+        assert all(torch.equal(x, y) for x, y in zip(got, eager))
+
+
 # ---- persistent launches ---------------------------------------------------------------------------
 def test_persistent_launch_bit_exact(ctx_f32):
     """Grid clamped to the resident block count: on problems with more tasks than that, every structural
