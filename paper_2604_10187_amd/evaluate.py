@@ -302,6 +302,51 @@ def cmd_persistent(a, torch):
             "summary": summary, "rows": rows}
 
 
+def cmd_vendor(a, torch):
+    """Context, not a target: the vendor library's GEMM (torch.matmul on ROCm, i.e. hipBLASLt / rocBLAS with its
+    own heuristics) on the same shapes and buffers, timed with HIP events around batches of launches like
+    wt_time_gemm does, beside this library under wt_select's configuration.  bf16 in, bf16 out."""
+    import wt_synth
+
+    ctx, path = _open_ctx(a, torch)
+    stream = torch.cuda.current_stream()
+    rng = np.random.default_rng(2008)
+    st = wt_synth.stream_shapes()
+    shapes = wt_synth.sweep_shapes() + [(16384, 8192, 8192)] + [st[i] for i in rng.choice(len(st), size=30, replace=False)]
+
+    def time_matmul(A, B, C, iters=5):
+        for _ in range(3):
+            torch.matmul(A, B.t(), out=C)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ms = 0.0
+        for _pass in range(2):
+            e0.record(stream)
+            for _ in range(iters):
+                torch.matmul(A, B.t(), out=C)
+            e1.record(stream)
+            e1.synchronize()
+            ms = e0.elapsed_time(e1)
+            if ms * 1000.0 >= 300.0:
+                break
+            iters = min(max(int(300.0 / max(ms * 1000.0 / iters, 0.5)) + 1, iters), iters * 64)
+        return ms * 1000.0 / iters
+
+    rows = []
+    for (M, N, K) in shapes:
+        A, B, C, sA, sB = _dev_operands(torch, M, N, K, wt.WT_BF16, wt.WT_OUT_BF16)
+        cfg = wt.wt_select(ctx, M, N, K)
+        ours = min(wt.wt_time_gemm(ctx, M, N, K, A, B, C, cfg, 3, 5, stream=stream) for _ in range(2))
+        vend = min(time_matmul(A, B, C) for _ in range(2))
+        rows.append({"M": M, "N": N, "K": K, "cfg": list(cfg.astuple()), "wt_us": ours, "vendor_us": vend,
+                     "vendor_over_wt": vend / ours})
+        _log(f"[eval] vendor {M}x{N}x{K}: wt {ours:.1f} us, torch.matmul {vend:.1f} us ({vend / ours:.2f}x)")
+    r = np.array([x["vendor_over_wt"] for x in rows])
+    summary = {"n_shapes": len(rows), "geomean_vendor_over_wt": float(np.exp(np.mean(np.log(r)))),
+               "min": float(r.min()), "max": float(r.max()), "torch": torch.__version__}
+    return {"workload": "torch.matmul (vendor library) vs wt_gemm under wt_select's configuration, bf16", "table": path,
+            "summary": summary, "rows": rows}
+
+
 def cmd_ablate(a, torch=None):
     """CPU only.  Re-fit the saved profiling records under model / (W, I) variants with wt_fit on a
     host-only context and score each variant's picks against saved exhaustive timings (the `times` of
@@ -364,7 +409,7 @@ def cmd_ablate(a, torch=None):
 
 def main(argv=None):
     ap = argparse.ArgumentParser()
-    ap.add_argument("cmd", choices=["sweep", "wave", "stream", "large", "grouped", "persistent", "ablate"])
+    ap.add_argument("cmd", choices=["sweep", "wave", "stream", "large", "grouped", "persistent", "vendor", "ablate"])
     ap.add_argument("--samples", default=None, help="ablate: .npz with `samples` and `occ`")
     ap.add_argument("--scores", nargs="*", default=[], help="ablate: sweep/stream result files with exhaustive timings")
     ap.add_argument("--cap-mode", type=int, default=1)
@@ -386,7 +431,7 @@ def main(argv=None):
     else:
         import torch
 
-        res = {"sweep": cmd_sweep, "wave": cmd_wave, "stream": cmd_stream, "large": cmd_large, "grouped": cmd_grouped, "persistent": cmd_persistent}[a.cmd](a, torch)
+        res = {"sweep": cmd_sweep, "wave": cmd_wave, "stream": cmd_stream, "large": cmd_large, "grouped": cmd_grouped, "persistent": cmd_persistent, "vendor": cmd_vendor}[a.cmd](a, torch)
     txt = json.dumps(res)
     if a.out:
         open(a.out, "w").write(txt)
