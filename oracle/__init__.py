@@ -14,6 +14,8 @@ Plain, slow, obviously-correct implementations written from the paper:
   select.py      two-stage runtime selection on a dual table (Sec. 4.4, 4.5) and a reader
                  for the binary table file the product library writes.
   exhaustive.py  brute-force search over a latency table (Sec. 5.1, brute-force baseline).
+  attention.py   scaled dot-product attention in fp64 and the attention row of the abstraction
+                 (Table 2, FlashAttention row; Sec. 4.2 head-aligned grid sizes; Eq. 6).
 
 Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import this package.
 It imports nothing from the product package and shares no code, tables or constants with it.
