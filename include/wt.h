@@ -48,7 +48,10 @@ typedef enum {
     WT_ERR_NO_DEVICE = -8        /* device work requested from a host-only context */
 } wt_status;
 
-typedef enum { WT_BF16 = 0, WT_FP8_E4M3 = 1 } wt_in_t;   /* storage type of A and B */
+/* Storage type of A and B.  WT_ATTN_BF16 makes an attention context instead of a GEMM one: its registry holds
+ * the FlashAttention-style kernels (see wt_attn), out_type must be WT_OUT_BF16, and the shape triple of
+ * wt_select / wt_wave_count / wt_predict_us reads (M, N, K) = (S_q, N_h, S_kv). */
+typedef enum { WT_BF16 = 0, WT_FP8_E4M3 = 1, WT_ATTN_BF16 = 2 } wt_in_t;
 typedef enum { WT_OUT_F32 = 0, WT_OUT_BF16 = 1 } wt_out_t; /* storage type of C */
 
 typedef struct wt_ctx wt_ctx; /* opaque: config registry, per-config resources, dual table */
@@ -103,6 +106,11 @@ typedef struct {
     int32_t row_fams; /* number of few-row families, 1..3 (0 is read as 1); used only when W_row > 0 */
     int32_t skip_near; /* 1: wt_sample_plan / wt_profile_sparse leave out the near-square family (to add few-row
                         * records to an existing set); wt_fit ignores it */
+    int32_t n_heads;   /* attention contexts only (must be >= 1 there): head count N_h of the profiled workloads.
+                        * Grid sizes are head-aligned, g = floor(b / N_h) * N_h >= a (Sec. 4.2), a grid point is
+                        * S_q = (g / N_h) * T_Q (Eq. 6), and k_anchors holds KV-length multipliers in percent of
+                        * S_q (Sec. 5.1: 1.0 to 3.0): L = ceil(floor(S_q * pct / 100) / T_KV), S_kv = L * T_KV.
+                        * tau, W_row, W_split are unused; max_out_elems caps S_q * N_h * 128. */
 } wt_grid;
 
 /* Latency models wt_fit can build into the dual table.  WAVE_BILINEAR is the method (Sec. 4.3);
@@ -180,6 +188,31 @@ int wt_wave_count_grouped(const wt_ctx* ctx, int32_t groups, const int64_t* grou
  * each group is taken to hold ceil(M_total/groups) rows.  Split-K keys are not candidates.  Host only. */
 int wt_select_grouped(const wt_ctx* ctx, int32_t groups, int64_t M_total, int64_t N, int64_t K, wt_cfg* out);
 
+/* ---- attention (Table 2, FlashAttention row: G = N_h * ceil(S_q/T_Q), L = ceil(S_kv/T_KV)) ---------------- */
+/* O = softmax(scale * Q K^T [+ causal mask]) V per head, one sequence, bf16 in and out, head dimension 128, on a
+ * WT_ATTN_BF16 context.  Device pointers: Q and O are [S_q, n_heads, 128], K and V are [S_kv, n_kv_heads, 128]
+ * (token-major, head dimension contiguous).  n_kv_heads divides n_heads: query head h reads KV head
+ * h / (n_heads / n_kv_heads) (grouped-query attention; equal counts = multi-head attention).  causal = 1: query i
+ * sees keys j <= i + (S_kv - S_q), which needs S_kv >= S_q.  S_kv = 0 writes zeros; S_q = 0 is a no-op.
+ * A configuration is <bm, bn, bk, nwave, stages, swizzle, split> = <T_Q, 1, T_KV, wavefronts, 1, order, 1>: a block
+ * owns T_Q query rows of one head and loops over the KV tiles; `order` is the micro parameter (0: the query tiles
+ * of a head are consecutive blocks; 1: the heads of a query tile are consecutive blocks; 2: as 0, with every one
+ * of the 8 XCDs given a contiguous range so that a head's K/V stay in one L2).  Scores and softmax are fp32, the
+ * probabilities are rounded to bf16 before they multiply V.  Asynchronous on hip_stream, never allocates or
+ * synchronises.  The persistent launch policy does not apply. */
+int wt_attn(wt_ctx* ctx, int64_t n_heads, int64_t n_kv_heads, int64_t S_q, int64_t S_kv, const void* Q,
+            const void* K, const void* V, void* O, float scale, int causal, wt_cfg cfg, void* hip_stream);
+/* wt_time_gemm's protocol for an attention launch. */
+int wt_time_attn(wt_ctx* ctx, int64_t n_heads, int64_t n_kv_heads, int64_t S_q, int64_t S_kv, const void* Q,
+                 const void* K, const void* V, void* O, float scale, int causal, wt_cfg cfg, int warmup, int iters,
+                 void* hip_stream, double* mean_us);
+/* Diagnostic: (head, query tile) of workgroup `block` under `order` -- the kernel's own mapping on the host. */
+int wt_attn_block_coords(int n_heads, int q_tiles, int order, int block, int* head, int* q_tile);
+/* Head-aligned grid samples (Sec. 4.2): up to cap_out pairs (g, q tiles per head) in w-major, i-minor order;
+ * g = 0 where the sub-interval holds no multiple of n_heads.  Host only. */
+int wt_sample_grid_heads(int64_t capacity, int32_t W, int32_t I, int32_t n_heads, int64_t* g, int64_t* q_tiles,
+                         size_t cap_out, size_t* n_out);
+
 /* Diagnostic: the (tile row, tile column) that workgroup `block` of a tiles_m x tiles_n grid computes
  * under rasterisation mode `swizzle` -- the kernel's own mapping evaluated on the host.  Host only. */
 int wt_tile_coords(int tiles_m, int tiles_n, int swizzle, int block, int* tm, int* tn);
@@ -201,6 +234,8 @@ int wt_sample_plan(const wt_ctx* ctx, const wt_grid* grid, size_t* n_samples, si
 /* Instantiate every sample (M = m*bm, N = n*bn, K = L*split*bk), run every micro with warm-up +
  * measured launches timed by HIP events on hip_stream, write one record per <key, micro, g, L>.
  * scrA/scrB/scrC: device scratch of at least the planned sizes (contents: any finite values).
+ * Attention contexts: scrA holds Q, scrB holds K followed by V, scrC holds O; workloads are multi-head
+ * (n_kv_heads = n_heads, Sec. 4.2), not causal, scale 1/sqrt(128).
  * Synchronises the stream. */
 int wt_profile_sparse(wt_ctx* ctx, const wt_grid* grid, void* scrA, void* scrB, void* scrC,
                       size_t bytesA, size_t bytesB, size_t bytesC, void* hip_stream,

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libwt.so")
 WT_OK = 0
 WT_ERR_INVALID_ARG, WT_ERR_UNSUPPORTED_CFG, WT_ERR_INFEASIBLE, WT_ERR_NOT_FITTED = -1, -2, -3, -4
 WT_ERR_HIP, WT_ERR_BUFFER_TOO_SMALL, WT_ERR_IO, WT_ERR_NO_DEVICE = -5, -6, -7, -8
-WT_BF16, WT_FP8_E4M3 = 0, 1
+WT_BF16, WT_FP8_E4M3, WT_ATTN_BF16 = 0, 1, 2
 WT_OUT_F32, WT_OUT_BF16 = 0, 1
 WT_MODEL_WAVE_BILINEAR, WT_MODEL_LINEAR, WT_MODEL_STEP = 0, 1, 2
 WT_CAP_CU_TIMES_OCC, WT_CAP_CU_ONLY = 0, 1
@@ -53,7 +53,8 @@ class wt_grid(C.Structure):
                 ("p", C.c_int32), ("n_k_anchors", C.c_int32), ("k_anchors", C.POINTER(C.c_int32)),
                 ("warmup", C.c_int32), ("iters", C.c_int32), ("key_first", C.c_int32),
                 ("key_count", C.c_int32), ("max_out_elems", C.c_int64), ("model", C.c_int32),
-                ("W_split", C.c_int32), ("W_row", C.c_int32), ("row_fams", C.c_int32), ("skip_near", C.c_int32)]
+                ("W_split", C.c_int32), ("W_row", C.c_int32), ("row_fams", C.c_int32), ("skip_near", C.c_int32),
+                ("n_heads", C.c_int32)]
 
 
 class WtError(RuntimeError):
@@ -95,6 +96,11 @@ def lib():
                                      C.POINTER(C.c_double)],
             "wt_wave_count_grouped": [vp, i32, vp, i64, i64, wt_cfg, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32)],
             "wt_select_grouped": [vp, i32, i64, i64, i64, C.POINTER(wt_cfg)],
+            "wt_attn": [vp, i64, i64, i64, i64, vp, vp, vp, vp, C.c_float, C.c_int, wt_cfg, vp],
+            "wt_time_attn": [vp, i64, i64, i64, i64, vp, vp, vp, vp, C.c_float, C.c_int, wt_cfg, C.c_int, C.c_int, vp,
+                             C.POINTER(C.c_double)],
+            "wt_attn_block_coords": [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)],
+            "wt_sample_grid_heads": [i64, i32, i32, i32, vp, vp, sz, C.POINTER(sz)],
             "wt_wave_count": [vp, i64, i64, i64, wt_cfg, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32)],
             "wt_sample_grid": [i64, i32, i32, i32, i32, i32, vp, vp, vp, sz, C.POINTER(sz)],
             "wt_sample_plan": [vp, C.POINTER(wt_grid), C.POINTER(sz), C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)],
@@ -122,7 +128,8 @@ EXPORTS = ("wt_create", "wt_destroy", "wt_last_hip_error", "wt_status_string", "
            "wt_config_find", "wt_key_count", "wt_key_set_occ", "wt_set_capacity_mode", "wt_set_persistent", "wt_tile_coords", "wt_gemm", "wt_gemm_grouped",
            "wt_time_gemm_grouped", "wt_wave_count_grouped", "wt_select_grouped", "wt_wave_count", "wt_sample_grid",
            "wt_sample_plan", "wt_profile_sparse", "wt_time_gemm", "wt_mfma_ceiling", "wt_fit", "wt_select", "wt_predict_us",
-           "wt_select_bench", "wt_save", "wt_load")
+           "wt_select_bench", "wt_save", "wt_load", "wt_attn", "wt_time_attn", "wt_attn_block_coords",
+           "wt_sample_grid_heads")
 
 
 def status_string(status: int) -> str:
@@ -150,10 +157,11 @@ def _stream(stream):
 
 
 def make_grid(W=40, I=4, tau=(11, 10), p=10, k_anchors=(1024, 2048, 3072, 4096, 5120), warmup=3, iters=5,
-              key_first=0, key_count=0, max_out_elems=0, model=0, W_row=0, W_split=0, row_fams=0, skip_near=0):
+              key_first=0, key_count=0, max_out_elems=0, model=0, W_row=0, W_split=0, row_fams=0, skip_near=0,
+              n_heads=0):
     arr = (C.c_int32 * len(k_anchors))(*k_anchors)
     g = wt_grid(W, I, tau[0], tau[1], p, len(k_anchors), C.cast(arr, C.POINTER(C.c_int32)), warmup, iters,
-                key_first, key_count, max_out_elems, model, W_split, W_row, row_fams, skip_near)
+                key_first, key_count, max_out_elems, model, W_split, W_row, row_fams, skip_near, n_heads)
     g._keep = arr  # keep the anchor array alive with the struct
     return g
 
@@ -234,6 +242,35 @@ def wt_time_gemm_grouped(ctx, groups, offsets, M_total, N, K, A, B, Cout, cfg, w
                                       _ptr(scaleA), _ptr(scaleB), cfg, warmup, iters, _stream(stream),
                                       C.byref(us)), "wt_time_gemm_grouped")
     return us.value
+
+
+def wt_attn(ctx, n_heads, n_kv_heads, S_q, S_kv, Q, K, V, O, scale, causal, cfg, stream=None):
+    """Q, O: [S_q, n_heads, 128]; K, V: [S_kv, n_kv_heads, 128]; bf16 device tensors."""
+    _check(lib().wt_attn(ctx, n_heads, n_kv_heads, S_q, S_kv, _ptr(Q), _ptr(K), _ptr(V), _ptr(O), float(scale),
+                         int(bool(causal)), cfg, _stream(stream)), "wt_attn")
+
+
+def wt_time_attn(ctx, n_heads, n_kv_heads, S_q, S_kv, Q, K, V, O, scale, causal, cfg, warmup=3, iters=5,
+                 stream=None) -> float:
+    us = C.c_double()
+    _check(lib().wt_time_attn(ctx, n_heads, n_kv_heads, S_q, S_kv, _ptr(Q), _ptr(K), _ptr(V), _ptr(O), float(scale),
+                              int(bool(causal)), cfg, warmup, iters, _stream(stream), C.byref(us)), "wt_time_attn")
+    return us.value
+
+
+def wt_attn_block_coords(n_heads, q_tiles, order, block):
+    h, q = C.c_int(), C.c_int()
+    _check(lib().wt_attn_block_coords(n_heads, q_tiles, order, block, C.byref(h), C.byref(q)), "wt_attn_block_coords")
+    return h.value, q.value
+
+
+def wt_sample_grid_heads(capacity, W, I, n_heads):
+    n = W * I
+    g, q = np.zeros(n, dtype=np.int64), np.zeros(n, dtype=np.int64)
+    got = C.c_size_t()
+    _check(lib().wt_sample_grid_heads(capacity, W, I, n_heads, g.ctypes.data, q.ctypes.data, n, C.byref(got)),
+           "wt_sample_grid_heads")
+    return g[:got.value], q[:got.value]
 
 
 def wt_wave_count_grouped(ctx, group_rows, N, K, cfg):

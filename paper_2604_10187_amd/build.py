@@ -45,6 +45,9 @@ def build(jobs: int = 8, verbose: bool = False) -> str:
     obj = os.path.join(OUT, "wt_api.o")
     objs.append(obj)
     steps.append([hipcc, *HIP_FLAGS, "-c", os.path.join(CSRC, "wt_api.hip"), "-o", obj])
+    obj = os.path.join(OUT, "attn_inst.o")
+    objs.append(obj)
+    steps.append([hipcc, *HIP_FLAGS, "-c", os.path.join(CSRC, "attn_inst.hip"), "-o", obj])
     obj = os.path.join(OUT, "mfma_ceiling.o")
     objs.append(obj)
     steps.append([hipcc, *HIP_FLAGS, "-c", os.path.join(CSRC, "mfma_ceiling.hip"), "-o", obj])

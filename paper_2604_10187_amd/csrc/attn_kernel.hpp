@@ -1,0 +1,305 @@
+// FlashAttention-style forward kernel for gfx950 (bf16 in / bf16 out, head dimension 128), the second tile-based
+// kernel behind the <G, L> abstraction (Table 2, FlashAttention row: a block owns T_Q query rows of one head and
+// loops over ceil(S_kv / T_KV) key/value tiles).
+//
+// Layout.  Q and O are [S_q, H_q, 128], K and V are [S_kv, H_kv, 128] (token-major, head dimension contiguous);
+// query head h reads KV head h / (H_q / H_kv).
+//
+// Per block: NW wavefronts, each owning R = T_Q / NW query rows (32 or 64) and keeping their Q fragments in
+// registers.  Per KV tile:
+//   * S^T = K Q^T on v_mfma_f32_32x32x16_bf16 with K as the row operand, so a lane ends up with ONE query column
+//     and 16 key rows per 32-key block: the row maximum and row sum of the online softmax are in-lane reductions
+//     plus a single exchange with lane ^ 32, and the rescale factor is a per-lane scalar;
+//   * P^T (bf16) is fed back as the column operand of O^T += V^T P^T straight from those accumulator registers
+//     (eight consecutive accumulators are one k-step); the contraction order over keys that this implies
+//     (key = 32b + 8(e/4) + 4(lane/32) + e%4) is baked into how V is laid out in LDS;
+//   * K goes to LDS row-major (rows padded by 16 bytes), V is transposed in registers (4 keys x 8 dims per
+//     thread) and stored as V^T[d][permuted key] so that every MFMA operand is one 16-byte LDS read;
+//   * the global loads of tile t+1 are issued right after the barrier that publishes tile t and land in registers
+//     while tile t is computed.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace wt {
+
+constexpr int kHeadDim = 128;
+constexpr int kAttnOrders = 3;  // micro parameter: block -> (head, query tile) order
+constexpr int kAttnXcd = 8;
+
+typedef __attribute__((ext_vector_type(8))) __bf16 abf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 abf16x4;
+typedef __attribute__((ext_vector_type(16))) float af32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned au32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned au32x2;
+
+struct AttnArgs {
+    const __bf16* Q;
+    const __bf16* K;
+    const __bf16* V;
+    __bf16* O;
+    int S_q, S_kv, H_q, H_kv;
+    int q_tiles;       // ceil(S_q / T_Q)
+    int order;         // 0: query tiles of a head are consecutive blocks; 1: heads are consecutive blocks;
+                       // 2: like 0, but every XCD (blocks are dealt round-robin to 8 of them) gets a contiguous range
+    int causal;        // 1: query i sees keys j <= i + (S_kv - S_q)
+    float scale_log2;  // softmax scale times log2(e)
+};
+
+// Block index -> (head, query tile).  Also run on the host by the tests.
+__host__ __device__ inline void attn_block_coords(int block, int n_heads, int q_tiles, int order, int& head, int& qt) {
+    if (order == 1) {
+        qt = block / n_heads;
+        head = block % n_heads;
+        return;
+    }
+    int v = block;
+    if (order == 2) {
+        const int G = n_heads * q_tiles, x = block % kAttnXcd, r = block / kAttnXcd;
+        const int per = G / kAttnXcd, rem = G % kAttnXcd;
+        v = x * per + (x < rem ? x : rem) + r;  // XCD x owns per + (x < rem) consecutive entries
+    }
+    head = v / q_tiles;
+    qt = v % q_tiles;
+}
+
+template <int TQ, int TKV, int NW>
+struct AttnTraits {
+    static constexpr int R = TQ / NW;   // query rows per wavefront
+    static constexpr int RB = R / 32;   // 32-row blocks per wavefront
+    static constexpr int NT = NW * 64;
+    static constexpr int KB = TKV / 32;                 // 32-key blocks per tile
+    static constexpr int K_ROW = kHeadDim * 2 + 16;     // bytes per key row in LDS (padded: conflict-free 16-byte reads)
+    static constexpr int V_ROW = TKV * 2 + 16;          // bytes per head-dimension row of V^T in LDS
+    static constexpr int K_BYTES = TKV * K_ROW;
+    static constexpr int V_BYTES = kHeadDim * V_ROW;
+    static constexpr int LDS_BYTES = K_BYTES + V_BYTES;
+    static constexpr int K_TOTAL = TKV * 16;            // 16-byte chunks of a K tile
+    static constexpr int KC = (K_TOTAL + NT - 1) / NT;  // per thread
+    static constexpr int QN = TKV / 4;                  // key quads per tile
+    static constexpr int V_TOTAL = QN * 16;             // 4-key x 8-dim units of a V tile
+    static constexpr int VU = (V_TOTAL + NT - 1) / NT;  // per thread
+    static_assert(TQ % NW == 0 && (R == 32 || R == 64), "a wavefront owns 32 or 64 query rows");
+    static_assert(TKV % 32 == 0 && TKV >= 32, "KV tile is a multiple of 32 keys");
+};
+
+template <int TQ, int TKV, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
+    using T = AttnTraits<TQ, TKV, NW>;
+    extern __shared__ __attribute__((aligned(16))) char attn_smem[];
+    char* const k_lds = attn_smem;
+    char* const v_lds = attn_smem + T::K_BYTES;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, h = lane >> 5;
+    int head, qt;
+    attn_block_coords(static_cast<int>(blockIdx.x), a.H_q, a.q_tiles, a.order, head, qt);
+    const int kh = head / (a.H_q / a.H_kv);
+    const int q0 = qt * TQ + wave * T::R;
+    const int shift = a.S_kv - a.S_q;
+
+    // keys this block can see at all: the causal bound of its last query row
+    int kv_end = a.S_kv;
+    if (a.causal) {
+        const int last = qt * TQ + TQ + shift;  // exclusive
+        kv_end = last < kv_end ? last : kv_end;
+    }
+    const int n_tiles = (kv_end + TKV - 1) / TKV;
+
+    // ---- Q fragments: column operand of S^T = K Q^T; lane = (query l32, k-chunk h) ---------------------------
+    abf16x8 qf[T::RB][8];
+#pragma unroll
+    for (int rb = 0; rb < T::RB; ++rb) {
+        const int q = q0 + rb * 32 + l32;
+        const __bf16* src = a.Q + (static_cast<int64_t>(q) * a.H_q + head) * kHeadDim + 8 * h;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            au32x4 v = {0u, 0u, 0u, 0u};
+            if (q < a.S_q) v = *reinterpret_cast<const au32x4*>(src + 16 * s);
+            qf[rb][s] = __builtin_bit_cast(abf16x8, v);
+        }
+    }
+
+    // ---- staging registers for one KV tile --------------------------------------------------------------
+    au32x4 kreg[T::KC];
+    au32x4 vreg[T::VU][4];
+    auto load_tile = [&](int t) {
+        const int kv0 = t * TKV;
+#pragma unroll
+        for (int i = 0; i < T::KC; ++i) {
+            const int c = tid + i * T::NT;
+            const int kv = kv0 + (c >> 4);
+            au32x4 v = {0u, 0u, 0u, 0u};
+            if (c < T::K_TOTAL && kv < a.S_kv)
+                v = *reinterpret_cast<const au32x4*>(a.K + (static_cast<int64_t>(kv) * a.H_kv + kh) * kHeadDim + (c & 15) * 8);
+            kreg[i] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < T::VU; ++i) {
+            const int u = tid + i * T::NT;
+            const int quad = u % T::QN, dc = u / T::QN;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int kv = kv0 + 4 * quad + r;
+                au32x4 v = {0u, 0u, 0u, 0u};
+                if (u < T::V_TOTAL && kv < a.S_kv)
+                    v = *reinterpret_cast<const au32x4*>(a.V + (static_cast<int64_t>(kv) * a.H_kv + kh) * kHeadDim + dc * 8);
+                vreg[i][r] = v;
+            }
+        }
+    };
+    auto store_tile = [&]() {
+#pragma unroll
+        for (int i = 0; i < T::KC; ++i) {
+            const int c = tid + i * T::NT;
+            if (c < T::K_TOTAL) *reinterpret_cast<au32x4*>(k_lds + (c >> 4) * T::K_ROW + (c & 15) * 16) = kreg[i];
+        }
+#pragma unroll
+        for (int i = 0; i < T::VU; ++i) {
+            const int u = tid + i * T::NT;
+            if (u >= T::V_TOTAL) continue;
+            const int quad = u % T::QN, dc = u / T::QN;
+            // key = 32b + 8jj + 4hq + r  ->  16-byte chunk (2b + jj/2)*2 + hq, half jj%2, element r
+            const int b = quad >> 3, jj = (quad >> 1) & 3, hq = quad & 1;
+            char* dst = v_lds + (dc * 8) * T::V_ROW + (((b * 2 + (jj >> 1)) * 2 + hq) * 16) + (jj & 1) * 8;
+#pragma unroll
+            for (int d = 0; d < 8; ++d) {
+                const int w = d >> 1;
+                unsigned x0 = vreg[i][0][w], x1 = vreg[i][1][w], x2 = vreg[i][2][w], x3 = vreg[i][3][w];
+                au32x2 o;
+                if (d & 1) {
+                    o.x = (x0 >> 16) | (x1 & 0xffff0000u);
+                    o.y = (x2 >> 16) | (x3 & 0xffff0000u);
+                } else {
+                    o.x = (x0 & 0xffffu) | (x1 << 16);
+                    o.y = (x2 & 0xffffu) | (x3 << 16);
+                }
+                *reinterpret_cast<au32x2*>(dst + d * T::V_ROW) = o;
+            }
+        }
+    };
+
+    // ---- online softmax state: one query column per lane (lanes l and l^32 hold the same query) -------------
+    af32x16 o[T::RB][4];
+    float m_run[T::RB], l_run[T::RB];
+#pragma unroll
+    for (int rb = 0; rb < T::RB; ++rb) {
+        m_run[rb] = -INFINITY;
+        l_run[rb] = 0.0f;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) o[rb][db][e] = 0.0f;
+    }
+
+    if (n_tiles > 0) load_tile(0);
+    for (int t = 0; t < n_tiles; ++t) {
+        store_tile();
+        __syncthreads();
+        if (t + 1 < n_tiles) load_tile(t + 1);
+        const int kv0 = t * TKV;
+
+        // S^T[key][query] for the tile
+        af32x16 s[T::KB][T::RB];
+#pragma unroll
+        for (int b = 0; b < T::KB; ++b) {
+#pragma unroll
+            for (int rb = 0; rb < T::RB; ++rb)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) s[b][rb][e] = 0.0f;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                const abf16x8 kf = *reinterpret_cast<const abf16x8*>(k_lds + (32 * b + l32) * T::K_ROW + (2 * ks + h) * 16);
+#pragma unroll
+                for (int rb = 0; rb < T::RB; ++rb)
+                    s[b][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rb][ks], s[b][rb], 0, 0, 0);
+            }
+        }
+
+        // online softmax in base 2
+#pragma unroll
+        for (int rb = 0; rb < T::RB; ++rb) {
+            const int q = q0 + rb * 32 + l32;
+            // wave-uniform: can any element of this tile be masked for these 32 queries?
+            const bool ragged = kv0 + TKV > a.S_kv;
+            const bool diag = a.causal && (kv0 + TKV - 1 > q0 + rb * 32 + shift);
+            int limit = a.S_kv - 1;  // last visible key of this lane's query
+            if (a.causal && q + shift < limit) limit = q + shift;
+            float mx = -INFINITY;
+#pragma unroll
+            for (int b = 0; b < T::KB; ++b)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    float v = s[b][rb][e] * a.scale_log2;
+                    if (ragged || diag) {
+                        const int kv = kv0 + 32 * b + 8 * (e >> 2) + 4 * h + (e & 3);
+                        if (kv > limit) v = -INFINITY;
+                    }
+                    s[b][rb][e] = v;
+                    mx = fmaxf(mx, v);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m_run[rb], mx);
+            const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;  // a row that has seen no key yet
+            const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - m_use);
+            float rowsum = 0.0f;
+#pragma unroll
+            for (int b = 0; b < T::KB; ++b)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const float p = __builtin_amdgcn_exp2f(s[b][rb][e] - m_use);
+                    s[b][rb][e] = p;
+                    rowsum += p;
+                }
+            l_run[rb] = l_run[rb] * alpha + rowsum;
+            m_run[rb] = m_new;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) o[rb][db][e] *= alpha;
+        }
+
+        // O^T[d][query] += V^T[d][key] P^T[key][query]
+#pragma unroll
+        for (int b = 0; b < T::KB; ++b)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                abf16x8 pf[T::RB];
+#pragma unroll
+                for (int rb = 0; rb < T::RB; ++rb)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) pf[rb][e] = static_cast<__bf16>(s[b][rb][8 * ks + e]);
+#pragma unroll
+                for (int db = 0; db < 4; ++db) {
+                    const abf16x8 vf =
+                        *reinterpret_cast<const abf16x8*>(v_lds + (32 * db + l32) * T::V_ROW + ((b * 2 + ks) * 2 + h) * 16);
+#pragma unroll
+                    for (int rb = 0; rb < T::RB; ++rb)
+                        o[rb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[rb], o[rb][db], 0, 0, 0);
+                }
+            }
+        __syncthreads();  // every wavefront is done with this tile's LDS
+    }
+
+    // ---- normalise and store: lane holds query q, dims 32db + 8jj + 4h + r --------------------------------
+#pragma unroll
+    for (int rb = 0; rb < T::RB; ++rb) {
+        const int q = q0 + rb * 32 + l32;
+        const float lsum = l_run[rb] + __shfl_xor(l_run[rb], 32);
+        const float inv = lsum > 0.0f ? 1.0f / lsum : 0.0f;
+        if (q >= a.S_q) continue;
+        __bf16* dst = a.O + (static_cast<int64_t>(q) * a.H_q + head) * kHeadDim + 4 * h;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                abf16x4 v;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[r] = static_cast<__bf16>(o[rb][db][4 * jj + r] * inv);
+                *reinterpret_cast<abf16x4*>(dst + 32 * db + 8 * jj) = v;
+            }
+    }
+}
+
+}  // namespace wt

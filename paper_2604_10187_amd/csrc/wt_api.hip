@@ -7,6 +7,7 @@
 #include <new>
 #include <vector>
 
+#include "attn_kernel.hpp"
 #include "gemm_kernel.hpp"
 #include "wt_internal.hpp"
 
@@ -45,11 +46,37 @@ struct Problem {
     const float* sB;
     int groups = 0;
     const int32_t* offsets = nullptr;  // device, groups + 1 entries
+    // attention contexts: (M, N, K) = (S_q, H_q, S_kv), A = Q, B = K, C = O
+    const void* V = nullptr;
+    int64_t H_kv = 0;
+    float scale = 0.0f;
+    int causal = 0;
 };
+
+constexpr int64_t kMaxSeq = 1 << 22;  // S_q, S_kv: row offsets times heads times 128 stay far below 2^63, block ids below 2^31
+
+int launch_attn(wt_ctx* ctx, const Config& c, const Problem& p, hipStream_t stream) {
+    if (p.M == 0 || p.N == 0) return WT_OK;
+    const int64_t q_tiles = ceil_div64(p.M, c.cfg.bm), G = q_tiles * p.N;
+    if (G > 0x7FFFFFFF) return WT_ERR_INVALID_ARG;
+    AttnArgs a;
+    a.Q = static_cast<const __bf16*>(p.A); a.K = static_cast<const __bf16*>(p.B);
+    a.V = static_cast<const __bf16*>(p.V); a.O = static_cast<__bf16*>(p.C);
+    a.S_q = (int)p.M; a.S_kv = (int)p.K; a.H_q = (int)p.N; a.H_kv = (int)p.H_kv;
+    a.q_tiles = (int)q_tiles;
+    a.order = c.cfg.swizzle;
+    a.causal = p.causal;
+    a.scale_log2 = p.scale * 1.4426950408889634f;
+    void* params[] = {&a};
+    WT_HIP(ctx, hipLaunchKernel(c.fn, dim3((unsigned)G), dim3((unsigned)(c.cfg.nwave * 64)), params,
+                                (size_t)c.res.lds_bytes, stream));
+    return WT_OK;
+}
 
 constexpr int kMaxGroups = 1024;
 
 int launch(wt_ctx* ctx, const Config& c, const Problem& p, hipStream_t stream) {
+    if (ctx->in_type == WT_ATTN_BF16) return launch_attn(ctx, c, p, stream);
     const Key& key = ctx->keys[c.res.key_id];
     int64_t tiles_m = ceil_div64(p.M, c.cfg.bm);
     const int64_t tiles_n = ceil_div64(p.N, c.cfg.bn);
@@ -85,7 +112,7 @@ int launch(wt_ctx* ctx, const Config& c, const Problem& p, hipStream_t stream) {
 }
 
 int check_gemm_args(const wt_ctx* ctx, const Problem& p, const wt_cfg& cfg, int* id) {
-    if (!ctx) return WT_ERR_INVALID_ARG;
+    if (!ctx || ctx->in_type == WT_ATTN_BF16) return WT_ERR_INVALID_ARG;
     if (ctx->device < 0) return WT_ERR_NO_DEVICE;
     const int rc = validate_shape(ctx, p.M, p.N, p.K);
     if (rc != WT_OK) return rc;
@@ -145,6 +172,35 @@ int check_grid(const wt_grid* g) {
         return WT_ERR_INVALID_ARG;
     for (int j = 0; j < g->n_k_anchors; ++j)
         if (g->k_anchors[j] < 1) return WT_ERR_INVALID_ARG;
+    if (g->n_heads < 0) return WT_ERR_INVALID_ARG;
+    return WT_OK;
+}
+
+// Attention contexts (Sec. 4.2, attention rules): head-aligned grid sizes, S_q = (g / N_h) * T_Q, KV lengths from
+// the multipliers; fn gets (M, N, K) = (S_q, N_h, L * T_KV).
+template <typename F>
+int walk_plan_attn(const wt_ctx* ctx, const wt_grid* grid, F&& fn) {
+    if (grid->n_heads < 1) return WT_ERR_INVALID_ARG;
+    const int nk = (int)ctx->keys.size();
+    std::vector<GridPoint> pts;
+    std::vector<int64_t> anchors;
+    for (int k = 0; k < nk; ++k) {
+        if (!key_in_slice(grid, k, nk)) continue;
+        const Key& key = ctx->keys[k];
+        sample_grid_heads(key.cap, grid->W, grid->I, grid->n_heads, pts);
+        for (size_t s = 0; s < pts.size(); ++s) {
+            if (pts[s].g == 0) continue;
+            const int64_t S_q = pts[s].m * key.bm;
+            if (grid->max_out_elems > 0 && S_q * grid->n_heads * kHeadDim > grid->max_out_elems) continue;
+            const int w = (int)(s / (size_t)grid->I) + 1;
+            kv_loop_anchors(grid, S_q, key.bk, anchors);
+            for (int64_t L : anchors) {
+                if (L < 1 || L * key.bk > kMaxSeq || S_q > kMaxSeq) continue;
+                const int rc = fn(k, pts[s], w, 0, L, S_q, (int64_t)grid->n_heads, L * key.bk);
+                if (rc != WT_OK) return rc;
+            }
+        }
+    }
     return WT_OK;
 }
 
@@ -153,6 +209,7 @@ int check_grid(const wt_grid* g) {
 // (m = 1, 2, 4 tile rows: families 1, 2, 3) with n the widest that keeps the task count in the sub-interval.
 template <typename F>
 int walk_plan(const wt_ctx* ctx, const wt_grid* grid, F&& fn) {
+    if (ctx->in_type == WT_ATTN_BF16) return walk_plan_attn(ctx, grid, fn);
     const int nk = (int)ctx->keys.size();
     std::vector<GridPoint> pts;
     std::vector<int64_t> anchors;
@@ -206,7 +263,8 @@ int walk_plan(const wt_ctx* ctx, const wt_grid* grid, F&& fn) {
 extern "C" {
 
 int wt_create(wt_ctx** out, int device, int in_type, int out_type) {
-    if (!out || (in_type != WT_BF16 && in_type != WT_FP8_E4M3) || (out_type != WT_OUT_F32 && out_type != WT_OUT_BF16))
+    if (!out || (in_type != WT_BF16 && in_type != WT_FP8_E4M3 && in_type != WT_ATTN_BF16) ||
+        (out_type != WT_OUT_F32 && out_type != WT_OUT_BF16) || (in_type == WT_ATTN_BF16 && out_type != WT_OUT_BF16))
         return WT_ERR_INVALID_ARG;
     *out = nullptr;
     wt_ctx* ctx = new (std::nothrow) wt_ctx();
@@ -245,7 +303,7 @@ int wt_create(wt_ctx** out, int device, int in_type, int out_type) {
             hipFuncAttributes fa;
             memset(&fa, 0, sizeof(fa));
             e = hipFuncSetAttribute(c0.fn, hipFuncAttributeMaxDynamicSharedMemorySize, key.lds_bytes);
-            if (e == hipSuccess)
+            if (e == hipSuccess && c0.fn_persistent)
                 e = hipFuncSetAttribute(c0.fn_persistent, hipFuncAttributeMaxDynamicSharedMemorySize, key.lds_bytes);
             if (e == hipSuccess) e = hipFuncGetAttributes(&fa, c0.fn);
             if (e == hipSuccess)
@@ -255,8 +313,10 @@ int wt_create(wt_ctx** out, int device, int in_type, int out_type) {
             key.occ = occ;
             key.cap = key_capacity(ctx->cap_mode, occ);
             int occ_p = 0;
-            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_p, c0.fn_persistent, key.nwave * 64,
-                                                             (size_t)key.lds_bytes) != hipSuccess) {
+            if (!c0.fn_persistent) {
+                occ_p = 1;
+            } else if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_p, c0.fn_persistent, key.nwave * 64,
+                                                                    (size_t)key.lds_bytes) != hipSuccess) {
                 (void)hipGetLastError();
                 occ_p = 1;
             }
@@ -281,7 +341,7 @@ int wt_destroy(wt_ctx* ctx) {
 }
 
 int wt_set_persistent(wt_ctx* ctx, int on) {
-    if (!ctx || (on != 0 && on != 1)) return WT_ERR_INVALID_ARG;
+    if (!ctx || (on != 0 && on != 1) || (on && ctx->in_type == WT_ATTN_BF16)) return WT_ERR_INVALID_ARG;
     ctx->persistent = on;
     return WT_OK;
 }
@@ -336,6 +396,50 @@ int wt_time_gemm_grouped(wt_ctx* ctx, int32_t groups, const int32_t* group_offse
     return time_config(ctx, ctx->cfgs[id], p, warmup, iters, (hipStream_t)hip_stream, mean_us);
 }
 
+static int check_attn_args(const wt_ctx* ctx, int64_t H_q, int64_t H_kv, int64_t S_q, int64_t S_kv, const void* Q,
+                           const void* K, const void* V, void* O, float scale, int causal, const wt_cfg& cfg, int* id) {
+    if (!ctx || ctx->in_type != WT_ATTN_BF16) return WT_ERR_INVALID_ARG;
+    if (ctx->device < 0) return WT_ERR_NO_DEVICE;
+    if (H_q < 1 || H_kv < 1 || H_q % H_kv || H_q > 65536 || S_q < 0 || S_kv < 0 || S_q > kMaxSeq || S_kv > kMaxSeq ||
+        (causal != 0 && causal != 1) || (causal && S_kv < S_q) || !(scale == scale))
+        return WT_ERR_INVALID_ARG;
+    if (S_q > 0 && (!Q || !O || (S_kv > 0 && (!K || !V)))) return WT_ERR_INVALID_ARG;
+    *id = find_config(ctx, cfg);
+    if (*id < 0) return WT_ERR_UNSUPPORTED_CFG;
+    if (ctx->cfgs[*id].res.occ < 1) return WT_ERR_INFEASIBLE;
+    return WT_OK;
+}
+
+int wt_attn(wt_ctx* ctx, int64_t n_heads, int64_t n_kv_heads, int64_t S_q, int64_t S_kv, const void* Q,
+            const void* K, const void* V, void* O, float scale, int causal, wt_cfg cfg, void* hip_stream) {
+    int id = -1;
+    const int rc = check_attn_args(ctx, n_heads, n_kv_heads, S_q, S_kv, Q, K, V, O, scale, causal, cfg, &id);
+    if (rc != WT_OK) return rc;
+    Problem p{S_q, n_heads, S_kv, Q, K, O, nullptr, nullptr};
+    p.V = V; p.H_kv = n_kv_heads; p.scale = scale; p.causal = causal;
+    return launch(ctx, ctx->cfgs[id], p, (hipStream_t)hip_stream);
+}
+
+int wt_time_attn(wt_ctx* ctx, int64_t n_heads, int64_t n_kv_heads, int64_t S_q, int64_t S_kv, const void* Q,
+                 const void* K, const void* V, void* O, float scale, int causal, wt_cfg cfg, int warmup, int iters,
+                 void* hip_stream, double* mean_us) {
+    int id = -1;
+    if (!mean_us || warmup < 0 || iters < 1) return WT_ERR_INVALID_ARG;
+    const int rc = check_attn_args(ctx, n_heads, n_kv_heads, S_q, S_kv, Q, K, V, O, scale, causal, cfg, &id);
+    if (rc != WT_OK) return rc;
+    Problem p{S_q, n_heads, S_kv, Q, K, O, nullptr, nullptr};
+    p.V = V; p.H_kv = n_kv_heads; p.scale = scale; p.causal = causal;
+    return time_config(ctx, ctx->cfgs[id], p, warmup, iters, (hipStream_t)hip_stream, mean_us);
+}
+
+int wt_attn_block_coords(int n_heads, int q_tiles, int order, int block, int* head, int* q_tile) {
+    if (n_heads < 1 || q_tiles < 1 || order < 0 || order >= kAttnOrders || block < 0 ||
+        (int64_t)block >= (int64_t)n_heads * q_tiles || !head || !q_tile)
+        return WT_ERR_INVALID_ARG;
+    attn_block_coords(block, n_heads, q_tiles, order, *head, *q_tile);
+    return WT_OK;
+}
+
 int wt_sample_plan(const wt_ctx* ctx, const wt_grid* grid, size_t* n_samples, size_t* bytesA, size_t* bytesB,
                    size_t* bytesC) {
     if (!ctx) return WT_ERR_INVALID_ARG;
@@ -343,8 +447,15 @@ int wt_sample_plan(const wt_ctx* ctx, const wt_grid* grid, size_t* n_samples, si
     if (rc != WT_OK) return rc;
     Plan p;
     const size_t esz = ctx->in_type == WT_BF16 ? 2 : 1, osz = ctx->out_type == WT_OUT_F32 ? 4 : 2;
+    const bool attn = ctx->in_type == WT_ATTN_BF16;
     rc = walk_plan(ctx, grid, [&](int k, const GridPoint&, int, int, int64_t, int64_t M, int64_t N, int64_t K) {
         p.n_samples += (size_t)ctx->keys[k].n_micro;
+        if (attn) {  // Q, K followed by V, O; bf16
+            p.bytesA = std::max(p.bytesA, (size_t)(M * N * kHeadDim) * 2);
+            p.bytesB = std::max(p.bytesB, (size_t)(K * N * kHeadDim) * 4);
+            p.bytesC = std::max(p.bytesC, (size_t)(M * N * kHeadDim) * 2);
+            return (int)WT_OK;
+        }
         p.bytesA = std::max(p.bytesA, (size_t)(M * K) * esz);
         p.bytesB = std::max(p.bytesB, (size_t)(N * K) * esz);
         p.bytesC = std::max(p.bytesC, (size_t)(M * N) * osz);
@@ -378,7 +489,12 @@ int wt_profile_sparse(wt_ctx* ctx, const wt_grid* grid, void* scrA, void* scrB, 
             const Config& c = ctx->cfgs[key.first_cfg + m];
             double us = 0;
             if (c.res.occ < 1) return (int)WT_ERR_INFEASIBLE;
-            const Problem p{M, N, K, scrA, scrB, scrC, sA, sB};
+            Problem p{M, N, K, scrA, scrB, scrC, sA, sB};
+            if (ctx->in_type == WT_ATTN_BF16) {  // multi-head, full attention; V sits behind K in scrB
+                p.V = (const char*)scrB + (size_t)(K * N * kHeadDim) * 2;
+                p.H_kv = N;
+                p.scale = 0.08838834764831845f;  // 1 / sqrt(128)
+            }
             const int r = time_config(ctx, c, p, grid->warmup, grid->iters, stream, &us);
             if (r != WT_OK) return r;
             wt_sample s;

@@ -23,8 +23,14 @@ WT_DECL(0, 1, 0) WT_DECL(0, 1, 1) WT_DECL(0, 1, 2)
 WT_DECL(1, 0, 0) WT_DECL(1, 0, 1) WT_DECL(1, 0, 2)
 WT_DECL(1, 1, 0) WT_DECL(1, 1, 1) WT_DECL(1, 1, 2)
 #undef WT_DECL
+const KernelEntry* wt_kernels_attn(int* n);
 
 const KernelEntry* kernel_list(int in, int out, int list, int* n) {
+    if (in == WT_ATTN_BF16) {
+        if (out == WT_OUT_BF16 && list == 0) return wt_kernels_attn(n);
+        *n = 0;
+        return nullptr;
+    }
 #define WT_CASE(i, o, l) \
     if (in == i && out == o && list == l) return wt_kernels_in##i##_out##o##_list##l(n);
     WT_CASE(0, 0, 0) WT_CASE(0, 0, 1) WT_CASE(0, 0, 2)
@@ -109,6 +115,7 @@ int build_registry(wt_ctx* ctx) {
             base.push_back(e[i]);
         }
     }
+    if (ctx->in_type == WT_ATTN_BF16) return ctx->cfgs.empty() ? WT_ERR_UNSUPPORTED_CFG : WT_OK;
     // split-K keys reuse the kernel of their base entry
     const SplitEntry* sp = ctx->in_type == WT_BF16 ? kSplitBf16 : kSplitFp8;
     const size_t nsp = ctx->in_type == WT_BF16 ? sizeof(kSplitBf16) / sizeof(kSplitBf16[0])
@@ -191,6 +198,29 @@ void sample_grid(int64_t cap, int W, int I, int tau_num, int tau_den, int split,
             out.push_back(gp);
         }
     }
+}
+
+// Attention grid samples (Sec. 4.2): the head-aligned value floor(b / N_h) * N_h of each sub-interval [a, b],
+// kept only if it is still inside; m = query tiles per head, n = N_h.
+void sample_grid_heads(int64_t cap, int W, int I, int n_heads, std::vector<GridPoint>& out) {
+    out.clear();
+    for (int w = 1; w <= W; ++w) {
+        const int64_t lo = static_cast<int64_t>(w - 1) * cap + 1;
+        for (int i = 1; i <= I; ++i) {
+            const int64_t a = lo + (static_cast<int64_t>(i - 1) * cap) / I;
+            const int64_t b = lo - 1 + (static_cast<int64_t>(i) * cap) / I;
+            const int64_t g = (b / n_heads) * n_heads;
+            out.push_back(g >= a && g >= 1 ? GridPoint{g, g / n_heads, n_heads} : GridPoint{0, 0, 0});
+        }
+    }
+}
+
+// Loop counts of an attention grid point: KV length = floor(S_q * percent / 100) for every multiplier.
+void kv_loop_anchors(const wt_grid* grid, int64_t S_q, int t_kv, std::vector<int64_t>& out) {
+    out.clear();
+    for (int j = 0; j < grid->n_k_anchors; ++j) out.push_back(ceil_div64((S_q * grid->k_anchors[j]) / 100, t_kv));
+    std::sort(out.begin(), out.end());
+    out.erase(std::unique(out.begin(), out.end()), out.end());
 }
 
 void loop_anchors(const wt_grid* grid, int bk_eff, std::vector<int64_t>& out) {
@@ -727,6 +757,20 @@ int wt_sample_grid(int64_t capacity, int32_t W, int32_t I, int32_t tau_num, int3
         if (g) g[i] = pts[i].g;
         if (m) m[i] = pts[i].m;
         if (n) n[i] = pts[i].n;
+    }
+    return WT_OK;
+}
+
+int wt_sample_grid_heads(int64_t capacity, int32_t W, int32_t I, int32_t n_heads, int64_t* g, int64_t* q_tiles,
+                         size_t cap_out, size_t* n_out) {
+    if (capacity < 1 || W < 1 || I < 1 || n_heads < 1 || !n_out) return WT_ERR_INVALID_ARG;
+    std::vector<GridPoint> pts;
+    sample_grid_heads(capacity, W, I, n_heads, pts);
+    *n_out = pts.size();
+    if (pts.size() > cap_out) return WT_ERR_BUFFER_TOO_SMALL;
+    for (size_t i = 0; i < pts.size(); ++i) {
+        if (g) g[i] = pts[i].g;
+        if (q_tiles) q_tiles[i] = pts[i].m;
     }
     return WT_OK;
 }

@@ -108,5 +108,7 @@ struct GridPoint {
 };
 void sample_grid(int64_t cap, int W, int I, int tau_num, int tau_den, int split, std::vector<GridPoint>& out);
 void loop_anchors(const wt_grid* grid, int bk_eff, std::vector<int64_t>& out);
+void sample_grid_heads(int64_t cap, int W, int I, int n_heads, std::vector<GridPoint>& out);
+void kv_loop_anchors(const wt_grid* grid, int64_t S_q, int t_kv, std::vector<int64_t>& out);
 
 }  // namespace wt

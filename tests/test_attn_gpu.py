@@ -1,0 +1,115 @@
+"""GPU parity: wt_attn (through the C ABI) against the fp64 oracle, element by element.
+
+Tolerance.  Inputs are bf16; scores and the online softmax are fp32; probabilities are rounded to bf16 before they
+multiply V (relative error 2^-9 per term, averaging down over the keys) and the output is rounded to bf16
+(2^-9 relative).  With N(0,1) values the outputs have magnitude <= a few units, so |O - O_ref| <= 2e-2 *
+max(|O_ref|, 1) per element leaves a margin of about 5x over the worst observed error.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_10187_amd as wt
+import wt_synth
+from gpu_util import all_configs, dev_bits, note
+from oracle import attention as oa
+from oracle import gemm as og
+
+pytestmark = pytest.mark.gpu
+
+ELEM_TOL = 2e-2
+SCALE = 1.0 / math.sqrt(128.0)
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = wt.wt_create(0, wt.WT_ATTN_BF16, wt.WT_OUT_BF16)
+    yield c
+    wt.wt_destroy(c)
+
+
+def run_attn(ctx, cfg, qb, kb, vb, causal, scale=SCALE):
+    S_q, H_q, _ = qb.shape
+    S_kv, H_kv, _ = kb.shape
+    dQ, dK, dV = (dev_bits(x.reshape(-1, 128)).view(torch.bfloat16) for x in (qb, kb, vb))
+    dO = torch.full((max(S_q, 1) * H_q, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
+    torch.cuda.synchronize()
+    wt.wt_attn(ctx, H_q, H_kv, S_q, S_kv, dQ, dK, dV, dO, scale, causal, cfg, stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    return dO.float().cpu().numpy()[: S_q * H_q].reshape(S_q, H_q, 128)
+
+
+def reference(qb, kb, vb, causal, scale=SCALE):
+    dec = lambda b: og.bf16_bits_to_f64(b.reshape(-1, 128)).reshape(b.shape)
+    return oa.attention(dec(qb), dec(kb), dec(vb), scale, causal)
+
+
+def check(got, want, what):
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    err = np.abs(got - want) / np.maximum(np.abs(want), 1.0)
+    assert err.max() <= ELEM_TOL, f"{what}: max scaled error {err.max():.4g} at {np.unravel_index(err.argmax(), err.shape)}"
+
+
+def test_every_config_is_launchable(ctx):
+    assert wt.wt_key_count(ctx) >= 8
+    for cfg, res in all_configs(ctx):
+        assert res.occ >= 1 and res.lds_bytes <= 160 * 1024, cfg
+
+
+def test_every_config_matches_the_oracle_on_ragged_shapes(ctx):
+    """Every <T_Q, T_KV, wavefronts, order>: several query tiles and KV tiles with ragged tails in both, grouped
+    heads (3 query heads per KV head)."""
+    for cfg, _ in all_configs(ctx):
+        S_q, S_kv, H_q, H_kv = 2 * cfg.bm + 19, 3 * cfg.bk + 21, 6, 2
+        note(f"attn cfg={cfg.astuple()} S_q={S_q} S_kv={S_kv}")
+        qb, kb, vb = wt_synth.attn_operands(S_q, S_kv, H_q, H_kv, 300 + cfg.id)
+        check(run_attn(ctx, cfg, qb, kb, vb, 0), reference(qb, kb, vb, False), f"{cfg}")
+
+
+def test_causal_matches_the_oracle(ctx):
+    """Causal masking with the queries aligned to the end of the keys: square prefill and a prefix of 77 cached
+    tokens, for every structural key (order 0 and 2)."""
+    for cfg, _ in all_configs(ctx):
+        if cfg.swizzle == 1:
+            continue
+        for S_q, S_kv in ((2 * cfg.bm + 5, 2 * cfg.bm + 5), (cfg.bm + 40, cfg.bm + 117)):
+            note(f"attn causal cfg={cfg.astuple()} S_q={S_q} S_kv={S_kv}")
+            qb, kb, vb = wt_synth.attn_operands(S_q, S_kv, 4, 4, 500 + cfg.id)
+            check(run_attn(ctx, cfg, qb, kb, vb, 1), reference(qb, kb, vb, True), f"causal {cfg} {S_q}x{S_kv}")
+
+
+def test_sharp_softmax_and_scale(ctx):
+    """Queries with gain 6 make the softmax nearly one-hot (large score range): exercises the running maximum
+    and the rescaling; also a non-default scale."""
+    cfg, _ = wt.wt_config_get(ctx, wt.wt_config_find(ctx, 128, 1, 64, 4, 1, 0))
+    qb, kb, vb = wt_synth.attn_operands(200, 700, 4, 2, 71, q_gain=6.0)
+    check(run_attn(ctx, cfg, qb, kb, vb, 0), reference(qb, kb, vb, False), "sharp")
+    check(run_attn(ctx, cfg, qb, kb, vb, 0, scale=0.31), reference(qb, kb, vb, False, scale=0.31), "scale 0.31")
+
+
+def test_degenerate_sizes(ctx):
+    cfg, _ = wt.wt_config_get(ctx, wt.wt_config_find(ctx, 64, 1, 32, 2, 1, 2))
+    for S_q, S_kv in ((1, 1), (1, 33), (65, 1), (3, 0)):
+        note(f"attn degenerate S_q={S_q} S_kv={S_kv}")
+        qb, kb, vb = wt_synth.attn_operands(S_q, S_kv, 2, 1, 90 + S_q + S_kv)
+        check(run_attn(ctx, cfg, qb, kb, vb, 0), reference(qb, kb, vb, False), f"{S_q}x{S_kv}")
+    # S_q = 0 is a no-op
+    wt.wt_attn(ctx, 2, 1, 0, 5, None, None, None, None, SCALE, 0, cfg)
+    torch.cuda.synchronize()
+
+
+def test_argument_errors(ctx):
+    cfg, _ = wt.wt_config_get(ctx, 0)
+    t = torch.zeros(64 * 4 * 128, dtype=torch.bfloat16, device="cuda")
+    for args in ((4, 3, 8, 8), (0, 1, 8, 8), (4, 4, -1, 8)):
+        with pytest.raises(wt.WtError):
+            wt.wt_attn(ctx, args[0], args[1], args[2], args[3], t, t, t, t, SCALE, 0, cfg)
+    with pytest.raises(wt.WtError):   # causal with fewer keys than queries
+        wt.wt_attn(ctx, 4, 4, 16, 8, t, t, t, t, SCALE, 1, cfg)
+    with pytest.raises(wt.WtError):   # a GEMM call on an attention context
+        wt.wt_gemm(ctx, 8, 8, 8, t, t, t, cfg)
+    bad = wt.wt_cfg(64, 1, 48, 2, 1, 0, 1, -1)
+    with pytest.raises(wt.WtError):
+        wt.wt_attn(ctx, 4, 4, 8, 8, t, t, t, t, SCALE, 0, bad)

@@ -134,3 +134,33 @@ def group_offsets(counts) -> np.ndarray:
 # an 8-expert / top-2 / hidden 4096 / expert width 14336 layer.
 MOE_LAYERS = [(128, 8, 1536, 2048), (128, 8, 2048, 768), (8, 2, 28672, 4096), (8, 2, 4096, 14336)]
 MOE_TOKENS = [16, 128, 1024, 8192]
+
+
+# ---- attention workloads (stand-in for the paper's FlashAttention test set: sequence lengths 64..16384,
+#      16..128 query heads, 2..16 KV heads, head dimension 128; not public, so drawn from the same ranges) ----
+ATTN_HEAD_DIM = 128
+ATTN_Q_HEADS = (16, 32, 64, 128)
+ATTN_KV_HEADS = (2, 4, 8, 16)
+
+
+def attn_operands(S_q: int, S_kv: int, H_q: int, H_kv: int, seed: int, q_gain: float = 1.0):
+    """(Q [S_q,H_q,128], K [S_kv,H_kv,128], V [S_kv,H_kv,128]) as bf16 storage bits; N(0,1) entries, Q scaled by
+    q_gain (a gain above 1 sharpens the softmax)."""
+    rng = np.random.default_rng(seed)
+    q = rng.standard_normal((S_q, H_q, ATTN_HEAD_DIM), dtype=np.float32) * np.float32(q_gain)
+    k = rng.standard_normal((S_kv, H_kv, ATTN_HEAD_DIM), dtype=np.float32)
+    v = rng.standard_normal((S_kv, H_kv, ATTN_HEAD_DIM), dtype=np.float32)
+    return tuple(to_bf16_bits(x.reshape(-1, ATTN_HEAD_DIM)).reshape(x.shape) for x in (q, k, v))
+
+
+def attn_shapes(count: int = 64, seed: int = 1006):
+    """(S_q, S_kv, H_q, H_kv) draws: log-uniform sequence length in [64, 16384] (prefill: S_kv = S_q), head counts
+    from the lists above with H_kv <= H_q."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        s = int(np.clip(round(math.exp(rng.uniform(math.log(64), math.log(16384)))), 64, 16384))
+        hq = int(ATTN_Q_HEADS[rng.integers(0, len(ATTN_Q_HEADS))])
+        hkv = int(ATTN_KV_HEADS[rng.integers(0, len(ATTN_KV_HEADS))])
+        out.append((s, s, hq, min(hkv, hq)))
+    return out
