@@ -76,6 +76,30 @@ def select(table: DualTable, M: int, N: int, K: int):
     return k, micro, t
 
 
+def select_attn(table: DualTable, n_heads: int, S_q: int, S_kv: int):
+    """Runtime selection for an attention launch on a table of attention keys <T_Q, T_KV, wavefronts> (stored in
+    the key descriptor as bm = T_Q, bk = T_KV): Stage I prices every key at Phi of Table 2's FlashAttention row,
+    Stage II takes the micro of the nearest loop anchor.  Returns (key, micro, T-hat) or None."""
+    from .attention import phi_attn
+
+    best = None
+    for k, kd in enumerate(table.keys):
+        G, L = phi_attn(n_heads, S_q, S_kv, kd.bm, kd.bk)
+        b = bucket_for(table, k, wave_count(G, kd.cap), 0)
+        if b is None:
+            continue
+        t = predict(b.theta, G, L)
+        if math.isnan(t):
+            continue
+        if best is None or t < best[0]:
+            best = (t, k, b, L)
+    if best is None:
+        return None
+    t, k, b, L = best
+    _, micro = nearest_anchor(b.anchors, L) if b.anchors else (0, 0)
+    return k, micro, t
+
+
 def select_grouped(table: DualTable, E: int, M_total: int, N: int, K: int):
     """Grouped GEMM at run time: the dense table serves (Sec. 4.2 samples grouped GEMM as the single-group
     case); G comes from Table 2's grouped row evaluated on the uniform approximation of the routing

@@ -4,6 +4,7 @@
     python -m paper_2604_10187_amd.evaluate wave    [--table T] [--out F]   # M=K=4096, N=128..16384 step 128
     python -m paper_2604_10187_amd.evaluate stream  [--table T] [--out F] [--sample 300]  # 10,000-shape stream
     python -m paper_2604_10187_amd.evaluate large   [--out F]               # 16384x8192x8192 bf16 and fp8
+    python -m paper_2604_10187_amd.evaluate attn    [--table T] [--out F] [--sample 48] [--causal]  # attention test set
 
 "pick" = the configuration wt_select returns; "best" = exhaustive search over the frozen registry
 with the same timing protocol (3 warm-up + 5 measured launches, mean; Sec. 4.2).  The pick's time is
@@ -347,6 +348,70 @@ def cmd_vendor(a, torch):
             "summary": summary, "rows": rows}
 
 
+def cmd_attn(a, torch):
+    """Attention test set (stand-in for Sec. 5.1's: sequence length 64..16384, 16..128 query heads, 2..16 KV
+    heads, head dimension 128): wt_select(S_q, N_h, S_kv) on the attention table against exhaustive search over the
+    attention registry, plus the best single configuration as the fixed-default baseline and the vendor
+    library's scaled_dot_product_attention as context."""
+    import wt_synth
+
+    ctx = wt.wt_create(0, wt.WT_ATTN_BF16, wt.WT_OUT_BF16)
+    path = a.table or tune.table_path(wt.WT_ATTN_BF16, wt.WT_OUT_BF16)
+    wt.wt_load(ctx, path)
+    cfgs = [wt.wt_config_get(ctx, i) for i in range(wt.wt_config_count(ctx))]
+    stream = torch.cuda.current_stream()
+    causal = int(bool(a.causal))
+    scale = 1.0 / math.sqrt(128.0)
+    rows, t0 = [], time.time()
+    for n, (S_q, S_kv, H_q, H_kv) in enumerate(wt_synth.attn_shapes(a.sample, a.sample_seed)):
+        g = torch.Generator(device="cuda")
+        g.manual_seed(3000 + n)
+        Q = torch.randn((S_q * H_q, 128), device="cuda", generator=g).to(torch.bfloat16)
+        K = torch.randn((S_kv * H_kv, 128), device="cuda", generator=g).to(torch.bfloat16)
+        V = torch.randn((S_kv * H_kv, 128), device="cuda", generator=g).to(torch.bfloat16)
+        O = torch.empty_like(Q)
+        times = {}
+        for i, (c, r) in enumerate(cfgs):
+            times[i] = wt.wt_time_attn(ctx, H_q, H_kv, S_q, S_kv, Q, K, V, O, scale, causal, c, 2, 4, stream)
+        pick = wt.wt_select(ctx, S_q, H_q, S_kv)
+        best_id = min(times, key=times.get)
+        flop = 4.0 * S_q * S_kv * 128 * H_q * (0.5 if causal else 1.0)
+        q4 = Q.view(S_q, H_q, 128).permute(1, 0, 2)[None]
+        k4 = K.view(S_kv, H_kv, 128).permute(1, 0, 2)[None].repeat_interleave(H_q // H_kv, 1)
+        v4 = V.view(S_kv, H_kv, 128).permute(1, 0, 2)[None].repeat_interleave(H_q // H_kv, 1)
+        for _ in range(2):
+            torch.nn.functional.scaled_dot_product_attention(q4, k4, v4, is_causal=bool(causal), scale=scale)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(4):
+            torch.nn.functional.scaled_dot_product_attention(q4, k4, v4, is_causal=bool(causal), scale=scale)
+        e1.record()
+        torch.cuda.synchronize()
+        vendor_us = e0.elapsed_time(e1) * 1000.0 / 4
+        rows.append({"S_q": S_q, "S_kv": S_kv, "H_q": H_q, "H_kv": H_kv, "pick": list(pick.astuple()),
+                     "pick_us": times[pick.id], "best": list(cfgs[best_id][0].astuple()), "best_us": times[best_id],
+                     "frac": times[best_id] / times[pick.id], "pick_tflops": flop / times[pick.id] / 1e6,
+                     "best_tflops": flop / times[best_id] / 1e6, "vendor_us": vendor_us,
+                     "times": {str(i): round(t, 3) for i, t in times.items()}})
+        if n % 8 == 0:
+            _log(f"[attn] {n + 1} shapes, {time.time() - t0:.0f}s, last frac {rows[-1]['frac']:.3f}")
+    fr = np.array([r["frac"] for r in rows])
+    gm = lambda x: float(np.exp(np.mean(np.log(np.asarray(x, dtype=np.float64)))))
+    # the best single configuration over the whole set = a fixed default
+    fixed = min(range(len(cfgs)), key=lambda i: gm([r["times"][str(i)] for r in rows]))
+    summary = {"n_shapes": len(rows), "geomean_frac": gm(fr), "min_frac": float(fr.min()),
+               "frac_ge_95": float(np.mean(fr >= 0.95)),
+               "fixed_default": list(cfgs[fixed][0].astuple()),
+               "fixed_default_geomean_frac": gm([r["best_us"] / r["times"][str(fixed)] for r in rows]),
+               "speedup_pick_over_fixed_default": gm([r["times"][str(fixed)] / r["pick_us"] for r in rows]),
+               "speedup_best_over_fixed_default": gm([r["times"][str(fixed)] / r["best_us"] for r in rows]),
+               "vendor_over_pick_geomean": gm([r["vendor_us"] / r["pick_us"] for r in rows]),
+               "max_pick_tflops": float(max(r["pick_tflops"] for r in rows))}
+    wt.wt_destroy(ctx)
+    return {"workload": f"attention test set, {len(rows)} shapes, causal={causal}", "table": path, "causal": causal,
+            "summary": summary, "rows": rows}
+
+
 def cmd_ablate(a, torch=None):
     """CPU only.  Re-fit the saved profiling records under model / (W, I) variants with wt_fit on a
     host-only context and score each variant's picks against saved exhaustive timings (the `times` of
@@ -409,7 +474,8 @@ def cmd_ablate(a, torch=None):
 
 def main(argv=None):
     ap = argparse.ArgumentParser()
-    ap.add_argument("cmd", choices=["sweep", "wave", "stream", "large", "grouped", "persistent", "vendor", "ablate"])
+    ap.add_argument("cmd", choices=["sweep", "wave", "stream", "large", "grouped", "persistent", "vendor", "ablate", "attn"])
+    ap.add_argument("--causal", action="store_true", help="attn: causal masking (queries aligned to the end of the keys)")
     ap.add_argument("--samples", default=None, help="ablate: .npz with `samples` and `occ`")
     ap.add_argument("--scores", nargs="*", default=[], help="ablate: sweep/stream result files with exhaustive timings")
     ap.add_argument("--cap-mode", type=int, default=1)
@@ -431,12 +497,12 @@ def main(argv=None):
     else:
         import torch
 
-        res = {"sweep": cmd_sweep, "wave": cmd_wave, "stream": cmd_stream, "large": cmd_large, "grouped": cmd_grouped, "persistent": cmd_persistent, "vendor": cmd_vendor}[a.cmd](a, torch)
+        res = {"sweep": cmd_sweep, "wave": cmd_wave, "stream": cmd_stream, "large": cmd_large, "grouped": cmd_grouped, "persistent": cmd_persistent, "vendor": cmd_vendor, "attn": cmd_attn}[a.cmd](a, torch)
     txt = json.dumps(res)
     if a.out:
         open(a.out, "w").write(txt)
     summ = res.get("summary") or {k: v for k, v in res.items() if k != "rows"}
-    print(json.dumps(summ if a.cmd in ("sweep", "stream") else {"workload": res["workload"]}))
+    print(json.dumps(summ if a.cmd in ("sweep", "stream", "attn") else {"workload": res["workload"]}))
 
 
 if __name__ == "__main__":

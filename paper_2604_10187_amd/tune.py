@@ -23,9 +23,13 @@ TABLE_DIR = os.path.join(os.path.dirname(os.path.abspath(__file__)), "tables")
 # K = 8192..28672, and rows whose stride is a large power of two behave differently in HBM (channel
 # aliasing makes the rasterisation mode matter), which no anchor below 8192 shows.
 K_ANCHORS = (1024, 2048, 3072, 4096, 5120, 8192)
+# Attention contexts: KV-length multipliers of S_q in percent (Sec. 5.1: 1.0 to 3.0).
+KV_MULTIPLIERS = (100, 150, 200, 250, 300)
 
 
 def table_path(in_type: int, out_type: int) -> str:
+    if in_type == wt.WT_ATTN_BF16:
+        return os.path.join(TABLE_DIR, "mi355x_attn.wt")
     return os.path.join(TABLE_DIR, f"mi355x_in{in_type}_out{out_type}.wt")
 
 
@@ -37,7 +41,7 @@ def profile(ctx, grid, in_type, out_type, log=print, chunk_keys=1):
     first = grid.key_first if grid.key_count > 0 else 0
     count = grid.key_count if grid.key_count > 0 else nkeys
     _, bA, bB, bC = wt.wt_sample_plan(ctx, grid)
-    esz = 2 if in_type == wt.WT_BF16 else 1
+    esz = 1 if in_type == wt.WT_FP8_E4M3 else 2
     # finite, non-constant contents; values do not influence timing of dense MFMA work
     scrA = (torch.randn(max(bA // esz, 16), device="cuda") * 0.5).to(torch.bfloat16 if esz == 2 else torch.float8_e4m3fn)
     scrB = (torch.randn(max(bB // esz, 16), device="cuda") * 0.5).to(torch.bfloat16 if esz == 2 else torch.float8_e4m3fn)
@@ -49,7 +53,7 @@ def profile(ctx, grid, in_type, out_type, log=print, chunk_keys=1):
         g = wt.make_grid(W=grid.W, I=grid.I, tau=(grid.tau_num, grid.tau_den), p=grid.p,
                          k_anchors=[grid.k_anchors[j] for j in range(grid.n_k_anchors)], warmup=grid.warmup,
                          iters=grid.iters, key_first=k0, key_count=kc, max_out_elems=grid.max_out_elems, model=grid.model, W_row=grid.W_row,
-                         W_split=grid.W_split, row_fams=grid.row_fams, skip_near=grid.skip_near)
+                         W_split=grid.W_split, row_fams=grid.row_fams, skip_near=grid.skip_near, n_heads=grid.n_heads)
         recs = wt.wt_profile_sparse(ctx, g, scrA, scrB, scrC, stream=torch.cuda.current_stream())
         out.append(recs)
         log(f"[tune] keys {k0}..{k0 + kc - 1}: {len(recs)} records, {time.time() - t0:.0f}s elapsed")
@@ -65,7 +69,10 @@ def main(argv=None):
     ap.add_argument("--p", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--iters", type=int, default=5)
-    ap.add_argument("--k-anchors", type=int, nargs="+", default=list(K_ANCHORS))
+    ap.add_argument("--k-anchors", type=int, nargs="+", default=None,
+                    help="GEMM: K values of the loop anchors; attention: KV-length multipliers in percent of S_q")
+    ap.add_argument("--n-heads", type=int, nargs="+", default=[32],
+                    help="attention contexts: head counts to profile (records of all of them are fitted together)")
     ap.add_argument("--key-first", type=int, default=0)
     ap.add_argument("--key-count", type=int, default=0)
     ap.add_argument("--max-out-elems", type=int, default=0)
@@ -79,9 +86,13 @@ def main(argv=None):
     ap.add_argument("--fit-from", nargs="*", default=None)
     ap.add_argument("--out", default=None)
     a = ap.parse_args(argv)
+    attn = a.in_type == wt.WT_ATTN_BF16
+    if a.k_anchors is None:
+        a.k_anchors = list(KV_MULTIPLIERS if attn else K_ANCHORS)
     grid = wt.make_grid(W=a.W, I=a.I, p=a.p, k_anchors=a.k_anchors, warmup=a.warmup, iters=a.iters,
                         key_first=a.key_first, key_count=a.key_count, max_out_elems=a.max_out_elems, model=a.model, W_row=a.W_row,
-                        W_split=a.W_split, row_fams=a.row_fams, skip_near=int(a.skip_near))
+                        W_split=a.W_split, row_fams=a.row_fams, skip_near=int(a.skip_near),
+                        n_heads=a.n_heads[0] if attn else 0)
     if a.fit_from is not None:
         recs = np.concatenate([np.load(f) for f in a.fit_from])
         occ_files = [f.replace(".npy", ".occ.npy") for f in a.fit_from]
@@ -94,9 +105,14 @@ def main(argv=None):
     else:
         ctx = wt.wt_create(0, a.in_type, a.out_type)
         wt.wt_set_capacity_mode(ctx, a.cap_mode)
-        n, bA, bB, bC = wt.wt_sample_plan(ctx, grid)
-        print(f"[tune] plan: {n} records, scratch A {bA >> 20} MiB, B {bB >> 20} MiB, C {bC >> 20} MiB", flush=True)
-        recs = profile(ctx, grid, a.in_type, a.out_type, log=lambda s: print(s, flush=True))
+        parts = []
+        for nh in (a.n_heads if attn else [0]):
+            grid.n_heads = nh
+            n, bA, bB, bC = wt.wt_sample_plan(ctx, grid)
+            print(f"[tune] plan{f' ({nh} heads)' if attn else ''}: {n} records, scratch A {bA >> 20} MiB, B {bB >> 20} MiB, "
+                  f"C {bC >> 20} MiB", flush=True)
+            parts.append(profile(ctx, grid, a.in_type, a.out_type, log=lambda s: print(s, flush=True)))
+        recs = np.concatenate(parts)
         if a.samples_out:
             np.save(a.samples_out, recs)
             occ = np.array([wt.wt_config_get(ctx, 3 * k)[1].occ for k in range(wt.wt_key_count(ctx))], dtype=np.int32)

@@ -1,0 +1,133 @@
+"""Host-side parity of the attention context (no GPU): Phi, head-aligned sampler, sampling plan, fit and
+selection of libwt against the oracle."""
+import os
+
+import numpy as np
+import pytest
+
+import paper_2604_10187_amd as wt
+import wt_synth
+from oracle import attention as oa
+from oracle import fit as ofit
+from oracle import select as osel
+from oracle.geometry import ceil_div
+
+MULT = (100, 150, 200, 250, 300)
+TABLE = os.path.join(os.path.dirname(wt.LIB_PATH), "tables", "mi355x_attn.wt")
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = wt.wt_create(-1, wt.WT_ATTN_BF16, wt.WT_OUT_BF16)
+    yield c
+    wt.wt_destroy(c)
+
+
+def _keys(ctx):
+    out = []
+    for k in range(wt.wt_key_count(ctx)):
+        c, r = wt.wt_config_get(ctx, 3 * k)
+        assert r.key_id == k and c.bn == 1 and c.split == 1 and c.stages == 1
+        out.append(c)
+    return out
+
+
+def test_attention_context_rules():
+    with pytest.raises(wt.WtError):
+        wt.wt_create(-1, wt.WT_ATTN_BF16, wt.WT_OUT_F32)       # bf16 output only
+    c = wt.wt_create(-1, wt.WT_ATTN_BF16, wt.WT_OUT_BF16)
+    try:
+        assert wt.wt_config_count(c) == 3 * wt.wt_key_count(c) >= 24
+        with pytest.raises(wt.WtError):
+            wt.wt_set_persistent(c, True)
+        with pytest.raises(wt.WtError):                          # n_heads missing
+            wt.wt_sample_plan(c, wt.make_grid(W=2, I=3, k_anchors=MULT))
+    finally:
+        wt.wt_destroy(c)
+
+
+def test_phi_matches_table_2(ctx):
+    rng = np.random.default_rng(7)
+    for c in _keys(ctx):
+        for _ in range(50):
+            S_q, S_kv, H = int(rng.integers(1, 20000)), int(rng.integers(1, 50000)), int(rng.integers(1, 129))
+            G, L = oa.phi_attn(H, S_q, S_kv, c.bm, c.bk)
+            assert wt.wt_wave_count(ctx, S_q, H, S_kv, c) == (G, L, ceil_div(G, 256))
+
+
+@pytest.mark.parametrize("cap,W,I,heads", [(256, 10, 3, 32), (256, 20, 3, 16), (256, 6, 3, 128), (512, 7, 4, 40),
+                                           (256, 35, 3, 64), (100, 9, 5, 7)])
+def test_head_aligned_sampler_bit_exact(cap, W, I, heads):
+    g, q = wt.wt_sample_grid_heads(cap, W, I, heads)
+    want = oa.sample_set_heads(cap, W, I, heads)
+    assert [(int(a), int(b)) for a, b in zip(g, q)] == [(s.g, s.q_tiles) for s in want]
+
+
+def _plan(keys, W, I, heads):
+    """(key, g, w, L) of every workload, from the oracle's rules (capacity 256)."""
+    out = []
+    for k, c in enumerate(keys):
+        for s in oa.sample_set_heads(256, W, I, heads):
+            if s.g == 0:
+                continue
+            S_q, _ = oa.instantiate_attn(s.g, 1, heads, c.bm, c.bk)
+            for L in oa.kv_loop_counts(S_q, c.bk, MULT):
+                out.append((k, s.g, s.w, L))
+    return out
+
+
+@pytest.mark.parametrize("heads", [16, 32, 128])
+def test_sampling_plan_counts_and_buffers(ctx, heads):
+    keys = _keys(ctx)
+    W, I = 6, 3
+    plan = _plan(keys, W, I, heads)
+    n, bQ, bKV, bO = wt.wt_sample_plan(ctx, wt.make_grid(W=W, I=I, k_anchors=MULT, n_heads=heads))
+    assert n == 3 * len(plan)
+    sq = max(oa.instantiate_attn(g, L, heads, keys[k].bm, keys[k].bk)[0] for k, g, w, L in plan)
+    skv = max(oa.instantiate_attn(g, L, heads, keys[k].bm, keys[k].bk)[1] for k, g, w, L in plan)
+    assert (bQ, bKV, bO) == (sq * heads * 128 * 2, skv * heads * 128 * 4, sq * heads * 128 * 2)
+
+
+def test_fit_and_select_parity_on_a_synthetic_surface(ctx, tmp_path):
+    keys = _keys(ctx)
+    W, I, p, heads = 8, 3, 4, 32
+    recs = []
+    for (k, g, w, L) in _plan(keys, W, I, heads):
+        th = wt_synth.random_theta(900 + k, W)[w - 1]
+        scale = keys[k].bm * keys[k].bk / (128.0 * 64)
+        for micro in range(3):
+            t = scale * (th[0] * g * L + th[1] * g) + th[2] * L + th[3]
+            recs.append((k, micro, g, L, w, 0, t * (1.0 + 0.04 * ((micro + L // 5 + k) % 3))))
+    samples = np.array(recs, dtype=wt.SAMPLE_DTYPE)
+    wt.wt_fit(ctx, wt.make_grid(W=W, I=I, p=p, k_anchors=MULT, n_heads=heads), samples)
+    path = str(tmp_path / "attn.wt")
+    wt.wt_save(ctx, path)
+    table, _ = osel.read_table(path)
+    kds = table.keys
+    assert [(kd.bm, kd.bn, kd.bk, kd.nwave, kd.stages, kd.cap, kd.split) for kd in kds] == \
+        [(c.bm, 1, c.bk, c.nwave, 1, 256, 1) for c in keys]
+    want = ofit.fit_tables([tuple(r)[:5] + (float(r["mean_us"]),) for r in samples], kds, W, p)
+    for k in range(len(keys)):
+        for gb, wb in list(zip(table.local[k], want.local[k])) + [(table.ext[k], want.ext[k])]:
+            assert gb.status == wb.status and gb.anchors == wb.anchors
+    for (S_q, S_kv, H_q, _) in wt_synth.attn_shapes(400, 11):
+        key, micro, t = osel.select_attn(table, H_q, S_q, S_kv)
+        c = wt.wt_select(ctx, S_q, H_q, S_kv)
+        assert (c.bm, c.bk, c.nwave, c.swizzle) == (keys[key].bm, keys[key].bk, keys[key].nwave, micro)
+        assert wt.wt_predict_us(ctx, S_q, H_q, S_kv, c) == t
+
+
+def test_shipped_attention_table_selects_like_the_oracle():
+    c = wt.wt_create(-1, wt.WT_ATTN_BF16, wt.WT_OUT_BF16)
+    try:
+        wt.wt_load(c, TABLE)
+        table, meta = osel.read_table(TABLE)
+        keys = _keys(c)
+        assert len(table.keys) == len(keys)
+        for (S_q, S_kv, H_q, _) in wt_synth.attn_shapes(300, 12):
+            key, micro, t = osel.select_attn(table, H_q, S_q, S_kv)
+            got = wt.wt_select(c, S_q, H_q, S_kv)
+            assert (got.bm, got.bk, got.nwave, got.swizzle) == (keys[key].bm, keys[key].bk, keys[key].nwave, micro)
+            assert wt.wt_predict_us(c, S_q, H_q, S_kv, got) == t
+    finally:
+        wt.wt_destroy(c)
