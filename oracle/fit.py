@@ -126,6 +126,20 @@ def fit_bilinear(rows) -> tuple[tuple, int]:
     return (alpha, beta, gamma, delta), status
 
 
+# The table format gives a bucket room for this many <loop count, micro> anchors.
+MAX_ANCHORS = 8
+
+
+def thin_anchors(anchors: list, limit: int = MAX_ANCHORS) -> list:
+    """Reading for buckets with more loop counts than the table can hold (attention grids: each grid size has its
+    own KV lengths): keep the anchors at ranks floor(i*(n-1)/(limit-1)), i = 0..limit-1 -- the smallest, the
+    largest and an even spread between them.  The fit still uses every loop count's rows."""
+    n = len(anchors)
+    if n <= limit:
+        return list(anchors)
+    return [anchors[(i * (n - 1)) // (limit - 1)] for i in range(limit)]
+
+
 def _fit_group(records) -> Bucket:
     """Shared micro per L, then one bilinear fit over the chosen micros' rows."""
     by_L = defaultdict(list)
@@ -139,7 +153,7 @@ def _fit_group(records) -> Bucket:
         anchors.append((L, pick[0]))
         rows.extend(pick[1])
     theta, status = fit_bilinear(rows)
-    return Bucket(theta=theta, status=status, anchors=anchors)
+    return Bucket(theta=theta, status=status, anchors=thin_anchors(anchors))
 
 
 def fit_step(records, cap: int):

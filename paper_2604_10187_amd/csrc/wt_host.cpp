@@ -10,6 +10,7 @@
 #include <algorithm>
 #include <chrono>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "wt_internal.hpp"
@@ -318,6 +319,7 @@ static void fit_bucket(std::vector<const wt_sample*>& recs, Bucket& out) {
         return x->G < y->G;
     });
     std::vector<Row> rows;
+    std::vector<std::pair<int32_t, int32_t>> anchors;  // (L, micro) of every loop count, ascending L
     size_t i = 0;
     while (i < recs.size()) {
         size_t j = i;
@@ -347,15 +349,21 @@ static void fit_bucket(std::vector<const wt_sample*>& recs, Bucket& out) {
             t = u;
         }
         if (have) {
-            if (out.n_anchor < kMaxAnchors) {
-                out.anchor_L[out.n_anchor] = static_cast<int32_t>(recs[best_lo]->L);
-                out.anchor_micro[out.n_anchor] = recs[best_lo]->micro_id;
-                ++out.n_anchor;
-            }
+            anchors.emplace_back(static_cast<int32_t>(recs[best_lo]->L), recs[best_lo]->micro_id);
             for (size_t r = best_lo; r < best_hi; ++r)
                 rows.push_back(Row{static_cast<double>(recs[r]->G), static_cast<double>(recs[r]->L), recs[r]->mean_us});
         }
         i = j;
+    }
+    // A bucket stores kMaxAnchors anchors.  With more loop counts than that (attention: every grid size brings
+    // its own KV lengths) the ones at ranks floor(i * (n - 1) / (kMaxAnchors - 1)) are kept: first, last and an
+    // even spread between them.
+    const int n = static_cast<int>(anchors.size());
+    out.n_anchor = n < kMaxAnchors ? n : kMaxAnchors;
+    for (int a = 0; a < out.n_anchor; ++a) {
+        const int src = n <= kMaxAnchors ? a : (a * (n - 1)) / (kMaxAnchors - 1);
+        out.anchor_L[a] = anchors[src].first;
+        out.anchor_micro[a] = anchors[src].second;
     }
     out.status = fit_rows(rows, out.th);
 }

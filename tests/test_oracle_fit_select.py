@@ -386,3 +386,14 @@ def test_few_row_families_are_chosen_by_tile_rows():
     (bk, _), bt = oex.argmin_config(cand)
     key, _, t = osel.select(table, M, N, K)
     assert key == bk and abs(t - bt) < 1e-6 * bt
+
+
+def test_thin_anchors_keeps_ends_and_an_even_spread():
+    """Buckets with more loop counts than the table holds keep ranks floor(i*(n-1)/7): hand values."""
+    a15 = [(L, L % 3) for L in range(10, 25)]
+    assert ofit.thin_anchors(a15) == [a15[i] for i in (0, 2, 4, 6, 8, 10, 12, 14)]
+    a9 = [(L, 0) for L in range(9)]
+    assert ofit.thin_anchors(a9) == [a9[i] for i in (0, 1, 2, 3, 4, 5, 6, 8)]
+    a8 = [(L, 1) for L in range(8)]
+    assert ofit.thin_anchors(a8) == a8 and ofit.thin_anchors(a8[:3]) == a8[:3]
+    assert ofit.thin_anchors(a15, 2) == [a15[0], a15[-1]]
