@@ -193,7 +193,8 @@ int wt_select_grouped(const wt_ctx* ctx, int32_t groups, int64_t M_total, int64_
  * WT_ATTN_BF16 context.  Device pointers: Q and O are [S_q, n_heads, 128], K and V are [S_kv, n_kv_heads, 128]
  * (token-major, head dimension contiguous).  n_kv_heads divides n_heads: query head h reads KV head
  * h / (n_heads / n_kv_heads) (grouped-query attention; equal counts = multi-head attention).  causal = 1: query i
- * sees keys j <= i + (S_kv - S_q), which needs S_kv >= S_q.  S_kv = 0 writes zeros; S_q = 0 is a no-op.
+ * sees keys j <= i + (S_kv - S_q), which needs S_kv >= S_q.  scale must be positive and finite (the kernel
+ * tracks the running maximum in unscaled units).  S_kv = 0 writes zeros; S_q = 0 is a no-op.
  * A configuration is <bm, bn, bk, nwave, stages, swizzle, split> = <T_Q, 1, T_KV, wavefronts, 1, order, 1>: a block
  * owns T_Q query rows of one head and loops over the KV tiles; `order` is the micro parameter (0: the query tiles
  * of a head are consecutive blocks; 1: the heads of a query tile are consecutive blocks; 2: as 0, with every one

@@ -16,7 +16,9 @@
 //   * K goes to LDS row-major (rows padded by 16 bytes), V is transposed in registers (4 keys x 8 dims per
 //     thread) and stored as V^T[d][permuted key] so that every MFMA operand is one 16-byte LDS read;
 //   * the global loads of tile t+1 are issued right after the barrier that publishes tile t and land in registers
-//     while tile t is computed.
+//     while tile t is computed; two barriers per tile (publish / release);
+//   * softmax in base 2 with the scale folded into one fma per element (the running maximum is kept in raw score
+//     units, which needs scale > 0), and the rescale of O skipped when no lane's maximum moved.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -95,6 +97,7 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
     const int l32 = lane & 31, h = lane >> 5;
     int head, qt;
     attn_block_coords(static_cast<int>(blockIdx.x), a.H_q, a.q_tiles, a.order, head, qt);
+    if (a.causal) qt = a.q_tiles - 1 - qt;  // the query tiles with the most keys start first
     const int kh = head / (a.H_q / a.H_kv);
     const int q0 = qt * TQ + wave * T::R;
     const int shift = a.S_kv - a.S_q;
@@ -121,10 +124,10 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
         }
     }
 
-    // ---- staging registers for one KV tile --------------------------------------------------------------
+    // ---- staging registers for one K tile and one V tile ----------------------------------------------------
     au32x4 kreg[T::KC];
     au32x4 vreg[T::VU][4];
-    auto load_tile = [&](int t) {
+    auto load_k = [&](int t) {
         const int kv0 = t * TKV;
 #pragma unroll
         for (int i = 0; i < T::KC; ++i) {
@@ -135,6 +138,9 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
                 v = *reinterpret_cast<const au32x4*>(a.K + (static_cast<int64_t>(kv) * a.H_kv + kh) * kHeadDim + (c & 15) * 8);
             kreg[i] = v;
         }
+    };
+    auto load_v = [&](int t) {
+        const int kv0 = t * TKV;
 #pragma unroll
         for (int i = 0; i < T::VU; ++i) {
             const int u = tid + i * T::NT;
@@ -149,12 +155,16 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
             }
         }
     };
-    auto store_tile = [&]() {
+    auto store_k = [&]() {
+        char* const base = k_lds;
 #pragma unroll
         for (int i = 0; i < T::KC; ++i) {
             const int c = tid + i * T::NT;
-            if (c < T::K_TOTAL) *reinterpret_cast<au32x4*>(k_lds + (c >> 4) * T::K_ROW + (c & 15) * 16) = kreg[i];
+            if (c < T::K_TOTAL) *reinterpret_cast<au32x4*>(base + (c >> 4) * T::K_ROW + (c & 15) * 16) = kreg[i];
         }
+    };
+    auto store_v = [&]() {
+        char* const base = v_lds;
 #pragma unroll
         for (int i = 0; i < T::VU; ++i) {
             const int u = tid + i * T::NT;
@@ -162,7 +172,7 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
             const int quad = u % T::QN, dc = u / T::QN;
             // key = 32b + 8jj + 4hq + r  ->  16-byte chunk (2b + jj/2)*2 + hq, half jj%2, element r
             const int b = quad >> 3, jj = (quad >> 1) & 3, hq = quad & 1;
-            char* dst = v_lds + (dc * 8) * T::V_ROW + (((b * 2 + (jj >> 1)) * 2 + hq) * 16) + (jj & 1) * 8;
+            char* dst = base + (dc * 8) * T::V_ROW + (((b * 2 + (jj >> 1)) * 2 + hq) * 16) + (jj & 1) * 8;
 #pragma unroll
             for (int d = 0; d < 8; ++d) {
                 const int w = d >> 1;
@@ -181,6 +191,7 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
     };
 
     // ---- online softmax state: one query column per lane (lanes l and l^32 hold the same query) -------------
+    // m_run is kept in raw score units (scale > 0, so the maximum commutes with the scaling)
     af32x16 o[T::RB][4];
     float m_run[T::RB], l_run[T::RB];
 #pragma unroll
@@ -193,74 +204,79 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
             for (int e = 0; e < 16; ++e) o[rb][db][e] = 0.0f;
     }
 
-    if (n_tiles > 0) load_tile(0);
-    for (int t = 0; t < n_tiles; ++t) {
-        store_tile();
-        __syncthreads();
-        if (t + 1 < n_tiles) load_tile(t + 1);
-        const int kv0 = t * TKV;
-
-        // S^T[key][query] for the tile
-        af32x16 s[T::KB][T::RB];
+    struct Scores {
+        af32x16 v[T::KB][T::RB];
+    };
+    // S^T[key][query] of the tile in LDS
+    auto qk = [&](Scores& s) {
+        const char* const base = k_lds;
 #pragma unroll
         for (int b = 0; b < T::KB; ++b) {
 #pragma unroll
             for (int rb = 0; rb < T::RB; ++rb)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) s[b][rb][e] = 0.0f;
+                for (int e = 0; e < 16; ++e) s.v[b][rb][e] = 0.0f;
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) {
-                const abf16x8 kf = *reinterpret_cast<const abf16x8*>(k_lds + (32 * b + l32) * T::K_ROW + (2 * ks + h) * 16);
+                const abf16x8 kf = *reinterpret_cast<const abf16x8*>(base + (32 * b + l32) * T::K_ROW + (2 * ks + h) * 16);
 #pragma unroll
                 for (int rb = 0; rb < T::RB; ++rb)
-                    s[b][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rb][ks], s[b][rb], 0, 0, 0);
+                    s.v[b][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rb][ks], s.v[b][rb], 0, 0, 0);
             }
         }
-
-        // online softmax in base 2
+    };
+    // online softmax in base 2 over the tile starting at key kv0: s becomes the unnormalised probabilities
+    auto softmax = [&](Scores& s, int kv0) {
 #pragma unroll
         for (int rb = 0; rb < T::RB; ++rb) {
             const int q = q0 + rb * 32 + l32;
             // wave-uniform: can any element of this tile be masked for these 32 queries?
             const bool ragged = kv0 + TKV > a.S_kv;
             const bool diag = a.causal && (kv0 + TKV - 1 > q0 + rb * 32 + shift);
-            int limit = a.S_kv - 1;  // last visible key of this lane's query
-            if (a.causal && q + shift < limit) limit = q + shift;
+            if (ragged || diag) {
+                int limit = a.S_kv - 1;  // last visible key of this lane's query
+                if (a.causal && q + shift < limit) limit = q + shift;
+#pragma unroll
+                for (int b = 0; b < T::KB; ++b)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int kv = kv0 + 32 * b + 8 * (e >> 2) + 4 * h + (e & 3);
+                        if (kv > limit) s.v[b][rb][e] = -INFINITY;
+                    }
+            }
             float mx = -INFINITY;
 #pragma unroll
             for (int b = 0; b < T::KB; ++b)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    float v = s[b][rb][e] * a.scale_log2;
-                    if (ragged || diag) {
-                        const int kv = kv0 + 32 * b + 8 * (e >> 2) + 4 * h + (e & 3);
-                        if (kv > limit) v = -INFINITY;
-                    }
-                    s[b][rb][e] = v;
-                    mx = fmaxf(mx, v);
-                }
+                for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s.v[b][rb][e]);
             mx = fmaxf(mx, __shfl_xor(mx, 32));
             const float m_new = fmaxf(m_run[rb], mx);
             const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;  // a row that has seen no key yet
-            const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - m_use);
+            const float alpha = __builtin_amdgcn_exp2f((m_run[rb] - m_use) * a.scale_log2);
+            const float neg = -m_use * a.scale_log2;
             float rowsum = 0.0f;
 #pragma unroll
             for (int b = 0; b < T::KB; ++b)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    const float p = __builtin_amdgcn_exp2f(s[b][rb][e] - m_use);
-                    s[b][rb][e] = p;
+                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s.v[b][rb][e], a.scale_log2, neg));
+                    s.v[b][rb][e] = p;
                     rowsum += p;
                 }
             l_run[rb] = l_run[rb] * alpha + rowsum;
             m_run[rb] = m_new;
+            // the running maximum moves in the first few tiles only: skip the rescale when no lane needs it
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+                for (int db = 0; db < 4; ++db)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) o[rb][db][e] *= alpha;
+                    for (int e = 0; e < 16; ++e) o[rb][db][e] *= alpha;
+            }
         }
-
-        // O^T[d][query] += V^T[d][key] P^T[key][query]
+    };
+    // O^T[d][query] += V^T[d][key] P^T[key][query]
+    auto pv = [&](const Scores& s) {
+        const char* const base = v_lds;
 #pragma unroll
         for (int b = 0; b < T::KB; ++b)
 #pragma unroll
@@ -269,16 +285,28 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
 #pragma unroll
                 for (int rb = 0; rb < T::RB; ++rb)
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) pf[rb][e] = static_cast<__bf16>(s[b][rb][8 * ks + e]);
+                    for (int e = 0; e < 8; ++e) pf[rb][e] = static_cast<__bf16>(s.v[b][rb][8 * ks + e]);
 #pragma unroll
                 for (int db = 0; db < 4; ++db) {
                     const abf16x8 vf =
-                        *reinterpret_cast<const abf16x8*>(v_lds + (32 * db + l32) * T::V_ROW + ((b * 2 + ks) * 2 + h) * 16);
+                        *reinterpret_cast<const abf16x8*>(base + (32 * db + l32) * T::V_ROW + ((b * 2 + ks) * 2 + h) * 16);
 #pragma unroll
                     for (int rb = 0; rb < T::RB; ++rb)
                         o[rb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[rb], o[rb][db], 0, 0, 0);
                 }
             }
+    };
+
+    if (n_tiles > 0) { load_k(0); load_v(0); }
+    for (int t = 0; t < n_tiles; ++t) {
+        store_k();
+        store_v();
+        __syncthreads();
+        if (t + 1 < n_tiles) { load_k(t + 1); load_v(t + 1); }
+        Scores s;
+        qk(s);
+        softmax(s, t * TKV);
+        pv(s);
         __syncthreads();  // every wavefront is done with this tile's LDS
     }
 

@@ -401,7 +401,7 @@ static int check_attn_args(const wt_ctx* ctx, int64_t H_q, int64_t H_kv, int64_t
     if (!ctx || ctx->in_type != WT_ATTN_BF16) return WT_ERR_INVALID_ARG;
     if (ctx->device < 0) return WT_ERR_NO_DEVICE;
     if (H_q < 1 || H_kv < 1 || H_q % H_kv || H_q > 65536 || S_q < 0 || S_kv < 0 || S_q > kMaxSeq || S_kv > kMaxSeq ||
-        (causal != 0 && causal != 1) || (causal && S_kv < S_q) || !(scale == scale))
+        (causal != 0 && causal != 1) || (causal && S_kv < S_q) || !(scale > 0.0f) || !(scale < 1e30f))
         return WT_ERR_INVALID_ARG;
     if (S_q > 0 && (!Q || !O || (S_kv > 0 && (!K || !V)))) return WT_ERR_INVALID_ARG;
     *id = find_config(ctx, cfg);

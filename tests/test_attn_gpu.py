@@ -100,6 +100,25 @@ def test_degenerate_sizes(ctx):
     torch.cuda.synchronize()
 
 
+def test_full_size_sampled_rows(ctx):
+    """16384 x 16384, 16 heads (4 KV heads), the launch configuration the evaluation times: the oracle computes a
+    sample of query rows one by one (each a softmax over all 16384 keys), non-causal and causal."""
+    S, H_q, H_kv = 16384, 16, 4
+    cfg, _ = wt.wt_config_get(ctx, wt.wt_config_find(ctx, 256, 1, 64, 8, 1, 2))
+    note(f"attn full size S={S} cfg={cfg.astuple()}")
+    qb, kb, vb = wt_synth.attn_operands(S, S, H_q, H_kv, 77)
+    dec = lambda b: og.bf16_bits_to_f64(b.reshape(-1, 128)).reshape(b.shape)
+    K64, V64 = dec(kb), dec(vb)
+    rows = [0, 1, 255, 256, 4097, 8191, 12345, 16383]
+    for causal in (0, 1):
+        got = run_attn(ctx, cfg, qb, kb, vb, causal)
+        for i in rows:
+            q1 = dec(qb[i:i + 1])
+            keys = i + 1 if causal else S       # S_q == S_kv: query i sees keys 0..i
+            want = oa.attention(q1, K64[:keys], V64[:keys], SCALE, False)
+            check(got[i:i + 1], want, f"full-size row {i} causal={causal}")
+
+
 def test_argument_errors(ctx):
     cfg, _ = wt.wt_config_get(ctx, 0)
     t = torch.zeros(64 * 4 * 128, dtype=torch.bfloat16, device="cuda")
@@ -108,6 +127,9 @@ def test_argument_errors(ctx):
             wt.wt_attn(ctx, args[0], args[1], args[2], args[3], t, t, t, t, SCALE, 0, cfg)
     with pytest.raises(wt.WtError):   # causal with fewer keys than queries
         wt.wt_attn(ctx, 4, 4, 16, 8, t, t, t, t, SCALE, 1, cfg)
+    for bad_scale in (0.0, -0.5, float("nan"), float("inf")):
+        with pytest.raises(wt.WtError):
+            wt.wt_attn(ctx, 4, 4, 8, 8, t, t, t, t, bad_scale, 0, cfg)
     with pytest.raises(wt.WtError):   # a GEMM call on an attention context
         wt.wt_gemm(ctx, 8, 8, 8, t, t, t, cfg)
     bad = wt.wt_cfg(64, 1, 48, 2, 1, 0, 1, -1)
