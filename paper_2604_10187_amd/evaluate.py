@@ -426,6 +426,9 @@ def cmd_ablate(a, torch=None):
     if "family" not in recs.dtype.names:      # records saved before the family field had its name
         recs = recs.view(wt.SAMPLE_DTYPE)
     W0, I0 = int(recs["w"].max()), a.I
+    attn = a.in_type == wt.WT_ATTN_BF16       # rows hold (S_q, H_q, S_kv); anchors are KV multipliers
+    anchors = tune.KV_MULTIPLIERS if attn else tune.K_ANCHORS
+    shape = (lambda r: (r["S_q"], r["H_q"], r["S_kv"])) if attn else (lambda r: (r["M"], r["N"], r["K"]))
 
     def score(model, W, I, cap_mode, W_row=0, row_fams=0):
         ctx = wt.wt_create(-1, a.in_type, a.out_type)
@@ -444,11 +447,11 @@ def cmd_ablate(a, torch=None):
                 idx = np.minimum(pos * I0 // cap, I0 - 1)            # which of the I0 sub-intervals
                 keep[np.where(m)[0]] = (idx % step) == (step - 1)
             sub = sub[keep]
-        wt.wt_fit(ctx, wt.make_grid(W=W, I=I, p=min(a.p, W), k_anchors=tune.K_ANCHORS, model=model, W_row=W_row,
-                                      row_fams=row_fams), sub)
+        wt.wt_fit(ctx, wt.make_grid(W=W, I=I, p=min(a.p, W), k_anchors=anchors, model=model, W_row=W_row,
+                                      row_fams=row_fams, n_heads=32 if attn else 0), sub)
         fr = []
         for r in rows:
-            c = wt.wt_select(ctx, r["M"], r["N"], r["K"])
+            c = wt.wt_select(ctx, *shape(r))
             t = r["times"].get(str(c.id))
             fr.append(r["best_us"] / t if t else 1.0 / a.prune)
         wt.wt_destroy(ctx)
@@ -463,8 +466,8 @@ def cmd_ablate(a, torch=None):
                                 **score(0, W0, I0, a.cap_mode, Wr, nf)})
     for name, model in (("wave-bilinear (full)", 0), ("linear", 1), ("step", 2)):
         out["variants"].append({"model": name, "W": W0, "I": I0, **score(model, W0, I0, a.cap_mode)})
-    for W in (5, 10, 20, W0):
-        for I in (1, 2, I0):
+    for W in sorted({w for w in (2, 5, 10, 20, W0) if w <= W0}):
+        for I in sorted({i for i in (1, 2, I0) if I0 % i == 0}):
             if (W, I) != (W0, I0):
                 out["variants"].append({"model": "wave-bilinear (full)", "W": W, "I": I, **score(0, W, I, a.cap_mode)})
     for v in out["variants"]:
