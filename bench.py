@@ -51,6 +51,38 @@ def get_table(wt, ctx, in_type, out_type, torch):
     return "reprofiled:W6_I2"
 
 
+def attention_extra(wt, torch):
+    """Outside the timed step: the attention kernel (the second kernel behind the selector) on one large prefill
+    shape, configuration from wt_select on the shipped attention table, timed with HIP events inside the library."""
+    import math
+
+    from paper_2604_10187_amd import tune
+
+    path = tune.table_path(wt.WT_ATTN_BF16, wt.WT_OUT_BF16)
+    if not os.path.exists(path):
+        return None
+    ctx = wt.wt_create(0, wt.WT_ATTN_BF16, wt.WT_OUT_BF16)
+    try:
+        wt.wt_load(ctx, path)
+        S, H_q, H_kv = 8192, 32, 8
+        Q = torch.randn(S * H_q, 128, device="cuda").to(torch.bfloat16)
+        K = torch.randn(S * H_kv, 128, device="cuda").to(torch.bfloat16)
+        V = torch.randn(S * H_kv, 128, device="cuda").to(torch.bfloat16)
+        O = torch.empty_like(Q)
+        pick = wt.wt_select(ctx, S, H_q, S)
+        us = wt.wt_time_attn(ctx, H_q, H_kv, S, S, Q, K, V, O, 1.0 / math.sqrt(128.0), 0, pick, 2, 5,
+                             torch.cuda.current_stream())
+        tf = 4.0 * S * S * 128 * H_q / us / 1e6
+        return {"workload": f"attention S_q=S_kv={S}, {H_q} query / {H_kv} KV heads, head dim 128, bf16, not causal",
+                "config": list(pick.astuple()), "us": round(us, 1), "tflops": round(tf, 1),
+                "frac_of_mfma_peak": round(tf / PEAK_BF16_TFLOPS, 4)}
+    except wt.WtError as e:
+        log(f"[bench] attention extra skipped: {e}")
+        return None
+    finally:
+        wt.wt_destroy(ctx)
+
+
 def cpu_baseline(np, wt_synth):
     """The oracle GEMM as it stands (fp64 triple loop in C, rows spread over OpenMP threads), timed on
     a bounded sample of the sweep: the largest sweep shape's first 2048 rows (185 GFLOP)."""
@@ -172,6 +204,7 @@ def main():
                       "configs_in_grid": wt.wt_config_count(ctx)},
            "roofline": roofline}
     out.update(extra)
+    out["attention"] = attention_extra(wt, torch)
     if not a.no_cpu:
         out["cpu_baseline"] = cpu_baseline(np, wt_synth)
     wt.wt_destroy(ctx)

@@ -119,6 +119,46 @@ def test_full_size_sampled_rows(ctx):
             check(got[i:i + 1], want, f"full-size row {i} causal={causal}")
 
 
+def test_profile_fit_select_round_trip(ctx):
+    """wt_profile_sparse on an attention context: the records are the plan the oracle derives (head-aligned grid
+    sizes, KV multipliers, Eq. 6), every latency is positive, and a table fitted from them selects one of the
+    profiled keys with a finite prediction."""
+    heads, W, I, mult = 16, 2, 3, (100, 200, 300)
+    first, count = 2, 2
+    grid = wt.make_grid(W=W, I=I, k_anchors=mult, warmup=1, iters=1, key_first=first, key_count=count, n_heads=heads)
+    n, bQ, bKV, bO = wt.wt_sample_plan(ctx, grid)
+    note(f"attn profile: {n} records, Q {bQ >> 20} MiB, KV {bKV >> 20} MiB")
+    scrQ = torch.randn(bQ // 2, device="cuda").to(torch.bfloat16)
+    scrKV = torch.randn(bKV // 2, device="cuda").to(torch.bfloat16)
+    scrO = torch.empty(bO // 2, dtype=torch.bfloat16, device="cuda")
+    recs = wt.wt_profile_sparse(ctx, grid, scrQ, scrKV, scrO, stream=torch.cuda.current_stream())
+    want = []
+    for k in range(first, first + count):
+        cfg, res = wt.wt_config_get(ctx, 3 * k)
+        for s in oa.sample_set_heads(256, W, I, heads):
+            if s.g == 0:
+                continue
+            S_q, _ = oa.instantiate_attn(s.g, 1, heads, cfg.bm, cfg.bk)
+            for L in oa.kv_loop_counts(S_q, cfg.bk, mult):
+                want += [(k, m, s.g, L, s.w) for m in range(3)]
+    assert len(recs) == n == len(want)
+    assert [(int(r["key_id"]), int(r["micro_id"]), int(r["G"]), int(r["L"]), int(r["w"])) for r in recs] == want
+    assert (recs["mean_us"] > 0).all() and np.isfinite(recs["mean_us"]).all()
+    # more work takes longer: within a key and micro, the largest (G, L) is slower than the smallest
+    r0 = recs[(recs["key_id"] == first) & (recs["micro_id"] == 0)]
+    assert r0["mean_us"][np.argmax(r0["G"] * r0["L"])] > r0["mean_us"][np.argmin(r0["G"] * r0["L"])]
+    c2 = wt.wt_create(-1, wt.WT_ATTN_BF16, wt.WT_OUT_BF16)
+    try:
+        wt.wt_fit(c2, grid, recs)
+        for (S_q, S_kv, H) in ((512, 512, 16), (4096, 8192, 32), (100, 100, 64)):
+            pick = wt.wt_select(c2, S_q, H, S_kv)
+            _, res = wt.wt_config_get(c2, pick.id)
+            assert first <= res.key_id < first + count
+            assert np.isfinite(wt.wt_predict_us(c2, S_q, H, S_kv, pick))
+    finally:
+        wt.wt_destroy(c2)
+
+
 def test_argument_errors(ctx):
     cfg, _ = wt.wt_config_get(ctx, 0)
     t = torch.zeros(64 * 4 * 128, dtype=torch.bfloat16, device="cuda")
