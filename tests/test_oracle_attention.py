@@ -7,6 +7,7 @@ import numpy as np
 import pytest
 import torch
 
+from _pins import load_pins
 from oracle import attention as att
 from oracle.sampler import sub_interval
 
@@ -110,12 +111,15 @@ def test_representative_heads_is_the_largest_multiple_in_the_interval(n_heads):
 
 
 def test_grid_point_counts_match_the_paper_s_range():
-    # Sec. 5.1: I = 3 and W from 20 to 35 give 60 to 105 grid points per KV-length anchor
-    for W, n_heads in ((20, 16), (35, 128)):
-        pts = att.sample_set_heads(256 * 2, W, 3, n_heads)  # capacity 512: every third holds a multiple of 128
-        assert len(pts) == 3 * W and all(p.g > 0 for p in pts)
-    assert sum(p.g > 0 for p in att.sample_set_heads(256, 20, 3, 16)) == 60
-    assert sum(p.g > 0 for p in att.sample_set_heads(256, 35, 3, 64)) == 105
+    # Sec. 5.1 (values in tests/golden/paper_pins.txt): I = 3 and W from 20 to 35 give 60 to 105 grid points per
+    # KV-length anchor -- the sampler must produce exactly that many when every sub-interval holds a head multiple
+    P = load_pins()
+    I, W_lo, W_hi = P["attn_I"], P["attn_W_lo"], P["attn_W_hi"]
+    for W, n_heads in ((W_lo, 16), (W_hi, 128)):
+        pts = att.sample_set_heads(256 * 2, W, I, n_heads)  # capacity 512: every third holds a multiple of 128
+        assert len(pts) == I * W and all(p.g > 0 for p in pts)
+    assert sum(p.g > 0 for p in att.sample_set_heads(256, W_lo, I, 16)) == P["attn_points_lo"]
+    assert sum(p.g > 0 for p in att.sample_set_heads(256, W_hi, I, 64)) == P["attn_points_hi"]
 
 
 def test_sample_set_heads_layout_and_alignment():
