@@ -282,19 +282,21 @@ int wt_create(wt_ctx** out, int device, int in_type, int out_type) {
         if (e != hipSuccess) { delete ctx; return WT_ERR_HIP; }
         ctx->ev_start = e0; ctx->ev_stop = e1;
         // split-K workspace: partial tiles, then the arrival counters (zero now; every launch leaves them zero)
-        void* ws = nullptr;
-        const size_t ws_bytes = (size_t)kWsElems * sizeof(float), cnt_bytes = (size_t)kMaxSplitTiles * sizeof(int);
-        e = hipMalloc(&ws, ws_bytes + cnt_bytes);
-        if (e == hipSuccess) e = hipMemset((char*)ws + ws_bytes, 0, cnt_bytes);
-        if (e == hipSuccess) e = hipDeviceSynchronize();
-        if (e != hipSuccess) {
-            if (ws) (void)hipFree(ws);
-            (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
-            delete ctx;
-            return WT_ERR_HIP;
+        if (in_type != WT_ATTN_BF16) {  // attention kernels use no workspace
+            void* ws = nullptr;
+            const size_t ws_bytes = (size_t)kWsElems * sizeof(float), cnt_bytes = (size_t)kMaxSplitTiles * sizeof(int);
+            e = hipMalloc(&ws, ws_bytes + cnt_bytes);
+            if (e == hipSuccess) e = hipMemset((char*)ws + ws_bytes, 0, cnt_bytes);
+            if (e == hipSuccess) e = hipDeviceSynchronize();
+            if (e != hipSuccess) {
+                if (ws) (void)hipFree(ws);
+                (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+                delete ctx;
+                return WT_ERR_HIP;
+            }
+            ctx->ws = (float*)ws;
+            ctx->counters = (int*)((char*)ws + ws_bytes);
         }
-        ctx->ws = (float*)ws;
-        ctx->counters = (int*)((char*)ws + ws_bytes);
         // per-key resources from the runtime: LDS opt-in, register count, resident blocks per CU
         for (size_t k = 0; k < ctx->keys.size(); ++k) {
             Key& key = ctx->keys[k];

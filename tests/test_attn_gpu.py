@@ -119,6 +119,50 @@ def test_full_size_sampled_rows(ctx):
             check(got[i:i + 1], want, f"full-size row {i} causal={causal}")
 
 
+def test_many_heads_and_decode_like_shapes(ctx):
+    """128 query heads on 2 KV heads (the widest grouping of the test ranges), a single query against 20 000 keys
+    (one block per head, 157-313 KV tiles, ragged tail), and a causal single query (sees every key)."""
+    cfg_a, _ = wt.wt_config_get(ctx, wt.wt_config_find(ctx, 128, 1, 128, 4, 1, 1))
+    cfg_b, _ = wt.wt_config_get(ctx, wt.wt_config_find(ctx, 64, 1, 64, 2, 1, 2))
+    for cfg, (S_q, S_kv, H_q, H_kv), causal in ((cfg_a, (70, 300, 128, 2), 0), (cfg_b, (1, 20000, 8, 4), 0),
+                                                 (cfg_a, (1, 20000, 8, 4), 1), (cfg_b, (33, 5000, 16, 16), 1)):
+        note(f"attn cfg={cfg.astuple()} S_q={S_q} S_kv={S_kv} H={H_q}/{H_kv} causal={causal}")
+        qb, kb, vb = wt_synth.attn_operands(S_q, S_kv, H_q, H_kv, 7000 + S_q + H_q)
+        check(run_attn(ctx, cfg, qb, kb, vb, causal), reference(qb, kb, vb, bool(causal)), f"{S_q}x{S_kv} H={H_q}/{H_kv}")
+
+
+def test_hip_graph_replay(ctx):
+    """wt_attn neither allocates nor synchronises: a captured launch replays bit-identically, with eager launches
+    and synchronisations between the replays."""
+    cfg, _ = wt.wt_config_get(ctx, wt.wt_config_find(ctx, 256, 1, 64, 8, 1, 2))
+    S_q, S_kv, H_q, H_kv = 700, 1500, 8, 2
+    qb, kb, vb = wt_synth.attn_operands(S_q, S_kv, H_q, H_kv, 4242)
+    dQ, dK, dV = (dev_bits(x.reshape(-1, 128)).view(torch.bfloat16) for x in (qb, kb, vb))
+    eager = torch.empty((S_q * H_q, 128), dtype=torch.bfloat16, device="cuda")
+    out = torch.zeros_like(eager)
+    wt.wt_attn(ctx, H_q, H_kv, S_q, S_kv, dQ, dK, dV, eager, SCALE, 1, cfg, stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    check(eager.float().cpu().numpy().reshape(S_q, H_q, 128), reference(qb, kb, vb, True), "eager")
+    cur = torch.cuda.current_stream()
+    side = torch.cuda.Stream()
+    side.wait_stream(cur)
+    with torch.cuda.stream(side):       # warm-up on a side stream, as torch asks before a capture
+        wt.wt_attn(ctx, H_q, H_kv, S_q, S_kv, dQ, dK, dV, out, SCALE, 1, cfg, stream=side)
+    cur.wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        wt.wt_attn(ctx, H_q, H_kv, S_q, S_kv, dQ, dK, dV, out, SCALE, 1, cfg, stream=torch.cuda.current_stream())
+    for rep in range(3):
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), f"replay {rep} differs from the eager launch"
+        wt.wt_attn(ctx, H_q, H_kv, S_q, S_kv, dQ, dK, dV, eager, SCALE, 1, cfg, stream=torch.cuda.current_stream())
+        torch.cuda.synchronize()
+
+
 def test_profile_fit_select_round_trip(ctx):
     """wt_profile_sparse on an attention context: the records are the plan the oracle derives (head-aligned grid
     sizes, KV multipliers, Eq. 6), every latency is positive, and a table fitted from them selects one of the
