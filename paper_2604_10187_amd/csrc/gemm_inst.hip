@@ -27,16 +27,21 @@
 
 namespace wt {
 
-#define WT_CFGK(BM, BN, BK, WM, WN, WK, ST)                                                      \
-    {BM, BN, BK, WM, WN, WK, ST, GemmTraits<BM, BN, BK, WM, WN, ST, WT_IN, WT_OUT, WK>::LDS_BYTES, \
-     reinterpret_cast<const void*>(&gemm_kernel<BM, BN, BK, WM, WN, ST, WT_IN, WT_OUT, WK>),       \
-     reinterpret_cast<const void*>(&gemm_kernel_persistent<BM, BN, BK, WM, WN, ST, WT_IN, WT_OUT, WK>)},
-#define WT_CFG(BM, BN, BK, WM, WN, ST) WT_CFGK(BM, BN, BK, WM, WN, 1, ST)
+#define WT_CFGX(BM, BN, BK, WM, WN, WK, ST, MIF)                                                       \
+    {BM, BN, BK, WM, WN, WK, ST, GemmTraits<BM, BN, BK, WM, WN, ST, WT_IN, WT_OUT, WK, MIF>::LDS_BYTES,  \
+     reinterpret_cast<const void*>(&gemm_kernel<BM, BN, BK, WM, WN, ST, WT_IN, WT_OUT, WK, MIF>),        \
+     reinterpret_cast<const void*>(&gemm_kernel_persistent<BM, BN, BK, WM, WN, ST, WT_IN, WT_OUT, WK, MIF>)},
+#define WT_CFGK(BM, BN, BK, WM, WN, WK, ST) WT_CFGX(BM, BN, BK, WM, WN, WK, ST, 0)
+#define WT_CFG(BM, BN, BK, WM, WN, ST) WT_CFGX(BM, BN, BK, WM, WN, 1, ST, 0)
+// the same key computed with 16x16 MFMA tiles although its sub-tile would allow 32x32
+#define WT_CFG16(BM, BN, BK, WM, WN, ST) WT_CFGX(BM, BN, BK, WM, WN, 1, ST, 16)
 static const KernelEntry kEntries[] = {
 #include "configs.def"
 };
 #undef WT_CFG
+#undef WT_CFG16
 #undef WT_CFGK
+#undef WT_CFGX
 
 const KernelEntry* WT_FN_NAME(int* n) {
     *n = static_cast<int>(sizeof(kEntries) / sizeof(kEntries[0]));

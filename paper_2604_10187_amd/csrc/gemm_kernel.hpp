@@ -150,7 +150,7 @@ struct InTraits<1> {  // fp8 e4m3
     static constexpr int epc = 16;
 };
 
-template <int BM, int BN, int BK, int WM, int WN, int ST, int IN, int OUT, int WK = 1>
+template <int BM, int BN, int BK, int WM, int WN, int ST, int IN, int OUT, int WK = 1, int MIF = 0>
 struct GemmTraits {
     static constexpr int NW = WM * WN * WK;  // WK wavefronts share a sub-tile and divide each k-tile's k-steps
     static constexpr int NT = NW * kWave;
@@ -160,7 +160,10 @@ struct GemmTraits {
     static constexpr int CPR = RB / 16;          // 16-byte chunks per row
     static constexpr int TM = BM / WM;           // wavefront sub-tile
     static constexpr int TN = BN / WN;
-    static constexpr int MI = (TM % 32 == 0 && TN % 32 == 0) ? 32 : 16;
+    // MFMA tile side: 32 when the sub-tile allows it, unless the configuration asks for 16 (MIF = 16): for some
+    // kernels, notably 256x256x64 on 8 wavefronts, twice as many half-length MFMAs schedule measurably better
+    static constexpr int MI = MIF ? MIF : ((TM % 32 == 0 && TN % 32 == 0) ? 32 : 16);
+    static_assert(MIF == 0 || MIF == 16, "MFMA tile side override");
     // k extent of one MFMA: bf16 32x32x16 / 16x16x32; fp8 32x32x64 / 16x16x128
     static constexpr int KS = (IN == 0) ? (MI == 32 ? 16 : 32) : (MI == 32 ? 64 : 128);
     static constexpr int CPK = KS * esize / 16;  // chunks one MFMA consumes along k per row
@@ -218,9 +221,9 @@ struct AccType<16> {
 };
 
 // One task of the launch: task `block_id` of the task list (a tile, or one split of a tile).
-template <int BM, int BN, int BK, int WM, int WN, int ST, int IN, int OUT, int WK>
+template <int BM, int BN, int BK, int WM, int WN, int ST, int IN, int OUT, int WK, int MIF = 0>
 __device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_id) {
-    using T = GemmTraits<BM, BN, BK, WM, WN, ST, IN, OUT, WK>;
+    using T = GemmTraits<BM, BN, BK, WM, WN, ST, IN, OUT, WK, MIF>;
     using acc_t = typename AccType<T::MI>::type;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
@@ -636,19 +639,19 @@ __device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_
 }
 
 // One block per task.
-template <int BM, int BN, int BK, int WM, int WN, int ST, int IN, int OUT, int WK = 1>
+template <int BM, int BN, int BK, int WM, int WN, int ST, int IN, int OUT, int WK = 1, int MIF = 0>
 __global__ __launch_bounds__(WM* WN* WK* kWave) void gemm_kernel(const GemmArgs args) {
-    gemm_task<BM, BN, BK, WM, WN, ST, IN, OUT, WK>(args, blockIdx.x);
+    gemm_task<BM, BN, BK, WM, WN, ST, IN, OUT, WK, MIF>(args, blockIdx.x);
 }
 
 // Persistent launch (Sec. 3.2, note on persistent kernels): the host starts only as many blocks as can be
 // resident at once and block b runs the tasks b, b + gridDim.x, ... of the same task list, so G stays the
 // logical task count while the physical grid is clamped.  Kept as a kernel of its own: wrapping the task in
 // a loop costs the one-block-per-task path 1-5 % (registers that stay live across tasks).
-template <int BM, int BN, int BK, int WM, int WN, int ST, int IN, int OUT, int WK = 1>
+template <int BM, int BN, int BK, int WM, int WN, int ST, int IN, int OUT, int WK = 1, int MIF = 0>
 __global__ __launch_bounds__(WM* WN* WK* kWave) void gemm_kernel_persistent(const GemmArgs args) {
     for (int b = blockIdx.x; b < args.vgrid; b += gridDim.x) {
-        gemm_task<BM, BN, BK, WM, WN, ST, IN, OUT, WK>(args, b);
+        gemm_task<BM, BN, BK, WM, WN, ST, IN, OUT, WK, MIF>(args, b);
         if (b + static_cast<int>(gridDim.x) < args.vgrid) __syncthreads();  // LDS is reused by the next task
     }
 }
