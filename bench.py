@@ -27,7 +27,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM-side bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled
 # by the copy-kernel calibration (x2.0 / x1.0): profiles/gemm_traffic_pmc.md.  Keyed by (kernel, shape);
 # reported as null when the run picks another kernel than the profiled one.
-TRAFFIC_BYTES = {((256, 256, 64, 8, 2, 2, 1), (4096, 11008, 4096)): 719.2e6}
+TRAFFIC_BYTES = {((256, 256, 64, 8, 2, 2, 1), (4096, 11008, 4096)): 725.5e6}
 
 
 def log(*a):
