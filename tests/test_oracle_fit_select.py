@@ -397,3 +397,28 @@ def test_thin_anchors_keeps_ends_and_an_even_spread():
     a8 = [(L, 1) for L in range(8)]
     assert ofit.thin_anchors(a8) == a8 and ofit.thin_anchors(a8[:3]) == a8[:3]
     assert ofit.thin_anchors(a15, 2) == [a15[0], a15[-1]]
+
+
+def test_select_attn_hand_worked_two_keys():
+    """Two attention keys <T_Q, T_KV> = <64, 32> and <256, 64> with hand-set planes: S_q = 300, S_kv = 1000, 8 heads.
+    Key 0: G = 8*ceil(300/64) = 40, L = ceil(1000/32) = 32 -> T = 0.01*40*32 + 1 = 13.8.
+    Key 1: G = 8*ceil(300/256) = 16, L = ceil(1000/64) = 16 -> T = 0.05*16*16 + 2 = 14.8.  Key 0 wins; its anchors
+    (L = 10 -> micro 2, L = 40 -> micro 0): 32 is nearer to 40.  At S_kv = 4000 (L = 125 / 63) key 1 wins:
+    0.01*40*125 + 1 = 51 against 0.05*16*63 + 2 = 52.4 -> still key 0; at 64 heads and w > W the ext tuples decide."""
+    keys = [ofit.KeyDesc(64, 1, 32, 2, 1, 1, 256), ofit.KeyDesc(256, 1, 64, 8, 1, 1, 256)]
+    b0 = ofit.Bucket(theta=(0.01, 0.0, 0.0, 1.0), status=15, anchors=[(10, 2), (40, 0)])
+    b1 = ofit.Bucket(theta=(0.05, 0.0, 0.0, 2.0), status=15, anchors=[(16, 1)])
+    e0 = ofit.Bucket(theta=(0.02, 0.0, 0.0, 0.0), status=15, anchors=[(10, 1)])
+    e1 = ofit.Bucket(theta=(0.01, 0.0, 0.0, 0.0), status=15, anchors=[(16, 2)])
+    table = ofit.DualTable(W=1, keys=keys, local=[[b0], [b1]], ext=[e0, e1])
+    k, micro, t = osel.select_attn(table, 8, 300, 1000)
+    assert (k, micro) == (0, 0) and t == pytest.approx(13.8)
+    k, micro, t = osel.select_attn(table, 8, 300, 4000)
+    assert (k, micro) == (0, 0) and t == pytest.approx(51.0)
+    # 64 heads, S_q = 1024: key 0 has G = 1024 (w = 4 > W), key 1 has G = 256 (w = 1, local bucket)
+    # key 0 ext: 0.02*1024*32 = 655.36; key 1 local: 0.05*256*16 + 2 = 206.8 -> key 1, micro of its only anchor
+    k, micro, t = osel.select_attn(table, 64, 1024, 1024)
+    assert (k, micro) == (1, 1) and t == pytest.approx(206.8)
+    # 128 heads: both beyond W -> ext tuples: key 0: 0.02*2048*32 = 1310.72; key 1: 0.01*512*16 = 81.92
+    k, micro, t = osel.select_attn(table, 128, 1024, 1024)
+    assert (k, micro) == (1, 2) and t == pytest.approx(81.92)
