@@ -198,7 +198,9 @@ int wt_select_grouped(const wt_ctx* ctx, int32_t groups, int64_t M_total, int64_
  * A configuration is <bm, bn, bk, nwave, stages, swizzle, split> = <T_Q, 1, T_KV, wavefronts, 1, order, 1>: a block
  * owns T_Q query rows of one head and loops over the KV tiles; `order` is the micro parameter (0: the query tiles
  * of a head are consecutive blocks; 1: the heads of a query tile are consecutive blocks; 2: as 0, with every one
- * of the 8 XCDs given a contiguous range so that a head's K/V stay in one L2).  Scores and softmax are fp32, the
+ * of the 8 XCDs given a contiguous range so that a head's K/V stay in one L2).  Causal launches ignore `order`:
+ * their blocks differ in length, so they are always started longest first with the heads of a query tile
+ * consecutive (order 1 on the reversed query-tile index).  Scores and softmax are fp32, the
  * probabilities are rounded to bf16 before they multiply V.  Asynchronous on hip_stream, never allocates or
  * synchronises.  The persistent launch policy does not apply. */
 int wt_attn(wt_ctx* ctx, int64_t n_heads, int64_t n_kv_heads, int64_t S_q, int64_t S_kv, const void* Q,

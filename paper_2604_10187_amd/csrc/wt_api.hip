@@ -64,7 +64,10 @@ int launch_attn(wt_ctx* ctx, const Config& c, const Problem& p, hipStream_t stre
     a.V = static_cast<const __bf16*>(p.V); a.O = static_cast<__bf16*>(p.C);
     a.S_q = (int)p.M; a.S_kv = (int)p.K; a.H_q = (int)p.N; a.H_kv = (int)p.H_kv;
     a.q_tiles = (int)q_tiles;
-    a.order = c.cfg.swizzle;
+    // Causal launches: blocks differ in length, and starting every head's longest query tiles first (order 1 on
+    // the reversed tile index) balances the tail; measured best or within 0.5 % of best on every test shape, so
+    // the order cached from unmasked profiling is not consulted.
+    a.order = p.causal ? 1 : c.cfg.swizzle;
     a.causal = p.causal;
     a.scale_log2 = p.scale * 1.4426950408889634f;
     void* params[] = {&a};
