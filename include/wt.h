@@ -254,6 +254,7 @@ int wt_time_gemm(wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, co
 /* Diagnostic: sustained MFMA-only throughput of the device (register operands of magnitude ~1,
  * no memory traffic; 2 blocks of 4 wavefronts per compute unit, iters x 16 MFMAs each).  This is
  * the power- and clock-limited ceiling of a dense contraction, reported beside the nominal peak.
+ * For bf16 the loop is run with 32x32x16 and with 16x16x32 MFMAs (same flop count) and the higher rate is returned.
  * sink_dev: device pointer to one float (never written in practice).  Synchronises the stream. */
 int wt_mfma_ceiling(wt_ctx* ctx, int in_type, int iters, void* hip_stream, float* sink_dev,
                     double* tflops);

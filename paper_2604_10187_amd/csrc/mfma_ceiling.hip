@@ -16,9 +16,47 @@ __device__ __forceinline__ uint32_t mix(uint32_t x) {
     return x;
 }
 
+// IN = 0: bf16 on 32x32x16; IN = 1: fp8 on 32x32x64; IN = 2: bf16 on 16x16x32 (two MFMAs per accumulator tile and
+// iteration, so that every variant does the same flop count per iteration on the same number of operand registers).
 template <int IN>
 __global__ __launch_bounds__(256) void mfma_ceiling_kernel(int iters, float* sink) {
     const uint32_t seed = mix(threadIdx.x + 977u * blockIdx.x);
+    if constexpr (IN == 2) {
+        f32x4 acc4[4][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc4[i][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        bf16x8 a[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            union { uint32_t u[4]; bf16x8 v; } ua, ub;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                ua.u[q] = (mix(seed + 11u * i + q) & 0x80FF80FFu) | 0x3F003F00u;
+                ub.u[q] = (mix(seed + 101u * i + q + 7u) & 0x80FF80FFu) | 0x3F003F00u;
+            }
+            a[i] = ua.v; b[i] = ub.v;
+        }
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int r = 0; r < 2; ++r)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        acc4[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[j], acc4[i][j], 0, 0, 0);
+        }
+        float s4 = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) s4 += acc4[i][j][e];
+        if (s4 == 12345.678f) sink[0] = s4;
+        return;
+    }
     f32x16 acc[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -86,24 +124,33 @@ extern "C" int wt_mfma_ceiling(wt_ctx* ctx, int in_type, int iters, void* hip_st
     hipStream_t stream = (hipStream_t)hip_stream;
     hipEvent_t e0 = (hipEvent_t)ctx->ev_start, e1 = (hipEvent_t)ctx->ev_stop;
     const int blocks = kNumCU * 2;  // two 4-wavefront blocks per compute unit
-    hipError_t e = hipSuccess;
-    for (int rep = 0; rep < 2 && e == hipSuccess; ++rep) {  // first pass warms up
-        e = hipEventRecord(e0, stream);
-        if (e != hipSuccess) break;
-        if (in_type == WT_BF16)
-            hipLaunchKernelGGL(mfma_ceiling_kernel<0>, dim3(blocks), dim3(256), 0, stream, iters, sink_dev);
-        else
-            hipLaunchKernelGGL(mfma_ceiling_kernel<1>, dim3(blocks), dim3(256), 0, stream, iters, sink_dev);
-        e = hipGetLastError();
-        if (e == hipSuccess) e = hipEventRecord(e1, stream);
-        if (e == hipSuccess) e = hipEventSynchronize(e1);
+    // bf16 is measured with both MFMA shapes the GEMM kernels use (32x32x16, then 16x16x32) and the higher rate is
+    // reported: under the power limit the two do not sustain the same clock.
+    float best_ms = 0;
+    for (int variant = 0; variant < (in_type == WT_BF16 ? 2 : 1); ++variant) {
+        hipError_t e = hipSuccess;
+        for (int rep = 0; rep < 2 && e == hipSuccess; ++rep) {  // first pass warms up
+            e = hipEventRecord(e0, stream);
+            if (e != hipSuccess) break;
+            if (in_type != WT_BF16)
+                hipLaunchKernelGGL(mfma_ceiling_kernel<1>, dim3(blocks), dim3(256), 0, stream, iters, sink_dev);
+            else if (variant == 0)
+                hipLaunchKernelGGL(mfma_ceiling_kernel<0>, dim3(blocks), dim3(256), 0, stream, iters, sink_dev);
+            else
+                hipLaunchKernelGGL(mfma_ceiling_kernel<2>, dim3(blocks), dim3(256), 0, stream, iters, sink_dev);
+            e = hipGetLastError();
+            if (e == hipSuccess) e = hipEventRecord(e1, stream);
+            if (e == hipSuccess) e = hipEventSynchronize(e1);
+        }
+        float ms = 0;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+        if (e != hipSuccess) { ctx->last_hip = (int)e; return WT_ERR_HIP; }
+        if (variant == 0 || ms < best_ms) best_ms = ms;
     }
-    float ms = 0;
-    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
-    if (e != hipSuccess) { ctx->last_hip = (int)e; return WT_ERR_HIP; }
-    // flops per MFMA: bf16 32x32x16 = 2*32*32*16 = 32768; fp8 32x32x64 = 2*32*32*64 = 131072
+    // flops per iteration and accumulator tile: bf16 2*32*32*16 = 32768 (one 32x32x16 or two 16x16x32);
+    // fp8 32x32x64 = 2*32*32*64 = 131072
     const double per_mfma = in_type == WT_BF16 ? 32768.0 : 131072.0;
     const double flops = (double)blocks * 4.0 * (double)iters * 16.0 * per_mfma;
-    *tflops = flops / ((double)ms * 1e-3) / 1e12;
+    *tflops = flops / ((double)best_ms * 1e-3) / 1e12;
     return WT_OK;
 }
