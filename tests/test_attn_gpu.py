@@ -119,6 +119,29 @@ def test_full_size_sampled_rows(ctx):
             check(got[i:i + 1], want, f"full-size row {i} causal={causal}")
 
 
+def test_bench_shape_under_the_selected_config(ctx):
+    """The shape bench.py reports (8192 x 8192, 32 query / 8 KV heads) under the configuration wt_select returns from
+    the shipped attention table: sampled query rows against the oracle."""
+    import os
+
+    S, H_q, H_kv = 8192, 32, 8
+    sel = wt.wt_create(-1, wt.WT_ATTN_BF16, wt.WT_OUT_BF16)
+    try:
+        wt.wt_load(sel, os.path.join(os.path.dirname(wt.LIB_PATH), "tables", "mi355x_attn.wt"))
+        pick = wt.wt_select(sel, S, H_q, S)
+    finally:
+        wt.wt_destroy(sel)
+    cfg, _ = wt.wt_config_get(ctx, wt.wt_config_find(ctx, pick.bm, 1, pick.bk, pick.nwave, 1, pick.swizzle))
+    note(f"attn bench shape S={S} H={H_q}/{H_kv} cfg={cfg.astuple()}")
+    qb, kb, vb = wt_synth.attn_operands(S, S, H_q, H_kv, 78)
+    dec = lambda b: og.bf16_bits_to_f64(b.reshape(-1, 128)).reshape(b.shape)
+    K64, V64 = dec(kb), dec(vb)
+    got = run_attn(ctx, cfg, qb, kb, vb, 0)
+    for i in (0, 255, 256, 4095, 8191):
+        want = oa.attention(dec(qb[i:i + 1]), K64, V64, SCALE, False)
+        check(got[i:i + 1], want, f"bench-shape row {i}")
+
+
 def test_many_heads_and_decode_like_shapes(ctx):
     """128 query heads on 2 KV heads (the widest grouping of the test ranges), a single query against 20 000 keys
     (one block per head, 157-313 KV tiles, ragged tail), and a causal single query (sees every key)."""
