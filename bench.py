@@ -95,8 +95,22 @@ def cpu_baseline(np, wt_synth):
     t0 = time.perf_counter()
     og.gemm_c(ab, bb)
     dt = time.perf_counter() - t0
-    return {"value": round(2.0 * M * N * K / dt / 1e12, 5), "unit": "TFLOP/s", "cores": og.c_threads(), "kind": "oracle",
-            "sample": f"rows 0..{M - 1} of the 4096x11008x4096 sweep shape (fp64 triple loop, {dt:.1f} s)"}
+    out = {"value": round(2.0 * M * N * K / dt / 1e12, 5), "unit": "TFLOP/s", "cores": og.c_threads(), "kind": "oracle",
+           "sample": f"rows 0..{M - 1} of the 4096x11008x4096 sweep shape (fp64 triple loop, {dt:.1f} s)"}
+    # the oracle's selector (plain Python over the same table file) on a sample of the 10,000-shape stream
+    try:
+        from oracle import select as osel
+        from paper_2604_10187_amd import tune
+
+        table, _ = osel.read_table(tune.table_path(0, 1))
+        shapes = wt_synth.stream_shapes(300)
+        t0 = time.perf_counter()
+        for (m, n, k) in shapes:
+            osel.select(table, m, n, k)
+        out["select_us_oracle"] = round((time.perf_counter() - t0) / len(shapes) * 1e6, 1)
+    except Exception as e:      # a reported baseline only: never fail the bench line over it
+        log(f"[bench] oracle selector timing skipped: {e}")
+    return out
 
 
 def main():
