@@ -127,30 +127,59 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
     // ---- staging registers for one K tile and one V tile ----------------------------------------------------
     au32x4 kreg[T::KC];
     au32x4 vreg[T::VU][4];
+    // Per-thread element offsets of its K chunks and V units inside a tile are loop-invariant; a tile adds a uniform
+    // stride.  Tiles that lie wholly inside S_kv (all but possibly the last) are loaded without per-row predicates.
+    const int64_t tile_stride = static_cast<int64_t>(TKV) * a.H_kv * kHeadDim;
+    int64_t k_off[T::KC], v_off[T::VU];
+#pragma unroll
+    for (int i = 0; i < T::KC; ++i) {
+        const int c = tid + i * T::NT;
+        k_off[i] = (static_cast<int64_t>(c >> 4) * a.H_kv + kh) * kHeadDim + (c & 15) * 8;
+    }
+#pragma unroll
+    for (int i = 0; i < T::VU; ++i) {
+        const int u = tid + i * T::NT;
+        v_off[i] = (static_cast<int64_t>(4 * (u % T::QN)) * a.H_kv + kh) * kHeadDim + (u / T::QN) * 8;
+    }
+    const int64_t v_row = static_cast<int64_t>(a.H_kv) * kHeadDim;  // elements between consecutive keys
     auto load_k = [&](int t) {
         const int kv0 = t * TKV;
+        const __bf16* base = a.K + t * tile_stride;
+        if (kv0 + TKV <= a.S_kv) {
+#pragma unroll
+            for (int i = 0; i < T::KC; ++i)
+                if (tid + i * T::NT < T::K_TOTAL) kreg[i] = *reinterpret_cast<const au32x4*>(base + k_off[i]);
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < T::KC; ++i) {
             const int c = tid + i * T::NT;
-            const int kv = kv0 + (c >> 4);
             au32x4 v = {0u, 0u, 0u, 0u};
-            if (c < T::K_TOTAL && kv < a.S_kv)
-                v = *reinterpret_cast<const au32x4*>(a.K + (static_cast<int64_t>(kv) * a.H_kv + kh) * kHeadDim + (c & 15) * 8);
+            if (c < T::K_TOTAL && kv0 + (c >> 4) < a.S_kv) v = *reinterpret_cast<const au32x4*>(base + k_off[i]);
             kreg[i] = v;
         }
     };
     auto load_v = [&](int t) {
         const int kv0 = t * TKV;
+        const __bf16* base = a.V + t * tile_stride;
+        if (kv0 + TKV <= a.S_kv) {
+#pragma unroll
+            for (int i = 0; i < T::VU; ++i)
+                if (tid + i * T::NT < T::V_TOTAL) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) vreg[i][r] = *reinterpret_cast<const au32x4*>(base + v_off[i] + r * v_row);
+                }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < T::VU; ++i) {
             const int u = tid + i * T::NT;
-            const int quad = u % T::QN, dc = u / T::QN;
+            const int quad = u % T::QN;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int kv = kv0 + 4 * quad + r;
                 au32x4 v = {0u, 0u, 0u, 0u};
-                if (u < T::V_TOTAL && kv < a.S_kv)
-                    v = *reinterpret_cast<const au32x4*>(a.V + (static_cast<int64_t>(kv) * a.H_kv + kh) * kHeadDim + dc * 8);
+                if (u < T::V_TOTAL && kv0 + 4 * quad + r < a.S_kv)
+                    v = *reinterpret_cast<const au32x4*>(base + v_off[i] + r * v_row);
                 vreg[i][r] = v;
             }
         }
