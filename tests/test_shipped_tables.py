@@ -1,0 +1,56 @@
+"""The dual tables shipped with the package match the compiled registry, their profiling records are consistent
+with them, and the GEMM tables select exactly like the oracle's selector on the same file (no GPU)."""
+import os
+
+import numpy as np
+import pytest
+
+import paper_2604_10187_amd as wt
+import wt_synth
+from oracle import fit as ofit
+from oracle import select as osel
+
+TABLES = os.path.join(os.path.dirname(wt.LIB_PATH), "tables")
+CASES = [(wt.WT_BF16, "mi355x_in0_out1"), (wt.WT_FP8_E4M3, "mi355x_in1_out1"), (wt.WT_ATTN_BF16, "mi355x_attn")]
+
+
+@pytest.mark.parametrize("in_type,stem", CASES)
+def test_table_loads_into_the_registry_and_records_match(in_type, stem):
+    ctx = wt.wt_create(-1, in_type, wt.WT_OUT_BF16)
+    try:
+        wt.wt_load(ctx, os.path.join(TABLES, stem + ".wt"))       # refuses a table whose keys differ from the registry
+        nk = wt.wt_key_count(ctx)
+        table, _ = osel.read_table(os.path.join(TABLES, stem + ".wt"))
+        assert len(table.keys) == nk
+        for k, kd in enumerate(table.keys):
+            c, _ = wt.wt_config_get(ctx, 3 * k)
+            assert (kd.bm, kd.bn, kd.bk, kd.nwave, kd.stages, kd.split) == (c.bm, c.bn, c.bk, c.nwave, c.stages, c.split)
+        z = np.load(os.path.join(TABLES, stem + "_samples.npz"))
+        recs, occ = z["samples"], z["occ"]
+        assert len(occ) == nk and int(recs["key_id"].max()) < nk and int(recs["key_id"].min()) == 0
+        assert (recs["mean_us"] > 0).all() and (recs["micro_id"] < 3).all() and (recs["w"] >= 1).all()
+        # every key has records of the paper's sampler (family 0)
+        f0 = recs[recs["family"] == 0]
+        assert set(int(k) for k in np.unique(f0["key_id"])) == set(range(nk))
+    finally:
+        wt.wt_destroy(ctx)
+
+
+@pytest.mark.parametrize("in_type,stem", CASES[:2])
+def test_shipped_gemm_tables_select_like_the_oracle(in_type, stem):
+    ctx = wt.wt_create(-1, in_type, wt.WT_OUT_BF16)
+    try:
+        path = os.path.join(TABLES, stem + ".wt")
+        wt.wt_load(ctx, path)
+        table, _ = osel.read_table(path)
+        for (M, N, K) in wt_synth.sweep_shapes() + wt_synth.stream_shapes(400):
+            if in_type == wt.WT_FP8_E4M3 and K % 16:
+                continue
+            key, micro, t = osel.select(table, M, N, K)
+            c = wt.wt_select(ctx, M, N, K)
+            kd = table.keys[key]
+            assert (c.bm, c.bn, c.bk, c.nwave, c.stages, c.swizzle, c.split) == \
+                (kd.bm, kd.bn, kd.bk, kd.nwave, kd.stages, micro, kd.split)
+            assert wt.wt_predict_us(ctx, M, N, K, c) == t
+    finally:
+        wt.wt_destroy(ctx)
