@@ -102,7 +102,10 @@ def cpu_baseline(np, wt_synth):
         from oracle import select as osel
         from paper_2604_10187_amd import tune
 
-        table, _ = osel.read_table(tune.table_path(0, 1))
+        import paper_2604_10187_amd as wt
+
+        table, _ = osel.read_table(tune.table_path(0, 1), ws_elems=wt.WT_SPLITK_WS_FLOATS,
+                                   max_split_tiles=wt.WT_SPLITK_MAX_TILES)
         shapes = wt_synth.stream_shapes(300)
         t0 = time.perf_counter()
         for (m, n, k) in shapes:

@@ -45,7 +45,8 @@ typedef enum {
     WT_ERR_HIP = -5,             /* a HIP call failed; see wt_last_hip_error() */
     WT_ERR_BUFFER_TOO_SMALL = -6,
     WT_ERR_IO = -7,
-    WT_ERR_NO_DEVICE = -8        /* device work requested from a host-only context */
+    WT_ERR_NO_DEVICE = -8,       /* device work requested from a host-only context */
+    WT_ERR_NO_MEMORY = -9        /* a host allocation failed */
 } wt_status;
 
 /* Storage type of A and B.  WT_ATTN_BF16 makes an attention context instead of a GEMM one: its registry holds
@@ -55,6 +56,16 @@ typedef enum { WT_BF16 = 0, WT_FP8_E4M3 = 1, WT_ATTN_BF16 = 2 } wt_in_t;
 typedef enum { WT_OUT_F32 = 0, WT_OUT_BF16 = 1 } wt_out_t; /* storage type of C */
 
 typedef struct wt_ctx wt_ctx; /* opaque: config registry, per-config resources, dual table */
+
+/* Feasibility limits of this library (properties of the build, not of the method):
+ *   a context's split-K workspace holds WT_SPLITK_WS_FLOATS fp32 partial-tile elements and one arrival counter
+ *   for each of at most WT_SPLITK_MAX_TILES output tiles per launch; a split-K configuration whose partial tiles
+ *   for a shape exceed either is not a candidate of wt_select and wt_gemm returns WT_ERR_INFEASIBLE for it;
+ *   a dual-table bucket stores at most WT_MAX_ANCHORS <loop count, micro> anchors (Sec. 4.3 anchor table) --
+ *   with more distinct loop counts in a bucket, those at ranks floor(i*(n-1)/(WT_MAX_ANCHORS-1)) are kept. */
+#define WT_SPLITK_WS_FLOATS (1 << 26)
+#define WT_SPLITK_MAX_TILES (1 << 16)
+#define WT_MAX_ANCHORS 8
 
 /* One kernel configuration.  id is the registry index (or -1: look the fields up). */
 typedef struct {
@@ -86,7 +97,7 @@ typedef struct {
  * over several calls.  max_out_elems caps M*N of an instantiated workload (0 = no cap): grid
  * points whose output would exceed it are skipped. */
 typedef struct {
-    int32_t W, I, tau_num, tau_den, p;
+    int32_t W, I, tau_num, tau_den, p; /* 1 <= W <= 4096, 1 <= I <= 4096, tau_num >= tau_den >= 1, p >= 1 */
     int32_t n_k_anchors;
     const int32_t* k_anchors; /* host pointer, n_k_anchors entries */
     int32_t warmup, iters;

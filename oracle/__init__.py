@@ -18,7 +18,10 @@ Plain, slow, obviously-correct implementations written from the paper:
                  (Table 2, FlashAttention row; Sec. 4.2 head-aligned grid sizes; Eq. 6).
 
 Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import this package.
-It imports nothing from the product package and shares no code, tables or constants with it.
+It imports nothing from the product package and shares no code or tables with it.  Three feasibility
+limits of the product (split-K workspace floats, split-K tile count, anchor slots per table bucket) are
+not results of the method; the oracle takes them as arguments (geometry.split_fits, fit.thin_anchors,
+select.read_table), None meaning "no limit", and the tests pass in the values the product's header states.
 
 Pins (tests/test_oracle_*.py) tie each function to facts fixed by the paper or by mathematics;
 a function whose behaviour could not be pinned says "parity unpinned" in its docstring.

@@ -55,6 +55,10 @@ class DualTable:
     W_row: int = 0        # few-row families (extension): profiled waves, 0 = absent
     row_local: list = field(default_factory=list)   # row_local[fam-1][key][w-1] -> Bucket, fam = 1..row_fams
     row_ext: list = field(default_factory=list)     # row_ext[fam-1][key] -> Bucket
+    # feasibility limits of whatever runs the split-K keys (floats of partial tiles per launch, output
+    # tiles per launch); None = unlimited.  Not part of the method: set by the caller (see geometry.split_fits)
+    ws_elems: Optional[int] = None
+    max_split_tiles: Optional[int] = None
 
     @property
     def row_fams(self) -> int:
@@ -126,21 +130,20 @@ def fit_bilinear(rows) -> tuple[tuple, int]:
     return (alpha, beta, gamma, delta), status
 
 
-# The table format gives a bucket room for this many <loop count, micro> anchors.
-MAX_ANCHORS = 8
-
-
-def thin_anchors(anchors: list, limit: int = MAX_ANCHORS) -> list:
-    """Reading for buckets with more loop counts than the table can hold (attention grids: each grid size has its
+def thin_anchors(anchors: list, limit=None) -> list:
+    """Reading for buckets with more loop counts than a table has room for (attention grids: each grid size has its
     own KV lengths): keep the anchors at ranks floor(i*(n-1)/(limit-1)), i = 0..limit-1 -- the smallest, the
-    largest and an even spread between them.  The fit still uses every loop count's rows."""
+    largest and an even spread between them.  The fit still uses every loop count's rows.  limit = None (the
+    method as the paper states it) keeps every anchor; a table format's capacity is the caller's to pass in."""
     n = len(anchors)
-    if n <= limit:
+    if limit is None or n <= limit:
         return list(anchors)
+    if limit < 2:
+        raise ValueError("limit >= 2")
     return [anchors[(i * (n - 1)) // (limit - 1)] for i in range(limit)]
 
 
-def _fit_group(records) -> Bucket:
+def _fit_group(records, max_anchors=None) -> Bucket:
     """Shared micro per L, then one bilinear fit over the chosen micros' rows."""
     by_L = defaultdict(list)
     for r in records:
@@ -153,7 +156,7 @@ def _fit_group(records) -> Bucket:
         anchors.append((L, pick[0]))
         rows.extend(pick[1])
     theta, status = fit_bilinear(rows)
-    return Bucket(theta=theta, status=status, anchors=thin_anchors(anchors))
+    return Bucket(theta=theta, status=status, anchors=thin_anchors(anchors, max_anchors))
 
 
 def fit_step(records, cap: int):
@@ -188,10 +191,10 @@ MODEL_WAVE_BILINEAR, MODEL_LINEAR, MODEL_STEP = 0, 1, 2
 
 
 def fit_tables(samples, keys, W: int, p: int, model: int = MODEL_WAVE_BILINEAR, W_row: int = 0,
-               row_fams: int = 1) -> DualTable:
+               row_fams: int = 1, max_anchors=None) -> DualTable:
     """Build the dual table (Sec. 4.3) with per-key extrapolation entries fitted on the merged
     samples of the last p profiled waves, max(1, W-p+1)..W (Sec. 4.5).  Samples with w > W are
-    ignored.
+    ignored.  max_anchors: anchor slots per bucket of the table being imitated (see thin_anchors; None = all).
 
     model selects the ablations of Sec. 5.4 expressed in the same table form:
       LINEAR  no wave buckets; one bilinear tuple per key fitted on all waves (stored as the
@@ -203,16 +206,17 @@ def fit_tables(samples, keys, W: int, p: int, model: int = MODEL_WAVE_BILINEAR, 
     if W_row > 0:
         # every few-row family is a further, independent set of buckets built the same way
         # (wave buckets 1..W_row, extrapolation from the last min(p, W_row) of them)
-        t = fit_tables([s for s in samples if s.fam == 0], keys, W, p, model)
+        t = fit_tables([s for s in samples if s.fam == 0], keys, W, p, model, max_anchors=max_anchors)
         t.W_row = W_row
         for f in range(1, row_fams + 1):
-            rows_t = fit_tables([s._replace(fam=0) for s in samples if s.fam == f], keys, W_row, min(p, W_row))
+            rows_t = fit_tables([s._replace(fam=0) for s in samples if s.fam == f], keys, W_row, min(p, W_row),
+                                max_anchors=max_anchors)
             t.row_local.append(rows_t.local)
             t.row_ext.append(rows_t.ext)
         return t
     samples = [s for s in samples if s.fam == 0]
     if model == MODEL_LINEAR:
-        t = fit_tables(samples, keys, W, W, MODEL_WAVE_BILINEAR)
+        t = fit_tables(samples, keys, W, W, MODEL_WAVE_BILINEAR, max_anchors=max_anchors)
         for k in range(len(keys)):
             t.local[k] = [Bucket() for _ in range(W)]
         return t
@@ -238,9 +242,9 @@ def fit_tables(samples, keys, W: int, p: int, model: int = MODEL_WAVE_BILINEAR, 
     local, ext = [], []
     lo = max(1, W - p + 1)
     for k in range(len(keys)):
-        local.append([_fit_group(per_key_w.get((k, w), [])) for w in range(1, W + 1)])
+        local.append([_fit_group(per_key_w.get((k, w), []), max_anchors) for w in range(1, W + 1)])
         merged = [s for w in range(lo, W + 1) for s in per_key_w.get((k, w), [])]
-        ext.append(_fit_group(merged))
+        ext.append(_fit_group(merged, max_anchors))
     return DualTable(W=W, keys=list(keys), local=local, ext=ext)
 
 

@@ -33,20 +33,18 @@ def phi_gemm(M: int, N: int, K: int, BM: int, BN: int, BK: int, S: int = 1) -> t
     return S * ceil_div(M, BM) * ceil_div(N, BN), ceil_div(ceil_div(K, BK), S)
 
 
-# Limits of the product's split-K workspace as stated in its header: partial tiles of one launch may
-# hold at most 2^26 floats and there is one arrival counter for each of at most 2^16 output tiles.
-WS_ELEMS = 1 << 26
-MAX_SPLIT_TILES = 1 << 16
-
-
-def split_fits(M: int, N: int, BM: int, BN: int, S: int, ws_elems: int = WS_ELEMS,
-               max_tiles: int = MAX_SPLIT_TILES) -> bool:
-    """Whether a split-K configuration can run a shape: S fp32 partial tiles of BM x BN per output
-    tile must fit the workspace.  Unsplit configurations always fit."""
+def split_fits(M: int, N: int, BM: int, BN: int, S: int, ws_elems=None, max_tiles=None) -> bool:
+    """Whether a split-K configuration can run a shape when the S fp32 partial tiles of BM x BN per
+    output tile have to fit a workspace of ws_elems floats with one arrival counter for each of at
+    most max_tiles output tiles.  The method itself knows no such limit (None = unlimited, the
+    default): whoever checks an implementation against this oracle passes that implementation's
+    limits in.  Unsplit configurations always fit."""
     if S == 1:
         return True
     tiles = ceil_div(M, BM) * ceil_div(N, BN)
-    return tiles <= max_tiles and tiles * S * BM * BN <= ws_elems
+    if max_tiles is not None and tiles > max_tiles:
+        return False
+    return ws_elems is None or tiles * S * BM * BN <= ws_elems
 
 
 def phi_grouped(rows, N: int, K: int, BM: int, BN: int, BK: int) -> tuple[int, int]:

@@ -57,7 +57,7 @@ def select(table: DualTable, M: int, N: int, K: int):
     Stage II: nearest loop anchor in the chosen bucket.  Returns (key, micro, T-hat) or None."""
     best = None
     for k, kd in enumerate(table.keys):
-        if not split_fits(M, N, kd.bm, kd.bn, kd.split):
+        if not split_fits(M, N, kd.bm, kd.bn, kd.split, table.ws_elems, table.max_split_tiles):
             continue     # its partial tiles would not fit the workspace: not a candidate
         G, L = phi_gemm(M, N, K, kd.bm, kd.bn, kd.bk, kd.split)
         w = wave_count(G, kd.cap)
@@ -130,8 +130,9 @@ def select_grouped(table: DualTable, E: int, M_total: int, N: int, K: int):
 MAGIC = b"WTDT"
 
 
-def read_table(path: str) -> tuple[DualTable, dict]:
-    """Parse the flat little-endian dual-table file.
+def read_table(path: str, ws_elems=None, max_split_tiles=None) -> tuple[DualTable, dict]:
+    """Parse the flat little-endian dual-table file.  ws_elems / max_split_tiles: the split-K feasibility
+    limits of the library that will run the table's keys (they are not in the file; None = unlimited).
 
     Header, 16 uint32: magic 'WTDT', version (1, 2 or 3), n_keys, W, I, p, tau_num, tau_den, n_cu,
     A (anchor slots per bucket), in_type, out_type, key_mode, W_row (version >= 2, else 0), number of
@@ -180,4 +181,5 @@ def read_table(path: str) -> tuple[DualTable, dict]:
         raise ValueError("trailing bytes in dual table")
     meta = dict(I=I, p=p, tau_num=tnum, tau_den=tden, n_cu=n_cu, A=A, in_type=in_t, out_type=out_t, key_mode=mode,
                 W_row=W_row)
-    return DualTable(W=W, keys=keys, local=local, ext=ext, W_row=W_row, row_local=row_local, row_ext=row_ext), meta
+    return DualTable(W=W, keys=keys, local=local, ext=ext, W_row=W_row, row_local=row_local, row_ext=row_ext,
+                     ws_elems=ws_elems, max_split_tiles=max_split_tiles), meta

@@ -16,11 +16,12 @@ LIB_PATH = os.path.join(_HERE, "libwt.so")
 
 WT_OK = 0
 WT_ERR_INVALID_ARG, WT_ERR_UNSUPPORTED_CFG, WT_ERR_INFEASIBLE, WT_ERR_NOT_FITTED = -1, -2, -3, -4
-WT_ERR_HIP, WT_ERR_BUFFER_TOO_SMALL, WT_ERR_IO, WT_ERR_NO_DEVICE = -5, -6, -7, -8
+WT_ERR_HIP, WT_ERR_BUFFER_TOO_SMALL, WT_ERR_IO, WT_ERR_NO_DEVICE, WT_ERR_NO_MEMORY = -5, -6, -7, -8, -9
 WT_BF16, WT_FP8_E4M3, WT_ATTN_BF16 = 0, 1, 2
 WT_OUT_F32, WT_OUT_BF16 = 0, 1
 WT_MODEL_WAVE_BILINEAR, WT_MODEL_LINEAR, WT_MODEL_STEP = 0, 1, 2
 WT_CAP_CU_TIMES_OCC, WT_CAP_CU_ONLY = 0, 1
+WT_SPLITK_WS_FLOATS, WT_SPLITK_MAX_TILES, WT_MAX_ANCHORS = 1 << 26, 1 << 16, 8   # as #defined in wt.h
 
 
 class wt_cfg(C.Structure):

@@ -119,7 +119,7 @@ __device__ __forceinline__ void load_lds_16B(i32x4 rsrc, uint32_t voffset, uint3
         "buffer_load_dwordx4 %1, %2, %3 offen lds"
         :
         : "s"(lds_base), "v"(voffset), "s"(rsrc), "s"(soffset)
-        : "memory");
+        : "memory", "m0");
 }
 
 __device__ __forceinline__ void wait_lgkmcnt0() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }

@@ -170,7 +170,7 @@ bool key_in_slice(const wt_grid* g, int k, int nk) {
 }
 
 int check_grid(const wt_grid* g) {
-    if (!g || g->W < 1 || g->I < 1 || g->tau_den < 1 || g->tau_num < g->tau_den || g->p < 1 || g->n_k_anchors < 1 ||
+    if (!g || g->W < 1 || g->W > kMaxWaves || g->I < 1 || g->I > kMaxSubIntervals || g->W_row > kMaxWaves || g->tau_den < 1 || g->tau_num < g->tau_den || g->p < 1 || g->n_k_anchors < 1 ||
         !g->k_anchors || g->warmup < 0 || g->iters < 1 || g->W_row < 0 || g->W_split < 0 || g->row_fams < 0 || g->row_fams > kMaxRowFams)
         return WT_ERR_INVALID_ARG;
     for (int j = 0; j < g->n_k_anchors; ++j)
@@ -261,7 +261,37 @@ int walk_plan(const wt_ctx* ctx, const wt_grid* grid, F&& fn) {
     return WT_OK;
 }
 
+int sample_plan_impl(const wt_ctx* ctx, const wt_grid* grid, size_t* n_samples, size_t* bytesA, size_t* bytesB,
+                            size_t* bytesC) {
+    int rc = WT_OK;
+    Plan p;
+    const size_t esz = ctx->in_type == WT_BF16 ? 2 : 1, osz = ctx->out_type == WT_OUT_F32 ? 4 : 2;
+    const bool attn = ctx->in_type == WT_ATTN_BF16;
+    rc = walk_plan(ctx, grid, [&](int k, const GridPoint&, int, int, int64_t, int64_t M, int64_t N, int64_t K) {
+        p.n_samples += (size_t)ctx->keys[k].n_micro;
+        if (attn) {  // Q, K followed by V, O; bf16
+            p.bytesA = std::max(p.bytesA, (size_t)(M * N * kHeadDim) * 2);
+            p.bytesB = std::max(p.bytesB, (size_t)(K * N * kHeadDim) * 4);
+            p.bytesC = std::max(p.bytesC, (size_t)(M * N * kHeadDim) * 2);
+            return (int)WT_OK;
+        }
+        p.bytesA = std::max(p.bytesA, (size_t)(M * K) * esz);
+        p.bytesB = std::max(p.bytesB, (size_t)(N * K) * esz);
+        p.bytesC = std::max(p.bytesC, (size_t)(M * N) * osz);
+        return (int)WT_OK;
+    });
+    if (rc != WT_OK) return rc;
+    if (n_samples) *n_samples = p.n_samples;
+    if (bytesA) *bytesA = p.bytesA;
+    if (bytesB) *bytesB = p.bytesB;
+    if (bytesC) *bytesC = p.bytesC;
+    return WT_OK;
+}
+
 }  // namespace
+
+static int profile_sparse_impl(wt_ctx* ctx, const wt_grid* grid, void* scrA, void* scrB, void* scrC, size_t bytesA,
+                               size_t bytesB, size_t bytesC, void* hip_stream, wt_sample* out, size_t cap, size_t* n_out);
 
 extern "C" {
 
@@ -275,7 +305,11 @@ int wt_create(wt_ctx** out, int device, int in_type, int out_type) {
     ctx->device = device;
     ctx->in_type = in_type;
     ctx->out_type = out_type;
-    int rc = build_registry(ctx);
+    int rc = WT_ERR_NO_MEMORY;
+    try {
+        rc = build_registry(ctx);
+    } catch (...) {
+    }
     if (rc != WT_OK) { delete ctx; return rc; }
     if (device >= 0) {
         hipError_t e = hipSetDevice(device);
@@ -450,34 +484,20 @@ int wt_sample_plan(const wt_ctx* ctx, const wt_grid* grid, size_t* n_samples, si
     if (!ctx) return WT_ERR_INVALID_ARG;
     int rc = check_grid(grid);
     if (rc != WT_OK) return rc;
-    Plan p;
-    const size_t esz = ctx->in_type == WT_BF16 ? 2 : 1, osz = ctx->out_type == WT_OUT_F32 ? 4 : 2;
-    const bool attn = ctx->in_type == WT_ATTN_BF16;
-    rc = walk_plan(ctx, grid, [&](int k, const GridPoint&, int, int, int64_t, int64_t M, int64_t N, int64_t K) {
-        p.n_samples += (size_t)ctx->keys[k].n_micro;
-        if (attn) {  // Q, K followed by V, O; bf16
-            p.bytesA = std::max(p.bytesA, (size_t)(M * N * kHeadDim) * 2);
-            p.bytesB = std::max(p.bytesB, (size_t)(K * N * kHeadDim) * 4);
-            p.bytesC = std::max(p.bytesC, (size_t)(M * N * kHeadDim) * 2);
-            return (int)WT_OK;
-        }
-        p.bytesA = std::max(p.bytesA, (size_t)(M * K) * esz);
-        p.bytesB = std::max(p.bytesB, (size_t)(N * K) * esz);
-        p.bytesC = std::max(p.bytesC, (size_t)(M * N) * osz);
-        return (int)WT_OK;
-    });
-    if (rc != WT_OK) return rc;
-    if (n_samples) *n_samples = p.n_samples;
-    if (bytesA) *bytesA = p.bytesA;
-    if (bytesB) *bytesB = p.bytesB;
-    if (bytesC) *bytesC = p.bytesC;
-    return WT_OK;
+    WT_GUARD(sample_plan_impl(ctx, grid, n_samples, bytesA, bytesB, bytesC));
 }
 
 int wt_profile_sparse(wt_ctx* ctx, const wt_grid* grid, void* scrA, void* scrB, void* scrC, size_t bytesA,
                       size_t bytesB, size_t bytesC, void* hip_stream, wt_sample* out, size_t cap, size_t* n_out) {
     if (!ctx || !out || !n_out || !scrA || !scrB || !scrC) return WT_ERR_INVALID_ARG;
     if (ctx->device < 0) return WT_ERR_NO_DEVICE;
+    WT_GUARD(profile_sparse_impl(ctx, grid, scrA, scrB, scrC, bytesA, bytesB, bytesC, hip_stream, out, cap, n_out));
+}
+
+}  // extern "C"
+
+static int profile_sparse_impl(wt_ctx* ctx, const wt_grid* grid, void* scrA, void* scrB, void* scrC, size_t bytesA,
+                               size_t bytesB, size_t bytesC, void* hip_stream, wt_sample* out, size_t cap, size_t* n_out) {
     size_t need = 0, nA = 0, nB = 0, nC = 0;
     int rc = wt_sample_plan(ctx, grid, &need, &nA, &nB, &nC);
     if (rc != WT_OK) return rc;
@@ -512,5 +532,3 @@ int wt_profile_sparse(wt_ctx* ctx, const wt_grid* grid, void* scrA, void* scrB, 
     *n_out = n;
     return rc;
 }
-
-}  // extern "C"

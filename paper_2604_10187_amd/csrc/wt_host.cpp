@@ -10,6 +10,7 @@
 #include <algorithm>
 #include <chrono>
 #include <new>
+#include <stdexcept>
 #include <utility>
 #include <vector>
 
@@ -465,7 +466,8 @@ static int fit_family(const wt_ctx* ctx, int family, int model, int W, int p, co
 
 static int fit_table(wt_ctx* ctx, const wt_grid* grid, const wt_sample* s, size_t n) {
     const int W = grid->W;
-    if (W < 1 || grid->p < 1 || grid->W_row < 0 || grid->W_row > 4096) return WT_ERR_INVALID_ARG;
+    // the same bounds wt_load applies, so that every table that can be fitted and saved can be loaded again
+    if (W < 1 || W > kMaxWaves || grid->I < 1 || grid->p < 1 || grid->W_row < 0 || grid->W_row > kMaxWaves) return WT_ERR_INVALID_ARG;
     if (grid->model < WT_MODEL_WAVE_BILINEAR || grid->model > WT_MODEL_STEP) return WT_ERR_INVALID_ARG;
     Table t;
     t.W = W; t.I = grid->I; t.p = grid->p; t.tau_num = grid->tau_num; t.tau_den = grid->tau_den;
@@ -630,10 +632,12 @@ static int load_table(wt_ctx* ctx, const char* path) {
     if (rc == WT_OK && hdr[1] == 1u) hdr[13] = 0;
     if (rc == WT_OK) hdr[14] = hdr[13] == 0 ? 0u : (hdr[1] == 3u ? hdr[14] : 1u);
     if (rc == WT_OK && hdr[14] > static_cast<uint32_t>(kMaxRowFams)) rc = WT_ERR_INVALID_ARG;
-    if (rc == WT_OK && hdr[13] > 4096u) rc = WT_ERR_INVALID_ARG;
+    if (rc == WT_OK && hdr[13] > static_cast<uint32_t>(kMaxWaves)) rc = WT_ERR_INVALID_ARG;
     if (rc == WT_OK && (hdr[2] != ctx->keys.size() || hdr[9] != static_cast<uint32_t>(kMaxAnchors) ||
-                        hdr[10] != static_cast<uint32_t>(ctx->in_type) || hdr[3] < 1 || hdr[3] > 4096 || hdr[12] > 1u))
-        rc = WT_ERR_INVALID_ARG;  // table was built for another registry
+                        hdr[8] != static_cast<uint32_t>(kNumCU) || hdr[10] != static_cast<uint32_t>(ctx->in_type) ||
+                        hdr[11] != static_cast<uint32_t>(ctx->out_type) || hdr[3] < 1 ||
+                        hdr[3] > static_cast<uint32_t>(kMaxWaves) || hdr[12] > 1u))
+        rc = WT_ERR_INVALID_ARG;  // table was built for another registry, device size or storage type
     if (rc == WT_OK) {
         t.W = static_cast<int>(hdr[3]); t.I = static_cast<int>(hdr[4]); t.p = static_cast<int>(hdr[5]);
         t.tau_num = static_cast<int>(hdr[6]); t.tau_den = static_cast<int>(hdr[7]);
@@ -687,6 +691,7 @@ const char* wt_status_string(int s) {
         case WT_ERR_BUFFER_TOO_SMALL: return "buffer too small";
         case WT_ERR_IO: return "file error";
         case WT_ERR_NO_DEVICE: return "host-only context";
+        case WT_ERR_NO_MEMORY: return "out of host memory";
         default: return "unknown status";
     }
 }
@@ -755,37 +760,43 @@ int wt_wave_count(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, wt_cfg cfg
 
 int wt_sample_grid(int64_t capacity, int32_t W, int32_t I, int32_t tau_num, int32_t tau_den, int32_t split,
                    int64_t* g, int64_t* m, int64_t* n, size_t cap_out, size_t* n_out) {
-    if (capacity < 1 || W < 1 || I < 1 || tau_num < tau_den || tau_den < 1 || split < 1 || !n_out)
+    if (capacity < 1 || W < 1 || W > kMaxWaves || I < 1 || I > kMaxSubIntervals || tau_num < tau_den || tau_den < 1 ||
+        split < 1 || !n_out)
         return WT_ERR_INVALID_ARG;
-    std::vector<GridPoint> pts;
-    sample_grid(capacity, W, I, tau_num, tau_den, split, pts);
-    *n_out = pts.size();
-    if (pts.size() > cap_out) return WT_ERR_BUFFER_TOO_SMALL;
-    for (size_t i = 0; i < pts.size(); ++i) {
-        if (g) g[i] = pts[i].g;
-        if (m) m[i] = pts[i].m;
-        if (n) n[i] = pts[i].n;
-    }
-    return WT_OK;
+    WT_GUARD([&]() -> int {
+        std::vector<GridPoint> pts;
+        sample_grid(capacity, W, I, tau_num, tau_den, split, pts);
+        *n_out = pts.size();
+        if (pts.size() > cap_out) return WT_ERR_BUFFER_TOO_SMALL;
+        for (size_t i = 0; i < pts.size(); ++i) {
+            if (g) g[i] = pts[i].g;
+            if (m) m[i] = pts[i].m;
+            if (n) n[i] = pts[i].n;
+        }
+        return WT_OK;
+    }());
 }
 
 int wt_sample_grid_heads(int64_t capacity, int32_t W, int32_t I, int32_t n_heads, int64_t* g, int64_t* q_tiles,
                          size_t cap_out, size_t* n_out) {
-    if (capacity < 1 || W < 1 || I < 1 || n_heads < 1 || !n_out) return WT_ERR_INVALID_ARG;
-    std::vector<GridPoint> pts;
-    sample_grid_heads(capacity, W, I, n_heads, pts);
-    *n_out = pts.size();
-    if (pts.size() > cap_out) return WT_ERR_BUFFER_TOO_SMALL;
-    for (size_t i = 0; i < pts.size(); ++i) {
-        if (g) g[i] = pts[i].g;
-        if (q_tiles) q_tiles[i] = pts[i].m;
-    }
-    return WT_OK;
+    if (capacity < 1 || W < 1 || W > kMaxWaves || I < 1 || I > kMaxSubIntervals || n_heads < 1 || !n_out)
+        return WT_ERR_INVALID_ARG;
+    WT_GUARD([&]() -> int {
+        std::vector<GridPoint> pts;
+        sample_grid_heads(capacity, W, I, n_heads, pts);
+        *n_out = pts.size();
+        if (pts.size() > cap_out) return WT_ERR_BUFFER_TOO_SMALL;
+        for (size_t i = 0; i < pts.size(); ++i) {
+            if (g) g[i] = pts[i].g;
+            if (q_tiles) q_tiles[i] = pts[i].m;
+        }
+        return WT_OK;
+    }());
 }
 
 int wt_fit(wt_ctx* ctx, const wt_grid* grid, const wt_sample* samples, size_t n) {
     if (!ctx || !grid || (!samples && n)) return WT_ERR_INVALID_ARG;
-    return fit_table(ctx, grid, samples, n);
+    WT_GUARD(fit_table(ctx, grid, samples, n));
 }
 
 int wt_select(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, wt_cfg* out) {
@@ -852,7 +863,12 @@ int wt_select_bench(const wt_ctx* ctx, const int64_t* shapes, size_t n, int repe
                     double* p99_ns) {
     if (!ctx || !shapes || n == 0 || repeats < 1) return WT_ERR_INVALID_ARG;
     if (!ctx->table.fitted) return WT_ERR_NOT_FITTED;
-    std::vector<double> per(n, 0.0);
+    std::vector<double> per;
+    try {
+        per.assign(n, 0.0);
+    } catch (...) {
+        return WT_ERR_NO_MEMORY;
+    }
     volatile int sink = 0;
     double total = 0;
     for (int r = 0; r < repeats; ++r) {
@@ -879,12 +895,12 @@ int wt_select_bench(const wt_ctx* ctx, const int64_t* shapes, size_t n, int repe
 
 int wt_save(const wt_ctx* ctx, const char* path) {
     if (!ctx || !path) return WT_ERR_INVALID_ARG;
-    return save_table(ctx, path);
+    WT_GUARD(save_table(ctx, path));
 }
 
 int wt_load(wt_ctx* ctx, const char* path) {
     if (!ctx || !path) return WT_ERR_INVALID_ARG;
-    return load_table(ctx, path);
+    WT_GUARD(load_table(ctx, path));
 }
 
 }  // extern "C"

@@ -3,6 +3,8 @@
 
 #include <stdint.h>
 
+#include <new>
+#include <stdexcept>
 #include <vector>
 
 #include "../../include/wt.h"
@@ -13,13 +15,15 @@ namespace wt {
 constexpr int kNumCU = 256;            // compute units of one MI355X
 constexpr int kLdsPerCU = 160 * 1024;  // bytes
 constexpr int kNumSwizzle = 3;         // micro parameter values 0..2
-constexpr int kMaxAnchors = 8;         // loop anchors stored per bucket
+constexpr int kMaxAnchors = WT_MAX_ANCHORS;  // loop anchors stored per bucket
+constexpr int kMaxWaves = 4096;         // largest W (and W_row) of a table or a sample grid
+constexpr int kMaxSubIntervals = 4096;  // largest I of a sample grid
 constexpr int kMaxRowFams = 3;         // few-row sample families: 1, 2 and 4 tile rows
 // Family consulted for a shape with `rows` = ceil(M/bm) tile rows: 1 -> 1, 2..3 -> 2, 4..7 -> 3, else 0.
 inline int row_family(int64_t rows) { return rows <= 1 ? 1 : rows <= 3 ? 2 : rows <= 7 ? 3 : 0; }
 // Split-K workspace owned by a context: fp32 partial tiles and one arrival counter per output tile.
-constexpr int64_t kWsElems = int64_t{1} << 26;   // 256 MiB of floats
-constexpr int64_t kMaxSplitTiles = 1 << 16;      // arrival counters
+constexpr int64_t kWsElems = WT_SPLITK_WS_FLOATS;        // 256 MiB of floats
+constexpr int64_t kMaxSplitTiles = WT_SPLITK_MAX_TILES;  // arrival counters
 
 struct Config {
     wt_cfg cfg;
@@ -64,6 +68,18 @@ struct Table {
 };
 
 }  // namespace wt
+
+// No exception crosses the ABI: entry points that allocate host memory evaluate their body inside this guard.
+#define WT_GUARD(expr)                    \
+    try {                                 \
+        return (expr);                    \
+    } catch (const std::bad_alloc&) {     \
+        return WT_ERR_NO_MEMORY;          \
+    } catch (const std::length_error&) {  \
+        return WT_ERR_NO_MEMORY;          \
+    } catch (...) {                       \
+        return WT_ERR_INVALID_ARG;        \
+    }
 
 struct wt_ctx {
     int device = -1;

@@ -3,6 +3,11 @@
     python -m paper_2604_10187_amd.run_one M N K bm bn bk nwave stages swizzle [iters] [in_type] [out_type] [split]
 
 in_type 0 = bf16, 1 = fp8 e4m3; out_type 0 = f32, 1 = bf16; split = blocks per output tile along K (default 1).  N(0,1) operands (fp8: per-tensor scales).
+
+    python -m paper_2604_10187_amd.run_one copy [MiB]
+
+runs three plain device-to-device copies of MiB mebibytes (default 1024) and nothing else: the dispatch of known
+size against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled.
 """
 import sys
 
@@ -11,8 +16,22 @@ import torch
 from . import binding as wt
 
 
+def copy_of_known_size(mib):
+    n = mib * (1 << 20) // 4
+    src = torch.arange(n, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        dst.copy_(src)          # one copy kernel per call: reads n*4 bytes, writes n*4 bytes
+    torch.cuda.synchronize()
+    print(f"copied {n * 4} bytes per dispatch (read) and the same written; 3 dispatches", flush=True)
+
+
 def main(argv=None):
-    a = [int(x) for x in (argv or sys.argv[1:])]
+    argv = list(argv or sys.argv[1:])
+    if argv and argv[0] == "copy":
+        return copy_of_known_size(int(argv[1]) if len(argv) > 1 else 1024)
+    a = [int(x) for x in argv]
     if len(a) < 9:
         print(__doc__)
         sys.exit(2)

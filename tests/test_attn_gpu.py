@@ -1,9 +1,11 @@
 """GPU parity: wt_attn (through the C ABI) against the fp64 oracle, element by element.
 
-Tolerance.  Inputs are bf16; scores and the online softmax are fp32; probabilities are rounded to bf16 before they
-multiply V (relative error 2^-9 per term, averaging down over the keys) and the output is rounded to bf16
-(2^-9 relative).  With N(0,1) values the outputs have magnitude <= a few units, so |O - O_ref| <= 2e-2 *
-max(|O_ref|, 1) per element leaves a margin of about 5x over the worst observed error.
+Tolerance: |O - O_ref| <= 2e-2 * max(|O_ref|, rms(O_ref)) per element, rms over the rows compared -- the same
+reading of "2e-2 per element, bf16 out" as for the GEMM (a purely relative error is undefined where O_ref crosses
+zero, and an absolute floor would be vacuous at long KV lengths, where outputs average thousands of N(0,1) values
+and have rms 0.01-0.02).  Expected error: inputs are bf16; scores and the online softmax are fp32; probabilities
+are rounded to bf16 before they multiply V (2^-9 relative per term, independent over the keys -> about 1e-3 of the
+output's rms) and the output is rounded to bf16 (2^-9 relative).
 """
 import math
 
@@ -46,10 +48,18 @@ def reference(qb, kb, vb, causal, scale=SCALE):
     return oa.attention(dec(qb), dec(kb), dec(vb), scale, causal)
 
 
+WORST = {"err": 0.0, "what": ""}    # largest scaled error seen in this session, printed by the last test
+
+
 def check(got, want, what):
     assert np.isfinite(got).all(), f"{what}: non-finite output"
-    err = np.abs(got - want) / np.maximum(np.abs(want), 1.0)
-    assert err.max() <= ELEM_TOL, f"{what}: max scaled error {err.max():.4g} at {np.unravel_index(err.argmax(), err.shape)}"
+    scale = np.maximum(np.abs(want), math.sqrt(float(np.mean(np.square(want)))) if want.size else 0.0)
+    diff = np.abs(got - want)
+    err = np.divide(diff, scale, out=np.where(diff > 0, np.inf, 0.0), where=scale > 0)   # all-zero reference: exact
+    worst = float(err.max()) if err.size else 0.0
+    if worst > WORST["err"]:
+        WORST.update(err=worst, what=what)
+    assert worst <= ELEM_TOL, f"{what}: max scaled error {worst:.4g} at {np.unravel_index(err.argmax(), err.shape)}"
 
 
 def test_every_config_is_launchable(ctx):
@@ -242,3 +252,9 @@ def test_argument_errors(ctx):
     bad = wt.wt_cfg(64, 1, 48, 2, 1, 0, 1, -1)
     with pytest.raises(wt.WtError):
         wt.wt_attn(ctx, 4, 4, 8, 8, t, t, t, t, SCALE, 0, bad)
+
+
+def test_zz_report_worst_scaled_error():
+    """Not a check of its own: prints the largest |O - O_ref| / max(|O_ref|, rms) the checks above saw."""
+    note(f"attention parity: worst scaled error {WORST['err']:.3e} ({WORST['what']}); bound {ELEM_TOL}")
+    assert WORST["err"] <= ELEM_TOL

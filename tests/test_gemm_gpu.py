@@ -536,27 +536,105 @@ def test_wave_count_on_device_context(ctx_f32):
     wt.wt_set_capacity_mode(ctx_f32, wt.WT_CAP_CU_ONLY)
 
 
-def test_profile_fit_select_round_trip_on_device(ctx_bf16, tmp_path):
-    """A reduced sparse profile on the GPU (a few structural keys), fit, save; the oracle's selector on
-    the saved table must return exactly what wt_select returns."""
+# ---- sparse profiling on the device -> fit -> select, against the oracle at every step --------------------------
+RT_W, RT_I, RT_P, RT_ANCHORS, RT_WSPLIT = 3, 2, 2, (1024, 2048), 2
+RT_SLICES = ((15, 3), (61, 2))      # three unsplit keys and two split-K keys of the bf16 registry
+
+
+@pytest.fixture(scope="module")
+def device_records(ctx_bf16):
+    """One reduced sparse profile on the GPU, shared by the model variants below: slices of the registry's keys,
+    W = 3 waves (2 for split-K keys), I = 2, two K anchors, 1 warm-up + 2 timed launches."""
+    out = []
+    for (first, count) in RT_SLICES:
+        grid = wt.make_grid(W=RT_W, I=RT_I, p=RT_P, k_anchors=RT_ANCHORS, warmup=1, iters=2, key_first=first,
+                            key_count=count, W_split=RT_WSPLIT)
+        n, bA, bB, bC = wt.wt_sample_plan(ctx_bf16, grid)
+        scrA = torch.zeros(bA // 2, dtype=torch.bfloat16, device="cuda")
+        scrB = torch.zeros(bB // 2, dtype=torch.bfloat16, device="cuda")
+        scrC = torch.empty(bC, dtype=torch.uint8, device="cuda")
+        note(f"profile_sparse keys {first}..{first + count - 1}, {n} records")
+        recs = wt.wt_profile_sparse(ctx_bf16, grid, scrA, scrB, scrC, stream=torch.cuda.current_stream())
+        assert len(recs) == n
+        out.append(recs)
+        del scrA, scrB, scrC
+    return out
+
+
+def test_device_records_are_the_oracles_plan(ctx_bf16, device_records):
+    """Every record <key, micro, G, L, w, family> of wt_profile_sparse, in order, is what the oracle derives:
+    sample_set (Eq. 3-4) x loop anchors x micros, instantiated by Eq. 5 so that Phi of the workload gives back
+    (G, L); split-K keys over their own task counts and only W_split waves."""
+    from _pins import split_limits
+    from oracle import geometry as geo
+    from oracle import sampler as smp
+
+    lim = split_limits()
+    for (first, count), recs in zip(RT_SLICES, device_records):
+        want = []
+        for k in range(first, first + count):
+            cfg, res = wt.wt_config_get(ctx_bf16, 3 * k)
+            assert res.key_id == k
+            S = cfg.split
+            W = RT_W if S == 1 else min(RT_W, RT_WSPLIT)
+            for smpl in smp.sample_set(256, W, RT_I, S=S):
+                if smpl.g == 0 or not geo.split_fits(smpl.m * cfg.bm, smpl.n * cfg.bn, cfg.bm, cfg.bn, S,
+                                                     lim["ws_elems"], lim["max_split_tiles"]):
+                    continue
+                for L in smp.loop_anchors(RT_ANCHORS, cfg.bk, S):
+                    M, N, K = smp.instantiate(smpl.m, smpl.n, L, cfg.bm, cfg.bn, cfg.bk, S)
+                    assert geo.phi_gemm(M, N, K, cfg.bm, cfg.bn, cfg.bk, S) == (smpl.g, L)
+                    assert geo.wave_count(smpl.g, 256) == smpl.w
+                    want += [(k, m, smpl.g, L, smpl.w, 0) for m in range(3)]
+        got = [(int(r["key_id"]), int(r["micro_id"]), int(r["G"]), int(r["L"]), int(r["w"]), int(r["family"])) for r in recs]
+        assert got == want
+        assert np.all(recs["mean_us"] > 0) and np.isfinite(recs["mean_us"]).all()
+    # more work takes longer: for one key and micro, the largest G*L is slower than the smallest
+    r0 = device_records[0]
+    r0 = r0[(r0["key_id"] == RT_SLICES[0][0]) & (r0["micro_id"] == 0)]
+    assert r0["mean_us"][np.argmax(r0["G"] * r0["L"])] > r0["mean_us"][np.argmin(r0["G"] * r0["L"])]
+
+
+@pytest.mark.parametrize("model", [wt.WT_MODEL_WAVE_BILINEAR, wt.WT_MODEL_LINEAR, wt.WT_MODEL_STEP])
+def test_profile_fit_select_round_trip_on_device(ctx_bf16, tmp_path, device_records, model):
+    """Device records -> wt_fit under each latency model (the method and its two ablations, Sec. 5.4) -> wt_save;
+    the table equals the oracle's fit of the same records (coefficients to 1e-9, status and anchors exactly), and
+    the oracle's selector on the saved file returns exactly what wt_select returns, prediction included."""
+    from _pins import lib_limits, split_limits
+    from oracle import fit as ofit
     from oracle import select as osel
 
-    grid = wt.make_grid(W=3, I=2, p=2, k_anchors=(1024, 2048), warmup=1, iters=2, key_first=15, key_count=3)
-    n, bA, bB, bC = wt.wt_sample_plan(ctx_bf16, grid)
-    scrA = torch.zeros(bA // 2, dtype=torch.bfloat16, device="cuda")
-    scrB = torch.zeros(bB // 2, dtype=torch.bfloat16, device="cuda")
-    scrC = torch.empty(bC, dtype=torch.uint8, device="cuda")
-    note(f"profile_sparse keys 15..17, {n} records")
-    recs = wt.wt_profile_sparse(ctx_bf16, grid, scrA, scrB, scrC, stream=torch.cuda.current_stream())
-    assert len(recs) == n and np.all(recs["mean_us"] > 0)
-    assert set(recs["key_id"].tolist()) == {15, 16, 17} and set(recs["micro_id"].tolist()) == {0, 1, 2}
+    recs = np.concatenate(device_records)
+    grid = wt.make_grid(W=RT_W, I=RT_I, p=RT_P, k_anchors=RT_ANCHORS, W_split=RT_WSPLIT, model=model)
     wt.wt_fit(ctx_bf16, grid, recs)
-    path = str(tmp_path / "t.wt")
+    path = str(tmp_path / f"t{model}.wt")
     wt.wt_save(ctx_bf16, path)
-    table, _ = osel.read_table(path)
+    table, _ = osel.read_table(path, **split_limits())
+    profiled = {k for (first, count) in RT_SLICES for k in range(first, first + count)}
+    want = ofit.fit_tables([(int(r["key_id"]), int(r["micro_id"]), int(r["G"]), int(r["L"]), int(r["w"]),
+                             float(r["mean_us"])) for r in recs], table.keys, RT_W, RT_P, model=model,
+                           max_anchors=lib_limits()["max_anchors"])
+    n_fitted = 0
+    for k in range(len(table.keys)):
+        for got_b, want_b in list(zip(table.local[k], want.local[k])) + [(table.ext[k], want.ext[k])]:
+            assert got_b.status == want_b.status, (k, model)
+            assert (got_b.status != 0) <= (k in profiled)
+            if not want_b.status:
+                continue
+            n_fitted += 1
+            assert got_b.anchors == want_b.anchors
+            # compare through predictions over the bucket's own range (coefficients cancel heavily)
+            for (G, L) in ((1, 1), (256, 16), (700, 64), (2048, 160)):
+                a, b = osel.predict(got_b.theta, G, L), osel.predict(want_b.theta, G, L)
+                assert abs(a - b) <= 1e-9 * max(abs(b), max(abs(x) for x in want_b.theta)), (k, model, G, L, a, b)
+    assert n_fitted >= len(profiled)
+    picked = set()
     for (M, N, K) in wt_synth.sweep_shapes() + wt_synth.stream_shapes(300):
         key, micro, t = osel.select(table, M, N, K)
         c = wt.wt_select(ctx_bf16, M, N, K)
         kd = table.keys[key]
-        assert (c.bm, c.bn, c.bk, c.nwave, c.stages, c.swizzle, c.split) == (kd.bm, kd.bn, kd.bk, kd.nwave, kd.stages, micro, 1)
-        assert key in (15, 16, 17)
+        assert (c.bm, c.bn, c.bk, c.nwave, c.stages, c.swizzle, c.split) == (kd.bm, kd.bn, kd.bk, kd.nwave, kd.stages, micro, kd.split)
+        assert wt.wt_predict_us(ctx_bf16, M, N, K, c) == t      # the same bits
+        assert key in profiled
+        picked.add(key)
+    assert len(picked) >= 2

@@ -10,6 +10,10 @@ import wt_synth
 from oracle import attention as oa
 from oracle import fit as ofit
 from oracle import select as osel
+from _pins import lib_limits, split_limits
+
+SPLIT_LIMITS = split_limits()                 # the library's split-K workspace limits, from include/wt.h
+MAX_ANCHORS = lib_limits()["max_anchors"]     # anchor slots per bucket of its table format
 from oracle.geometry import ceil_div
 
 MULT = (100, 150, 200, 250, 300)
@@ -102,11 +106,11 @@ def test_fit_and_select_parity_on_a_synthetic_surface(ctx, tmp_path):
     wt.wt_fit(ctx, wt.make_grid(W=W, I=I, p=p, k_anchors=MULT, n_heads=heads), samples)
     path = str(tmp_path / "attn.wt")
     wt.wt_save(ctx, path)
-    table, _ = osel.read_table(path)
+    table, _ = osel.read_table(path, **SPLIT_LIMITS)
     kds = table.keys
     assert [(kd.bm, kd.bn, kd.bk, kd.nwave, kd.stages, kd.cap, kd.split) for kd in kds] == \
         [(c.bm, 1, c.bk, c.nwave, 1, 256, 1) for c in keys]
-    want = ofit.fit_tables([tuple(r)[:5] + (float(r["mean_us"]),) for r in samples], kds, W, p)
+    want = ofit.fit_tables([tuple(r)[:5] + (float(r["mean_us"]),) for r in samples], kds, W, p, max_anchors=MAX_ANCHORS)
     for k in range(len(keys)):
         for gb, wb in list(zip(table.local[k], want.local[k])) + [(table.ext[k], want.ext[k])]:
             assert gb.status == wb.status and gb.anchors == wb.anchors
@@ -121,7 +125,7 @@ def test_shipped_attention_table_selects_like_the_oracle():
     c = wt.wt_create(-1, wt.WT_ATTN_BF16, wt.WT_OUT_BF16)
     try:
         wt.wt_load(c, TABLE)
-        table, meta = osel.read_table(TABLE)
+        table, meta = osel.read_table(TABLE, **SPLIT_LIMITS)
         keys = _keys(c)
         assert len(table.keys) == len(keys)
         for (S_q, S_kv, H_q, _) in wt_synth.attn_shapes(300, 12):

@@ -13,6 +13,10 @@ from oracle import fit as ofit
 from oracle import geometry as geo
 from oracle import sampler as smp
 from oracle import select as osel
+from _pins import lib_limits, split_limits
+
+SPLIT_LIMITS = split_limits()                 # the library's split-K workspace limits, from include/wt.h
+MAX_ANCHORS = lib_limits()["max_anchors"]     # anchor slots per bucket of its table format
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 K_ANCHORS = (1024, 2048, 3072, 4096, 5120)
@@ -42,6 +46,50 @@ def test_library_exports_every_declared_symbol():
     L = wt.lib()
     for name in declared:
         assert getattr(L, name) is not None
+
+
+def test_binding_states_the_headers_limits():
+    lim = lib_limits()
+    assert (wt.WT_SPLITK_WS_FLOATS, wt.WT_SPLITK_MAX_TILES, wt.WT_MAX_ANCHORS) == (lim["ws_elems"], lim["max_split_tiles"], lim["max_anchors"])
+
+
+def test_oversized_grids_and_foreign_tables_are_refused(tmp_path):
+    """No exception crosses the ABI and nothing that can be fitted and saved fails to load: W and I beyond 4096
+    are invalid arguments for wt_fit / wt_sample_grid / wt_sample_plan, and a table written for another output
+    type or another compute-unit count is refused by wt_load."""
+    c = wt.wt_create(-1, wt.WT_BF16, wt.WT_OUT_BF16)
+    other = wt.wt_create(-1, wt.WT_BF16, wt.WT_OUT_F32)
+    try:
+        one = np.zeros(1, dtype=wt.SAMPLE_DTYPE)
+        one["w"], one["G"], one["L"], one["mean_us"] = 1, 10, 4, 1.0
+        for bad in (dict(W=4097), dict(W=2**31 - 1), dict(I=0), dict(W=0)):
+            with pytest.raises(wt.WtError) as e:
+                wt.wt_fit(c, wt.make_grid(**{**dict(W=4, I=2, p=2), **bad}), one)
+            assert e.value.status == wt.WT_ERR_INVALID_ARG
+        import ctypes
+        got = ctypes.c_size_t()      # straight through the ABI (the binding would size host arrays from W * I)
+        assert wt.lib().wt_sample_grid(256, 2**31 - 1, 4, 11, 10, 1, None, None, None, 0, ctypes.byref(got)) == wt.WT_ERR_INVALID_ARG
+        assert wt.lib().wt_sample_grid_heads(256, 4, 2**31 - 1, 8, None, None, 0, ctypes.byref(got)) == wt.WT_ERR_INVALID_ARG
+        with pytest.raises(wt.WtError) as e:
+            wt.wt_sample_plan(c, wt.make_grid(W=2**31 - 1, I=4))
+        assert e.value.status == wt.WT_ERR_INVALID_ARG
+        wt.wt_fit(c, wt.make_grid(W=4096, I=1, p=1), one)       # the largest W is accepted ...
+        path = str(tmp_path / "big.wt")
+        wt.wt_save(c, path)
+        wt.wt_load(c, path)                                      # ... and loads again
+        with pytest.raises(wt.WtError) as e:                     # bf16-out table into an f32-out context
+            wt.wt_load(other, path)
+        assert e.value.status == wt.WT_ERR_INVALID_ARG
+        raw = bytearray(open(path, "rb").read())
+        raw[32:36] = (132).to_bytes(4, "little")                 # header word 8: compute units
+        p2 = tmp_path / "cu.wt"
+        p2.write_bytes(bytes(raw))
+        with pytest.raises(wt.WtError) as e:
+            wt.wt_load(c, str(p2))
+        assert e.value.status == wt.WT_ERR_INVALID_ARG
+    finally:
+        wt.wt_destroy(c)
+        wt.wt_destroy(other)
 
 
 def test_registry_shape(ctx):
@@ -135,7 +183,7 @@ def _synthetic_samples(keys, W, I, noise_seed=None):
         # split-K keys are profiled for the first waves only and cost a little extra per task
         Wk = W if kd.split == 1 else min(W, W_SPLIT)
         for s in smp.sample_set(kd.cap, Wk, I, S=kd.split):
-            if s.g == 0 or not geo.split_fits(s.m * kd.bm, s.n * kd.bn, kd.bm, kd.bn, kd.split):
+            if s.g == 0 or not geo.split_fits(s.m * kd.bm, s.n * kd.bn, kd.bm, kd.bn, kd.split, SPLIT_LIMITS["ws_elems"], SPLIT_LIMITS["max_split_tiles"]):
                 continue                              # no such grid, or it cannot run: never profiled
             for L in smp.loop_anchors(K_ANCHORS, kd.bk, kd.split):
                 for micro in range(3):
@@ -158,11 +206,11 @@ def test_fit_and_select_parity(ctx, tmp_path, noise_seed):
     wt.wt_fit(ctx, grid, samples)
     path = str(tmp_path / "table.wt")
     wt.wt_save(ctx, path)
-    table, meta = osel.read_table(path)
+    table, meta = osel.read_table(path, **SPLIT_LIMITS)
     assert meta["I"] == I and meta["p"] == p and table.W == W and len(table.keys) == len(keys)
     assert table.keys == keys
     # (1) coefficients and anchors against the oracle's own fit of the same records
-    want = ofit.fit_tables([tuple(r)[:5] + (float(r["mean_us"]),) for r in samples], keys, W, p)
+    want = ofit.fit_tables([tuple(r)[:5] + (float(r["mean_us"]),) for r in samples], keys, W, p, max_anchors=MAX_ANCHORS)
     for k in range(len(keys)):
         for got_b, want_b in list(zip(table.local[k], want.local[k])) + [(table.ext[k], want.ext[k])]:
             assert got_b.status == want_b.status and got_b.anchors == want_b.anchors
@@ -202,7 +250,7 @@ def test_split_keys_in_selection(ctx, tmp_path):
     wt.wt_fit(ctx, grid, samples)
     path = str(tmp_path / "split.wt")
     wt.wt_save(ctx, path)
-    table, _ = osel.read_table(path)
+    table, _ = osel.read_table(path, **SPLIT_LIMITS)
     assert table.keys == keys
     # the plan holds exactly the records the oracle's sampler enumerates (3 micros each)
     n_plan, *_ = wt.wt_sample_plan(ctx, grid)
@@ -225,7 +273,7 @@ def test_split_keys_in_selection(ctx, tmp_path):
         assert geo.wave_count(G, kd.cap) > W_SPLIT
         with pytest.raises(wt.WtError) as e:
             wt.wt_predict_us(ctx, M, N, 4096, cfg)
-        fits = geo.split_fits(M, N, kd.bm, kd.bn, kd.split)
+        fits = geo.split_fits(M, N, kd.bm, kd.bn, kd.split, SPLIT_LIMITS["ws_elems"], SPLIT_LIMITS["max_split_tiles"])
         assert e.value.status == (wt.WT_ERR_NOT_FITTED if fits else wt.WT_ERR_INFEASIBLE)
 
 
@@ -238,7 +286,7 @@ def test_grouped_geometry_and_selection(ctx):
     import tempfile
     with tempfile.TemporaryDirectory() as d:
         wt.wt_save(ctx, d + "/g.wt")
-        table, _ = osel.read_table(d + "/g.wt")
+        table, _ = osel.read_table(d + "/g.wt", **SPLIT_LIMITS)
     for (E, top_k, N, K) in wt_synth.MOE_LAYERS:
         for tokens in wt_synth.MOE_TOKENS:
             rows = wt_synth.moe_routing(tokens, E, top_k, seed=tokens + E)
@@ -296,8 +344,8 @@ def test_ablation_models_parity(ctx, tmp_path, model):
     wt.wt_fit(ctx, wt.make_grid(W=W, I=I, p=p, k_anchors=K_ANCHORS, model=model), samples)
     path = str(tmp_path / "abl.wt")
     wt.wt_save(ctx, path)
-    table, _ = osel.read_table(path)
-    want = ofit.fit_tables([tuple(r)[:5] + (float(r["mean_us"]),) for r in samples], keys, W, p, model=model)
+    table, _ = osel.read_table(path, **SPLIT_LIMITS)
+    want = ofit.fit_tables([tuple(r)[:5] + (float(r["mean_us"]),) for r in samples], keys, W, p, model=model, max_anchors=MAX_ANCHORS)
     for k in range(len(keys)):
         for got_b, want_b in list(zip(table.local[k], want.local[k])) + [(table.ext[k], want.ext[k])]:
             assert got_b.status == want_b.status
@@ -331,7 +379,7 @@ def test_occupancy_aware_capacity_mode(tmp_path):
         wt.wt_fit(c, wt.make_grid(W=W, I=I, p=3, k_anchors=K_ANCHORS), samples)
         path = str(tmp_path / "occ.wt")
         wt.wt_save(c, path)
-        table, meta = osel.read_table(path)
+        table, meta = osel.read_table(path, **SPLIT_LIMITS)
         assert meta["key_mode"] == 0 and table.keys == keys
         c2 = wt.wt_create(-1, wt.WT_BF16, wt.WT_OUT_F32)
         assert wt.wt_wave_count(c2, 4096, 4096, 4096, cfg)[2] == geo.wave_count(G, 256)
@@ -364,7 +412,7 @@ def test_few_row_families_parity(ctx, tmp_path, row_fams):
             th = wt_synth.random_theta(900 + 7 * f + k, W_row)
             Wk = W_row if kd.split == 1 else min(W_row, W_SPLIT)
             for s in smp.row_sample_set(kd.cap, Wk, I, m, kd.split):
-                if s.g == 0 or not geo.split_fits(s.m * kd.bm, s.n * kd.bn, kd.bm, kd.bn, kd.split):
+                if s.g == 0 or not geo.split_fits(s.m * kd.bm, s.n * kd.bn, kd.bm, kd.bn, kd.split, SPLIT_LIMITS["ws_elems"], SPLIT_LIMITS["max_split_tiles"]):
                     continue
                 for L in smp.loop_anchors(K_ANCHORS, kd.bk, kd.split):
                     for micro in range(3):
@@ -376,11 +424,11 @@ def test_few_row_families_parity(ctx, tmp_path, row_fams):
     wt.wt_fit(ctx, grid, samples)
     path = str(tmp_path / "row.wt")
     wt.wt_save(ctx, path)
-    table, meta = osel.read_table(path)
+    table, meta = osel.read_table(path, **SPLIT_LIMITS)
     assert meta["W_row"] == W_row and table.W_row == W_row and table.row_fams == row_fams
     want = ofit.fit_tables([(int(r["key_id"]), int(r["micro_id"]), int(r["G"]), int(r["L"]), int(r["w"]),
                              float(r["mean_us"]), int(r["family"])) for r in samples], keys, W, p, W_row=W_row,
-                           row_fams=row_fams)
+                           row_fams=row_fams, max_anchors=MAX_ANCHORS)
     for k in range(len(keys)):
         pairs = list(zip(table.local[k], want.local[k])) + [(table.ext[k], want.ext[k])]
         for f in range(row_fams):

@@ -391,12 +391,13 @@ def test_few_row_families_are_chosen_by_tile_rows():
 def test_thin_anchors_keeps_ends_and_an_even_spread():
     """Buckets with more loop counts than the table holds keep ranks floor(i*(n-1)/7): hand values."""
     a15 = [(L, L % 3) for L in range(10, 25)]
-    assert ofit.thin_anchors(a15) == [a15[i] for i in (0, 2, 4, 6, 8, 10, 12, 14)]
+    assert ofit.thin_anchors(a15, 8) == [a15[i] for i in (0, 2, 4, 6, 8, 10, 12, 14)]
     a9 = [(L, 0) for L in range(9)]
-    assert ofit.thin_anchors(a9) == [a9[i] for i in (0, 1, 2, 3, 4, 5, 6, 8)]
+    assert ofit.thin_anchors(a9, 8) == [a9[i] for i in (0, 1, 2, 3, 4, 5, 6, 8)]
     a8 = [(L, 1) for L in range(8)]
-    assert ofit.thin_anchors(a8) == a8 and ofit.thin_anchors(a8[:3]) == a8[:3]
+    assert ofit.thin_anchors(a8, 8) == a8 and ofit.thin_anchors(a8[:3], 8) == a8[:3]
     assert ofit.thin_anchors(a15, 2) == [a15[0], a15[-1]]
+    assert ofit.thin_anchors(a15) == a15          # no limit given (the method as stated): every anchor is kept
 
 
 def test_select_attn_hand_worked_two_keys():
@@ -422,3 +423,29 @@ def test_select_attn_hand_worked_two_keys():
     # 128 heads: both beyond W -> ext tuples: key 0: 0.02*2048*32 = 1310.72; key 1: 0.01*512*16 = 81.92
     k, micro, t = osel.select_attn(table, 128, 1024, 1024)
     assert (k, micro) == (1, 2) and t == pytest.approx(81.92)
+
+
+def test_r_squared_exact_surface_hand_value_and_constant_rows():
+    """Coefficient of determination R^2 = 1 - SS_res/SS_tot (the statistic Sec. 3.3 / Fig. 5 quotes for the G- and
+    L-linearity of a wave).  (i) rows lying on the plane -> exactly 1; (ii) a hand case: T = (1, 2, 6) at
+    (G, L) = (1,0), (2,0), (3,0) against the line T-hat = 2G - 1 = (1, 3, 5): SS_res = 0 + 1 + 1 = 2, mean 3,
+    SS_tot = 4 + 1 + 9 = 14 -> R^2 = 1 - 2/14 = 6/7; (iii) a model no better than the mean -> 0; worse than the mean
+    -> negative; (iv) constant rows have SS_tot = 0 and are defined as 1; (v) the least-squares fit of noisy rows
+    maximises R^2: perturbing any coefficient lowers it."""
+    theta = (0.003, 0.25, 1.5, 7.0)
+    rows = [(g, l, theta[0] * g * l + theta[1] * g + theta[2] * l + theta[3]) for g in (260, 300, 410, 512) for l in (16, 48, 80)]
+    assert ofit.r_squared(rows, theta) == pytest.approx(1.0, abs=1e-14)
+    hand = [(1, 0, 1.0), (2, 0, 2.0), (3, 0, 6.0)]
+    assert ofit.r_squared(hand, (0.0, 2.0, 0.0, -1.0)) == pytest.approx(6.0 / 7.0, abs=1e-15)
+    assert ofit.r_squared(hand, (0.0, 0.0, 0.0, 3.0)) == pytest.approx(0.0, abs=1e-15)
+    assert ofit.r_squared(hand, (0.0, 0.0, 0.0, 10.0)) < 0.0
+    assert ofit.r_squared([(1, 1, 5.0), (2, 3, 5.0)], (0.0, 0.0, 0.0, 4.0)) == 1.0
+    rng = np.random.default_rng(8)
+    noisy = [(g, l, t * (1.0 + 0.05 * rng.standard_normal())) for (g, l, t) in rows]
+    best, _ = ofit.fit_bilinear(noisy)
+    r2 = ofit.r_squared(noisy, best)
+    assert 0.9 < r2 < 1.0
+    for i in range(4):
+        worse = list(best)
+        worse[i] *= 1.02
+        assert ofit.r_squared(noisy, tuple(worse)) < r2

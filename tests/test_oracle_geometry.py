@@ -154,7 +154,10 @@ def test_sampler_matches_brute_force(cap, I):
         assert (s.g or None) == want
 
 
-def test_paper_sample_counts_and_invariants():
+def test_sample_set_has_W_times_I_sub_intervals_152_non_empty_at_capacity_256():
+    """Sec. 5.1 quotes 160 grid points for W = 40, I = 4: that is the nominal W*I, one slot per sub-interval.  The
+    list below always has W*I entries; at capacity 256 eight of those sub-intervals hold no value with a near-square
+    factorisation (g = 0 entries), so 152 real samples exist; at larger capacities every sub-interval has one."""
     W, I = P["train_W"], P["train_I"]
     for occ in (1, 2, 3, 5, 8):
         cap = geo.capacity(occ)
@@ -170,6 +173,9 @@ def test_paper_sample_counts_and_invariants():
             assert a <= s.g <= b and s.m * s.n == s.g and s.m <= s.n and 10 * s.n <= 11 * s.m
             assert geo.wave_count(s.g, cap) == s.w
     assert sum(s.g == 0 for s in smp.sample_set(256, W, I)) == 8
+    assert sum(s.g > 0 for s in smp.sample_set(256, W, I)) == 152
+    for occ in (2, 3, 5, 8):
+        assert all(s.g > 0 for s in smp.sample_set(geo.capacity(occ), W, I))
     # attention's counting rule: I=3 and W in [20,35] gives 60..105 points
     assert P["attn_I"] * P["attn_W_lo"] == P["attn_points_lo"]
     assert P["attn_I"] * P["attn_W_hi"] == P["attn_points_hi"]
@@ -228,11 +234,16 @@ def test_split_phi_partitions_the_k_tiles():
 
 
 def test_split_workspace_rule():
-    assert geo.split_fits(10**6, 10**6, 256, 256, 1)
+    lim = dict(ws_elems=1 << 26, max_tiles=1 << 16)
+    assert geo.split_fits(10**6, 10**6, 256, 256, 1, **lim)
     # 2^26 floats hold 1024 tiles of 128x128 split in 4, and not one more
-    assert geo.split_fits(128 * 32, 128 * 32, 128, 128, 4)
-    assert not geo.split_fits(128 * 32 + 1, 128 * 32, 128, 128, 4)
-    assert geo.split_fits(16 * 256, 16 * 256, 16, 16, 2) and not geo.split_fits(16 * 256 + 1, 16 * 256, 16, 16, 2)  # 2^16 tiles
+    assert geo.split_fits(128 * 32, 128 * 32, 128, 128, 4, **lim)
+    assert not geo.split_fits(128 * 32 + 1, 128 * 32, 128, 128, 4, **lim)
+    assert geo.split_fits(16 * 256, 16 * 256, 16, 16, 2, **lim) and not geo.split_fits(16 * 256 + 1, 16 * 256, 16, 16, 2, **lim)  # 2^16 tiles
+    # the limits are the caller's: without them every split fits, and each works alone
+    assert geo.split_fits(128 * 32 + 1, 128 * 32, 128, 128, 4) and geo.split_fits(10**5, 10**5, 16, 16, 8)
+    assert not geo.split_fits(64, 64, 16, 16, 2, ws_elems=16 * 16 * 2 * 16 - 1) and geo.split_fits(64, 64, 16, 16, 2, ws_elems=16 * 16 * 2 * 16)
+    assert not geo.split_fits(64, 64, 16, 16, 2, max_tiles=15) and geo.split_fits(64, 64, 16, 16, 2, max_tiles=16)
 
 
 @pytest.mark.parametrize("cap,S", [(8, 2), (12, 4), (64, 2), (64, 8), (132, 4), (256, 8)])

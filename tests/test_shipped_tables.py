@@ -9,6 +9,10 @@ import paper_2604_10187_amd as wt
 import wt_synth
 from oracle import fit as ofit
 from oracle import select as osel
+from _pins import lib_limits, split_limits
+
+SPLIT_LIMITS = split_limits()                 # the library's split-K workspace limits, from include/wt.h
+MAX_ANCHORS = lib_limits()["max_anchors"]     # anchor slots per bucket of its table format
 
 TABLES = os.path.join(os.path.dirname(wt.LIB_PATH), "tables")
 CASES = [(wt.WT_BF16, "mi355x_in0_out1"), (wt.WT_FP8_E4M3, "mi355x_in1_out1"), (wt.WT_ATTN_BF16, "mi355x_attn")]
@@ -20,7 +24,7 @@ def test_table_loads_into_the_registry_and_records_match(in_type, stem):
     try:
         wt.wt_load(ctx, os.path.join(TABLES, stem + ".wt"))       # refuses a table whose keys differ from the registry
         nk = wt.wt_key_count(ctx)
-        table, _ = osel.read_table(os.path.join(TABLES, stem + ".wt"))
+        table, _ = osel.read_table(os.path.join(TABLES, stem + ".wt"), **SPLIT_LIMITS)
         assert len(table.keys) == nk
         for k, kd in enumerate(table.keys):
             c, _ = wt.wt_config_get(ctx, 3 * k)
@@ -42,7 +46,7 @@ def test_shipped_gemm_tables_select_like_the_oracle(in_type, stem):
     try:
         path = os.path.join(TABLES, stem + ".wt")
         wt.wt_load(ctx, path)
-        table, _ = osel.read_table(path)
+        table, _ = osel.read_table(path, **SPLIT_LIMITS)
         for (M, N, K) in wt_synth.sweep_shapes() + wt_synth.stream_shapes(400):
             if in_type == wt.WT_FP8_E4M3 and K % 16:
                 continue
