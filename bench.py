@@ -23,11 +23,25 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
+PEAK_FP8_TFLOPS = 5000.0    # dense fp8
 PEAK_HBM_GBS = 8000.0
-# HBM-side bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled
-# by the copy-kernel calibration (x2.0 / x1.0): profiles/gemm_traffic_pmc.md.  Keyed by (kernel, shape);
-# reported as null when the run picks another kernel than the profiled one.
-TRAFFIC_BYTES = {((256, 256, 64, 8, 2, 2, 1), (4096, 11008, 4096)): 725.5e6}
+LARGE_PREFILL = (16384, 8192, 8192)     # the shape the >= 70 %-of-peak target is stated on
+SKINNY = (16, 11008, 4096)              # an HBM-bound shape of the sweep
+
+
+def traffic_table():
+    """HBM-side bytes per launch (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the copy-kernel calibration)
+    as measured per (kernel, shape) and listed in profiles/gemm_traffic_table.txt; a (kernel, shape) that was not
+    profiled reports null."""
+    out = {}
+    path = os.path.join(ROOT, "profiles", "gemm_traffic_table.txt")
+    if os.path.exists(path):
+        for line in open(path):
+            f = line.split("#", 1)[0].split()
+            if len(f) == 13:
+                v = [int(x) for x in f[:11]]
+                out[(v[0], tuple(v[1:8]), tuple(v[8:11]))] = float(f[11]) + float(f[12])
+    return out
 
 
 def log(*a):
@@ -79,6 +93,71 @@ def attention_extra(wt, torch):
     except wt.WtError as e:
         log(f"[bench] attention extra skipped: {e}")
         return None
+    finally:
+        wt.wt_destroy(ctx)
+
+
+def large_prefill_leg(wt, wt_synth, torch, np, in_type, ctx, stream):
+    """Outside the timed step: 16384 x 8192 x 8192 (bf16 out) under wt_select's configuration, timed with HIP events
+    on the launch stream inside the library, next to the MFMA-only ceiling measured in the same run."""
+    M, N, K = LARGE_PREFILL
+    a32, b32 = wt_synth.gemm_operands(M, N, K, 1004 if in_type == wt.WT_BF16 else 1014)
+    sA = sB = None
+    if in_type == wt.WT_BF16:
+        dA = torch.from_numpy(wt_synth.to_bf16_bits(a32).view(np.int16)).cuda()
+        dB = torch.from_numpy(wt_synth.to_bf16_bits(b32).view(np.int16)).cuda()
+    else:
+        qa, sa = wt_synth.to_e4m3_bits(a32)
+        qb, sb = wt_synth.to_e4m3_bits(b32)
+        dA, dB = torch.from_numpy(qa).cuda(), torch.from_numpy(qb).cuda()
+        sA = torch.tensor([sa], dtype=torch.float32, device="cuda")
+        sB = torch.tensor([sb], dtype=torch.float32, device="cuda")
+    del a32, b32
+    dC = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    cfg = wt.wt_select(ctx, M, N, K)
+    us = wt.wt_time_gemm(ctx, M, N, K, dA, dB, dC, cfg, 3, 10, sA, sB, stream)
+    ceiling = wt.wt_mfma_ceiling(ctx, in_type, 20000, stream)
+    peak = PEAK_BF16_TFLOPS if in_type == wt.WT_BF16 else PEAK_FP8_TFLOPS
+    ach = 2.0 * M * N * K / us / 1e6
+    name = "bf16" if in_type == wt.WT_BF16 else "fp8_e4m3"
+    return {"bound": "mfma", "achieved": round(ach, 1), "peak": peak, "unit": "TFLOP/s", "frac": round(ach / peak, 4),
+            "traffic": traffic_table().get((in_type, cfg.astuple(), LARGE_PREFILL)),
+            "algorithmic_flop": 2.0 * M * N * K, "mfma_only_ceiling": round(ceiling, 1),
+            "frac_of_mfma_only_ceiling": round(ach / ceiling, 4), "target_frac": 0.70, "meets_target": bool(ach / peak >= 0.70),
+            "kernel": f"gemm_kernel<{cfg.bm},{cfg.bn},{cfg.bk},nw{cfg.nwave},st{cfg.stages}> sw{cfg.swizzle} "
+                      f"split{cfg.split} {name} on {M}x{N}x{K}", "avg_us": round(us, 2), "dtype": name}
+
+
+def small_case_leg(wt, wt_synth, torch, np, picks_from):
+    """Outside the timed step: the 256^3 bf16 case with fp32 output.  Exhaustive search over its own grid (every
+    registry entry with bm, bn in {64,128}, bk in {32,64}, 1 or 2 stages, unsplit) and over the whole registry,
+    against the configuration wt_select returns for 256^3 (structural key and micro from the shipped table)."""
+    ctx = wt.wt_create(0, wt.WT_BF16, wt.WT_OUT_F32)
+    try:
+        a32, b32 = wt_synth.gemm_operands(256, 256, 256, 1001)
+        dA = torch.from_numpy(wt_synth.to_bf16_bits(a32).view(np.int16)).cuda()
+        dB = torch.from_numpy(wt_synth.to_bf16_bits(b32).view(np.int16)).cuda()
+        dC = torch.empty((256, 256), dtype=torch.float32, device="cuda")
+        stream = torch.cuda.current_stream()
+        pick = wt.wt_select(picks_from, 256, 256, 256)
+        times, small = {}, {}
+        for i in range(wt.wt_config_count(ctx)):
+            c, r = wt.wt_config_get(ctx, i)
+            if r.occ < 1:
+                continue
+            times[i] = wt.wt_time_gemm(ctx, 256, 256, 256, dA, dB, dC, c, warmup=3, iters=5, stream=stream)
+            if c.bm in (64, 128) and c.bn in (64, 128) and c.bk in (32, 64) and c.stages in (1, 2) and c.split == 1:
+                small[i] = times[i]
+        if pick.id not in times:
+            times[pick.id] = wt.wt_time_gemm(ctx, 256, 256, 256, dA, dB, dC, pick, warmup=3, iters=5, stream=stream)
+        best_small = min(small, key=small.get)
+        cb, _ = wt.wt_config_get(ctx, best_small)
+        return {"workload": "256x256x256 bf16, fp32 out", "grid_configs": len(small), "registry_configs": len(times),
+                "grid_best": list(cb.astuple()), "grid_best_us": round(small[best_small], 2),
+                "registry_best_us": round(min(times.values()), 2), "pick": list(pick.astuple()),
+                "pick_us": round(times[pick.id], 2), "pick_in_grid": pick.id in small,
+                "pick_pct_of_grid_best": round(100.0 * small[best_small] / times[pick.id], 2),
+                "pick_pct_of_registry_best": round(100.0 * min(times.values()) / times[pick.id], 2)}
     finally:
         wt.wt_destroy(ctx)
 
@@ -168,20 +247,34 @@ def main():
     ms_per_step = dt * 1e3 / a.steps
     value = flops * a.steps / dt / 1e12
 
-    # ---- roofline of the dominant kernel: the pick for the largest shape, HIP events on its stream
+    # ---- rooflines, HIP events on the launch stream (inside the library) -------------------------------------
+    traffic = traffic_table()
+    # (1) the sweep's dominant kernel: the pick for its largest shape
     big = max(shapes, key=lambda s: s[0] * s[1] * s[2])
     cfg_big = wt.wt_select(ctx, *big)
     dA, dB, dC = bufs[big]
     us_big = wt.wt_time_gemm(ctx, *big, dA, dB, dC, cfg_big, warmup=3, iters=20, stream=stream)
     ach = 2.0 * big[0] * big[1] * big[2] / us_big / 1e6
     ceiling = wt.wt_mfma_ceiling(ctx, in_type, 20000, stream)   # MFMA-only loop, N(0,1)-like operands
-    roofline = {"bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(ach / PEAK_BF16_TFLOPS, 4),
-                "traffic": TRAFFIC_BYTES.get((cfg_big.astuple(), tuple(big))),
-                "algorithmic_flop": 2.0 * big[0] * big[1] * big[2],
-                "mfma_only_ceiling": round(ceiling, 1), "frac_of_mfma_only_ceiling": round(ach / ceiling, 4),
-                "kernel": f"gemm_kernel<{cfg_big.bm},{cfg_big.bn},{cfg_big.bk},nw{cfg_big.nwave},st{cfg_big.stages}>"
-                          f" sw{cfg_big.swizzle} split{cfg_big.split} on {big[0]}x{big[1]}x{big[2]}", "avg_us": round(us_big, 2)}
+    roofline_sweep = {"bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                      "frac": round(ach / PEAK_BF16_TFLOPS, 4),
+                      "traffic": traffic.get((in_type, cfg_big.astuple(), tuple(big))),
+                      "algorithmic_flop": 2.0 * big[0] * big[1] * big[2],
+                      "mfma_only_ceiling": round(ceiling, 1), "frac_of_mfma_only_ceiling": round(ach / ceiling, 4),
+                      "kernel": f"gemm_kernel<{cfg_big.bm},{cfg_big.bn},{cfg_big.bk},nw{cfg_big.nwave},st{cfg_big.stages}>"
+                                f" sw{cfg_big.swizzle} split{cfg_big.split} on {big[0]}x{big[1]}x{big[2]}", "avg_us": round(us_big, 2)}
+    # (2) an HBM-bound shape of the sweep: algorithmic bytes e*(M*K + N*K) + e_out*M*N against 8 TB/s
+    sk = SKINNY
+    cfg_sk = wt.wt_select(ctx, *sk)
+    dA, dB, dC = bufs[sk]
+    us_sk = wt.wt_time_gemm(ctx, *sk, dA, dB, dC, cfg_sk, warmup=3, iters=20, stream=stream)
+    bytes_sk = 2.0 * (sk[0] * sk[2] + sk[1] * sk[2]) + 2.0 * sk[0] * sk[1]
+    gbs = bytes_sk / us_sk / 1e3
+    roofline_hbm = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": traffic.get((in_type, cfg_sk.astuple(), tuple(sk))),
+                    "algorithmic_bytes": bytes_sk,
+                    "kernel": f"gemm_kernel<{cfg_sk.bm},{cfg_sk.bn},{cfg_sk.bk},nw{cfg_sk.nwave},st{cfg_sk.stages}>"
+                              f" sw{cfg_sk.swizzle} split{cfg_sk.split} on {sk[0]}x{sk[1]}x{sk[2]}", "avg_us": round(us_sk, 2)}
 
     # ---- pick vs exhaustive search over the frozen grid (same timing protocol for both) --------
     extra = {}
@@ -209,7 +302,22 @@ def main():
     mean_ns, p99_ns = wt.wt_select_bench(ctx, shapes, repeats=50)
     extra["select_us_mean"] = round(mean_ns / 1e3, 3)
     extra["select_us_p99"] = round(p99_ns / 1e3, 3)
-    extra["pct_of_mfma_peak_large"] = round(100.0 * ach / PEAK_BF16_TFLOPS, 2)
+    # (3) the large prefill shape, bf16 (the bench line's roofline block) and fp8; the sweep's buffers go first
+    bufs.clear()
+    del dA, dB, dC
+    torch.cuda.empty_cache()
+    roofline = large_prefill_leg(wt, wt_synth, torch, np, in_type, ctx, stream)
+    extra["pct_of_mfma_peak_large"] = round(100.0 * roofline["frac"], 2)
+    try:
+        ctx8 = wt.wt_create(0, wt.WT_FP8_E4M3, out_type)
+        try:
+            extra["table_fp8"] = get_table(wt, ctx8, wt.WT_FP8_E4M3, out_type, torch)
+            extra["roofline_fp8"] = large_prefill_leg(wt, wt_synth, torch, np, wt.WT_FP8_E4M3, ctx8, stream)
+        finally:
+            wt.wt_destroy(ctx8)
+    except wt.WtError as e:
+        log(f"[bench] fp8 large-prefill leg skipped: {e}")
+    extra["small_case"] = small_case_leg(wt, wt_synth, torch, np, ctx)
 
     out = {"metric": "GEMM TFLOP/s as % of exhaustive-best config and of MFMA peak; select us",
            "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
@@ -219,7 +327,7 @@ def main():
                                   "(N,K) in {(4096,4096),(11008,4096),(4096,11008)}, bf16 in, fp32 accumulate, bf16 out; "
                                   "config per shape from wt_select", "table": table_src,
                       "configs_in_grid": wt.wt_config_count(ctx)},
-           "roofline": roofline}
+           "roofline": roofline, "roofline_sweep_dominant": roofline_sweep, "roofline_hbm": roofline_hbm}
     out.update(extra)
     out["attention"] = attention_extra(wt, torch)
     if not a.no_cpu:
