@@ -167,6 +167,22 @@ int wt_set_capacity_mode(wt_ctx* ctx, int mode);
 int wt_gemm(wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
             const float* scaleA, const float* scaleB, wt_cfg cfg, void* hip_stream);
 
+/* For callers that cannot allocate device memory -- code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc: wt_gemm with the split-K partial tiles and arrival counters kept in a static device array
+ * of the library (WT_NOALLOC_WS_FLOATS fp32 elements + WT_NOALLOC_MAX_TILES counters, 64 MiB + 128 KiB, held by
+ * every GPU the library runs on until the process ends) instead of the context's workspace.  Same arguments, same
+ * results bit for bit as wt_gemm.  The call itself allocates nothing on host or device and does not synchronise;
+ * the array's address on the context's GPU is looked up once, by wt_create (WT_ERR_HIP here if that failed).
+ * WT_ERR_INFEASIBLE when a split-K configuration's partial tiles exceed the array: ceil(M/bm)*ceil(N/bn)*split*bm*bn
+ * > WT_NOALLOC_WS_FLOATS or more than WT_NOALLOC_MAX_TILES output tiles.  Unsplit configurations use no scratch and
+ * have no such limit.  All calls on one GPU -- from any context, on any stream -- share that GPU's array: a
+ * split-K launch first zeroes its tiles' counters (a small kernel on hip_stream), and two split-K launches that
+ * overlap in time on one GPU race on the array; order them on one stream. */
+#define WT_NOALLOC_WS_FLOATS (1 << 24)
+#define WT_NOALLOC_MAX_TILES (1 << 15)
+int wt_gemm_noalloc(wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
+                    const float* scaleA, const float* scaleB, wt_cfg cfg, void* hip_stream);
+
 /* Launch policy (Sec. 3.2, note on persistent kernels: the launched grid is clamped to what the device holds
  * at once while G remains the logical task count).  on = 1: every later launch of this context starts
  * min(G, 256 x resident blocks per CU) blocks and block b runs tasks b, b + grid, b + 2*grid, ... of the same

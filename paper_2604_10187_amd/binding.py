@@ -22,6 +22,7 @@ WT_OUT_F32, WT_OUT_BF16 = 0, 1
 WT_MODEL_WAVE_BILINEAR, WT_MODEL_LINEAR, WT_MODEL_STEP = 0, 1, 2
 WT_CAP_CU_TIMES_OCC, WT_CAP_CU_ONLY = 0, 1
 WT_SPLITK_WS_FLOATS, WT_SPLITK_MAX_TILES, WT_MAX_ANCHORS = 1 << 26, 1 << 16, 8   # as #defined in wt.h
+WT_NOALLOC_WS_FLOATS, WT_NOALLOC_MAX_TILES = 1 << 24, 1 << 15
 
 
 class wt_cfg(C.Structure):
@@ -92,6 +93,7 @@ def lib():
             "wt_set_persistent": [vp, C.c_int],
             "wt_tile_coords": [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)],
             "wt_gemm": [vp, i64, i64, i64, vp, vp, vp, vp, vp, wt_cfg, vp],
+            "wt_gemm_noalloc": [vp, i64, i64, i64, vp, vp, vp, vp, vp, wt_cfg, vp],
             "wt_gemm_grouped": [vp, i32, vp, i64, i64, i64, vp, vp, vp, vp, vp, wt_cfg, vp],
             "wt_time_gemm_grouped": [vp, i32, vp, i64, i64, i64, vp, vp, vp, vp, vp, wt_cfg, C.c_int, C.c_int, vp,
                                      C.POINTER(C.c_double)],
@@ -126,7 +128,7 @@ def lib():
 
 
 EXPORTS = ("wt_create", "wt_destroy", "wt_last_hip_error", "wt_status_string", "wt_config_count", "wt_config_get",
-           "wt_config_find", "wt_key_count", "wt_key_set_occ", "wt_set_capacity_mode", "wt_set_persistent", "wt_tile_coords", "wt_gemm", "wt_gemm_grouped",
+           "wt_config_find", "wt_key_count", "wt_key_set_occ", "wt_set_capacity_mode", "wt_set_persistent", "wt_tile_coords", "wt_gemm", "wt_gemm_noalloc", "wt_gemm_grouped",
            "wt_time_gemm_grouped", "wt_wave_count_grouped", "wt_select_grouped", "wt_wave_count", "wt_sample_grid",
            "wt_sample_plan", "wt_profile_sparse", "wt_time_gemm", "wt_mfma_ceiling", "wt_fit", "wt_select", "wt_predict_us",
            "wt_select_bench", "wt_save", "wt_load", "wt_attn", "wt_time_attn", "wt_attn_block_coords",
@@ -228,6 +230,11 @@ def wt_tile_coords(tiles_m, tiles_n, swizzle, block):
 def wt_gemm(ctx, M, N, K, A, B, Cout, cfg, scaleA=None, scaleB=None, stream=None):
     _check(lib().wt_gemm(ctx, M, N, K, _ptr(A), _ptr(B), _ptr(Cout), _ptr(scaleA), _ptr(scaleB), cfg,
                          _stream(stream)), "wt_gemm")
+
+
+def wt_gemm_noalloc(ctx, M, N, K, A, B, Cout, cfg, scaleA=None, scaleB=None, stream=None):
+    _check(lib().wt_gemm_noalloc(ctx, M, N, K, _ptr(A), _ptr(B), _ptr(Cout), _ptr(scaleA), _ptr(scaleB), cfg,
+                                 _stream(stream)), "wt_gemm_noalloc")
 
 
 def wt_gemm_grouped(ctx, groups, offsets, M_total, N, K, A, B, Cout, cfg, scaleA=None, scaleB=None, stream=None):

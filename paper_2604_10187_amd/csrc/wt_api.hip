@@ -4,6 +4,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -13,7 +14,52 @@
 
 using namespace wt;
 
+// Device memory for callers that cannot allocate (wt_gemm_noalloc): split-K partial tiles, then the arrival
+// counters.  Every GPU the library runs on holds its own copy until the process ends.  In host code the name
+// `scratch` is only a handle for hipGetSymbolAddress; the address each device uses is in g_scratch_ptr[device].
+constexpr size_t kStaticWsFloats = WT_NOALLOC_WS_FLOATS;
+constexpr size_t kStaticTiles = WT_NOALLOC_MAX_TILES;
+constexpr size_t kStaticBytes = kStaticWsFloats * sizeof(float) + kStaticTiles * sizeof(int);
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};   // per device: address of that device's copy of `scratch`
+
+// Called with `device` current (wt_create).  Returns the device's address of the static array, or NULL with the
+// HIP error in *err.
+void* static_scratch_for(int device, hipError_t* err) {
+    *err = hipSuccess;
+    if (device < 0 || device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[device]) {
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            *err = e != hipSuccess ? e : hipErrorInvalidSymbol;
+            return nullptr;
+        }
+        g_scratch_ptr[device] = ptr;
+    }
+    return g_scratch_ptr[device];
+}
+
+// Arrival counters of the tiles a launch is about to use, set to zero on the launch's stream (a kernel, not a
+// memset node: the call may be under graph capture).
+__global__ void zero_ints(int* p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+// Where a launch keeps its split-K partial tiles and counters, and how much room there is.
+struct Workspace {
+    float* ws;
+    int* counters;
+    int64_t ws_elems, max_tiles;
+};
 
 #define WT_HIP(ctx, call)                     \
     do {                                      \
@@ -78,8 +124,10 @@ int launch_attn(wt_ctx* ctx, const Config& c, const Problem& p, hipStream_t stre
 
 constexpr int kMaxGroups = 1024;
 
-int launch(wt_ctx* ctx, const Config& c, const Problem& p, hipStream_t stream) {
+int launch(wt_ctx* ctx, const Config& c, const Problem& p, hipStream_t stream, const Workspace* alt = nullptr) {
     if (ctx->in_type == WT_ATTN_BF16) return launch_attn(ctx, c, p, stream);
+    const Workspace own{ctx->ws, ctx->counters, kWsElems, kMaxSplitTiles};
+    const Workspace& W = alt ? *alt : own;
     const Key& key = ctx->keys[c.res.key_id];
     int64_t tiles_m = ceil_div64(p.M, c.cfg.bm);
     const int64_t tiles_n = ceil_div64(p.N, c.cfg.bn);
@@ -90,7 +138,8 @@ int launch(wt_ctx* ctx, const Config& c, const Problem& p, hipStream_t stream) {
     }
     const int64_t tiles = tiles_m * tiles_n, G = tiles << key.sh_s;
     if (G > 0x7FFFFFFF) return WT_ERR_INVALID_ARG;
-    if (!key_fits(key, tiles)) return WT_ERR_INFEASIBLE;
+    if (key.split > 1 && (tiles > W.max_tiles || ((tiles << key.sh_s) << (key.sh_m + key.sh_n)) > W.ws_elems))
+        return WT_ERR_INFEASIBLE;
     GemmArgs args;
     args.A = p.A; args.B = p.B; args.C = p.C; args.scaleA = p.sA; args.scaleB = p.sB;
     args.M = (int)p.M; args.N = (int)p.N; args.K = (int)p.K;
@@ -99,15 +148,21 @@ int launch(wt_ctx* ctx, const Config& c, const Problem& p, hipStream_t stream) {
     args.splits = key.split;
     // each block of a split tile walks L = ceil(K / (S*bk)) k-tiles
     args.k_per_split = (int)(ceil_div64(p.K, (int64_t)key.bk * key.split) * key.bk);
-    args.ws = ctx->ws;
-    args.counters = ctx->counters;
+    args.ws = W.ws;
+    args.counters = W.counters;
     args.group_offsets = p.groups > 0 ? p.offsets : nullptr;
     args.groups = p.groups;
     args.vgrid = (int)G;
     // persistent launch: as many blocks as the device holds at once, each walking the task list with that stride
     const int64_t resident = (int64_t)kNumCU * std::max(1, c.occ_persistent);
     const int64_t grid = ctx->persistent ? std::min(G, resident) : G;
-    if (key.split > 1 && (!ctx->ws || !ctx->counters)) return WT_ERR_NO_DEVICE;
+    if (key.split > 1 && (!W.ws || !W.counters)) return WT_ERR_NO_DEVICE;
+    if (alt && key.split > 1) {
+        // the static array keeps whatever the last call left: this launch's counters start at zero
+        const int n = (int)tiles;
+        hipLaunchKernelGGL(zero_ints, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, W.counters, n);
+        WT_HIP(ctx, hipGetLastError());
+    }
     void* params[] = {&args};
     WT_HIP(ctx, hipLaunchKernel(ctx->persistent ? c.fn_persistent : c.fn, dim3((unsigned)grid), dim3((unsigned)(c.cfg.nwave * 64)), params,
                                 (size_t)c.res.lds_bytes, stream));
@@ -318,6 +373,11 @@ int wt_create(wt_ctx** out, int device, int in_type, int out_type) {
         if (e == hipSuccess) e = hipEventCreate(&e1);
         if (e != hipSuccess) { delete ctx; return WT_ERR_HIP; }
         ctx->ev_start = e0; ctx->ev_stop = e1;
+        {   // this device's copy of the static scratch array (wt_gemm_noalloc); a failure is reported by that call
+            hipError_t es = hipSuccess;
+            ctx->static_scratch = static_scratch_for(device, &es);
+            if (!ctx->static_scratch) ctx->last_hip = (int)es;
+        }
         // split-K workspace: partial tiles, then the arrival counters (zero now; every launch leaves them zero)
         if (in_type != WT_ATTN_BF16) {  // attention kernels use no workspace
             void* ws = nullptr;
@@ -400,6 +460,18 @@ int wt_gemm(wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, const v
     const int rc = check_gemm_args(ctx, p, cfg, &id);
     if (rc != WT_OK) return rc;
     return launch(ctx, ctx->cfgs[id], p, (hipStream_t)hip_stream);
+}
+
+int wt_gemm_noalloc(wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
+                    const float* scaleA, const float* scaleB, wt_cfg cfg, void* hip_stream) {
+    int id = -1;
+    const Problem p{M, N, K, A, B, C, scaleA, scaleB};
+    const int rc = check_gemm_args(ctx, p, cfg, &id);
+    if (rc != WT_OK) return rc;
+    if (!ctx->static_scratch) return WT_ERR_HIP;   // hipGetSymbolAddress failed at wt_create (wt_last_hip_error)
+    float* base = static_cast<float*>(ctx->static_scratch);
+    const Workspace w{base, reinterpret_cast<int*>(base + kStaticWsFloats), (int64_t)kStaticWsFloats, (int64_t)kStaticTiles};
+    return launch(ctx, ctx->cfgs[id], p, (hipStream_t)hip_stream, &w);
 }
 
 int wt_time_gemm(wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,

@@ -94,6 +94,7 @@ struct wt_ctx {
     void* ev_stop = nullptr;
     float* ws = nullptr;       // device: split-K partial tiles (kWsElems floats), then the counters
     int* counters = nullptr;   // device: kMaxSplitTiles ints, zero between launches
+    void* static_scratch = nullptr;  // device: this GPU's copy of the library's static scratch array (wt_gemm_noalloc)
 };
 
 namespace wt {
