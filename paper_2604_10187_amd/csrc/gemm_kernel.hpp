@@ -187,6 +187,9 @@ struct GemmTraits {
     // loads of k-tile t+ST-1 ride along the MFMAs of k-tile t); with two stages it has to follow the
     // barrier inside the last k-step (k-tile t+ST then rides along the last MFMAs of k-tile t).
     static constexpr bool SPREAD = ST >= 3;
+    // 256 accumulators per lane (one wavefront per SIMD): the MFMAs are issued from inline asm that accumulates in
+    // place in the accumulation registers
+    static constexpr bool ASMACC = (IN == 0) && (MI == 16) && (FM * FN == 64) && (WK == 1);
     static_assert(BK % KS == 0, "BK must hold whole MFMA k-steps");
     static_assert(KSTEPS % WK == 0, "k-steps divide evenly over the WK wavefronts");
     static_assert((BM * CPR) % kWave == 0 && (BN * CPR) % kWave == 0, "whole 1 KiB loads");
@@ -402,6 +405,8 @@ __device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_
             if constexpr (IN == 0) {
                 if constexpr (T::MI == 32)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+                else if constexpr (T::ASMACC)
+                    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(f.a[i]), "v"(f.b[j]));
                 else
                     acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
             } else {
@@ -515,6 +520,7 @@ __device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_
             for (; kt + AHEAD < L_full; ++kt) tile_body(kt, std::false_type{});
             for (; kt < L; ++kt) tile_body(kt, std::true_type{});
             wait_vmcnt<0>();
+            if constexpr (T::ASMACC) asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
         }
 
         // ---- reduction over the WK wavefronts of a sub-tile --------------------------------------

@@ -48,18 +48,32 @@ def reference(qb, kb, vb, causal, scale=SCALE):
     return oa.attention(dec(qb), dec(kb), dec(vb), scale, causal)
 
 
-WORST = {"err": 0.0, "what": ""}    # largest scaled error seen in this session, printed by the last test
+# largest scaled errors seen in this session (printed by the last test): scaled by the rms of everything compared,
+# and by the rms of the element's own output row (one query of one head, 128 values)
+WORST = {"err": 0.0, "what": "", "err_row": 0.0, "what_row": ""}
+
+
+def _scaled(diff, want, rms):
+    scale = np.maximum(np.abs(want), rms)
+    return np.divide(diff, scale, out=np.where(diff > 0, np.inf, 0.0), where=scale > 0)   # all-zero reference: exact
 
 
 def check(got, want, what):
+    """Both bounds must hold: every element within 2e-2 of max(|O_ref|, rms over all compared elements), and within
+    2e-2 of max(|O_ref|, rms of its own 128-value output row).  The second is the tighter one wherever rows differ
+    in scale (under a causal mask a late row averages hundreds of keys and is ten times smaller than an early one)."""
     assert np.isfinite(got).all(), f"{what}: non-finite output"
-    scale = np.maximum(np.abs(want), math.sqrt(float(np.mean(np.square(want)))) if want.size else 0.0)
+    if not want.size:
+        return
     diff = np.abs(got - want)
-    err = np.divide(diff, scale, out=np.where(diff > 0, np.inf, 0.0), where=scale > 0)   # all-zero reference: exact
-    worst = float(err.max()) if err.size else 0.0
-    if worst > WORST["err"]:
-        WORST.update(err=worst, what=what)
-    assert worst <= ELEM_TOL, f"{what}: max scaled error {worst:.4g} at {np.unravel_index(err.argmax(), err.shape)}"
+    err = _scaled(diff, want, math.sqrt(float(np.mean(np.square(want)))))
+    err_row = _scaled(diff, want, np.sqrt(np.mean(np.square(want), axis=-1, keepdims=True)))
+    if float(err.max()) > WORST["err"]:
+        WORST.update(err=float(err.max()), what=what)
+    if float(err_row.max()) > WORST["err_row"]:
+        WORST.update(err_row=float(err_row.max()), what_row=what)
+    assert err.max() <= ELEM_TOL, f"{what}: max scaled error {err.max():.4g} at {np.unravel_index(err.argmax(), err.shape)}"
+    assert err_row.max() <= ELEM_TOL, f"{what}: max row-scaled error {err_row.max():.4g} at {np.unravel_index(err_row.argmax(), err_row.shape)}"
 
 
 def test_every_config_is_launchable(ctx):
@@ -256,5 +270,6 @@ def test_argument_errors(ctx):
 
 def test_zz_report_worst_scaled_error():
     """Not a check of its own: prints the largest |O - O_ref| / max(|O_ref|, rms) the checks above saw."""
-    note(f"attention parity: worst scaled error {WORST['err']:.3e} ({WORST['what']}); bound {ELEM_TOL}")
-    assert WORST["err"] <= ELEM_TOL
+    note(f"attention parity: worst scaled error {WORST['err']:.3e} ({WORST['what']}); "
+         f"worst row-scaled error {WORST['err_row']:.3e} ({WORST['what_row']}); bound {ELEM_TOL}")
+    assert WORST["err"] <= ELEM_TOL and WORST["err_row"] <= ELEM_TOL
