@@ -190,6 +190,19 @@ struct GemmTraits {
     // 256 accumulators per lane (one wavefront per SIMD): the MFMAs are issued from inline asm that accumulates in
     // place in the accumulation registers
     static constexpr bool ASMACC = (IN == 0) && (MI == 16) && (FM * FN == 64) && (WK == 1);
+    // Epilogue through LDS (when a sub-tile row of C is at least one 128-byte line and the staging fits the
+    // workgroup's LDS): the MFMA operands are swapped so that a lane holds four consecutive columns of one row,
+    // each wavefront parks one row of MFMA tiles (MI rows x TN columns, converted to the output type) in its own
+    // LDS region and reads it back row-contiguous, 16 bytes per lane, so that C is written in whole lines.
+    // Rows are padded to a stride of EPI_Q (mod 64) dwords, which spreads both access patterns over the banks.
+    static constexpr int OSIZE = OUT == 0 ? 4 : 2;
+    static constexpr int EPI_ROW = TN * OSIZE;                               // bytes of one sub-tile row
+    static constexpr int EPI_Q = (kWave / MI) * OSIZE;                       // wanted row stride in dwords, mod 64
+    static constexpr int EPI_STRIDE = EPI_ROW + 4 * ((EPI_Q - EPI_ROW / 4) & 63);   // bytes
+    static constexpr int EPI_WAVE_BYTES = MI * EPI_STRIDE;
+    static constexpr bool LDS_EPI = (WK == 1) && (EPI_ROW >= 128) && (NW * EPI_WAVE_BYTES <= LDS_BYTES);
+    static constexpr int EPI_LPR = EPI_ROW / 16;                             // lanes that cover one row, 16 bytes each
+    static constexpr int EPI_READS = MI * EPI_ROW / 1024;                    // 1 KiB wavefront reads per MFMA tile row
     static_assert(BK % KS == 0, "BK must hold whole MFMA k-steps");
     static_assert(KSTEPS % WK == 0, "k-steps divide evenly over the WK wavefronts");
     static_assert((BM * CPR) % kWave == 0 && (BN * CPR) % kWave == 0, "whole 1 KiB loads");
@@ -402,19 +415,25 @@ __device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_
             for (int j = 0; j < T::FN; ++j) f.b[j] = read_frag(stage, BM + wn * T::TN + j * T::MI + frow, ks);
         };
         auto mfma = [&](const Frags& f, int i, int j) {
+            // x = the MFMA's row operand, y = its column operand.  As (A, B) a lane holds one column of the C tile
+            // and groups of four consecutive rows; swapped, (B, A), it holds one row (lane % MI) and groups of four
+            // consecutive columns (16x16: 4*(lane/16) + e; 32x32: 8*(e/4) + 4*(lane/32) + e%4).  Products and
+            // summation order are the same either way.
+            const frag_t& x = T::LDS_EPI ? f.b[j] : f.a[i];
+            const frag_t& y = T::LDS_EPI ? f.a[i] : f.b[j];
             if constexpr (IN == 0) {
                 if constexpr (T::MI == 32)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, acc[i][j], 0, 0, 0);
                 else if constexpr (T::ASMACC)
-                    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(f.a[i]), "v"(f.b[j]));
+                    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(x), "v"(y));
                 else
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, y, acc[i][j], 0, 0, 0);
             } else {
                 // cbsz = blgp = 0 select e4m3 for both operands; unit block scales
                 if constexpr (T::MI == 32)
-                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f.a[i], f.b[j], acc[i][j], 0, 0, 0, 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(x, y, acc[i][j], 0, 0, 0, 0, 0, 0);
                 else
-                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(f.a[i], f.b[j], acc[i][j], 0, 0, 0, 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(x, y, acc[i][j], 0, 0, 0, 0, 0, 0);
             }
         };
         auto mma = [&](const Frags& f) {
@@ -619,24 +638,94 @@ __device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_
         float scale = 1.0f;
         if constexpr (IN == 1) scale = args.scaleA[0] * args.scaleB[0];
         const int M = m_end, N = args.N;
+        if constexpr (T::LDS_EPI) {
+            typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+            constexpr int EPV = 16 / T::OSIZE;           // elements per 16-byte piece
+            constexpr int NGRP = T::ACC / 4;             // column groups a lane holds per MFMA tile
+            // rows of C keep 16-byte alignment when N is a multiple of EPV and C itself is aligned (wave-uniform)
+            const bool vec_ok = (N % EPV == 0) && ((reinterpret_cast<uintptr_t>(args.C) & 15) == 0);
+            if (!vec_ok) {
+                // rows of C are not 16-byte aligned: element by element straight from the registers
+                const int lrow = lane % T::MI, lcol = 4 * (lane / T::MI);
     #pragma unroll
-        for (int i = 0; i < T::FM; ++i) {
+                for (int i = 0; i < T::FM; ++i) {
+                    const int row = row0 + wm * T::TM + i * T::MI + lrow;
     #pragma unroll
-            for (int j = 0; j < T::FN; ++j) {
-                const int col = col0 + wn * T::TN + j * T::MI + (lane % T::MI);
+                    for (int j = 0; j < T::FN; ++j) {
     #pragma unroll
-                for (int e = 0; e < T::ACC; ++e) {
-                    // 32x32: row = 8*(e/4) + 4*(lane/32) + e%4 ; 16x16: row = 4*(lane/16) + e
-                    const int rin = (T::MI == 32) ? (8 * (e / 4) + 4 * (lane / 32) + (e % 4)) : (4 * (lane / 16) + e);
-                    const int row = row0 + wm * T::TM + i * T::MI + rin;
-                    if (row < M && col < N) {
-                        float v = acc[i][j][e];
-                        if constexpr (IN == 1) v *= scale;
-                        const int64_t idx = static_cast<int64_t>(row) * N + col;
+                        for (int e = 0; e < T::ACC; ++e) {
+                            const int col = col0 + wn * T::TN + j * T::MI + 8 * (e / 4) + lcol + (e % 4);
+                            if (row < M && col < N) {
+                                float v = acc[i][j][e];
+                                if constexpr (IN == 1) v *= scale;
+                                const int64_t idx = static_cast<int64_t>(row) * N + col;
+                                if constexpr (OUT == 0)
+                                    static_cast<float*>(args.C)[idx] = v;
+                                else
+                                    static_cast<__bf16*>(args.C)[idx] = static_cast<__bf16>(v);
+                            }
+                        }
+                    }
+                }
+                return;
+            }
+            __syncthreads();   // every wavefront is past its last read of the stages (and of the split-K flag)
+            char* const mine = smem + wv * T::EPI_WAVE_BYTES;
+            char* const wr = mine + (lane % T::MI) * T::EPI_STRIDE + (4 * (lane / T::MI)) * T::OSIZE;
+    #pragma unroll
+            for (int i = 0; i < T::FM; ++i) {
+    #pragma unroll
+                for (int j = 0; j < T::FN; ++j) {
+    #pragma unroll
+                    for (int g = 0; g < NGRP; ++g) {
+                        float v[4];
+    #pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            v[e] = acc[i][j][4 * g + e];
+                            if constexpr (IN == 1) v[e] *= scale;
+                        }
+                        char* dst = wr + (j * T::MI + 8 * g) * T::OSIZE;
                         if constexpr (OUT == 0)
-                            static_cast<float*>(args.C)[idx] = v;
+                            *reinterpret_cast<f32x4*>(dst) = f32x4{v[0], v[1], v[2], v[3]};
                         else
-                            static_cast<__bf16*>(args.C)[idx] = static_cast<__bf16>(v);
+                            *reinterpret_cast<bf16x4*>(dst) = bf16x4{static_cast<__bf16>(v[0]), static_cast<__bf16>(v[1]),
+                                                                      static_cast<__bf16>(v[2]), static_cast<__bf16>(v[3])};
+                    }
+                }
+                // (LDS serves one wavefront's accesses in order: the reads below see the writes above)
+    #pragma unroll
+                for (int t = 0; t < T::EPI_READS; ++t) {
+                    const int p = t * kWave + lane;
+                    const int r = p / T::EPI_LPR, k = p % T::EPI_LPR;
+                    const f32x4 piece = *reinterpret_cast<const f32x4*>(mine + r * T::EPI_STRIDE + k * 16);
+                    const int row = row0 + wm * T::TM + i * T::MI + r;
+                    const int col = col0 + wn * T::TN + k * EPV;
+                    // col and N are multiples of EPV here, so a piece that starts inside the matrix lies wholly inside
+                    if (row < M && col < N)
+                        *reinterpret_cast<f32x4*>(static_cast<char*>(args.C) + (static_cast<int64_t>(row) * N + col) * T::OSIZE) = piece;
+                }
+                wait_lgkmcnt0();   // the pieces are in registers before the next tile row overwrites the region
+            }
+        } else {
+    #pragma unroll
+            for (int i = 0; i < T::FM; ++i) {
+    #pragma unroll
+                for (int j = 0; j < T::FN; ++j) {
+                    const int col = col0 + wn * T::TN + j * T::MI + (lane % T::MI);
+    #pragma unroll
+                    for (int e = 0; e < T::ACC; ++e) {
+                        // 32x32: row = 8*(e/4) + 4*(lane/32) + e%4 ; 16x16: row = 4*(lane/16) + e
+                        const int rin = (T::MI == 32) ? (8 * (e / 4) + 4 * (lane / 32) + (e % 4)) : (4 * (lane / 16) + e);
+                        const int row = row0 + wm * T::TM + i * T::MI + rin;
+                        if (row < M && col < N) {
+                            float v = acc[i][j][e];
+                            if constexpr (IN == 1) v *= scale;
+                            const int64_t idx = static_cast<int64_t>(row) * N + col;
+                            if constexpr (OUT == 0)
+                                static_cast<float*>(args.C)[idx] = v;
+                            else
+                                static_cast<__bf16*>(args.C)[idx] = static_cast<__bf16>(v);
+                        }
                     }
                 }
             }
