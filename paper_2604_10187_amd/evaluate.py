@@ -48,9 +48,10 @@ class Exhaustive:
     """Times every configuration of the registry on one shape; prunes a configuration after one
     timed launch if it is more than `prune` times slower than the best so far."""
 
-    def __init__(self, ctx, torch, in_type, out_type, prune=2.5, warmup=3, iters=5):
+    def __init__(self, ctx, torch, in_type, out_type, prune=2.5, warmup=3, iters=5, refine=0):
         self.ctx, self.torch, self.in_type, self.out_type = ctx, torch, in_type, out_type
-        self.prune, self.warmup, self.iters = prune, warmup, iters
+        self.prune, self.warmup, self.iters, self.refine = prune, warmup, iters, refine
+        self.first_pass = {}
         self.cfgs = [wt.wt_config_get(ctx, i) for i in range(wt.wt_config_count(ctx))]
         self.stream = torch.cuda.current_stream()
         self.launches = 0
@@ -82,6 +83,19 @@ class Exhaustive:
             self.gpu_s += (self.warmup + self.iters) * t * 1e-6
             times[i] = t
             best = min(best, t)
+        # One 3+5 measurement has a few per cent of scatter (clock state, neighbours in the timing order), and the
+        # search takes the minimum over up to 240 of them.  With refine > 0 the `refine` fastest configurations and
+        # the ones in `must` are measured a second time, in reverse order, and each keeps the smaller of its two
+        # means; the first-pass times stay available in self.first_pass.
+        self.first_pass = dict(times)
+        if self.refine > 0:
+            again = sorted(times, key=times.get)[: self.refine] + [i for i in must if i in times]
+            for i in reversed(list(dict.fromkeys(again))):
+                c, _ = self.cfgs[i]
+                t = wt.wt_time_gemm(self.ctx, M, N, K, A, B, C, c, self.warmup, self.iters, sA, sB, self.stream)
+                self.launches += self.warmup + self.iters
+                self.gpu_s += (self.warmup + self.iters) * t * 1e-6
+                times[i] = min(times[i], t)
         return times
 
 
@@ -100,7 +114,9 @@ def _pick_vs_best(ctx, ex, shapes):
         times = ex.run(M, N, K, must=(pick.id,))
         best_id = min(times, key=times.get)
         bc = ex.cfgs[best_id][0]
+        fp = ex.first_pass
         rows.append({"M": M, "N": N, "K": K, "pick": list(pick.astuple()), "pick_us": times[pick.id],
+                     "frac_single_pass": min(fp.values()) / fp[pick.id],
                      "best": list(bc.astuple()), "best_us": times[best_id], "frac": times[best_id] / times[pick.id],
                      "pick_tflops": 2.0 * M * N * K / times[pick.id] / 1e6,
                      "best_tflops": 2.0 * M * N * K / times[best_id] / 1e6,
@@ -109,7 +125,11 @@ def _pick_vs_best(ctx, ex, shapes):
         if n % 10 == 0:
             _log(f"[eval] {n + 1}/{len(shapes)} shapes, {time.time() - t0:.0f}s, last frac {rows[-1]['frac']:.3f}")
     fr = np.array([r["frac"] for r in rows])
-    summary = {"n_shapes": len(rows), "geomean_frac": float(np.exp(np.mean(np.log(fr)))), "min_frac": float(fr.min()),
+    f1 = np.array([r["frac_single_pass"] for r in rows])
+    summary = {"n_shapes": len(rows), "refine": ex.refine,
+               "single_pass": {"geomean_frac": float(np.exp(np.mean(np.log(f1)))), "min_frac": float(f1.min()),
+                               "p5_frac": float(np.percentile(f1, 5)), "frac_ge_95": float(np.mean(f1 >= 0.95))},
+               "geomean_frac": float(np.exp(np.mean(np.log(fr)))), "min_frac": float(fr.min()),
                "p5_frac": float(np.percentile(fr, 5)), "mean_frac": float(fr.mean()),
                "frac_ge_95": float(np.mean(fr >= 0.95)), "exhaustive_launches": ex.launches,
                "exhaustive_gpu_seconds": ex.gpu_s}
@@ -120,7 +140,7 @@ def cmd_sweep(a, torch):
     import wt_synth
 
     ctx, path = _open_ctx(a, torch)
-    ex = Exhaustive(ctx, torch, a.in_type, a.out_type, prune=a.prune)
+    ex = Exhaustive(ctx, torch, a.in_type, a.out_type, prune=a.prune, refine=a.refine)
     rows, summary = _pick_vs_best(ctx, ex, wt_synth.sweep_shapes())
     return {"workload": "LLM-projection sweep (27 shapes)", "table": path, "summary": summary, "rows": rows}
 
@@ -139,7 +159,7 @@ def cmd_stream(a, torch):
     for sh in draws:
         weight[sh] = weight.get(sh, 0) + 1
     sample = sorted(weight)
-    ex = Exhaustive(ctx, torch, a.in_type, a.out_type, prune=a.prune)
+    ex = Exhaustive(ctx, torch, a.in_type, a.out_type, prune=a.prune, refine=a.refine)
     rows, summary = _pick_vs_best(ctx, ex, sample)
     wts = np.array([weight[(r["M"], r["N"], r["K"])] for r in rows], dtype=float)
     fr = np.array([r["frac"] for r in rows])
@@ -200,9 +220,10 @@ def cmd_large(a, torch):
     out = {"workload": f"large prefill GEMM {M}x{N}x{K}, bf16 out", "results": []}
     for in_type, name, peak in ((wt.WT_BF16, "bf16", 2500.0), (wt.WT_FP8_E4M3, "fp8_e4m3", 5000.0)):
         ctx = wt.wt_create(0, in_type, wt.WT_OUT_BF16)
-        ex = Exhaustive(ctx, torch, in_type, wt.WT_OUT_BF16, prune=1.5)
-        times = ex.run(M, N, K)
-        top = sorted(times.items(), key=lambda kv: kv[1])[:5]
+        ex = Exhaustive(ctx, torch, in_type, wt.WT_OUT_BF16, prune=1.5, refine=8)
+        ex.run(M, N, K)            # a first pass only to bring the chip to its sustained clock: its times are dropped
+        times = ex.run(M, N, K)    # (the first configurations measured on an idle chip would otherwise read slow)
+        top = sorted(times.items(), key=lambda kv: kv[1])[:6]
         ceiling = wt.wt_mfma_ceiling(ctx, in_type, 20000, torch.cuda.current_stream())
         res = {"in": name, "nominal_peak_tflops": peak, "mfma_only_ceiling_tflops": ceiling, "top": []}
         for i, us in top:
@@ -492,6 +513,8 @@ def main(argv=None):
     ap.add_argument("--skew", type=float, default=1.0, help="grouped: routing probabilities ~ 1/rank^skew (0 = uniform)")
     ap.add_argument("--sample-seed", type=int, default=2005, help="stream: seed of the sampled draws")
     ap.add_argument("--prune", type=float, default=2.5)
+    ap.add_argument("--refine", type=int, default=0,
+                    help="sweep / stream: re-time the N fastest configurations and the pick, keep each one's smaller mean")
     ap.add_argument("--cfgs", type=lambda s: [tuple(int(x) for x in c.split(",")) for c in s.split(";")],
                     default=[(128, 128, 64, 4, 2, 0), (256, 256, 64, 8, 2, 0), (64, 64, 64, 4, 2, 0)])
     a = ap.parse_args(argv)

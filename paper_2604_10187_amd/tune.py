@@ -2,7 +2,7 @@
 
     python -m paper_2604_10187_amd.tune --out tables/mi355x_in0_out1.wt [--W 40 --I 4 ...]
         [--key-first a --key-count n --samples-out file.npy]      # profile a slice of keys only
-        [--fit-from a.npy b.npy ...]                              # fit saved records, no GPU
+        [--fit-from a.npy b.npy ...] [--records-out r.npz]        # fit saved records, no GPU
 
 Every step runs inside libwt (wt_profile_sparse, wt_fit, wt_save); this script only allocates the
 scratch buffers with torch and moves records between files.
@@ -23,6 +23,12 @@ TABLE_DIR = os.path.join(os.path.dirname(os.path.abspath(__file__)), "tables")
 # K = 8192..28672, and rows whose stride is a large power of two behave differently in HBM (channel
 # aliasing makes the rasterisation mode matter), which no anchor below 8192 shows.
 K_ANCHORS = (1024, 2048, 3072, 4096, 5120, 8192)
+# Second profiling pass of the shipped GEMM tables: two long-K anchors for the first waves only
+# (`--W 12 --k-anchors 16384 28672`, records merged with the first pass by --fit-from).  The serving shapes reach
+# K = 28672, 3.5 times beyond the last anchor above; up to 12 waves a bucket then holds eight loop anchors and is
+# interpolated in L instead of extrapolated.  Deeper waves of such K would take hours to profile and keep six.
+K_ANCHORS_LONG = (16384, 28672)
+W_LONG = 12
 # Attention contexts: KV-length multipliers of S_q in percent (Sec. 5.1: 1.0 to 3.0).
 KV_MULTIPLIERS = (100, 150, 200, 250, 300)
 
@@ -84,6 +90,9 @@ def main(argv=None):
     ap.add_argument("--W-split", type=int, default=8, help="split-K keys are profiled for the first W-split waves only (0 = all)")
     ap.add_argument("--samples-out", default=None)
     ap.add_argument("--fit-from", nargs="*", default=None)
+    ap.add_argument("--records-out", default=None,
+                    help="with --out: also write the fitted records and the keys' occupancy as one compressed .npz "
+                         "(arrays `samples`, `occ`), the form kept beside the shipped tables")
     ap.add_argument("--out", default=None)
     a = ap.parse_args(argv)
     attn = a.in_type == wt.WT_ATTN_BF16
@@ -122,6 +131,9 @@ def main(argv=None):
         os.makedirs(os.path.dirname(os.path.abspath(a.out)), exist_ok=True)
         wt.wt_save(ctx, a.out)
         print(f"[tune] fitted {len(recs)} records -> {a.out} ({os.path.getsize(a.out)} bytes)")
+        if a.records_out:
+            occ = np.array([wt.wt_config_get(ctx, 3 * k)[1].occ for k in range(wt.wt_key_count(ctx))], dtype=np.int32)
+            np.savez_compressed(a.records_out, samples=recs, occ=occ)
     wt.wt_destroy(ctx)
 
 

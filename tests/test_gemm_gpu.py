@@ -107,6 +107,36 @@ def test_bf16_output(ctx_bf16):
         assert og.max_scaled_err(got, want) <= 2.0 ** -8    # one bf16 rounding of an fp32 sum
 
 
+def test_unaligned_output_rows_and_pointer(ctx_f32, ctx_bf16):
+    """The line-wise epilogue needs 16-byte aligned rows of C; everything else falls back to element-wise stores.
+    Integer inputs (bit-exact) on kernels that stage C through LDS and on one that does not: N a multiple of 8 with C
+    16-byte aligned (line-wise path), the same C shifted by one element (pointer unaligned), N = 8k + 4 (bf16 rows
+    unaligned, fp32 rows aligned) and N odd; untouched guard elements before and after C stay NaN."""
+    keys = ((256, 256, 64, 4, 2, 0), (256, 256, 64, 8, 2, 2), (128, 128, 64, 4, 3, 1), (128, 64, 128, 4, 2, 0),
+            (64, 64, 64, 4, 2, 0), (16, 64, 128, 4, 2, 0), (128, 128, 64, 4, 3, 0, 2))
+    for ctx, dt in ((ctx_f32, torch.float32), (ctx_bf16, torch.bfloat16)):
+        for fields in keys:
+            cfg, _ = wt.wt_config_get(ctx, wt.wt_config_find(ctx, *fields))
+            for (M, N) in ((cfg.bm + 37, 2 * cfg.bn + 8), (cfg.bm + 37, cfg.bn + 12), (70, cfg.bn + 33)):
+                K = 2 * cfg.bk * cfg.split + 24
+                ab, bb = _bf16_case(M, N, K, 900 + N, "int")
+                want = torch.from_numpy(og.gemm_c(ab, bb).astype(np.float32))   # exact integers below 2^24
+                if dt == torch.bfloat16:
+                    want = want.to(torch.bfloat16).float()      # one round-to-nearest-even of the exact sum
+                dA = torch.from_numpy(ab.view(np.int16).copy()).cuda()
+                dB = torch.from_numpy(bb.view(np.int16).copy()).cuda()
+                for shift in (0, 1):
+                    note(f"epilogue paths cfg={cfg.astuple()} out={dt} shape={(M, N, K)} shift={shift}")
+                    buf = torch.full((M * N + 16,), float("nan"), dtype=dt, device="cuda")
+                    dC = buf[8 + shift: 8 + shift + M * N].view(M, N)
+                    assert (dC.data_ptr() % 16 == 0) == (shift == 0)
+                    wt.wt_gemm(ctx, M, N, K, dA, dB, dC, cfg, stream=torch.cuda.current_stream())
+                    torch.cuda.synchronize()
+                    assert torch.equal(dC.float().cpu(), want), f"{cfg} {dt} N={N} shift={shift}"
+                    guard = torch.cat([buf[: 8 + shift], buf[8 + shift + M * N:]])
+                    assert torch.isnan(guard).all(), "wrote outside C"
+
+
 def _split_configs(ctx):
     return [(c, r) for c, r in all_configs(ctx) if c.split > 1]
 
