@@ -76,28 +76,41 @@ constexpr uint32_t kOobOffset = 0x7FFFFFF0u;  // >= any num_records we set: read
 constexpr int kXcd = 8;
 constexpr int kGroupM = 8;
 
-// Grids of at most kGroupM tile rows are walked the same way under every mode: as one group, column by
-// column, each XCD taking a contiguous range.  On such grids row-major order is never the better one (the
-// XCDs would each stream every B panel), so the mode only distinguishes taller grids.
-__host__ __device__ __forceinline__ void tile_coords(int bid, int tiles_m, int tiles_n, int mode, int& tm, int& tn) {
-    if (mode == 0 && tiles_m > kGroupM) {
-        tm = bid / tiles_n;
-        tn = bid - tm * tiles_n;
+// Block rasterisation.  The modes are defined on a grid that is at least as wide as it is tall (rows <= cols) and
+// are mirrored -- rows and columns change roles -- on a taller one.  Every order sweeps the long side once per band of
+// the short side, so the operand that is read again for every band is the smaller of A and B (the one more likely to
+// stay in the memory-side cache), and a tall grid behaves like the wide grid of the transposed problem, which is the
+// kind of grid the near-square sampler (n_G >= m_G) profiles.
+//   mode 0      plain short-side-major order (column by column on a wide grid): XCD x takes every eighth tile;
+//   mode 1, 2   the sequence "bands of 4 (8) rows, each walked column by column" cut into eight contiguous ranges,
+//               XCD x taking the x-th: tiles that share panels run on the same XCD and meet in its L2.
+// Grids of at most kGroupM rows are walked the same way under every mode: as one band, each XCD a contiguous range.
+__host__ __device__ __forceinline__ void tile_coords_wide(int bid, int rows, int cols, int mode, int& r, int& c) {
+    if (mode == 0 && rows > kGroupM) {
+        c = bid / rows;
+        r = bid - c * rows;
         return;
     }
     // XCD x receives the workgroups with bid % 8 == x; hand it the x-th contiguous chunk of the sequence
-    const int total = tiles_m * tiles_n;
+    const int total = rows * cols;
     const int per = total / kXcd, rem = total - per * kXcd;
     const int xcd = bid % kXcd, local = bid / kXcd;
     const int id = xcd * per + (xcd < rem ? xcd : rem) + local;
-    const int rows = (mode == 1 && tiles_m > kGroupM) ? kGroupM / 2 : kGroupM;
-    const int group = rows * tiles_n;
+    const int band = (mode == 1 && rows > kGroupM) ? kGroupM / 2 : kGroupM;
+    const int group = band * cols;
     const int gid = id / group;
-    const int first_m = gid * rows;
-    const int gm = (tiles_m - first_m) < rows ? (tiles_m - first_m) : rows;
+    const int first = gid * band;
+    const int gm = (rows - first) < band ? (rows - first) : band;
     const int in_group = id - gid * group;
-    tm = first_m + in_group % gm;
-    tn = in_group / gm;
+    r = first + in_group % gm;
+    c = in_group / gm;
+}
+
+__host__ __device__ __forceinline__ void tile_coords(int bid, int tiles_m, int tiles_n, int mode, int& tm, int& tn) {
+    if (tiles_m > tiles_n)
+        tile_coords_wide(bid, tiles_n, tiles_m, mode, tn, tm);
+    else
+        tile_coords_wide(bid, tiles_m, tiles_n, mode, tm, tn);
 }
 
 __device__ __forceinline__ i32x4 make_rsrc(const void* base, uint32_t num_records) {

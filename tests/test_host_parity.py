@@ -456,30 +456,34 @@ def test_few_row_families_parity(ctx, tmp_path, row_fams):
 
 @pytest.mark.parametrize("tiles", [(1, 1), (1, 61), (3, 80), (5, 29), (7, 8), (16, 43), (38, 12), (64, 32), (9, 9)])
 def test_rasterisation_is_a_bijection(tiles):
-    """The kernel's block -> tile mapping, evaluated on the host: every mode visits every tile exactly
-    once; modes 1/2 hand each XCD (block index mod 8) a contiguous range of the grouped order; grids of at
-    most 8 tile rows are walked as a single group whatever the mode."""
+    """The kernel's block -> tile mapping, evaluated on the host: every mode visits every tile exactly once.  On a grid
+    at least as wide as tall, mode 0 is column-major and modes 1/2 hand each XCD (block index mod 8) a contiguous range
+    of the banded order (bands of 4 / 8 tile rows, column by column); grids of at most 8 rows are one band whatever the
+    mode; a taller grid is walked like the transposed one with rows and columns exchanged."""
     tm_n, tn_n = tiles
     total = tm_n * tn_n
     for sw in (0, 1, 2):
         seen = [wt.wt_tile_coords(tm_n, tn_n, sw, b) for b in range(total)]
         assert sorted(seen) == [(i, j) for i in range(tm_n) for j in range(tn_n)]
     modes = [[wt.wt_tile_coords(tm_n, tn_n, sw, b) for b in range(total)] for sw in (0, 1, 2)]
-    if tm_n > 8:     # tall grids: mode 0 is plain row-major and the three modes differ
-        assert modes[0] == [(b // tn_n, b % tn_n) for b in range(total)]
+    mirrored = tm_n > tn_n
+    short, long_ = min(tm_n, tn_n), max(tm_n, tn_n)
+    back = (lambda rc: (rc[1], rc[0])) if mirrored else (lambda rc: rc)      # (short index, long index) -> (tm, tn)
+    if short > 8:    # mode 0 runs down the short side first and the three modes differ
+        assert modes[0] == [back((b % short, b // short)) for b in range(total)]
         assert modes[0] != modes[1] != modes[2]
-    else:            # at most 8 tile rows: one group under every mode
+    else:            # at most 8 rows (columns, mirrored): one band under every mode
         assert modes[0] == modes[1] == modes[2]
-    rows = 8
-    order = []                                   # grouped order: groups of 8 tile rows, column by column
-    for g0 in range(0, tm_n, rows):
-        gm = min(rows, tm_n - g0)
-        order += [(g0 + i, j) for j in range(tn_n) for i in range(gm)]
     per, rem = divmod(total, 8)
-    for x in range(8):
-        mine = [wt.wt_tile_coords(tm_n, tn_n, 2, b) for b in range(x, total, 8)]
-        start = x * per + min(x, rem)
-        assert mine == order[start:start + len(mine)]
+    for sw, band in ((1, 4 if short > 8 else 8), (2, 8)):
+        order = []                               # banded order on the wide orientation
+        for g0 in range(0, short, band):
+            gm = min(band, short - g0)
+            order += [back((g0 + i, j)) for j in range(long_) for i in range(gm)]
+        for x in range(8):
+            mine = [wt.wt_tile_coords(tm_n, tn_n, sw, b) for b in range(x, total, 8)]
+            start = x * per + min(x, rem)
+            assert mine == order[start:start + len(mine)]
     with pytest.raises(wt.WtError):
         wt.wt_tile_coords(tm_n, tn_n, 3, 0)
     with pytest.raises(wt.WtError):
