@@ -115,7 +115,9 @@ def large_prefill_leg(wt, wt_synth, torch, np, in_type, ctx, stream):
     del a32, b32
     dC = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
     cfg = wt.wt_select(ctx, M, N, K)
-    us = wt.wt_time_gemm(ctx, M, N, K, dA, dB, dC, cfg, 3, 10, sA, sB, stream)
+    # The operands above were generated on the host, so the GPU has sat idle for seconds and its clock takes tens of
+    # milliseconds of load to come back up: warm up for that long before the timed launches.
+    us = wt.wt_time_gemm(ctx, M, N, K, dA, dB, dC, cfg, 40, 20, sA, sB, stream)
     ceiling = wt.wt_mfma_ceiling(ctx, in_type, 20000, stream)
     peak = PEAK_BF16_TFLOPS if in_type == wt.WT_BF16 else PEAK_FP8_TFLOPS
     ach = 2.0 * M * N * K / us / 1e6
