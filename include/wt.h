@@ -186,8 +186,13 @@ int wt_gemm_noalloc(wt_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A,
 /* Launch policy (Sec. 3.2, note on persistent kernels: the launched grid is clamped to what the device holds
  * at once while G remains the logical task count).  on = 1: every later launch of this context starts
  * min(G, 256 x resident blocks per CU) blocks and block b runs tasks b, b + grid, b + 2*grid, ... of the same
- * task list (same rasterisation, same split-K protocol, same results); on = 0 (default): one block per task.
- * Phi, wave counts, tables and selection are unaffected. */
+ * task list (same rasterisation, same split-K protocol, same results); on = 2: the same grid, but a block draws its
+ * further tasks from a device-side queue as it gets to them (the queue lives beside the context's split-K counters:
+ * launches of one context that overlap in time race on it, as they do on the split-K workspace); on = 0 (default):
+ * one block per task.  Where a kernel's LDS has room, a persistent block requests its next task's first k-tiles
+ * before it writes the current tile out.  Phi, wave counts, tables and selection are unaffected.  wt_gemm_noalloc
+ * launches treat 2 as 1 (the queue is context memory).  Errors: WT_ERR_INVALID_ARG (on outside 0..2, attention
+ * context), WT_ERR_NO_DEVICE (on = 2 on a host-only context). */
 int wt_set_persistent(wt_ctx* ctx, int on);
 
 /* ---- grouped GEMM (Table 2, grouped-GEMM row: G = sum_e ceil(M_e/bm) * ceil(N/bn), L = ceil(K/bk)) ---- */

@@ -217,8 +217,10 @@ def wt_set_capacity_mode(ctx, mode: int):
     _check(lib().wt_set_capacity_mode(ctx, mode), "wt_set_capacity_mode")
 
 
-def wt_set_persistent(ctx, on: bool):
-    _check(lib().wt_set_persistent(ctx, int(bool(on))), "wt_set_persistent")
+def wt_set_persistent(ctx, on):
+    """0 / False: one block per task; 1 / True: resident blocks walk the task list with a fixed stride; 2: they draw
+    their tasks from a device-side queue."""
+    _check(lib().wt_set_persistent(ctx, int(on)), "wt_set_persistent")
 
 
 def wt_tile_coords(tiles_m, tiles_n, swizzle, block):

@@ -6,7 +6,7 @@
 namespace wt {
 
 #define WT_ATTN(TQ, TKV, NW)                                                \
-    {TQ, 1, TKV, NW, 1, 1, 1, AttnTraits<TQ, TKV, NW>::LDS_BYTES,           \
+    {TQ, 1, TKV, NW, 1, 1, 1, AttnTraits<TQ, TKV, NW>::LDS_BYTES, 0,        \
      reinterpret_cast<const void*>(&attn_kernel<TQ, TKV, NW>), nullptr},
 static const KernelEntry kAttnEntries[] = {
 #define WT_LIST_ATTN

@@ -29,6 +29,7 @@ namespace wt {
 
 #define WT_CFGX(BM, BN, BK, WM, WN, WK, ST, MIF)                                                       \
     {BM, BN, BK, WM, WN, WK, ST, GemmTraits<BM, BN, BK, WM, WN, ST, WT_IN, WT_OUT, WK, MIF>::LDS_BYTES,  \
+     GemmTraits<BM, BN, BK, WM, WN, ST, WT_IN, WT_OUT, WK, MIF>::LDS_BYTES_PERSISTENT,                   \
      reinterpret_cast<const void*>(&gemm_kernel<BM, BN, BK, WM, WN, ST, WT_IN, WT_OUT, WK, MIF>),        \
      reinterpret_cast<const void*>(&gemm_kernel_persistent<BM, BN, BK, WM, WN, ST, WT_IN, WT_OUT, WK, MIF>)},
 #define WT_CFGK(BM, BN, BK, WM, WN, WK, ST) WT_CFGX(BM, BN, BK, WM, WN, WK, ST, 0)

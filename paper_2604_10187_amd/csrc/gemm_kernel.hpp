@@ -69,6 +69,8 @@ struct GemmArgs {
     const int* group_offsets;
     int groups;
     int vgrid;          // number of tasks; read by the persistent kernel only
+    int* queue;         // persistent kernel: NULL = block b runs tasks b, b + grid, ...; else two ints, zero before and
+                        // after every launch: [0] hands out the tasks beyond the first grid-ful, [1] counts finished blocks
 };
 
 constexpr int kWave = 64;
@@ -214,6 +216,13 @@ struct GemmTraits {
     static constexpr int EPI_STRIDE = EPI_ROW + 4 * ((EPI_Q - EPI_ROW / 4) & 63);   // bytes
     static constexpr int EPI_WAVE_BYTES = MI * EPI_STRIDE;
     static constexpr bool LDS_EPI = (WK == 1) && (EPI_ROW >= 128) && (NW * EPI_WAVE_BYTES <= LDS_BYTES);
+    // Persistent kernel: when the C staging fits beside the stages, the next task's first k-tiles are requested before
+    // this task's epilogue (the staging then lives behind the stages); 16 more bytes hold the next task's index.
+    static constexpr int EPI_BYTES = LDS_EPI ? NW * EPI_WAVE_BYTES : 0;
+    static constexpr bool PIPE_OK = (ST >= 2) && (WK == 1) && (LDS_BYTES + EPI_BYTES + 16 <= 160 * 1024);
+    // (kernels without that room pass the index through the first bytes of the stages, between tasks)
+    static constexpr int SLOT_OFF = PIPE_OK ? LDS_BYTES + EPI_BYTES : 0;
+    static constexpr int LDS_BYTES_PERSISTENT = PIPE_OK ? SLOT_OFF + 16 : LDS_BYTES;
     static constexpr int EPI_LPR = EPI_ROW / 16;                             // lanes that cover one row, 16 bytes each
     static constexpr int EPI_READS = MI * EPI_ROW / 1024;                    // 1 KiB wavefront reads per MFMA tile row
     static_assert(BK % KS == 0, "BK must hold whole MFMA k-steps");
@@ -249,17 +258,20 @@ struct AccType<16> {
     using type = f32x4;
 };
 
-// One task of the launch: task `block_id` of the task list (a tile, or one split of a tile).
-template <int BM, int BN, int BK, int WM, int WN, int ST, int IN, int OUT, int WK, int MIF = 0>
-__device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_id) {
-    using T = GemmTraits<BM, BN, BK, WM, WN, ST, IN, OUT, WK, MIF>;
-    using acc_t = typename AccType<T::MI>::type;
-    extern __shared__ __attribute__((aligned(1024))) char smem[];
+// What a task is, in block-uniform scalars: the tile (and split) it computes and where its operands start.
+struct TaskDesc {
+    int tile, split;
+    int row0, m_end, col0;
+    int k0, K;            // this task's k range [k0, k0 + K)
+    const char* Bbase;
+    bool valid;           // false: a surplus task of a grouped launch (past the last row tile)
+};
 
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wk = wv / (WM * WN), wmn = wv - wk * (WM * WN);  // k slice, position in the sub-tile grid
-    const int wm = wmn / WN, wn = wmn - wm * WN;
+template <class T, int BM, int BN>
+__device__ __forceinline__ TaskDesc task_setup(const GemmArgs& args, const int block_id, const int lane) {
+    TaskDesc d;
+    d.valid = false;
+    d.tile = 0; d.split = 0; d.row0 = 0; d.m_end = 0; d.col0 = 0; d.k0 = 0; d.K = 0; d.Bbase = nullptr;
     {
         // blocks [s*tiles, (s+1)*tiles) form split s; within a split the rasterisation is the usual one
         int tile = block_id, split = 0;
@@ -302,7 +314,7 @@ __device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_
             }
             const int excl = incl - mine;
             const unsigned long long hit = __ballot(tm >= excl && tm < incl);
-            if (hit == 0) return;  // past the last row tile
+            if (hit == 0) return d;  // past the last row tile
             const int src = __builtin_amdgcn_readfirstlane(__ffsll(static_cast<long long>(hit)) - 1);
             int first = __builtin_amdgcn_readfirstlane(__shfl(excl, src));
             int e = src * c, lo = 0, hi = 0;
@@ -312,7 +324,7 @@ __device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_
                 if (tm < first + t) { found = true; break; }
                 first += t;
             }
-            if (!found) return;
+            if (!found) return d;
             row0 = lo + (tm - first) * BM;
             m_end = hi;
             Bbase += static_cast<int64_t>(e) * args.N * (static_cast<int64_t>(args.K) * T::esize);
@@ -326,6 +338,35 @@ __device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_
             if (K == 0) k0 = 0;  // empty range: every load is sent out of range below
         }
 
+        d.tile = tile; d.split = split; d.row0 = row0; d.m_end = m_end; d.col0 = col0; d.k0 = k0; d.K = K; d.Bbase = Bbase;
+        d.valid = true;
+    }
+    return d;
+}
+
+// State a persistent block carries from task to task.
+struct PipeState {
+    TaskDesc next;        // the task after the current one (valid only if have_next)
+    int next_id;          // its index in the task list (>= vgrid: none)
+    int my_next;          // thread 0: the index obtained for the next task (static stride or from the queue)
+    bool have_next;       // next / next_id are filled in
+    bool prefetched;      // the first k-tiles of `next` have been requested into the stages
+};
+
+// One task of the launch: task `block_id` of the task list (a tile, or one split of a tile).
+template <int BM, int BN, int BK, int WM, int WN, int ST, int IN, int OUT, int WK, int MIF = 0, bool PIPE = false>
+__device__ __forceinline__ void gemm_task(const GemmArgs& args, const TaskDesc& d, PipeState* const ps = nullptr) {
+    using T = GemmTraits<BM, BN, BK, WM, WN, ST, IN, OUT, WK, MIF>;
+    using acc_t = typename AccType<T::MI>::type;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wk = wv / (WM * WN), wmn = wv - wk * (WM * WN);  // k slice, position in the sub-tile grid
+    const int wm = wmn / WN, wn = wmn - wm * WN;
+    {
+        const int tile = d.tile, split = d.split, row0 = d.row0, m_end = d.m_end, col0 = d.col0, k0 = d.k0, K = d.K;
+        const char* const Bbase = d.Bbase;
         // ---- global -> LDS plan: this wavefront's LPW loads per stage --------------------------
         const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
             (__attribute__((address_space(3))) char*)smem));
@@ -339,6 +380,9 @@ __device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_
                                       records(m_end - row0));
         const i32x4 rsrcB = make_rsrc(Bbase + static_cast<int64_t>(col0) * row_bytes + k0_bytes,
                                       records(args.N - col0));
+        // has the previous task of this persistent block already requested this task's first k-tiles?
+        bool prefetched = false;
+        if constexpr (PIPE) prefetched = ps->prefetched;
         // Load slot t of this wavefront fills the 1 KiB LDS piece j = wv + t*NW of a stage.  The lane's
         // source offset at k-tile 0 stays in a register for the whole kernel; the k advance is a scalar.
         // ld_tail[t] is the same offset for the one partial k-tile (K % BK != 0), already replaced by
@@ -360,7 +404,7 @@ __device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_
         // One load: slot t of k-tile kt into LDS stage `stage`.  TAIL = the k-tile may be the partial one
         // or lie past the end (then every piece is out of range and zero-fills the stage), so every
         // k-tile index issues the same number of loads and the vmcnt bookkeeping stays uniform.
-        auto issue_load = [&](int t, int kt, int stage, bool tail) {
+        auto issue_load_rs = [&](const i32x4& rA, const i32x4& rB, int t, int kt, int stage, bool tail) {
             const int j = wv + t * T::NW;
             const uint32_t dst = lds0 + stage * T::STAGE_BYTES + j * 1024;
             // The hardware range-checks the per-lane offset only (the scalar offset is added after the
@@ -373,19 +417,20 @@ __device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_
             }
             if constexpr (T::SPLIT) {
                 if (t < T::A_INSTR / T::NW)
-                    load_lds_16B(rsrcA, voff, koff, dst);
+                    load_lds_16B(rA, voff, koff, dst);
                 else
-                    load_lds_16B(rsrcB, voff, koff, dst);
+                    load_lds_16B(rB, voff, koff, dst);
             } else {
                 const bool is_a = j < T::A_INSTR;  // wave-uniform
                 i32x4 rs;
-                rs.x = is_a ? rsrcA.x : rsrcB.x;
-                rs.y = is_a ? rsrcA.y : rsrcB.y;
-                rs.z = is_a ? rsrcA.z : rsrcB.z;
-                rs.w = rsrcA.w;
+                rs.x = is_a ? rA.x : rB.x;
+                rs.y = is_a ? rA.y : rB.y;
+                rs.z = is_a ? rA.z : rB.z;
+                rs.w = rA.w;
                 load_lds_16B(rs, voff, koff, dst);
             }
         };
+        auto issue_load = [&](int t, int kt, int stage, bool tail) { issue_load_rs(rsrcA, rsrcB, t, kt, stage, tail); };
         auto issue_tile = [&](int kt, int stage) {
     #pragma unroll
             for (int t = 0; t < T::LPW; ++t) issue_load(t, kt, stage, true);
@@ -492,9 +537,15 @@ __device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_
             constexpr int WAIT_LOOP = T::SPREAD ? T::LPW * (ST - 3) + N_BEFORE : T::LPW * (ST - 2);
             static_assert(WAIT_LOOP <= 63, "vmcnt range");
             Frags f[2];
+            if (!prefetched) {
     #pragma unroll
-            for (int s = 0; s < AHEAD; ++s) issue_tile(s, s);
-            wait_vmcnt<T::LPW*(AHEAD - 1)>();
+                for (int s = 0; s < AHEAD; ++s) issue_tile(s, s);
+                wait_vmcnt<T::LPW*(AHEAD - 1)>();
+            } else {
+                // requested before the previous task's epilogue; its C stores are in the same counter and loads and
+                // stores do not retire in one order, so wait for everything
+                wait_vmcnt<0>();
+            }
             block_barrier();
             load_frags(f[0], 0, 0);
             int stage = 0;
@@ -553,6 +604,32 @@ __device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_
             for (; kt < L; ++kt) tile_body(kt, std::true_type{});
             wait_vmcnt<0>();
             if constexpr (T::ASMACC) asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+            // ---- hand-over (persistent kernel): request the next task's first k-tiles before this task's epilogue
+            if constexpr (PIPE && T::PIPE_OK) {
+                if (args.splits == 1) {
+                    int* const slot = reinterpret_cast<int*>(smem + T::SLOT_OFF);
+                    if (threadIdx.x == 0) *slot = ps->my_next;
+                    __syncthreads();   // every wavefront is past its last read of the stages; the slot is written
+                    const int nid = __builtin_amdgcn_readfirstlane(*slot);
+                    ps->next_id = nid;
+                    ps->have_next = true;
+                    ps->prefetched = false;
+                    if (nid < args.vgrid) {
+                        ps->next = task_setup<T, BM, BN>(args, nid, lane);
+                        if (ps->next.valid) {
+                            const TaskDesc& n = ps->next;   // (splits == 1: same k range, same k-tile counts)
+                            const i32x4 nA = make_rsrc(static_cast<const char*>(args.A) + static_cast<int64_t>(n.row0) * row_bytes,
+                                                       records(n.m_end - n.row0));
+                            const i32x4 nB = make_rsrc(n.Bbase + static_cast<int64_t>(n.col0) * row_bytes, records(args.N - n.col0));
+    #pragma unroll
+                            for (int s = 0; s < AHEAD; ++s)
+    #pragma unroll
+                                for (int t = 0; t < T::LPW; ++t) issue_load_rs(nA, nB, t, s, s, true);
+                            ps->prefetched = true;
+                        }
+                    }
+                }
+            }
         }
 
         // ---- reduction over the WK wavefronts of a sub-tile --------------------------------------
@@ -682,8 +759,11 @@ __device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_
                 }
                 return;
             }
-            __syncthreads();   // every wavefront is past its last read of the stages (and of the split-K flag)
-            char* const mine = smem + wv * T::EPI_WAVE_BYTES;
+            // the persistent kernel stages C behind the stages, which may already be receiving the next task
+            constexpr int EPI_BASE = (PIPE && T::PIPE_OK) ? T::LDS_BYTES : 0;
+            if (!(PIPE && T::PIPE_OK) || args.splits > 1)
+                __syncthreads();   // every wavefront is past its last read of the stages (and of the split-K flag)
+            char* const mine = smem + EPI_BASE + wv * T::EPI_WAVE_BYTES;
             char* const wr = mine + (lane % T::MI) * T::EPI_STRIDE + (4 * (lane / T::MI)) * T::OSIZE;
     #pragma unroll
             for (int i = 0; i < T::FM; ++i) {
@@ -749,18 +829,59 @@ __device__ __forceinline__ void gemm_task(const GemmArgs& args, const int block_
 // One block per task.
 template <int BM, int BN, int BK, int WM, int WN, int ST, int IN, int OUT, int WK = 1, int MIF = 0>
 __global__ __launch_bounds__(WM* WN* WK* kWave) void gemm_kernel(const GemmArgs args) {
-    gemm_task<BM, BN, BK, WM, WN, ST, IN, OUT, WK, MIF>(args, blockIdx.x);
+    using T = GemmTraits<BM, BN, BK, WM, WN, ST, IN, OUT, WK, MIF>;
+    const TaskDesc d = task_setup<T, BM, BN>(args, blockIdx.x, threadIdx.x & (kWave - 1));
+    if (!d.valid) return;
+    gemm_task<BM, BN, BK, WM, WN, ST, IN, OUT, WK, MIF>(args, d);
 }
 
-// Persistent launch (Sec. 3.2, note on persistent kernels): the host starts only as many blocks as can be
-// resident at once and block b runs the tasks b, b + gridDim.x, ... of the same task list, so G stays the
-// logical task count while the physical grid is clamped.  Kept as a kernel of its own: wrapping the task in
-// a loop costs the one-block-per-task path 1-5 % (registers that stay live across tasks).
+// Persistent launch (Sec. 3.2, note on persistent kernels): the host starts only as many blocks as can be resident at
+// once and every block works through tasks of the same task list, so G stays the logical task count while the
+// physical grid is clamped.  A block's first task is its own index; further tasks are either index + grid, ... or, when
+// args.queue is set, fetched from a global counter as the block gets to them (workers drawing from a queue).  Where
+// the layout allows (T::PIPE_OK, unsplit tasks) a task's first k-tiles are requested before the previous task's
+// epilogue, so the C stores of one tile and the first loads of the next overlap.
 template <int BM, int BN, int BK, int WM, int WN, int ST, int IN, int OUT, int WK = 1, int MIF = 0>
 __global__ __launch_bounds__(WM* WN* WK* kWave) void gemm_kernel_persistent(const GemmArgs args) {
-    for (int b = blockIdx.x; b < args.vgrid; b += gridDim.x) {
-        gemm_task<BM, BN, BK, WM, WN, ST, IN, OUT, WK, MIF>(args, b);
-        if (b + static_cast<int>(gridDim.x) < args.vgrid) __syncthreads();  // LDS is reused by the next task
+    using T = GemmTraits<BM, BN, BK, WM, WN, ST, IN, OUT, WK, MIF>;
+    static_assert(T::LDS_BYTES_PERSISTENT <= 160 * 1024, "LDS per workgroup");
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const int lane = threadIdx.x & (kWave - 1);
+    int* const slot = reinterpret_cast<int*>(smem + T::SLOT_OFF);
+    PipeState ps;
+    ps.prefetched = false;
+    int id = blockIdx.x;
+    TaskDesc cur = task_setup<T, BM, BN>(args, id, lane);
+    while (id < args.vgrid) {
+        // the index of the task after this one: asked for now, needed when this task's main loop is over
+        ps.my_next = id + static_cast<int>(gridDim.x);
+        if (args.queue && threadIdx.x == 0)
+            ps.my_next = static_cast<int>(gridDim.x) +
+                         __hip_atomic_fetch_add(args.queue, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        ps.have_next = false;
+        if (cur.valid) gemm_task<BM, BN, BK, WM, WN, ST, IN, OUT, WK, MIF, true>(args, cur, &ps);
+        if (!ps.have_next) {
+            // no hand-over inside the task: agree on the next index here; LDS is free again after the barrier
+            __syncthreads();
+            if (threadIdx.x == 0) *slot = ps.my_next;
+            __syncthreads();
+            ps.next_id = __builtin_amdgcn_readfirstlane(*slot);
+            if constexpr (!T::PIPE_OK) __syncthreads();   // the slot lies inside the stages: read it before they refill
+            ps.prefetched = false;
+            if (ps.next_id < args.vgrid) ps.next = task_setup<T, BM, BN>(args, ps.next_id, lane);
+        }
+        id = ps.next_id;
+        cur = ps.next;
+    }
+    if (args.queue) {
+        // the last block to run out of tasks puts both counters back to zero for the next launch
+        if (threadIdx.x == 0) {
+            const int done = __hip_atomic_fetch_add(args.queue + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (done == static_cast<int>(gridDim.x) - 1) {
+                __hip_atomic_store(args.queue, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(args.queue + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
     }
 }
 

@@ -7,6 +7,7 @@ namespace wt {
 struct KernelEntry {
     int bm, bn, bk, wm, wn, wk, st;  // wk: wavefronts sharing a sub-tile along k (nwave = wm*wn*wk)
     int lds_bytes;
+    int lds_bytes_persistent;  // dynamic LDS of the persistent kernel (stages + C staging + hand-over slot)
     const void* fn;  // __global__ function taking GemmArgs by value (NULL in a host-only build)
     const void* fn_persistent;  // the same configuration as a persistent kernel
 };

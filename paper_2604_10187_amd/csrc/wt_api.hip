@@ -153,6 +153,7 @@ int launch(wt_ctx* ctx, const Config& c, const Problem& p, hipStream_t stream, c
     args.group_offsets = p.groups > 0 ? p.offsets : nullptr;
     args.groups = p.groups;
     args.vgrid = (int)G;
+    args.queue = (ctx->persistent == 2 && !alt) ? ctx->queue : nullptr;
     // persistent launch: as many blocks as the device holds at once, each walking the task list with that stride
     const int64_t resident = (int64_t)kNumCU * std::max(1, c.occ_persistent);
     const int64_t grid = ctx->persistent ? std::min(G, resident) : G;
@@ -165,7 +166,7 @@ int launch(wt_ctx* ctx, const Config& c, const Problem& p, hipStream_t stream, c
     }
     void* params[] = {&args};
     WT_HIP(ctx, hipLaunchKernel(ctx->persistent ? c.fn_persistent : c.fn, dim3((unsigned)grid), dim3((unsigned)(c.cfg.nwave * 64)), params,
-                                (size_t)c.res.lds_bytes, stream));
+                                (size_t)(ctx->persistent ? c.lds_persistent : c.res.lds_bytes), stream));
     return WT_OK;
 }
 
@@ -381,7 +382,8 @@ int wt_create(wt_ctx** out, int device, int in_type, int out_type) {
         // split-K workspace: partial tiles, then the arrival counters (zero now; every launch leaves them zero)
         if (in_type != WT_ATTN_BF16) {  // attention kernels use no workspace
             void* ws = nullptr;
-            const size_t ws_bytes = (size_t)kWsElems * sizeof(float), cnt_bytes = (size_t)kMaxSplitTiles * sizeof(int);
+            // (two more ints behind the counters: the persistent kernels' task queue, zero between launches as well)
+            const size_t ws_bytes = (size_t)kWsElems * sizeof(float), cnt_bytes = (size_t)(kMaxSplitTiles + 2) * sizeof(int);
             e = hipMalloc(&ws, ws_bytes + cnt_bytes);
             if (e == hipSuccess) e = hipMemset((char*)ws + ws_bytes, 0, cnt_bytes);
             if (e == hipSuccess) e = hipDeviceSynchronize();
@@ -393,6 +395,7 @@ int wt_create(wt_ctx** out, int device, int in_type, int out_type) {
             }
             ctx->ws = (float*)ws;
             ctx->counters = (int*)((char*)ws + ws_bytes);
+            ctx->queue = ctx->counters + kMaxSplitTiles;
         }
         // per-key resources from the runtime: LDS opt-in, register count, resident blocks per CU
         for (size_t k = 0; k < ctx->keys.size(); ++k) {
@@ -403,7 +406,7 @@ int wt_create(wt_ctx** out, int device, int in_type, int out_type) {
             memset(&fa, 0, sizeof(fa));
             e = hipFuncSetAttribute(c0.fn, hipFuncAttributeMaxDynamicSharedMemorySize, key.lds_bytes);
             if (e == hipSuccess && c0.fn_persistent)
-                e = hipFuncSetAttribute(c0.fn_persistent, hipFuncAttributeMaxDynamicSharedMemorySize, key.lds_bytes);
+                e = hipFuncSetAttribute(c0.fn_persistent, hipFuncAttributeMaxDynamicSharedMemorySize, c0.lds_persistent);
             if (e == hipSuccess) e = hipFuncGetAttributes(&fa, c0.fn);
             if (e == hipSuccess)
                 e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, c0.fn, key.nwave * 64, (size_t)key.lds_bytes);
@@ -415,7 +418,7 @@ int wt_create(wt_ctx** out, int device, int in_type, int out_type) {
             if (!c0.fn_persistent) {
                 occ_p = 1;
             } else if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_p, c0.fn_persistent, key.nwave * 64,
-                                                                    (size_t)key.lds_bytes) != hipSuccess) {
+                                                                    (size_t)c0.lds_persistent) != hipSuccess) {
                 (void)hipGetLastError();
                 occ_p = 1;
             }
@@ -440,7 +443,8 @@ int wt_destroy(wt_ctx* ctx) {
 }
 
 int wt_set_persistent(wt_ctx* ctx, int on) {
-    if (!ctx || (on != 0 && on != 1) || (on && ctx->in_type == WT_ATTN_BF16)) return WT_ERR_INVALID_ARG;
+    if (!ctx || on < 0 || on > 2 || (on && ctx->in_type == WT_ATTN_BF16)) return WT_ERR_INVALID_ARG;
+    if (on == 2 && !ctx->queue) return WT_ERR_NO_DEVICE;
     ctx->persistent = on;
     return WT_OK;
 }

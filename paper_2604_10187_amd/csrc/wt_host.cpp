@@ -100,6 +100,7 @@ static void add_key(wt_ctx* ctx, const KernelEntry& e, int split) {
         c.wm = e.wm; c.wn = e.wn;
         c.fn = e.fn;
         c.fn_persistent = e.fn_persistent;
+        c.lds_persistent = e.lds_bytes_persistent;
         ctx->cfgs.push_back(c);
     }
     ctx->keys.push_back(k);

@@ -32,6 +32,7 @@ struct Config {
     const void* fn;
     const void* fn_persistent;
     int occ_persistent = 1;  // resident blocks per CU of the persistent kernel (its grid is 256 x this)
+    int lds_persistent = 0;  // its dynamic LDS bytes
 };
 
 struct Key {
@@ -86,7 +87,8 @@ struct wt_ctx {
     int in_type = 0, out_type = 0;
     int last_hip = 0;
     int cap_mode = WT_CAP_CU_ONLY;  // wt_cap_mode
-    int persistent = 0;             // 1: launches clamp the grid to the resident block count
+    int persistent = 0;             // 1, 2: launches clamp the grid to the resident block count (2: tasks from a queue)
+    int* queue = nullptr;           // two ints behind the split-K counters: the persistent kernels' task queue
     std::vector<wt::Config> cfgs;
     std::vector<wt::Key> keys;
     wt::Table table;

@@ -290,9 +290,9 @@ def cmd_grouped(a, torch):
 
 
 def cmd_persistent(a, torch):
-    """Persistent launch (grid clamped to the resident block count, blocks walk the task list) against the
-    ordinary one block per task, same configuration (wt_select's pick), same protocol, on the sweep, the
-    large prefill and a sample of the stream."""
+    """Persistent launches (grid clamped to the resident block count; mode 1: blocks walk the task list with a fixed
+    stride, mode 2: blocks draw tasks from the device-side queue) against the ordinary one block per task, same
+    configuration (wt_select's pick), same protocol, on the sweep, the large prefill and a sample of the stream."""
     import wt_synth
 
     ctx, path = _open_ctx(a, torch)
@@ -305,23 +305,27 @@ def cmd_persistent(a, torch):
         A, B, C, sA, sB = _dev_operands(torch, M, N, K, a.in_type, a.out_type)
         cfg = wt.wt_select(ctx, M, N, K)
         G, L, w = wt.wt_wave_count(ctx, M, N, K, cfg)
-        t = []
+        t = {0: [], 1: [], 2: []}
         for rep in range(2):                     # alternate to cancel clock drift
-            for on in (False, True):
-                wt.wt_set_persistent(ctx, on)
-                t.append(wt.wt_time_gemm(ctx, M, N, K, A, B, C, cfg, 3, 10, sA, sB, stream))
-        wt.wt_set_persistent(ctx, False)
-        plain, pers = min(t[0], t[2]), min(t[1], t[3])
+            for mode in (0, 1, 2):
+                wt.wt_set_persistent(ctx, mode)
+                t[mode].append(wt.wt_time_gemm(ctx, M, N, K, A, B, C, cfg, 3, 10, sA, sB, stream))
+        wt.wt_set_persistent(ctx, 0)
+        plain, pers, queue = min(t[0]), min(t[1]), min(t[2])
         rows.append({"M": M, "N": N, "K": K, "cfg": list(cfg.astuple()), "tasks": G, "waves": w,
-                     "plain_us": plain, "persistent_us": pers, "speedup": plain / pers})
-        _log(f"[eval] persistent {M}x{N}x{K} {cfg.astuple()} tasks {G}: {plain:.1f} -> {pers:.1f} us ({plain / pers:.3f}x)")
-    multi = [r["speedup"] for r in rows if r["waves"] > 1]
-    sp = np.array([r["speedup"] for r in rows])
-    summary = {"n_shapes": len(rows), "geomean_speedup": float(np.exp(np.mean(np.log(sp)))),
-               "geomean_speedup_multi_wave": float(np.exp(np.mean(np.log(multi)))) if multi else None,
-               "min": float(sp.min()), "max": float(sp.max())}
-    return {"workload": "persistent vs one-block-per-task launch under wt_select's configuration", "table": path,
-            "summary": summary, "rows": rows}
+                     "plain_us": plain, "persistent_us": pers, "queue_us": queue, "speedup": plain / pers,
+                     "speedup_queue": plain / queue})
+        _log(f"[eval] persistent {M}x{N}x{K} {cfg.astuple()} tasks {G}: {plain:.1f} -> stride {pers:.1f} us "
+             f"({plain / pers:.3f}x), queue {queue:.1f} us ({plain / queue:.3f}x)")
+    summary = {"n_shapes": len(rows)}
+    for key, name in (("speedup", "stride"), ("speedup_queue", "queue")):
+        sp = np.array([r[key] for r in rows])
+        multi = [r[key] for r in rows if r["waves"] > 1]
+        summary[name] = {"geomean_speedup": float(np.exp(np.mean(np.log(sp)))),
+                         "geomean_speedup_multi_wave": float(np.exp(np.mean(np.log(multi)))) if multi else None,
+                         "min": float(sp.min()), "max": float(sp.max())}
+    return {"workload": "persistent (fixed stride / task queue) vs one-block-per-task launch under wt_select's configuration",
+            "table": path, "summary": summary, "rows": rows}
 
 
 def cmd_vendor(a, torch):

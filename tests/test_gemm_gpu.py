@@ -252,23 +252,27 @@ def test_launches_replay_from_a_hip_graph(ctx_f32):
 
 
 # ---- persistent launches ---------------------------------------------------------------------------
-def test_persistent_launch_bit_exact(ctx_f32):
-    """Grid clamped to the resident block count: on problems with more tasks than that, every structural
-    key (split-K ones included) must give the bits of the one-block-per-task launch and of the oracle."""
+@pytest.mark.parametrize("mode", [1, 2])
+def test_persistent_launch_bit_exact(ctx_f32, mode):
+    """Grid clamped to the resident block count (mode 1: fixed stride through the task list, mode 2: tasks drawn from
+    the device-side queue, which every launch must leave at zero for the next): on problems with more tasks than
+    that, every structural key (split-K ones included) must give the bits of the one-block-per-task launch and of
+    the oracle.  Where the kernel has room it requests the next task's first k-tiles before the current epilogue."""
     import math
 
-    wt.wt_set_persistent(ctx_f32, True)
+    wt.wt_set_persistent(ctx_f32, mode)
     try:
         for cfg, res in all_configs(ctx_f32):
             if cfg.swizzle != cfg.id // 3 % 3:
                 continue
-            need = (256 * res.occ) // cfg.split + 37            # tiles, so that tasks exceed what is resident
+            # tiles, so that tasks exceed what is resident (every third key: by more than two rounds)
+            need = ((256 * res.occ) // cfg.split) * (3 if cfg.id % 9 == 0 and cfg.bm * cfg.bn <= 128 * 128 else 1) + 37
             tm = max(2, math.isqrt(need))
             tn = -(-need // tm) + 1
-            M, N, K = tm * cfg.bm - 3, tn * cfg.bn - 5, cfg.split * cfg.bk + 24
+            M, N, K = tm * cfg.bm - 3, tn * cfg.bn - 5, cfg.split * cfg.bk * (1 + cfg.id % 4) + 24
             G, L, w = wt.wt_wave_count(ctx_f32, M, N, K, cfg)
             assert G > 256 * res.occ
-            note(f"persistent cfg={cfg.astuple()} shape={(M, N, K)} tasks={G} resident={256 * res.occ}")
+            note(f"persistent mode={mode} cfg={cfg.astuple()} shape={(M, N, K)} tasks={G} resident={256 * res.occ}")
             ab, bb = _bf16_case(M, N, K, 300 + cfg.id, "int")
             got = run_gemm(ctx_f32, cfg, ab, bb, wt.WT_OUT_F32, fill=float("nan"))
             assert np.array_equal(got, og.gemm_c(ab, bb)), f"{cfg}"
@@ -276,10 +280,11 @@ def test_persistent_launch_bit_exact(ctx_f32):
         wt.wt_set_persistent(ctx_f32, False)
 
 
-def test_persistent_grouped_and_normal(ctx_bf16):
+@pytest.mark.parametrize("mode", [1, 2])
+def test_persistent_grouped_and_normal(ctx_bf16, mode):
     """Persistent launch of a grouped problem (surplus blocks past the last row tile) and of an N(0,1)
     problem spanning several waves, bf16 out."""
-    wt.wt_set_persistent(ctx_bf16, True)
+    wt.wt_set_persistent(ctx_bf16, mode)
     try:
         counts = [700, 0, 33, 1, 900, 64, 2000]
         off = wt_synth.group_offsets(counts)
@@ -445,7 +450,7 @@ def test_fp8_grouped_and_persistent_bit_exact(ctx_fp8_f32):
     one = torch.ones(1, dtype=torch.float32, device="cuda")
     dOff = torch.from_numpy(off.copy()).cuda()
     dA, dB = torch.from_numpy(aq.copy()).cuda(), torch.from_numpy(bq.reshape(E * N, K).copy()).cuda()
-    for persistent in (False, True):
+    for persistent in (0, 1, 2):
         wt.wt_set_persistent(ctx_fp8_f32, persistent)
         try:
             for cfg, res in all_configs(ctx_fp8_f32):

@@ -48,6 +48,23 @@ def test_library_exports_every_declared_symbol():
         assert getattr(L, name) is not None
 
 
+def test_persistent_modes_are_checked():
+    """Launch policy: 0 one block per task, 1 fixed stride, 2 device-side queue (needs a device context)."""
+    c = wt.wt_create(-1, wt.WT_BF16, wt.WT_OUT_BF16)
+    try:
+        wt.wt_set_persistent(c, 1)
+        wt.wt_set_persistent(c, 0)
+        with pytest.raises(wt.WtError) as e:
+            wt.wt_set_persistent(c, 2)
+        assert e.value.status == wt.WT_ERR_NO_DEVICE
+        for bad in (-1, 3):
+            with pytest.raises(wt.WtError) as e:
+                wt.wt_set_persistent(c, bad)
+            assert e.value.status == wt.WT_ERR_INVALID_ARG
+    finally:
+        wt.wt_destroy(c)
+
+
 def test_binding_states_the_headers_limits():
     lim = lib_limits()
     assert (wt.WT_SPLITK_WS_FLOATS, wt.WT_SPLITK_MAX_TILES, wt.WT_MAX_ANCHORS) == (lim["ws_elems"], lim["max_split_tiles"], lim["max_anchors"])
