@@ -13,8 +13,11 @@
 //   * P^T (bf16) is fed back as the column operand of O^T += V^T P^T straight from those accumulator registers
 //     (eight consecutive accumulators are one k-step); the contraction order over keys that this implies
 //     (key = 32b + 8(e/4) + 4(lane/32) + e%4) is baked into how V is laid out in LDS;
-//   * K goes to LDS row-major (rows padded by 16 bytes), V is transposed in registers (4 keys x 8 dims per
-//     thread) and stored as V^T[d][permuted key] so that every MFMA operand is one 16-byte LDS read;
+//   * K and V both go to LDS row-major as loaded (16 bytes per lane, rows padded).  The V^T operand of O^T += V^T P^T
+//     needs, per lane, four consecutive keys of ONE head dimension -- a column of the staged tile -- and is read
+//     with the transposing LDS read (ds_read_b64_tr_b16): within 16 lanes, lane s supplies the 8-byte piece
+//     (key k0 + s/4, dims d0 + 4*(s%4) .. +3) and lane j receives (keys k0 .. k0+3, dim d0 + j); two such reads make
+//     one operand, and no vector ALU work goes into the transposition;
 //   * the global loads of tile t+1 are issued right after the barrier that publishes tile t and land in registers
 //     while tile t is computed; two barriers per tile (publish / release);
 //   * softmax in base 2 with the scale folded into one fma per element (the running maximum is kept in raw score
@@ -35,6 +38,7 @@ typedef __attribute__((ext_vector_type(4))) __bf16 abf16x4;
 typedef __attribute__((ext_vector_type(16))) float af32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned au32x4;
 typedef __attribute__((ext_vector_type(2))) unsigned au32x2;
+typedef __attribute__((ext_vector_type(4))) short as16x4;
 
 struct AttnArgs {
     const __bf16* Q;
@@ -73,15 +77,14 @@ struct AttnTraits {
     static constexpr int NT = NW * 64;
     static constexpr int KB = TKV / 32;                 // 32-key blocks per tile
     static constexpr int K_ROW = kHeadDim * 2 + 16;     // bytes per key row in LDS (padded: conflict-free 16-byte reads)
-    static constexpr int V_ROW = TKV * 2 + 16;          // bytes per head-dimension row of V^T in LDS
+    // bytes per key row of V in LDS: 16 dwords (mod 64) apart, so that the four key rows one transposing read touches
+    // (64 contiguous bytes of each, per half wavefront) fall on disjoint banks
+    static constexpr int V_ROW = kHeadDim * 2 + 64;
     static constexpr int K_BYTES = TKV * K_ROW;
-    static constexpr int V_BYTES = kHeadDim * V_ROW;
+    static constexpr int V_BYTES = TKV * V_ROW;
     static constexpr int LDS_BYTES = K_BYTES + V_BYTES;
     static constexpr int K_TOTAL = TKV * 16;            // 16-byte chunks of a K tile
     static constexpr int KC = (K_TOTAL + NT - 1) / NT;  // per thread
-    static constexpr int QN = TKV / 4;                  // key quads per tile
-    static constexpr int V_TOTAL = QN * 16;             // 4-key x 8-dim units of a V tile
-    static constexpr int VU = (V_TOTAL + NT - 1) / NT;  // per thread
     static_assert(TQ % NW == 0 && (R == 32 || R == 64), "a wavefront owns 32 or 64 query rows");
     static_assert(TKV % 32 == 0 && TKV >= 32, "KV tile is a multiple of 32 keys");
 };
@@ -126,22 +129,16 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
 
     // ---- staging registers for one K tile and one V tile ----------------------------------------------------
     au32x4 kreg[T::KC];
-    au32x4 vreg[T::VU][4];
+    au32x4 vreg[T::KC];
     // Per-thread element offsets of its K chunks and V units inside a tile are loop-invariant; a tile adds a uniform
     // stride.  Tiles that lie wholly inside S_kv (all but possibly the last) are loaded without per-row predicates.
     const int64_t tile_stride = static_cast<int64_t>(TKV) * a.H_kv * kHeadDim;
-    int64_t k_off[T::KC], v_off[T::VU];
+    int64_t k_off[T::KC];   // (V has K's layout: the same offsets serve both)
 #pragma unroll
     for (int i = 0; i < T::KC; ++i) {
         const int c = tid + i * T::NT;
         k_off[i] = (static_cast<int64_t>(c >> 4) * a.H_kv + kh) * kHeadDim + (c & 15) * 8;
     }
-#pragma unroll
-    for (int i = 0; i < T::VU; ++i) {
-        const int u = tid + i * T::NT;
-        v_off[i] = (static_cast<int64_t>(4 * (u % T::QN)) * a.H_kv + kh) * kHeadDim + (u / T::QN) * 8;
-    }
-    const int64_t v_row = static_cast<int64_t>(a.H_kv) * kHeadDim;  // elements between consecutive keys
     auto load_k = [&](int t) {
         const int kv0 = t * TKV;
         const __bf16* base = a.K + t * tile_stride;
@@ -164,24 +161,16 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
         const __bf16* base = a.V + t * tile_stride;
         if (kv0 + TKV <= a.S_kv) {
 #pragma unroll
-            for (int i = 0; i < T::VU; ++i)
-                if (tid + i * T::NT < T::V_TOTAL) {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) vreg[i][r] = *reinterpret_cast<const au32x4*>(base + v_off[i] + r * v_row);
-                }
+            for (int i = 0; i < T::KC; ++i)
+                if (tid + i * T::NT < T::K_TOTAL) vreg[i] = *reinterpret_cast<const au32x4*>(base + k_off[i]);
             return;
         }
 #pragma unroll
-        for (int i = 0; i < T::VU; ++i) {
-            const int u = tid + i * T::NT;
-            const int quad = u % T::QN;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                au32x4 v = {0u, 0u, 0u, 0u};
-                if (u < T::V_TOTAL && kv0 + 4 * quad + r < a.S_kv)
-                    v = *reinterpret_cast<const au32x4*>(base + v_off[i] + r * v_row);
-                vreg[i][r] = v;
-            }
+        for (int i = 0; i < T::KC; ++i) {
+            const int c = tid + i * T::NT;
+            au32x4 v = {0u, 0u, 0u, 0u};
+            if (c < T::K_TOTAL && kv0 + (c >> 4) < a.S_kv) v = *reinterpret_cast<const au32x4*>(base + k_off[i]);
+            vreg[i] = v;
         }
     };
     auto store_k = [&]() {
@@ -195,27 +184,9 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
     auto store_v = [&]() {
         char* const base = v_lds;
 #pragma unroll
-        for (int i = 0; i < T::VU; ++i) {
-            const int u = tid + i * T::NT;
-            if (u >= T::V_TOTAL) continue;
-            const int quad = u % T::QN, dc = u / T::QN;
-            // key = 32b + 8jj + 4hq + r  ->  16-byte chunk (2b + jj/2)*2 + hq, half jj%2, element r
-            const int b = quad >> 3, jj = (quad >> 1) & 3, hq = quad & 1;
-            char* dst = base + (dc * 8) * T::V_ROW + (((b * 2 + (jj >> 1)) * 2 + hq) * 16) + (jj & 1) * 8;
-#pragma unroll
-            for (int d = 0; d < 8; ++d) {
-                const int w = d >> 1;
-                unsigned x0 = vreg[i][0][w], x1 = vreg[i][1][w], x2 = vreg[i][2][w], x3 = vreg[i][3][w];
-                au32x2 o;
-                if (d & 1) {
-                    o.x = (x0 >> 16) | (x1 & 0xffff0000u);
-                    o.y = (x2 >> 16) | (x3 & 0xffff0000u);
-                } else {
-                    o.x = (x0 & 0xffffu) | (x1 << 16);
-                    o.y = (x2 & 0xffffu) | (x3 << 16);
-                }
-                *reinterpret_cast<au32x2*>(dst + d * T::V_ROW) = o;
-            }
+        for (int i = 0; i < T::KC; ++i) {
+            const int c = tid + i * T::NT;
+            if (c < T::K_TOTAL) *reinterpret_cast<au32x4*>(base + (c >> 4) * T::V_ROW + (c & 15) * 16) = vreg[i];
         }
     };
 
@@ -303,9 +274,14 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
             }
         }
     };
-    // O^T[d][query] += V^T[d][key] P^T[key][query]
+    // O^T[d][query] += V^T[d][key] P^T[key][query].  The k slots of a k-step hold, for the lanes of k-half h, the keys
+    // 32b + 16ks + 4h + {0..3} and the same + 8 (the order in which the score accumulators come out), so the V^T
+    // operand is two transposing reads: lane (s = lane % 16, group = lane / 16) supplies the piece at key
+    // 32b + 16ks + 4h + s/4 (+ 8), dims 32db + 16*(group % 2) + 4*(s % 4), and receives dim 32db + lane % 32.
     auto pv = [&](const Scores& s) {
-        const char* const base = v_lds;
+        const int sl = lane & 15;
+        const char* const base = v_lds + (4 * h + (sl >> 2)) * T::V_ROW + (16 * ((lane >> 4) & 1) + 4 * (sl & 3)) * 2;
+        typedef __attribute__((address_space(3))) as16x4 lds_s16x4;
 #pragma unroll
         for (int b = 0; b < T::KB; ++b)
 #pragma unroll
@@ -317,8 +293,12 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
                     for (int e = 0; e < 8; ++e) pf[rb][e] = static_cast<__bf16>(s.v[b][rb][8 * ks + e]);
 #pragma unroll
                 for (int db = 0; db < 4; ++db) {
-                    const abf16x8 vf =
-                        *reinterpret_cast<const abf16x8*>(base + (32 * db + l32) * T::V_ROW + ((b * 2 + ks) * 2 + h) * 16);
+                    const char* p = base + (32 * b + 16 * ks) * T::V_ROW + 64 * db;
+                    const as16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+                    const as16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * T::V_ROW));
+                    typedef __attribute__((ext_vector_type(8))) short as16x8;
+                    const as16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    const abf16x8 vf = __builtin_bit_cast(abf16x8, both);
 #pragma unroll
                     for (int rb = 0; rb < T::RB; ++rb)
                         o[rb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[rb], o[rb][db], 0, 0, 0);

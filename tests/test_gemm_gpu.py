@@ -494,17 +494,36 @@ def _sampled_check(ctx, cfg, M, N, K, in_type, out_type, seed, n_rows=12, n_cols
     assert np.isfinite(got).all()
 
 
+def _large_prefill_configs(ctx, in_type, four_wave, eight_wave):
+    """The configuration bench.py times on 16384 x 8192 x 8192 (wt_select on the shipped table) and the two 256 x 256
+    kernels it chooses between, whatever the table says today."""
+    import os
+
+    from paper_2604_10187_amd import tune
+
+    cfgs = {}
+    path = tune.table_path(in_type, wt.WT_OUT_BF16)
+    if os.path.exists(path):
+        wt.wt_load(ctx, path)
+        pick = wt.wt_select(ctx, 16384, 8192, 8192)
+        cfgs[pick.id] = pick
+    for fields in (four_wave, eight_wave):
+        c, _ = wt.wt_config_get(ctx, wt.wt_config_find(ctx, *fields))
+        cfgs.setdefault(c.id, c)
+    return list(cfgs.values())
+
+
 def test_large_prefill_bf16_sampled(ctx_bf16):
-    """16384 x 8192 x 8192, bf16 in / bf16 out, under the flagship configuration."""
-    cfg, _ = wt.wt_config_get(ctx_bf16, wt.wt_config_find(ctx_bf16, 256, 256, 64, 8, 2, 0))
-    note(f"large prefill bf16 cfg={cfg.astuple()}")
-    _sampled_check(ctx_bf16, cfg, 16384, 8192, 8192, wt.WT_BF16, wt.WT_OUT_BF16, 1004)
+    """16384 x 8192 x 8192, bf16 in / bf16 out, under the selector's pick and both flagship kernels."""
+    for cfg in _large_prefill_configs(ctx_bf16, wt.WT_BF16, (256, 256, 64, 4, 2, 0), (256, 256, 64, 8, 2, 2)):
+        note(f"large prefill bf16 cfg={cfg.astuple()}")
+        _sampled_check(ctx_bf16, cfg, 16384, 8192, 8192, wt.WT_BF16, wt.WT_OUT_BF16, 1004, n_rows=8, n_cols=4)
 
 
 def test_large_prefill_fp8_sampled(ctx_fp8_bf16):
-    cfg, _ = wt.wt_config_get(ctx_fp8_bf16, wt.wt_config_find(ctx_fp8_bf16, 256, 256, 128, 8, 2, 0))
-    note(f"large prefill fp8 cfg={cfg.astuple()}")
-    _sampled_check(ctx_fp8_bf16, cfg, 16384, 8192, 8192, wt.WT_FP8_E4M3, wt.WT_OUT_BF16, 1014)
+    for cfg in _large_prefill_configs(ctx_fp8_bf16, wt.WT_FP8_E4M3, (256, 256, 128, 4, 2, 1), (256, 256, 128, 8, 2, 0)):
+        note(f"large prefill fp8 cfg={cfg.astuple()}")
+        _sampled_check(ctx_fp8_bf16, cfg, 16384, 8192, 8192, wt.WT_FP8_E4M3, wt.WT_OUT_BF16, 1014, n_rows=8, n_cols=4)
 
 
 def test_sweep_shapes_full_size_under_selected_config(ctx_bf16):
