@@ -58,3 +58,26 @@ def test_shipped_gemm_tables_select_like_the_oracle(in_type, stem):
             assert wt.wt_predict_us(ctx, M, N, K, c) == t
     finally:
         wt.wt_destroy(ctx)
+
+
+@pytest.mark.parametrize("in_type,stem", CASES)
+def test_shipped_tables_are_the_oracles_fit_of_the_shipped_records(in_type, stem):
+    """The table files were written by the library's wt_fit from the profiling records stored beside them.  The
+    oracle's fit of the same records (its own grouping, shared-micro choice, least squares and anchor thinning) must
+    give the same table: every bucket's status and (L, micro) anchors identical, every coefficient equal to within
+    the rounding of two different least-squares routines."""
+    table, meta = osel.read_table(os.path.join(TABLES, stem + ".wt"), **SPLIT_LIMITS)
+    recs = np.load(os.path.join(TABLES, stem + "_samples.npz"))["samples"]
+    samples = [(int(r["key_id"]), int(r["micro_id"]), int(r["G"]), int(r["L"]), int(r["w"]), float(r["mean_us"]),
+                int(r["family"])) for r in recs]
+    mine = ofit.fit_tables(samples, table.keys, table.W, meta["p"], max_anchors=MAX_ANCHORS)
+    n_fitted = 0
+    for k in range(len(table.keys)):
+        for w in range(table.W + 1):
+            a = table.local[k][w] if w < table.W else table.ext[k]
+            b = mine.local[k][w] if w < table.W else mine.ext[k]
+            assert a.status == b.status and a.anchors == b.anchors, (k, w)
+            n_fitted += a.status != 0
+            for x, y in zip(a.theta, b.theta):
+                assert abs(x - y) <= 1e-8 * max(abs(x), abs(y)) + 1e-12, (k, w, a.theta, b.theta)
+    assert n_fitted >= len(table.keys)
