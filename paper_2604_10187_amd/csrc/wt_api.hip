@@ -123,6 +123,7 @@ int launch_attn(wt_ctx* ctx, const Config& c, const Problem& p, hipStream_t stre
 }
 
 constexpr int kMaxGroups = 1024;
+constexpr int64_t kStreamCBytes = 128ll << 20;
 
 int launch(wt_ctx* ctx, const Config& c, const Problem& p, hipStream_t stream, const Workspace* alt = nullptr) {
     if (ctx->in_type == WT_ATTN_BF16) return launch_attn(ctx, c, p, stream);
@@ -154,6 +155,9 @@ int launch(wt_ctx* ctx, const Config& c, const Problem& p, hipStream_t stream, c
     args.groups = p.groups;
     args.vgrid = (int)G;
     args.queue = (ctx->persistent == 2 && !alt) ? ctx->queue : nullptr;
+    // an output larger than half the 256 MB memory-side cache is written with the non-temporal hint
+    const int64_t c_bytes = p.M * p.N * (ctx->out_type == WT_OUT_BF16 ? 2 : 4);
+    args.stream_c = c_bytes > kStreamCBytes ? 1 : 0;
     // persistent launch: as many blocks as the device holds at once, each walking the task list with that stride
     const int64_t resident = (int64_t)kNumCU * std::max(1, c.occ_persistent);
     const int64_t grid = ctx->persistent ? std::min(G, resident) : G;

@@ -137,6 +137,23 @@ def test_unaligned_output_rows_and_pointer(ctx_f32, ctx_bf16):
                     assert torch.isnan(guard).all(), "wrote outside C"
 
 
+def test_outputs_beyond_the_streaming_threshold_bit_exact(ctx_f32, ctx_bf16):
+    """A C of more than 128 MiB is written with non-temporal stores (the line-wise epilogue's other branch): integer
+    inputs, bit-exact against the oracle, fp32 and bf16 out, one block per task."""
+    for ctx, dt, (M, N) in ((ctx_f32, wt.WT_OUT_F32, (6144, 5640)), (ctx_bf16, wt.WT_OUT_BF16, (8200, 8328))):
+        K = 136
+        assert M * N * (4 if dt == wt.WT_OUT_F32 else 2) > 128 << 20
+        ab, bb = _bf16_case(M, N, K, 990 + dt, "int")
+        want = og.gemm_c(ab, bb).astype(np.float32)
+        if dt == wt.WT_OUT_BF16:
+            want = torch.from_numpy(want).to(torch.bfloat16).float().numpy()
+        for fields in ((256, 256, 64, 4, 2, 0), (128, 128, 64, 4, 3, 1), (256, 128, 64, 8, 2, 2)):
+            cfg, _ = wt.wt_config_get(ctx, wt.wt_config_find(ctx, *fields))
+            note(f"streaming C cfg={cfg.astuple()} out={dt} shape={(M, N, K)}")
+            got = run_gemm(ctx, cfg, ab, bb, dt, fill=float("nan"))
+            assert np.array_equal(got, want), f"{cfg}"
+
+
 def _split_configs(ctx):
     return [(c, r) for c, r in all_configs(ctx) if c.split > 1]
 
