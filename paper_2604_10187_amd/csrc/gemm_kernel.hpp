@@ -213,7 +213,10 @@ struct GemmTraits {
     // Rows are padded to a stride of EPI_Q (mod 64) dwords, which spreads both access patterns over the banks.
     static constexpr int OSIZE = OUT == 0 ? 4 : 2;
     static constexpr int EPI_ROW = TN * OSIZE;                               // bytes of one sub-tile row
-    static constexpr int EPI_Q = (kWave / MI) * OSIZE;                       // wanted row stride in dwords, mod 64
+    // wanted row stride in dwords, mod 64.  (16x16 tiles, bf16 out: an 8-byte write is served 32 lanes at a time -- 16
+    // rows x 2 column groups, 4 dwords a row -- so rows 4 dwords apart touch every bank once; measured 2-3 % on
+    // launches of one tile per CU.  The same reasoning gives 2 for 32x32 tiles, which measured 4-6 % slower than 4.)
+    static constexpr int EPI_Q = (MI == 16 && OSIZE == 2) ? 4 : (kWave / MI) * OSIZE;
     static constexpr int EPI_STRIDE = EPI_ROW + 4 * ((EPI_Q - EPI_ROW / 4) & 63);   // bytes
     static constexpr int EPI_WAVE_BYTES = MI * EPI_STRIDE;
     static constexpr bool LDS_EPI = (WK == 1) && (EPI_ROW >= 128) && (NW * EPI_WAVE_BYTES <= LDS_BYTES);
