@@ -164,6 +164,38 @@ def small_case_leg(wt, wt_synth, torch, np, picks_from):
         wt.wt_destroy(ctx)
 
 
+def stream_leg(wt, wt_synth, torch, np, ctx, draws=24, seed=2005):
+    """Outside the timed step: the runtime stream (10,000 seeded shapes, M log-uniform in 1..8192, four (N, K) pairs).
+    wt_select's latency over all 10,000 shapes, and pick vs exhaustive search on a seeded sample of `draws` of them
+    (every configuration of the registry, 3 warm-up + 5 timed launches each, configurations more than 2.5 times
+    slower than the running best dropped after one launch -- a bounded sample so that the run stays short; the
+    325- and 311-shape samples are in results/stream_bf16*.json)."""
+    from paper_2604_10187_amd import evaluate
+
+    shapes = wt_synth.stream_shapes()
+    mean_ns, p99_ns = wt.wt_select_bench(ctx, shapes, repeats=5)
+    rng = np.random.default_rng(seed)
+    sample = sorted({shapes[i] for i in rng.choice(len(shapes), size=draws, replace=False)})
+    ex = evaluate.Exhaustive(ctx, torch, wt.WT_BF16, wt.WT_OUT_BF16, prune=2.5, warmup=3, iters=5, refine=0)
+    fracs, tf = [], []
+    for (M, N, K) in sample:
+        pick = wt.wt_select(ctx, M, N, K)
+        times = ex.run(M, N, K, must=(pick.id,))
+        fracs.append(min(times.values()) / times[pick.id])
+        tf.append(2.0 * M * N * K / times[pick.id] / 1e6)
+    fr = np.array(fracs)
+    return {"workload": "runtime stream: 10,000 seeded shapes, M log-uniform 1..8192, (N,K) in {(8192,8192),(28672,8192),"
+                        "(8192,28672),(10240,8192)}, bf16",
+            "select_us_mean": round(mean_ns / 1e3, 3), "select_us_p99": round(p99_ns / 1e3, 3),
+            "exhaustive_shapes": len(sample), "sample_seed": seed,
+            "pct_of_exhaustive_best_geomean": round(100.0 * float(np.exp(np.mean(np.log(fr)))), 2),
+            "pct_of_exhaustive_best_min": round(100.0 * float(fr.min()), 2),
+            "share_of_shapes_at_95pct": round(float(np.mean(fr >= 0.95)), 3),
+            "target_pct": 95.0, "meets_target": bool(np.exp(np.mean(np.log(fr))) >= 0.95),
+            "pick_tflops_geomean": round(float(np.exp(np.mean(np.log(tf)))), 1),
+            "exhaustive_launches": ex.launches, "exhaustive_gpu_s": round(ex.gpu_s, 2)}
+
+
 def cpu_baseline(np, wt_synth):
     """The oracle GEMM as it stands (fp64 triple loop in C, rows spread over OpenMP threads), timed on
     a bounded sample of the sweep: the largest sweep shape's first 2048 rows (185 GFLOP)."""
@@ -308,6 +340,9 @@ def main():
     bufs.clear()
     del dA, dB, dC
     torch.cuda.empty_cache()
+    if not a.no_exhaustive:
+        extra["stream"] = stream_leg(wt, wt_synth, torch, np, ctx)
+        torch.cuda.empty_cache()
     roofline = large_prefill_leg(wt, wt_synth, torch, np, in_type, ctx, stream)
     extra["pct_of_mfma_peak_large"] = round(100.0 * roofline["frac"], 2)
     try:

@@ -122,7 +122,17 @@ typedef struct {
                         * S_q = (g / N_h) * T_Q (Eq. 6), and k_anchors holds KV-length multipliers in percent of
                         * S_q (Sec. 5.1: 1.0 to 3.0): L = ceil(floor(S_q * pct / 100) / T_KV), S_kv = L * T_KV.
                         * tau, W_row, W_split are unused; max_out_elems caps S_q * N_h * 128. */
+    int32_t weighting; /* wt_weighting: what the least squares of wt_fit's bilinear buckets minimise (below) */
 } wt_grid;
+
+/* Objective of the per-bucket least squares (Sec. 4.3 bucket model; Sec. 5.1 "least-squares regression").
+ *   WT_FIT_ABSOLUTE  sum of (That - T)^2, ordinary least squares: the paper as written, and the default;
+ *   WT_FIT_RELATIVE  sum of ((That - T) / T)^2: every record weighs 1 / T^2.  A deviation made for loop-anchor sets
+ *                    wider than the paper's [1024, 5120]: with anchors from K = 256 to 28672 a bucket's latencies span
+ *                    two orders of magnitude and ordinary least squares spends its accuracy on the long-K records,
+ *                    leaving short-K predictions off by their own size (even negative).  Every record must then have
+ *                    mean_us > 0 (WT_ERR_INVALID_ARG otherwise).  The Step ablation is always fitted absolutely. */
+typedef enum { WT_FIT_ABSOLUTE = 0, WT_FIT_RELATIVE = 1 } wt_weighting;
 
 /* Latency models wt_fit can build into the dual table.  WAVE_BILINEAR is the method (Sec. 4.3);
  * the other two are its ablations (Sec. 5.4) expressed in the same table form:

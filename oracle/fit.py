@@ -88,9 +88,14 @@ def shared_micro(records) -> Optional[tuple[int, list]]:
     return best[1], [(r.G, r.L, r.us) for r in best[2]]
 
 
-def fit_bilinear(rows) -> tuple[tuple, int]:
-    """Ordinary least squares of T ~ alpha*G*L + beta*G + gamma*L + delta (Sec. 4.3, bucket
+def fit_bilinear(rows, relative: bool = False) -> tuple[tuple, int]:
+    """Least squares of T ~ alpha*G*L + beta*G + gamma*L + delta (Sec. 4.3, bucket
     model; Sec. 5.1 "least-squares regression").  rows = [(G, L, T)].
+
+    relative = False: ordinary least squares, the sum of (That - T)^2 -- the paper as written.
+    relative = True: the sum of ((That - T)/T)^2, i.e. every equation of the system divided by its measured T
+    (a reading for loop-anchor sets much wider than the paper's [1024, 5120], where a bucket's latencies span
+    two orders of magnitude; needs T > 0).
 
     Solved in centred, scaled variables u=(G-g0)/sg, v=(L-l0)/sl (on a product grid the columns
     uv, u, v, 1 are mutually orthogonal), then mapped back.  With a single distinct G (or L) the
@@ -107,21 +112,33 @@ def fit_bilinear(rows) -> tuple[tuple, int]:
     sg = float(np.max(np.abs(G - g0))) or 1.0
     sl = float(np.max(np.abs(L - l0))) or 1.0
     u, v, one = (G - g0) / sg, (L - l0) / sl, np.ones_like(G)
+    if relative:
+        if not (T > 0).all():
+            raise ValueError("relative residuals need positive latencies")
+        scale = 1.0 / T      # each equation x.theta = T becomes (x/T).theta = 1
+    else:
+        scale = np.ones_like(T)
+
+    def solve(columns):
+        X = np.stack(columns, axis=1) * scale[:, None]
+        return np.linalg.lstsq(X, T * scale, rcond=None)[0]
+
     a = b = c = 0.0
     if nG >= 2 and nL >= 2:
-        sol = np.linalg.lstsq(np.stack([u * v, u, v, one], axis=1), T, rcond=None)[0]
+        sol = solve([u * v, u, v, one])
         a, b, c, d = (float(x) for x in sol)
         status = 0b1111
     elif nG >= 2:
-        sol = np.linalg.lstsq(np.stack([u, one], axis=1), T, rcond=None)[0]
+        sol = solve([u, one])
         b, d = float(sol[0]), float(sol[1])
         status = 0b1010
     elif nL >= 2:
-        sol = np.linalg.lstsq(np.stack([v, one], axis=1), T, rcond=None)[0]
+        sol = solve([v, one])
         c, d = float(sol[0]), float(sol[1])
         status = 0b1100
     else:
-        d = float(T.mean())
+        # the minimiser of sum((d - T)^2) is the mean; of sum(((d - T)/T)^2) it is sum(1/T) / sum(1/T^2)
+        d = float(np.sum(1.0 / T) / np.sum(1.0 / T ** 2)) if relative else float(T.mean())
         status = 0b1000
     alpha = a / (sg * sl)
     beta = b / sg - a * l0 / (sg * sl)
@@ -143,7 +160,7 @@ def thin_anchors(anchors: list, limit=None) -> list:
     return [anchors[(i * (n - 1)) // (limit - 1)] for i in range(limit)]
 
 
-def _fit_group(records, max_anchors=None) -> Bucket:
+def _fit_group(records, max_anchors=None, relative: bool = False) -> Bucket:
     """Shared micro per L, then one bilinear fit over the chosen micros' rows."""
     by_L = defaultdict(list)
     for r in records:
@@ -155,7 +172,7 @@ def _fit_group(records, max_anchors=None) -> Bucket:
             continue
         anchors.append((L, pick[0]))
         rows.extend(pick[1])
-    theta, status = fit_bilinear(rows)
+    theta, status = fit_bilinear(rows, relative)
     return Bucket(theta=theta, status=status, anchors=thin_anchors(anchors, max_anchors))
 
 
@@ -191,10 +208,11 @@ MODEL_WAVE_BILINEAR, MODEL_LINEAR, MODEL_STEP = 0, 1, 2
 
 
 def fit_tables(samples, keys, W: int, p: int, model: int = MODEL_WAVE_BILINEAR, W_row: int = 0,
-               row_fams: int = 1, max_anchors=None) -> DualTable:
+               row_fams: int = 1, max_anchors=None, relative: bool = False) -> DualTable:
     """Build the dual table (Sec. 4.3) with per-key extrapolation entries fitted on the merged
     samples of the last p profiled waves, max(1, W-p+1)..W (Sec. 4.5).  Samples with w > W are
     ignored.  max_anchors: anchor slots per bucket of the table being imitated (see thin_anchors; None = all).
+    relative: the objective of every bilinear bucket fit (see fit_bilinear); the Step ablation is always absolute.
 
     model selects the ablations of Sec. 5.4 expressed in the same table form:
       LINEAR  no wave buckets; one bilinear tuple per key fitted on all waves (stored as the
@@ -206,17 +224,17 @@ def fit_tables(samples, keys, W: int, p: int, model: int = MODEL_WAVE_BILINEAR, 
     if W_row > 0:
         # every few-row family is a further, independent set of buckets built the same way
         # (wave buckets 1..W_row, extrapolation from the last min(p, W_row) of them)
-        t = fit_tables([s for s in samples if s.fam == 0], keys, W, p, model, max_anchors=max_anchors)
+        t = fit_tables([s for s in samples if s.fam == 0], keys, W, p, model, max_anchors=max_anchors, relative=relative)
         t.W_row = W_row
         for f in range(1, row_fams + 1):
             rows_t = fit_tables([s._replace(fam=0) for s in samples if s.fam == f], keys, W_row, min(p, W_row),
-                                max_anchors=max_anchors)
+                                max_anchors=max_anchors, relative=relative)
             t.row_local.append(rows_t.local)
             t.row_ext.append(rows_t.ext)
         return t
     samples = [s for s in samples if s.fam == 0]
     if model == MODEL_LINEAR:
-        t = fit_tables(samples, keys, W, W, MODEL_WAVE_BILINEAR, max_anchors=max_anchors)
+        t = fit_tables(samples, keys, W, W, MODEL_WAVE_BILINEAR, max_anchors=max_anchors, relative=relative)
         for k in range(len(keys)):
             t.local[k] = [Bucket() for _ in range(W)]
         return t
@@ -242,9 +260,9 @@ def fit_tables(samples, keys, W: int, p: int, model: int = MODEL_WAVE_BILINEAR, 
     local, ext = [], []
     lo = max(1, W - p + 1)
     for k in range(len(keys)):
-        local.append([_fit_group(per_key_w.get((k, w), []), max_anchors) for w in range(1, W + 1)])
+        local.append([_fit_group(per_key_w.get((k, w), []), max_anchors, relative) for w in range(1, W + 1)])
         merged = [s for w in range(lo, W + 1) for s in per_key_w.get((k, w), [])]
-        ext.append(_fit_group(merged, max_anchors))
+        ext.append(_fit_group(merged, max_anchors, relative))
     return DualTable(W=W, keys=list(keys), local=local, ext=ext)
 
 

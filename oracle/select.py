@@ -136,7 +136,8 @@ def read_table(path: str, ws_elems=None, max_split_tiles=None) -> tuple[DualTabl
 
     Header, 16 uint32: magic 'WTDT', version (1, 2 or 3), n_keys, W, I, p, tau_num, tau_den, n_cu,
     A (anchor slots per bucket), in_type, out_type, key_mode, W_row (version >= 2, else 0), number of
-    few-row families (version 3; version 2 has one), 1 reserved.
+    few-row families (version 3; version 2 has one), the least-squares objective the buckets were fitted with
+    (0 absolute, 1 relative; informational, returned in the meta dict).
     Then per key: 8 int32 (bm, bn, bk, nwave, stages, occ, n_micro, split [0 = 1]), int64 cap, and a
     bucket block of R = W+1 rows (w = 1..W, then ext): R*4 float64 theta, R int32 status, R int32
     n_anchor, R*A int32 anchor L, R*A int32 anchor micro.  Versions 2 / 3 append, per key, one further
@@ -180,6 +181,6 @@ def read_table(path: str, ws_elems=None, max_split_tiles=None) -> tuple[DualTabl
     if off != len(raw):
         raise ValueError("trailing bytes in dual table")
     meta = dict(I=I, p=p, tau_num=tnum, tau_den=tden, n_cu=n_cu, A=A, in_type=in_t, out_type=out_t, key_mode=mode,
-                W_row=W_row)
+                W_row=W_row, weighting=hdr[15])
     return DualTable(W=W, keys=keys, local=local, ext=ext, W_row=W_row, row_local=row_local, row_ext=row_ext,
                      ws_elems=ws_elems, max_split_tiles=max_split_tiles), meta

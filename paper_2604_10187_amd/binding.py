@@ -20,6 +20,7 @@ WT_ERR_HIP, WT_ERR_BUFFER_TOO_SMALL, WT_ERR_IO, WT_ERR_NO_DEVICE, WT_ERR_NO_MEMO
 WT_BF16, WT_FP8_E4M3, WT_ATTN_BF16 = 0, 1, 2
 WT_OUT_F32, WT_OUT_BF16 = 0, 1
 WT_MODEL_WAVE_BILINEAR, WT_MODEL_LINEAR, WT_MODEL_STEP = 0, 1, 2
+WT_FIT_ABSOLUTE, WT_FIT_RELATIVE = 0, 1
 WT_CAP_CU_TIMES_OCC, WT_CAP_CU_ONLY = 0, 1
 WT_SPLITK_WS_FLOATS, WT_SPLITK_MAX_TILES, WT_MAX_ANCHORS = 1 << 26, 1 << 16, 8   # as #defined in wt.h
 WT_NOALLOC_WS_FLOATS, WT_NOALLOC_MAX_TILES = 1 << 24, 1 << 15
@@ -56,7 +57,7 @@ class wt_grid(C.Structure):
                 ("warmup", C.c_int32), ("iters", C.c_int32), ("key_first", C.c_int32),
                 ("key_count", C.c_int32), ("max_out_elems", C.c_int64), ("model", C.c_int32),
                 ("W_split", C.c_int32), ("W_row", C.c_int32), ("row_fams", C.c_int32), ("skip_near", C.c_int32),
-                ("n_heads", C.c_int32)]
+                ("n_heads", C.c_int32), ("weighting", C.c_int32)]
 
 
 class WtError(RuntimeError):
@@ -161,10 +162,10 @@ def _stream(stream):
 
 def make_grid(W=40, I=4, tau=(11, 10), p=10, k_anchors=(1024, 2048, 3072, 4096, 5120), warmup=3, iters=5,
               key_first=0, key_count=0, max_out_elems=0, model=0, W_row=0, W_split=0, row_fams=0, skip_near=0,
-              n_heads=0):
+              n_heads=0, weighting=0):
     arr = (C.c_int32 * len(k_anchors))(*k_anchors)
     g = wt_grid(W, I, tau[0], tau[1], p, len(k_anchors), C.cast(arr, C.POINTER(C.c_int32)), warmup, iters,
-                key_first, key_count, max_out_elems, model, W_split, W_row, row_fams, skip_near, n_heads)
+                key_first, key_count, max_out_elems, model, W_split, W_row, row_fams, skip_near, n_heads, weighting)
     g._keep = arr  # keep the anchor array alive with the struct
     return g
 

@@ -266,7 +266,10 @@ static bool solve_small(int n, double a[4][4], double b[4], double x[4]) {
 // Least squares of T ~ alpha*G*L + beta*G + gamma*L + delta through the normal equations in
 // centred variables scaled to unit spread (on a product grid those columns are orthogonal, so the
 // system is nearly diagonal).  Terms that a single distinct G (or L) cannot identify are dropped.
-static int fit_rows(const std::vector<Row>& rows, double th[4]) {
+// relative = false: ordinary least squares, sum of (That - T)^2 (Sec. 4.3 / Sec. 5.1 as written);
+// relative = true: sum of ((That - T) / T)^2 -- every record weighs 1/T^2, so that a bucket whose loop anchors span
+// latencies two orders of magnitude apart is fitted to the same relative accuracy at both ends.
+static int fit_rows(const std::vector<Row>& rows, double th[4], bool relative) {
     th[0] = th[1] = th[2] = th[3] = 0.0;
     const size_t n = rows.size();
     if (n == 0) return 0;
@@ -294,9 +297,10 @@ static int fit_rows(const std::vector<Row>& rows, double th[4]) {
     for (const Row& r : rows) {
         const double u = (r.G - gm) / gs, v = (r.L - lm) / ls;
         const double f[4] = {u * v, u, v, 1.0};
+        const double wgt = relative ? 1.0 / (r.T * r.T) : 1.0;
         for (int i = 0; i < nc; ++i) {
-            for (int j = 0; j < nc; ++j) ata[i][j] += f[cols[i]] * f[cols[j]];
-            atb[i] += f[cols[i]] * r.T;
+            for (int j = 0; j < nc; ++j) ata[i][j] += wgt * (f[cols[i]] * f[cols[j]]);
+            atb[i] += wgt * (f[cols[i]] * r.T);
         }
     }
     if (!solve_small(nc, ata, atb, x)) return 0;
@@ -313,7 +317,7 @@ static int fit_rows(const std::vector<Row>& rows, double th[4]) {
 // One bucket: records of a single <key, wave set>.  For every loop count pick the micro whose mean
 // latency over the bucket's grid sizes is smallest (it must have a record at each of them; ties go
 // to the lower id), keep it as the anchor for that loop count, and fit on those records only.
-static void fit_bucket(std::vector<const wt_sample*>& recs, Bucket& out) {
+static void fit_bucket(std::vector<const wt_sample*>& recs, Bucket& out, bool relative) {
     memset(&out, 0, sizeof(out));
     std::sort(recs.begin(), recs.end(), [](const wt_sample* x, const wt_sample* y) {
         if (x->L != y->L) return x->L < y->L;
@@ -367,7 +371,7 @@ static void fit_bucket(std::vector<const wt_sample*>& recs, Bucket& out) {
         out.anchor_L[a] = anchors[src].first;
         out.anchor_micro[a] = anchors[src].second;
     }
-    out.status = fit_rows(rows, out.th);
+    out.status = fit_rows(rows, out.th, relative);
 }
 
 // Ablation "Step": T = w*(a*L + b) with w = ceil(G/cap).  Shared micro per loop count over all of the
@@ -375,7 +379,7 @@ static void fit_bucket(std::vector<const wt_sample*>& recs, Bucket& out) {
 // magnitude.  With a single distinct L only b is identified.
 static void fit_step(std::vector<const wt_sample*>& recs, int64_t cap, double* a_out, double* b_out, Bucket& anchors) {
     Bucket tmp;
-    fit_bucket(recs, tmp);  // sorts recs by (L, micro, G) and yields the anchors (shared micro per L)
+    fit_bucket(recs, tmp, false);  // sorts recs by (L, micro, G) and yields the anchors (shared micro per L)
     anchors = tmp;
     double sxx = 0, sxz = 0, szz = 0, sxy = 0, szy = 0, xmax = 0, zmax = 0;
     bool many = false;
@@ -419,7 +423,7 @@ static void fit_step(std::vector<const wt_sample*>& recs, int64_t cap, double* a
 
 // Buckets of one sample family: wave buckets 1..W plus the extrapolation entry from the last p waves,
 // laid out as out[key * (W + 1) + (w - 1)] with the extrapolation entry last.
-static int fit_family(const wt_ctx* ctx, int family, int model, int W, int p, const wt_sample* s, size_t n,
+static int fit_family(const wt_ctx* ctx, int family, int model, int W, int p, bool relative, const wt_sample* s, size_t n,
                       std::vector<Bucket>& out) {
     const int nk = static_cast<int>(ctx->keys.size());
     out.assign(static_cast<size_t>(nk) * (W + 1), Bucket{});
@@ -427,6 +431,7 @@ static int fit_family(const wt_ctx* ctx, int family, int model, int W, int p, co
     for (size_t i = 0; i < n; ++i) {
         if (s[i].key_id < 0 || s[i].key_id >= nk) return WT_ERR_INVALID_ARG;
         if (s[i].family != family || s[i].w < 1 || s[i].w > W) continue;
+        if (relative && !(s[i].mean_us > 0.0)) return WT_ERR_INVALID_ARG;   // a relative residual needs T > 0
         by[static_cast<size_t>(s[i].key_id) * W + (s[i].w - 1)].push_back(&s[i]);
     }
     const int first_ext = model == WT_MODEL_LINEAR ? 1 : std::max(1, W - p + 1);
@@ -458,9 +463,9 @@ static int fit_family(const wt_ctx* ctx, int family, int model, int W, int p, co
         for (int w = 1; w <= W; ++w) {
             std::vector<const wt_sample*>& recs = by[static_cast<size_t>(k) * W + (w - 1)];
             if (w >= first_ext) merged.insert(merged.end(), recs.begin(), recs.end());
-            if (model == WT_MODEL_WAVE_BILINEAR) fit_bucket(recs, kb[w - 1]);
+            if (model == WT_MODEL_WAVE_BILINEAR) fit_bucket(recs, kb[w - 1], relative);
         }
-        fit_bucket(merged, kb[W]);
+        fit_bucket(merged, kb[W], relative);
     }
     return WT_OK;
 }
@@ -470,16 +475,19 @@ static int fit_table(wt_ctx* ctx, const wt_grid* grid, const wt_sample* s, size_
     // the same bounds wt_load applies, so that every table that can be fitted and saved can be loaded again
     if (W < 1 || W > kMaxWaves || grid->I < 1 || grid->p < 1 || grid->W_row < 0 || grid->W_row > kMaxWaves) return WT_ERR_INVALID_ARG;
     if (grid->model < WT_MODEL_WAVE_BILINEAR || grid->model > WT_MODEL_STEP) return WT_ERR_INVALID_ARG;
+    if (grid->weighting != WT_FIT_ABSOLUTE && grid->weighting != WT_FIT_RELATIVE) return WT_ERR_INVALID_ARG;
+    const bool relative = grid->weighting == WT_FIT_RELATIVE;
     Table t;
     t.W = W; t.I = grid->I; t.p = grid->p; t.tau_num = grid->tau_num; t.tau_den = grid->tau_den;
-    int rc = fit_family(ctx, 0, grid->model, W, grid->p, s, n, t.buckets);
+    t.weighting = grid->weighting;
+    int rc = fit_family(ctx, 0, grid->model, W, grid->p, relative, s, n, t.buckets);
     if (rc != WT_OK) return rc;
     if (grid->W_row > 0) {  // the few-row families always use the wave-bucketed bilinear model
         if (grid->row_fams < 0 || grid->row_fams > kMaxRowFams) return WT_ERR_INVALID_ARG;
         t.W_row = grid->W_row;
         t.row_fams = grid->row_fams > 0 ? grid->row_fams : 1;
         for (int f = 1; f <= t.row_fams; ++f) {
-            rc = fit_family(ctx, f, WT_MODEL_WAVE_BILINEAR, t.W_row, std::min(grid->p, t.W_row), s, n, t.row_buckets[f - 1]);
+            rc = fit_family(ctx, f, WT_MODEL_WAVE_BILINEAR, t.W_row, std::min(grid->p, t.W_row), relative, s, n, t.row_buckets[f - 1]);
             if (rc != WT_OK) return rc;
         }
     }
@@ -606,7 +614,7 @@ static int save_table(const wt_ctx* ctx, const char* path) {
                               static_cast<uint32_t>(t.tau_den), static_cast<uint32_t>(kNumCU),
                               static_cast<uint32_t>(kMaxAnchors), static_cast<uint32_t>(ctx->in_type),
                               static_cast<uint32_t>(ctx->out_type), static_cast<uint32_t>(ctx->cap_mode),
-                              static_cast<uint32_t>(t.W_row), static_cast<uint32_t>(t.row_fams), 0u};
+                              static_cast<uint32_t>(t.W_row), static_cast<uint32_t>(t.row_fams), static_cast<uint32_t>(t.weighting)};
     bool ok = fwrite(hdr, sizeof(hdr), 1, f) == 1;
     const int R = t.W + 1;
     for (uint32_t k = 0; ok && k < nk; ++k) {
@@ -637,13 +645,14 @@ static int load_table(wt_ctx* ctx, const char* path) {
     if (rc == WT_OK && (hdr[2] != ctx->keys.size() || hdr[9] != static_cast<uint32_t>(kMaxAnchors) ||
                         hdr[8] != static_cast<uint32_t>(kNumCU) || hdr[10] != static_cast<uint32_t>(ctx->in_type) ||
                         hdr[11] != static_cast<uint32_t>(ctx->out_type) || hdr[3] < 1 ||
-                        hdr[3] > static_cast<uint32_t>(kMaxWaves) || hdr[12] > 1u))
+                        hdr[3] > static_cast<uint32_t>(kMaxWaves) || hdr[12] > 1u || hdr[15] > 1u))
         rc = WT_ERR_INVALID_ARG;  // table was built for another registry, device size or storage type
     if (rc == WT_OK) {
         t.W = static_cast<int>(hdr[3]); t.I = static_cast<int>(hdr[4]); t.p = static_cast<int>(hdr[5]);
         t.tau_num = static_cast<int>(hdr[6]); t.tau_den = static_cast<int>(hdr[7]);
         const int R = t.W + 1;
         t.W_row = static_cast<int>(hdr[13]);
+        t.weighting = static_cast<int>(hdr[15]);
         t.row_fams = static_cast<int>(hdr[14]);
         t.buckets.assign(ctx->keys.size() * R, Bucket{});
         for (int fam = 0; fam < t.row_fams; ++fam) t.row_buckets[fam].assign(ctx->keys.size() * (t.W_row + 1), Bucket{});

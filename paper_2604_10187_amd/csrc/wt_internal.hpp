@@ -59,6 +59,7 @@ struct Bucket {
 struct Table {
     bool fitted = false;
     int W = 0, I = 0, p = 0, tau_num = 11, tau_den = 10;
+    int weighting = 0;   // wt_weighting the buckets were fitted with (recorded in the table file; lookups do not use it)
     // buckets[key * (W + 1) + (w - 1)] for w = 1..W; index W is the extrapolation entry
     std::vector<Bucket> buckets;
     // few-row families (extension) f = 1..row_fams, grids of 1, 2, 4 tile rows:

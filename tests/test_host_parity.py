@@ -214,20 +214,28 @@ def _synthetic_samples(keys, W, I, noise_seed=None):
     return arr
 
 
-@pytest.mark.parametrize("noise_seed", [None, 5])
-def test_fit_and_select_parity(ctx, tmp_path, noise_seed):
+@pytest.mark.parametrize("noise_seed,weighting", [(None, 0), (5, 0), (None, 1), (5, 1), (6, 1)])
+def test_fit_and_select_parity(ctx, tmp_path, noise_seed, weighting):
+    """weighting 0: ordinary least squares per bucket; 1: relative residuals (every record weighs 1/T^2)."""
     W, I, p = 12, 4, 5
     keys = _keys(ctx)
     samples = _synthetic_samples(keys, W, I, noise_seed)
-    grid = wt.make_grid(W=W, I=I, p=p, k_anchors=K_ANCHORS)
+    grid = wt.make_grid(W=W, I=I, p=p, k_anchors=K_ANCHORS, weighting=weighting)
     wt.wt_fit(ctx, grid, samples)
     path = str(tmp_path / "table.wt")
     wt.wt_save(ctx, path)
     table, meta = osel.read_table(path, **SPLIT_LIMITS)
     assert meta["I"] == I and meta["p"] == p and table.W == W and len(table.keys) == len(keys)
+    assert meta["weighting"] == weighting
     assert table.keys == keys
     # (1) coefficients and anchors against the oracle's own fit of the same records
-    want = ofit.fit_tables([tuple(r)[:5] + (float(r["mean_us"]),) for r in samples], keys, W, p, max_anchors=MAX_ANCHORS)
+    want = ofit.fit_tables([tuple(r)[:5] + (float(r["mean_us"]),) for r in samples], keys, W, p, max_anchors=MAX_ANCHORS,
+                           relative=bool(weighting))
+    if weighting and noise_seed is not None:
+        # the two objectives are different fits: on noisy records the relative table is not the absolute one
+        other = ofit.fit_tables([tuple(r)[:5] + (float(r["mean_us"]),) for r in samples], keys, W, p, max_anchors=MAX_ANCHORS)
+        assert any(not np.allclose(a.theta, b.theta, rtol=1e-6, atol=0.0)
+                   for k in range(len(keys)) for a, b in zip(want.local[k], other.local[k]) if a.status == 0b1111)
     for k in range(len(keys)):
         for got_b, want_b in list(zip(table.local[k], want.local[k])) + [(table.ext[k], want.ext[k])]:
             assert got_b.status == want_b.status and got_b.anchors == want_b.anchors

@@ -449,3 +449,60 @@ def test_r_squared_exact_surface_hand_value_and_constant_rows():
         worse = list(best)
         worse[i] *= 1.02
         assert ofit.r_squared(noisy, tuple(worse)) < r2
+
+
+# ---- relative least squares (every record weighs 1/T^2) ----------------------------------------------
+def test_relative_fit_recovers_an_exact_surface_and_differs_from_the_absolute_fit_on_noise():
+    th = (3e-4, 0.02, 0.5, 7.0)
+    rows = [(g, l, th[0] * g * l + th[1] * g + th[2] * l + th[3]) for g in (260, 300, 390, 512) for l in (4, 16, 64, 448)]
+    got, status = ofit.fit_bilinear(rows, relative=True)
+    assert status == 0b1111 and np.allclose(got, th, rtol=1e-9)
+    noisy = [(g, l, t * (1.0 + 0.05 * ((i * 7) % 5 - 2) / 2)) for i, (g, l, t) in enumerate(rows)]
+    a, _ = ofit.fit_bilinear(noisy)
+    r, _ = ofit.fit_bilinear(noisy, relative=True)
+    assert not np.allclose(a, r, rtol=1e-4)
+
+    def sum_sq(theta, rel):
+        return sum(((theta[0] * g * l + theta[1] * g + theta[2] * l + theta[3] - t) / (t if rel else 1.0)) ** 2
+                   for g, l, t in noisy)
+    # each fit is the better one under its own objective
+    assert sum_sq(r, True) < sum_sq(a, True) and sum_sq(a, False) < sum_sq(r, False)
+
+
+def test_relative_fit_matches_exact_rational_weighted_normal_equations():
+    """The minimiser of sum(((x.theta - T)/T)^2) solves (X^T D X) theta = X^T D T with D = diag(1/T^2): solved here
+    in exact rationals, in the raw variables (no centring, no scaling), by Gauss-Jordan elimination."""
+    rows = [(257, 8, Fraction(31, 4)), (257, 40, Fraction(97, 4)), (300, 8, Fraction(17, 2)), (300, 40, Fraction(121, 4)),
+            (390, 8, Fraction(45, 4)), (390, 40, Fraction(151, 4)), (512, 8, Fraction(27, 2)), (512, 40, Fraction(95, 2)),
+            (512, 224, Fraction(1001, 4)), (257, 224, Fraction(533, 4))]
+    X = [[Fraction(g * l), Fraction(g), Fraction(l), Fraction(1)] for g, l, _ in rows]
+    A = [[sum(X[n][i] * X[n][j] / rows[n][2] ** 2 for n in range(len(rows))) for j in range(4)] for i in range(4)]
+    b = [sum(X[n][i] / rows[n][2] for n in range(len(rows))) for i in range(4)]     # x * T / T^2
+    for c in range(4):
+        piv = next(r for r in range(c, 4) if A[r][c] != 0)
+        A[c], A[piv], b[c], b[piv] = A[piv], A[c], b[piv], b[c]
+        for r in range(4):
+            if r != c:
+                f = A[r][c] / A[c][c]
+                A[r] = [x - f * y for x, y in zip(A[r], A[c])]
+                b[r] -= f * b[c]
+    exact = [float(b[i] / A[i][i]) for i in range(4)]
+    got, status = ofit.fit_bilinear([(g, l, float(t)) for g, l, t in rows], relative=True)
+    assert status == 0b1111
+    pred = lambda th, g, l: th[0] * g * l + th[1] * g + th[2] * l + th[3]
+    for g, l, _ in rows:      # coefficients cancel heavily: compare through the predictions they give
+        assert abs(pred(got, g, l) - pred(exact, g, l)) <= 1e-9 * abs(pred(exact, g, l))
+
+
+def test_relative_fit_of_a_constant_is_the_ratio_of_inverse_sums():
+    # one grid size, one loop count: d minimises sum((d - T)^2 / T^2)  =>  d = sum(1/T) / sum(1/T^2)
+    got, status = ofit.fit_bilinear([(64, 8, 1.0), (64, 8, 2.0)], relative=True)
+    assert status == 0b1000 and got[:3] == (0.0, 0.0, 0.0) and abs(got[3] - 1.2) < 1e-12
+    # a single distinct G: slope and intercept in L, again by hand -- T(L=1) in {1, 2}, T(L=3) = 4:
+    # weights 1, 1/4, 1/16; normal equations of c*L + d:  [[1+1/4+9/16, 1+1/4+3/16],[.., 1+1/4+1/16]] [c d] = [1+1/2+3/4, 1+1/2+1/4]
+    got, status = ofit.fit_bilinear([(64, 1, 1.0), (64, 1, 2.0), (64, 3, 4.0)], relative=True)
+    A = np.array([[29 / 16, 23 / 16], [23 / 16, 21 / 16]])
+    c, d = np.linalg.solve(A, np.array([9 / 4, 7 / 4]))
+    assert status == 0b1100 and abs(got[2] - c) < 1e-12 and abs(got[3] - d) < 1e-12
+    with pytest.raises(ValueError):
+        ofit.fit_bilinear([(64, 8, 0.0), (64, 8, 2.0)], relative=True)
