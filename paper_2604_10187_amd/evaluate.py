@@ -145,6 +145,21 @@ def cmd_sweep(a, torch):
     return {"workload": "LLM-projection sweep (27 shapes)", "table": path, "summary": summary, "rows": rows}
 
 
+def cmd_shapes(a, torch):
+    """Pick vs exhaustive search on a named synthetic shape set: `paper` = shapes in the ranges of the paper's
+    Dense-GEMM test set, `shortk` = small launches with K from 256 to 2048 (wt_synth)."""
+    import wt_synth
+
+    ctx, path = _open_ctx(a, torch)
+    sets = {"paper": ("shapes in the ranges of the paper's Dense-GEMM test set (M 64..16384, N 384..8192, K 2048..8192)",
+                      wt_synth.paper_range_shapes),
+            "shortk": ("small launches, K in {256..2048}, M 16..4096, N 256..4096", wt_synth.short_k_shapes)}
+    name, gen = sets[a.set]
+    ex = Exhaustive(ctx, torch, a.in_type, a.out_type, prune=a.prune, refine=a.refine)
+    rows, summary = _pick_vs_best(ctx, ex, gen())
+    return {"workload": name, "table": path, "summary": summary, "rows": rows}
+
+
 def cmd_stream(a, torch):
     import wt_synth
 
@@ -455,13 +470,18 @@ def cmd_ablate(a, torch=None):
     anchors = tune.KV_MULTIPLIERS if attn else tune.K_ANCHORS
     shape = (lambda r: (r["S_q"], r["H_q"], r["S_kv"])) if attn else (lambda r: (r["M"], r["N"], r["K"]))
 
-    def score(model, W, I, cap_mode, W_row=0, row_fams=0):
+    def score(model, W, I, cap_mode, W_row=0, row_fams=0, weighting=None, short_k=True):
+        weighting = a.weighting if weighting is None else weighting
         ctx = wt.wt_create(-1, a.in_type, a.out_type)
         wt.wt_set_capacity_mode(ctx, cap_mode)
         for k, o in enumerate(occ):
             wt.wt_key_set_occ(ctx, k, int(o))
         sub = recs[((recs["family"] == 0) & (recs["w"] <= W)) |
                    ((recs["family"] >= 1) & (recs["family"] <= row_fams) & (recs["w"] <= W_row))]
+        if not short_k and not attn:     # leave out the records of loop anchors below K = 1024
+            lo = np.array([-(-1024 // (wt.wt_config_get(ctx, 3 * k)[0].bk * wt.wt_config_get(ctx, 3 * k)[0].split))
+                           for k in range(len(occ))])
+            sub = sub[sub["L"] >= lo[sub["key_id"]]]
         if I < I0:       # sub-intervals of a coarser split are unions of the finer ones: keep each union's top sample
             keep = np.zeros(len(sub), dtype=bool)
             step = I0 // I
@@ -473,7 +493,7 @@ def cmd_ablate(a, torch=None):
                 keep[np.where(m)[0]] = (idx % step) == (step - 1)
             sub = sub[keep]
         wt.wt_fit(ctx, wt.make_grid(W=W, I=I, p=min(a.p, W), k_anchors=anchors, model=model, W_row=W_row,
-                                      row_fams=row_fams, n_heads=32 if attn else 0), sub)
+                                      row_fams=row_fams, n_heads=32 if attn else 0, weighting=weighting), sub)
         fr = []
         for r in rows:
             c = wt.wt_select(ctx, *shape(r))
@@ -491,6 +511,11 @@ def cmd_ablate(a, torch=None):
                                 **score(0, W0, I0, a.cap_mode, Wr, nf)})
     for name, model in (("wave-bilinear (full)", 0), ("linear", 1), ("step", 2)):
         out["variants"].append({"model": name, "W": W0, "I": I0, **score(model, W0, I0, a.cap_mode)})
+    if not attn:
+        for wname, wgt in (("relative", 1), ("ordinary", 0)):
+            for sname, sk in (("with", True), ("without", False)):
+                out["variants"].append({"model": f"wave-bilinear, {wname} least squares, {sname} the K = 256 / 512 anchors",
+                                        "W": W0, "I": I0, **score(0, W0, I0, a.cap_mode, weighting=wgt, short_k=sk)})
     for W in sorted({w for w in (2, 5, 10, 20, W0) if w <= W0}):
         for I in sorted({i for i in (1, 2, I0) if I0 % i == 0}):
             if (W, I) != (W0, I0):
@@ -502,11 +527,13 @@ def cmd_ablate(a, torch=None):
 
 def main(argv=None):
     ap = argparse.ArgumentParser()
-    ap.add_argument("cmd", choices=["sweep", "wave", "stream", "large", "grouped", "persistent", "vendor", "ablate", "attn"])
+    ap.add_argument("cmd", choices=["sweep", "wave", "stream", "shapes", "large", "grouped", "persistent", "vendor", "ablate", "attn"])
+    ap.add_argument("--set", choices=["paper", "shortk"], default="paper", help="shapes: which synthetic shape set")
     ap.add_argument("--causal", action="store_true", help="attn: causal masking (queries aligned to the end of the keys)")
     ap.add_argument("--samples", default=None, help="ablate: .npz with `samples` and `occ`")
     ap.add_argument("--scores", nargs="*", default=[], help="ablate: sweep/stream result files with exhaustive timings")
     ap.add_argument("--cap-mode", type=int, default=1)
+    ap.add_argument("--weighting", type=int, default=1, help="ablate: objective of the bucket fits (0 ordinary, 1 relative: the shipped GEMM tables)")
     ap.add_argument("--I", type=int, default=4)
     ap.add_argument("--p", type=int, default=10)
     ap.add_argument("--in-type", type=int, default=wt.WT_BF16)
@@ -527,12 +554,12 @@ def main(argv=None):
     else:
         import torch
 
-        res = {"sweep": cmd_sweep, "wave": cmd_wave, "stream": cmd_stream, "large": cmd_large, "grouped": cmd_grouped, "persistent": cmd_persistent, "vendor": cmd_vendor, "attn": cmd_attn}[a.cmd](a, torch)
+        res = {"sweep": cmd_sweep, "wave": cmd_wave, "stream": cmd_stream, "shapes": cmd_shapes, "large": cmd_large, "grouped": cmd_grouped, "persistent": cmd_persistent, "vendor": cmd_vendor, "attn": cmd_attn}[a.cmd](a, torch)
     txt = json.dumps(res)
     if a.out:
         open(a.out, "w").write(txt)
     summ = res.get("summary") or {k: v for k, v in res.items() if k != "rows"}
-    print(json.dumps(summ if a.cmd in ("sweep", "stream", "attn") else {"workload": res["workload"]}))
+    print(json.dumps(summ if a.cmd in ("sweep", "stream", "shapes", "attn") else {"workload": res["workload"]}))
 
 
 if __name__ == "__main__":

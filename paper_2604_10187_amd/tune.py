@@ -29,6 +29,12 @@ K_ANCHORS = (1024, 2048, 3072, 4096, 5120, 8192)
 # interpolated in L instead of extrapolated.  Deeper waves of such K would take hours to profile and keep six.
 K_ANCHORS_LONG = (16384, 28672)
 W_LONG = 12
+# Third pass of the shipped GEMM tables: two short-K anchors over the same first waves (`--W 12 --k-anchors 256 512`,
+# a few seconds of GPU time).  Below K = 1024 a launch is mostly fixed cost, which no plane through the anchors
+# above shows: extrapolated downwards they predict a fraction of a microsecond, or less than nothing, for launches
+# that take three.  With anchors from 256 to 28672 a bucket's latencies span two orders of magnitude, so the shipped
+# tables are fitted with relative residuals (`--weighting 1`, WT_FIT_RELATIVE).
+K_ANCHORS_SHORT = (256, 512)
 # Attention contexts: KV-length multipliers of S_q in percent (Sec. 5.1: 1.0 to 3.0).
 KV_MULTIPLIERS = (100, 150, 200, 250, 300)
 
@@ -59,7 +65,8 @@ def profile(ctx, grid, in_type, out_type, log=print, chunk_keys=1):
         g = wt.make_grid(W=grid.W, I=grid.I, tau=(grid.tau_num, grid.tau_den), p=grid.p,
                          k_anchors=[grid.k_anchors[j] for j in range(grid.n_k_anchors)], warmup=grid.warmup,
                          iters=grid.iters, key_first=k0, key_count=kc, max_out_elems=grid.max_out_elems, model=grid.model, W_row=grid.W_row,
-                         W_split=grid.W_split, row_fams=grid.row_fams, skip_near=grid.skip_near, n_heads=grid.n_heads)
+                         W_split=grid.W_split, row_fams=grid.row_fams, skip_near=grid.skip_near, n_heads=grid.n_heads,
+                         weighting=grid.weighting)
         recs = wt.wt_profile_sparse(ctx, g, scrA, scrB, scrC, stream=torch.cuda.current_stream())
         out.append(recs)
         log(f"[tune] keys {k0}..{k0 + kc - 1}: {len(recs)} records, {time.time() - t0:.0f}s elapsed")
@@ -87,6 +94,8 @@ def main(argv=None):
     ap.add_argument("--W-row", type=int, default=0, help="extension: waves of single-tile-row grids to profile/fit (0 = off)")
     ap.add_argument("--row-fams", type=int, default=1, help="extension: few-row families to profile/fit when --W-row > 0 (1..3: 1, 2, 4 tile rows)")
     ap.add_argument("--skip-near", action="store_true", help="profile only the few-row families (records are merged by --fit-from)")
+    ap.add_argument("--weighting", type=int, default=0,
+                    help="objective of the bucket fits: 0 ordinary least squares (the paper as written), 1 relative residuals")
     ap.add_argument("--W-split", type=int, default=8, help="split-K keys are profiled for the first W-split waves only (0 = all)")
     ap.add_argument("--samples-out", default=None)
     ap.add_argument("--fit-from", nargs="*", default=None)
@@ -101,7 +110,7 @@ def main(argv=None):
     grid = wt.make_grid(W=a.W, I=a.I, p=a.p, k_anchors=a.k_anchors, warmup=a.warmup, iters=a.iters,
                         key_first=a.key_first, key_count=a.key_count, max_out_elems=a.max_out_elems, model=a.model, W_row=a.W_row,
                         W_split=a.W_split, row_fams=a.row_fams, skip_near=int(a.skip_near),
-                        n_heads=a.n_heads[0] if attn else 0)
+                        n_heads=a.n_heads[0] if attn else 0, weighting=a.weighting)
     if a.fit_from is not None:
         recs = np.concatenate([np.load(f) for f in a.fit_from])
         occ_files = [f.replace(".npy", ".occ.npy") for f in a.fit_from]

@@ -70,7 +70,8 @@ def test_shipped_tables_are_the_oracles_fit_of_the_shipped_records(in_type, stem
     recs = np.load(os.path.join(TABLES, stem + "_samples.npz"))["samples"]
     samples = [(int(r["key_id"]), int(r["micro_id"]), int(r["G"]), int(r["L"]), int(r["w"]), float(r["mean_us"]),
                 int(r["family"])) for r in recs]
-    mine = ofit.fit_tables(samples, table.keys, table.W, meta["p"], max_anchors=MAX_ANCHORS)
+    mine = ofit.fit_tables(samples, table.keys, table.W, meta["p"], max_anchors=MAX_ANCHORS,
+                           relative=bool(meta["weighting"]))      # the objective the file says it was fitted with
     n_fitted = 0
     for k in range(len(table.keys)):
         for w in range(table.W + 1):

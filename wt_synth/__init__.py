@@ -90,6 +90,33 @@ def stream_shapes(count: int = 10000, seed: int = 1005):
     return out
 
 
+def paper_range_shapes(count: int = 60, seed: int = 3001):
+    """Shapes in the ranges of the paper's Dense-GEMM test set (Sec. 5.1: M in [64, 16384], N in [384, 8192],
+    K in [2048, 8192]; the set itself is not public): M log-uniform, N log-uniform rounded to a multiple of 128,
+    K a multiple of 256.  `count` distinct shapes, sorted."""
+    rng = np.random.default_rng(seed)
+    out = set()
+    while len(out) < count:
+        m = int(round(math.exp(rng.uniform(math.log(64), math.log(16384)))))
+        n = int(round(math.exp(rng.uniform(math.log(384), math.log(8192))) / 128)) * 128
+        k = int(rng.integers(8, 33)) * 256
+        out.add((m, max(n, 384), k))
+    return sorted(out)
+
+
+def short_k_shapes(count: int = 40, seed: int = 3002):
+    """Small launches below the paper's lowest loop anchor and around it: M log-uniform in [16, 4096],
+    N in {256 .. 4096}, K in {256, 512, 1024, 1536, 2048}, plus the cubes 256, 512 and 1024.  Sorted."""
+    rng = np.random.default_rng(seed)
+    out = {(256, 256, 256), (1024, 1024, 1024), (512, 512, 512)}
+    while len(out) < count:
+        m = int(round(math.exp(rng.uniform(math.log(16), math.log(4096)))))
+        n = int(rng.choice([256, 512, 1024, 2048, 4096]))
+        k = int(rng.choice([256, 512, 1024, 1536, 2048]))
+        out.add((m, n, k))
+    return sorted(out)
+
+
 def noise_factors(n: int, seed: int, rel: float) -> np.ndarray:
     """n multiplicative noise factors 1 + rel*N(0,1), clipped to stay positive."""
     rng = np.random.default_rng(seed)
