@@ -557,6 +557,7 @@ def main(argv=None):
         res = {"sweep": cmd_sweep, "wave": cmd_wave, "stream": cmd_stream, "shapes": cmd_shapes, "large": cmd_large, "grouped": cmd_grouped, "persistent": cmd_persistent, "vendor": cmd_vendor, "attn": cmd_attn}[a.cmd](a, torch)
     txt = json.dumps(res)
     if a.out:
+        os.makedirs(os.path.dirname(os.path.abspath(a.out)), exist_ok=True)
         open(a.out, "w").write(txt)
     summ = res.get("summary") or {k: v for k, v in res.items() if k != "rows"}
     print(json.dumps(summ if a.cmd in ("sweep", "stream", "shapes", "attn") else {"workload": res["workload"]}))

@@ -666,25 +666,27 @@ def test_device_records_are_the_oracles_plan(ctx_bf16, device_records):
     assert r0["mean_us"][np.argmax(r0["G"] * r0["L"])] > r0["mean_us"][np.argmin(r0["G"] * r0["L"])]
 
 
-@pytest.mark.parametrize("model", [wt.WT_MODEL_WAVE_BILINEAR, wt.WT_MODEL_LINEAR, wt.WT_MODEL_STEP])
-def test_profile_fit_select_round_trip_on_device(ctx_bf16, tmp_path, device_records, model):
-    """Device records -> wt_fit under each latency model (the method and its two ablations, Sec. 5.4) -> wt_save;
-    the table equals the oracle's fit of the same records (coefficients to 1e-9, status and anchors exactly), and
-    the oracle's selector on the saved file returns exactly what wt_select returns, prediction included."""
+@pytest.mark.parametrize("model,weighting", [(wt.WT_MODEL_WAVE_BILINEAR, 0), (wt.WT_MODEL_LINEAR, 0),
+                                             (wt.WT_MODEL_STEP, 0), (wt.WT_MODEL_WAVE_BILINEAR, 1)])
+def test_profile_fit_select_round_trip_on_device(ctx_bf16, tmp_path, device_records, model, weighting):
+    """Device records -> wt_fit under each latency model (the method and its two ablations, Sec. 5.4; the method also
+    with relative residuals, the objective of the shipped tables) -> wt_save; the table equals the oracle's fit of
+    the same records (coefficients to 1e-9, status and anchors exactly), and the oracle's selector on the saved
+    file returns exactly what wt_select returns, prediction included."""
     from _pins import lib_limits, split_limits
     from oracle import fit as ofit
     from oracle import select as osel
 
     recs = np.concatenate(device_records)
-    grid = wt.make_grid(W=RT_W, I=RT_I, p=RT_P, k_anchors=RT_ANCHORS, W_split=RT_WSPLIT, model=model)
+    grid = wt.make_grid(W=RT_W, I=RT_I, p=RT_P, k_anchors=RT_ANCHORS, W_split=RT_WSPLIT, model=model, weighting=weighting)
     wt.wt_fit(ctx_bf16, grid, recs)
-    path = str(tmp_path / f"t{model}.wt")
+    path = str(tmp_path / f"t{model}_{weighting}.wt")
     wt.wt_save(ctx_bf16, path)
     table, _ = osel.read_table(path, **split_limits())
     profiled = {k for (first, count) in RT_SLICES for k in range(first, first + count)}
     want = ofit.fit_tables([(int(r["key_id"]), int(r["micro_id"]), int(r["G"]), int(r["L"]), int(r["w"]),
                              float(r["mean_us"])) for r in recs], table.keys, RT_W, RT_P, model=model,
-                           max_anchors=lib_limits()["max_anchors"])
+                           max_anchors=lib_limits()["max_anchors"], relative=bool(weighting))
     n_fitted = 0
     for k in range(len(table.keys)):
         for got_b, want_b in list(zip(table.local[k], want.local[k])) + [(table.ext[k], want.ext[k])]:
