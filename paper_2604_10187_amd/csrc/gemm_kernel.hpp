@@ -206,6 +206,10 @@ struct GemmTraits {
     // 256 accumulators per lane (one wavefront per SIMD): the MFMAs are issued from inline asm that accumulates in
     // place in the accumulation registers
     static constexpr bool ASMACC = (IN == 0) && (MI == 16) && (FM * FN == 64) && (WK == 1);
+    // fp8, 256 accumulators per lane on 16x16x128 MFMAs (asked for with MIF = 16): one k-step per k-tile, a fragment
+    // is 8 registers, so two full fragment sets do not fit beside the accumulators.  The A fragments are kept in ONE
+    // set and replaced row by row as the MFMAs of a row are issued; only the B fragments are double-buffered.
+    static constexpr bool ROLL = (IN == 1) && (MIF == 16) && (FM == 8) && (FN == 8) && (WK == 1) && (ST == 2) && (BK == KS);
     // Epilogue through LDS (when a sub-tile row of C is at least one 128-byte line and the staging fits the
     // workgroup's LDS): the MFMA operands are swapped so that a lane holds four consecutive columns of one row,
     // each wavefront parks one row of MFMA tiles (MI rows x TN columns, converted to the output type) in its own
@@ -223,7 +227,7 @@ struct GemmTraits {
     // Persistent kernel: when the C staging fits beside the stages, the next task's first k-tiles are requested before
     // this task's epilogue (the staging then lives behind the stages); 16 more bytes hold the next task's index.
     static constexpr int EPI_BYTES = LDS_EPI ? NW * EPI_WAVE_BYTES : 0;
-    static constexpr bool PIPE_OK = (ST >= 2) && (WK == 1) && (LDS_BYTES + EPI_BYTES + 16 <= 160 * 1024);
+    static constexpr bool PIPE_OK = (ST >= 2) && (WK == 1) && !ROLL && (LDS_BYTES + EPI_BYTES + 16 <= 160 * 1024);
     // (kernels without that room pass the index through the first bytes of the stages, between tasks)
     static constexpr int SLOT_OFF = PIPE_OK ? LDS_BYTES + EPI_BYTES : 0;
     static constexpr int LDS_BYTES_PERSISTENT = PIPE_OK ? SLOT_OFF + 16 : LDS_BYTES;
@@ -522,6 +526,77 @@ __device__ __forceinline__ void gemm_task(const GemmArgs& args, const TaskDesc& 
                 }
                 block_barrier();
             }
+        } else if constexpr (T::ROLL) {
+            // One k-step per k-tile, 64 MFMAs in row-major order (A fragment i against B fragments 0..7).  Everything
+            // k-tile t needs from LDS is read during k-tile t-1: B into the other B set, A fragment i into the single
+            // A set as soon as row i of k-tile t-1 has been issued.  So when a wavefront has issued row 0 of k-tile t
+            // and waited for its reads, it has nothing left to read from stage t%2: it waits for its share of k-tile
+            // t+1, meets the others at the barrier, and over rows 1..7 reads k-tile t+1's fragments and (rows 1..4)
+            // issues k-tile t+2 into the freed stage.  Row 0 ahead of the barrier hides the latency of the last reads
+            // of the previous k-tile (A fragment 7, issued after its row 7).
+            static_assert(T::LPW == 16 && KSTEPS == 1, "shape of the rolling schedule");
+            frag_t fa[8], fb[2][8];
+            if (!prefetched) {
+                issue_tile(0, 0);
+                issue_tile(1, 1);
+                wait_vmcnt<T::LPW>();
+            } else {
+                wait_vmcnt<0>();
+            }
+            block_barrier();
+    #pragma unroll
+            for (int i = 0; i < 8; ++i) fa[i] = read_frag(0, wm * T::TM + i * T::MI + frow, 0);
+    #pragma unroll
+            for (int j = 0; j < 8; ++j) fb[0][j] = read_frag(0, BM + wn * T::TN + j * T::MI + frow, 0);
+            int stage = 0;
+            // (LDS epilogue: the B fragment is the MFMA's row operand, the A fragment its column operand)
+            auto mf = [&](int i, int j, const frag_t& bj) {
+                asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(bj), "v"(fa[i]));
+            };
+            static_assert(T::LDS_EPI, "operand order of the in-place MFMA");
+            auto tile_body = [&](int kt, auto tail_tag, auto par_tag) {
+                constexpr bool TAIL = decltype(tail_tag)::value;
+                constexpr int P = decltype(par_tag)::value;
+                const int nxt = stage ^ 1;
+    #pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    mf(0, j, fb[P][j]);
+                    sched_fence();
+                }
+                wait_lgkmcnt0();     // every fragment of k-tile kt is in registers
+                wait_vmcnt<0>();     // this wavefront's share of k-tile kt+1 has landed
+                block_barrier();
+                sched_fence();
+    #pragma unroll
+                for (int r = 1; r < 8; ++r) {
+    #pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        mf(r, j, fb[P][j]);
+                        if (j == 0) fa[r - 1] = read_frag(nxt, wm * T::TM + (r - 1) * T::MI + frow, 0);
+                        if (j == 4) fb[P ^ 1][r - 1] = read_frag(nxt, BM + wn * T::TN + (r - 1) * T::MI + frow, 0);
+                        if (r == 7 && j == 6) fb[P ^ 1][7] = read_frag(nxt, BM + wn * T::TN + 7 * T::MI + frow, 0);
+                        if (r <= 4 && (j & 1) == 0) issue_load((r - 1) * 4 + j / 2, kt + 2, stage, TAIL);
+                        sched_fence();
+                    }
+                }
+                fa[7] = read_frag(nxt, wm * T::TM + 7 * T::MI + frow, 0);   // (used last; in by the next barrier)
+                sched_fence();
+                stage = nxt;
+            };
+            using P0 = std::integral_constant<int, 0>;
+            using P1 = std::integral_constant<int, 1>;
+            int kt = 0;
+            for (; kt + 3 < L_full; kt += 2) {      // both refill targets, kt+2 and kt+3, lie wholly inside K
+                tile_body(kt, std::false_type{}, P0{});
+                tile_body(kt + 1, std::false_type{}, P1{});
+            }
+            for (; kt < L; kt += 2) {
+                tile_body(kt, std::true_type{}, P0{});
+                if (kt + 1 < L) tile_body(kt + 1, std::true_type{}, P1{});
+            }
+            wait_vmcnt<0>();
+            wait_lgkmcnt0();
+            asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
         } else {
             // Software pipeline, one barrier per k-tile.  Every MFMA is followed by at most one fragment
             // read and a share of the global->LDS loads, and the scheduler is fenced after each such
