@@ -297,18 +297,35 @@ def main():
                       "mfma_only_ceiling": round(ceiling, 1), "frac_of_mfma_only_ceiling": round(ach / ceiling, 4),
                       "kernel": f"gemm_kernel<{cfg_big.bm},{cfg_big.bn},{cfg_big.bk},nw{cfg_big.nwave},st{cfg_big.stages}>"
                                 f" sw{cfg_big.swizzle} split{cfg_big.split} on {big[0]}x{big[1]}x{big[2]}", "avg_us": round(us_big, 2)}
-    # (2) an HBM-bound shape of the sweep: algorithmic bytes e*(M*K + N*K) + e_out*M*N against 8 TB/s
+    # (2) an HBM-bound shape of the sweep: algorithmic bytes e*(M*K + N*K) + e_out*M*N against 8 TB/s.  Its 90 MB
+    # weight fits the 256 MB memory-side cache, so launches that re-read ONE buffer are served from that cache, not
+    # from HBM: the timed launches rotate over eight copies of the weight (720 MB), as consecutive layers of a model
+    # would; the single-buffer figure is reported beside it.
     sk = SKINNY
     cfg_sk = wt.wt_select(ctx, *sk)
     dA, dB, dC = bufs[sk]
-    us_sk = wt.wt_time_gemm(ctx, *sk, dA, dB, dC, cfg_sk, warmup=3, iters=20, stream=stream)
+    us_sk_cached = wt.wt_time_gemm(ctx, *sk, dA, dB, dC, cfg_sk, warmup=3, iters=20, stream=stream)
+    copies = [dB] + [dB.clone() for _ in range(7)]
+    for b in copies:
+        wt.wt_gemm(ctx, *sk, dA, b, dC, cfg_sk, stream=stream)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for i in range(20 * len(copies)):
+        wt.wt_gemm(ctx, *sk, dA, copies[i % len(copies)], dC, cfg_sk, stream=stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    us_sk = e0.elapsed_time(e1) * 1e3 / (20 * len(copies))
+    del copies
     bytes_sk = 2.0 * (sk[0] * sk[2] + sk[1] * sk[2]) + 2.0 * sk[0] * sk[1]
     gbs = bytes_sk / us_sk / 1e3
     roofline_hbm = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": traffic.get((in_type, cfg_sk.astuple(), tuple(sk))),
                     "algorithmic_bytes": bytes_sk,
                     "kernel": f"gemm_kernel<{cfg_sk.bm},{cfg_sk.bn},{cfg_sk.bk},nw{cfg_sk.nwave},st{cfg_sk.stages}>"
-                              f" sw{cfg_sk.swizzle} split{cfg_sk.split} on {sk[0]}x{sk[1]}x{sk[2]}", "avg_us": round(us_sk, 2)}
+                              f" sw{cfg_sk.swizzle} split{cfg_sk.split} on {sk[0]}x{sk[1]}x{sk[2]}", "avg_us": round(us_sk, 2),
+                    "weights_rotated": 8,
+                    "single_buffer": {"avg_us": round(us_sk_cached, 2), "achieved": round(bytes_sk / us_sk_cached / 1e3, 1),
+                                      "note": "one 90 MB weight re-read from the 256 MB memory-side cache"}}
 
     # ---- pick vs exhaustive search over the frozen grid (same timing protocol for both) --------
     extra = {}

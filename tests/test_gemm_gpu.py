@@ -430,6 +430,29 @@ def test_fp8_integer_matrices_bit_exact_every_config(ctx_fp8_f32):
         assert np.array_equal(got, want), f"{cfg}: max diff {np.abs(got - want).max()}"
 
 
+def test_flagship_kernels_every_k_tile_count_bit_exact(ctx_f32, ctx_fp8_f32):
+    """The two large-prefill kernels (bf16 256x256x64 and fp8 256x256x128 on four wavefronts) run their k-tiles in a
+    software pipeline whose prologue issues two k-tiles and, for fp8, handles k-tiles in pairs: every k-tile count
+    from 1 to 6, with and without a partial last k-tile, ragged M and N, integer data, bit for bit."""
+    for ctx, kind, fields, align in ((ctx_f32, "bf16", (256, 256, 64, 4, 2, 1), 8), (ctx_fp8_f32, "e4m3", (256, 256, 128, 4, 2, 1), 16)):
+        cfg, _ = wt.wt_config_get(ctx, wt.wt_config_find(ctx, *fields))
+        M, N = 300, 523
+        for tiles in range(1, 7):
+            for K in (tiles * cfg.bk, (tiles - 1) * cfg.bk + align, (tiles - 1) * cfg.bk + cfg.bk - align):
+                note(f"k-tile counts {kind} cfg={cfg.astuple()} K={K}")
+                a32, b32 = wt_synth.gemm_operands(M, N, K, 7100 + K, "int")
+                if kind == "bf16":
+                    ab, bb = wt_synth.to_bf16_bits(a32), wt_synth.to_bf16_bits(b32)
+                    want = og.gemm_c(ab, bb, "bf16")
+                    got = run_gemm(ctx, cfg, ab, bb, wt.WT_OUT_F32, fill=float("nan"))
+                else:
+                    ab = torch.from_numpy(a32).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+                    bb = torch.from_numpy(b32).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+                    want = og.gemm_c(ab, bb, "e4m3", 1.0, 1.0)
+                    got = run_gemm(ctx, cfg, ab, bb, wt.WT_OUT_F32, 1.0, 1.0, fill=float("nan"))
+                assert np.array_equal(got, want), f"{kind} K={K}: max diff {np.abs(got - want).max()}"
+
+
 def test_fp8_scaled_normal_inputs(ctx_fp8_f32, ctx_fp8_bf16):
     """N(0,1) inputs quantised with per-tensor scales s = amax/448; C = sA*sB*sum(qA*qB)."""
     M, N, K = 200, 333, 1040
