@@ -359,6 +359,40 @@ def test_bad_table_file(ctx, tmp_path):
         wt.wt_load(ctx, str(tmp_path / "missing.wt"))
 
 
+def test_fit_objective_argument_checks_and_header_word(ctx, tmp_path):
+    """wt_grid.weighting takes WT_FIT_ABSOLUTE or WT_FIT_RELATIVE only; relative residuals need positive latencies;
+    the objective is recorded in header word 15, and a file whose word 15 is zero (every file written before the
+    field existed) loads as an absolutely fitted table."""
+    import struct
+
+    keys = _keys(ctx)
+    samples = _synthetic_samples(keys, 4, 2)
+    with pytest.raises(wt.WtError) as e:
+        wt.wt_fit(ctx, wt.make_grid(W=4, I=2, p=2, k_anchors=K_ANCHORS, weighting=2), samples)
+    assert e.value.status == wt.WT_ERR_INVALID_ARG
+    bad = samples.copy()
+    bad["mean_us"][5] = 0.0
+    with pytest.raises(wt.WtError) as e:
+        wt.wt_fit(ctx, wt.make_grid(W=4, I=2, p=2, k_anchors=K_ANCHORS, weighting=wt.WT_FIT_RELATIVE), bad)
+    assert e.value.status == wt.WT_ERR_INVALID_ARG
+    wt.wt_fit(ctx, wt.make_grid(W=4, I=2, p=2, k_anchors=K_ANCHORS, weighting=wt.WT_FIT_ABSOLUTE), bad)   # fine absolutely
+    wt.wt_fit(ctx, wt.make_grid(W=4, I=2, p=2, k_anchors=K_ANCHORS, weighting=wt.WT_FIT_RELATIVE), samples)
+    path = str(tmp_path / "rel.wt")
+    wt.wt_save(ctx, path)
+    raw = bytearray(open(path, "rb").read())
+    assert struct.unpack_from("<I", raw, 60)[0] == 1
+    pick = wt.wt_select(ctx, 4096, 4096, 4096).id
+    struct.pack_into("<I", raw, 60, 0)
+    old = str(tmp_path / "old.wt")
+    open(old, "wb").write(bytes(raw))
+    wt.wt_load(ctx, old)
+    assert osel.read_table(old, **SPLIT_LIMITS)[1]["weighting"] == 0 and wt.wt_select(ctx, 4096, 4096, 4096).id == pick
+    struct.pack_into("<I", raw, 60, 7)
+    open(old, "wb").write(bytes(raw))
+    with pytest.raises(wt.WtError):
+        wt.wt_load(ctx, old)
+
+
 @pytest.mark.parametrize("model", [wt.WT_MODEL_LINEAR, wt.WT_MODEL_STEP])
 def test_ablation_models_parity(ctx, tmp_path, model):
     """Step and Linear tables built by the library equal the oracle's (coefficients to 1e-9, anchors
