@@ -49,9 +49,13 @@ class Exhaustive:
     """Times every configuration of the registry on one shape; prunes a configuration after one
     timed launch if it is more than `prune` times slower than the best so far."""
 
-    def __init__(self, ctx, torch, in_type, out_type, prune=2.5, warmup=3, iters=5, refine=0):
+    def __init__(self, ctx, torch, in_type, out_type, prune=2.5, warmup=3, iters=5, refine=0, rotate_mb=0):
         self.ctx, self.torch, self.in_type, self.out_type = ctx, torch, in_type, out_type
         self.prune, self.warmup, self.iters, self.refine = prune, warmup, iters, refine
+        # rotate_mb > 0: every launch reads another copy of the weight B, the copies adding up to at least rotate_mb
+        # megabytes (more than the 256 MB memory-side cache), so that B streams from HBM as the weights of consecutive
+        # layers would; launches are then timed from here with events on the launch stream, `iters` rounds over the copies
+        self.rotate_mb = rotate_mb
         self.first_pass = {}
         self.cfgs = [wt.wt_config_get(ctx, i) for i in range(wt.wt_config_count(ctx))]
         self.stream = torch.cuda.current_stream()
@@ -65,8 +69,29 @@ class Exhaustive:
         tiles = -(-M // c.bm) * -(-N // c.bn)
         return c.split == 1 or (tiles <= (1 << 16) and tiles * c.split * c.bm * c.bn <= (1 << 26))
 
+    def _timer(self, M, N, K, A, B, C, sA, sB):
+        """time(cfg, warmup, iters) -> mean microseconds per launch, under the protocol in force."""
+        if self.rotate_mb <= 0:
+            return lambda c, warmup, iters: wt.wt_time_gemm(self.ctx, M, N, K, A, B, C, c, warmup, iters, sA, sB, self.stream)
+        torch = self.torch
+        n = max(2, -(-self.rotate_mb * 1000000 // (B.numel() * B.element_size())))
+        copies = [B] + [B.clone() for _ in range(n - 1)]
+
+        def timed(c, warmup, iters):
+            for i in range(min(warmup, 1) * n):
+                wt.wt_gemm(self.ctx, M, N, K, A, copies[i % n], C, c, sA, sB, stream=self.stream)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(self.stream)
+            for i in range(iters * n):
+                wt.wt_gemm(self.ctx, M, N, K, A, copies[i % n], C, c, sA, sB, stream=self.stream)
+            e1.record(self.stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / (iters * n)
+        return timed
+
     def run(self, M, N, K, must=()):
         A, B, C, sA, sB = _dev_operands(self.torch, M, N, K, self.in_type, self.out_type)
+        time_cfg = self._timer(M, N, K, A, B, C, sA, sB)
         times, best = {}, math.inf
         order = sorted(range(len(self.cfgs)), key=lambda i: i not in must)
         for i in order:
@@ -74,12 +99,12 @@ class Exhaustive:
             if r.occ < 1 or not self.runnable(c, M, N):
                 continue
             if i not in must and best < math.inf:
-                t1 = wt.wt_time_gemm(self.ctx, M, N, K, A, B, C, c, 1, 1, sA, sB, self.stream)
+                t1 = time_cfg(c, 1, 1)
                 self.launches += 2
                 self.gpu_s += 2 * t1 * 1e-6
                 if t1 > self.prune * best:
                     continue
-            t = wt.wt_time_gemm(self.ctx, M, N, K, A, B, C, c, self.warmup, self.iters, sA, sB, self.stream)
+            t = time_cfg(c, self.warmup, self.iters)
             self.launches += self.warmup + self.iters
             self.gpu_s += (self.warmup + self.iters) * t * 1e-6
             times[i] = t
@@ -93,7 +118,7 @@ class Exhaustive:
             again = sorted(times, key=times.get)[: self.refine] + [i for i in must if i in times]
             for i in reversed(list(dict.fromkeys(again))):
                 c, _ = self.cfgs[i]
-                t = wt.wt_time_gemm(self.ctx, M, N, K, A, B, C, c, self.warmup, self.iters, sA, sB, self.stream)
+                t = time_cfg(c, self.warmup, self.iters)
                 self.launches += self.warmup + self.iters
                 self.gpu_s += (self.warmup + self.iters) * t * 1e-6
                 times[i] = min(times[i], t)
@@ -141,9 +166,11 @@ def cmd_sweep(a, torch):
     import wt_synth
 
     ctx, path = _open_ctx(a, torch)
-    ex = Exhaustive(ctx, torch, a.in_type, a.out_type, prune=a.prune, refine=a.refine)
+    ex = Exhaustive(ctx, torch, a.in_type, a.out_type, prune=a.prune, refine=a.refine, rotate_mb=a.rotate_mb)
     rows, summary = _pick_vs_best(ctx, ex, wt_synth.sweep_shapes())
-    return {"workload": "LLM-projection sweep (27 shapes)", "table": path, "summary": summary, "rows": rows}
+    summary["weights_rotated_over_mb"] = a.rotate_mb
+    return {"workload": "LLM-projection sweep (27 shapes)" + (", weights rotating through HBM" if a.rotate_mb else ""),
+            "table": path, "summary": summary, "rows": rows}
 
 
 def cmd_shapes(a, torch):
@@ -545,6 +572,9 @@ def main(argv=None):
     ap.add_argument("--skew", type=float, default=1.0, help="grouped: routing probabilities ~ 1/rank^skew (0 = uniform)")
     ap.add_argument("--sample-seed", type=int, default=2005, help="stream: seed of the sampled draws")
     ap.add_argument("--prune", type=float, default=2.5)
+    ap.add_argument("--rotate-mb", type=int, default=0,
+                    help="sweep: time every launch on another copy of the weight, the copies adding up to this many "
+                         "megabytes (say 1200), so that weights stream from HBM instead of the memory-side cache")
     ap.add_argument("--refine", type=int, default=0,
                     help="sweep / stream: re-time the N fastest configurations and the pick, keep each one's smaller mean")
     ap.add_argument("--cfgs", type=lambda s: [tuple(int(x) for x in c.split(",")) for c in s.split(";")],
