@@ -247,6 +247,14 @@ int wt_select_grouped(const wt_ctx* ctx, int32_t groups, int64_t M_total, int64_
  * synchronises.  The persistent launch policy does not apply. */
 int wt_attn(wt_ctx* ctx, int64_t n_heads, int64_t n_kv_heads, int64_t S_q, int64_t S_kv, const void* Q,
             const void* K, const void* V, void* O, float scale, int causal, wt_cfg cfg, void* hip_stream);
+/* The same for `batch` sequences of equal lengths in one launch: Q and O are [batch, S_q, n_heads, 128], K and V
+ * [batch, S_kv, n_kv_heads, 128].  The grid holds batch * n_heads * ceil(S_q/T_Q) blocks, mapped by `order` as if the
+ * launch had batch * n_heads heads -- Table 2's attention row with the batch folded into N_h -- so the configuration
+ * for such a launch is wt_select(ctx, S_q, batch * n_heads, S_kv).  0 <= batch <= 65536 (0 is a no-op); every other
+ * argument as for wt_attn, which is this call with batch = 1.  Results per sequence are bit-identical to wt_attn's. */
+int wt_attn_batched(wt_ctx* ctx, int64_t batch, int64_t n_heads, int64_t n_kv_heads, int64_t S_q, int64_t S_kv,
+                    const void* Q, const void* K, const void* V, void* O, float scale, int causal, wt_cfg cfg,
+                    void* hip_stream);
 /* wt_time_gemm's protocol for an attention launch. */
 int wt_time_attn(wt_ctx* ctx, int64_t n_heads, int64_t n_kv_heads, int64_t S_q, int64_t S_kv, const void* Q,
                  const void* K, const void* V, void* O, float scale, int causal, wt_cfg cfg, int warmup, int iters,

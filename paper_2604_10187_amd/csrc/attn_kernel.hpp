@@ -2,8 +2,8 @@
 // kernel behind the <G, L> abstraction (Table 2, FlashAttention row: a block owns T_Q query rows of one head and
 // loops over ceil(S_kv / T_KV) key/value tiles).
 //
-// Layout.  Q and O are [S_q, H_q, 128], K and V are [S_kv, H_kv, 128] (token-major, head dimension contiguous);
-// query head h reads KV head h / (H_q / H_kv).
+// Layout.  Q and O are [batch, S_q, H_q, 128], K and V are [batch, S_kv, H_kv, 128] (token-major, head dimension
+// contiguous); query head h reads KV head h / (H_q / H_kv).
 //
 // Per block: NW wavefronts, each owning R = T_Q / NW query rows (32 or 64) and keeping their Q fragments in
 // registers.  Per KV tile:
@@ -46,6 +46,8 @@ struct AttnArgs {
     const __bf16* V;
     __bf16* O;
     int S_q, S_kv, H_q, H_kv;
+    int batch;         // sequences per launch (>= 1): Q/O are [batch, S_q, H_q, 128], K/V [batch, S_kv, H_kv, 128]; blocks are
+                       // mapped as if the launch had batch * H_q heads (Table 2: a batch multiplies N_h in G)
     int q_tiles;       // ceil(S_q / T_Q)
     int order;         // 0: query tiles of a head are consecutive blocks; 1: heads are consecutive blocks;
                        // 2: like 0, but every XCD (blocks are dealt round-robin to 8 of them) gets a contiguous range
@@ -99,8 +101,14 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5;
     int head, qt;
-    attn_block_coords(static_cast<int>(blockIdx.x), a.H_q, a.q_tiles, a.order, head, qt);
+    attn_block_coords(static_cast<int>(blockIdx.x), a.batch * a.H_q, a.q_tiles, a.order, head, qt);
+    const int seq = head / a.H_q;           // which sequence of the batch (block-uniform)
+    head -= seq * a.H_q;
     if (a.causal) qt = a.q_tiles - 1 - qt;  // the query tiles with the most keys start first
+    const __bf16* const Qs = a.Q + static_cast<int64_t>(seq) * a.S_q * a.H_q * kHeadDim;
+    const __bf16* const Ks = a.K + static_cast<int64_t>(seq) * a.S_kv * a.H_kv * kHeadDim;
+    const __bf16* const Vs = a.V + static_cast<int64_t>(seq) * a.S_kv * a.H_kv * kHeadDim;
+    __bf16* const Os = a.O + static_cast<int64_t>(seq) * a.S_q * a.H_q * kHeadDim;
     const int kh = head / (a.H_q / a.H_kv);
     const int q0 = qt * TQ + wave * T::R;
     const int shift = a.S_kv - a.S_q;
@@ -118,7 +126,7 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
 #pragma unroll
     for (int rb = 0; rb < T::RB; ++rb) {
         const int q = q0 + rb * 32 + l32;
-        const __bf16* src = a.Q + (static_cast<int64_t>(q) * a.H_q + head) * kHeadDim + 8 * h;
+        const __bf16* src = Qs + (static_cast<int64_t>(q) * a.H_q + head) * kHeadDim + 8 * h;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
             au32x4 v = {0u, 0u, 0u, 0u};
@@ -141,7 +149,7 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
     }
     auto load_k = [&](int t) {
         const int kv0 = t * TKV;
-        const __bf16* base = a.K + t * tile_stride;
+        const __bf16* base = Ks + t * tile_stride;
         if (kv0 + TKV <= a.S_kv) {
 #pragma unroll
             for (int i = 0; i < T::KC; ++i)
@@ -158,7 +166,7 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
     };
     auto load_v = [&](int t) {
         const int kv0 = t * TKV;
-        const __bf16* base = a.V + t * tile_stride;
+        const __bf16* base = Vs + t * tile_stride;
         if (kv0 + TKV <= a.S_kv) {
 #pragma unroll
             for (int i = 0; i < T::KC; ++i)
@@ -326,7 +334,7 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
         const float lsum = l_run[rb] + __shfl_xor(l_run[rb], 32);
         const float inv = lsum > 0.0f ? 1.0f / lsum : 0.0f;
         if (q >= a.S_q) continue;
-        __bf16* dst = a.O + (static_cast<int64_t>(q) * a.H_q + head) * kHeadDim + 4 * h;
+        __bf16* dst = Os + (static_cast<int64_t>(q) * a.H_q + head) * kHeadDim + 4 * h;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll

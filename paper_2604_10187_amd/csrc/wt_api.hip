@@ -97,15 +97,17 @@ struct Problem {
     int64_t H_kv = 0;
     float scale = 0.0f;
     int causal = 0;
+    int64_t batch = 1;   // sequences per attention launch
 };
 
 constexpr int64_t kMaxSeq = 1 << 22;  // S_q, S_kv: row offsets times heads times 128 stay far below 2^63, block ids below 2^31
 
 int launch_attn(wt_ctx* ctx, const Config& c, const Problem& p, hipStream_t stream) {
     if (p.M == 0 || p.N == 0) return WT_OK;
-    const int64_t q_tiles = ceil_div64(p.M, c.cfg.bm), G = q_tiles * p.N;
-    if (G > 0x7FFFFFFF) return WT_ERR_INVALID_ARG;
+    const int64_t q_tiles = ceil_div64(p.M, c.cfg.bm), G = q_tiles * p.N * p.batch;
+    if (G > 0x7FFFFFFF || p.batch * p.N > 0x7FFFFFFF) return WT_ERR_INVALID_ARG;
     AttnArgs a;
+    a.batch = (int)p.batch;
     a.Q = static_cast<const __bf16*>(p.A); a.K = static_cast<const __bf16*>(p.B);
     a.V = static_cast<const __bf16*>(p.V); a.O = static_cast<__bf16*>(p.C);
     a.S_q = (int)p.M; a.S_kv = (int)p.K; a.H_q = (int)p.N; a.H_kv = (int)p.H_kv;
@@ -529,14 +531,22 @@ static int check_attn_args(const wt_ctx* ctx, int64_t H_q, int64_t H_kv, int64_t
     return WT_OK;
 }
 
-int wt_attn(wt_ctx* ctx, int64_t n_heads, int64_t n_kv_heads, int64_t S_q, int64_t S_kv, const void* Q,
-            const void* K, const void* V, void* O, float scale, int causal, wt_cfg cfg, void* hip_stream) {
+int wt_attn_batched(wt_ctx* ctx, int64_t batch, int64_t n_heads, int64_t n_kv_heads, int64_t S_q, int64_t S_kv,
+                    const void* Q, const void* K, const void* V, void* O, float scale, int causal, wt_cfg cfg,
+                    void* hip_stream) {
     int id = -1;
+    if (batch < 0 || batch > 65536) return WT_ERR_INVALID_ARG;
     const int rc = check_attn_args(ctx, n_heads, n_kv_heads, S_q, S_kv, Q, K, V, O, scale, causal, cfg, &id);
     if (rc != WT_OK) return rc;
+    if (batch == 0) return WT_OK;
     Problem p{S_q, n_heads, S_kv, Q, K, O, nullptr, nullptr};
-    p.V = V; p.H_kv = n_kv_heads; p.scale = scale; p.causal = causal;
+    p.V = V; p.H_kv = n_kv_heads; p.scale = scale; p.causal = causal; p.batch = batch;
     return launch(ctx, ctx->cfgs[id], p, (hipStream_t)hip_stream);
+}
+
+int wt_attn(wt_ctx* ctx, int64_t n_heads, int64_t n_kv_heads, int64_t S_q, int64_t S_kv, const void* Q,
+            const void* K, const void* V, void* O, float scale, int causal, wt_cfg cfg, void* hip_stream) {
+    return wt_attn_batched(ctx, 1, n_heads, n_kv_heads, S_q, S_kv, Q, K, V, O, scale, causal, cfg, hip_stream);
 }
 
 int wt_time_attn(wt_ctx* ctx, int64_t n_heads, int64_t n_kv_heads, int64_t S_q, int64_t S_kv, const void* Q,

@@ -104,6 +104,36 @@ def test_causal_matches_the_oracle(ctx):
             check(run_attn(ctx, cfg, qb, kb, vb, 1), reference(qb, kb, vb, True), f"causal {cfg} {S_q}x{S_kv}")
 
 
+def test_batched_launch_equals_one_launch_per_sequence(ctx):
+    """wt_attn_batched on [batch, S, H, 128] operands: every sequence against the fp64 oracle, and bit for bit what
+    wt_attn writes for that sequence alone; every structural key under every block order, ragged lengths, grouped
+    heads, causal and not (Table 2's attention row with the batch folded into the head count)."""
+    batch, H_q, H_kv = 3, 4, 2
+    for cfg, _ in all_configs(ctx):
+        S_q, S_kv = cfg.bm + 37, 2 * cfg.bk + 9 + cfg.bm
+        seqs = [wt_synth.attn_operands(S_q, S_kv, H_q, H_kv, 900 + 7 * cfg.id + b) for b in range(batch)]
+        qb, kb, vb = (np.stack([s[i] for s in seqs]) for i in range(3))
+        dQ, dK, dV = (dev_bits(x.reshape(-1, 128)).view(torch.bfloat16) for x in (qb, kb, vb))
+        for causal in (0, 1):
+            note(f"attn batched cfg={cfg.astuple()} S_q={S_q} S_kv={S_kv} causal={causal}")
+            dO = torch.full((batch * S_q * H_q, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
+            wt.wt_attn_batched(ctx, batch, H_q, H_kv, S_q, S_kv, dQ, dK, dV, dO, SCALE, causal, cfg,
+                               stream=torch.cuda.current_stream())
+            torch.cuda.synchronize()
+            got = dO.float().cpu().numpy().reshape(batch, S_q, H_q, 128)
+            for b in range(batch):
+                check(got[b], reference(qb[b], kb[b], vb[b], bool(causal)), f"batched {cfg} seq {b} causal {causal}")
+                assert np.array_equal(got[b], run_attn(ctx, cfg, qb[b], kb[b], vb[b], causal)), (cfg, b, causal)
+    # Phi of a batched launch: the batch multiplies the head count
+    cfg, _ = wt.wt_config_get(ctx, wt.wt_config_find(ctx, 128, 1, 64, 4, 1, 0))
+    G, L, w = wt.wt_wave_count(ctx, 1000, batch * 32, 3000, cfg)
+    assert (G, L) == (batch * 32 * 8, 47) and w == -(-G // 256)
+    # batch = 0 is a no-op; a negative batch is refused
+    wt.wt_attn_batched(ctx, 0, H_q, H_kv, S_q, S_kv, dQ, dK, dV, dO, SCALE, 0, cfg, stream=torch.cuda.current_stream())
+    with pytest.raises(wt.WtError):
+        wt.wt_attn_batched(ctx, -1, H_q, H_kv, S_q, S_kv, dQ, dK, dV, dO, SCALE, 0, cfg, stream=torch.cuda.current_stream())
+
+
 def test_sharp_softmax_and_scale(ctx):
     """Queries with gain 6 make the softmax nearly one-hot (large score range): exercises the running maximum
     and the rescaling; also a non-default scale."""
