@@ -255,6 +255,20 @@ int wt_attn(wt_ctx* ctx, int64_t n_heads, int64_t n_kv_heads, int64_t S_q, int64
 int wt_attn_batched(wt_ctx* ctx, int64_t batch, int64_t n_heads, int64_t n_kv_heads, int64_t S_q, int64_t S_kv,
                     const void* Q, const void* K, const void* V, void* O, float scale, int causal, wt_cfg cfg,
                     void* hip_stream);
+/* A batch of sequences of DIFFERENT lengths in one launch, their tokens packed back to back: Q and O are
+ * [total_q, n_heads, 128], K and V [total_kv, n_kv_heads, 128]; cu_q and cu_kv are DEVICE pointers to batch + 1
+ * ascending int32 token offsets (sequence b owns query tokens [cu_q[b], cu_q[b+1]) and key tokens [cu_kv[b],
+ * cu_kv[b+1])).  As with the grouped GEMM the host never reads them (a serving engine builds them on the device): the
+ * grid is sized for the worst case, n_heads * (ceil(total_q/T_Q) + batch) blocks, a block finds its sequence from the
+ * offsets, and blocks past the last query tile exit at once.  Offsets are clipped to [0, total] in the kernel, so no
+ * content of the arrays can make an access leave the tensors.  causal = 1 aligns every sequence's queries to the end
+ * of its own keys; a query that sees no key (a sequence with fewer keys than queries) yields zeros.  0 <= batch <= 1024.
+ * The selector sees only the totals: under the uniform approximation of Sec. 5.2 the configuration is
+ * wt_select(ctx, ceil(total_q/batch), batch * n_heads, ceil(total_kv/batch)).  Results per sequence are bit-identical
+ * to wt_attn's.  Asynchronous, never allocates or synchronises. */
+int wt_attn_varlen(wt_ctx* ctx, int64_t batch, int64_t n_heads, int64_t n_kv_heads, int64_t total_q, int64_t total_kv,
+                   const int32_t* cu_q, const int32_t* cu_kv, const void* Q, const void* K, const void* V, void* O,
+                   float scale, int causal, wt_cfg cfg, void* hip_stream);
 /* wt_time_gemm's protocol for an attention launch. */
 int wt_time_attn(wt_ctx* ctx, int64_t n_heads, int64_t n_kv_heads, int64_t S_q, int64_t S_kv, const void* Q,
                  const void* K, const void* V, void* O, float scale, int causal, wt_cfg cfg, int warmup, int iters,

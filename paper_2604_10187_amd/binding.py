@@ -102,6 +102,7 @@ def lib():
             "wt_select_grouped": [vp, i32, i64, i64, i64, C.POINTER(wt_cfg)],
             "wt_attn": [vp, i64, i64, i64, i64, vp, vp, vp, vp, C.c_float, C.c_int, wt_cfg, vp],
             "wt_attn_batched": [vp, i64, i64, i64, i64, i64, vp, vp, vp, vp, C.c_float, C.c_int, wt_cfg, vp],
+            "wt_attn_varlen": [vp, i64, i64, i64, i64, i64, vp, vp, vp, vp, vp, vp, C.c_float, C.c_int, wt_cfg, vp],
             "wt_time_attn": [vp, i64, i64, i64, i64, vp, vp, vp, vp, C.c_float, C.c_int, wt_cfg, C.c_int, C.c_int, vp,
                              C.POINTER(C.c_double)],
             "wt_attn_block_coords": [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)],
@@ -133,7 +134,7 @@ EXPORTS = ("wt_create", "wt_destroy", "wt_last_hip_error", "wt_status_string", "
            "wt_config_find", "wt_key_count", "wt_key_set_occ", "wt_set_capacity_mode", "wt_set_persistent", "wt_tile_coords", "wt_gemm", "wt_gemm_noalloc", "wt_gemm_grouped",
            "wt_time_gemm_grouped", "wt_wave_count_grouped", "wt_select_grouped", "wt_wave_count", "wt_sample_grid",
            "wt_sample_plan", "wt_profile_sparse", "wt_time_gemm", "wt_mfma_ceiling", "wt_fit", "wt_select", "wt_predict_us",
-           "wt_select_bench", "wt_save", "wt_load", "wt_attn", "wt_attn_batched", "wt_time_attn", "wt_attn_block_coords",
+           "wt_select_bench", "wt_save", "wt_load", "wt_attn", "wt_attn_batched", "wt_attn_varlen", "wt_time_attn", "wt_attn_block_coords",
            "wt_sample_grid_heads")
 
 
@@ -260,6 +261,14 @@ def wt_attn_batched(ctx, batch, n_heads, n_kv_heads, S_q, S_kv, Q, K, V, O, scal
     """Q, O: [batch, S_q, n_heads, 128]; K, V: [batch, S_kv, n_kv_heads, 128]; device bf16."""
     _check(lib().wt_attn_batched(ctx, batch, n_heads, n_kv_heads, S_q, S_kv, _ptr(Q), _ptr(K), _ptr(V), _ptr(O),
                                  float(scale), int(bool(causal)), cfg, _stream(stream)), "wt_attn_batched")
+
+
+def wt_attn_varlen(ctx, batch, n_heads, n_kv_heads, total_q, total_kv, cu_q, cu_kv, Q, K, V, O, scale, causal, cfg,
+                   stream=None):
+    """cu_q, cu_kv: device int32 tensors of batch + 1 token offsets; Q, O: [total_q, n_heads, 128]; K, V: [total_kv, n_kv_heads, 128]."""
+    _check(lib().wt_attn_varlen(ctx, batch, n_heads, n_kv_heads, total_q, total_kv, _ptr(cu_q), _ptr(cu_kv), _ptr(Q),
+                                _ptr(K), _ptr(V), _ptr(O), float(scale), int(bool(causal)), cfg, _stream(stream)),
+           "wt_attn_varlen")
 
 
 def wt_attn(ctx, n_heads, n_kv_heads, S_q, S_kv, Q, K, V, O, scale, causal, cfg, stream=None):

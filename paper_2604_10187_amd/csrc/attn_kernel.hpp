@@ -48,6 +48,13 @@ struct AttnArgs {
     int S_q, S_kv, H_q, H_kv;
     int batch;         // sequences per launch (>= 1): Q/O are [batch, S_q, H_q, 128], K/V [batch, S_kv, H_kv, 128]; blocks are
                        // mapped as if the launch had batch * H_q heads (Table 2: a batch multiplies N_h in G)
+    // Variable-length batch (cu_q != NULL): the sequences' tokens are packed back to back, Q/O [S_q, H_q, 128] and K/V
+    // [S_kv, H_kv, 128] with S_q / S_kv the TOTAL token counts; cu_q / cu_kv are device pointers to batch + 1 ascending
+    // token offsets (sequence b owns [cu[b], cu[b+1])).  q_tiles is then an upper bound, ceil(S_q / T_Q) + batch, on
+    // the query tiles of all sequences together; surplus blocks exit at once.  The offsets are read on the device
+    // only and clipped to [0, S_q] / [0, S_kv], so whatever they hold, every access stays inside the tensors.
+    const int* cu_q;
+    const int* cu_kv;
     int q_tiles;       // ceil(S_q / T_Q)
     int order;         // 0: query tiles of a head are consecutive blocks; 1: heads are consecutive blocks;
                        // 2: like 0, but every XCD (blocks are dealt round-robin to 8 of them) gets a contiguous range
@@ -101,20 +108,71 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5;
     int head, qt;
-    attn_block_coords(static_cast<int>(blockIdx.x), a.batch * a.H_q, a.q_tiles, a.order, head, qt);
-    const int seq = head / a.H_q;           // which sequence of the batch (block-uniform)
-    head -= seq * a.H_q;
-    if (a.causal) qt = a.q_tiles - 1 - qt;  // the query tiles with the most keys start first
-    const __bf16* const Qs = a.Q + static_cast<int64_t>(seq) * a.S_q * a.H_q * kHeadDim;
-    const __bf16* const Ks = a.K + static_cast<int64_t>(seq) * a.S_kv * a.H_kv * kHeadDim;
-    const __bf16* const Vs = a.V + static_cast<int64_t>(seq) * a.S_kv * a.H_kv * kHeadDim;
-    __bf16* const Os = a.O + static_cast<int64_t>(seq) * a.S_q * a.H_q * kHeadDim;
+    int S_q = a.S_q, S_kv = a.S_kv;          // this block's sequence
+    int64_t q_tok0 = 0, kv_tok0 = 0;         // its first query / key token in the tensors
+    if (a.cu_q == nullptr) {
+        attn_block_coords(static_cast<int>(blockIdx.x), a.batch * a.H_q, a.q_tiles, a.order, head, qt);
+        const int seq = head / a.H_q;        // which sequence of the batch (block-uniform)
+        head -= seq * a.H_q;
+        q_tok0 = static_cast<int64_t>(seq) * a.S_q;
+        kv_tok0 = static_cast<int64_t>(seq) * a.S_kv;
+    } else {
+        // qt counts query tiles over the sequences' concatenated tile lists: find the sequence it falls in.  Every
+        // wavefront does the lookup for itself: lane l sums the tiles of sequences [l*c, (l+1)*c), a scan over the
+        // lanes locates the lane whose range holds qt, and only that lane's <= c sequences are walked one by one.
+        attn_block_coords(static_cast<int>(blockIdx.x), a.H_q, a.q_tiles, a.order, head, qt);
+        const int B = a.batch;
+        auto bounds = [&](const int* cu, int total, int b, int& lo, int& hi) {
+            lo = min(max(cu[b], 0), total);
+            hi = min(max(cu[b + 1], lo), total);
+        };
+        const int c = (B + 63) / 64;
+        int mine = 0;
+        for (int i = 0; i < c; ++i) {
+            const int b = lane * c + i;
+            int lo, hi;
+            if (b < B) { bounds(a.cu_q, a.S_q, b, lo, hi); mine += (hi - lo + TQ - 1) / TQ; }
+        }
+        int incl = mine;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int v = __shfl_up(incl, d);
+            if (lane >= d) incl += v;
+        }
+        const int excl = incl - mine;
+        const unsigned long long hit = __ballot(qt >= excl && qt < incl);
+        if (hit == 0) return;                // past the last query tile of the batch
+        const int src = __builtin_amdgcn_readfirstlane(__ffsll(static_cast<long long>(hit)) - 1);
+        int first = __builtin_amdgcn_readfirstlane(__shfl(excl, src));
+        int b = src * c, lo = 0, hi = 0;
+        bool found = false;
+        for (int i = 0; i < c && b < B; ++i, ++b) {
+            bounds(a.cu_q, a.S_q, b, lo, hi);
+            const int t = (hi - lo + TQ - 1) / TQ;
+            if (qt < first + t) { found = true; break; }
+            first += t;
+        }
+        if (!found) return;
+        qt -= first;
+        S_q = hi - lo;
+        q_tok0 = lo;
+        int klo, khi;
+        bounds(a.cu_kv, a.S_kv, b, klo, khi);
+        S_kv = khi - klo;
+        kv_tok0 = klo;
+    }
+    // the query tiles with the most keys start first (a variable-length batch keeps its tile order)
+    if (a.causal && a.cu_q == nullptr) qt = a.q_tiles - 1 - qt;
+    const __bf16* const Qs = a.Q + q_tok0 * a.H_q * kHeadDim;
+    const __bf16* const Ks = a.K + kv_tok0 * a.H_kv * kHeadDim;
+    const __bf16* const Vs = a.V + kv_tok0 * a.H_kv * kHeadDim;
+    __bf16* const Os = a.O + q_tok0 * a.H_q * kHeadDim;
     const int kh = head / (a.H_q / a.H_kv);
     const int q0 = qt * TQ + wave * T::R;
-    const int shift = a.S_kv - a.S_q;
+    const int shift = S_kv - S_q;
 
     // keys this block can see at all: the causal bound of its last query row
-    int kv_end = a.S_kv;
+    int kv_end = S_kv;
     if (a.causal) {
         const int last = qt * TQ + TQ + shift;  // exclusive
         kv_end = last < kv_end ? last : kv_end;
@@ -130,7 +188,7 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
             au32x4 v = {0u, 0u, 0u, 0u};
-            if (q < a.S_q) v = *reinterpret_cast<const au32x4*>(src + 16 * s);
+            if (q < S_q) v = *reinterpret_cast<const au32x4*>(src + 16 * s);
             qf[rb][s] = __builtin_bit_cast(abf16x8, v);
         }
     }
@@ -150,7 +208,7 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
     auto load_k = [&](int t) {
         const int kv0 = t * TKV;
         const __bf16* base = Ks + t * tile_stride;
-        if (kv0 + TKV <= a.S_kv) {
+        if (kv0 + TKV <= S_kv) {
 #pragma unroll
             for (int i = 0; i < T::KC; ++i)
                 if (tid + i * T::NT < T::K_TOTAL) kreg[i] = *reinterpret_cast<const au32x4*>(base + k_off[i]);
@@ -160,14 +218,14 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
         for (int i = 0; i < T::KC; ++i) {
             const int c = tid + i * T::NT;
             au32x4 v = {0u, 0u, 0u, 0u};
-            if (c < T::K_TOTAL && kv0 + (c >> 4) < a.S_kv) v = *reinterpret_cast<const au32x4*>(base + k_off[i]);
+            if (c < T::K_TOTAL && kv0 + (c >> 4) < S_kv) v = *reinterpret_cast<const au32x4*>(base + k_off[i]);
             kreg[i] = v;
         }
     };
     auto load_v = [&](int t) {
         const int kv0 = t * TKV;
         const __bf16* base = Vs + t * tile_stride;
-        if (kv0 + TKV <= a.S_kv) {
+        if (kv0 + TKV <= S_kv) {
 #pragma unroll
             for (int i = 0; i < T::KC; ++i)
                 if (tid + i * T::NT < T::K_TOTAL) vreg[i] = *reinterpret_cast<const au32x4*>(base + k_off[i]);
@@ -177,7 +235,7 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
         for (int i = 0; i < T::KC; ++i) {
             const int c = tid + i * T::NT;
             au32x4 v = {0u, 0u, 0u, 0u};
-            if (c < T::K_TOTAL && kv0 + (c >> 4) < a.S_kv) v = *reinterpret_cast<const au32x4*>(base + k_off[i]);
+            if (c < T::K_TOTAL && kv0 + (c >> 4) < S_kv) v = *reinterpret_cast<const au32x4*>(base + k_off[i]);
             vreg[i] = v;
         }
     };
@@ -239,10 +297,10 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
         for (int rb = 0; rb < T::RB; ++rb) {
             const int q = q0 + rb * 32 + l32;
             // wave-uniform: can any element of this tile be masked for these 32 queries?
-            const bool ragged = kv0 + TKV > a.S_kv;
+            const bool ragged = kv0 + TKV > S_kv;
             const bool diag = a.causal && (kv0 + TKV - 1 > q0 + rb * 32 + shift);
             if (ragged || diag) {
-                int limit = a.S_kv - 1;  // last visible key of this lane's query
+                int limit = S_kv - 1;  // last visible key of this lane's query
                 if (a.causal && q + shift < limit) limit = q + shift;
 #pragma unroll
                 for (int b = 0; b < T::KB; ++b)
@@ -333,7 +391,7 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
         const int q = q0 + rb * 32 + l32;
         const float lsum = l_run[rb] + __shfl_xor(l_run[rb], 32);
         const float inv = lsum > 0.0f ? 1.0f / lsum : 0.0f;
-        if (q >= a.S_q) continue;
+        if (q >= S_q) continue;
         __bf16* dst = Os + (static_cast<int64_t>(q) * a.H_q + head) * kHeadDim + 4 * h;
 #pragma unroll
         for (int db = 0; db < 4; ++db)

@@ -98,16 +98,22 @@ struct Problem {
     float scale = 0.0f;
     int causal = 0;
     int64_t batch = 1;   // sequences per attention launch
+    const int32_t* cu_q = nullptr;    // variable-length batch: device, batch + 1 token offsets into Q / O (M = total)
+    const int32_t* cu_kv = nullptr;   //                        ... into K / V (K = total)
 };
 
 constexpr int64_t kMaxSeq = 1 << 22;  // S_q, S_kv: row offsets times heads times 128 stay far below 2^63, block ids below 2^31
 
 int launch_attn(wt_ctx* ctx, const Config& c, const Problem& p, hipStream_t stream) {
     if (p.M == 0 || p.N == 0) return WT_OK;
-    const int64_t q_tiles = ceil_div64(p.M, c.cfg.bm), G = q_tiles * p.N * p.batch;
+    // variable-length batch: every sequence may end in a partial query tile, so the grid is sized for
+    // ceil(total / T_Q) + batch tiles per head and the blocks past the last real tile exit at once
+    const int64_t q_tiles = ceil_div64(p.M, c.cfg.bm) + (p.cu_q ? p.batch : 0);
+    const int64_t G = q_tiles * p.N * (p.cu_q ? 1 : p.batch);
     if (G > 0x7FFFFFFF || p.batch * p.N > 0x7FFFFFFF) return WT_ERR_INVALID_ARG;
     AttnArgs a;
     a.batch = (int)p.batch;
+    a.cu_q = p.cu_q; a.cu_kv = p.cu_kv;
     a.Q = static_cast<const __bf16*>(p.A); a.K = static_cast<const __bf16*>(p.B);
     a.V = static_cast<const __bf16*>(p.V); a.O = static_cast<__bf16*>(p.C);
     a.S_q = (int)p.M; a.S_kv = (int)p.K; a.H_q = (int)p.N; a.H_kv = (int)p.H_kv;
@@ -541,6 +547,23 @@ int wt_attn_batched(wt_ctx* ctx, int64_t batch, int64_t n_heads, int64_t n_kv_he
     if (batch == 0) return WT_OK;
     Problem p{S_q, n_heads, S_kv, Q, K, O, nullptr, nullptr};
     p.V = V; p.H_kv = n_kv_heads; p.scale = scale; p.causal = causal; p.batch = batch;
+    return launch(ctx, ctx->cfgs[id], p, (hipStream_t)hip_stream);
+}
+
+int wt_attn_varlen(wt_ctx* ctx, int64_t batch, int64_t n_heads, int64_t n_kv_heads, int64_t total_q, int64_t total_kv,
+                   const int32_t* cu_q, const int32_t* cu_kv, const void* Q, const void* K, const void* V, void* O,
+                   float scale, int causal, wt_cfg cfg, void* hip_stream) {
+    int id = -1;
+    if (batch < 0 || batch > kMaxGroups || total_q > 0x7FFFFFFF || total_kv > 0x7FFFFFFF) return WT_ERR_INVALID_ARG;
+    // (a causal sequence with fewer keys than queries is not an error here: the host does not see the lengths;
+    //  its queries that see no key come out as zeros)
+    const int rc = check_attn_args(ctx, n_heads, n_kv_heads, total_q, causal ? std::max(total_q, total_kv) : total_kv,
+                                   Q, K, V, O, scale, causal, cfg, &id);
+    if (rc != WT_OK) return rc;
+    if (batch == 0 || total_q == 0) return WT_OK;
+    if (!cu_q || !cu_kv) return WT_ERR_INVALID_ARG;
+    Problem p{total_q, n_heads, total_kv, Q, K, O, nullptr, nullptr};
+    p.V = V; p.H_kv = n_kv_heads; p.scale = scale; p.causal = causal; p.batch = batch; p.cu_q = cu_q; p.cu_kv = cu_kv;
     return launch(ctx, ctx->cfgs[id], p, (hipStream_t)hip_stream);
 }
 

@@ -134,6 +134,55 @@ def test_batched_launch_equals_one_launch_per_sequence(ctx):
         wt.wt_attn_batched(ctx, -1, H_q, H_kv, S_q, S_kv, dQ, dK, dV, dO, SCALE, 0, cfg, stream=torch.cuda.current_stream())
 
 
+def test_variable_length_batch_equals_one_launch_per_sequence(ctx):
+    """wt_attn_varlen: sequences of different lengths packed back to back, offsets resident on the device -- an empty
+    sequence, one shorter than a tile, several tiles with ragged tails, decode-like (1 query, long context) and a
+    causal sequence with fewer keys than queries.  Every sequence against the oracle and bit for bit against wt_attn on
+    that sequence alone, for every structural key (one block order each)."""
+    H_q, H_kv = 4, 2
+    lens = [(0, 0), (5, 9), (300, 300), (1, 700), (130, 257), (64, 40), (517, 517)]
+    batch = len(lens)
+    seqs = [wt_synth.attn_operands(max(sq, 1), max(sk, 1), H_q, H_kv, 1300 + b) for b, (sq, sk) in enumerate(lens)]
+    qb = np.concatenate([s[0][:sq] for s, (sq, sk) in zip(seqs, lens)])
+    kb = np.concatenate([s[1][:sk] for s, (sq, sk) in zip(seqs, lens)])
+    vb = np.concatenate([s[2][:sk] for s, (sq, sk) in zip(seqs, lens)])
+    cu_q = np.concatenate([[0], np.cumsum([l[0] for l in lens])]).astype(np.int32)
+    cu_kv = np.concatenate([[0], np.cumsum([l[1] for l in lens])]).astype(np.int32)
+    tq, tkv = int(cu_q[-1]), int(cu_kv[-1])
+    dQ, dK, dV = (dev_bits(x.reshape(-1, 128)).view(torch.bfloat16) for x in (qb, kb, vb))
+    dcq, dck = torch.from_numpy(cu_q).cuda(), torch.from_numpy(cu_kv).cuda()
+    for cfg, _ in all_configs(ctx):
+        if cfg.swizzle != (cfg.id // 3) % 3:
+            continue
+        for causal in (0, 1):
+            note(f"attn varlen cfg={cfg.astuple()} causal={causal}")
+            dO = torch.full((tq * H_q, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
+            wt.wt_attn_varlen(ctx, batch, H_q, H_kv, tq, tkv, dcq, dck, dQ, dK, dV, dO, SCALE, causal, cfg,
+                              stream=torch.cuda.current_stream())
+            torch.cuda.synchronize()
+            got = dO.float().cpu().numpy().reshape(tq, H_q, 128)
+            assert np.isfinite(got).all()
+            for b, (sq, sk) in enumerate(lens):
+                if sq == 0:
+                    continue
+                mine = got[cu_q[b]:cu_q[b + 1]]
+                q1, k1, v1 = qb[cu_q[b]:cu_q[b + 1]], kb[cu_kv[b]:cu_kv[b + 1]], vb[cu_kv[b]:cu_kv[b + 1]]
+                if causal and sk < sq:
+                    # queries i with i + (sk - sq) < 0 see no key: zeros; the rest see keys 0 .. i + sk - sq
+                    assert not mine[: sq - sk].any()
+                    check(mine[sq - sk:], reference(q1[sq - sk:], k1, v1, True), f"varlen {cfg} seq {b} causal short")
+                    continue
+                check(mine, reference(q1, k1, v1, bool(causal)), f"varlen {cfg} seq {b} causal {causal}")
+                assert np.array_equal(mine, run_attn(ctx, cfg, q1, k1, v1, causal)), (cfg, b, causal)
+    # offsets that point outside the tensors are clipped, never followed: the launch completes and writes nothing wild
+    cfg, _ = wt.wt_config_get(ctx, wt.wt_config_find(ctx, 128, 1, 64, 4, 1, 0))
+    bad = torch.tensor([0, -5, 10 ** 9, 7, tq + 99, tq, tq, tq], dtype=torch.int32, device="cuda")
+    guard = torch.full(((tq + 8) * H_q, 128), 7.0, dtype=torch.bfloat16, device="cuda")
+    wt.wt_attn_varlen(ctx, batch, H_q, H_kv, tq, tkv, bad, bad, dQ, dK, dV, guard, SCALE, 0, cfg, stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    assert (guard[tq * H_q:] == 7.0).all() and torch.isfinite(guard.float()).all()
+
+
 def test_sharp_softmax_and_scale(ctx):
     """Queries with gain 6 make the softmax nearly one-hot (large score range): exercises the running maximum
     and the rescaling; also a non-default scale."""
