@@ -480,6 +480,62 @@ def cmd_attn(a, torch):
             "summary": summary, "rows": rows}
 
 
+def cmd_attn_varlen(a, torch):
+    """Variable-length prefill batches (the shape of the paper's end-to-end setting, Sec. 5.3: batches of 4 prompts of
+    512..16384 tokens; 32 query / 4 KV heads of dimension 128): wt_attn_varlen under the configuration
+    wt_select(ceil(total/batch), batch * heads, ceil(total/batch)) -- the selector sees only the totals -- against
+    exhaustive search over the attention registry with the real lengths, causal."""
+    ctx = wt.wt_create(0, wt.WT_ATTN_BF16, wt.WT_OUT_BF16)
+    path = a.table or tune.table_path(wt.WT_ATTN_BF16, wt.WT_OUT_BF16)
+    wt.wt_load(ctx, path)
+    cfgs = [wt.wt_config_get(ctx, i) for i in range(wt.wt_config_count(ctx))]
+    stream = torch.cuda.current_stream()
+    H_q, H_kv, scale = 32, 4, 1.0 / math.sqrt(128.0)
+    rng = np.random.default_rng(a.sample_seed)
+    rows = []
+    for case in range(a.sample):
+        batch = int(rng.choice([2, 4, 8]))
+        lens = [int(round(math.exp(rng.uniform(math.log(512), math.log(16384))))) for _ in range(batch)]
+        total = sum(lens)
+        cu = torch.tensor(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32), device="cuda")
+        g = torch.Generator(device="cuda")
+        g.manual_seed(5000 + case)
+        Q = torch.randn((total * H_q, 128), device="cuda", generator=g).to(torch.bfloat16)
+        K = torch.randn((total * H_kv, 128), device="cuda", generator=g).to(torch.bfloat16)
+        V = torch.randn((total * H_kv, 128), device="cuda", generator=g).to(torch.bfloat16)
+        O = torch.empty_like(Q)
+
+        def timed(c, iters=4):
+            for _ in range(2):
+                wt.wt_attn_varlen(ctx, batch, H_q, H_kv, total, total, cu, cu, Q, K, V, O, scale, 1, c, stream)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(iters):
+                wt.wt_attn_varlen(ctx, batch, H_q, H_kv, total, total, cu, cu, Q, K, V, O, scale, 1, c, stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / iters
+        times = {i: timed(c) for i, (c, r) in enumerate(cfgs)}
+        mean_len = -(-total // batch)
+        pick = wt.wt_select(ctx, mean_len, batch * H_q, mean_len)
+        best = min(times, key=times.get)
+        flop = sum(4.0 * s * s * 128 * H_q * 0.5 for s in lens)
+        rows.append({"batch": batch, "lens": lens, "pick": list(pick.astuple()), "pick_us": times[pick.id],
+                     "best": list(cfgs[best][0].astuple()), "best_us": times[best], "frac": times[best] / times[pick.id],
+                     "pick_tflops": flop / times[pick.id] / 1e6, "times": {str(i): round(t, 2) for i, t in times.items()}})
+        _log(f"[varlen] case {case}: batch {batch}, {total} tokens, frac {rows[-1]['frac']:.3f}, {rows[-1]['pick_tflops']:.0f} TF")
+    fr = np.array([r["frac"] for r in rows])
+    gm = lambda x: float(np.exp(np.mean(np.log(np.asarray(x, dtype=np.float64)))))
+    fixed = min(range(len(cfgs)), key=lambda i: gm([r["times"][str(i)] for r in rows]))
+    summary = {"n_cases": len(rows), "geomean_frac": gm(fr), "min_frac": float(fr.min()), "frac_ge_95": float(np.mean(fr >= 0.95)),
+               "fixed_default": list(cfgs[fixed][0].astuple()),
+               "fixed_default_geomean_frac": gm([r["best_us"] / r["times"][str(fixed)] for r in rows]),
+               "pick_tflops_geomean": gm([r["pick_tflops"] for r in rows])}
+    wt.wt_destroy(ctx)
+    return {"workload": "variable-length causal prefill batches (2/4/8 prompts of 512..16384 tokens, 32/4 heads)",
+            "table": path, "summary": summary, "rows": rows}
+
+
 def cmd_ablate(a, torch=None):
     """CPU only.  Re-fit the saved profiling records under model / (W, I) variants with wt_fit on a
     host-only context and score each variant's picks against saved exhaustive timings (the `times` of
@@ -555,7 +611,7 @@ def cmd_ablate(a, torch=None):
 
 def main(argv=None):
     ap = argparse.ArgumentParser()
-    ap.add_argument("cmd", choices=["sweep", "wave", "stream", "shapes", "large", "grouped", "persistent", "vendor", "ablate", "attn"])
+    ap.add_argument("cmd", choices=["sweep", "wave", "stream", "shapes", "large", "grouped", "persistent", "vendor", "ablate", "attn", "attn_varlen"])
     ap.add_argument("--set", choices=["paper", "shortk"], default="paper", help="shapes: which synthetic shape set")
     ap.add_argument("--causal", action="store_true", help="attn: causal masking (queries aligned to the end of the keys)")
     ap.add_argument("--samples", default=None, help="ablate: .npz with `samples` and `occ`")
@@ -585,13 +641,13 @@ def main(argv=None):
     else:
         import torch
 
-        res = {"sweep": cmd_sweep, "wave": cmd_wave, "stream": cmd_stream, "shapes": cmd_shapes, "large": cmd_large, "grouped": cmd_grouped, "persistent": cmd_persistent, "vendor": cmd_vendor, "attn": cmd_attn}[a.cmd](a, torch)
+        res = {"sweep": cmd_sweep, "wave": cmd_wave, "stream": cmd_stream, "shapes": cmd_shapes, "large": cmd_large, "grouped": cmd_grouped, "persistent": cmd_persistent, "vendor": cmd_vendor, "attn": cmd_attn, "attn_varlen": cmd_attn_varlen}[a.cmd](a, torch)
     txt = json.dumps(res)
     if a.out:
         os.makedirs(os.path.dirname(os.path.abspath(a.out)), exist_ok=True)
         open(a.out, "w").write(txt)
     summ = res.get("summary") or {k: v for k, v in res.items() if k != "rows"}
-    print(json.dumps(summ if a.cmd in ("sweep", "stream", "shapes", "attn") else {"workload": res["workload"]}))
+    print(json.dumps(summ if a.cmd in ("sweep", "stream", "shapes", "attn", "attn_varlen") else {"workload": res["workload"]}))
 
 
 if __name__ == "__main__":
