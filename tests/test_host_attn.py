@@ -46,6 +46,20 @@ def test_attention_context_rules():
             wt.wt_set_persistent(c, True)
         with pytest.raises(wt.WtError):                          # n_heads missing
             wt.wt_sample_plan(c, wt.make_grid(W=2, I=3, k_anchors=MULT))
+        # launches on a context without a device are refused with a status, batched and variable-length ones too
+        cfg, _ = wt.wt_config_get(c, 0)
+        for call in (lambda: wt.wt_attn(c, 4, 2, 64, 64, None, None, None, None, 0.1, 0, cfg),
+                     lambda: wt.wt_attn_batched(c, 3, 4, 2, 64, 64, None, None, None, None, 0.1, 0, cfg),
+                     lambda: wt.wt_attn_varlen(c, 3, 4, 2, 64, 64, None, None, None, None, None, None, 0.1, 0, cfg)):
+            with pytest.raises(wt.WtError) as e:
+                call()
+            assert e.value.status == wt.WT_ERR_NO_DEVICE
+        for call in (lambda: wt.wt_attn_batched(c, -1, 4, 2, 64, 64, None, None, None, None, 0.1, 0, cfg),
+                     lambda: wt.wt_attn_batched(c, 1 << 20, 4, 2, 64, 64, None, None, None, None, 0.1, 0, cfg),
+                     lambda: wt.wt_attn_varlen(c, 1025, 4, 2, 64, 64, None, None, None, None, None, None, 0.1, 0, cfg)):
+            with pytest.raises(wt.WtError) as e:
+                call()
+            assert e.value.status == wt.WT_ERR_INVALID_ARG
     finally:
         wt.wt_destroy(c)
 
