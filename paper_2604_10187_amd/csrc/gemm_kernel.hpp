@@ -22,6 +22,9 @@
 //     scheduler is fenced after each such group.  vmcnt is managed by hand (the direct-to-LDS
 //     loads are issued from inline asm so that the compiler does not serialise them against
 //     every LDS read).
+//     The fp8 256x256x128 kernel on four wavefronts (16x16x128 MFMAs, 256 accumulators per lane) keeps ONE set of A
+//     fragments that is replaced row by row and double-buffers only the B fragments (GemmTraits::ROLL): two full
+//     sets of 8-register fragments do not fit beside the accumulators.
 //   * block rasterisation (the micro parameter).  Workgroups are dealt round-robin to the 8 XCDs,
 //     each with its own L2.  0 = row-major (so XCD x walks the tile columns x, x+8, ...);
 //     1 and 2 give each XCD a contiguous range of a grouped tile sequence (groups of 4 resp. 8
