@@ -8,7 +8,11 @@ the method (sparse profiling + fit); it is loaded from paper_2604_10187_amd/tabl
 file is absent or does not match the kernel registry, rebuilt here (outside the timed region) with
 a reduced wave range.
 
-Prints ONE JSON line.  value = total sweep FLOPs / time (whole job, one GPU).
+Prints ONE JSON line.  value = total sweep FLOPs / time (whole job, one GPU).  Outside the timed step the line also
+carries: `roofline` / `roofline_fp8` (16384 x 8192 x 8192 under wt_select's pick, HIP events on the launch stream, beside
+an MFMA-only ceiling measured in the same run), `roofline_sweep_dominant`, `roofline_hbm` (a few-row shape timed over
+rotating copies of its weight, so that it streams from HBM), pick against exhaustive search on the sweep and on a seeded
+sample of the 10,000-shape stream, wt_select's latency, the 256^3 case, the attention kernel, and the CPU oracle.
 """
 from __future__ import annotations
 

@@ -5,6 +5,10 @@
     python -m paper_2604_10187_amd.evaluate stream  [--table T] [--out F] [--sample 300]  # 10,000-shape stream
     python -m paper_2604_10187_amd.evaluate large   [--out F]               # 16384x8192x8192 bf16 and fp8
     python -m paper_2604_10187_amd.evaluate attn    [--table T] [--out F] [--sample 48] [--causal]  # attention test set
+    python -m paper_2604_10187_amd.evaluate shapes  --set paper|shortk      # shapes in the paper's test ranges / K = 256..2048
+    python -m paper_2604_10187_amd.evaluate attn_varlen [--sample 20]       # ragged causal prefill batches (wt_attn_varlen)
+    python -m paper_2604_10187_amd.evaluate grouped|persistent|vendor|ablate ...   # see each command's docstring
+    (sweep --rotate-mb 1200: every launch on another copy of the weight, so that weights stream from HBM)
 
 "pick" = the configuration wt_select returns; "best" = exhaustive search over the frozen registry
 with the same timing protocol (3 warm-up + 5 measured launches, mean; Sec. 4.2).  The pick's time is
