@@ -63,6 +63,23 @@ def phi_attn(n_heads: int, S_q: int, S_kv: int, T_Q: int, T_KV: int) -> tuple[in
     return n_heads * ceil_div(S_q, T_Q), ceil_div(S_kv, T_KV)
 
 
+def phi_attn_varlen(n_heads: int, lens_q, lens_kv, T_Q: int, T_KV: int) -> tuple[int, int]:
+    """Table 2's FlashAttention row read for a batch of sequences of different lengths (the paper states it for one
+    length; Sec. 5.3 runs ragged prefill batches): sequence i contributes ceil(q_i / T_Q) query tiles per head, each
+    looping over ceil(kv_i / T_KV) key tiles.  G counts every block; L is the mean loop count over the blocks, rounded
+    half up, so that G * L is the launch's number of key-tile iterations to within rounding, as it is exactly for
+    equal lengths.  No block at all gives (0, 0)."""
+    if n_heads < 1 or len(lens_q) != len(lens_kv):
+        raise ValueError("n_heads >= 1, one kv length per query length")
+    tiles = [ceil_div(q, T_Q) for q in lens_q]
+    loops = [ceil_div(kv, T_KV) for kv in lens_kv]
+    t = sum(tiles)
+    if t == 0:
+        return 0, 0
+    iters = sum(a * b for a, b in zip(tiles, loops))
+    return n_heads * t, (2 * iters + t) // (2 * t)
+
+
 def representative_heads(a: int, b: int, n_heads: int) -> int:
     """Sec. 4.2: the sub-interval [a, b] is projected to the head-aligned value floor(b / N_h) * N_h, which
     counts only if it is still >= a; 0 means the sub-interval holds no multiple of N_h."""

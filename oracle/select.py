@@ -126,6 +126,58 @@ def select_grouped(table: DualTable, E: int, M_total: int, N: int, K: int):
     return k, micro, t
 
 
+def select_attn_varlen(table: DualTable, n_heads: int, lens_q, lens_kv):
+    """Runtime selection for a ragged attention batch whose per-sequence lengths the host knows: the two stages of
+    select_attn() with every key priced at phi_attn_varlen of the real lengths.  Returns (key, micro, T-hat) or None."""
+    from .attention import phi_attn_varlen
+
+    best = None
+    for k, kd in enumerate(table.keys):
+        G, L = phi_attn_varlen(n_heads, lens_q, lens_kv, kd.bm, kd.bk)
+        b = bucket_for(table, k, wave_count(G, kd.cap), 0)
+        if b is None:
+            continue
+        t = predict(b.theta, G, L)
+        if math.isnan(t):
+            continue
+        if best is None or t < best[0]:
+            best = (t, k, b, L)
+    if best is None:
+        return None
+    t, k, b, L = best
+    _, micro = nearest_anchor(b.anchors, L) if b.anchors else (0, 0)
+    return k, micro, t
+
+
+def select_grouped_rows(table: DualTable, rows, N: int, K: int):
+    """Grouped GEMM whose per-group row counts the host knows (a router that has synchronised, or a fixed split):
+    select_grouped() with G from Table 2's grouped row on the real counts instead of the uniform approximation.  The
+    few-row family is that of the mean group, ceil(sum / E) rows, which is the uniform reading when the groups are
+    equal.  Returns (key, micro, T-hat) or None."""
+    rows = list(rows)
+    if not rows:
+        raise ValueError("at least one group")
+    mean_rows = ceil_div(sum(rows), len(rows))
+    best = None
+    for k, kd in enumerate(table.keys):
+        if kd.split != 1:
+            continue
+        G, L = phi_grouped(rows, N, K, kd.bm, kd.bn, kd.bk)
+        b = bucket_for(table, k, wave_count(G, kd.cap), row_family(ceil_div(mean_rows, kd.bm)))
+        if b is None:
+            continue
+        t = predict(b.theta, G, L)
+        if math.isnan(t):
+            continue
+        if best is None or t < best[0]:
+            best = (t, k, b, L)
+    if best is None:
+        return None
+    t, k, b, L = best
+    _, micro = nearest_anchor(b.anchors, L) if b.anchors else (0, 0)
+    return k, micro, t
+
+
 # ---- reader for the product's table file ------------------------------------------------------
 MAGIC = b"WTDT"
 

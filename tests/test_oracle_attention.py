@@ -100,6 +100,37 @@ def test_phi_attn_hand_values():
     assert att.phi_attn(8, 0, 64, 64, 64) == (0, 1)
 
 
+def test_phi_attn_varlen_hand_values_block_enumeration_and_equal_lengths():
+    """Two sequences of 100 and 300 tokens (queries = keys), T_Q = 128, T_KV = 64, 2 heads: 1 and 3 query tiles per
+    head, looping 2 and 5 times -> 4 tiles, 2 + 15 = 17 iterations per head, mean 4.25 -> L = 4, G = 8.  A mean of
+    exactly 2.5 (one tile looping twice, one three times) rounds up to 3."""
+    from fractions import Fraction
+
+    assert att.phi_attn_varlen(2, [100, 300], [100, 300], 128, 64) == (8, 4)
+    assert att.phi_attn_varlen(1, [10, 10], [100, 150], 64, 64) == (2, 3)
+    assert att.phi_attn_varlen(4, [0, 0], [64, 64], 64, 64) == (0, 0)
+    assert att.phi_attn_varlen(4, [], [], 64, 64) == (0, 0)
+    assert att.phi_attn_varlen(3, [5, 0, 70], [0, 900, 70], 64, 32) == (9, 2)      # tiles 1, 0, 2; loops 0, 29, 3
+    with pytest.raises(ValueError):
+        att.phi_attn_varlen(2, [1, 2], [1], 64, 64)
+    # every block listed one by one: G is their number, L the mean of their loop counts rounded half up
+    rng = np.random.default_rng(12)
+    for _ in range(200):
+        b, H = int(rng.integers(1, 9)), int(rng.integers(1, 9))
+        T_Q, T_KV = int(rng.choice([64, 128, 256])), int(rng.choice([32, 64, 128]))
+        lq = [int(x) for x in rng.integers(0, 3000, size=b)]
+        lkv = [int(x) for x in rng.integers(0, 5000, size=b)]
+        blocks = [-(-kv // T_KV) for q, kv in zip(lq, lkv) for _h in range(H) for _t in range(-(-q // T_Q))]
+        G, L = att.phi_attn_varlen(H, lq, lkv, T_Q, T_KV)
+        assert G == len(blocks)
+        if blocks:
+            assert L == math.floor(Fraction(sum(blocks), len(blocks)) + Fraction(1, 2))
+            assert abs(G * L - sum(blocks)) * 2 <= G
+    # equal lengths: Table 2's row with the batch folded into the head count
+    for (b, H, S_q, S_kv, T_Q, T_KV) in [(1, 8, 300, 1000, 64, 32), (4, 32, 1024, 2048, 256, 128), (7, 5, 1, 1, 128, 64)]:
+        assert att.phi_attn_varlen(H, [S_q] * b, [S_kv] * b, T_Q, T_KV) == att.phi_attn(b * H, S_q, S_kv, T_Q, T_KV)
+
+
 @pytest.mark.parametrize("n_heads", [1, 7, 16, 40, 128])
 def test_representative_heads_is_the_largest_multiple_in_the_interval(n_heads):
     rng = np.random.default_rng(n_heads)

@@ -425,6 +425,34 @@ def test_select_attn_hand_worked_two_keys():
     assert (k, micro) == (1, 2) and t == pytest.approx(81.92)
 
 
+def test_select_attn_varlen_hand_worked_and_equal_lengths():
+    """Two prompts of 100 and 900 tokens (queries = keys), 8 heads, keys <64, 32> and <256, 64>, planes T = a*G*L + d.
+    Real lengths:  key 0: tiles 2 + 15 = 17, iterations 2*4 + 15*29 = 443, L = round(26.06) = 26, G = 136,
+                          T = 0.01*136*26 + 1 = 36.36
+                   key 1: tiles 1 + 4 = 5, iterations 1*2 + 4*15 = 62, L = round(12.4) = 12, G = 40,
+                          T = 0.06*40*12 + 7 = 35.8   <- wins; its anchors L = 8 and 16 are equally far: the smaller.
+    Mean length 500 (what a selector that sees only totals prices): key 0: G = 16*8 = 128, L = 16 -> 21.48 <- wins,
+    anchors 10 and 40: 10; key 1: G = 16*2 = 32, L = 8 -> 22.36.  So the case tells the two readings apart."""
+    keys = [ofit.KeyDesc(64, 1, 32, 2, 1, 1, 256), ofit.KeyDesc(256, 1, 64, 8, 1, 1, 256)]
+    b0 = ofit.Bucket(theta=(0.01, 0.0, 0.0, 1.0), status=15, anchors=[(10, 2), (40, 0)])
+    b1 = ofit.Bucket(theta=(0.06, 0.0, 0.0, 7.0), status=15, anchors=[(8, 1), (16, 2)])
+    e0 = ofit.Bucket(theta=(0.02, 0.0, 0.0, 0.0), status=15, anchors=[(10, 1)])
+    e1 = ofit.Bucket(theta=(0.01, 0.0, 0.0, 0.0), status=15, anchors=[(16, 2)])
+    table = ofit.DualTable(W=1, keys=keys, local=[[b0], [b1]], ext=[e0, e1])
+    k, micro, t = osel.select_attn_varlen(table, 8, [100, 900], [100, 900])
+    assert (k, micro) == (1, 1) and t == pytest.approx(35.8)
+    k, micro, t = osel.select_attn(table, 2 * 8, 500, 500)
+    assert (k, micro) == (0, 2) and t == pytest.approx(21.48)
+    # no block at all: G = L = 0 lies outside every wave bucket, the extrapolation constants decide (a tie at 0: key 0)
+    assert osel.select_attn_varlen(table, 8, [0, 0], [5, 5])[0] == 0
+    # equal lengths: the fixed-length selector with the batch folded into the heads
+    rng = np.random.default_rng(3)
+    for _ in range(200):
+        b, H = int(rng.integers(1, 9)), int(rng.integers(1, 33))
+        S_q, S_kv = int(rng.integers(1, 3000)), int(rng.integers(1, 6000))
+        assert osel.select_attn_varlen(table, H, [S_q] * b, [S_kv] * b) == osel.select_attn(table, b * H, S_q, S_kv)
+
+
 def test_r_squared_exact_surface_hand_value_and_constant_rows():
     """Coefficient of determination R^2 = 1 - SS_res/SS_tot (the statistic Sec. 3.3 / Fig. 5 quotes for the G- and
     L-linearity of a wave).  (i) rows lying on the plane -> exactly 1; (ii) a hand case: T = (1, 2, 6) at

@@ -145,3 +145,59 @@ def test_select_grouped_with_one_group_is_the_dense_selector_on_unsplit_keys():
         assert got == osel.select(table, M, N, K)
         seen.add(got[0])
     assert len(seen) >= 2       # the case is not degenerate: more than one key gets picked
+
+
+def test_select_grouped_rows_hand_worked_real_counts_flip_the_choice():
+    """The table of the hand-worked case above (split key left out), N = 128, K = 256 (L = 4), 100 rows in 3 groups.
+      rows (100, 0, 0): key 0 <128, 64, 64>: (1 + 0 + 0) row tiles x 2 -> G = 2, T = 1.0*2 + 0.5*4 + 2 = 6   <- wins
+                        key 1 <32, 64, 64>:  (4 + 0 + 0) x 2 -> G = 8, T = 0.5*8 + 0.5*4 + 1 = 7
+      (an empty group adds no tile; the uniform reading of the same launch, 34 rows each, picks key 1 at 9 against 10)
+      rows (33, 33, 34): key 0: 3 x 2 -> G = 6, T = 10; key 1: (2 + 2 + 2) x 2 -> G = 12, T = 9 <- wins, as uniform.
+      rows (90, 5, 5):   key 0: 3 x 2 -> 10;  key 1: (3 + 1 + 1) x 2 = 10 -> T = 5 + 2 + 1 = 8 <- wins."""
+    keys = [ofit.KeyDesc(128, 64, 64, 4, 2, 1, 256), ofit.KeyDesc(32, 64, 64, 4, 2, 1, 256),
+            ofit.KeyDesc(128, 64, 64, 4, 2, 1, 256, 2)]
+    local = [[_bucket((0.0, 1.0, 0.5, 2.0), [(4, 0)])], [_bucket((0.0, 0.5, 0.5, 1.0), [(2, 1), (8, 2)])],
+             [_bucket((0.0, 0.0, 0.0, 0.1), [(2, 0)])]]          # the split key's plane would win if it were priced
+    ext = [_bucket((0.0, 0.0, 0.0, 1e6), [(4, 0)]) for _ in keys]
+    table = ofit.DualTable(W=1, keys=keys, local=local, ext=ext)
+    assert osel.select_grouped_rows(table, [100, 0, 0], 128, 256) == (0, 0, 6.0)
+    assert osel.select_grouped(table, 3, 100, 128, 256) == (1, 1, 9.0)
+    assert osel.select_grouped_rows(table, [33, 33, 34], 128, 256) == (1, 1, 9.0)
+    assert osel.select_grouped_rows(table, [90, 5, 5], 128, 256) == (1, 1, 8.0)
+    # one group: the dense problem on the unsplit keys
+    assert osel.select_grouped_rows(table, [100], 128, 256) == (0, 0, 6.0)
+    with pytest.raises(ValueError):
+        osel.select_grouped_rows(table, [], 128, 256)
+
+
+def test_select_grouped_rows_family_of_the_mean_group_and_uniform_equivalence():
+    """Few-row families: the family consulted is that of the mean group, ceil(sum / E) rows.  rows (100, 0, 0) -> 34:
+    key 1 (bm = 32) has 2 tile rows -> family 2 (T = 5), key 0 family 1 (T = 20): key 1 at 5, whatever the split of
+    the 100 rows.  And on equal groups the function is select_grouped: same G, same family, same stages."""
+    keys = [ofit.KeyDesc(128, 64, 64, 4, 2, 1, 256), ofit.KeyDesc(32, 64, 64, 4, 2, 1, 256)]
+    near = [[_bucket((0.0, 0.0, 0.0, 100.0), [(4, 0)])] for _ in keys]
+    ext = [_bucket((0.0, 0.0, 0.0, 1e6), [(4, 0)]) for _ in keys]
+    const = lambda t, micro: _bucket((0.0, 0.0, 0.0, t), [(4, micro)])
+    none = lambda: ofit.Bucket()
+    row_local = [[[const(20.0, 1)], [none()]], [[none()], [const(5.0, 2)]], [[none()], [const(50.0, 0)]]]
+    row_ext = [[none(), none()] for _ in range(3)]
+    table = ofit.DualTable(W=1, keys=keys, local=near, ext=ext, W_row=1, row_local=row_local, row_ext=row_ext)
+    assert osel.select_grouped_rows(table, [100, 0, 0], 128, 256) == (1, 2, 5.0)
+    assert osel.select_grouped_rows(table, [40, 30, 30], 128, 256) == (1, 2, 5.0)
+
+    keys = [ofit.KeyDesc(256, 256, 64, 4, 2, 1, 256), ofit.KeyDesc(128, 128, 64, 4, 2, 2, 256),
+            ofit.KeyDesc(64, 64, 64, 4, 2, 5, 256), ofit.KeyDesc(16, 64, 128, 1, 2, 8, 256)]
+    W = 4
+    local = [[_bucket(tuple(wt_synth.random_theta(300 + 11 * k, W)[w]), [(8, (k + w) % 3), (40, (k + w + 1) % 3)])
+              for w in range(W)] for k in range(len(keys))]
+    ext = [_bucket(tuple(wt_synth.random_theta(500 + k, 1)[0]), [(16, k % 3)]) for k in range(len(keys))]
+    table = ofit.DualTable(W=W, keys=keys, local=local, ext=ext)
+    rng = np.random.default_rng(6)
+    seen = set()
+    for _ in range(300):
+        E, M = int(rng.integers(1, 40)), int(rng.integers(0, 6000))
+        N, K = int(rng.integers(1, 3000)), 8 * int(rng.integers(1, 700))
+        got = osel.select_grouped_rows(table, geo.uniform_rows(M, E), N, K)
+        assert got == osel.select_grouped(table, E, M, N, K)
+        seen.add(got[0])
+    assert len(seen) >= 2
