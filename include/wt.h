@@ -229,6 +229,14 @@ int wt_wave_count_grouped(const wt_ctx* ctx, int32_t groups, const int64_t* grou
  * single-group case) under the uniform approximation of Sec. 5.2: per-group counts are unknown on the host, so
  * each group is taken to hold ceil(M_total/groups) rows.  Split-K keys are not candidates.  Host only. */
 int wt_select_grouped(const wt_ctx* ctx, int32_t groups, int64_t M_total, int64_t N, int64_t K, wt_cfg* out);
+/* The same when the host does know the per-group row counts (a router that has synchronised, a fixed split):
+ * group_rows is a HOST pointer to `groups` counts >= 0, and G is Table 2's grouped row on them, sum_e ceil(M_e/bm) *
+ * ceil(N/bn), instead of the uniform approximation; an empty group adds no tile.  The few-row family, where the table
+ * has them, is that of the mean group, ceil(sum/groups) rows, so equal groups give wt_select_grouped's answer.
+ * 1 <= groups <= 1024; the counts' sum must fit an int32 and sum * N * K must stay below 2^62 (WT_ERR_INVALID_ARG
+ * otherwise, and for an attention context).  WT_ERR_NOT_FITTED without a table.  Host only. */
+int wt_select_grouped_rows(const wt_ctx* ctx, int32_t groups, const int64_t* group_rows, int64_t N, int64_t K,
+                           wt_cfg* out);
 
 /* ---- attention (Table 2, FlashAttention row: G = N_h * ceil(S_q/T_Q), L = ceil(S_kv/T_KV)) ---------------- */
 /* O = softmax(scale * Q K^T [+ causal mask]) V per head, one sequence, bf16 in and out, head dimension 128, on a
@@ -263,12 +271,23 @@ int wt_attn_batched(wt_ctx* ctx, int64_t batch, int64_t n_heads, int64_t n_kv_he
  * offsets, and blocks past the last query tile exit at once.  Offsets are clipped to [0, total] in the kernel, so no
  * content of the arrays can make an access leave the tensors.  causal = 1 aligns every sequence's queries to the end
  * of its own keys; a query that sees no key (a sequence with fewer keys than queries) yields zeros.  0 <= batch <= 1024.
- * The selector sees only the totals: under the uniform approximation of Sec. 5.2 the configuration is
- * wt_select(ctx, ceil(total_q/batch), batch * n_heads, ceil(total_kv/batch)).  Results per sequence are bit-identical
+ * Selection: wt_select_attn_varlen when the host knows the lengths; from the totals alone, under the uniform
+ * approximation of Sec. 5.2, wt_select(ctx, ceil(total_q/batch), batch * n_heads, ceil(total_kv/batch)).  Results per sequence are bit-identical
  * to wt_attn's.  Asynchronous, never allocates or synchronises. */
 int wt_attn_varlen(wt_ctx* ctx, int64_t batch, int64_t n_heads, int64_t n_kv_heads, int64_t total_q, int64_t total_kv,
                    const int32_t* cu_q, const int32_t* cu_kv, const void* Q, const void* K, const void* V, void* O,
                    float scale, int causal, wt_cfg cfg, void* hip_stream);
+/* Runtime selection for a wt_attn_varlen launch when the host knows the sequence lengths (HOST pointers len_q and
+ * len_kv, `batch` entries >= 0 each; a serving engine that schedules the batch has them).  Table 2's attention row is
+ * read per sequence: sequence b contributes ceil(len_q[b]/T_Q) blocks per head, each looping ceil(len_kv[b]/T_KV)
+ * times; G = n_heads * the number of query tiles, and L is the mean loop count over the blocks, rounded half up, so
+ * that G*L is the launch's number of key-tile iterations to within rounding -- exactly the row of Table 2 with the
+ * batch folded into N_h when the lengths are equal.  The mean length that wt_select on the totals prices understates
+ * a ragged batch's work, which its longest sequences carry.  1 <= batch <= 1024, 1 <= n_heads <= 65536, each sum of
+ * lengths must fit an int32 and n_heads * sum(len_q) * sum(len_kv) must stay below 2^62 (WT_ERR_INVALID_ARG
+ * otherwise, and for a context that is not an attention context).  WT_ERR_NOT_FITTED without a table.  Host only. */
+int wt_select_attn_varlen(const wt_ctx* ctx, int32_t batch, const int64_t* len_q, const int64_t* len_kv,
+                          int64_t n_heads, wt_cfg* out);
 /* wt_time_gemm's protocol for an attention launch. */
 int wt_time_attn(wt_ctx* ctx, int64_t n_heads, int64_t n_kv_heads, int64_t S_q, int64_t S_kv, const void* Q,
                  const void* K, const void* V, void* O, float scale, int causal, wt_cfg cfg, int warmup, int iters,

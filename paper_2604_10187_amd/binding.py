@@ -100,6 +100,8 @@ def lib():
                                      C.POINTER(C.c_double)],
             "wt_wave_count_grouped": [vp, i32, vp, i64, i64, wt_cfg, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32)],
             "wt_select_grouped": [vp, i32, i64, i64, i64, C.POINTER(wt_cfg)],
+            "wt_select_grouped_rows": [vp, i32, vp, i64, i64, C.POINTER(wt_cfg)],
+            "wt_select_attn_varlen": [vp, i32, vp, vp, i64, C.POINTER(wt_cfg)],
             "wt_attn": [vp, i64, i64, i64, i64, vp, vp, vp, vp, C.c_float, C.c_int, wt_cfg, vp],
             "wt_attn_batched": [vp, i64, i64, i64, i64, i64, vp, vp, vp, vp, C.c_float, C.c_int, wt_cfg, vp],
             "wt_attn_varlen": [vp, i64, i64, i64, i64, i64, vp, vp, vp, vp, vp, vp, C.c_float, C.c_int, wt_cfg, vp],
@@ -132,7 +134,7 @@ def lib():
 
 EXPORTS = ("wt_create", "wt_destroy", "wt_last_hip_error", "wt_status_string", "wt_config_count", "wt_config_get",
            "wt_config_find", "wt_key_count", "wt_key_set_occ", "wt_set_capacity_mode", "wt_set_persistent", "wt_tile_coords", "wt_gemm", "wt_gemm_noalloc", "wt_gemm_grouped",
-           "wt_time_gemm_grouped", "wt_wave_count_grouped", "wt_select_grouped", "wt_wave_count", "wt_sample_grid",
+           "wt_time_gemm_grouped", "wt_wave_count_grouped", "wt_select_grouped", "wt_select_grouped_rows", "wt_select_attn_varlen", "wt_wave_count", "wt_sample_grid",
            "wt_sample_plan", "wt_profile_sparse", "wt_time_gemm", "wt_mfma_ceiling", "wt_fit", "wt_select", "wt_predict_us",
            "wt_select_bench", "wt_save", "wt_load", "wt_attn", "wt_attn_batched", "wt_attn_varlen", "wt_time_attn", "wt_attn_block_coords",
            "wt_sample_grid_heads")
@@ -311,6 +313,24 @@ def wt_wave_count_grouped(ctx, group_rows, N, K, cfg):
 def wt_select_grouped(ctx, groups, M_total, N, K) -> wt_cfg:
     c = wt_cfg()
     _check(lib().wt_select_grouped(ctx, groups, M_total, N, K, C.byref(c)), "wt_select_grouped")
+    return c
+
+
+def wt_select_grouped_rows(ctx, group_rows, N, K) -> wt_cfg:
+    rows = np.ascontiguousarray(np.asarray(group_rows, dtype=np.int64))
+    c = wt_cfg()
+    _check(lib().wt_select_grouped_rows(ctx, len(rows), rows.ctypes.data, N, K, C.byref(c)), "wt_select_grouped_rows")
+    return c
+
+
+def wt_select_attn_varlen(ctx, len_q, len_kv, n_heads) -> wt_cfg:
+    lq = np.ascontiguousarray(np.asarray(len_q, dtype=np.int64))
+    lkv = np.ascontiguousarray(np.asarray(len_kv, dtype=np.int64))
+    if len(lq) != len(lkv):
+        raise ValueError("one kv length per query length")
+    c = wt_cfg()
+    _check(lib().wt_select_attn_varlen(ctx, len(lq), lq.ctypes.data, lkv.ctypes.data, n_heads, C.byref(c)),
+           "wt_select_attn_varlen")
     return c
 
 

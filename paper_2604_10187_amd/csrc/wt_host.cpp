@@ -521,14 +521,11 @@ static inline double predict(const double th[4], int64_t G, int64_t L) {
     return t;
 }
 
-// groups = 0: dense GEMM of M rows.  groups > 0: grouped GEMM of M rows in total under the uniform
-// approximation (Sec. 5.2, grouped-GEMM discussion: per-expert counts are not known on the host without
-// a synchronisation): every group is taken to hold ceil(M/groups) rows, so G = groups * tiles of one
-// group (Table 2, grouped row), looked up in the dense table (Sec. 4.2 reduces grouped sampling to the
-// dense case).  Split-K keys do not run grouped launches and are skipped.
-static int select_impl(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, int groups, int* key_out, int* micro_out,
-                       double* t_out) {
-    const int64_t Mg = groups > 0 ? ceil_div64(M, groups) : M;
+// The two stages over a pricing rule: phi(k, key, &G, &L, &tile_rows) says whether key k is a candidate and, if so,
+// gives its <G, L> and the tile-row count that names its few-row family.  Stage I: strict '<', so ties keep the
+// lowest key id.  Stage II: nearest loop anchor of the chosen bucket.
+template <class Phi>
+static int select_by(const wt_ctx* ctx, Phi&& phi, int* key_out, int* micro_out, double* t_out) {
     const Table& t = ctx->table;
     const int nk = static_cast<int>(ctx->keys.size());
     const Bucket* best_b = nullptr;
@@ -537,16 +534,10 @@ static int select_impl(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, int g
     int64_t best_L = 0;
     for (int k = 0; k < nk; ++k) {
         const Key& key = ctx->keys[k];
-        int64_t tiles, G, L;
-        key_phi(key, Mg, N, K, &tiles, &G, &L);
-        if (groups > 0) {
-            if (key.split != 1) continue;
-            G *= groups;
-        } else if (!key_fits(key, tiles)) {
-            continue;
-        }
+        int64_t G, L, tile_rows;
+        if (!phi(k, key, &G, &L, &tile_rows)) continue;
         const int64_t w = (G + key.cap - 1) / key.cap;
-        const Bucket* b = pick_bucket(t, k, w, (Mg + key.bm - 1) >> key.sh_m);
+        const Bucket* b = pick_bucket(t, k, w, tile_rows);
         if (!b) continue;
         const double th = predict(b->th, G, L);
         if (th != th) continue;
@@ -571,6 +562,68 @@ static int select_impl(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, int g
     *micro_out = micro;
     if (t_out) *t_out = best_t;
     return WT_OK;
+}
+
+// groups = 0: dense GEMM of M rows.  groups > 0: grouped GEMM of M rows in total under the uniform
+// approximation (Sec. 5.2, grouped-GEMM discussion: per-expert counts are not known on the host without
+// a synchronisation): every group is taken to hold ceil(M/groups) rows, so G = groups * tiles of one
+// group (Table 2, grouped row), looked up in the dense table (Sec. 4.2 reduces grouped sampling to the
+// dense case).  Split-K keys do not run grouped launches and are skipped.
+static int select_impl(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, int groups, int* key_out, int* micro_out,
+                       double* t_out) {
+    const int64_t Mg = groups > 0 ? ceil_div64(M, groups) : M;
+    return select_by(ctx, [&](int, const Key& key, int64_t* G, int64_t* L, int64_t* tile_rows) {
+        int64_t tiles;
+        key_phi(key, Mg, N, K, &tiles, G, L);
+        if (groups > 0) {
+            if (key.split != 1) return false;
+            *G *= groups;
+        } else if (!key_fits(key, tiles)) {
+            return false;
+        }
+        *tile_rows = (Mg + key.bm - 1) >> key.sh_m;
+        return true;
+    }, key_out, micro_out, t_out);
+}
+
+// Grouped GEMM with the real per-group row counts: G of Table 2's grouped row summed over the groups; the few-row
+// family is that of the mean group, ceil(sum / groups) rows (the uniform reading when the groups are equal).
+static int select_rows_impl(const wt_ctx* ctx, int groups, const int64_t* rows, int64_t N, int64_t K, int* key_out,
+                            int* micro_out) {
+    int64_t total = 0;
+    for (int e = 0; e < groups; ++e) total += rows[e];
+    const int64_t mean_rows = ceil_div64(total, groups);
+    return select_by(ctx, [&](int, const Key& key, int64_t* G, int64_t* L, int64_t* tile_rows) {
+        if (key.split != 1) return false;
+        int64_t g = 0, tiles, ge;
+        for (int e = 0; e < groups; ++e) {
+            key_phi(key, rows[e], N, K, &tiles, &ge, L);
+            g += ge;
+        }
+        *G = g;
+        *tile_rows = (mean_rows + key.bm - 1) >> key.sh_m;
+        return true;
+    }, key_out, micro_out, nullptr);
+}
+
+// A ragged attention batch with the real per-sequence lengths (Table 2's attention row per sequence): G counts every
+// block, L is the mean loop count over the blocks rounded half up, so G*L is the launch's number of key-tile
+// iterations to within rounding.  No block at all: G = L = 0.
+static int select_varlen_impl(const wt_ctx* ctx, int batch, const int64_t* len_q, const int64_t* len_kv,
+                              int64_t n_heads, int* key_out, int* micro_out) {
+    return select_by(ctx, [&](int, const Key& key, int64_t* G, int64_t* L, int64_t* tile_rows) {
+        int64_t t = 0, iters = 0;
+        for (int b = 0; b < batch; ++b) {
+            const int64_t tiles = (len_q[b] + key.bm - 1) >> key.sh_m;
+            const int64_t loops = (len_kv[b] + (int64_t{1} << key.sh_k) - 1) >> key.sh_k;
+            t += tiles;
+            iters += tiles * loops;
+        }
+        *G = n_heads * t;
+        *L = t ? (2 * iters + t) / (2 * t) : 0;
+        *tile_rows = 0;  // attention tables carry no few-row families
+        return true;
+    }, key_out, micro_out, nullptr);
 }
 
 // ---- table file ------------------------------------------------------------------------------------
@@ -826,6 +879,59 @@ int wt_select_grouped(const wt_ctx* ctx, int32_t groups, int64_t M_total, int64_
     if (!ctx->table.fitted) return WT_ERR_NOT_FITTED;
     int key, micro;
     const int rc = select_impl(ctx, M_total, N, K, groups, &key, &micro, nullptr);
+    if (rc != WT_OK) return rc;
+    const Key& k = ctx->keys[key];
+    if (micro < 0 || micro >= k.n_micro) micro = 0;
+    *out = ctx->cfgs[k.first_cfg + micro].cfg;
+    return WT_OK;
+}
+
+// Limits of the selectors that take per-part sizes: the part count the launches accept, totals that fit the int32
+// offsets those launches read, and a G*L that cannot leave int64 (tiles <= rows, column tiles <= N, loops <= K).
+static constexpr int kMaxSelectParts = 1024;
+static constexpr int64_t kMaxSelectTokens = 0x7FFFFFFF;
+static inline bool product_fits(int64_t a, int64_t b, int64_t c) {
+    if (a <= 0 || b <= 0 || c <= 0) return true;
+    return a <= ((int64_t{1} << 62) / b) / c;
+}
+
+int wt_select_grouped_rows(const wt_ctx* ctx, int32_t groups, const int64_t* group_rows, int64_t N, int64_t K,
+                           wt_cfg* out) {
+    if (!ctx || !out || groups < 1 || groups > kMaxSelectParts || !group_rows || N < 0 || K < 0 ||
+        ctx->in_type == WT_ATTN_BF16)
+        return WT_ERR_INVALID_ARG;
+    int64_t total = 0;
+    for (int e = 0; e < groups; ++e) {
+        if (group_rows[e] < 0 || group_rows[e] > kMaxSelectTokens - total) return WT_ERR_INVALID_ARG;
+        total += group_rows[e];
+    }
+    if (!product_fits(total, N, K)) return WT_ERR_INVALID_ARG;
+    if (!ctx->table.fitted) return WT_ERR_NOT_FITTED;
+    int key, micro;
+    const int rc = select_rows_impl(ctx, groups, group_rows, N, K, &key, &micro);
+    if (rc != WT_OK) return rc;
+    const Key& k = ctx->keys[key];
+    if (micro < 0 || micro >= k.n_micro) micro = 0;
+    *out = ctx->cfgs[k.first_cfg + micro].cfg;
+    return WT_OK;
+}
+
+int wt_select_attn_varlen(const wt_ctx* ctx, int32_t batch, const int64_t* len_q, const int64_t* len_kv,
+                          int64_t n_heads, wt_cfg* out) {
+    if (!ctx || !out || batch < 1 || batch > kMaxSelectParts || !len_q || !len_kv || n_heads < 1 || n_heads > 65536 ||
+        ctx->in_type != WT_ATTN_BF16)
+        return WT_ERR_INVALID_ARG;
+    int64_t tq = 0, tkv = 0;
+    for (int b = 0; b < batch; ++b) {
+        if (len_q[b] < 0 || len_kv[b] < 0 || len_q[b] > kMaxSelectTokens - tq || len_kv[b] > kMaxSelectTokens - tkv)
+            return WT_ERR_INVALID_ARG;
+        tq += len_q[b];
+        tkv += len_kv[b];
+    }
+    if (!product_fits(n_heads, tq, tkv)) return WT_ERR_INVALID_ARG;
+    if (!ctx->table.fitted) return WT_ERR_NOT_FITTED;
+    int key, micro;
+    const int rc = select_varlen_impl(ctx, batch, len_q, len_kv, n_heads, &key, &micro);
     if (rc != WT_OK) return rc;
     const Key& k = ctx->keys[key];
     if (micro < 0 || micro >= k.n_micro) micro = 0;

@@ -286,7 +286,8 @@ def cmd_large(a, torch):
 def cmd_grouped(a, torch):
     """Grouped GEMM (MoE expert projections): synthetic skewed routing, every unsplit configuration timed
     with the routing's real group sizes; the pick comes from wt_select_grouped, which sees only the number
-    of groups and the total row count (uniform approximation).
+    of groups and the total row count (uniform approximation); beside it, the pick of wt_select_grouped_rows,
+    which is given the real counts (a router that has synchronised).
     """
     import wt_synth
 
@@ -305,11 +306,12 @@ def cmd_grouped(a, torch):
             A = torch.randn((M_total, K), device="cuda", generator=g).to(torch.bfloat16)
             C = torch.empty((M_total, N), device="cuda", dtype=torch.bfloat16)
             pick = wt.wt_select_grouped(ctx, E, M_total, N, K)
+            pick_rows = wt.wt_select_grouped_rows(ctx, counts, N, K)
             times, best = {}, math.inf
             for i, (c, r) in enumerate(cfgs):
                 if c.split != 1 or r.occ < 1:
                     continue
-                if i != pick.id and best < math.inf:
+                if i not in (pick.id, pick_rows.id) and best < math.inf:
                     t1 = wt.wt_time_gemm_grouped(ctx, E, off, M_total, N, K, A, B, C, c, 1, 1, stream=stream)
                     if t1 > a.prune * best:
                         continue
@@ -322,16 +324,20 @@ def cmd_grouped(a, torch):
                          "pick": list(pick.astuple()), "pick_us": times[pick.id],
                          "best": list(cfgs[best_id][0].astuple()), "best_us": times[best_id],
                          "frac": times[best_id] / times[pick.id],
+                         "pick_rows": list(pick_rows.astuple()), "frac_rows": times[best_id] / times[pick_rows.id],
                          "pick_tflops": 2.0 * M_total * N * K / times[pick.id] / 1e6,
                          "best_tflops": 2.0 * M_total * N * K / times[best_id] / 1e6, "n_timed": len(times),
                          "times": {str(i): round(t, 3) for i, t in times.items()}})
-            _log(f"[eval] grouped E={E} tokens={tokens} N={N} K={K}: frac {rows[-1]['frac']:.3f} "
+            _log(f"[eval] grouped E={E} tokens={tokens} N={N} K={K}: frac {rows[-1]['frac']:.3f} (real counts {rows[-1]['frac_rows']:.3f}) "
                  f"pick {rows[-1]['pick_us']:.1f}us {rows[-1]['pick_tflops']:.0f} TF")
             del A, C
         del B
     fr = np.array([r["frac"] for r in rows])
+    frr = np.array([r["frac_rows"] for r in rows])
     summary = {"n_cases": len(rows), "geomean_frac": float(np.exp(np.mean(np.log(fr)))), "min_frac": float(fr.min()),
-               "frac_ge_95": float(np.mean(fr >= 0.95))}
+               "frac_ge_95": float(np.mean(fr >= 0.95)),
+               "real_counts": {"geomean_frac": float(np.exp(np.mean(np.log(frr)))), "min_frac": float(frr.min()),
+                               "frac_ge_95": float(np.mean(frr >= 0.95))}}
     return {"workload": f"grouped GEMM, MoE expert projections, routing probabilities 1/rank^{a.skew}, bf16", "table": path,
             "summary": summary, "rows": rows}
 
@@ -485,22 +491,22 @@ def cmd_attn(a, torch):
 
 
 def cmd_attn_varlen(a, torch):
-    """Variable-length prefill batches (the shape of the paper's end-to-end setting, Sec. 5.3: batches of 4 prompts of
-    512..16384 tokens; 32 query / 4 KV heads of dimension 128): wt_attn_varlen under the configuration
-    wt_select(ceil(total/batch), batch * heads, ceil(total/batch)) -- the selector sees only the totals -- against
-    exhaustive search over the attention registry with the real lengths, causal."""
+    """Variable-length prefill batches (the shape of the paper's end-to-end setting, Sec. 5.3: batches of 2/4/8 prompts
+    of 512..16384 tokens; 32 query / 4 KV heads of dimension 128): wt_attn_varlen under the pick of
+    wt_select_attn_varlen (the host knows the lengths) and, beside it, under wt_select(ceil(total/batch), batch * heads,
+    ceil(total/batch)) (a selector that sees only the totals), against exhaustive search over the attention registry
+    with the real lengths, causal."""
+    import wt_synth
+
     ctx = wt.wt_create(0, wt.WT_ATTN_BF16, wt.WT_OUT_BF16)
     path = a.table or tune.table_path(wt.WT_ATTN_BF16, wt.WT_OUT_BF16)
     wt.wt_load(ctx, path)
     cfgs = [wt.wt_config_get(ctx, i) for i in range(wt.wt_config_count(ctx))]
     stream = torch.cuda.current_stream()
     H_q, H_kv, scale = 32, 4, 1.0 / math.sqrt(128.0)
-    rng = np.random.default_rng(a.sample_seed)
     rows = []
-    for case in range(a.sample):
-        batch = int(rng.choice([2, 4, 8]))
-        lens = [int(round(math.exp(rng.uniform(math.log(512), math.log(16384))))) for _ in range(batch)]
-        total = sum(lens)
+    for case, lens in enumerate(wt_synth.varlen_batches(a.sample, a.sample_seed)):
+        batch, total = len(lens), sum(lens)
         cu = torch.tensor(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32), device="cuda")
         g = torch.Generator(device="cuda")
         g.manual_seed(5000 + case)
@@ -521,17 +527,21 @@ def cmd_attn_varlen(a, torch):
             return e0.elapsed_time(e1) * 1e3 / iters
         times = {i: timed(c) for i, (c, r) in enumerate(cfgs)}
         mean_len = -(-total // batch)
-        pick = wt.wt_select(ctx, mean_len, batch * H_q, mean_len)
+        pick = wt.wt_select_attn_varlen(ctx, lens, lens, H_q)
+        pick_totals = wt.wt_select(ctx, mean_len, batch * H_q, mean_len)
         best = min(times, key=times.get)
         flop = sum(4.0 * s * s * 128 * H_q * 0.5 for s in lens)
         rows.append({"batch": batch, "lens": lens, "pick": list(pick.astuple()), "pick_us": times[pick.id],
                      "best": list(cfgs[best][0].astuple()), "best_us": times[best], "frac": times[best] / times[pick.id],
+                     "pick_totals": list(pick_totals.astuple()), "frac_totals": times[best] / times[pick_totals.id],
                      "pick_tflops": flop / times[pick.id] / 1e6, "times": {str(i): round(t, 2) for i, t in times.items()}})
         _log(f"[varlen] case {case}: batch {batch}, {total} tokens, frac {rows[-1]['frac']:.3f}, {rows[-1]['pick_tflops']:.0f} TF")
     fr = np.array([r["frac"] for r in rows])
     gm = lambda x: float(np.exp(np.mean(np.log(np.asarray(x, dtype=np.float64)))))
     fixed = min(range(len(cfgs)), key=lambda i: gm([r["times"][str(i)] for r in rows]))
+    ft = np.array([r["frac_totals"] for r in rows])
     summary = {"n_cases": len(rows), "geomean_frac": gm(fr), "min_frac": float(fr.min()), "frac_ge_95": float(np.mean(fr >= 0.95)),
+               "totals_only": {"geomean_frac": gm(ft), "min_frac": float(ft.min()), "frac_ge_95": float(np.mean(ft >= 0.95))},
                "fixed_default": list(cfgs[fixed][0].astuple()),
                "fixed_default_geomean_frac": gm([r["best_us"] / r["times"][str(fixed)] for r in rows]),
                "pick_tflops_geomean": gm([r["pick_tflops"] for r in rows])}

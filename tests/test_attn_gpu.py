@@ -245,6 +245,38 @@ def test_bench_shape_under_the_selected_config(ctx):
         check(got[i:i + 1], want, f"bench-shape row {i}")
 
 
+def test_ragged_batch_under_the_varlen_selectors_pick(ctx):
+    """A ragged causal prefill batch (four prompts, 8 query / 2 KV heads) under the configuration that
+    wt_select_attn_varlen returns from the shipped table for its real lengths: the pick is the oracle's, and every
+    sequence of the launch is checked against the fp64 oracle."""
+    import os
+    from oracle import select as osel
+
+    lens, H_q, H_kv = [700, 90, 1500, 33], 8, 2
+    path = os.path.join(os.path.dirname(wt.LIB_PATH), "tables", "mi355x_attn.wt")
+    wt.wt_load(ctx, path)
+    pick = wt.wt_select_attn_varlen(ctx, lens, lens, H_q)
+    table, _ = osel.read_table(path)
+    key, micro, _ = osel.select_attn_varlen(table, H_q, lens, lens)
+    kd = table.keys[key]
+    assert (pick.bm, pick.bk, pick.nwave, pick.swizzle) == (kd.bm, kd.bk, kd.nwave, micro)
+    note(f"attn ragged batch lens={lens} H={H_q}/{H_kv} cfg={pick.astuple()}")
+    seqs = [wt_synth.attn_operands(s, s, H_q, H_kv, 1700 + b) for b, s in enumerate(lens)]
+    qb, kb, vb = (np.concatenate([s[i] for s in seqs]) for i in range(3))
+    cu = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).cuda()
+    total = sum(lens)
+    dQ, dK, dV = (dev_bits(x.reshape(-1, 128)).view(torch.bfloat16) for x in (qb, kb, vb))
+    dO = torch.full((total * H_q, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
+    wt.wt_attn_varlen(ctx, len(lens), H_q, H_kv, total, total, cu, cu, dQ, dK, dV, dO, SCALE, 1, pick,
+                      stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    got = dO.float().cpu().numpy().reshape(total, H_q, 128)
+    off = 0
+    for b, s in enumerate(lens):
+        check(got[off:off + s], reference(*seqs[b], True), f"ragged batch seq {b}")
+        off += s
+
+
 def test_many_heads_and_decode_like_shapes(ctx):
     """128 query heads on 2 KV heads (the widest grouping of the test ranges), a single query against 20 000 keys
     (one block per head, 157-313 KV tiles, ragged tail), and a causal single query (sees every key)."""

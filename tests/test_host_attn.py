@@ -133,6 +133,57 @@ def test_fit_and_select_parity_on_a_synthetic_surface(ctx, tmp_path):
         c = wt.wt_select(ctx, S_q, H_q, S_kv)
         assert (c.bm, c.bk, c.nwave, c.swizzle) == (keys[key].bm, keys[key].bk, keys[key].nwave, micro)
         assert wt.wt_predict_us(ctx, S_q, H_q, S_kv, c) == t
+    _varlen_selection_matches(ctx, table, keys, seed=21)
+
+
+def _varlen_selection_matches(ctx, table, keys, seed):
+    """wt_select_attn_varlen against the oracle's select_attn_varlen on ragged batches (prefill: keys = queries; decode
+    and chunked prefill: keys > queries; some empty sequences), and its reduction to wt_select on equal lengths."""
+    rng = np.random.default_rng(seed)
+    batches = wt_synth.varlen_batches(60, seed) + wt_synth.varlen_batches(40, seed + 1, lo=1, hi=700)
+    differs = 0
+    for i, lens in enumerate(batches):
+        H_q = int(wt_synth.ATTN_Q_HEADS[i % 4])
+        lq = list(lens)
+        lkv = list(lens) if i % 3 else [s + int(rng.integers(0, 4000)) for s in lens]
+        if i % 7 == 0:
+            lq[0] = 0
+        key, micro, _ = osel.select_attn_varlen(table, H_q, lq, lkv)
+        c = wt.wt_select_attn_varlen(ctx, lq, lkv, H_q)
+        assert (c.bm, c.bk, c.nwave, c.swizzle) == (keys[key].bm, keys[key].bk, keys[key].nwave, micro), (lq, lkv, H_q)
+        mean_q, mean_kv = -(-sum(lq) // len(lq)), -(-sum(lkv) // len(lkv))
+        differs += wt.wt_select(ctx, mean_q, len(lq) * H_q, mean_kv).id != c.id
+    assert differs >= 3          # pricing the real lengths is not pricing the mean length
+    for (S_q, S_kv, H_q, _) in wt_synth.attn_shapes(40, seed + 2):
+        for b in (1, 3):
+            assert wt.wt_select_attn_varlen(ctx, [S_q] * b, [S_kv] * b, H_q).id == wt.wt_select(ctx, S_q, b * H_q, S_kv).id
+
+
+def test_varlen_selector_argument_checks(ctx):
+    INV = wt.WT_ERR_INVALID_ARG
+    for (lq, lkv, H) in [([], [], 8), ([1] * 1025, [1] * 1025, 8), ([5, -1], [5, 5], 8), ([5, 5], [5, -2], 8),
+                         ([5], [5], 0), ([5], [5], 65537), ([2**30] * 3, [1] * 3, 8), ([1] * 3, [2**30] * 3, 8),
+                         ([2**30], [2**30], 65536)]:
+        with pytest.raises(wt.WtError) as e:
+            wt.wt_select_attn_varlen(ctx, lq, lkv, H)
+        assert e.value.status == INV, (len(lq), H)
+    with pytest.raises(ValueError):
+        wt.wt_select_attn_varlen(ctx, [1, 2], [1], 8)
+    fresh = wt.wt_create(-1, wt.WT_ATTN_BF16, wt.WT_OUT_BF16)
+    gemm = wt.wt_create(-1, wt.WT_BF16, wt.WT_OUT_BF16)
+    try:
+        with pytest.raises(wt.WtError) as e:
+            wt.wt_select_attn_varlen(fresh, [5], [5], 8)
+        assert e.value.status == wt.WT_ERR_NOT_FITTED
+        with pytest.raises(wt.WtError) as e:
+            wt.wt_select_attn_varlen(gemm, [5], [5], 8)
+        assert e.value.status == INV
+        with pytest.raises(wt.WtError) as e:
+            wt.wt_select_grouped_rows(fresh, [5], 8, 8)
+        assert e.value.status == INV
+    finally:
+        wt.wt_destroy(fresh)
+        wt.wt_destroy(gemm)
 
 
 def test_shipped_attention_table_selects_like_the_oracle():
@@ -147,5 +198,6 @@ def test_shipped_attention_table_selects_like_the_oracle():
             got = wt.wt_select(c, S_q, H_q, S_kv)
             assert (got.bm, got.bk, got.nwave, got.swizzle) == (keys[key].bm, keys[key].bk, keys[key].nwave, micro)
             assert wt.wt_predict_us(c, S_q, H_q, S_kv, got) == t
+        _varlen_selection_matches(c, table, keys, seed=31)
     finally:
         wt.wt_destroy(c)

@@ -312,6 +312,7 @@ def test_grouped_geometry_and_selection(ctx):
     with tempfile.TemporaryDirectory() as d:
         wt.wt_save(ctx, d + "/g.wt")
         table, _ = osel.read_table(d + "/g.wt", **SPLIT_LIMITS)
+    differs = 0
     for (E, top_k, N, K) in wt_synth.MOE_LAYERS:
         for tokens in wt_synth.MOE_TOKENS:
             rows = wt_synth.moe_routing(tokens, E, top_k, seed=tokens + E)
@@ -326,10 +327,34 @@ def test_grouped_geometry_and_selection(ctx):
             key, micro, t = osel.select_grouped(table, E, tokens * top_k, N, K)
             c = wt.wt_select_grouped(ctx, E, tokens * top_k, N, K)
             assert c.id == 3 * key + micro and c.split == 1
+            routings = [wt_synth.moe_routing(tokens, E, top_k, seed=tokens + E, skew=skew) for skew in (1.0, 0.25)]
+            routings.append(np.array([tokens * top_k] + [0] * (E - 1)))        # every row in one group
+            for rows in routings:           # the real counts (Table 2's grouped row as it stands)
+                key_r, micro_r, _ = osel.select_grouped_rows(table, rows.tolist(), N, K)
+                c = wt.wt_select_grouped_rows(ctx, rows, N, K)
+                assert c.id == 3 * key_r + micro_r and c.split == 1
+                differs += (key_r, micro_r) != (key, micro)
+    assert differs >= 3         # the real counts do change picks, so the comparison above tells the two calls apart
     # one group is the dense problem
     for (M, N, K) in wt_synth.sweep_shapes():
         key, micro, _ = osel.select_grouped(table, 1, M, N, K)
         assert wt.wt_select_grouped(ctx, 1, M, N, K).id == 3 * key + micro
+        assert wt.wt_select_grouped_rows(ctx, [M], N, K).id == 3 * key + micro
+    # argument checks of the real-counts call: no group, too many, a negative count, a sum beyond int32, G*L beyond int64
+    for bad in ([], [1] * 1025, [5, -1], [2**30, 2**30, 2**30]):
+        with pytest.raises(wt.WtError) as e:
+            wt.wt_select_grouped_rows(ctx, bad, 128, 128)
+        assert e.value.status == wt.WT_ERR_INVALID_ARG
+    with pytest.raises(wt.WtError) as e:
+        wt.wt_select_grouped_rows(ctx, [2**30], 2**20, 2**20)
+    assert e.value.status == wt.WT_ERR_INVALID_ARG
+    fresh = wt.wt_create(-1, wt.WT_BF16, wt.WT_OUT_BF16)
+    try:
+        with pytest.raises(wt.WtError) as e:
+            wt.wt_select_grouped_rows(fresh, [5, 5], 128, 128)
+        assert e.value.status == wt.WT_ERR_NOT_FITTED
+    finally:
+        wt.wt_destroy(fresh)
 
 
 def _pred_close(th_a, th_b, kd):

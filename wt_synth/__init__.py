@@ -191,3 +191,14 @@ def attn_shapes(count: int = 64, seed: int = 1006):
         hkv = int(ATTN_KV_HEADS[rng.integers(0, len(ATTN_KV_HEADS))])
         out.append((s, s, hq, min(hkv, hq)))
     return out
+
+
+def varlen_batches(count: int = 20, seed: int = 4001, lo: int = 512, hi: int = 16384):
+    """Ragged prefill batches (the shape of the paper's end-to-end setting, Sec. 5.3): 2, 4 or 8 prompts each, prompt
+    lengths log-uniform in [lo, hi].  Returns a list of length lists."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        batch = int(rng.choice([2, 4, 8]))
+        out.append([int(round(math.exp(rng.uniform(math.log(lo), math.log(hi))))) for _ in range(batch)])
+    return out
