@@ -233,8 +233,8 @@ int wt_select_grouped(const wt_ctx* ctx, int32_t groups, int64_t M_total, int64_
  * group_rows is a HOST pointer to `groups` counts >= 0, and G is Table 2's grouped row on them, sum_e ceil(M_e/bm) *
  * ceil(N/bn), instead of the uniform approximation; an empty group adds no tile.  The few-row family, where the table
  * has them, is that of the mean group, ceil(sum/groups) rows, so equal groups give wt_select_grouped's answer.
- * 1 <= groups <= 1024; the counts' sum must fit an int32 and sum * N * K must stay below 2^62 (WT_ERR_INVALID_ARG
- * otherwise, and for an attention context).  WT_ERR_NOT_FITTED without a table.  Host only. */
+ * 1 <= groups <= 1024 and the counts' sum must fit an int32 (WT_ERR_INVALID_ARG otherwise, and for an attention
+ * context).  WT_ERR_NOT_FITTED without a table.  Host only. */
 int wt_select_grouped_rows(const wt_ctx* ctx, int32_t groups, const int64_t* group_rows, int64_t N, int64_t K,
                            wt_cfg* out);
 
@@ -349,7 +349,10 @@ int wt_fit(wt_ctx* ctx, const wt_grid* grid, const wt_sample* samples, size_t n)
 /* ---- runtime selection (Sec. 4.4, 4.5) ---------------------------------------------------- */
 /* Stage I: argmin over structural keys of the bucket's bilinear prediction (extrapolation tuple
  * when w > W or the bucket is empty); Stage II: nearest loop anchor -> micro.  Host only,
- * read-only, thread-safe, no allocation, no system calls. */
+ * read-only, thread-safe, no allocation, no system calls.  WT_ERR_NOT_FITTED without a table.  This call and every
+ * other that evaluates Phi or a prediction (wt_wave_count, wt_predict_us, the grouped and variable-length forms)
+ * returns WT_ERR_INVALID_ARG for a negative dimension and for a shape so large that G*L could leave int64:
+ * M * N * max(K, 16) above 2^62 (grouped: M = rows + groups), far beyond what a launch accepts. */
 int wt_select(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, wt_cfg* out);
 /* Predicted latency of one configuration's structural key for a shape (microseconds). */
 int wt_predict_us(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, wt_cfg cfg, double* us);

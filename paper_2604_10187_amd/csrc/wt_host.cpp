@@ -521,6 +521,17 @@ static inline double predict(const double th[4], int64_t G, int64_t L) {
     return t;
 }
 
+// Limits of the selectors that take per-part sizes: the part count the launches accept, totals that fit the int32
+// offsets those launches read, and a G*L that cannot leave int64 (tiles <= rows, column tiles <= N, loops <= K).
+static constexpr int kMaxSelectParts = 1024;
+static constexpr int64_t kMaxSelectTokens = 0x7FFFFFFF;
+static inline bool product_fits(int64_t a, int64_t b, int64_t c) {
+    if (a <= 0 || b <= 0 || c <= 0) return true;
+    return a <= ((int64_t{1} << 62) / b) / c;
+}
+// Every shape the selectors price must keep G*L inside int64 for every key: tiles <= M*N, at most 16 splits, L <= K.
+static inline bool shape_fits(int64_t M, int64_t N, int64_t K) { return product_fits(M, N, K < 16 ? 16 : K); }
+
 // The two stages over a pricing rule: phi(k, key, &G, &L, &tile_rows) says whether key k is a candidate and, if so,
 // gives its <G, L> and the tile-row count that names its few-row family.  Stage I: strict '<', so ties keep the
 // lowest key id.  Stage II: nearest loop anchor of the chosen bucket.
@@ -809,7 +820,7 @@ int wt_set_capacity_mode(wt_ctx* ctx, int mode) {
 
 int wt_wave_count(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, wt_cfg cfg, int64_t* G, int64_t* L,
                   int32_t* w) {
-    if (!ctx || M < 0 || N < 0 || K < 0) return WT_ERR_INVALID_ARG;
+    if (!ctx || M < 0 || N < 0 || K < 0 || !shape_fits(M, N, K)) return WT_ERR_INVALID_ARG;
     const int id = find_config(ctx, cfg);
     if (id < 0) return WT_ERR_UNSUPPORTED_CFG;
     const Key& k = ctx->keys[ctx->cfgs[id].res.key_id];
@@ -863,7 +874,7 @@ int wt_fit(wt_ctx* ctx, const wt_grid* grid, const wt_sample* samples, size_t n)
 }
 
 int wt_select(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, wt_cfg* out) {
-    if (!ctx || !out || M < 0 || N < 0 || K < 0) return WT_ERR_INVALID_ARG;
+    if (!ctx || !out || M < 0 || N < 0 || K < 0 || !shape_fits(M, N, K)) return WT_ERR_INVALID_ARG;
     if (!ctx->table.fitted) return WT_ERR_NOT_FITTED;
     int key, micro;
     const int rc = select_impl(ctx, M, N, K, 0, &key, &micro, nullptr);
@@ -875,7 +886,8 @@ int wt_select(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, wt_cfg* out) {
 }
 
 int wt_select_grouped(const wt_ctx* ctx, int32_t groups, int64_t M_total, int64_t N, int64_t K, wt_cfg* out) {
-    if (!ctx || !out || groups < 1 || M_total < 0 || N < 0 || K < 0) return WT_ERR_INVALID_ARG;
+    if (!ctx || !out || groups < 1 || M_total < 0 || N < 0 || K < 0 || !shape_fits(M_total + groups, N, K))
+        return WT_ERR_INVALID_ARG;
     if (!ctx->table.fitted) return WT_ERR_NOT_FITTED;
     int key, micro;
     const int rc = select_impl(ctx, M_total, N, K, groups, &key, &micro, nullptr);
@@ -884,15 +896,6 @@ int wt_select_grouped(const wt_ctx* ctx, int32_t groups, int64_t M_total, int64_
     if (micro < 0 || micro >= k.n_micro) micro = 0;
     *out = ctx->cfgs[k.first_cfg + micro].cfg;
     return WT_OK;
-}
-
-// Limits of the selectors that take per-part sizes: the part count the launches accept, totals that fit the int32
-// offsets those launches read, and a G*L that cannot leave int64 (tiles <= rows, column tiles <= N, loops <= K).
-static constexpr int kMaxSelectParts = 1024;
-static constexpr int64_t kMaxSelectTokens = 0x7FFFFFFF;
-static inline bool product_fits(int64_t a, int64_t b, int64_t c) {
-    if (a <= 0 || b <= 0 || c <= 0) return true;
-    return a <= ((int64_t{1} << 62) / b) / c;
 }
 
 int wt_select_grouped_rows(const wt_ctx* ctx, int32_t groups, const int64_t* group_rows, int64_t N, int64_t K,
@@ -905,7 +908,7 @@ int wt_select_grouped_rows(const wt_ctx* ctx, int32_t groups, const int64_t* gro
         if (group_rows[e] < 0 || group_rows[e] > kMaxSelectTokens - total) return WT_ERR_INVALID_ARG;
         total += group_rows[e];
     }
-    if (!product_fits(total, N, K)) return WT_ERR_INVALID_ARG;
+    if (!shape_fits(total + groups, N, K)) return WT_ERR_INVALID_ARG;
     if (!ctx->table.fitted) return WT_ERR_NOT_FITTED;
     int key, micro;
     const int rc = select_rows_impl(ctx, groups, group_rows, N, K, &key, &micro);
@@ -946,9 +949,13 @@ int wt_wave_count_grouped(const wt_ctx* ctx, int32_t groups, const int64_t* grou
     if (id < 0) return WT_ERR_UNSUPPORTED_CFG;
     const Key& k = ctx->keys[ctx->cfgs[id].res.key_id];
     if (k.split != 1) return WT_ERR_UNSUPPORTED_CFG;
-    int64_t g = 0, l = 0;
+    int64_t g = 0, l = 0, total = 0;
     for (int e = 0; e < groups; ++e) {
-        if (group_rows[e] < 0) return WT_ERR_INVALID_ARG;
+        if (group_rows[e] < 0 || group_rows[e] > kMaxSelectTokens - total) return WT_ERR_INVALID_ARG;
+        total += group_rows[e];
+    }
+    if (!shape_fits(total + groups, N, K)) return WT_ERR_INVALID_ARG;
+    for (int e = 0; e < groups; ++e) {
         int64_t tiles, ge;
         key_phi(k, group_rows[e], N, K, &tiles, &ge, &l);
         g += ge;
@@ -960,7 +967,7 @@ int wt_wave_count_grouped(const wt_ctx* ctx, int32_t groups, const int64_t* grou
 }
 
 int wt_predict_us(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, wt_cfg cfg, double* us) {
-    if (!ctx || !us || M < 0 || N < 0 || K < 0) return WT_ERR_INVALID_ARG;
+    if (!ctx || !us || M < 0 || N < 0 || K < 0 || !shape_fits(M, N, K)) return WT_ERR_INVALID_ARG;
     if (!ctx->table.fitted) return WT_ERR_NOT_FITTED;
     const int id = find_config(ctx, cfg);
     if (id < 0) return WT_ERR_UNSUPPORTED_CFG;

@@ -366,6 +366,23 @@ def _pred_close(th_a, th_b, kd):
     return True
 
 
+def test_shapes_whose_task_loop_product_could_leave_int64_are_refused(ctx):
+    """G*L is formed in int64 (the oracle uses unbounded integers): shapes with M*N*max(K,16) above 2^62 are an argument
+    error in every call that evaluates Phi or a prediction, and the largest launchable shape is far below that."""
+    wt.wt_fit(ctx, wt.make_grid(W=4, I=2, p=2, k_anchors=K_ANCHORS), _synthetic_samples(_keys(ctx), 4, 2))
+    c, _ = wt.wt_config_get(ctx, 0)
+    big = 2 ** 30
+    for call in (lambda: wt.wt_select(ctx, big, big, 2 ** 21), lambda: wt.wt_predict_us(ctx, big, big, 2 ** 21, c),
+                 lambda: wt.wt_wave_count(ctx, 2 ** 31, 2 ** 31, 8, c), lambda: wt.wt_select_grouped(ctx, 4, big, big, 2 ** 21),
+                 lambda: wt.wt_wave_count_grouped(ctx, [big, big - 1], big, 2 ** 21, c)):
+        with pytest.raises(wt.WtError) as e:
+            call()
+        assert e.value.status == wt.WT_ERR_INVALID_ARG
+    G, L, w = wt.wt_wave_count(ctx, 2 ** 24, 2 ** 24, 2 ** 14, c)            # 2^62 exactly: accepted, exact
+    assert (G, L) == geo.phi_gemm(2 ** 24, 2 ** 24, 2 ** 14, c.bm, c.bn, c.bk, c.split)
+    assert wt.wt_select(ctx, 2 ** 24, 2 ** 24, 2 ** 14).id >= 0
+
+
 def test_select_is_fast_and_allocates_nothing_visible(ctx):
     W, I = 8, 2
     samples = _synthetic_samples(_keys(ctx), W, I)
