@@ -55,6 +55,8 @@ class DualTable:
     W_row: int = 0        # few-row families (extension): profiled waves, 0 = absent
     row_local: list = field(default_factory=list)   # row_local[fam-1][key][w-1] -> Bucket, fam = 1..row_fams
     row_ext: list = field(default_factory=list)     # row_ext[fam-1][key] -> Bucket
+    row_mode: int = 0     # 0: family f holds grids of 1, 2, 4 tile rows and is consulted per key by the shape's tile rows;
+                          # 1: family f holds matrices of 16, 32, 64, 128 rows and is consulted by the shape's M for all keys
     # feasibility limits of whatever runs the split-K keys (floats of partial tiles per launch, output
     # tiles per launch); None = unlimited.  Not part of the method: set by the caller (see geometry.split_fits)
     ws_elems: Optional[int] = None
@@ -208,7 +210,7 @@ MODEL_WAVE_BILINEAR, MODEL_LINEAR, MODEL_STEP = 0, 1, 2
 
 
 def fit_tables(samples, keys, W: int, p: int, model: int = MODEL_WAVE_BILINEAR, W_row: int = 0,
-               row_fams: int = 1, max_anchors=None, relative: bool = False) -> DualTable:
+               row_fams: int = 1, max_anchors=None, relative: bool = False, row_mode: int = 0) -> DualTable:
     """Build the dual table (Sec. 4.3) with per-key extrapolation entries fitted on the merged
     samples of the last p profiled waves, max(1, W-p+1)..W (Sec. 4.5).  Samples with w > W are
     ignored.  max_anchors: anchor slots per bucket of the table being imitated (see thin_anchors; None = all).
@@ -226,6 +228,7 @@ def fit_tables(samples, keys, W: int, p: int, model: int = MODEL_WAVE_BILINEAR, 
         # (wave buckets 1..W_row, extrapolation from the last min(p, W_row) of them)
         t = fit_tables([s for s in samples if s.fam == 0], keys, W, p, model, max_anchors=max_anchors, relative=relative)
         t.W_row = W_row
+        t.row_mode = row_mode     # only says how the families are consulted; each is fitted from its records alike
         for f in range(1, row_fams + 1):
             rows_t = fit_tables([s._replace(fam=0) for s in samples if s.fam == f], keys, W_row, min(p, W_row),
                                 max_anchors=max_anchors, relative=relative)

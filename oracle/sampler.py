@@ -11,7 +11,7 @@ from __future__ import annotations
 import math
 from typing import NamedTuple, Optional
 
-from .geometry import wave_region
+from .geometry import ceil_div, wave_region
 
 
 class GridSample(NamedTuple):
@@ -117,6 +117,26 @@ def row_family(tile_rows: int) -> int:
     """Which sample family serves a shape with ceil(M/T_M) = tile_rows tile rows: the 1-row family for 1,
     the 2-row family for 2..3, the 4-row family for 4..7, the paper's near-square samples (0) otherwise."""
     return 1 if tile_rows <= 1 else 2 if tile_rows <= 3 else 3 if tile_rows <= 7 else 0
+
+
+ROW_BANDS = (16, 32, 64, 128)
+
+
+def band_family(M: int, bands=ROW_BANDS) -> int:
+    """Row-band families (extension, the second form of the few-row families): which family serves a shape of M rows --
+    that of the smallest band holding M, whatever the key's tile height, so that every key is priced from samples of
+    the same matrices; 0 (the paper's near-square samples) above the last band."""
+    for f, rows in enumerate(bands, start=1):
+        if M <= rows:
+            return f
+    return 0
+
+
+def band_sample_set(cap: int, W_row: int, I: int, rows: int, BM: int, S: int = 1) -> list[GridSample]:
+    """Samples of a row-band family under a key of tile height BM: matrices of exactly `rows` rows, i.e.
+    m = ceil(rows/BM) tile rows of which the last may be partial, as wide as the sub-interval allows -- the rule of
+    row_sample_set with that m.  The workload has M = rows (not m*BM), N = n*T_N."""
+    return row_sample_set(cap, W_row, I, ceil_div(rows, BM), S)
 
 
 def instantiate(m: int, n: int, L: int, BM: int, BN: int, BK: int, S: int = 1) -> tuple[int, int, int]:

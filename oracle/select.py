@@ -13,7 +13,7 @@ import numpy as np
 
 from .fit import Bucket, DualTable, KeyDesc
 from .geometry import ceil_div, phi_gemm, phi_grouped, split_fits, uniform_rows, wave_count
-from .sampler import row_family
+from .sampler import band_family, row_family
 
 
 def predict(theta, G: int, L: int) -> float:
@@ -42,6 +42,14 @@ def bucket_for(table: DualTable, key: int, w: int, fam: int = 0):
     return b if b.status else None
 
 
+def family_of(table: DualTable, M: int, BM: int) -> int:
+    """Which few-row family a shape of M rows consults under a key of tile height BM: by its tile-row count (row_mode 0,
+    per key) or by the row band M falls in (row_mode 1, the same for every key); 0 without families."""
+    if table.W_row <= 0:
+        return 0
+    return band_family(M) if table.row_mode == 1 else row_family(ceil_div(M, BM))
+
+
 def nearest_anchor(anchors, L: int):
     """Sec. 4.4 Stage II: anchor minimising |L* - L_i|; equal distances go to the smaller anchor."""
     best = None
@@ -61,7 +69,7 @@ def select(table: DualTable, M: int, N: int, K: int):
             continue     # its partial tiles would not fit the workspace: not a candidate
         G, L = phi_gemm(M, N, K, kd.bm, kd.bn, kd.bk, kd.split)
         w = wave_count(G, kd.cap)
-        b = bucket_for(table, k, w, row_family(ceil_div(M, kd.bm)))
+        b = bucket_for(table, k, w, family_of(table, M, kd.bm))
         if b is None:
             continue
         t = predict(b.theta, G, L)
@@ -111,7 +119,7 @@ def select_grouped(table: DualTable, E: int, M_total: int, N: int, K: int):
         if kd.split != 1:
             continue
         G, L = phi_grouped(rows, N, K, kd.bm, kd.bn, kd.bk)
-        b = bucket_for(table, k, wave_count(G, kd.cap), row_family(ceil_div(rows[0], kd.bm)))
+        b = bucket_for(table, k, wave_count(G, kd.cap), family_of(table, rows[0], kd.bm))
         if b is None:
             continue
         t = predict(b.theta, G, L)
@@ -163,7 +171,7 @@ def select_grouped_rows(table: DualTable, rows, N: int, K: int):
         if kd.split != 1:
             continue
         G, L = phi_grouped(rows, N, K, kd.bm, kd.bn, kd.bk)
-        b = bucket_for(table, k, wave_count(G, kd.cap), row_family(ceil_div(mean_rows, kd.bm)))
+        b = bucket_for(table, k, wave_count(G, kd.cap), family_of(table, mean_rows, kd.bm))
         if b is None:
             continue
         t = predict(b.theta, G, L)
@@ -186,22 +194,22 @@ def read_table(path: str, ws_elems=None, max_split_tiles=None) -> tuple[DualTabl
     """Parse the flat little-endian dual-table file.  ws_elems / max_split_tiles: the split-K feasibility
     limits of the library that will run the table's keys (they are not in the file; None = unlimited).
 
-    Header, 16 uint32: magic 'WTDT', version (1, 2 or 3), n_keys, W, I, p, tau_num, tau_den, n_cu,
+    Header, 16 uint32: magic 'WTDT', version (1 to 4), n_keys, W, I, p, tau_num, tau_den, n_cu,
     A (anchor slots per bucket), in_type, out_type, key_mode, W_row (version >= 2, else 0), number of
-    few-row families (version 3; version 2 has one), the least-squares objective the buckets were fitted with
+    few-row families (versions 3 and 4; version 2 has one; version 4: row-band families, row_mode 1), the least-squares objective the buckets were fitted with
     (0 absolute, 1 relative; informational, returned in the meta dict).
     Then per key: 8 int32 (bm, bn, bk, nwave, stages, occ, n_micro, split [0 = 1]), int64 cap, and a
     bucket block of R = W+1 rows (w = 1..W, then ext): R*4 float64 theta, R int32 status, R int32
-    n_anchor, R*A int32 anchor L, R*A int32 anchor micro.  Versions 2 / 3 append, per key, one further
+    n_anchor, R*A int32 anchor L, R*A int32 anchor micro.  Versions 2 to 4 append, per key, one further
     block of W_row+1 rows for every few-row family.
     """
     raw = open(path, "rb").read()
     hdr = struct.unpack_from("<4s15I", raw, 0)
-    if hdr[0] != MAGIC or hdr[1] not in (1, 2, 3):
-        raise ValueError("not a version-1/2/3 dual table")
+    if hdr[0] != MAGIC or hdr[1] not in (1, 2, 3, 4):
+        raise ValueError("not a version-1..4 dual table")
     n_keys, W, I, p, tnum, tden, n_cu, A, in_t, out_t, mode = hdr[2:13]
     W_row = hdr[13] if hdr[1] >= 2 else 0
-    n_fams = 0 if W_row == 0 else (hdr[14] if hdr[1] == 3 else 1)
+    n_fams = 0 if W_row == 0 else (hdr[14] if hdr[1] >= 3 else 1)
     off = 64
 
     def block(R):
@@ -233,6 +241,6 @@ def read_table(path: str, ws_elems=None, max_split_tiles=None) -> tuple[DualTabl
     if off != len(raw):
         raise ValueError("trailing bytes in dual table")
     meta = dict(I=I, p=p, tau_num=tnum, tau_den=tden, n_cu=n_cu, A=A, in_type=in_t, out_type=out_t, key_mode=mode,
-                W_row=W_row, weighting=hdr[15])
+                W_row=W_row, weighting=hdr[15], row_mode=int(hdr[1] == 4))
     return DualTable(W=W, keys=keys, local=local, ext=ext, W_row=W_row, row_local=row_local, row_ext=row_ext,
-                     ws_elems=ws_elems, max_split_tiles=max_split_tiles), meta
+                     row_mode=int(hdr[1] == 4), ws_elems=ws_elems, max_split_tiles=max_split_tiles), meta

@@ -388,6 +388,72 @@ def test_few_row_families_are_chosen_by_tile_rows():
     assert key == bk and abs(t - bt) < 1e-6 * bt
 
 
+def test_row_band_families_are_chosen_by_m_for_every_key_alike():
+    """Row-band families (row_mode 1): family f holds matrices of 16, 32, 64, 128 rows under EVERY key, and a shape
+    consults the family of the smallest band holding its M whatever the key's tile height.  Hand values of the band
+    rule and of the sample sets; then Stage I on a table whose bands have surfaces x3, x2 of the near-square one:
+    every key is priced from the same band, where the tile-row rule would mix families across tile heights."""
+    assert [smp.band_family(M) for M in (0, 1, 16, 17, 32, 33, 64, 65, 128, 129, 5000)] == [1, 1, 1, 2, 2, 3, 3, 4, 4, 0, 0]
+    # 64 rows under a 16-row tile: 4 tile rows; under a 256-row tile: one (partial) tile row.  cap 256, I = 4, wave 1,
+    # sub-intervals end at 64, 128, 192, 256: widest n with 4n <= b is 16, 32, 48, 64
+    s16 = smp.band_sample_set(256, 1, 4, 64, 16)
+    assert [(x.g, x.m, x.n) for x in s16] == [(64, 4, 16), (128, 4, 32), (192, 4, 48), (256, 4, 64)]
+    s256 = smp.band_sample_set(256, 1, 4, 64, 256)
+    assert [(x.g, x.m, x.n) for x in s256] == [(64, 1, 64), (128, 1, 128), (192, 1, 192), (256, 1, 256)]
+    # split in two: task counts are multiples of 2 * m; 17 rows under a 16-row tile are 2 tile rows
+    assert [(x.g, x.m, x.n) for x in smp.band_sample_set(256, 1, 2, 17, 16, S=2)] == [(128, 2, 32), (256, 2, 64)]
+    for rows in smp.ROW_BANDS:
+        for bm in (16, 64, 256):
+            for x in smp.band_sample_set(256, 3, 4, rows, bm):
+                a, b = smp.sub_interval(x.w, x.i, 256, 4)
+                m = geo.ceil_div(rows, bm)
+                assert x.g == 0 or (x.m == m and a <= x.g <= b and x.g == m * x.n and m * (x.n + 1) > b)
+
+    W, W_row, I = 6, 2, 4
+    near = _make_samples(W, I, _penalty)
+    slow = {1: 3.0, 2: 2.0}
+    extra = []
+    for f in (1, 2):
+        for k, kd in enumerate(KEYS):
+            for x in smp.band_sample_set(kd.cap, W_row, I, smp.ROW_BANDS[f - 1], kd.bm):
+                if x.g == 0:
+                    continue
+                for L in smp.loop_anchors(K_ANCHORS, kd.bk):
+                    for mi in range(N_MICRO):
+                        extra.append(ofit.Sample(k, mi, x.g, L, x.w, slow[f] * _latency(k, mi, x.g, L, 6, _penalty), f))
+    table = ofit.fit_tables(near + extra, KEYS, W, p=3, W_row=W_row, row_fams=2, row_mode=1)
+    tiles = ofit.fit_tables(near + extra, KEYS, W, p=3, W_row=W_row, row_fams=2, row_mode=0)
+    assert table.row_mode == 1 and table.row_fams == 2 and tiles.row_mode == 0
+    for M, f in ((1, 1), (16, 1), (17, 2), (32, 2), (33, 3), (200, 0)):
+        for kid, kd in enumerate(KEYS):
+            assert osel.family_of(table, M, kd.bm) == f                 # the same family under every key
+    for kid in range(len(KEYS)):                                        # a band the table lacks: the paper's buckets
+        assert osel.bucket_for(table, kid, 1, 3) is table.local[kid][0]
+        assert osel.bucket_for(table, kid, 1, 2) is table.row_local[1][kid][0]
+    # the tile-row rule on the same M = 30: two tile rows under the 16-row key, one under the 256-row key
+    assert (osel.family_of(tiles, 30, 16), osel.family_of(tiles, 30, 256)) == (2, 1)
+    assert osel.family_of(ofit.fit_tables(near, KEYS, W, p=3), 5, 16) == 0          # no families in the table
+    for (M, N, K) in ((12, 4096, 4096), (30, 4096, 2048), (33, 4096, 4096)):
+        f = smp.band_family(M) if smp.band_family(M) <= 2 else 0
+        cand = []
+        for kid, kd in enumerate(KEYS):
+            G, L = geo.phi_gemm(M, N, K, kd.bm, kd.bn, kd.bk)
+            for mi in range(N_MICRO):
+                cand.append(((kid, mi), slow.get(f, 1.0) * _latency(kid, mi, G, L, W, _penalty)))
+        (bk, _), bt = oex.argmin_config(cand)
+        key, _, t = osel.select(table, M, N, K)
+        assert key == bk and abs(t - bt) < 1e-6 * bt
+    # the grouped selectors take the band of one group's rows (uniform reading) or of the mean group (real counts)
+    kd = KEYS[4]                                     # <16, 64, 128>: 4 groups of 10 rows are 4 x 64 tasks of band 1
+    G, L = geo.phi_grouped([10] * 4, 4096, 4096, kd.bm, kd.bn, kd.bk)
+    b = osel.bucket_for(table, 4, geo.wave_count(G, kd.cap), 1)
+    assert b is table.row_local[0][4][0]
+    got = osel.select_grouped(table, 4, 40, 4096, 4096)
+    assert got == osel.select_grouped_rows(table, [10, 10, 10, 10], 4096, 4096)
+    if got[0] == 4:
+        assert got[2] == osel.predict(b.theta, G, L)
+
+
 def test_thin_anchors_keeps_ends_and_an_even_spread():
     """Buckets with more loop counts than the table holds keep ranks floor(i*(n-1)/7): hand values."""
     a15 = [(L, L % 3) for L in range(10, 25)]
