@@ -87,7 +87,8 @@ typedef struct {
     int32_t key_id, micro_id;
     int64_t G, L;
     int32_t w;
-    int32_t family; /* 0: near-square grid (the paper's sampler); 1, 2, 3: grids of 1, 2, 4 tile rows (wt_grid.W_row) */
+    int32_t family; /* 0: near-square grid (the paper's sampler); 1..: a few-row family of wt_grid.W_row -- grids of 1, 2,
+                     * 4 tile rows (WT_ROWS_TILES) or matrices of 16, 32, 64, 128 rows (WT_ROWS_BAND) */
     double mean_us;
 } wt_sample;
 
@@ -107,14 +108,15 @@ typedef struct {
     int32_t W_split;  /* split-K keys are profiled for waves 1..min(W, W_split) only (0 = all W); beyond their
                        * profiled waves they have no model and wt_select does not consider them */
     int32_t W_row;    /* extension, 0 = off (the paper's method): also profile and fit W_row waves of few-row
-                       * grids -- families 1..row_fams with m_G = 1, 2, 4 tile rows (M = m_G*bm) and, per
-                       * sub-interval, the widest n_G that keeps the task count inside it -- kept in their own
-                       * bucket sets.  wt_select consults family 1 for shapes with ceil(M/bm) = 1, family 2 for
-                       * 2..3 and family 3 for 4..7 tile rows, falling back to the paper's buckets.  The paper's
-                       * sampler stays near-square (tau) and its test shapes have M >= 64; these grids cover
-                       * the serving shapes (few tile rows, very wide) whose B operand streams from HBM with
-                       * little reuse, which near-square samples of the same G do not show. */
-    int32_t row_fams; /* number of few-row families, 1..3 (0 is read as 1); used only when W_row > 0 */
+                       * grids -- families 1..row_fams, each, per sub-interval, with the widest n_G that keeps the
+                       * task count inside it -- kept in their own bucket sets, which wt_select consults for shapes
+                       * of few rows, falling back to the paper's buckets.  What a family holds and which shapes
+                       * consult it is row_mode's (wt_row_mode, below).  The paper's sampler stays near-square (tau)
+                       * and its test shapes have M >= 64; these grids cover the serving shapes (few rows, very
+                       * wide) whose B operand streams from HBM with little reuse, which near-square samples of the
+                       * same G do not show. */
+    int32_t row_fams; /* number of few-row families: 1..3 under WT_ROWS_TILES, 1..4 under WT_ROWS_BAND (0 is read as
+                       * 1); used only when W_row > 0 */
     int32_t skip_near; /* 1: wt_sample_plan / wt_profile_sparse leave out the near-square family (to add few-row
                         * records to an existing set); wt_fit ignores it */
     int32_t n_heads;   /* attention contexts only (must be >= 1 there): head count N_h of the profiled workloads.
@@ -123,6 +125,7 @@ typedef struct {
                         * S_q (Sec. 5.1: 1.0 to 3.0): L = ceil(floor(S_q * pct / 100) / T_KV), S_kv = L * T_KV.
                         * tau, W_row, W_split are unused; max_out_elems caps S_q * N_h * 128. */
     int32_t weighting; /* wt_weighting: what the least squares of wt_fit's bilinear buckets minimise (below) */
+    int32_t row_mode;  /* which grids the few-row families hold when W_row > 0 (wt_row_mode, below) */
 } wt_grid;
 
 /* Objective of the per-bucket least squares (Sec. 4.3 bucket model; Sec. 5.1 "least-squares regression").
@@ -133,6 +136,15 @@ typedef struct {
  *                    leaving short-K predictions off by their own size (even negative).  Every record must then have
  *                    mean_us > 0 (WT_ERR_INVALID_ARG otherwise).  The Step ablation is always fitted absolutely. */
 typedef enum { WT_FIT_ABSOLUTE = 0, WT_FIT_RELATIVE = 1 } wt_weighting;
+
+/* What the few-row families of wt_grid.W_row hold (extension; the paper's sampler has no such grids).
+ *   WT_ROWS_TILES  families 1..3 are grids of 1, 2, 4 full tile rows of the key at hand (M = m_G * bm), and a shape
+ *                  consults, per key, the family of its own tile-row count.  Keys of different tile heights are then
+ *                  priced from different matrices.
+ *   WT_ROWS_BAND   families 1..4 are grids of exactly 16, 32, 64, 128 rows under EVERY key (ceil(rows/bm) tile rows,
+ *                  the last one partial), and a shape with M <= 128 consults the family of the smallest band that
+ *                  holds M under every key alike, so that Stage I compares predictions made from the same matrices. */
+typedef enum { WT_ROWS_TILES = 0, WT_ROWS_BAND = 1 } wt_row_mode;
 
 /* Latency models wt_fit can build into the dual table.  WAVE_BILINEAR is the method (Sec. 4.3);
  * the other two are its ablations (Sec. 5.4) expressed in the same table form:

@@ -57,7 +57,7 @@ class wt_grid(C.Structure):
                 ("warmup", C.c_int32), ("iters", C.c_int32), ("key_first", C.c_int32),
                 ("key_count", C.c_int32), ("max_out_elems", C.c_int64), ("model", C.c_int32),
                 ("W_split", C.c_int32), ("W_row", C.c_int32), ("row_fams", C.c_int32), ("skip_near", C.c_int32),
-                ("n_heads", C.c_int32), ("weighting", C.c_int32)]
+                ("n_heads", C.c_int32), ("weighting", C.c_int32), ("row_mode", C.c_int32)]
 
 
 class WtError(RuntimeError):
@@ -166,10 +166,10 @@ def _stream(stream):
 
 def make_grid(W=40, I=4, tau=(11, 10), p=10, k_anchors=(1024, 2048, 3072, 4096, 5120), warmup=3, iters=5,
               key_first=0, key_count=0, max_out_elems=0, model=0, W_row=0, W_split=0, row_fams=0, skip_near=0,
-              n_heads=0, weighting=0):
+              n_heads=0, weighting=0, row_mode=0):
     arr = (C.c_int32 * len(k_anchors))(*k_anchors)
     g = wt_grid(W, I, tau[0], tau[1], p, len(k_anchors), C.cast(arr, C.POINTER(C.c_int32)), warmup, iters,
-                key_first, key_count, max_out_elems, model, W_split, W_row, row_fams, skip_near, n_heads, weighting)
+                key_first, key_count, max_out_elems, model, W_split, W_row, row_fams, skip_near, n_heads, weighting, row_mode)
     g._keep = arr  # keep the anchor array alive with the struct
     return g
 

@@ -239,7 +239,8 @@ bool key_in_slice(const wt_grid* g, int k, int nk) {
 
 int check_grid(const wt_grid* g) {
     if (!g || g->W < 1 || g->W > kMaxWaves || g->I < 1 || g->I > kMaxSubIntervals || g->W_row > kMaxWaves || g->tau_den < 1 || g->tau_num < g->tau_den || g->p < 1 || g->n_k_anchors < 1 ||
-        !g->k_anchors || g->warmup < 0 || g->iters < 1 || g->W_row < 0 || g->W_split < 0 || g->row_fams < 0 || g->row_fams > kMaxRowFams)
+        !g->k_anchors || g->warmup < 0 || g->iters < 1 || g->W_row < 0 || g->W_split < 0 || g->row_fams < 0 ||
+        (g->row_mode != WT_ROWS_TILES && g->row_mode != WT_ROWS_BAND) || g->row_fams > (g->row_mode == WT_ROWS_BAND ? 4 : 3))
         return WT_ERR_INVALID_ARG;
     for (int j = 0; j < g->n_k_anchors; ++j)
         if (g->k_anchors[j] < 1) return WT_ERR_INVALID_ARG;
@@ -306,7 +307,10 @@ int walk_plan(const wt_ctx* ctx, const wt_grid* grid, F&& fn) {
         const int n_fams = grid->W_row > 0 ? (grid->row_fams > 0 ? grid->row_fams : 1) : 0;
         const int W_row = (key.split > 1 && grid->W_split > 0) ? std::min(grid->W_row, grid->W_split) : grid->W_row;
         for (int fam = 1; fam <= n_fams; ++fam) {
-            const int64_t m = int64_t{1} << (fam - 1);
+            // tile-row families: m = 1, 2, 4 full tile rows; row-band families: 16, 32, 64, 128 rows whatever the
+            // key's tile height, so that every key of a band is profiled on the same matrices
+            const int64_t band_rows = int64_t{kRowBand0} << (fam - 1);
+            const int64_t m = grid->row_mode == WT_ROWS_BAND ? ceil_div64(band_rows, key.bm) : int64_t{1} << (fam - 1);
             for (int w = 1; w <= W_row; ++w) {
                 for (int i = 1; i <= grid->I; ++i) {
                     const int64_t lo = (int64_t)(w - 1) * key.cap + 1;
@@ -315,7 +319,7 @@ int walk_plan(const wt_ctx* ctx, const wt_grid* grid, F&& fn) {
                     const int64_t n = b / (m * key.split);
                     const GridPoint pt{n * m * key.split, m, n};
                     if (n < 1 || pt.g < a) continue;
-                    const int64_t M = m * key.bm, N = n * key.bn;
+                    const int64_t M = grid->row_mode == WT_ROWS_BAND ? band_rows : m * key.bm, N = n * key.bn;
                     if (grid->max_out_elems > 0 && M * N > grid->max_out_elems) continue;
                     if (!key_fits(key, m * n)) continue;
                     for (int64_t L : anchors) {

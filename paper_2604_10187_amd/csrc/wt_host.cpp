@@ -483,7 +483,9 @@ static int fit_table(wt_ctx* ctx, const wt_grid* grid, const wt_sample* s, size_
     int rc = fit_family(ctx, 0, grid->model, W, grid->p, relative, s, n, t.buckets);
     if (rc != WT_OK) return rc;
     if (grid->W_row > 0) {  // the few-row families always use the wave-bucketed bilinear model
-        if (grid->row_fams < 0 || grid->row_fams > kMaxRowFams) return WT_ERR_INVALID_ARG;
+        if (grid->row_mode != WT_ROWS_TILES && grid->row_mode != WT_ROWS_BAND) return WT_ERR_INVALID_ARG;
+        if (grid->row_fams < 0 || grid->row_fams > (grid->row_mode == WT_ROWS_BAND ? 4 : 3)) return WT_ERR_INVALID_ARG;
+        t.row_mode = grid->row_mode;
         t.W_row = grid->W_row;
         t.row_fams = grid->row_fams > 0 ? grid->row_fams : 1;
         for (int f = 1; f <= t.row_fams; ++f) {
@@ -497,8 +499,10 @@ static int fit_table(wt_ctx* ctx, const wt_grid* grid, const wt_sample* s, size_
 }
 
 // ---- two-stage selection (Sec. 4.4, 4.5) -------------------------------------------------------
-static inline const Bucket* pick_bucket(const Table& t, int key, int64_t w, int64_t tile_rows) {
-    const int fam = t.W_row > 0 ? row_family(tile_rows) : 0;
+// rows: the shape's row count M (one group's rows for a grouped launch).  Tile-row families are consulted per key by
+// ceil(rows/bm); row-band families by the band rows falls in, the same under every key.
+static inline const Bucket* pick_bucket(const Table& t, int key, int bm, int64_t w, int64_t rows) {
+    const int fam = t.W_row <= 0 ? 0 : t.row_mode == WT_ROWS_BAND ? band_family(rows) : row_family(ceil_div64(rows, bm));
     if (fam >= 1 && fam <= t.row_fams) {  // few tile rows: that family's buckets first, the paper's as fallback
         const Bucket* rb = &t.row_buckets[fam - 1][static_cast<size_t>(key) * (t.W_row + 1)];
         if (w >= 1 && w <= t.W_row && rb[w - 1].status) return &rb[w - 1];
@@ -532,8 +536,8 @@ static inline bool product_fits(int64_t a, int64_t b, int64_t c) {
 // Every shape the selectors price must keep G*L inside int64 for every key: tiles <= M*N, at most 16 splits, L <= K.
 static inline bool shape_fits(int64_t M, int64_t N, int64_t K) { return product_fits(M, N, K < 16 ? 16 : K); }
 
-// The two stages over a pricing rule: phi(k, key, &G, &L, &tile_rows) says whether key k is a candidate and, if so,
-// gives its <G, L> and the tile-row count that names its few-row family.  Stage I: strict '<', so ties keep the
+// The two stages over a pricing rule: phi(k, key, &G, &L, &rows) says whether key k is a candidate and, if so,
+// gives its <G, L> and the row count that names its few-row family.  Stage I: strict '<', so ties keep the
 // lowest key id.  Stage II: nearest loop anchor of the chosen bucket.
 template <class Phi>
 static int select_by(const wt_ctx* ctx, Phi&& phi, int* key_out, int* micro_out, double* t_out) {
@@ -545,10 +549,10 @@ static int select_by(const wt_ctx* ctx, Phi&& phi, int* key_out, int* micro_out,
     int64_t best_L = 0;
     for (int k = 0; k < nk; ++k) {
         const Key& key = ctx->keys[k];
-        int64_t G, L, tile_rows;
-        if (!phi(k, key, &G, &L, &tile_rows)) continue;
+        int64_t G, L, rows;
+        if (!phi(k, key, &G, &L, &rows)) continue;
         const int64_t w = (G + key.cap - 1) / key.cap;
-        const Bucket* b = pick_bucket(t, k, w, tile_rows);
+        const Bucket* b = pick_bucket(t, k, key.bm, w, rows);
         if (!b) continue;
         const double th = predict(b->th, G, L);
         if (th != th) continue;
@@ -583,7 +587,7 @@ static int select_by(const wt_ctx* ctx, Phi&& phi, int* key_out, int* micro_out,
 static int select_impl(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, int groups, int* key_out, int* micro_out,
                        double* t_out) {
     const int64_t Mg = groups > 0 ? ceil_div64(M, groups) : M;
-    return select_by(ctx, [&](int, const Key& key, int64_t* G, int64_t* L, int64_t* tile_rows) {
+    return select_by(ctx, [&](int, const Key& key, int64_t* G, int64_t* L, int64_t* rows) {
         int64_t tiles;
         key_phi(key, Mg, N, K, &tiles, G, L);
         if (groups > 0) {
@@ -592,27 +596,27 @@ static int select_impl(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, int g
         } else if (!key_fits(key, tiles)) {
             return false;
         }
-        *tile_rows = (Mg + key.bm - 1) >> key.sh_m;
+        *rows = Mg;
         return true;
     }, key_out, micro_out, t_out);
 }
 
 // Grouped GEMM with the real per-group row counts: G of Table 2's grouped row summed over the groups; the few-row
 // family is that of the mean group, ceil(sum / groups) rows (the uniform reading when the groups are equal).
-static int select_rows_impl(const wt_ctx* ctx, int groups, const int64_t* rows, int64_t N, int64_t K, int* key_out,
-                            int* micro_out) {
+static int select_rows_impl(const wt_ctx* ctx, int groups, const int64_t* group_rows, int64_t N, int64_t K,
+                            int* key_out, int* micro_out) {
     int64_t total = 0;
-    for (int e = 0; e < groups; ++e) total += rows[e];
+    for (int e = 0; e < groups; ++e) total += group_rows[e];
     const int64_t mean_rows = ceil_div64(total, groups);
-    return select_by(ctx, [&](int, const Key& key, int64_t* G, int64_t* L, int64_t* tile_rows) {
+    return select_by(ctx, [&](int, const Key& key, int64_t* G, int64_t* L, int64_t* rows) {
         if (key.split != 1) return false;
         int64_t g = 0, tiles, ge;
         for (int e = 0; e < groups; ++e) {
-            key_phi(key, rows[e], N, K, &tiles, &ge, L);
+            key_phi(key, group_rows[e], N, K, &tiles, &ge, L);
             g += ge;
         }
         *G = g;
-        *tile_rows = (mean_rows + key.bm - 1) >> key.sh_m;
+        *rows = mean_rows;
         return true;
     }, key_out, micro_out, nullptr);
 }
@@ -622,7 +626,7 @@ static int select_rows_impl(const wt_ctx* ctx, int groups, const int64_t* rows, 
 // iterations to within rounding.  No block at all: G = L = 0.
 static int select_varlen_impl(const wt_ctx* ctx, int batch, const int64_t* len_q, const int64_t* len_kv,
                               int64_t n_heads, int* key_out, int* micro_out) {
-    return select_by(ctx, [&](int, const Key& key, int64_t* G, int64_t* L, int64_t* tile_rows) {
+    return select_by(ctx, [&](int, const Key& key, int64_t* G, int64_t* L, int64_t* rows) {
         int64_t t = 0, iters = 0;
         for (int b = 0; b < batch; ++b) {
             const int64_t tiles = (len_q[b] + key.bm - 1) >> key.sh_m;
@@ -632,18 +636,18 @@ static int select_varlen_impl(const wt_ctx* ctx, int batch, const int64_t* len_q
         }
         *G = n_heads * t;
         *L = t ? (2 * iters + t) / (2 * t) : 0;
-        *tile_rows = 0;  // attention tables carry no few-row families
+        *rows = 0;  // attention tables carry no few-row families
         return true;
     }, key_out, micro_out, nullptr);
 }
 
 // ---- table file ------------------------------------------------------------------------------------
 // Little-endian.  Header: 16 uint32 = 'WTDT', version (1; 2 with the single-tile-row family; 3 with several
-// few-row families), n_keys, W, I, p, tau_num, tau_den, n_cu, anchor slots A, in_type, out_type, key_mode
-// (capacity mode), W_row (version >= 2), row_fams (version 3), 1 reserved.  Per key: 8 int32 (bm, bn, bk, nwave, stages, occ,
+// tile-row families; 4 with row-band families), n_keys, W, I, p, tau_num, tau_den, n_cu, anchor slots A, in_type, out_type, key_mode
+// (capacity mode), W_row (version >= 2), row_fams (versions 3, 4), fit objective.  Per key: 8 int32 (bm, bn, bk, nwave, stages, occ,
 // n_micro, split [0 in older files = 1]), int64 cap (256, or 256*occ when key_mode = 0), then a bucket block of R = W+1 rows
 // (w = 1..W then ext): R*4 float64 theta, R int32 status, R int32 n_anchor, R*A int32 anchor L,
-// R*A int32 anchor micro; versions 2 / 3 append one block of W_row+1 rows per few-row family.
+// R*A int32 anchor micro; versions 2 to 4 append one block of W_row+1 rows per few-row family.
 static const uint32_t kMagic = 0x54445457u;  // "WTDT"
 
 static bool write_block(FILE* f, const Bucket* b, int R) {
@@ -673,7 +677,7 @@ static int save_table(const wt_ctx* ctx, const char* path) {
     FILE* f = fopen(path, "wb");
     if (!f) return WT_ERR_IO;
     const uint32_t nk = static_cast<uint32_t>(ctx->keys.size());
-    const uint32_t hdr[16] = {kMagic, t.W_row > 0 ? (t.row_fams > 1 ? 3u : 2u) : 1u, nk, static_cast<uint32_t>(t.W), static_cast<uint32_t>(t.I),
+    const uint32_t hdr[16] = {kMagic, t.W_row > 0 ? (t.row_mode == WT_ROWS_BAND ? 4u : t.row_fams > 1 ? 3u : 2u) : 1u, nk, static_cast<uint32_t>(t.W), static_cast<uint32_t>(t.I),
                               static_cast<uint32_t>(t.p), static_cast<uint32_t>(t.tau_num),
                               static_cast<uint32_t>(t.tau_den), static_cast<uint32_t>(kNumCU),
                               static_cast<uint32_t>(kMaxAnchors), static_cast<uint32_t>(ctx->in_type),
@@ -701,10 +705,11 @@ static int load_table(wt_ctx* ctx, const char* path) {
     int rc = WT_OK;
     Table t;
     std::vector<int> occs;
-    if (fread(hdr, sizeof(hdr), 1, f) != 1 || hdr[0] != kMagic || hdr[1] < 1u || hdr[1] > 3u) rc = WT_ERR_IO;
+    if (fread(hdr, sizeof(hdr), 1, f) != 1 || hdr[0] != kMagic || hdr[1] < 1u || hdr[1] > 4u) rc = WT_ERR_IO;
     if (rc == WT_OK && hdr[1] == 1u) hdr[13] = 0;
-    if (rc == WT_OK) hdr[14] = hdr[13] == 0 ? 0u : (hdr[1] == 3u ? hdr[14] : 1u);
-    if (rc == WT_OK && hdr[14] > static_cast<uint32_t>(kMaxRowFams)) rc = WT_ERR_INVALID_ARG;
+    if (rc == WT_OK) hdr[14] = hdr[13] == 0 ? 0u : (hdr[1] >= 3u ? hdr[14] : 1u);
+    if (rc == WT_OK && hdr[14] > (hdr[1] == 4u ? 4u : 3u)) rc = WT_ERR_INVALID_ARG;
+    if (rc == WT_OK && hdr[1] == 4u && hdr[14] == 0) rc = WT_ERR_INVALID_ARG;  // version 4 means row-band families are present
     if (rc == WT_OK && hdr[13] > static_cast<uint32_t>(kMaxWaves)) rc = WT_ERR_INVALID_ARG;
     if (rc == WT_OK && (hdr[2] != ctx->keys.size() || hdr[9] != static_cast<uint32_t>(kMaxAnchors) ||
                         hdr[8] != static_cast<uint32_t>(kNumCU) || hdr[10] != static_cast<uint32_t>(ctx->in_type) ||
@@ -718,6 +723,7 @@ static int load_table(wt_ctx* ctx, const char* path) {
         t.W_row = static_cast<int>(hdr[13]);
         t.weighting = static_cast<int>(hdr[15]);
         t.row_fams = static_cast<int>(hdr[14]);
+        t.row_mode = hdr[1] == 4u ? WT_ROWS_BAND : WT_ROWS_TILES;
         t.buckets.assign(ctx->keys.size() * R, Bucket{});
         for (int fam = 0; fam < t.row_fams; ++fam) t.row_buckets[fam].assign(ctx->keys.size() * (t.W_row + 1), Bucket{});
         for (size_t k = 0; rc == WT_OK && k < ctx->keys.size(); ++k) {
@@ -976,7 +982,7 @@ int wt_predict_us(const wt_ctx* ctx, int64_t M, int64_t N, int64_t K, wt_cfg cfg
     int64_t tiles, G, L;
     key_phi(k, M, N, K, &tiles, &G, &L);
     if (!key_fits(k, tiles)) return WT_ERR_INFEASIBLE;
-    const Bucket* b = pick_bucket(ctx->table, kid, ceil_div64(G, k.cap), ceil_div64(M, k.bm));
+    const Bucket* b = pick_bucket(ctx->table, kid, k.bm, ceil_div64(G, k.cap), M);
     if (!b) return WT_ERR_NOT_FITTED;
     *us = predict(b->th, G, L);
     return WT_OK;

@@ -18,9 +18,16 @@ constexpr int kNumSwizzle = 3;         // micro parameter values 0..2
 constexpr int kMaxAnchors = WT_MAX_ANCHORS;  // loop anchors stored per bucket
 constexpr int kMaxWaves = 4096;         // largest W (and W_row) of a table or a sample grid
 constexpr int kMaxSubIntervals = 4096;  // largest I of a sample grid
-constexpr int kMaxRowFams = 3;         // few-row sample families: 1, 2 and 4 tile rows
+constexpr int kMaxRowFams = 4;         // few-row sample families: 1, 2, 4 tile rows (three), or 16, 32, 64, 128 rows (four)
+constexpr int kRowBand0 = 16;          // rows of the first row-band family; each further family doubles them
 // Family consulted for a shape with `rows` = ceil(M/bm) tile rows: 1 -> 1, 2..3 -> 2, 4..7 -> 3, else 0.
 inline int row_family(int64_t rows) { return rows <= 1 ? 1 : rows <= 3 ? 2 : rows <= 7 ? 3 : 0; }
+// Row-band families: the family of the smallest band (16, 32, 64, 128 rows) that holds M; 0 above the last band.
+inline int band_family(int64_t M) {
+    for (int f = 1; f <= 4; ++f)
+        if (M <= (int64_t{kRowBand0} << (f - 1))) return f;
+    return 0;
+}
 // Split-K workspace owned by a context: fp32 partial tiles and one arrival counter per output tile.
 constexpr int64_t kWsElems = WT_SPLITK_WS_FLOATS;        // 256 MiB of floats
 constexpr int64_t kMaxSplitTiles = WT_SPLITK_MAX_TILES;  // arrival counters
@@ -60,13 +67,14 @@ struct Table {
     bool fitted = false;
     int W = 0, I = 0, p = 0, tau_num = 11, tau_den = 10;
     int weighting = 0;   // wt_weighting the buckets were fitted with (recorded in the table file; lookups do not use it)
+    int row_mode = 0;    // wt_row_mode of the few-row families (meaningful when W_row > 0)
     // buckets[key * (W + 1) + (w - 1)] for w = 1..W; index W is the extrapolation entry
     std::vector<Bucket> buckets;
     // few-row families (extension) f = 1..row_fams, grids of 1, 2, 4 tile rows:
     // row_buckets[f - 1][key * (W_row + 1) + (w - 1)], last = extrapolation
     int W_row = 0;
     int row_fams = 0;
-    std::vector<Bucket> row_buckets[3];
+    std::vector<Bucket> row_buckets[kMaxRowFams];
 };
 
 }  // namespace wt

@@ -35,6 +35,11 @@ W_LONG = 12
 # that take three.  With anchors from 256 to 28672 a bucket's latencies span two orders of magnitude, so the shipped
 # tables are fitted with relative residuals (`--weighting 1`, WT_FIT_RELATIVE).
 K_ANCHORS_SHORT = (256, 512)
+# Fourth pass of the shipped bf16 table: the 16-row family (`--W-row 8 --row-fams 1 --row-mode 1 --skip-near` with all
+# ten anchors above): matrices of exactly 16 rows under every key, eight waves wide.  Shapes with M <= 16 have one tile
+# row under every key, their B operand streams from HBM once, and near-square samples of the same G price them 2-3
+# times too fast and rank the keys by noise; the family prices every key from the same skinny matrices.
+K_ANCHORS_ALL = K_ANCHORS_SHORT + K_ANCHORS + K_ANCHORS_LONG
 # Attention contexts: KV-length multipliers of S_q in percent (Sec. 5.1: 1.0 to 3.0).
 KV_MULTIPLIERS = (100, 150, 200, 250, 300)
 
@@ -66,7 +71,7 @@ def profile(ctx, grid, in_type, out_type, log=print, chunk_keys=1):
                          k_anchors=[grid.k_anchors[j] for j in range(grid.n_k_anchors)], warmup=grid.warmup,
                          iters=grid.iters, key_first=k0, key_count=kc, max_out_elems=grid.max_out_elems, model=grid.model, W_row=grid.W_row,
                          W_split=grid.W_split, row_fams=grid.row_fams, skip_near=grid.skip_near, n_heads=grid.n_heads,
-                         weighting=grid.weighting)
+                         weighting=grid.weighting, row_mode=grid.row_mode)
         recs = wt.wt_profile_sparse(ctx, g, scrA, scrB, scrC, stream=torch.cuda.current_stream())
         out.append(recs)
         log(f"[tune] keys {k0}..{k0 + kc - 1}: {len(recs)} records, {time.time() - t0:.0f}s elapsed")
@@ -93,6 +98,7 @@ def main(argv=None):
     ap.add_argument("--model", type=int, default=0, help="0 wave-bilinear, 1 linear, 2 step")
     ap.add_argument("--W-row", type=int, default=0, help="extension: waves of single-tile-row grids to profile/fit (0 = off)")
     ap.add_argument("--row-fams", type=int, default=1, help="extension: few-row families to profile/fit when --W-row > 0 (1..3: 1, 2, 4 tile rows)")
+    ap.add_argument("--row-mode", type=int, default=0, help="few-row families: 0 grids of 1/2/4 tile rows, 1 grids of 16/32/64/128 rows under every key")
     ap.add_argument("--skip-near", action="store_true", help="profile only the few-row families (records are merged by --fit-from)")
     ap.add_argument("--weighting", type=int, default=0,
                     help="objective of the bucket fits: 0 ordinary least squares (the paper as written), 1 relative residuals")
@@ -110,7 +116,7 @@ def main(argv=None):
     grid = wt.make_grid(W=a.W, I=a.I, p=a.p, k_anchors=a.k_anchors, warmup=a.warmup, iters=a.iters,
                         key_first=a.key_first, key_count=a.key_count, max_out_elems=a.max_out_elems, model=a.model, W_row=a.W_row,
                         W_split=a.W_split, row_fams=a.row_fams, skip_near=int(a.skip_near),
-                        n_heads=a.n_heads[0] if attn else 0, weighting=a.weighting)
+                        n_heads=a.n_heads[0] if attn else 0, weighting=a.weighting, row_mode=a.row_mode)
     if a.fit_from is not None:
         recs = np.concatenate([np.load(f) for f in a.fit_from])
         occ_files = [f.replace(".npy", ".occ.npy") for f in a.fit_from]

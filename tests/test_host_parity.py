@@ -499,20 +499,22 @@ def test_occupancy_aware_capacity_mode(tmp_path):
         wt.wt_destroy(c)
 
 
-@pytest.mark.parametrize("row_fams", [1, 3])
-def test_few_row_families_parity(ctx, tmp_path, row_fams):
-    """Extension: records of 1-, 2- and 4-row grids (families 1..3) build further bucket sets; table, file
-    (version 2 with one family, 3 with several) and lookups match the oracle exactly."""
+@pytest.mark.parametrize("row_fams,row_mode", [(1, 0), (3, 0), (1, 1), (4, 1)])
+def test_few_row_families_parity(ctx, tmp_path, row_fams, row_mode):
+    """Extension: records of 1-, 2- and 4-tile-row grids (row_mode 0, families 1..3) or of 16-, 32-, 64- and 128-row
+    matrices (row_mode 1, families 1..4) build further bucket sets; table, file (version 2 with one tile-row family,
+    3 with several, 4 with row-band families) and lookups match the oracle exactly."""
     W, W_row, I, p = 8, 3, 4, 4
     keys = _keys(ctx)
     near = _synthetic_samples(keys, W, I, noise_seed=11)
     rows = []
     for f in range(1, row_fams + 1):
-        m = 1 << (f - 1)
         for k, kd in enumerate(keys):
             th = wt_synth.random_theta(900 + 7 * f + k, W_row)
             Wk = W_row if kd.split == 1 else min(W_row, W_SPLIT)
-            for s in smp.row_sample_set(kd.cap, Wk, I, m, kd.split):
+            fam_set = (smp.band_sample_set(kd.cap, Wk, I, smp.ROW_BANDS[f - 1], kd.bm, kd.split) if row_mode else
+                       smp.row_sample_set(kd.cap, Wk, I, 1 << (f - 1), kd.split))
+            for s in fam_set:
                 if s.g == 0 or not geo.split_fits(s.m * kd.bm, s.n * kd.bn, kd.bm, kd.bn, kd.split, SPLIT_LIMITS["ws_elems"], SPLIT_LIMITS["max_split_tiles"]):
                     continue
                 for L in smp.loop_anchors(K_ANCHORS, kd.bk, kd.split):
@@ -521,15 +523,16 @@ def test_few_row_families_parity(ctx, tmp_path, row_fams):
                         t = (4.0 / (f + 1)) * (kd.bn * kd.bk / 8192.0) * (a * s.g * L + b * s.g) + c * L + d
                         rows.append((k, micro, s.g, L, s.w, f, t * (1.0 + 0.02 * ((micro + k) % 3))))
     samples = np.concatenate([near, np.array(rows, dtype=wt.SAMPLE_DTYPE)])
-    grid = wt.make_grid(W=W, I=I, p=p, k_anchors=K_ANCHORS, W_row=W_row, row_fams=row_fams, W_split=W_SPLIT)
+    grid = wt.make_grid(W=W, I=I, p=p, k_anchors=K_ANCHORS, W_row=W_row, row_fams=row_fams, W_split=W_SPLIT, row_mode=row_mode)
     wt.wt_fit(ctx, grid, samples)
     path = str(tmp_path / "row.wt")
     wt.wt_save(ctx, path)
     table, meta = osel.read_table(path, **SPLIT_LIMITS)
-    assert meta["W_row"] == W_row and table.W_row == W_row and table.row_fams == row_fams
+    assert meta["W_row"] == W_row and table.W_row == W_row and table.row_fams == row_fams and table.row_mode == row_mode
+    assert open(path, "rb").read()[4] == (4 if row_mode else 3 if row_fams > 1 else 2)          # the version word
     want = ofit.fit_tables([(int(r["key_id"]), int(r["micro_id"]), int(r["G"]), int(r["L"]), int(r["w"]),
                              float(r["mean_us"]), int(r["family"])) for r in samples], keys, W, p, W_row=W_row,
-                           row_fams=row_fams, max_anchors=MAX_ANCHORS)
+                           row_fams=row_fams, max_anchors=MAX_ANCHORS, row_mode=row_mode)
     for k in range(len(keys)):
         pairs = list(zip(table.local[k], want.local[k])) + [(table.ext[k], want.ext[k])]
         for f in range(row_fams):
@@ -541,10 +544,10 @@ def test_few_row_families_parity(ctx, tmp_path, row_fams):
                 _pred_close(got_b.theta, want_b.theta, keys[k])
     ctx2 = wt.wt_create(-1, wt.WT_BF16, wt.WT_OUT_F32)
     wt.wt_load(ctx2, path)
-    used = [0, 0, 0, 0]
+    used = [0, 0, 0, 0, 0]
     for (M, N, K) in wt_synth.sweep_shapes() + wt_synth.stream_shapes(2000):
         key, micro, t = osel.select(table, M, N, K)
-        used[smp.row_family(geo.ceil_div(M, keys[key].bm))] += 1
+        used[osel.family_of(table, M, keys[key].bm)] += 1
         for cc in (ctx, ctx2):
             c = wt.wt_select(cc, M, N, K)
             assert c.id == 3 * key + micro and wt.wt_predict_us(cc, M, N, K, c) == t
@@ -553,6 +556,21 @@ def test_few_row_families_parity(ctx, tmp_path, row_fams):
     n_near, *_ = wt.wt_sample_plan(ctx, wt.make_grid(W=W, I=I, p=p, k_anchors=K_ANCHORS, W_split=W_SPLIT))
     n_both, *_ = wt.wt_sample_plan(ctx, grid)
     assert n_both - n_near == len(rows)          # the plan adds exactly the few-row workloads
+    if row_mode:
+        # a band's workloads have exactly the band's rows (the last tile row partial), not full tile rows: with the
+        # near-square grids left out, the A operand of the 16-row family never exceeds 16 rows of the longest K
+        only = wt.make_grid(W=W, I=I, p=p, k_anchors=K_ANCHORS, W_row=W_row, row_fams=1, W_split=W_SPLIT, row_mode=1, skip_near=1)
+        _, bytesA, _, _ = wt.wt_sample_plan(ctx, only)
+        k_max = max(geo.ceil_div(max(K_ANCHORS), kd.bk * kd.split) * kd.bk * kd.split for kd in keys)
+        assert bytesA == 16 * k_max * 2
+    for bad in (dict(row_mode=2), dict(row_mode=0, row_fams=4), dict(row_mode=1, row_fams=5)):
+        kw = dict(W=W, I=I, p=p, k_anchors=K_ANCHORS, W_row=W_row, row_fams=1, W_split=W_SPLIT)
+        kw.update(bad)
+        with pytest.raises(wt.WtError) as e:
+            wt.wt_fit(ctx, wt.make_grid(**kw), samples)
+        assert e.value.status == wt.WT_ERR_INVALID_ARG
+        with pytest.raises(wt.WtError):
+            wt.wt_sample_plan(ctx, wt.make_grid(**kw))
 
 
 @pytest.mark.parametrize("tiles", [(1, 1), (1, 61), (3, 80), (5, 29), (7, 8), (16, 43), (38, 12), (64, 32), (9, 9)])

@@ -71,14 +71,37 @@ def test_shipped_tables_are_the_oracles_fit_of_the_shipped_records(in_type, stem
     samples = [(int(r["key_id"]), int(r["micro_id"]), int(r["G"]), int(r["L"]), int(r["w"]), float(r["mean_us"]),
                 int(r["family"])) for r in recs]
     mine = ofit.fit_tables(samples, table.keys, table.W, meta["p"], max_anchors=MAX_ANCHORS,
-                           relative=bool(meta["weighting"]))      # the objective the file says it was fitted with
+                           relative=bool(meta["weighting"]),      # the objective the file says it was fitted with
+                           W_row=table.W_row, row_fams=max(table.row_fams, 1), row_mode=table.row_mode)
+    assert (mine.W_row, mine.row_fams, mine.row_mode) == (table.W_row, table.row_fams, table.row_mode)
     n_fitted = 0
+
+    def same(a, b, where):
+        nonlocal n_fitted
+        assert a.status == b.status and a.anchors == b.anchors, where
+        n_fitted += a.status != 0
+        for x, y in zip(a.theta, b.theta):
+            assert abs(x - y) <= 1e-8 * max(abs(x), abs(y)) + 1e-12, (where, a.theta, b.theta)
+
     for k in range(len(table.keys)):
         for w in range(table.W + 1):
-            a = table.local[k][w] if w < table.W else table.ext[k]
-            b = mine.local[k][w] if w < table.W else mine.ext[k]
-            assert a.status == b.status and a.anchors == b.anchors, (k, w)
-            n_fitted += a.status != 0
-            for x, y in zip(a.theta, b.theta):
-                assert abs(x - y) <= 1e-8 * max(abs(x), abs(y)) + 1e-12, (k, w, a.theta, b.theta)
-    assert n_fitted >= len(table.keys)
+            same(table.local[k][w] if w < table.W else table.ext[k], mine.local[k][w] if w < table.W else mine.ext[k], (k, w))
+        for f in range(table.row_fams):         # the few-row families, where the table has them
+            for w in range(table.W_row + 1):
+                same(table.row_local[f][k][w] if w < table.W_row else table.row_ext[f][k],
+                     mine.row_local[f][k][w] if w < table.W_row else mine.row_ext[f][k], (f + 1, k, w))
+    assert n_fitted >= len(table.keys) * (1 + table.row_fams)
+
+
+def test_shipped_bf16_table_serves_the_decode_regime_from_its_16_row_family():
+    """The bf16 table carries one row-band family (matrices of 16 rows under every key): shapes with M <= 16 are priced
+    from it under every key alike, everything else from the paper's near-square buckets."""
+    table, meta = osel.read_table(os.path.join(TABLES, "mi355x_in0_out1.wt"), **SPLIT_LIMITS)
+    assert (table.W_row, table.row_fams, table.row_mode) == (8, 1, 1)
+    recs = np.load(os.path.join(TABLES, "mi355x_in0_out1_samples.npz"))["samples"]
+    f1 = recs[recs["family"] == 1]
+    assert set(int(k) for k in np.unique(f1["key_id"])) == set(range(len(table.keys))) and int(f1["w"].max()) <= 8
+    for k, kd in enumerate(table.keys):
+        assert osel.family_of(table, 16, kd.bm) == 1 and osel.family_of(table, 17, kd.bm) in (0, 2)
+        assert osel.bucket_for(table, k, 1, osel.family_of(table, 17, kd.bm)) is table.local[k][0]
+        assert osel.bucket_for(table, k, 1, 1) is table.row_local[0][k][0]
