@@ -59,7 +59,7 @@ def build(jobs: int = 8, verbose: bool = False) -> str:
     steps.append([hipcc, *HIP_FLAGS, "-c", os.path.join(CSRC, "mfma_ceiling.hip"), "-o", obj])
     obj = os.path.join(OUT, "wt_host.o")
     objs.append(obj)
-    steps.append(["g++", "-O2", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Wall", "-c",
+    steps.append(["g++", "-O2", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Wall", "-Wextra", "-Wshadow", "-c",
                   os.path.join(CSRC, "wt_host.cpp"), "-o", obj])
     with ThreadPoolExecutor(max_workers=max(1, jobs)) as ex:
         for out in ex.map(_run, steps):
