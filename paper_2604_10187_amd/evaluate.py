@@ -206,13 +206,13 @@ def cmd_stream(a, torch):
     for sh in draws:
         weight[sh] = weight.get(sh, 0) + 1
     sample = sorted(weight)
-    ex = Exhaustive(ctx, torch, a.in_type, a.out_type, prune=a.prune, refine=a.refine)
+    ex = Exhaustive(ctx, torch, a.in_type, a.out_type, prune=a.prune, refine=a.refine, rotate_mb=a.rotate_mb)
     rows, summary = _pick_vs_best(ctx, ex, sample)
     wts = np.array([weight[(r["M"], r["N"], r["K"])] for r in rows], dtype=float)
     fr = np.array([r["frac"] for r in rows])
     for r, w in zip(rows, wts):
         r["weight"] = int(w)
-    summary.update({"stream_shapes": len(shapes), "unique_shapes": len(set(shapes)), "sampled_draws": len(draws),
+    summary.update({"weights_rotated_over_mb": a.rotate_mb, "stream_shapes": len(shapes), "unique_shapes": len(set(shapes)), "sampled_draws": len(draws),
                     "exhaustive_shapes": len(sample),
                     "weighted_geomean_frac": float(np.exp(np.sum(wts * np.log(fr)) / wts.sum())),
                     "weighted_frac_ge_95": float(np.sum(wts * (fr >= 0.95)) / wts.sum()),
@@ -643,7 +643,7 @@ def main(argv=None):
     ap.add_argument("--sample-seed", type=int, default=2005, help="stream: seed of the sampled draws")
     ap.add_argument("--prune", type=float, default=2.5)
     ap.add_argument("--rotate-mb", type=int, default=0,
-                    help="sweep: time every launch on another copy of the weight, the copies adding up to this many "
+                    help="sweep, stream: time every launch on another copy of the weight, the copies adding up to this many "
                          "megabytes (say 1200), so that weights stream from HBM instead of the memory-side cache")
     ap.add_argument("--refine", type=int, default=0,
                     help="sweep / stream: re-time the N fastest configurations and the pick, keep each one's smaller mean")
