@@ -21,6 +21,7 @@ WT_BF16, WT_FP8_E4M3, WT_ATTN_BF16 = 0, 1, 2
 WT_OUT_F32, WT_OUT_BF16 = 0, 1
 WT_MODEL_WAVE_BILINEAR, WT_MODEL_LINEAR, WT_MODEL_STEP = 0, 1, 2
 WT_FIT_ABSOLUTE, WT_FIT_RELATIVE = 0, 1
+WT_ROWS_TILES, WT_ROWS_BAND = 0, 1
 WT_CAP_CU_TIMES_OCC, WT_CAP_CU_ONLY = 0, 1
 WT_SPLITK_WS_FLOATS, WT_SPLITK_MAX_TILES, WT_MAX_ANCHORS = 1 << 26, 1 << 16, 8   # as #defined in wt.h
 WT_NOALLOC_WS_FLOATS, WT_NOALLOC_MAX_TILES = 1 << 24, 1 << 15

@@ -374,6 +374,28 @@ def test_grouped_moe_layer_normal(ctx_bf16):
         got = run_gemm_grouped(ctx_bf16, cfg, ab, bb, off, wt.WT_OUT_BF16)
         assert og.max_scaled_err(got, want) <= BF16_ELEM
         assert og.max_scaled_err(got, want) <= 2.0 ** -8
+    # the same launch under what the two grouped selectors return from the shipped table (the uniform reading of the
+    # routing, and its real counts): both are the oracle's picks on that table, and both launches are correct
+    import os
+    from oracle import select as osel
+    from _pins import split_limits
+    path = os.path.join(os.path.dirname(wt.LIB_PATH), "tables", "mi355x_in0_out1.wt")
+    sel = wt.wt_create(-1, wt.WT_BF16, wt.WT_OUT_BF16)
+    try:
+        wt.wt_load(sel, path)
+        picks = [wt.wt_select_grouped(sel, E, M_total, N, K), wt.wt_select_grouped_rows(sel, counts, N, K)]
+    finally:
+        wt.wt_destroy(sel)
+    table, _ = osel.read_table(path, **split_limits())
+    wants = [osel.select_grouped(table, E, M_total, N, K), osel.select_grouped_rows(table, counts.tolist(), N, K)]
+    for pick, (key, micro, _) in zip(picks, wants):
+        kd = table.keys[key]
+        assert (pick.bm, pick.bn, pick.bk, pick.nwave, pick.stages, pick.swizzle, pick.split) == \
+            (kd.bm, kd.bn, kd.bk, kd.nwave, kd.stages, micro, 1)
+        cfg, _ = wt.wt_config_get(ctx_bf16, wt.wt_config_find(ctx_bf16, pick.bm, pick.bn, pick.bk, pick.nwave, pick.stages, pick.swizzle))
+        note(f"grouped MoE layer under the selector's pick cfg={cfg.astuple()}")
+        got = run_gemm_grouped(ctx_bf16, cfg, ab, bb, off, wt.WT_OUT_BF16)
+        assert og.max_scaled_err(got, want) <= 2.0 ** -8
 
 
 def test_degenerate_shapes_and_errors(ctx_f32):
@@ -734,3 +756,83 @@ def test_profile_fit_select_round_trip_on_device(ctx_bf16, tmp_path, device_reco
         assert key in profiled
         picked.add(key)
     assert len(picked) >= 2
+
+
+def test_row_band_families_profile_fit_select_on_device(ctx_bf16, tmp_path, device_records):
+    """The row-band few-row families end to end on the GPU: wt_profile_sparse with row_mode = WT_ROWS_BAND profiles, for
+    two families, matrices of exactly 16 and 32 rows under every key of the slice; the records are the oracle's plan
+    (band_sample_set x loop anchors x micros, family tagged, Phi of the 16- or 32-row workload giving back G and L);
+    fitted together with the near-square records the table file is version 4 and equals the oracle's fit; shapes with
+    M <= 32 are then priced from the family of their band under every key alike, bit for bit as the oracle prices them."""
+    from _pins import lib_limits, split_limits
+    from oracle import fit as ofit
+    from oracle import geometry as geo
+    from oracle import sampler as smp
+    from oracle import select as osel
+
+    W_row, fams = 2, 2
+    lim = split_limits()
+    band_recs = []
+    for (first, count) in RT_SLICES:
+        grid = wt.make_grid(W=RT_W, I=RT_I, p=RT_P, k_anchors=RT_ANCHORS, warmup=1, iters=2, key_first=first, key_count=count,
+                            W_split=RT_WSPLIT, W_row=W_row, row_fams=fams, row_mode=wt.WT_ROWS_BAND, skip_near=1)
+        n, bA, bB, bC = wt.wt_sample_plan(ctx_bf16, grid)
+        scrA = torch.zeros(bA // 2, dtype=torch.bfloat16, device="cuda")
+        scrB = torch.zeros(bB // 2, dtype=torch.bfloat16, device="cuda")
+        scrC = torch.empty(bC, dtype=torch.uint8, device="cuda")
+        note(f"profile_sparse row-band families keys {first}..{first + count - 1}, {n} records")
+        recs = wt.wt_profile_sparse(ctx_bf16, grid, scrA, scrB, scrC, stream=torch.cuda.current_stream())
+        assert len(recs) == n
+        want = []
+        for k in range(first, first + count):
+            cfg, _ = wt.wt_config_get(ctx_bf16, 3 * k)
+            S = cfg.split
+            Wk = W_row if S == 1 else min(W_row, RT_WSPLIT)
+            for f in range(1, fams + 1):
+                rows = smp.ROW_BANDS[f - 1]
+                for smpl in smp.band_sample_set(256, Wk, RT_I, rows, cfg.bm, S):
+                    if smpl.g == 0 or not geo.split_fits(smpl.m * cfg.bm, smpl.n * cfg.bn, cfg.bm, cfg.bn, S,
+                                                         lim["ws_elems"], lim["max_split_tiles"]):
+                        continue
+                    for L in smp.loop_anchors(RT_ANCHORS, cfg.bk, S):
+                        assert geo.phi_gemm(rows, smpl.n * cfg.bn, L * S * cfg.bk, cfg.bm, cfg.bn, cfg.bk, S) == (smpl.g, L)
+                        want += [(k, m, smpl.g, L, smpl.w, f) for m in range(3)]
+        got = [(int(r["key_id"]), int(r["micro_id"]), int(r["G"]), int(r["L"]), int(r["w"]), int(r["family"])) for r in recs]
+        assert got == want
+        assert np.all(recs["mean_us"] > 0) and np.isfinite(recs["mean_us"]).all()
+        band_recs.append(recs)
+        del scrA, scrB, scrC
+    recs = np.concatenate(list(device_records) + band_recs)
+    grid = wt.make_grid(W=RT_W, I=RT_I, p=RT_P, k_anchors=RT_ANCHORS, W_split=RT_WSPLIT, W_row=W_row, row_fams=fams,
+                        row_mode=wt.WT_ROWS_BAND, weighting=1)
+    wt.wt_fit(ctx_bf16, grid, recs)
+    path = str(tmp_path / "bands.wt")
+    wt.wt_save(ctx_bf16, path)
+    assert open(path, "rb").read()[4] == 4
+    table, _ = osel.read_table(path, **lim)
+    assert (table.W_row, table.row_fams, table.row_mode) == (W_row, fams, 1)
+    want_t = ofit.fit_tables([(int(r["key_id"]), int(r["micro_id"]), int(r["G"]), int(r["L"]), int(r["w"]),
+                               float(r["mean_us"]), int(r["family"])) for r in recs], table.keys, RT_W, RT_P, W_row=W_row,
+                             row_fams=fams, row_mode=1, max_anchors=lib_limits()["max_anchors"], relative=True)
+    profiled = {k for (first, count) in RT_SLICES for k in range(first, first + count)}
+    n_fitted = 0
+    for k in profiled:
+        for f in range(fams):
+            for got_b, want_b in list(zip(table.row_local[f][k], want_t.row_local[f][k])) + [(table.row_ext[f][k], want_t.row_ext[f][k])]:
+                assert got_b.status == want_b.status and got_b.anchors == want_b.anchors, (k, f)
+                if not want_b.status:
+                    continue
+                n_fitted += 1
+                for (G, L) in ((1, 1), (256, 16), (500, 32)):
+                    a, b = osel.predict(got_b.theta, G, L), osel.predict(want_b.theta, G, L)
+                    assert abs(a - b) <= 1e-9 * max(abs(b), max(abs(x) for x in want_b.theta)), (k, f, G, L, a, b)
+    assert n_fitted >= 2 * len(profiled)
+    used = {0: 0, 1: 0, 2: 0, 3: 0, 4: 0}
+    for (M, N, K) in wt_synth.sweep_shapes() + wt_synth.stream_shapes(300):
+        key, micro, t = osel.select(table, M, N, K)
+        c = wt.wt_select(ctx_bf16, M, N, K)
+        kd = table.keys[key]
+        assert (c.bm, c.bn, c.bk, c.nwave, c.stages, c.swizzle, c.split) == (kd.bm, kd.bn, kd.bk, kd.nwave, kd.stages, micro, kd.split)
+        assert wt.wt_predict_us(ctx_bf16, M, N, K, c) == t
+        used[osel.family_of(table, M, kd.bm)] += 1
+    assert used[1] > 10 and used[2] > 5 and used[0] > 50
