@@ -374,6 +374,12 @@ int wt_select_bench(const wt_ctx* ctx, const int64_t* shapes, size_t n, int repe
                     double* mean_ns, double* p99_ns);
 
 /* ---- dual-table artifact ------------------------------------------------------------------- */
+/* The dual table of Sec. 4.3 / 4.5 (per key and wave: four coefficients, status, loop anchors with their micro; the
+ * extrapolation tuple; the few-row families where fitted) as one little-endian file.  wt_save: WT_ERR_NOT_FITTED
+ * without a table, WT_ERR_IO if the file cannot be written.  wt_load replaces the context's table, capacity mode and
+ * per-key occupancy with the file's, or leaves the context as it was and returns WT_ERR_IO (unreadable, not a table
+ * file, unknown version, shorter or longer than its header says) or WT_ERR_INVALID_ARG (written for another registry,
+ * storage type or compute-unit count, or a header field out of range). */
 int wt_save(const wt_ctx* ctx, const char* path);
 int wt_load(wt_ctx* ctx, const char* path);
 

@@ -738,6 +738,8 @@ static int load_table(wt_ctx* ctx, const char* path) {
             for (int fam = 0; ok && fam < t.row_fams; ++fam) ok = read_block(f, &t.row_buckets[fam][k * (t.W_row + 1)], t.W_row + 1);
             if (!ok) rc = WT_ERR_IO;
         }
+        // the header's sizes must account for every byte: a file longer than they say was written under other ones
+        if (rc == WT_OK && fgetc(f) != EOF) rc = WT_ERR_IO;
     }
     fclose(f);
     if (rc != WT_OK) return rc;

@@ -435,6 +435,59 @@ def test_fit_objective_argument_checks_and_header_word(ctx, tmp_path):
         wt.wt_load(ctx, old)
 
 
+def test_family_table_file_header_is_checked(ctx, tmp_path):
+    """A version-4 file (row-band families) whose header is tampered with is refused, never half-loaded: a version the
+    library does not know, a family count beyond the mode's, version 4 with no family, a truncated or padded file;
+    and a file written with tile-row families read as row-band ones (version word changed) selects differently or
+    is refused, but the context keeps working on its previous table either way."""
+    import struct
+
+    keys = _keys(ctx)
+    W, W_row, I, p = 4, 2, 2, 2
+    near = _synthetic_samples(keys, W, I, noise_seed=3)
+    rows = []
+    for k, kd in enumerate(keys):
+        Wk = W_row if kd.split == 1 else min(W_row, W_SPLIT)
+        for sm in smp.band_sample_set(kd.cap, Wk, I, 16, kd.bm, kd.split):
+            if sm.g == 0 or not geo.split_fits(sm.m * kd.bm, sm.n * kd.bn, kd.bm, kd.bn, kd.split, SPLIT_LIMITS["ws_elems"], SPLIT_LIMITS["max_split_tiles"]):
+                continue
+            for L in smp.loop_anchors(K_ANCHORS, kd.bk, kd.split):
+                for micro in range(3):
+                    rows.append((k, micro, sm.g, L, sm.w, 1, 3.0 + 0.01 * sm.g + 0.2 * L + 0.1 * micro))
+    samples = np.concatenate([near, np.array(rows, dtype=wt.SAMPLE_DTYPE)])
+    wt.wt_fit(ctx, wt.make_grid(W=W, I=I, p=p, k_anchors=K_ANCHORS, W_row=W_row, row_fams=1, W_split=W_SPLIT, row_mode=1), samples)
+    good = str(tmp_path / "good.wt")
+    wt.wt_save(ctx, good)
+    raw = open(good, "rb").read()
+    assert struct.unpack_from("<I", raw, 4)[0] == 4 and struct.unpack_from("<2I", raw, 52) == (W_row, 1)
+    ref = [wt.wt_select(ctx, M, N, K).id for (M, N, K) in wt_synth.sweep_shapes()]
+
+    def tampered(offset, value, tail=None):
+        b = bytearray(raw)
+        struct.pack_into("<I", b, offset, value)
+        q = str(tmp_path / f"t{offset}_{value}.wt")
+        open(q, "wb").write(bytes(b) if tail is None else tail(bytes(b)))
+        return q
+
+    for q in (tampered(4, 5), tampered(4, 0), tampered(56, 5), tampered(56, 0), tampered(52, 1 << 20),
+              tampered(4, 4, tail=lambda b: b[:-8]), tampered(4, 4, tail=lambda b: b + b"\0" * 8)):
+        with pytest.raises(wt.WtError):
+            wt.wt_load(ctx, q)
+        assert [wt.wt_select(ctx, M, N, K).id for (M, N, K) in wt_synth.sweep_shapes()] == ref      # table untouched
+    # version 2 = the same bytes read as ONE tile-row family: loads, and consults the family by tile rows instead of by M
+    v2 = tampered(4, 2)
+    c2 = wt.wt_create(-1, wt.WT_BF16, wt.WT_OUT_F32)
+    try:
+        wt.wt_load(c2, v2)
+        t2, _ = osel.read_table(v2, **SPLIT_LIMITS)
+        assert t2.row_mode == 0 and t2.row_fams == 1
+        for (M, N, K) in wt_synth.sweep_shapes():
+            key, micro, _ = osel.select(t2, M, N, K)
+            assert wt.wt_select(c2, M, N, K).id == 3 * key + micro
+    finally:
+        wt.wt_destroy(c2)
+
+
 @pytest.mark.parametrize("model", [wt.WT_MODEL_LINEAR, wt.WT_MODEL_STEP])
 def test_ablation_models_parity(ctx, tmp_path, model):
     """Step and Linear tables built by the library equal the oracle's (coefficients to 1e-9, anchors
