@@ -139,8 +139,9 @@ typedef enum { WT_FIT_ABSOLUTE = 0, WT_FIT_RELATIVE = 1 } wt_weighting;
 
 /* What the few-row families of wt_grid.W_row hold (extension; the paper's sampler has no such grids).
  *   WT_ROWS_TILES  families 1..3 are grids of 1, 2, 4 full tile rows of the key at hand (M = m_G * bm), and a shape
- *                  consults, per key, the family of its own tile-row count.  Keys of different tile heights are then
- *                  priced from different matrices.
+ *                  consults, per key, the family of its own tile-row count ceil(M/bm): family 1 for one, 2 for two
+ *                  or three, 3 for four to seven tile rows.  Keys of different tile heights are then priced from
+ *                  different matrices.
  *   WT_ROWS_BAND   families 1..4 are grids of exactly 16, 32, 64, 128 rows under EVERY key (ceil(rows/bm) tile rows,
  *                  the last one partial), and a shape with M <= 128 consults the family of the smallest band that
  *                  holds M under every key alike, so that Stage I compares predictions made from the same matrices. */
