@@ -591,7 +591,8 @@ def cmd_ablate(a, torch=None):
                 keep[np.where(m)[0]] = (idx % step) == (step - 1)
             sub = sub[keep]
         wt.wt_fit(ctx, wt.make_grid(W=W, I=I, p=min(a.p, W), k_anchors=anchors, model=model, W_row=W_row,
-                                      row_fams=row_fams, n_heads=32 if attn else 0, weighting=weighting), sub)
+                                      row_fams=row_fams, n_heads=32 if attn else 0, weighting=weighting,
+                                      row_mode=a.row_mode), sub)
         fr = []
         for r in rows:
             c = wt.wt_select(ctx, *shape(r))
@@ -605,7 +606,7 @@ def cmd_ablate(a, torch=None):
     W0 = int(recs["w"][recs["family"] == 0].max())
     Wr = int(recs["w"][recs["family"] >= 1].max()) if (recs["family"] >= 1).any() else 0
     for nf in range(1, int(recs["family"].max()) + 1):
-        out["variants"].append({"model": f"wave-bilinear + {nf} few-row families", "W": W0, "I": I0, "W_row": Wr,
+        out["variants"].append({"model": f"wave-bilinear + {nf} few-row families (row_mode {a.row_mode})", "W": W0, "I": I0, "W_row": Wr,
                                 **score(0, W0, I0, a.cap_mode, Wr, nf)})
     for name, model in (("wave-bilinear (full)", 0), ("linear", 1), ("step", 2)):
         out["variants"].append({"model": name, "W": W0, "I": I0, **score(model, W0, I0, a.cap_mode)})
@@ -632,6 +633,7 @@ def main(argv=None):
     ap.add_argument("--scores", nargs="*", default=[], help="ablate: sweep/stream result files with exhaustive timings")
     ap.add_argument("--cap-mode", type=int, default=1)
     ap.add_argument("--weighting", type=int, default=1, help="ablate: objective of the bucket fits (0 ordinary, 1 relative: the shipped GEMM tables)")
+    ap.add_argument("--row-mode", type=int, default=1, help="ablate: what the few-row families of the records hold (0 tile rows, 1 row bands: the shipped bf16 records)")
     ap.add_argument("--I", type=int, default=4)
     ap.add_argument("--p", type=int, default=10)
     ap.add_argument("--in-type", type=int, default=wt.WT_BF16)
