@@ -283,7 +283,8 @@ int wt_attn_batched(wt_ctx* ctx, int64_t batch, int64_t n_heads, int64_t n_kv_he
  * grid is sized for the worst case, n_heads * (ceil(total_q/T_Q) + batch) blocks, a block finds its sequence from the
  * offsets, and blocks past the last query tile exit at once.  Offsets are clipped to [0, total] in the kernel, so no
  * content of the arrays can make an access leave the tensors.  causal = 1 aligns every sequence's queries to the end
- * of its own keys; a query that sees no key (a sequence with fewer keys than queries) yields zeros.  0 <= batch <= 1024.
+ * of its own keys; a query that sees no key (a sequence with fewer keys than queries) yields zeros; causal launches walk
+ * the batch's query tiles from the last to the first, longest blocks first.  0 <= batch <= 1024.
  * Selection: wt_select_attn_varlen when the host knows the lengths; from the totals alone, under the uniform
  * approximation of Sec. 5.2, wt_select(ctx, ceil(total_q/batch), batch * n_heads, ceil(total_kv/batch)).  Results per sequence are bit-identical
  * to wt_attn's.  Asynchronous, never allocates or synchronises. */

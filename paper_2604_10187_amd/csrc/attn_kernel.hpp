@@ -140,8 +140,13 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
             if (lane >= d) incl += v;
         }
         const int excl = incl - mine;
+        // Causal batch: a sequence's later query tiles loop over more keys, so the concatenated tile list is walked
+        // backwards -- every sequence's longest tiles before its shortest, and the launch ends on short blocks.
+        const int total_tiles = __builtin_amdgcn_readfirstlane(__shfl(incl, 63));
+        if (qt >= total_tiles) return;       // past the last query tile of the batch
+        if (a.causal) qt = total_tiles - 1 - qt;
         const unsigned long long hit = __ballot(qt >= excl && qt < incl);
-        if (hit == 0) return;                // past the last query tile of the batch
+        if (hit == 0) return;
         const int src = __builtin_amdgcn_readfirstlane(__ffsll(static_cast<long long>(hit)) - 1);
         int first = __builtin_amdgcn_readfirstlane(__shfl(excl, src));
         int b = src * c, lo = 0, hi = 0;
@@ -161,7 +166,7 @@ __global__ __launch_bounds__(NW * 64) void attn_kernel(const AttnArgs a) {
         S_kv = khi - klo;
         kv_tok0 = klo;
     }
-    // the query tiles with the most keys start first (a variable-length batch keeps its tile order)
+    // the query tiles with the most keys start first (a variable-length batch has reversed its tile list above)
     if (a.causal && a.cu_q == nullptr) qt = a.q_tiles - 1 - qt;
     const __bf16* const Qs = a.Q + q_tok0 * a.H_q * kHeadDim;
     const __bf16* const Ks = a.K + kv_tok0 * a.H_kv * kHeadDim;
